@@ -1,0 +1,322 @@
+"""Pins for the CPU oracle: every check here compares it against something other
+than its own formulas -- an independent library's softmax attention, closed
+forms worked by hand, brute-force enumeration, or invariants the paper states.
+A dropped term, a transposed operand, a wrong axis or a wrong tie-break in the
+oracle fails at least one of them.  CPU only."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import hybridkv_oracle as O
+from hkv_synth import bf16_round, make_workload
+
+
+def _sdpa_f64(q, K, V, scale):
+    """Independent reference: torch's scaled_dot_product_attention in float64."""
+    qt = torch.from_numpy(np.asarray(q, np.float64))[None]          # [1, G, d]
+    Kt = torch.from_numpy(np.asarray(K, np.float64))[None]          # [1, n, d]
+    Vt = torch.from_numpy(np.asarray(V, np.float64))[None]
+    o = torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt, scale=scale)
+    return o[0].numpy()
+
+
+# ---------------------------------------------------------------- attention
+def test_attention_matches_library_sdpa():
+    rng = np.random.default_rng(1)
+    q, K, V = rng.standard_normal((7, 128)), rng.standard_normal((300, 128)), rng.standard_normal((300, 128))
+    o, p = O.attention(q, K, V, 1 / math.sqrt(128), return_weights=True)
+    np.testing.assert_allclose(o, _sdpa_f64(q, K, V, 1 / math.sqrt(128)), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-12)     # weights sum to 1
+
+
+def test_attention_hand_worked():
+    # logits ln1, ln3 -> weights 1/4, 3/4; values 4 and 8 -> 7
+    q = np.array([[1.0]])
+    K = np.array([[0.0], [math.log(3.0)]])
+    V = np.array([[4.0], [8.0]])
+    np.testing.assert_allclose(O.attention(q, K, V, 1.0), [[7.0]], rtol=1e-14)
+    # scale enters the logits: scale 2 -> weights 1/10, 9/10 -> 7.6
+    np.testing.assert_allclose(O.attention(q, K, V, 2.0), [[7.6]], rtol=1e-14)
+
+
+def test_attention_permutation_invariant():
+    rng = np.random.default_rng(2)
+    q, K, V = rng.standard_normal((4, 16)), rng.standard_normal((50, 16)), rng.standard_normal((50, 16))
+    perm = rng.permutation(50)
+    np.testing.assert_allclose(O.attention(q, K, V, 0.25), O.attention(q, K[perm], V[perm], 0.25),
+                               rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- window scores
+def test_window_scores_hand_worked():
+    # G=2 heads, w=2 rows each, d=1, keys 0 and 1, scale 1.
+    # rows (logit of key1 - key0): ln2, ln3, ln4, ln1 -> p(key0) = 1/3, 1/4, 1/5, 1/2
+    q = np.array([[[math.log(2)], [math.log(3)]], [[math.log(4)], [0.0]]])
+    k = np.array([[0.0], [1.0]])
+    s = O.window_scores(q, k, 1.0)
+    want0 = (1 / 3 + 1 / 4 + 1 / 5 + 1 / 2) / 4
+    np.testing.assert_allclose(s, [want0, 1 - want0], rtol=1e-14)
+
+
+def test_window_scores_single_row_is_library_softmax():
+    rng = np.random.default_rng(3)
+    q, k = rng.standard_normal((1, 1, 32)), rng.standard_normal((77, 32))
+    s = O.window_scores(q, k, 0.3)
+    np.testing.assert_allclose(s, scipy.special.softmax((k @ q[0, 0]) * 0.3), rtol=1e-12)
+
+
+def test_window_scores_sum_to_one_and_uniform_closed_form():
+    rng = np.random.default_rng(4)
+    q, k = rng.standard_normal((7, 32, 128)), rng.standard_normal((512, 128))
+    s = O.window_scores(q, k, 1 / math.sqrt(128))
+    assert abs(s.sum() - 1.0) < 1e-12 and (s >= 0).all()
+    # zero queries (or identical keys) -> every row uniform -> s_w = 1/C exactly for C a power of two
+    s0 = O.window_scores(np.zeros((7, 32, 128)), k, 1 / math.sqrt(128))
+    assert (s0 == 1.0 / 512).all()
+    s1 = O.window_scores(q, np.tile(k[:1], (512, 1)), 1 / math.sqrt(128))
+    np.testing.assert_allclose(s1, 1.0 / 512, rtol=1e-12)
+
+
+def test_window_scores_dominant_key_is_indicator():
+    rng = np.random.default_rng(5)
+    u = np.zeros(16); u[3] = 1.0
+    q = np.tile(100.0 * u, (2, 4, 1))
+    k = 0.01 * rng.standard_normal((40, 16)); k[17] = 10.0 * u
+    s = O.window_scores(q, k, 1.0)
+    assert s[17] > 1 - 1e-12 and np.argmax(s) == 17
+
+
+def test_window_scores_causal_closed_form():
+    # zero queries: row i is uniform over the keys it may see (C-w+i+1 of them)
+    C, w = 12, 4
+    s = O.window_scores(np.zeros((3, w, 8)), np.ones((C, 8)), 1.0, causal=True)
+    want = np.zeros(C)
+    for i in range(w):
+        n = C - w + i + 1
+        want[:n] += 1.0 / n
+    np.testing.assert_allclose(s, want / w, rtol=1e-14)
+    assert abs(s.sum() - 1) < 1e-14
+
+
+# ---------------------------------------------------------------- selection
+@pytest.mark.parametrize("seed", range(6))
+def test_top_indices_brute_force(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(5, 12))
+    # few distinct values -> many ties
+    scores = rng.integers(0, 4, size=n).astype(np.float64)
+    cand = np.sort(rng.choice(n, size=int(rng.integers(3, n + 1)), replace=False))
+    for m in range(0, cand.size + 1):
+        got = tuple(O.top_indices(scores, cand, m).tolist())
+        best = max(scores[list(c)].sum() for c in itertools.combinations(cand.tolist(), m)) if m else 0.0
+        winners = sorted(c for c in itertools.combinations(cand.tolist(), m) if scores[list(c)].sum() == best)
+        # maximal total score and, among the maximisers, the lexicographically smallest index set
+        assert got == winners[0]
+
+
+def test_top_indices_all_equal_takes_first():
+    assert O.top_indices(np.full(10, 0.5), np.array([1, 3, 4, 8, 9]), 3).tolist() == [1, 3, 4]
+
+
+def test_select_chunks_ties_and_order():
+    sigma = np.array([1.0, 5.0, 5.0, -2.0, 5.0, 0.0])
+    assert O.select_chunks(sigma, 2).tolist() == [1, 2]
+    assert O.select_chunks(sigma, 4).tolist() == [0, 1, 2, 4]
+    assert O.select_chunks(sigma, 6).tolist() == list(range(6))
+
+
+# ---------------------------------------------------------------- static keep set
+def _layout():
+    #          0  1  2  3  4  5  6  7  8  9 10 11
+    return np.array([0, 1, 1, 0, 1, 1, 1, 0, 1, 0, 0, 0], np.uint8)   # w = 2 -> window {10, 11}
+
+
+def test_keep_set_three_sets():
+    vis = _layout()
+    s = np.array([.0, .05, .30, .0, .10, .30, .02, .0, .20, .0, .01, .02])
+    # text before window: {0,3,7,9}; budget 2+4+2 -> two best visual; tie .30/.30 -> both; then .20 next
+    assert O.static_keep_set(s, vis, 2, 8).tolist() == [0, 2, 3, 5, 7, 9, 10, 11]
+    assert O.static_keep_set(s, vis, 2, 9).tolist() == [0, 2, 3, 5, 7, 8, 9, 10, 11]
+    # one visual slot and a tie -> lower index wins
+    assert O.static_keep_set(s, vis, 2, 7).tolist() == [0, 2, 3, 7, 9, 10, 11]
+    # budget covers everything (or more) -> identity
+    assert O.static_keep_set(s, vis, 2, 12).tolist() == list(range(12))
+    assert O.static_keep_set(s, vis, 2, 50).tolist() == list(range(12))
+
+
+def test_keep_set_budget_below_text_plus_window():
+    vis = _layout()
+    s = np.array([.04, .5, .5, .01, .5, .5, .5, .04, .5, .03, .0, .0])
+    # budget 4: window + the 2 best historical TEXT tokens (0 and 7 tie at .04 > .03 > .01); no visual
+    assert O.static_keep_set(s, vis, 2, 4).tolist() == [0, 7, 10, 11]
+    assert O.static_keep_set(s, vis, 2, 3).tolist() == [0, 10, 11]
+    assert O.static_keep_set(s, vis, 2, 2).tolist() == [10, 11]
+    assert O.static_keep_set(s, vis, 2, 1).tolist() == [11]
+
+
+@pytest.mark.parametrize("budget", [1, 2, 3, 5, 6, 7, 9, 11, 12, 20])
+def test_retained_count_matches_keep_set(budget):
+    vis = _layout()
+    rng = np.random.default_rng(budget)
+    s = rng.random(12)
+    kept = O.static_keep_set(s, vis, 2, budget)
+    assert kept.size == O.retained_count(12, 2, 4, 6, budget) == min(budget, 12)
+    assert (np.diff(kept) > 0).all()
+
+
+def test_uniform_scores_keep_first_visual():
+    wl = make_workload(0, shrink=4)
+    C, w = int(wl.seqlens[0]), wl.window
+    s = np.full(C, 1.0 / C)
+    kept = O.static_keep_set(s, wl.is_visual, w, int(wl.budget[0, 0, 0]))
+    vis_hist = np.nonzero(wl.is_visual[: C - w])[0]
+    n_txt = (C - w) - vis_hist.size
+    m = int(wl.budget[0, 0, 0]) - w - n_txt
+    kept_vis = [j for j in kept if j < C - w and wl.is_visual[j]]
+    assert kept_vis == vis_hist[:m].tolist()
+
+
+# ---------------------------------------------------------------- chunks
+def test_chunk_means_closed_form_and_ragged_tail():
+    # rows 0..9 hold the row index in every column; c = 4 -> means 1.5, 5.5, and the short last chunk 8.5
+    k = np.tile(np.arange(10.0)[:, None], (1, 3))
+    mu = O.chunk_means(k, 4, "f32")
+    np.testing.assert_array_equal(mu, [[1.5] * 3, [5.5] * 3, [8.5] * 3])
+    assert O.chunk_rows(np.array([0, 2]), 4, 10).tolist() == [0, 1, 2, 3, 8, 9]
+
+
+def test_chunk_size_one_reduces_to_token_topk():
+    rng = np.random.default_rng(7)
+    k = bf16_round(rng.standard_normal((64, 128)).astype(np.float32))
+    q = bf16_round(rng.standard_normal((7, 128)).astype(np.float32))
+    mu = O.chunk_means(k, 1, "bf16")
+    np.testing.assert_array_equal(mu, k.astype(np.float64))          # mean of one row, already bf16
+    sigma = O.chunk_scores(q, mu)
+    ref = (torch.from_numpy(k).double() @ torch.from_numpy(q).double().sum(0)).numpy()
+    np.testing.assert_allclose(sigma, ref, rtol=1e-12)
+    assert O.select_chunks(sigma, 5).tolist() == sorted(np.argsort(-ref, kind="stable")[:5].tolist())
+
+
+def test_n_selected_chunks():
+    assert O.n_selected_chunks(128, 32, 64) == 4
+    assert O.n_selected_chunks(10, 32, 64) == 1
+    assert O.n_selected_chunks(4096, 32, 64) == 64
+    assert O.n_selected_chunks(100, 32, 64) == 3
+
+
+# ---------------------------------------------------------------- rounding
+def test_round_to_bf16():
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    x = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, -(1 + 2.0 ** -8), 1 + 2.0 ** -8 + 2.0 ** -40, 0.0, 3.0])
+    np.testing.assert_array_equal(O.round_to_dtype(x, "bf16"),
+                                  [1.0, 1 + 2.0 ** -6, -1.0, 1 + 2.0 ** -7, 0.0, 3.0])
+    # agrees with torch on float32-exact inputs
+    rng = np.random.default_rng(8)
+    y = rng.standard_normal(10000).astype(np.float32)
+    want = torch.from_numpy(y).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_to_dtype(y.astype(np.float64), "bf16"), want)
+    np.testing.assert_array_equal(bf16_round(y).astype(np.float64), want)
+
+
+# ---------------------------------------------------------------- drivers
+def _cfg_plan(wl, budget=None):
+    cfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                         head_dim=wl.head_dim, window=wl.window, dtype=wl.dtype)
+    plan = O.OraclePlan(cu_seqlens=wl.cu_seqlens, head_type=wl.head_type,
+                        budget=wl.budget if budget is None else budget, chunk_size=wl.chunk_size)
+    return cfg, plan
+
+
+def test_full_budget_reproduces_full_attention():
+    """Budget = whole context on every head: the kept set is the identity, every
+    chunk is selected, and the output equals plain softmax attention."""
+    wl = make_workload(0, shrink=4, steps=3)
+    full = np.full_like(wl.budget, int(wl.seqlens[0]) + 64)
+    cfg, plan = _cfg_plan(wl, full)
+    cache = O.compress(cfg, plan, wl.q_window, wl.k, wl.v, wl.is_visual)
+    C = int(wl.seqlens[0])
+    G = cfg.group
+    K_all = [[wl.k[0, :, h].astype(np.float64)] for h in range(4)]
+    V_all = [[wl.v[0, :, h].astype(np.float64)] for h in range(4)]
+    for s in range(wl.steps):
+        out, info = O.decode_attn(cache, wl.q_steps[s], wl.k_new[s], wl.v_new[s])
+        for h in range(4):
+            K_all[h].append(wl.k_new[s][0, 0, h][None].astype(np.float64))
+            V_all[h].append(wl.v_new[s][0, 0, h][None].astype(np.float64))
+            ref = _sdpa_f64(wl.q_steps[s][0, 0, h * G:(h + 1) * G], np.concatenate(K_all[h]),
+                            np.concatenate(V_all[h]), cfg.scale)
+            np.testing.assert_allclose(out[0, 0, h * G:(h + 1) * G], ref, rtol=1e-11, atol=1e-13)
+    for h in range(4):
+        u = cache.units[(0, 0, h)]
+        if u.kind == O.STATIC:
+            assert u.kept.tolist() == list(range(C))
+        else:
+            assert info[(0, 0, h)]["sel"].tolist() == list(range(u.mu.shape[0]))
+    # and the uncompressed driver agrees with the library on the prompt alone
+    outf = O.full_decode_attn(cfg, wl.cu_seqlens, wl.q_steps[0], wl.k, wl.v)
+    ref = _sdpa_f64(wl.q_steps[0][0, 0, :G], wl.k[0, :, 0], wl.v[0, :, 0], cfg.scale)
+    np.testing.assert_allclose(outf[0, 0, :G], ref, rtol=1e-11, atol=1e-13)
+
+
+def test_compress_counts_scores_and_planted_tokens():
+    wl = make_workload(0)
+    cfg, plan = _cfg_plan(wl)
+    cache = O.compress(cfg, plan, wl.q_window, wl.k, wl.v, wl.is_visual)
+    C, w = int(wl.seqlens[0]), wl.window
+    n_txt = int((wl.is_visual[: C - w] == 0).sum())
+    for h in range(4):
+        u = cache.units[(0, 0, h)]
+        if u.kind == O.STATIC:
+            assert abs(u.s_w.sum() - 1) < 1e-12
+            assert u.kept.size == int(wl.budget[0, 0, h]) == w + n_txt + 154      # retained = budget
+            assert set(range(C - w, C)) <= set(u.kept.tolist())                  # window kept
+            assert set(np.nonzero(wl.is_visual[: C - w] == 0)[0].tolist()) <= set(u.kept.tolist())
+            np.testing.assert_array_equal(u.K, wl.k[0, u.kept, h].astype(np.float64))
+            np.testing.assert_array_equal(u.V, wl.v[0, u.kept, h].astype(np.float64))
+            planted = wl.planted[(0, 0, h)]
+            frac = np.isin(planted, u.kept).mean()
+            assert frac > 0.8, frac        # planted keys carry +3 in logit: most of them make the cut
+        else:
+            assert u.mu.shape == (C // 32, 128) and u.k_sel == 4
+
+
+def test_decode_dynamic_rows_and_override():
+    wl = make_workload(0, shrink=4, steps=2)
+    cfg, plan = _cfg_plan(wl)
+    cache = O.compress(cfg, plan, wl.q_window, wl.k, wl.v, wl.is_visual)
+    out, info = O.decode_attn(cache, wl.q_steps[0], wl.k_new[0], wl.v_new[0])
+    G = cfg.group
+    for (b, l, h), d in info.items():
+        u = cache.units[(b, l, h)]
+        assert d["sel"].size == u.k_sel and (np.diff(d["sel"]) > 0).all()
+        rows = O.chunk_rows(d["sel"], u.c, u.C)
+        assert rows.size == u.k_sel * u.c
+        K = np.concatenate([wl.k[l, rows, h], wl.k_new[0][l, b, h][None]]).astype(np.float64)
+        V = np.concatenate([wl.v[l, rows, h], wl.v_new[0][l, b, h][None]]).astype(np.float64)
+        ref = _sdpa_f64(wl.q_steps[0][l, b, h * G:(h + 1) * G], K, V, cfg.scale)
+        np.testing.assert_allclose(out[l, b, h * G:(h + 1) * G], ref, rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- paper arithmetic
+def _golden():
+    import os
+    vals = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "paper_kv_footprint.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                key, val = line.split("=")
+                vals[key.strip()] = float(val)
+    return vals
+
+
+def test_paper_byte_model():
+    g = _golden()
+    per_token_72b = 80 * 8 * 128 * 2 * 2          # layers x KV heads x head_dim x (K,V) x 2 bytes
+    assert round(per_token_72b * g["intro_72b_tokens_images"] / 1e9) == g["intro_72b_gb_images"]
+    assert round(per_token_72b * g["intro_72b_tokens_video"] / 1e9) == g["intro_72b_gb_video"]
+    assert round(g["table3_full_gb"] / g["table3_b10_gb"], 1) == g["claimed_memory_ratio"]
+    assert round(g["table3_full_ms"] / g["table3_b10_ms"], 2) == g["claimed_decode_speedup"]
