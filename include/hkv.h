@@ -1,0 +1,199 @@
+/*
+ * hkv.h -- C ABI of the HybridKV hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the per-head hybrid
+ * KV-cache compression of the HybridKV paper (Section 3.3 "Hybrid KV Cache
+ * Compression" and Appendix A "Details of Hybrid KV Cache Compression") and the
+ * decode attention that runs over the compressed cache:
+ *
+ *   prefill  (hkv_compress)     static heads: observation-window scoring of the
+ *                               prompt (Appendix A, the S_w / s_w equations),
+ *                               Top-M historical visual tokens + all historical
+ *                               text + the window, compacted into a ragged cache;
+ *                               dynamic heads: full K/V adopted into the cache
+ *                               and one mean-key summary per fixed-size chunk.
+ *   decode   (hkv_decode_attn)  static heads: attention over the compacted rows;
+ *                               dynamic heads: query x chunk-summary scores,
+ *                               top-k chunks, attention over those chunks' rows;
+ *                               tokens generated during decoding are appended
+ *                               uncompressed to every head and always attended.
+ *
+ * Head types (Section 3.1) and per-head budgets (Section 3.2) are INPUTS.
+ *
+ * Conventions
+ *   - Plain C: pointers and sizes only.  Every pointer parameter is marked
+ *     [host] or [dev].  [dev] pointers must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - The library never allocates or frees device memory: the caller allocates
+ *     the cache arena and the workspace with the sizes hkv_query_sizes reports and
+ *     owns them.  Q/K/V/out buffers are borrowed for the duration of the call.
+ *   - hkv_compress, hkv_decode_attn and hkv_full_decode_attn only enqueue work on
+ *     `stream`; they never synchronise and never read device memory on the host.
+ *     hkv_cache_create, hkv_cache_export, hkv_cache_import and hkv_cache_rewind
+ *     perform small synchronous copies.
+ *   - Every function returns an hkv_status (0 = ok, negative = error).  Argument
+ *     errors are found on the host before anything is enqueued; on error nothing
+ *     is enqueued and no state changes.
+ *   - head_dim must be 128; n_q_heads / n_kv_heads (the query group size G) must
+ *     be an integer in 1..8.
+ *   - Ties in every selection go to the lower index.
+ */
+#ifndef HKV_H
+#define HKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HKV_ABI_VERSION 1u
+
+#ifndef HKV_API
+#define HKV_API __attribute__((visibility("default")))
+#endif
+
+typedef enum {
+  HKV_OK = 0,
+  HKV_EINVAL = -1,   /* null pointer, bad struct size / version, bad enum value */
+  HKV_ESHAPE = -2,   /* unsupported shape (head_dim, group size, window, chunk size, batch) */
+  HKV_EBUDGET = -3,  /* a budget is < 1 */
+  HKV_EALIGN = -4,   /* a device pointer is not 16-byte aligned */
+  HKV_ENOSPACE = -5, /* caller buffer too small, or the per-head tail is full */
+  HKV_ESTATE = -6,   /* call out of order (decode before compress, ...) */
+  HKV_EHIP = -7      /* a HIP runtime call failed */
+} hkv_status;
+
+typedef enum { HKV_F32 = 0, HKV_BF16 = 1 } hkv_dtype;
+typedef enum { HKV_STATIC = 0, HKV_DYNAMIC = 1 } hkv_head_type;
+
+/* What hkv_cache_export / hkv_cache_import move for one (sequence, layer, KV head) unit. */
+typedef enum {
+  HKV_X_KEPT_IDX = 0,   /* static : int32[retained]  ascending prompt positions kept            */
+  HKV_X_SCORES = 1,     /* static : float[C]         s_w of Appendix A                           */
+  HKV_X_CHUNK_SEL = 2,  /* dynamic: int32[k]         chunks picked by the last decode step, asc. */
+  HKV_X_CHUNK_SIGMA = 3,/* dynamic: float[n_chunks]  chunk scores of the last decode step        */
+  HKV_X_CHUNK_MEAN = 4, /* dynamic: dtype[n_chunks][head_dim] chunk summaries                    */
+  HKV_X_K_ROWS = 5,     /* dtype[rows][head_dim]: static = compacted rows then tail,
+                           dynamic = the whole prompt then tail                                  */
+  HKV_X_V_ROWS = 6
+} hkv_export_kind;
+
+typedef struct {
+  uint32_t struct_size;     /* sizeof(hkv_config) */
+  uint32_t abi_version;     /* HKV_ABI_VERSION */
+  int32_t n_layers;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;         /* 128 */
+  int32_t dtype;            /* hkv_dtype of Q, K, V, out and of the cache */
+  int32_t window;           /* w: observation-window length (Appendix A), 1..256, G*w <= 256 */
+  int32_t chunk_size;       /* c: tokens per chunk (Appendix A), power of two >= 4; used when
+                               hkv_plan.chunk_size is NULL */
+  int32_t score_causal;     /* 0: S_w as printed (no mask); 1: window row i sees keys <= C-w+i */
+  int32_t max_new_tokens;   /* capacity of every head's uncompressed decode tail */
+  float softmax_scale;      /* 0 -> 1/sqrt(head_dim) */
+} hkv_config;
+
+/* Per-prompt plan.  All arrays live in HOST memory and are only read during the call. */
+typedef struct {
+  int32_t batch;               /* number of sequences, 1..4096 */
+  const int32_t* cu_seqlens;   /* [host] [batch+1] packed token offsets, cu_seqlens[0] = 0 */
+  const uint8_t* is_visual;    /* [host] [total_tokens] 1 = visual token, 0 = text token */
+  const uint8_t* head_type;    /* [host] [batch][n_layers][n_kv_heads] hkv_head_type */
+  const int32_t* budget;       /* [host] [batch][n_layers][n_kv_heads] tokens, >= 1.
+                                  static : total prompt tokens retained, window and historical
+                                           text included (Appendix A); values above what exists
+                                           are clamped;
+                                  dynamic: tokens gathered per step; k = max(1, budget / c)
+                                           chunks, at most all chunks */
+  const int32_t* chunk_size;   /* [host] [batch] per-sequence chunk size, or NULL */
+} hkv_plan;
+
+typedef struct hkv_cache hkv_cache;   /* opaque host-side descriptor */
+
+/* Sizes of the device arena that holds the compressed cache (`cache_bytes`) and of the
+ * scratch workspace hkv_compress / hkv_decode_attn need (`workspace_bytes`, the maximum over
+ * both calls and any layer range). */
+HKV_API int hkv_query_sizes(const hkv_config* cfg, const hkv_plan* plan, size_t* cache_bytes,
+                    size_t* workspace_bytes);
+
+/* Lay the cache out inside `cache_dev` ([dev], >= cache_bytes, 256-byte aligned) and upload its
+ * descriptor tables (synchronous copy).  *out is a host object freed by hkv_cache_destroy; the
+ * device arena stays the caller's. */
+HKV_API int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev, size_t cache_bytes,
+                     hkv_cache** out);
+
+/* Prefill compression of layers [layer_begin, layer_end) (Section 3.3, Appendix A).
+ *   q_window [dev] [n][batch][window][n_q_heads][head_dim]  queries of each sequence's last
+ *            `window` prompt positions,
+ *   k, v     [dev] [n][total_tokens][n_kv_heads][head_dim]  prompt keys / values,
+ * with n = layer_end - layer_begin: the tensors hold exactly the layers of the call, in order.
+ * The cache keeps COPIES of what it retains; k and v may be released afterwards. */
+HKV_API int hkv_compress(hkv_cache* cache, int layer_begin, int layer_end, const void* q_window, const void* k,
+                 const void* v, void* workspace, size_t workspace_bytes, void* stream);
+
+/* One decode step of layers [layer_begin, layer_end).
+ *   q            [dev] [n][batch][n_q_heads][head_dim]
+ *   k_new, v_new [dev] [n][batch][n_kv_heads][head_dim] or both NULL (no append)
+ *   out          [dev] [n][batch][n_q_heads][head_dim]
+ * New K/V rows are appended to every head's tail first and take part in this step's attention.
+ * Returns HKV_ENOSPACE (nothing enqueued) when a tail would exceed max_new_tokens. */
+HKV_API int hkv_decode_attn(hkv_cache* cache, int layer_begin, int layer_end, const void* q, const void* k_new,
+                    const void* v_new, void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Uncompressed decode attention over caller-held K/V, the comparison kernel for the decode path:
+ * every head attends all tokens of its sequence.
+ *   cu_seqlens [host] [batch+1], batch <= 256
+ *   q, out     [dev] [n_layers_call][batch][n_q_heads][head_dim]
+ *   k, v       [dev] [n_layers_call][total_tokens][n_kv_heads][head_dim]
+ * *workspace_bytes of hkv_full_workspace_size tells the scratch it needs. */
+HKV_API int hkv_full_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens,
+                            int n_layers_call, size_t* workspace_bytes);
+HKV_API int hkv_full_decode_attn(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens,
+                         int n_layers_call, const void* q, const void* k, const void* v, void* out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Forget all appended decode tokens (tail length back to 0); the compressed prompt stays. */
+HKV_API int hkv_cache_rewind(hkv_cache* cache, void* stream);
+
+/* Per-unit facts computed on the host at creation (no device access):
+ * retained prompt rows (static) or gathered rows k*c (dynamic), number of chunks and k. */
+HKV_API int hkv_cache_unit_info(const hkv_cache* cache, int seq, int layer, int head, int32_t* prompt_rows,
+                        int32_t* n_chunks, int32_t* k_chunks);
+
+/* Same facts straight from a config and plan, without a cache or a device (host planning only). */
+HKV_API int hkv_plan_unit_info(const hkv_config* cfg, const hkv_plan* plan, int seq, int layer, int head,
+                               int32_t* prompt_rows, int32_t* n_chunks, int32_t* k_chunks);
+
+/* Bytes of K/V/summary data one decode step of layers [layer_begin, layer_end) must read with
+ * `tail` appended tokens per head: sum over static heads of 2*R*(rows + tail) and over dynamic
+ * heads of n_chunks*R + 2*R*(k*c + tail), R = head_dim * element size. */
+HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int layer_end, int tail,
+                         uint64_t* bytes);
+
+/* Test / debug access to one unit (synchronises `stream`, then copies).  `dst`/`src` are [host].
+ * Export returns HKV_ENOSPACE if `bytes` is smaller than the item; *written gets its size. */
+HKV_API int hkv_cache_export(const hkv_cache* cache, int what, int seq, int layer, int head, void* dst,
+                     size_t bytes, size_t* written, void* stream);
+/* Import overwrites HKV_X_SCORES (static) or HKV_X_CHUNK_SIGMA / HKV_X_CHUNK_MEAN (dynamic). */
+HKV_API int hkv_cache_import(hkv_cache* cache, int what, int seq, int layer, int head, const void* src,
+                     size_t bytes, void* stream);
+
+/* Stage-isolated runs for selection tests:
+ * hkv_compress_from_scores = hkv_compress without the scoring pass (uses the s_w stored in the
+ * cache, e.g. after hkv_cache_import); hkv_reselect_chunks re-runs the chunk top-k of the given
+ * layers from the stored chunk scores (no append, no attention). */
+HKV_API int hkv_compress_from_scores(hkv_cache* cache, int layer_begin, int layer_end, const void* k,
+                             const void* v, void* stream);
+HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end, void* stream);
+
+HKV_API void hkv_cache_destroy(hkv_cache* cache);   /* frees the host descriptor only */
+HKV_API const char* hkv_strerror(int status);
+HKV_API uint32_t hkv_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HKV_H */

@@ -1,0 +1,505 @@
+// Host side of libhkv: argument validation, cache layout planning, descriptor upload and kernel
+// sequencing behind the C ABI declared in hkv.h.  No device memory is allocated here.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "hkv_internal.h"
+
+using namespace hkv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_size(int dtype) { return dtype == HKV_BF16 ? 2 : 4; }
+
+struct Layout {
+  // host tables
+  std::vector<UnitDesc> units;
+  std::vector<int2> items;
+  std::vector<int32_t> static_units, dynamic_units;
+  std::vector<int32_t> static_begin, dynamic_begin, item_begin;   // [n_layers + 1]
+  std::vector<int32_t> cu;
+  int64_t total_tokens = 0;
+  int32_t max_C = 0, max_rows_static = 0, max_chunks = 0;
+  // element counts
+  int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
+  // arena offsets (bytes)
+  size_t off_units = 0, off_items = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
+         off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
+  size_t ws_bytes = 0;
+};
+
+int validate_config(const hkv_config* cfg) {
+  if (!cfg) return HKV_EINVAL;
+  if (cfg->struct_size != sizeof(hkv_config) || cfg->abi_version != HKV_ABI_VERSION) return HKV_EINVAL;
+  if (cfg->dtype != HKV_F32 && cfg->dtype != HKV_BF16) return HKV_EINVAL;
+  if (cfg->score_causal != 0 && cfg->score_causal != 1) return HKV_EINVAL;
+  if (cfg->head_dim != kD) return HKV_ESHAPE;
+  if (cfg->n_layers < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1) return HKV_ESHAPE;
+  if (cfg->n_q_heads % cfg->n_kv_heads != 0) return HKV_ESHAPE;
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  if (G < 1 || G > kMaxG) return HKV_ESHAPE;
+  if (cfg->window < 1 || G * cfg->window > kMaxScoreRows) return HKV_ESHAPE;
+  if (cfg->max_new_tokens < 0) return HKV_ESHAPE;
+  if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
+  return HKV_OK;
+}
+
+inline bool pow2_ge4(int c) { return c >= 4 && (c & (c - 1)) == 0; }
+
+int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
+  int rc = validate_config(cfg);
+  if (rc != HKV_OK) return rc;
+  if (!plan || !plan->cu_seqlens || !plan->is_visual || !plan->head_type || !plan->budget) return HKV_EINVAL;
+  if (plan->batch < 1 || plan->batch > 4096) return HKV_ESHAPE;
+  const int B = plan->batch, L = cfg->n_layers, H = cfg->n_kv_heads, w = cfg->window;
+  const int G = cfg->n_q_heads / H;
+  if (plan->cu_seqlens[0] != 0) return HKV_EINVAL;
+  lo.cu.assign(plan->cu_seqlens, plan->cu_seqlens + B + 1);
+  std::vector<int32_t> n_txt(B), n_vis(B), csz(B);
+  for (int b = 0; b < B; ++b) {
+    const int64_t C = (int64_t)lo.cu[b + 1] - lo.cu[b];
+    if (C < w || C < 1) return HKV_ESHAPE;               // the window must fit in the prompt
+    csz[b] = plan->chunk_size ? plan->chunk_size[b] : cfg->chunk_size;
+    if (!pow2_ge4(csz[b])) return HKV_ESHAPE;
+    int t = 0, v = 0;
+    for (int64_t j = lo.cu[b]; j < lo.cu[b + 1] - w; ++j) {
+      if (plan->is_visual[j] > 1) return HKV_EINVAL;
+      (plan->is_visual[j] ? v : t)++;
+    }
+    n_txt[b] = t; n_vis[b] = v;
+    lo.max_C = std::max<int32_t>(lo.max_C, (int32_t)C);
+  }
+  lo.total_tokens = lo.cu[B];
+
+  lo.units.resize((size_t)L * B * H);
+  lo.static_begin.assign(L + 1, 0); lo.dynamic_begin.assign(L + 1, 0); lo.item_begin.assign(L + 1, 0);
+  for (int l = 0; l < L; ++l) {
+    lo.static_begin[l] = (int32_t)lo.static_units.size();
+    lo.dynamic_begin[l] = (int32_t)lo.dynamic_units.size();
+    lo.item_begin[l] = (int32_t)lo.items.size();
+    for (int b = 0; b < B; ++b) {
+      const int32_t C = lo.cu[b + 1] - lo.cu[b];
+      for (int h = 0; h < H; ++h) {
+        const size_t pi = ((size_t)b * L + l) * H + h;       // plan arrays are [batch][layer][head]
+        const int32_t u = (int32_t)(((size_t)l * B + b) * H + h);
+        const int ht = plan->head_type[pi];
+        const int64_t budget = plan->budget[pi];
+        if (ht != HKV_STATIC && ht != HKV_DYNAMIC) return HKV_EINVAL;
+        if (budget < 1) return HKV_EBUDGET;
+        UnitDesc d;
+        std::memset(&d, 0, sizeof(d));
+        d.seq_start = lo.cu[b]; d.C = C; d.kind = ht; d.seq = b; d.layer = l; d.head = h;
+        d.kv_row_off = lo.n_rows;
+        int64_t phys_rows;
+        if (ht == HKV_STATIC) {
+          // Keep set = window + historical text + Top-M historical visual, M = budget - w - #text
+          // (Appendix A); text outranks visual when the budget is short (Section 3.3).
+          if (budget < w) { d.sel_mode = kSelSuffix; d.m_sel = 0; d.n_cand = 0; d.n_prompt_rows = (int32_t)budget; }
+          else {
+            const int64_t M = budget - w - n_txt[b];
+            if (M < 0) { d.sel_mode = kSelText; d.m_sel = (int32_t)(budget - w); d.n_cand = n_txt[b]; d.n_prompt_rows = (int32_t)budget; }
+            else { d.sel_mode = kSelVisual; d.m_sel = (int32_t)std::min<int64_t>(M, n_vis[b]); d.n_cand = n_vis[b];
+                   d.n_prompt_rows = w + n_txt[b] + d.m_sel; }
+          }
+          d.aux_off = lo.n_scores; lo.n_scores += C;
+          d.idx_off = lo.n_kept; lo.n_kept += d.n_prompt_rows;
+          d.type_ord = (int32_t)lo.static_units.size();
+          lo.static_units.push_back(u);
+          lo.max_rows_static = std::max(lo.max_rows_static, d.n_prompt_rows);
+          phys_rows = d.n_prompt_rows;
+        } else {
+          const int c = csz[b];
+          int lg = 0; while ((1 << lg) < c) ++lg;
+          d.c_log2 = lg;
+          d.n_chunks = (C + c - 1) / c;
+          d.k_sel = (int32_t)std::min<int64_t>(std::max<int64_t>(1, budget / c), d.n_chunks);
+          d.n_prompt_rows = d.k_sel * c;
+          d.aux_off = lo.n_sigma; lo.n_sigma += d.n_chunks;
+          d.idx_off = lo.n_sel; lo.n_sel += d.k_sel;
+          d.type_ord = (int32_t)lo.dynamic_units.size();
+          lo.dynamic_units.push_back(u);
+          lo.max_chunks = std::max(lo.max_chunks, d.n_chunks);
+          phys_rows = C;
+        }
+        lo.n_rows += phys_rows + cfg->max_new_tokens;
+        d.item_begin = (int32_t)lo.items.size();
+        d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + kTile - 1) / kTile);
+        for (int t = 0; t < d.n_tiles_max; ++t) lo.items.push_back(make_int2(u, t));
+        if (lo.items.size() > (size_t)0x7fffff00) return HKV_ESHAPE;
+        lo.units[u] = d;
+      }
+    }
+  }
+  lo.static_begin[L] = (int32_t)lo.static_units.size();
+  lo.dynamic_begin[L] = (int32_t)lo.dynamic_units.size();
+  lo.item_begin[L] = (int32_t)lo.items.size();
+  if ((size_t)(kD + 256 + 8 + lo.max_chunks) * sizeof(float) > 64 * 1024) return HKV_ESHAPE;
+
+  const size_t es = elem_size(cfg->dtype);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  lo.off_units = take(lo.units.size() * sizeof(UnitDesc));
+  lo.off_items = take(lo.items.size() * sizeof(int2));
+  lo.off_static = take(std::max<size_t>(1, lo.static_units.size()) * 4);
+  lo.off_dynamic = take(std::max<size_t>(1, lo.dynamic_units.size()) * 4);
+  lo.off_vis = take((size_t)lo.total_tokens);
+  lo.off_cnt = take((size_t)2 * L * 4);
+  lo.off_kept = take((size_t)std::max<int64_t>(1, lo.n_kept) * 4);
+  lo.off_sel = take((size_t)std::max<int64_t>(1, lo.n_sel) * 4);
+  lo.off_scores = take((size_t)std::max<int64_t>(1, lo.n_scores) * 4);
+  lo.off_sigma = take((size_t)std::max<int64_t>(1, lo.n_sigma) * 4);
+  lo.off_mu = take((size_t)std::max<int64_t>(1, lo.n_sigma) * kD * es);
+  lo.off_k = take((size_t)lo.n_rows * kD * es);
+  lo.off_v = take((size_t)lo.n_rows * kD * es);
+  lo.arena_bytes = off;
+
+  const int n_splits = (lo.max_C + kKeysPerBlock - 1) / kKeysPerBlock;
+  const size_t ws_compress = align_up(lo.static_units.size() * (size_t)n_splits * kMaxScoreRows * sizeof(float2)) +
+                             align_up(lo.static_units.size() * (size_t)kMaxScoreRows * sizeof(float2));
+  const size_t ws_decode = align_up(lo.items.size() * (size_t)G * kPartStride * sizeof(float));
+  lo.ws_bytes = std::max<size_t>(kAlign, std::max(ws_compress, ws_decode));
+  return HKV_OK;
+}
+
+}  // namespace
+
+struct hkv_cache {
+  hkv_config cfg;
+  int32_t batch;
+  Layout lo;
+  CacheView cv;
+  char* arena;
+  std::vector<int32_t> host_tail;     // [n_layers] appended tokens (host mirror of the device counter)
+  std::vector<uint8_t> compressed;    // [n_layers]
+};
+
+extern "C" {
+
+uint32_t hkv_abi_version(void) { return HKV_ABI_VERSION; }
+
+const char* hkv_strerror(int status) {
+  switch (status) {
+    case HKV_OK: return "ok";
+    case HKV_EINVAL: return "invalid argument";
+    case HKV_ESHAPE: return "unsupported shape";
+    case HKV_EBUDGET: return "budget must be at least 1 token";
+    case HKV_EALIGN: return "device pointer not 16-byte aligned";
+    case HKV_ENOSPACE: return "buffer too small or decode tail full";
+    case HKV_ESTATE: return "call out of order";
+    case HKV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int hkv_query_sizes(const hkv_config* cfg, const hkv_plan* plan, size_t* cache_bytes, size_t* workspace_bytes) {
+  if (!cache_bytes || !workspace_bytes) return HKV_EINVAL;
+  Layout lo;
+  const int rc = plan_layout(cfg, plan, lo);
+  if (rc != HKV_OK) return rc;
+  *cache_bytes = lo.arena_bytes;
+  *workspace_bytes = lo.ws_bytes;
+  return HKV_OK;
+}
+
+int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev, size_t cache_bytes,
+                     hkv_cache** out) {
+  if (!out || !cache_dev) return HKV_EINVAL;
+  if (reinterpret_cast<uintptr_t>(cache_dev) % kAlign != 0) return HKV_EALIGN;
+  hkv_cache* c = new (std::nothrow) hkv_cache();
+  if (!c) return HKV_EINVAL;
+  int rc = plan_layout(cfg, plan, c->lo);
+  if (rc != HKV_OK) { delete c; return rc; }
+  if (cache_bytes < c->lo.arena_bytes) { delete c; return HKV_ENOSPACE; }
+  c->cfg = *cfg;
+  c->batch = plan->batch;
+  c->arena = static_cast<char*>(cache_dev);
+  c->host_tail.assign(cfg->n_layers, 0);
+  c->compressed.assign(cfg->n_layers, 0);
+  const Layout& lo = c->lo;
+  char* a = c->arena;
+  CacheView& cv = c->cv;
+  cv.units = reinterpret_cast<const UnitDesc*>(a + lo.off_units);
+  cv.items = reinterpret_cast<const int2*>(a + lo.off_items);
+  cv.static_units = reinterpret_cast<const int32_t*>(a + lo.off_static);
+  cv.dynamic_units = reinterpret_cast<const int32_t*>(a + lo.off_dynamic);
+  cv.is_visual = reinterpret_cast<const uint8_t*>(a + lo.off_vis);
+  cv.cnt_a = reinterpret_cast<int32_t*>(a + lo.off_cnt);
+  cv.cnt_b = cv.cnt_a + cfg->n_layers;
+  cv.kept_idx = reinterpret_cast<int32_t*>(a + lo.off_kept);
+  cv.sel = reinterpret_cast<int32_t*>(a + lo.off_sel);
+  cv.scores = reinterpret_cast<float*>(a + lo.off_scores);
+  cv.sigma = reinterpret_cast<float*>(a + lo.off_sigma);
+  cv.mu = a + lo.off_mu;
+  cv.k_rows = a + lo.off_k;
+  cv.v_rows = a + lo.off_v;
+  cv.n_layers = cfg->n_layers; cv.batch = plan->batch; cv.n_q_heads = cfg->n_q_heads; cv.n_kv_heads = cfg->n_kv_heads;
+  cv.G = cfg->n_q_heads / cfg->n_kv_heads; cv.window = cfg->window; cv.max_new = cfg->max_new_tokens;
+  cv.causal = cfg->score_causal;
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  cv.scale_log2e = scale * 1.4426950408889634f;
+
+  hipError_t e = hipSuccess;
+  auto up = [&](size_t off, const void* src, size_t bytes) {
+    if (e == hipSuccess && bytes) e = hipMemcpy(a + off, src, bytes, hipMemcpyHostToDevice);
+  };
+  up(lo.off_units, lo.units.data(), lo.units.size() * sizeof(UnitDesc));
+  up(lo.off_items, lo.items.data(), lo.items.size() * sizeof(int2));
+  up(lo.off_static, lo.static_units.data(), lo.static_units.size() * 4);
+  up(lo.off_dynamic, lo.dynamic_units.data(), lo.dynamic_units.size() * 4);
+  up(lo.off_vis, plan->is_visual, (size_t)lo.total_tokens);
+  if (e == hipSuccess) e = hipMemset(a + lo.off_cnt, 0, (size_t)2 * cfg->n_layers * 4);
+  if (e != hipSuccess) { delete c; return HKV_EHIP; }
+  *out = c;
+  return HKV_OK;
+}
+
+void hkv_cache_destroy(hkv_cache* cache) { delete cache; }
+
+static int check_range(const hkv_cache* c, int lb, int le) {
+  if (!c) return HKV_EINVAL;
+  if (lb < 0 || le > c->cfg.n_layers || lb >= le) return HKV_EINVAL;
+  return HKV_OK;
+}
+
+static int compress_impl(hkv_cache* c, int lb, int le, const void* q_window, const void* k, const void* v,
+                         void* workspace, size_t workspace_bytes, void* stream, bool do_scoring) {
+  int rc = check_range(c, lb, le);
+  if (rc != HKV_OK) return rc;
+  if (!k || !v || (do_scoring && (!q_window || !workspace))) return HKV_EINVAL;
+  if (!aligned16(k) || !aligned16(v) || (do_scoring && (!aligned16(q_window) || !aligned16(workspace)))) return HKV_EALIGN;
+  if (do_scoring && workspace_bytes < c->lo.ws_bytes) return HKV_ENOSPACE;
+  const Layout& lo = c->lo;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int sb = lo.static_begin[lb], ns = lo.static_begin[le] - sb;
+  const int db = lo.dynamic_begin[lb], nd = lo.dynamic_begin[le] - db;
+  hipError_t e = hipSuccess;
+  if (do_scoring && ns > 0) {
+    const int n_splits = (lo.max_C + kKeysPerBlock - 1) / kKeysPerBlock;
+    float2* part = static_cast<float2*>(workspace);
+    float2* fin = reinterpret_cast<float2*>(static_cast<char*>(workspace) +
+                                            align_up((size_t)ns * n_splits * kMaxScoreRows * sizeof(float2)));
+    e = launch_score(c->cv, c->cfg.dtype, lb, sb, ns, lo.max_C, q_window, k, lo.total_tokens, part, fin, st);
+  }
+  if (e == hipSuccess) e = launch_select(c->cv, sb, ns, st);
+  if (e == hipSuccess) e = launch_compact(c->cv, c->cfg.dtype, lb, sb, ns, lo.max_rows_static, k, v, lo.total_tokens, st);
+  if (e == hipSuccess) e = launch_adopt(c->cv, c->cfg.dtype, lb, db, nd, lo.max_chunks, k, v, lo.total_tokens, st);
+  if (e == hipSuccess) e = launch_rewind(c->cv, lb, le, st);
+  if (e != hipSuccess) return HKV_EHIP;
+  for (int l = lb; l < le; ++l) { c->compressed[l] = 1; c->host_tail[l] = 0; }
+  return HKV_OK;
+}
+
+int hkv_compress(hkv_cache* cache, int layer_begin, int layer_end, const void* q_window, const void* k,
+                 const void* v, void* workspace, size_t workspace_bytes, void* stream) {
+  return compress_impl(cache, layer_begin, layer_end, q_window, k, v, workspace, workspace_bytes, stream, true);
+}
+
+int hkv_compress_from_scores(hkv_cache* cache, int layer_begin, int layer_end, const void* k, const void* v,
+                             void* stream) {
+  return compress_impl(cache, layer_begin, layer_end, nullptr, k, v, nullptr, 0, stream, false);
+}
+
+int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new, void* out,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_range(c, lb, le);
+  if (rc != HKV_OK) return rc;
+  if (!q || !out || !workspace) return HKV_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return HKV_EINVAL;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(workspace) || !aligned16(k_new) || !aligned16(v_new)) return HKV_EALIGN;
+  if (workspace_bytes < c->lo.ws_bytes) return HKV_ENOSPACE;
+  for (int l = lb; l < le; ++l) {
+    if (!c->compressed[l]) return HKV_ESTATE;
+    if (k_new && c->host_tail[l] + 1 > c->cfg.max_new_tokens) return HKV_ENOSPACE;
+  }
+  const Layout& lo = c->lo;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int ib = lo.item_begin[lb], ni = lo.item_begin[le] - ib;
+  hipError_t e = launch_prepare(c->cv, c->cfg.dtype, lb, le, q, k_new, v_new, 0, 1, lo.max_chunks, st);
+  if (e == hipSuccess) e = launch_attn_partial(c->cv, c->cfg.dtype, lb, ib, ni, q, static_cast<float*>(workspace), st);
+  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, ib, static_cast<const float*>(workspace), out, 1, st);
+  if (e != hipSuccess) return HKV_EHIP;
+  if (k_new) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
+  return HKV_OK;
+}
+
+int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
+  int rc = check_range(c, lb, le);
+  if (rc != HKV_OK) return rc;
+  hipError_t e = launch_prepare(c->cv, c->cfg.dtype, lb, le, nullptr, nullptr, nullptr, 1, 0, c->lo.max_chunks,
+                                static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HKV_OK : HKV_EHIP;
+}
+
+int hkv_cache_rewind(hkv_cache* c, void* stream) {
+  if (!c) return HKV_EINVAL;
+  hipError_t e = launch_rewind(c->cv, 0, c->cfg.n_layers, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return HKV_EHIP;
+  std::fill(c->host_tail.begin(), c->host_tail.end(), 0);
+  return HKV_OK;
+}
+
+static int full_view(const hkv_config* cfg, int32_t batch, const int32_t* cu, int n_layers_call, FullView& fv) {
+  int rc = validate_config(cfg);
+  if (rc != HKV_OK) return rc;
+  if (!cu) return HKV_EINVAL;
+  if (batch < 1 || batch > kFullMaxBatch || n_layers_call < 1) return HKV_ESHAPE;
+  if (cu[0] != 0) return HKV_EINVAL;
+  int32_t max_len = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (cu[b + 1] <= cu[b]) return HKV_ESHAPE;
+    max_len = std::max(max_len, cu[b + 1] - cu[b]);
+  }
+  std::memset(&fv, 0, sizeof(fv));
+  std::memcpy(fv.cu, cu, (size_t)(batch + 1) * 4);
+  fv.batch = batch; fv.n_layers_call = n_layers_call; fv.n_q_heads = cfg->n_q_heads; fv.n_kv_heads = cfg->n_kv_heads;
+  fv.G = cfg->n_q_heads / cfg->n_kv_heads;
+  fv.n_tiles_max = (max_len + kTile - 1) / kTile;
+  fv.total_tokens = cu[batch];
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  fv.scale_log2e = scale * 1.4426950408889634f;
+  if ((int64_t)n_layers_call * batch * cfg->n_kv_heads > 65535) return HKV_ESHAPE;
+  return HKV_OK;
+}
+
+int hkv_full_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens, int n_layers_call,
+                            size_t* workspace_bytes) {
+  if (!workspace_bytes) return HKV_EINVAL;
+  FullView fv;
+  int rc = full_view(cfg, batch, cu_seqlens, n_layers_call, fv);
+  if (rc != HKV_OK) return rc;
+  *workspace_bytes = align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float));
+  return HKV_OK;
+}
+
+int hkv_full_decode_attn(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens, int n_layers_call,
+                         const void* q, const void* k, const void* v, void* out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  FullView fv;
+  int rc = full_view(cfg, batch, cu_seqlens, n_layers_call, fv);
+  if (rc != HKV_OK) return rc;
+  if (!q || !k || !v || !out || !workspace) return HKV_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(workspace)) return HKV_EALIGN;
+  size_t need = 0;
+  hkv_full_workspace_size(cfg, batch, cu_seqlens, n_layers_call, &need);
+  if (workspace_bytes < need) return HKV_ENOSPACE;
+  hipError_t e = launch_full_attn(fv, cfg->dtype, q, k, v, static_cast<float*>(workspace), out,
+                                  static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? HKV_OK : HKV_EHIP;
+}
+
+static const UnitDesc* find_unit(const hkv_cache* c, int seq, int layer, int head) {
+  if (!c || seq < 0 || seq >= c->batch || layer < 0 || layer >= c->cfg.n_layers || head < 0 ||
+      head >= c->cfg.n_kv_heads)
+    return nullptr;
+  return &c->lo.units[((size_t)layer * c->batch + seq) * c->cfg.n_kv_heads + head];
+}
+
+int hkv_cache_unit_info(const hkv_cache* c, int seq, int layer, int head, int32_t* prompt_rows, int32_t* n_chunks,
+                        int32_t* k_chunks) {
+  const UnitDesc* d = find_unit(c, seq, layer, head);
+  if (!d) return HKV_EINVAL;
+  if (prompt_rows) *prompt_rows = d->n_prompt_rows;
+  if (n_chunks) *n_chunks = d->kind == HKV_DYNAMIC ? d->n_chunks : 0;
+  if (k_chunks) *k_chunks = d->kind == HKV_DYNAMIC ? d->k_sel : 0;
+  return HKV_OK;
+}
+
+int hkv_plan_unit_info(const hkv_config* cfg, const hkv_plan* plan, int seq, int layer, int head,
+                       int32_t* prompt_rows, int32_t* n_chunks, int32_t* k_chunks) {
+  Layout lo;
+  const int rc = plan_layout(cfg, plan, lo);
+  if (rc != HKV_OK) return rc;
+  if (seq < 0 || seq >= plan->batch || layer < 0 || layer >= cfg->n_layers || head < 0 || head >= cfg->n_kv_heads)
+    return HKV_EINVAL;
+  const UnitDesc& d = lo.units[((size_t)layer * plan->batch + seq) * cfg->n_kv_heads + head];
+  if (prompt_rows) *prompt_rows = d.n_prompt_rows;
+  if (n_chunks) *n_chunks = d.kind == HKV_DYNAMIC ? d.n_chunks : 0;
+  if (k_chunks) *k_chunks = d.kind == HKV_DYNAMIC ? d.k_sel : 0;
+  return HKV_OK;
+}
+
+int hkv_cache_step_bytes(const hkv_cache* c, int lb, int le, int tail, uint64_t* bytes) {
+  int rc = check_range(c, lb, le);
+  if (rc != HKV_OK) return rc;
+  if (!bytes || tail < 0) return HKV_EINVAL;
+  const uint64_t R = (uint64_t)kD * elem_size(c->cfg.dtype);
+  const size_t upl = (size_t)c->batch * c->cfg.n_kv_heads;
+  uint64_t tot = 0;
+  for (size_t u = lb * upl; u < le * upl; ++u) {
+    const UnitDesc& d = c->lo.units[u];
+    if (d.kind == HKV_STATIC) tot += 2 * R * (uint64_t)(d.n_prompt_rows + tail);
+    else {
+      // selected chunks' actual rows: k*c, minus what the short last chunk lacks cannot be known on
+      // the host (it depends on the selection), so the nominal k*c is used
+      tot += (uint64_t)d.n_chunks * R + 2 * R * (uint64_t)(d.n_prompt_rows + tail);
+    }
+  }
+  *bytes = tot;
+  return HKV_OK;
+}
+
+static int locate(const hkv_cache* c, int what, const UnitDesc* d, size_t& off, size_t& bytes) {
+  const size_t es = elem_size(c->cfg.dtype);
+  const Layout& lo = c->lo;
+  const int tail = c->host_tail[d->layer];
+  switch (what) {
+    case HKV_X_KEPT_IDX:
+      if (d->kind != HKV_STATIC) return HKV_EINVAL;
+      off = lo.off_kept + (size_t)d->idx_off * 4; bytes = (size_t)d->n_prompt_rows * 4; return HKV_OK;
+    case HKV_X_SCORES:
+      if (d->kind != HKV_STATIC) return HKV_EINVAL;
+      off = lo.off_scores + (size_t)d->aux_off * 4; bytes = (size_t)d->C * 4; return HKV_OK;
+    case HKV_X_CHUNK_SEL:
+      if (d->kind != HKV_DYNAMIC) return HKV_EINVAL;
+      off = lo.off_sel + (size_t)d->idx_off * 4; bytes = (size_t)d->k_sel * 4; return HKV_OK;
+    case HKV_X_CHUNK_SIGMA:
+      if (d->kind != HKV_DYNAMIC) return HKV_EINVAL;
+      off = lo.off_sigma + (size_t)d->aux_off * 4; bytes = (size_t)d->n_chunks * 4; return HKV_OK;
+    case HKV_X_CHUNK_MEAN:
+      if (d->kind != HKV_DYNAMIC) return HKV_EINVAL;
+      off = lo.off_mu + (size_t)d->aux_off * kD * es; bytes = (size_t)d->n_chunks * kD * es; return HKV_OK;
+    case HKV_X_K_ROWS:
+    case HKV_X_V_ROWS: {
+      const size_t rows = (size_t)(d->kind == HKV_STATIC ? d->n_prompt_rows : d->C) + tail;
+      off = (what == HKV_X_K_ROWS ? lo.off_k : lo.off_v) + (size_t)d->kv_row_off * kD * es;
+      bytes = rows * kD * es; return HKV_OK;
+    }
+    default: return HKV_EINVAL;
+  }
+}
+
+int hkv_cache_export(const hkv_cache* c, int what, int seq, int layer, int head, void* dst, size_t bytes,
+                     size_t* written, void* stream) {
+  const UnitDesc* d = find_unit(c, seq, layer, head);
+  if (!d) return HKV_EINVAL;
+  size_t off = 0, need = 0;
+  int rc = locate(c, what, d, off, need);
+  if (rc != HKV_OK) return rc;
+  if (written) *written = need;
+  if (!dst || bytes < need) return HKV_ENOSPACE;
+  if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return HKV_EHIP;
+  if (need && hipMemcpy(dst, c->arena + off, need, hipMemcpyDeviceToHost) != hipSuccess) return HKV_EHIP;
+  return HKV_OK;
+}
+
+int hkv_cache_import(hkv_cache* c, int what, int seq, int layer, int head, const void* src, size_t bytes,
+                     void* stream) {
+  const UnitDesc* d = find_unit(c, seq, layer, head);
+  if (!d || !src) return HKV_EINVAL;
+  if (what != HKV_X_SCORES && what != HKV_X_CHUNK_SIGMA && what != HKV_X_CHUNK_MEAN) return HKV_EINVAL;
+  size_t off = 0, need = 0;
+  int rc = locate(c, what, d, off, need);
+  if (rc != HKV_OK) return rc;
+  if (bytes != need) return HKV_ENOSPACE;
+  if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return HKV_EHIP;
+  if (need && hipMemcpy(c->arena + off, src, need, hipMemcpyHostToDevice) != hipSuccess) return HKV_EHIP;
+  return HKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,373 @@
+// Prefill-compression kernels of libhkv (gfx950), following the paper's Appendix A:
+//   score_kernel<pass 1>  observation-window logits on the matrix cores + per-row max / sum
+//   stats_finalize        combine the per-key-split row statistics in fixed order
+//   score_kernel<pass 2>  same logits again, softmax with the final row statistics, mean over the
+//                         G*w window rows -> relevance vector s_w over all prompt tokens
+//   select_kernel         Top-M of s_w over the historical visual tokens (radix select, ties to the
+//                         lower position) + window + historical text -> ascending kept positions
+//   compact_kernel        copy the kept K/V rows into the head's ragged cache segment
+//   adopt_kernel          dynamic heads: copy the whole K/V head-major into the cache and reduce
+//                         every chunk's keys to their mean (the chunk-level index)
+#include "hkv_device.h"
+#include "hkv_internal.h"
+#include "hkv_select.h"
+
+namespace hkv {
+
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+
+// One 32x32 tile update over a 16-byte piece of the head dimension.
+// a: this lane's piece of key row (lane % 32); b: this lane's piece of query row (lane % 32);
+// lanes 0-31 hold the first half of the piece pair, lanes 32-63 the second (same split in a and b).
+__device__ __forceinline__ floatx16 mma_piece(const uint4& a, const uint4& b, floatx16 c, bf16_t) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ floatx16 mma_piece(const uint4& a, const uint4& b, floatx16 c, float) {
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(bits_to_float(a.x), bits_to_float(b.x), c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(bits_to_float(a.y), bits_to_float(b.y), c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(bits_to_float(a.z), bits_to_float(b.z), c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(bits_to_float(a.w), bits_to_float(b.w), c, 0, 0, 0);
+  return c;
+}
+
+// grid = (key splits, static units of the call); block = 256 threads (4 waves).
+// Each block covers kKeysPerBlock keys of one static head; each wave 32 keys at a time against all
+// G*w window rows (row blocks of 32).  The matrix-core tile has keys along its register/row axis and
+// window rows along lanes, so row statistics reduce inside a lane and column sums across lanes.
+template <typename T, int PASS>
+__global__ __launch_bounds__(256) void score_kernel(CacheView cv, int layer_begin, int static_begin,
+                                                    const T* __restrict__ q_window, const T* __restrict__ k,
+                                                    int64_t total_tokens, float2* __restrict__ part_stats,
+                                                    const float2* __restrict__ final_stats, int n_splits_max) {
+  constexpr int ROWB = kD * sizeof(T);          // bytes per row
+  constexpr int PITCH = ROWB + 16;              // padded shared-memory pitch (bank spread)
+  constexpr int NPIECE = ROWB / 32;             // 32-byte piece pairs per row: 8 (bf16) / 16 (f32)
+  constexpr int NRB = kMaxScoreRows / 32;
+  extern __shared__ char qs[];                  // [rows_pad][PITCH]
+  __shared__ float2 wstats[4][kMaxScoreRows];
+
+  const int su = blockIdx.y;
+  const UnitDesc d = cv.units[cv.static_units[static_begin + su]];
+  const int key0 = blockIdx.x * kKeysPerBlock;
+  if (key0 >= d.C) return;
+  const int G = cv.G, w = cv.window;
+  const int rows = G * w;
+  const int n_rb = (rows + 31) / 32;
+  const int lrel = d.layer - layer_begin;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+
+  // stage the window queries: row r = g * w + i  <-  q_window[lrel][seq][i][head*G + g][:]
+  for (int idx = tid; idx < n_rb * 32 * (ROWB / 16); idx += 256) {
+    const int r = idx / (ROWB / 16), piece = idx % (ROWB / 16);
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (r < rows) {
+      const int g = r / w, i = r % w;
+      const size_t src = ((((size_t)lrel * cv.batch + d.seq) * w + i) * cv.n_q_heads + (size_t)d.head * G + g) * ROWB;
+      val = ld16(reinterpret_cast<const char*>(q_window) + src + piece * 16);
+    }
+    st16(qs + (size_t)r * PITCH + piece * 16, val);
+  }
+  __syncthreads();
+
+  float m_run[NRB], z_run[NRB];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = kNeg; z_run[rb] = 0.f; }
+
+  const char* kbase = reinterpret_cast<const char*>(k) +
+                      (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
+  const size_t kstride = (size_t)cv.n_kv_heads * ROWB;
+  const int hist_end = d.C - w;
+
+  for (int kt = 0; kt < kKeysPerBlock / 128; ++kt) {
+    const int j0 = key0 + (kt * 4 + wv) * 32;
+    if (j0 >= d.C) break;                        // wave-uniform
+    const int key = j0 + l32;
+    uint4 a[NPIECE];
+#pragma unroll
+    for (int j = 0; j < NPIECE; ++j) {
+      a[j] = make_uint4(0, 0, 0, 0);
+      if (key < d.C) a[j] = ld16(kbase + (size_t)key * kstride + j * 32 + half * 16);
+    }
+    float col[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) col[r] = 0.f;
+
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      if (rb < n_rb) {
+        floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        const char* qrow = qs + (size_t)(rb * 32 + l32) * PITCH + half * 16;
+#pragma unroll
+        for (int j = 0; j < NPIECE; ++j) acc = mma_piece(a[j], ld16(qrow + j * 32), acc, T{});
+        // acc[r] = q_row(rb*32 + l32) . k(j0 + 8*(r/4) + 4*half + r%4)
+        const int qr = rb * 32 + l32;
+        const int qi = qr % w;                   // position of the row inside the window
+        float lg[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kk = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+          const bool masked = (kk >= d.C) || (cv.causal && kk > hist_end + qi);
+          lg[r] = masked ? kNeg : acc[r] * cv.scale_log2e;
+        }
+        if constexpr (PASS == 1) {
+          float mx = lg[0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, lg[r]);
+          const float mn = fmaxf(m_run[rb], mx);
+          float z = z_run[rb] * fast_exp2(m_run[rb] - mn);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) z += (lg[r] > 0.5f * kNeg) ? fast_exp2(lg[r] - mn) : 0.f;
+          z_run[rb] = z; m_run[rb] = mn;
+        } else {
+          const float2 st = final_stats[(size_t)su * kMaxScoreRows + qr];   // (row max, 1/(Z*G*w)); zero for pad rows
+#pragma unroll
+          for (int r = 0; r < 16; ++r) col[r] += (lg[r] > 0.5f * kNeg) ? fast_exp2(lg[r] - st.x) * st.y : 0.f;
+        }
+      }
+    }
+    if constexpr (PASS == 2) {
+      float* sc = cv.scores + d.aux_off;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float tot = sum32(col[r]);         // over the 32 window rows held by this half-wave, then row blocks were already added
+        const int kk = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (l32 == 0 && kk < d.C) sc[kk] = tot;
+      }
+    }
+  }
+
+  if constexpr (PASS == 1) {
+    // fold the two half-waves (same window row, different keys), then the four waves
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      const float mo = lane_xor(m_run[rb], 32), zo = lane_xor(z_run[rb], 32);
+      const float mn = fmaxf(m_run[rb], mo);
+      z_run[rb] = z_run[rb] * fast_exp2(m_run[rb] - mn) + zo * fast_exp2(mo - mn);
+      m_run[rb] = mn;
+      if (half == 0) wstats[wv][rb * 32 + l32] = make_float2(m_run[rb], z_run[rb]);
+    }
+    __syncthreads();
+    for (int r = tid; r < kMaxScoreRows; r += 256) {
+      float mn = kNeg;
+      for (int x = 0; x < 4; ++x) mn = fmaxf(mn, wstats[x][r].x);
+      float z = 0.f;
+      for (int x = 0; x < 4; ++x) z += wstats[x][r].y * fast_exp2(wstats[x][r].x - mn);
+      part_stats[((size_t)su * n_splits_max + blockIdx.x) * kMaxScoreRows + r] = make_float2(mn, z);
+    }
+  }
+}
+
+// grid = static units of the call, block = kMaxScoreRows threads (one per window row).
+__global__ __launch_bounds__(kMaxScoreRows) void stats_finalize_kernel(CacheView cv, int static_begin,
+                                                                       const float2* __restrict__ part_stats,
+                                                                       float2* __restrict__ final_stats,
+                                                                       int n_splits_max) {
+  const int su = blockIdx.x, r = threadIdx.x;
+  const UnitDesc d = cv.units[cv.static_units[static_begin + su]];
+  const int n_splits = (d.C + kKeysPerBlock - 1) / kKeysPerBlock;
+  const int rows = cv.G * cv.window;
+  float2 res = make_float2(0.f, 0.f);
+  if (r < rows) {
+    const float2* p = part_stats + (size_t)su * n_splits_max * kMaxScoreRows + r;
+    float mn = kNeg;
+    for (int s = 0; s < n_splits; ++s) mn = fmaxf(mn, p[(size_t)s * kMaxScoreRows].x);
+    float z = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+      const float2 v = p[(size_t)s * kMaxScoreRows];
+      z += v.y * fast_exp2(v.x - mn);
+    }
+    res = make_float2(mn, 1.0f / (z * (float)rows));
+  }
+  final_stats[(size_t)su * kMaxScoreRows + r] = res;
+}
+
+// grid = static units of the call, block = 1024 threads.
+__global__ __launch_bounds__(1024) void select_kernel(CacheView cv, int static_begin) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t bc[2];
+  __shared__ int scan[18];
+  const UnitDesc d = cv.units[cv.static_units[static_begin + blockIdx.x]];
+  const float* sc = cv.scores + d.aux_off;
+  const uint8_t* vis = cv.is_visual + d.seq_start;
+  const int C = d.C, hist_end = d.C - cv.window, mode = d.sel_mode;
+  const int tid = threadIdx.x;
+
+  auto is_cand = [&](int j) -> bool {
+    if (mode == kSelVisual) return j < hist_end && vis[j] != 0;
+    if (mode == kSelText) return j < hist_end && vis[j] == 0;
+    return false;
+  };
+  auto is_fixed = [&](int j) -> bool {
+    if (mode == kSelVisual) return j >= hist_end || vis[j] == 0;
+    if (mode == kSelText) return j >= hist_end;
+    return j >= C - d.n_prompt_rows;
+  };
+
+  uint32_t T_key = 0xFFFFFFFFu;   // nothing is greater or equal: selects no candidate
+  int r_adm = 0;
+  if (d.m_sel >= d.n_cand) { T_key = 0; r_adm = d.n_cand; }       // everything (keys are >= 0)
+  else if (d.m_sel > 0) {
+    radix_select<1024>(C, d.m_sel,
+                       [&](int j, uint32_t& key) { if (!is_cand(j)) return false; key = float_to_bits(sc[j]); return true; },
+                       hist, bc, T_key, r_adm);
+  }
+  int base_eq = 0, base_keep = 0;
+  int32_t* kept = cv.kept_idx + d.idx_off;
+  for (int j0 = 0; j0 < C; j0 += 1024) {
+    const int j = j0 + tid;
+    const bool in = j < C;
+    const bool cand = in && is_cand(j);
+    const uint32_t key = cand ? float_to_bits(sc[j]) : 0u;
+    const int eq = (cand && key == T_key) ? 1 : 0;
+    const int gt = (cand && key > T_key) ? 1 : 0;
+    int tot_eq, tot_keep;
+    const int eq_rank = base_eq + block_exclusive_scan<1024>(eq, scan, &tot_eq);
+    const int keep = ((in && is_fixed(j)) ? 1 : 0) | gt | (eq & (eq_rank < r_adm ? 1 : 0));
+    const int pos = base_keep + block_exclusive_scan<1024>(keep, scan, &tot_keep);
+    if (keep && pos < d.n_prompt_rows) kept[pos] = j;
+    base_eq += tot_eq;
+    base_keep += tot_keep;
+  }
+}
+
+// grid = (row tiles of 64, static units of the call); block = 256 threads.
+template <typename T>
+__global__ __launch_bounds__(256) void compact_kernel(CacheView cv, int layer_begin, int static_begin,
+                                                      const T* __restrict__ k, const T* __restrict__ v,
+                                                      int64_t total_tokens) {
+  constexpr int LPR = Elem<T>::kLanesPerRow, ROWB = kD * sizeof(T);
+  const UnitDesc d = cv.units[cv.static_units[static_begin + blockIdx.y]];
+  const int row_base = blockIdx.x * 64;
+  if (row_base >= d.n_prompt_rows) return;
+  const int lrel = d.layer - layer_begin;
+  const int sub = threadIdx.x % LPR, slot = threadIdx.x / LPR;
+  const int32_t* kept = cv.kept_idx + d.idx_off;
+  const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
+  const size_t sstride = (size_t)cv.n_kv_heads * ROWB;
+  for (int i = row_base + slot; i < row_base + 64 && i < d.n_prompt_rows; i += 256 / LPR) {
+    const int pos = min(max(kept[i], 0), d.C - 1);
+    const size_t src = src0 + (size_t)pos * sstride + sub * 16;
+    const size_t dst = (size_t)(d.kv_row_off + i) * ROWB + sub * 16;
+    st16(reinterpret_cast<char*>(cv.k_rows) + dst, ld16(reinterpret_cast<const char*>(k) + src));
+    st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v) + src));
+  }
+}
+
+// grid = (chunk groups of 4, dynamic units of the call); block = 256 threads, one wave per chunk.
+template <typename T>
+__global__ __launch_bounds__(256) void adopt_kernel(CacheView cv, int layer_begin, int dynamic_begin,
+                                                    const T* __restrict__ k, const T* __restrict__ v,
+                                                    int64_t total_tokens) {
+  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RPW = 64 / LPR, ROWB = kD * sizeof(T);
+  const UnitDesc d = cv.units[cv.dynamic_units[dynamic_begin + blockIdx.y]];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int ch = blockIdx.x * 4 + wv;
+  if (ch >= d.n_chunks) return;               // wave-uniform
+  const int c = 1 << d.c_log2;
+  const int r_begin = ch * c, r_end = min(r_begin + c, d.C);
+  const int lrel = d.layer - layer_begin;
+  const int sub = lane % LPR, grp = lane / LPR;
+  const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
+  const size_t sstride = (size_t)cv.n_kv_heads * ROWB;
+  float acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  for (int r = r_begin + grp; r < r_begin + c; r += RPW) {     // uniform trip count (c is a multiple of RPW)
+    if (r < r_end) {
+      const size_t src = src0 + (size_t)r * sstride + sub * 16;
+      const size_t dst = (size_t)(d.kv_row_off + r) * ROWB + sub * 16;
+      const uint4 kraw = ld16(reinterpret_cast<const char*>(k) + src);
+      st16(reinterpret_cast<char*>(cv.k_rows) + dst, kraw);
+      st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v) + src));
+      float kf[EPL];
+      unpack16(kraw, kf, T{});
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] += kf[e];
+    }
+  }
+#pragma unroll
+  for (int mask = LPR; mask < 64; mask <<= 1) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] += lane_xor(acc[e], mask);
+  }
+  if (grp == 0) {
+    const float inv_n = (float)(r_end - r_begin);
+    float mf[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) mf[e] = acc[e] / inv_n;
+    st16(reinterpret_cast<char*>(cv.mu) + (size_t)(d.aux_off + ch) * ROWB + sub * 16, pack16(mf, T{}));
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------
+template <typename T>
+static hipError_t launch_score_t(const CacheView& cv, int layer_begin, int static_begin, int n_static, int max_C,
+                                 const void* q_window, const void* k, int64_t total_tokens, float2* part_stats,
+                                 float2* final_stats, hipStream_t st) {
+  const int n_splits = (max_C + kKeysPerBlock - 1) / kKeysPerBlock;
+  const int rows_pad = ((cv.G * cv.window + 31) / 32) * 32;
+  const size_t smem = (size_t)rows_pad * (kD * sizeof(T) + 16);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, 1>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, 2>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  const dim3 grid(n_splits, n_static);
+  hipLaunchKernelGGL((score_kernel<T, 1>), grid, dim3(256), smem, st, cv, layer_begin, static_begin,
+                     (const T*)q_window, (const T*)k, total_tokens, part_stats, (const float2*)final_stats, n_splits);
+  hipLaunchKernelGGL(stats_finalize_kernel, dim3(n_static), dim3(kMaxScoreRows), 0, st, cv, static_begin,
+                     (const float2*)part_stats, final_stats, n_splits);
+  hipLaunchKernelGGL((score_kernel<T, 2>), grid, dim3(256), smem, st, cv, layer_begin, static_begin,
+                     (const T*)q_window, (const T*)k, total_tokens, part_stats, (const float2*)final_stats, n_splits);
+  return hipGetLastError();
+}
+
+hipError_t launch_score(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static, int max_C,
+                        const void* q_window, const void* k, int64_t total_tokens, float2* part_stats,
+                        float2* final_stats, hipStream_t st) {
+  if (n_static <= 0) return hipSuccess;
+  if (dtype == HKV_F32)
+    return launch_score_t<float>(cv, layer_begin, static_begin, n_static, max_C, q_window, k, total_tokens,
+                                 part_stats, final_stats, st);
+  return launch_score_t<bf16_t>(cv, layer_begin, static_begin, n_static, max_C, q_window, k, total_tokens,
+                                part_stats, final_stats, st);
+}
+
+hipError_t launch_select(const CacheView& cv, int static_begin, int n_static, hipStream_t st) {
+  if (n_static <= 0) return hipSuccess;
+  hipLaunchKernelGGL(select_kernel, dim3(n_static), dim3(1024), 0, st, cv, static_begin);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,
+                          int max_rows, const void* k, const void* v, int64_t total_tokens, hipStream_t st) {
+  if (n_static <= 0 || max_rows <= 0) return hipSuccess;
+  const dim3 grid((max_rows + 63) / 64, n_static);
+  if (dtype == HKV_F32)
+    hipLaunchKernelGGL(compact_kernel<float>, grid, dim3(256), 0, st, cv, layer_begin, static_begin, (const float*)k,
+                       (const float*)v, total_tokens);
+  else
+    hipLaunchKernelGGL(compact_kernel<bf16_t>, grid, dim3(256), 0, st, cv, layer_begin, static_begin,
+                       (const bf16_t*)k, (const bf16_t*)v, total_tokens);
+  return hipGetLastError();
+}
+
+hipError_t launch_adopt(const CacheView& cv, int dtype, int layer_begin, int dynamic_begin, int n_dynamic,
+                        int max_chunks, const void* k, const void* v, int64_t total_tokens, hipStream_t st) {
+  if (n_dynamic <= 0 || max_chunks <= 0) return hipSuccess;
+  const dim3 grid((max_chunks + 3) / 4, n_dynamic);
+  if (dtype == HKV_F32)
+    hipLaunchKernelGGL(adopt_kernel<float>, grid, dim3(256), 0, st, cv, layer_begin, dynamic_begin, (const float*)k,
+                       (const float*)v, total_tokens);
+  else
+    hipLaunchKernelGGL(adopt_kernel<bf16_t>, grid, dim3(256), 0, st, cv, layer_begin, dynamic_begin,
+                       (const bf16_t*)k, (const bf16_t*)v, total_tokens);
+  return hipGetLastError();
+}
+
+}  // namespace hkv

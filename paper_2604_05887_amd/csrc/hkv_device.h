@@ -1,0 +1,120 @@
+// Device-side helpers for the libhkv kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hkv {
+
+struct bf16_t { uint16_t bits; };   // storage type of bfloat16 tensors
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kPer16 = 4;              // elements per 16-byte piece
+  static constexpr int kLanesPerRow = 32;       // lanes that cover one 128-element row
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kPer16 = 8;
+  static constexpr int kLanesPerRow = 16;
+};
+
+__device__ __forceinline__ float bits_to_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t float_to_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// float -> bfloat16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = float_to_bits(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Unpack one 16-byte piece into floats.
+__device__ __forceinline__ void unpack16(const uint4& v, float (&f)[4], float) {
+  f[0] = bits_to_float(v.x); f[1] = bits_to_float(v.y); f[2] = bits_to_float(v.z); f[3] = bits_to_float(v.w);
+}
+__device__ __forceinline__ void unpack16(const uint4& v, float (&f)[8], bf16_t) {
+  f[0] = bits_to_float(v.x << 16); f[1] = bits_to_float(v.x & 0xffff0000u);
+  f[2] = bits_to_float(v.y << 16); f[3] = bits_to_float(v.y & 0xffff0000u);
+  f[4] = bits_to_float(v.z << 16); f[5] = bits_to_float(v.z & 0xffff0000u);
+  f[6] = bits_to_float(v.w << 16); f[7] = bits_to_float(v.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ uint4 pack16(const float (&f)[4], float) {
+  return make_uint4(float_to_bits(f[0]), float_to_bits(f[1]), float_to_bits(f[2]), float_to_bits(f[3]));
+}
+__device__ __forceinline__ uint4 pack16(const float (&f)[8], bf16_t) {
+  uint4 v;
+  v.x = (uint32_t)f32_to_bf16_rne(f[0]) | ((uint32_t)f32_to_bf16_rne(f[1]) << 16);
+  v.y = (uint32_t)f32_to_bf16_rne(f[2]) | ((uint32_t)f32_to_bf16_rne(f[3]) << 16);
+  v.z = (uint32_t)f32_to_bf16_rne(f[4]) | ((uint32_t)f32_to_bf16_rne(f[5]) << 16);
+  v.w = (uint32_t)f32_to_bf16_rne(f[6]) | ((uint32_t)f32_to_bf16_rne(f[7]) << 16);
+  return v;
+}
+
+__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void st16(void* p, const uint4& v) { *reinterpret_cast<uint4*>(p) = v; }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- cross-lane primitives -------------------------------------------------------------
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float lane_xor(float x, int mask) {
+  const int lane = (int)__lane_id();
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, __builtin_bit_cast(int, x)));
+}
+__device__ __forceinline__ int lane_xor_i(int x, int mask) {
+  const int lane = (int)__lane_id();
+  return __builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, x);
+}
+
+// Sum over each aligned group of 16 lanes; every lane of the group gets the total.
+__device__ __forceinline__ float sum16(float x) {
+  x += dpp_mov<0xB1>(x);    // quad_perm [1,0,3,2]
+  x += dpp_mov<0x4E>(x);    // quad_perm [2,3,0,1]
+  x += dpp_mov<0x141>(x);   // row_half_mirror
+  x += dpp_mov<0x140>(x);   // row_mirror
+  return x;
+}
+__device__ __forceinline__ float sum32(float x) { x = sum16(x); return x + lane_xor(x, 16); }
+__device__ __forceinline__ float sum64(float x) { x = sum32(x); return x + lane_xor(x, 32); }
+template <int LANES> __device__ __forceinline__ float sum_lanes(float x) {
+  if constexpr (LANES == 16) return sum16(x);
+  else if constexpr (LANES == 32) return sum32(x);
+  else return sum64(x);
+}
+
+// Wave-wide inclusive prefix sum of ints (wave64).
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  const int lane = (int)__lane_id();
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    int n = __builtin_amdgcn_ds_bpermute(((lane - off) & 63) << 2, v);
+    if (lane >= off) v += n;
+  }
+  return v;
+}
+
+// Block-wide exclusive prefix sum for blockDim.x == NT (multiple of 64).  `smem` holds NT/64 + 1 ints.
+// Returns the exclusive prefix of `v`; *total gets the block sum.  Contains two barriers.
+template <int NT> __device__ __forceinline__ int block_exclusive_scan(int v, int* smem, int* total) {
+  constexpr int NW = NT / 64;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int inc = wave_inclusive_scan(v);
+  if (lane == 63) smem[wv] = inc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int i = 0; i < NW; ++i) { int t = smem[i]; smem[i] = run; run += t; }
+    smem[NW] = run;
+  }
+  __syncthreads();
+  const int res = smem[wv] + inc - v;
+  *total = smem[NW];
+  __syncthreads();   // smem may be reused by the caller's next scan
+  return res;
+}
+
+}  // namespace hkv

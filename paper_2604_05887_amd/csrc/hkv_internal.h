@@ -1,0 +1,93 @@
+// Internal declarations shared by the host API and the HIP kernels of libhkv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hkv.h"
+
+namespace hkv {
+
+constexpr int kD = 128;          // head_dim
+constexpr int kMaxG = 8;         // query heads per KV head
+constexpr int kTile = 128;       // logical rows per split-K work item of decode attention
+constexpr int kPartStride = 132; // floats per (work item, query head): m, l, 2 pad, o[128]
+constexpr int kKeysPerBlock = 512;   // keys one scoring block covers
+constexpr int kMaxScoreRows = 256;   // G * window upper bound
+constexpr int kFullMaxBatch = 256;
+constexpr float kNeg = -1.0e30f;     // "minus infinity" that stays finite under subtraction
+
+enum SelMode : int32_t { kSelVisual = 0, kSelText = 1, kSelSuffix = 2 };
+
+// One (sequence, layer, KV head) unit.  Units are numbered layer-major:
+// u = (layer * batch + seq) * n_kv_heads + head, so a layer range is a contiguous unit range.
+struct UnitDesc {
+  int64_t kv_row_off;   // first row of the unit in the cache K / V row arrays
+  int64_t aux_off;      // static: element offset into scores[]; dynamic: chunk offset into mu[] rows and sigma[]
+  int64_t idx_off;      // static: offset into kept_idx[]; dynamic: offset into sel[]
+  int32_t seq_start;    // first token of the sequence in the packed prompt tensors
+  int32_t C;            // prompt length of the sequence
+  int32_t kind;         // hkv_head_type
+  int32_t n_prompt_rows;// static: retained prompt rows; dynamic: k_sel * chunk (logical gathered rows)
+  int32_t c_log2;       // dynamic: log2(chunk size)
+  int32_t n_chunks;     // dynamic
+  int32_t k_sel;        // dynamic: chunks gathered per step
+  int32_t sel_mode;     // static: SelMode
+  int32_t m_sel;        // static: candidates to pick
+  int32_t n_cand;       // static: candidates available
+  int32_t item_begin;   // first split-K work item of the unit (global numbering)
+  int32_t n_tiles_max;  // work items reserved for the unit (tail at full capacity)
+  int32_t seq, layer, head;
+  int32_t type_ord;     // ordinal among the static (or dynamic) units, layer-major
+};
+
+struct CacheView {
+  const UnitDesc* units;
+  const int2* items;          // (unit, tile)
+  const int32_t* static_units;
+  const int32_t* dynamic_units;
+  const uint8_t* is_visual;
+  int32_t* cnt_a;             // [n_layers] tail length before the step in flight
+  int32_t* cnt_b;             // [n_layers] tail length the step in flight attends
+  int32_t* kept_idx;
+  int32_t* sel;
+  float* scores;
+  float* sigma;
+  void* mu;
+  void* k_rows;
+  void* v_rows;
+  int32_t n_layers, batch, n_q_heads, n_kv_heads, G, window, max_new, causal;
+  float scale_log2e;          // softmax scale * log2(e)
+};
+
+// ---- launchers implemented in the kernel translation units (all asynchronous on `st`) ----
+// decode
+hipError_t launch_prepare(const CacheView& cv, int dtype, int layer_begin, int layer_end, const void* q,
+                          const void* k_new, const void* v_new, int use_stored_sigma, int do_scoring,
+                          int max_chunks, hipStream_t st);
+hipError_t launch_attn_partial(const CacheView& cv, int dtype, int layer_begin, int item_begin, int n_items,
+                               const void* q, float* partials, hipStream_t st);
+hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int item_base,
+                             const float* partials, void* out, int advance_tail, hipStream_t st);
+hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
+
+struct FullView {
+  int32_t cu[kFullMaxBatch + 1];
+  int32_t batch, n_layers_call, n_q_heads, n_kv_heads, G, n_tiles_max;
+  int64_t total_tokens;
+  float scale_log2e;
+};
+hipError_t launch_full_attn(const FullView& fv, int dtype, const void* q, const void* k, const void* v,
+                            float* partials, void* out, hipStream_t st);
+
+// compress
+hipError_t launch_score(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,
+                        int max_C, const void* q_window, const void* k, int64_t total_tokens,
+                        float2* part_stats, float2* final_stats, hipStream_t st);
+hipError_t launch_select(const CacheView& cv, int static_begin, int n_static, hipStream_t st);
+hipError_t launch_compact(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,
+                          int max_rows, const void* k, const void* v, int64_t total_tokens, hipStream_t st);
+hipError_t launch_adopt(const CacheView& cv, int dtype, int layer_begin, int dynamic_begin, int n_dynamic,
+                        int max_chunks, const void* k, const void* v, int64_t total_tokens, hipStream_t st);
+
+}  // namespace hkv

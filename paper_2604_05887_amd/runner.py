@@ -1,0 +1,56 @@
+"""Moves a synthetic workload (hkv_synth.Workload, host numpy arrays) onto the GPU and wires it
+to the C ABI.  Memory plumbing only: no step of the method is computed here."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def hkv_dtype(dtype: str) -> int:
+    return B.HKV_BF16 if dtype == "bf16" else B.HKV_F32
+
+
+def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """float32 host array whose values are exact in `dtype` -> device tensor of that dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    return t.to(device=device, dtype=torch_dtype(dtype)).contiguous()
+
+
+def to_host_f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+@dataclass
+class DeviceWorkload:
+    cfg: B.hkv_config
+    plan: B.PlanArrays
+    cache: B.HybridKVCache
+    q_window: torch.Tensor
+    k: torch.Tensor
+    v: torch.Tensor
+    dtype: str
+
+
+def setup(wl, device="cuda:0", budget: Optional[np.ndarray] = None, head_type: Optional[np.ndarray] = None,
+          score_causal: int = 0, upload_prompt: bool = True) -> DeviceWorkload:
+    cfg = B.make_config(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                        dtype=hkv_dtype(wl.dtype), window=wl.window, chunk_size=int(wl.chunk_size[0]),
+                        max_new_tokens=wl.max_new_tokens, score_causal=score_causal)
+    plan = B.PlanArrays(wl.cu_seqlens, wl.is_visual, wl.head_type if head_type is None else head_type,
+                        wl.budget if budget is None else budget, wl.chunk_size)
+    cache = B.HybridKVCache(cfg, plan, device=device)
+    if upload_prompt:
+        qw, k, v = (to_device(wl.q_window, wl.dtype, device), to_device(wl.k, wl.dtype, device),
+                    to_device(wl.v, wl.dtype, device))
+    else:
+        qw = k = v = None
+    return DeviceWorkload(cfg=cfg, plan=plan, cache=cache, q_window=qw, k=k, v=v, dtype=wl.dtype)

@@ -1,0 +1,191 @@
+"""Shared machinery of the GPU parity tests: runs a workload through libhkv and through the
+CPU oracle and compares them unit by unit.
+
+Comparison rules
+  * integer results (kept positions, chunk picks, compacted rows) must be bit-exact whenever
+    both sides decide on the same values:
+      - stage-exact: the oracle's selection routine applied to the device's own fp32 scores must
+        reproduce the device's choice exactly, ties included;
+      - end-to-end: against the oracle's double-precision scores the sets must be equal unless
+        the cut falls inside a tie band (scores within TAU of the threshold), in which case the
+        two sets may differ only by tokens inside that band.
+  * floating-point results: s_w within SCORE_RTOL of the oracle; attention outputs within
+    OUT_TOL[dtype] relative (max-norm per head vector).
+"""
+from __future__ import annotations
+
+from typing import Dict, Tuple
+
+import numpy as np
+import torch
+
+from oracle import hybridkv_oracle as O
+from paper_2604_05887_amd import binding as B
+from paper_2604_05887_amd import runner
+
+TAU = 2e-5          # relative half-width of the tie band around a selection threshold
+SCORE_RTOL = 2e-5   # fp32 MFMA accumulation + exp2 + fp32 column sums vs double
+OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def oracle_setup(wl, budget=None, head_type=None, causal=False):
+    cfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                         head_dim=wl.head_dim, window=wl.window, dtype=wl.dtype, score_causal=causal)
+    plan = O.OraclePlan(cu_seqlens=wl.cu_seqlens, head_type=wl.head_type if head_type is None else head_type,
+                        budget=wl.budget if budget is None else budget, chunk_size=wl.chunk_size)
+    return cfg, plan
+
+
+def candidates_of(is_visual: np.ndarray, w: int, budget: int):
+    """(candidate positions, number to select) under the static keep rule."""
+    C = is_visual.size
+    hist = np.arange(C - w)
+    txt = hist[is_visual[: C - w] == 0]
+    vis = hist[is_visual[: C - w] == 1]
+    if budget < w:
+        return np.zeros(0, np.int64), 0
+    m = budget - w - txt.size
+    if m < 0:
+        return txt, budget - w
+    return vis, min(m, vis.size)
+
+
+def check_banded(got: np.ndarray, want: np.ndarray, scores: np.ndarray, cand: np.ndarray, m: int,
+                 tau_abs_fn) -> bool:
+    """got/want: ascending index sets.  Returns True when they are identical; otherwise asserts that
+    they differ only inside the tie band and returns False."""
+    assert got.size == want.size, (got.size, want.size)
+    if np.array_equal(got, want):
+        return True
+    hi, lo = O.selection_margin(scores, cand, m)
+    band = tau_abs_fn(hi)
+    diff = np.setxor1d(got, want)
+    s = np.asarray(scores, dtype=np.float64)[diff]
+    assert np.all(np.abs(s - hi) <= band), (
+        f"sets differ outside the tie band: thr={hi:.9e} next={lo:.9e} band={band:.3e} "
+        f"diff={diff[:8]} scores={s[:8]}")
+    return False
+
+
+def compare_compress(wl, dw, ocache, stats: Dict[str, float]) -> Dict[Tuple[int, int, int], np.ndarray]:
+    """Checks every unit after hkv_compress.  Returns the keep sets the oracle must adopt where the
+    device's differ inside a tie band (empty when everything matched exactly)."""
+    overrides = {}
+    w = wl.window
+    for (b, l, h), u in ocache.units.items():
+        lo, hi = int(wl.cu_seqlens[b]), int(wl.cu_seqlens[b + 1])
+        vis = wl.is_visual[lo:hi]
+        if u.kind == O.STATIC:
+            budget = int(ocache.plan.budget[b, l, h])
+            rows, _, _ = dw.cache.unit_info(b, l, h)
+            assert rows == u.kept.size == O.retained_count(hi - lo, w, int((vis[:hi - lo - w] == 0).sum()),
+                                                           int((vis[:hi - lo - w] == 1).sum()), budget)
+            s_gpu = dw.cache.export(B.HKV_X_SCORES, b, l, h)
+            kept_gpu = dw.cache.export(B.HKV_X_KEPT_IDX, b, l, h).astype(np.int64)
+            # scores
+            rel = np.abs(s_gpu.astype(np.float64) - u.s_w) / np.maximum(u.s_w, 1e-300)
+            big = u.s_w > 1e-30
+            stats["score_rel"] = max(stats.get("score_rel", 0.0), float(rel[big].max()))
+            assert rel[big].max() <= SCORE_RTOL, f"s_w off by {rel[big].max():.3e} on unit {(b, l, h)}"
+            assert abs(float(s_gpu.astype(np.float64).sum()) - 1.0) < 1e-4
+            # stage-exact: the oracle's rule on the device's own fp32 scores
+            want_stage = O.static_keep_set(s_gpu, vis, w, budget)
+            assert np.array_equal(kept_gpu, want_stage), f"selection not exact on unit {(b, l, h)}"
+            # end-to-end with tie band
+            cand, m = candidates_of(vis, w, budget)
+            same = check_banded(kept_gpu, u.kept, u.s_w, cand, m, lambda thr: TAU * thr)
+            if not same:
+                overrides[(b, l, h)] = kept_gpu
+                stats["banded_units"] = stats.get("banded_units", 0) + 1
+            # compacted rows are bit-exact copies, ascending position order
+            Kc = dw.cache.export(B.HKV_X_K_ROWS, b, l, h)
+            Vc = dw.cache.export(B.HKV_X_V_ROWS, b, l, h)
+            assert np.array_equal(Kc[: kept_gpu.size], wl.k[l, lo + kept_gpu, h])
+            assert np.array_equal(Vc[: kept_gpu.size], wl.v[l, lo + kept_gpu, h])
+        else:
+            rows, n_c, k_sel = dw.cache.unit_info(b, l, h)
+            assert (n_c, k_sel) == (u.mu.shape[0], u.k_sel) and rows == k_sel * u.c
+            mu_gpu = dw.cache.export(B.HKV_X_CHUNK_MEAN, b, l, h).astype(np.float64)
+            ulp = np.abs(u.mu) * (2.0 ** -7 if wl.dtype == "bf16" else 2.0 ** -22) + 1e-30
+            assert np.all(np.abs(mu_gpu - u.mu) <= ulp), "chunk summary off by more than one ulp"
+            stats["mu_mismatch_frac"] = max(stats.get("mu_mismatch_frac", 0.0), float((mu_gpu != u.mu).mean()))
+            Kd = dw.cache.export(B.HKV_X_K_ROWS, b, l, h)
+            Vd = dw.cache.export(B.HKV_X_V_ROWS, b, l, h)
+            assert np.array_equal(Kd[: hi - lo], wl.k[l, lo:hi, h]) and np.array_equal(Vd[: hi - lo], wl.v[l, lo:hi, h])
+    return overrides
+
+
+def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float], layer_ranges=None,
+                           append: bool = True):
+    """n_steps decode steps on both sides; the oracle takes the device's chunk summaries (they may
+    differ from its own by one rounding) and, inside a tie band, the device's chunk picks."""
+    L, Bn = wl.n_layers, wl.batch
+    tdt = runner.torch_dtype(wl.dtype)
+    out = torch.empty((L, Bn, wl.n_q_heads, wl.head_dim), dtype=tdt, device="cuda:0")
+    mu_dev = {}
+    for key, u in ocache.units.items():
+        if u.kind == O.DYNAMIC:
+            mu_dev[key] = dw.cache.export(B.HKV_X_CHUNK_MEAN, *key).astype(np.float64)
+    layer_ranges = layer_ranges or [(0, L)]
+    G = wl.group
+    for s in range(n_steps):
+        q = runner.to_device(wl.q_steps[s], wl.dtype)
+        kn = runner.to_device(wl.k_new[s], wl.dtype) if append else None
+        vn = runner.to_device(wl.v_new[s], wl.dtype) if append else None
+        for (lb, le) in layer_ranges:
+            dw.cache.decode_attn(q[lb:le], None if kn is None else kn[lb:le], None if vn is None else vn[lb:le],
+                                 out[lb:le], layer_begin=lb, layer_end=le)
+        torch.cuda.synchronize()
+        got = runner.to_host_f32(out).astype(np.float64)
+        # chunk picks first: they decide which rows the oracle attends
+        sel_over = {}
+        for key, u in ocache.units.items():
+            if u.kind != O.DYNAMIC:
+                continue
+            b, l, h = key
+            sig_gpu = dw.cache.export(B.HKV_X_CHUNK_SIGMA, b, l, h)
+            sel_gpu = dw.cache.export(B.HKV_X_CHUNK_SEL, b, l, h).astype(np.int64)
+            assert np.array_equal(sel_gpu, O.select_chunks(sig_gpu, u.k_sel)), f"chunk top-k not exact on {key}"
+            qh = wl.q_steps[s][l, b, h * G:(h + 1) * G].astype(np.float64)
+            sig_ref = O.chunk_scores(qh, mu_dev[key])
+            scale = np.linalg.norm(qh.sum(0)) * np.linalg.norm(mu_dev[key], axis=1).max()
+            err = np.abs(sig_gpu - sig_ref).max() / scale
+            stats["sigma_err"] = max(stats.get("sigma_err", 0.0), float(err))
+            assert err <= 1e-5, f"chunk scores off by {err:.3e} (relative to |q||mu|) on {key}"
+            want = O.select_chunks(sig_ref, u.k_sel)
+            same = check_banded(sel_gpu, want, sig_ref, np.arange(sig_ref.size), u.k_sel, lambda thr: 1e-5 * scale)
+            if not same:
+                sel_over[key] = sel_gpu
+                stats["banded_chunk_picks"] = stats.get("banded_chunk_picks", 0) + 1
+        ref, _ = O.decode_attn(ocache, wl.q_steps[s], wl.k_new[s] if append else None,
+                               wl.v_new[s] if append else None, sel_override=sel_over, mu_override=mu_dev)
+        err = np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+        stats["out_err"] = max(stats.get("out_err", 0.0), float(err.max()))
+        assert err.max() <= OUT_TOL[wl.dtype], f"step {s}: output off by {err.max():.3e}"
+    return out
+
+
+def full_pipeline(wl, budget=None, head_type=None, causal=False, n_steps=None, layer_ranges=None):
+    stats: Dict[str, float] = {}
+    dw = runner.setup(wl, budget=budget, head_type=head_type, score_causal=int(causal))
+    ocfg, oplan = oracle_setup(wl, budget, head_type, causal)
+    ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual)
+    if layer_ranges:
+        for (lb, le) in layer_ranges:
+            dw.cache.compress(dw.q_window[lb:le], dw.k[lb:le], dw.v[lb:le], layer_begin=lb, layer_end=le)
+    else:
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+    torch.cuda.synchronize()
+    overrides = compare_compress(wl, dw, ocache, stats)
+    if overrides:
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, keep_override=overrides)
+    run_decode_and_compare(wl, dw, ocache, wl.steps if n_steps is None else n_steps, stats, layer_ranges)
+    # tails hold the appended rows in order
+    steps = wl.steps if n_steps is None else n_steps
+    for (b, l, h), u in ocache.units.items():
+        Kr = dw.cache.export(B.HKV_X_K_ROWS, b, l, h)
+        base = u.kept.size if u.kind == O.STATIC else u.C
+        assert Kr.shape[0] == base + steps
+        assert np.array_equal(Kr[base:], wl.k_new[:steps, l, b, h])
+    dw.cache.close()
+    return stats

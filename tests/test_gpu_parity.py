@@ -1,0 +1,207 @@
+"""GPU parity: libhkv (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from hkv_synth import make_workload
+from oracle import hybridkv_oracle as O
+from paper_2604_05887_amd import binding as B
+from paper_2604_05887_amd import runner
+
+import parity_utils as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(name, stats):
+    print(f"\n[{name}] " + " ".join(f"{k}={v:.3g}" for k, v in sorted(stats.items())), flush=True)
+
+
+def test_cfg0_fp32_end_to_end():
+    """Config 0 at full size: compress + 16 decode steps, every unit, every step."""
+    wl = make_workload(0)
+    stats = P.full_pipeline(wl)
+    _say("cfg0", stats)
+    assert stats.get("banded_units", 0) == 0      # the seed has no tie-band hits
+
+
+def test_cfg1_shape_bf16_three_layers():
+    wl = make_workload(1, n_layers=3, shrink=4, steps=5)
+    stats = P.full_pipeline(wl)
+    _say("cfg1/4 L3", stats)
+
+
+def test_layer_by_layer_calls_match_one_call():
+    """Per-layer compress/decode calls (how a model would drive it) give the same bits as one call."""
+    wl = make_workload(1, n_layers=3, shrink=8, steps=3)
+    outs = []
+    for ranges in ([(0, 3)], [(0, 1), (1, 2), (2, 3)], [(0, 2), (2, 3)]):
+        dw = runner.setup(wl)
+        for (lb, le) in ranges:
+            dw.cache.compress(dw.q_window[lb:le], dw.k[lb:le], dw.v[lb:le], layer_begin=lb, layer_end=le)
+        out = torch.empty((3, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+        res = []
+        for s in range(wl.steps):
+            q, kn, vn = (runner.to_device(x[s], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+            for (lb, le) in ranges:
+                dw.cache.decode_attn(q[lb:le], kn[lb:le], vn[lb:le], out[lb:le], layer_begin=lb, layer_end=le)
+            torch.cuda.synchronize()
+            res.append(out.clone())
+        outs.append(torch.stack(res))
+        dw.cache.close()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_ragged_batch_both_chunk_sizes_and_short_last_chunk():
+    """Config 4 shape, shrunk: 16 ragged sequences, chunk sizes 32 and 64, prompt lengths that are
+    not multiples of the chunk size, hierarchical ragged budgets."""
+    wl = make_workload(4, n_layers=2, shrink=8, steps=3)
+    assert len(set(wl.chunk_size.tolist())) == 2 and any(int(c) % 64 for c in wl.seqlens)
+    stats = P.full_pipeline(wl)
+    _say("cfg4/8 L2", stats)
+
+
+def test_literal_total_budgets_hit_text_overflow_rule():
+    """Budgets read as a fraction of the whole context are smaller than text + window on these
+    shapes: the overflow rule (keep window, then best text tokens) decides the keep set."""
+    wl = make_workload(1, n_layers=2, shrink=4, steps=2, budget_rule="literal_total")
+    C, w = int(wl.seqlens[0]), wl.window
+    n_txt = int((wl.is_visual[: C - w] == 0).sum())
+    stat = wl.head_type[0] == 0
+    assert (wl.budget[0][stat] < w + n_txt).any()
+    stats = P.full_pipeline(wl)
+    _say("cfg1/4 literal", stats)
+
+
+def test_group_of_eight_72b_shape():
+    wl = make_workload(3, n_layers=2, shrink=16, steps=2)
+    assert wl.group == 8
+    stats = P.full_pipeline(wl)
+    _say("cfg3/16 L2", stats)
+
+
+@pytest.mark.parametrize("mix", ["all_static", "all_dynamic"])
+def test_degenerate_head_maps(mix):
+    wl = make_workload(0, shrink=2, steps=2, head_mix=mix)
+    stats = P.full_pipeline(wl)
+    _say(mix, stats)
+
+
+def test_tiny_budgets_and_budget_below_window():
+    wl = make_workload(0, shrink=4, steps=2)
+    budget = wl.budget.copy()
+    budget[0, 0, 0] = 5            # below the window: keep the last 5 positions
+    budget[0, 0, 1] = wl.window    # exactly the window
+    budget[0, 0, 2] = 1            # dynamic: one chunk
+    stats = P.full_pipeline(wl, budget=budget)
+    _say("tiny budgets", stats)
+
+
+def test_causal_window_scoring():
+    wl = make_workload(0, shrink=2, steps=1)
+    stats = P.full_pipeline(wl, causal=True)
+    _say("causal", stats)
+
+
+def test_full_budget_equals_full_attention_and_full_kernel():
+    """Budget = whole context: kept set is the identity, all chunks are picked, and the hybrid
+    output, the full-KV kernel and textbook attention agree."""
+    wl = make_workload(0, shrink=2, steps=1)
+    C = int(wl.seqlens[0])
+    budget = np.full_like(wl.budget, C)
+    dw = runner.setup(wl, budget=budget)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    out_h = torch.empty((1, 1, wl.n_q_heads, 128), dtype=torch.float32, device="cuda:0")
+    q = runner.to_device(wl.q_steps[0], wl.dtype)
+    dw.cache.decode_attn(q, None, None, out_h)
+    for h in range(4):
+        if wl.head_type[0, 0, h] == 0:
+            assert np.array_equal(dw.cache.export(B.HKV_X_KEPT_IDX, 0, 0, h), np.arange(C))
+        else:
+            assert np.array_equal(dw.cache.export(B.HKV_X_CHUNK_SEL, 0, 0, h), np.arange(C // 32))
+    ws_bytes = B.hkv_full_workspace_size(dw.cfg, wl.cu_seqlens, 1)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    out_f = torch.empty_like(out_h)
+    B.hkv_full_decode_attn(dw.cfg, wl.cu_seqlens, 1, q, dw.k, dw.v, out_f, ws, ws_bytes)
+    torch.cuda.synchronize()
+    ocfg, _ = P.oracle_setup(wl)
+    ref = O.full_decode_attn(ocfg, wl.cu_seqlens, wl.q_steps[0], wl.k, wl.v)
+    for got in (out_h, out_f):
+        g = runner.to_host_f32(got).astype(np.float64)
+        err = np.abs(g - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+        assert err.max() <= 1e-5, err.max()
+    dw.cache.close()
+
+
+def test_full_kv_kernel_ragged_batch_bf16():
+    wl = make_workload(4, n_layers=2, shrink=8, steps=1)
+    cfg = B.make_config(n_layers=2, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, dtype=B.HKV_BF16,
+                        window=wl.window, chunk_size=32)
+    q, k, v = (runner.to_device(x, "bf16") for x in (wl.q_steps[0], wl.k, wl.v))
+    ws_bytes = B.hkv_full_workspace_size(cfg, wl.cu_seqlens, 2)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty_like(q)
+    B.hkv_full_decode_attn(cfg, wl.cu_seqlens, 2, q, k, v, out, ws, ws_bytes)
+    torch.cuda.synchronize()
+    ocfg, _ = P.oracle_setup(wl)
+    ref = O.full_decode_attn(ocfg, wl.cu_seqlens, wl.q_steps[0], wl.k, wl.v)
+    g = runner.to_host_f32(out).astype(np.float64)
+    err = np.abs(g - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+    assert err.max() <= 2e-2, err.max()
+
+
+def test_selection_stage_with_planted_ties():
+    """Feed the device selection kernels oracle-made scores full of exact ties (quantised values):
+    kept positions and chunk picks must equal the oracle's, lowest index first."""
+    wl = make_workload(0, shrink=2, steps=1)
+    dw = runner.setup(wl)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    rng = np.random.default_rng(5)
+    C, w = int(wl.seqlens[0]), wl.window
+    for levels in (3, 17, 1):
+        for h in range(4):
+            if wl.head_type[0, 0, h] == 0:
+                s = (rng.integers(0, levels, size=C) / 64.0).astype(np.float32)
+                dw.cache.import_(B.HKV_X_SCORES, 0, 0, h, s)
+        dw.cache.compress_from_scores(dw.k, dw.v)
+        for h in range(4):
+            if wl.head_type[0, 0, h] == 0:
+                s = dw.cache.export(B.HKV_X_SCORES, 0, 0, h)
+                want = O.static_keep_set(s, wl.is_visual, w, int(wl.budget[0, 0, h]))
+                got = dw.cache.export(B.HKV_X_KEPT_IDX, 0, 0, h)
+                assert np.array_equal(got, want), (levels, h)
+                Kc = dw.cache.export(B.HKV_X_K_ROWS, 0, 0, h)
+                assert np.array_equal(Kc[: want.size], wl.k[0, want, h])
+    for levels in (2, 9, 1):
+        for h in range(4):
+            if wl.head_type[0, 0, h] == 1:
+                n_c = dw.cache.unit_info(0, 0, h)[1]
+                sig = (rng.integers(-levels, levels, size=n_c) / 8.0).astype(np.float32)
+                sig[rng.integers(0, n_c)] = -0.0
+                dw.cache.import_(B.HKV_X_CHUNK_SIGMA, 0, 0, h, sig)
+        B.hkv_reselect_chunks(dw.cache.handle, 0, 1)
+        for h in range(4):
+            if wl.head_type[0, 0, h] == 1:
+                sig = dw.cache.export(B.HKV_X_CHUNK_SIGMA, 0, 0, h)
+                k_sel = dw.cache.unit_info(0, 0, h)[2]
+                assert np.array_equal(dw.cache.export(B.HKV_X_CHUNK_SEL, 0, 0, h), O.select_chunks(sig, k_sel))
+    dw.cache.close()
+
+
+def test_tail_capacity_and_rewind():
+    wl = make_workload(0, shrink=4, steps=3, max_new_tokens=2)
+    dw = runner.setup(wl)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    out = torch.empty((1, 1, wl.n_q_heads, 128), dtype=torch.float32, device="cuda:0")
+    q, kn, vn = (runner.to_device(x[0], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+    dw.cache.decode_attn(q, kn, vn, out)
+    first = out.clone()
+    dw.cache.decode_attn(q, kn, vn, out)
+    with pytest.raises(B.HkvError) as ei:
+        dw.cache.decode_attn(q, kn, vn, out)
+    assert ei.value.status == B.HKV_ENOSPACE
+    dw.cache.rewind()
+    dw.cache.decode_attn(q, kn, vn, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, first)      # same state, same bits: the path is deterministic
+    dw.cache.close()

@@ -1,0 +1,116 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+host-side validation and planning behave as documented.  No kernel is launched."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from hkv_synth import make_workload
+from oracle import hybridkv_oracle as O
+from paper_2604_05887_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(os.path.join(ROOT, "paper_2604_05887_amd", "libhkv.so")):
+        from paper_2604_05887_amd.build import build_library
+        build_library(verbose=False)
+    return B.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "hkv.h")).read()
+    declared = set(re.findall(r"HKV_API[^;(]*?\b(hkv_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.hkv_abi_version() == B.HKV_ABI_VERSION
+    assert B.hkv_strerror(B.HKV_ESHAPE) == "unsupported shape"
+
+
+def _cfg(**kw):
+    base = dict(n_layers=1, n_q_heads=28, n_kv_heads=4, dtype=B.HKV_F32, window=32, chunk_size=32, max_new_tokens=4)
+    base.update(kw)
+    return B.make_config(**base)
+
+
+def _plan(wl, **kw):
+    args = dict(cu_seqlens=wl.cu_seqlens, is_visual=wl.is_visual, head_type=wl.head_type, budget=wl.budget,
+                chunk_size=wl.chunk_size)
+    args.update(kw)
+    return B.PlanArrays(**args)
+
+
+def test_argument_errors_are_reported_on_the_host(lib):
+    wl = make_workload(0, shrink=4, steps=1)
+    ok = B.hkv_query_sizes(_cfg(), _plan(wl))
+    assert ok[0] > 0 and ok[1] > 0
+
+    def status(cfg, plan):
+        with pytest.raises(B.HkvError) as ei:
+            B.hkv_query_sizes(cfg, plan)
+        return ei.value.status
+
+    assert status(_cfg(head_dim=64), _plan(wl)) == B.HKV_ESHAPE
+    assert status(_cfg(n_q_heads=36), _plan(wl)) == B.HKV_ESHAPE          # group of 9
+    assert status(_cfg(n_q_heads=30), _plan(wl)) == B.HKV_ESHAPE          # not divisible
+    assert status(_cfg(window=64), _plan(wl)) == B.HKV_ESHAPE             # G * w > 256
+    assert status(_cfg(window=0), _plan(wl)) == B.HKV_ESHAPE
+    assert status(_cfg(dtype=7), _plan(wl)) == B.HKV_EINVAL
+    bad = _cfg(); bad.struct_size = 12
+    assert status(bad, _plan(wl)) == B.HKV_EINVAL
+    assert status(_cfg(), _plan(wl, chunk_size=np.array([24]))) == B.HKV_ESHAPE       # not a power of two
+    b0 = wl.budget.copy(); b0[0, 0, 1] = 0
+    assert status(_cfg(), _plan(wl, budget=b0)) == B.HKV_EBUDGET
+    ht = wl.head_type.copy(); ht[0, 0, 0] = 3
+    assert status(_cfg(), _plan(wl, head_type=ht)) == B.HKV_EINVAL
+    assert status(_cfg(), _plan(wl, cu_seqlens=np.array([0, 20]))) == B.HKV_ESHAPE     # prompt shorter than window
+    # decode entry point rejects a null cache before touching the device
+    assert lib.hkv_decode_attn(None, 0, 1, None, None, None, None, None, 0, None) == B.HKV_EINVAL
+    assert lib.hkv_compress(None, 0, 1, None, None, None, None, 0, None) == B.HKV_EINVAL
+
+
+@pytest.mark.parametrize("rule", ["text_exempt", "literal_total"])
+def test_planned_rows_match_the_oracle_rule(lib, rule):
+    """Retained rows per static head and chunk counts per dynamic head, computed by the library's
+    host planner, equal what the oracle's keep rule yields -- for in-regime budgets, budgets below
+    text + window, and budgets below the window."""
+    wl = make_workload(4, n_layers=2, shrink=8, steps=1, budget_rule=rule)
+    budget = wl.budget.copy()
+    budget[0, 0, :] = [3, wl.window, 7, 100000][: wl.n_kv_heads]
+    cfg = _cfg(n_layers=2, dtype=B.HKV_BF16)
+    plan = _plan(wl, budget=budget)
+    w = wl.window
+    for b in range(wl.batch):
+        lo, hi = int(wl.cu_seqlens[b]), int(wl.cu_seqlens[b + 1])
+        C = hi - lo
+        vis = wl.is_visual[lo:hi]
+        n_txt, n_vis = int((vis[: C - w] == 0).sum()), int((vis[: C - w] == 1).sum())
+        for l in range(2):
+            for h in range(wl.n_kv_heads):
+                rows, n_c, k_sel = B.hkv_plan_unit_info(cfg, plan, b, l, h)
+                if wl.head_type[b, l, h] == 0:
+                    assert rows == O.retained_count(C, w, n_txt, n_vis, int(budget[b, l, h]))
+                    assert rows == O.static_keep_set(np.zeros(C), vis, w, int(budget[b, l, h])).size
+                else:
+                    c = int(wl.chunk_size[b])
+                    assert n_c == -(-C // c)
+                    assert k_sel == O.n_selected_chunks(int(budget[b, l, h]), c, n_c)
+                    assert rows == k_sel * c
+
+
+def test_cache_size_covers_the_rows_it_promises(lib):
+    wl = make_workload(1, n_layers=2, shrink=4, steps=8)
+    cfg = _cfg(n_layers=2, dtype=B.HKV_BF16, max_new_tokens=8)
+    plan = _plan(wl)
+    cache_bytes, ws_bytes = B.hkv_query_sizes(cfg, plan)
+    rows = 0
+    for l in range(2):
+        for h in range(4):
+            r, n_c, k = B.hkv_plan_unit_info(cfg, plan, 0, l, h)
+            rows += (r if wl.head_type[0, l, h] == 0 else int(wl.seqlens[0])) + 8
+    assert cache_bytes >= 2 * rows * 128 * 2
+    assert cache_bytes < 2 * rows * 128 * 2 * 1.2 + (1 << 20)
