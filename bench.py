@@ -1,0 +1,273 @@
+#!/usr/bin/env python3
+"""Benchmark of the HybridKV hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
+
+A "step" is one decode step of the whole model depth: tail append, chunk scoring and chunk top-k
+for dynamic heads, split-K attention over every head's retained rows, merge -- for all layers in one
+hkv_decode_attn call.  The prefill compression pass (scoring, top-M, compaction, chunk summaries) is
+timed in the same run and reported beside it, as is a full-KV decode-attention kernel on the same
+prompt and the CPU oracle on the host cores.
+
+Inputs are resident in HBM before any timed region.  To keep the timed steps reading from HBM
+rather than from the 256 MB memory-side cache, the benchmark rotates over several identical cache
+copies (a real decoder streams the model weights between attention layers, which has the same
+effect).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MALL_BYTES = 256 << 20
+
+
+def _read_traffic(name: str):
+    """Measured HBM traffic per launch of the dominant kernel (bytes), from the committed counter
+    summary for this workload, or None."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--config", type=int, default=1, help="workload id (1 = Qwen2.5-VL-7B shape, 8K context)")
+    ap.add_argument("--budget-rule", default="text_exempt", choices=["text_exempt", "literal_total"])
+    ap.add_argument("--budget-frac", type=float, default=None)
+    ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU hot path only; --gpus N with N > 1 is not supported "
+              "(no sharding or collectives are part of this build).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from hkv_synth import make_workload
+    from paper_2604_05887_amd import binding as B
+    from paper_2604_05887_amd import runner
+
+    if not os.path.exists(os.path.join(ROOT, "paper_2604_05887_amd", "libhkv.so")):
+        from paper_2604_05887_amd.build import build_library
+        build_library()
+    lib = B.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    K, W = args.steps, args.warmup
+    n_inputs = min(max(K, 16), 128)
+    wl = make_workload(args.config, steps=n_inputs, budget_rule=args.budget_rule, budget_frac=args.budget_frac,
+                       max_new_tokens=None)
+    L, Bn, Hq, Hkv, d = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    tdt = runner.torch_dtype(wl.dtype)
+
+    # ---- device-resident inputs ---------------------------------------------------------------
+    qw, k, v = (runner.to_device(x, wl.dtype, dev) for x in (wl.q_window, wl.k, wl.v))
+    q_all, kn_all, vn_all = (runner.to_device(x, wl.dtype, dev) for x in (wl.q_steps, wl.k_new, wl.v_new))
+    out = torch.empty((L, Bn, Hq, d), dtype=tdt, device=dev)
+
+    # the real run appends one token per step for `steps` steps; the rotation spreads the timed steps
+    # over several copies, so every copy's tail is pre-rolled to the middle of that range
+    probe = runner.setup(wl, dev, upload_prompt=False)
+    step_bytes_mid = probe.cache.step_bytes(wl.steps // 2)
+    probe.cache.close()
+    del probe
+    n_copies = args.copies or int(min(8, max(2, -(-2 * MALL_BYTES // step_bytes_mid) + 1)))
+    per_copy = -(-(K + W) // n_copies)
+    preroll = max(0, wl.steps // 2 - per_copy // 2)
+    wl.max_new_tokens = preroll + 2 * per_copy + 2 + K   # room for the profiled pass as well
+    copies = [runner.setup(wl, dev, upload_prompt=False) for _ in range(n_copies)]
+    stream = torch.cuda.current_stream()
+    sptr = int(stream.cuda_stream) or None
+
+    # ---- prefill compression pass (timed per copy; the first is the warm-up) ----------------------
+    comp_ms = []
+    for dw in copies:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        dw.cache.compress(qw, k, v)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        comp_ms.append(e0.elapsed_time(e1))
+    compress_ms = statistics.median(comp_ms[1:]) if len(comp_ms) > 1 else comp_ms[0]
+
+    def raw_step(dw, i):
+        j = i % n_inputs
+        st = lib.hkv_decode_attn(dw.cache.handle, 0, L, q_all[j].data_ptr(), kn_all[j].data_ptr(),
+                                 vn_all[j].data_ptr(), out.data_ptr(), dw.cache.workspace.data_ptr(),
+                                 dw.cache.workspace_bytes, sptr)
+        if st != 0:
+            raise B.HkvError(st, "hkv_decode_attn")
+
+    for dw in copies:                      # tail pre-roll (setup, untimed)
+        for i in range(preroll):
+            raw_step(dw, i)
+    for i in range(W):                     # warm-up
+        raw_step(copies[i % n_copies], i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps ---------------------------------------------------------
+    tail0 = preroll + -(-W // n_copies)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(K):
+        raw_step(copies[(W + i) % n_copies], W + i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / K
+    mean_tail = tail0 + (K / n_copies) / 2.0
+    step_bytes = copies[0].cache.step_bytes(int(round(mean_tail)))
+    step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations (separate pass: events between the kernels) ----------------------------
+    for dw in copies:
+        B.hkv_profile_enable(dw.cache.handle, -(-K // n_copies) + 1)
+    for i in range(K):
+        raw_step(copies[i % n_copies], i)
+    torch.cuda.synchronize()
+    kms = [0.0, 0.0, 0.0]
+    ncalls = 0
+    for dw in copies:
+        ms, n = B.hkv_profile_read(dw.cache.handle)
+        kms = [a + b for a, b in zip(kms, ms)]
+        ncalls += n
+        B.hkv_profile_disable(dw.cache.handle)
+    prep_us, attn_us, merge_us = (x / ncalls * 1e3 for x in kms)
+    R = d * wl.elem_bytes
+    tail_prof = tail0 + K / n_copies + (K / n_copies) / 2.0
+    # algorithmic bytes of ONE launch of the attention kernel: K and V rows of every retained row
+    attn_bytes = 0
+    for l in range(L):
+        for b in range(Bn):
+            for h in range(Hkv):
+                rows, _, _ = copies[0].cache.unit_info(b, l, h)
+                attn_bytes += 2 * R * (rows + tail_prof)
+    attn_gbs = attn_bytes / (attn_us * 1e-6) / 1e9
+
+    # ---- full-KV comparison kernel ------------------------------------------------------------------
+    cfg = copies[0].cfg
+    fws_bytes = B.hkv_full_workspace_size(cfg, wl.cu_seqlens, L)
+    fws = torch.empty(fws_bytes, dtype=torch.uint8, device=dev)
+    cu = np.ascontiguousarray(wl.cu_seqlens, dtype=np.int32)
+    import ctypes as C
+    cu_p = cu.ctypes.data_as(C.POINTER(C.c_int32))
+
+    def full_step(i):
+        j = i % n_inputs
+        st = lib.hkv_full_decode_attn(C.byref(cfg), Bn, cu_p, L, q_all[j].data_ptr(), k.data_ptr(), v.data_ptr(),
+                                      out.data_ptr(), fws.data_ptr(), fws_bytes, sptr)
+        if st != 0:
+            raise B.HkvError(st, "hkv_full_decode_attn")
+
+    n_full = max(8, min(K, 32))
+    for i in range(4):
+        full_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_full):
+        full_step(i)
+    torch.cuda.synchronize()
+    full_ms = (time.perf_counter() - t0) * 1e3 / n_full
+    full_bytes = 2 * R * int(wl.cu_seqlens[-1]) * Hkv * L
+    full_gbs = full_bytes / (full_ms * 1e-3) / 1e9
+
+    # ---- CPU oracle on the host cores (reported baseline only) -----------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import hybridkv_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        ocfg = O.OracleConfig(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, window=wl.window, dtype=wl.dtype)
+        oplan = O.OraclePlan(cu_seqlens=wl.cu_seqlens, head_type=wl.head_type, budget=wl.budget,
+                             chunk_size=wl.chunk_size)
+        n_lay = max(1, min(L, 4))
+        t0 = time.perf_counter()
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=range(n_lay))
+        t_comp = time.perf_counter() - t0
+        n_dec = 0
+        t0 = time.perf_counter()
+        while n_dec < min(K, n_inputs) and time.perf_counter() - t0 < args.cpu_seconds:
+            O.decode_attn(ocache, wl.q_steps[n_dec], wl.k_new[n_dec], wl.v_new[n_dec], layers=range(n_lay))
+            n_dec += 1
+        t_dec = time.perf_counter() - t0
+        cpu = {"value": round(t_dec / n_dec * (L / n_lay) * 1e6, 1), "unit": "us/step", "cores": int(cores),
+               "kind": "oracle",
+               "sample": f"{n_dec} decode steps of layers 0..{n_lay - 1} of {L}, scaled by {L}/{n_lay}; "
+                         f"oracle compress of those layers took {t_comp:.2f} s ({t_comp / n_lay * L:.1f} s scaled)"}
+
+    retained_frac = step_bytes / (full_bytes + 2 * R * mean_tail * Hkv * L * Bn)
+    result = {
+        "metric": "hybrid decode-attn us/step + HBM GB/s on retained KV vs full-KV, 1xMI355X",
+        "value": round(ms_per_step * 1e3, 2),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "batch": Bn,
+                   "context": int(wl.seqlens.max()), "budget_rule": wl.budget_rule,
+                   "nominal_budget": float(wl.budget_frac[0]), "retained_byte_fraction": round(retained_frac, 4),
+                   "chunk": int(wl.chunk_size[0]), "layer_range_per_call": L, "cache_copies_rotated": n_copies,
+                   "mean_tail_tokens": round(mean_tail, 1)},
+        "tokens_per_s": round(Bn / (ms_per_step * 1e-3), 1),
+        "gpu_ms_per_step_events": round(gpu_ms / K, 5),
+        "retained_bytes_per_step": int(step_bytes),
+        "hbm_gbs_on_retained_kv": round(step_gbs, 1),
+        "hbm_frac_on_retained_kv": round(step_gbs / HBM_PEAK_GBS, 4),
+        "full_kv_us_per_step": round(full_ms * 1e3, 2),
+        "full_kv_gbs": round(full_gbs, 1),
+        "speedup_vs_full_kv": round(full_ms / ms_per_step, 3),
+        "compress_ms": round(compress_ms, 3),
+        "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
+        "kernel_us": {"prepare": round(prep_us, 2), "attention": round(attn_us, 2), "merge": round(merge_us, 2)},
+        "roofline": {"kernel": "attn_partial_kernel", "bound": "hbm", "achieved": round(attn_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": _read_traffic(f"pmc_attn_partial_{wl.name}.txt"),
+                     "bytes_per_launch": int(attn_bytes), "avg_launch_us": round(attn_us, 2)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+    for dw in copies:
+        dw.cache.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -189,6 +189,16 @@ HKV_API int hkv_compress_from_scores(hkv_cache* cache, int layer_begin, int laye
                              const void* v, void* stream);
 HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end, void* stream);
 
+/* Optional per-kernel timing of hkv_decode_attn, for benchmarks.  After hkv_profile_enable every
+ * decode call on this cache (up to max_calls) records HIP events between its three kernels on the
+ * call's own stream (no synchronisation).  hkv_profile_read waits for the recorded events, returns
+ * the summed durations in milliseconds -- ms[0] tail append + chunk scoring + chunk top-k,
+ * ms[1] split-K attention, ms[2] merge -- and the number of calls summed, then starts over.
+ * hkv_profile_disable releases the events. */
+HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);
+HKV_API int hkv_profile_read(hkv_cache* cache, double* ms, int* n_calls);
+HKV_API int hkv_profile_disable(hkv_cache* cache);
+
 HKV_API void hkv_cache_destroy(hkv_cache* cache);   /* frees the host descriptor only */
 HKV_API const char* hkv_strerror(int status);
 HKV_API uint32_t hkv_abi_version(void);

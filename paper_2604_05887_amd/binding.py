@@ -27,6 +27,7 @@ EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
     "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
+    "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
 
@@ -80,6 +81,9 @@ def load_library() -> C.CDLL:
     lib.hkv_cache_import.argtypes = [vp, i32, i32, i32, i32, vp, sz, vp]
     lib.hkv_compress_from_scores.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.hkv_reselect_chunks.argtypes = [vp, i32, i32, vp]
+    lib.hkv_profile_enable.argtypes = [vp, i32]
+    lib.hkv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
+    lib.hkv_profile_disable.argtypes = [vp]
     lib.hkv_cache_destroy.argtypes = [vp]
     lib.hkv_cache_destroy.restype = None
     lib.hkv_strerror.argtypes = [i32]
@@ -223,6 +227,21 @@ def hkv_cache_step_bytes(handle: int, layer_begin: int, layer_end: int, tail: in
     _check(load_library().hkv_cache_step_bytes(handle, layer_begin, layer_end, tail, C.byref(v)),
            "hkv_cache_step_bytes")
     return int(v.value)
+
+
+def hkv_profile_enable(handle: int, max_calls: int) -> None:
+    _check(load_library().hkv_profile_enable(handle, max_calls), "hkv_profile_enable")
+
+
+def hkv_profile_read(handle: int) -> Tuple[Tuple[float, float, float], int]:
+    ms = (C.c_double * 3)()
+    n = C.c_int(0)
+    _check(load_library().hkv_profile_read(handle, ms, C.byref(n)), "hkv_profile_read")
+    return (float(ms[0]), float(ms[1]), float(ms[2])), int(n.value)
+
+
+def hkv_profile_disable(handle: int) -> None:
+    _check(load_library().hkv_profile_disable(handle), "hkv_profile_disable")
 
 
 _EXPORT_NP = {HKV_X_KEPT_IDX: np.int32, HKV_X_SCORES: np.float32, HKV_X_CHUNK_SEL: np.int32,

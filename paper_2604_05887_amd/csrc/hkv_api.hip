@@ -177,6 +177,8 @@ struct hkv_cache {
   char* arena;
   std::vector<int32_t> host_tail;     // [n_layers] appended tokens (host mirror of the device counter)
   std::vector<uint8_t> compressed;    // [n_layers]
+  std::vector<hipEvent_t> events;     // 4 per profiled decode call
+  int prof_calls = 0, prof_max = 0;
 };
 
 extern "C" {
@@ -259,7 +261,50 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   return HKV_OK;
 }
 
-void hkv_cache_destroy(hkv_cache* cache) { delete cache; }
+int hkv_profile_disable(hkv_cache* c) {
+  if (!c) return HKV_EINVAL;
+  for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+  c->events.clear();
+  c->prof_calls = c->prof_max = 0;
+  return HKV_OK;
+}
+
+int hkv_profile_enable(hkv_cache* c, int max_calls) {
+  if (!c || max_calls < 1 || max_calls > (1 << 20)) return HKV_EINVAL;
+  hkv_profile_disable(c);
+  c->events.resize((size_t)4 * max_calls);
+  for (size_t i = 0; i < c->events.size(); ++i) {
+    if (hipEventCreate(&c->events[i]) != hipSuccess) {
+      c->events.resize(i);
+      hkv_profile_disable(c);
+      return HKV_EHIP;
+    }
+  }
+  c->prof_max = max_calls;
+  return HKV_OK;
+}
+
+int hkv_profile_read(hkv_cache* c, double* ms, int* n_calls) {
+  if (!c || !ms || !n_calls) return HKV_EINVAL;
+  ms[0] = ms[1] = ms[2] = 0.0;
+  for (int i = 0; i < c->prof_calls; ++i) {
+    hipEvent_t* e = &c->events[(size_t)4 * i];
+    if (hipEventSynchronize(e[3]) != hipSuccess) return HKV_EHIP;
+    for (int j = 0; j < 3; ++j) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, e[j], e[j + 1]) != hipSuccess) return HKV_EHIP;
+      ms[j] += t;
+    }
+  }
+  *n_calls = c->prof_calls;
+  c->prof_calls = 0;
+  return HKV_OK;
+}
+
+void hkv_cache_destroy(hkv_cache* cache) {
+  if (cache) hkv_profile_disable(cache);
+  delete cache;
+}
 
 static int check_range(const hkv_cache* c, int lb, int le) {
   if (!c) return HKV_EINVAL;
@@ -320,10 +365,17 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   const Layout& lo = c->lo;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int ib = lo.item_begin[lb], ni = lo.item_begin[le] - ib;
-  hipError_t e = launch_prepare(c->cv, c->cfg.dtype, lb, le, q, k_new, v_new, 0, 1, lo.max_chunks, st);
+  hipEvent_t* ev = (c->prof_max > 0 && c->prof_calls < c->prof_max) ? &c->events[(size_t)4 * c->prof_calls] : nullptr;
+  hipError_t e = hipSuccess;
+  if (ev) e = hipEventRecord(ev[0], st);
+  if (e == hipSuccess) e = launch_prepare(c->cv, c->cfg.dtype, lb, le, q, k_new, v_new, 0, 1, lo.max_chunks, st);
+  if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
   if (e == hipSuccess) e = launch_attn_partial(c->cv, c->cfg.dtype, lb, ib, ni, q, static_cast<float*>(workspace), st);
+  if (ev && e == hipSuccess) e = hipEventRecord(ev[2], st);
   if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, ib, static_cast<const float*>(workspace), out, 1, st);
+  if (ev && e == hipSuccess) e = hipEventRecord(ev[3], st);
   if (e != hipSuccess) return HKV_EHIP;
+  if (ev) c->prof_calls += 1;
   if (k_new) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
   return HKV_OK;
 }
