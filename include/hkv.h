@@ -190,10 +190,11 @@ HKV_API int hkv_compress_from_scores(hkv_cache* cache, int layer_begin, int laye
 HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end, void* stream);
 
 /* Optional per-kernel timing of hkv_decode_attn, for benchmarks.  After hkv_profile_enable every
- * decode call on this cache (up to max_calls) records HIP events between its three kernels on the
+ * decode call on this cache (up to max_calls) records HIP events between its kernels on the
  * call's own stream (no synchronisation).  hkv_profile_read waits for the recorded events, returns
  * the summed durations in milliseconds -- ms[0] tail append + chunk scoring + chunk top-k,
- * ms[1] split-K attention, ms[2] merge -- and the number of calls summed, then starts over.
+ * ms[1] split-K attention including its fused combination, ms[2] reserved (0) -- and the number of
+ * calls summed, then starts over.
  * hkv_profile_disable releases the events. */
 HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);
 HKV_API int hkv_profile_read(hkv_cache* cache, double* ms, int* n_calls);

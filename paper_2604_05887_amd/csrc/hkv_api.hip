@@ -29,7 +29,7 @@ struct Layout {
   // element counts
   int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
   // arena offsets (bytes)
-  size_t off_units = 0, off_items = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
+  size_t off_units = 0, off_items = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_done = 0, off_kept = 0,
          off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
   size_t ws_bytes = 0;
 };
@@ -59,6 +59,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
   if (plan->batch < 1 || plan->batch > 4096) return HKV_ESHAPE;
   const int B = plan->batch, L = cfg->n_layers, H = cfg->n_kv_heads, w = cfg->window;
   const int G = cfg->n_q_heads / H;
+  const int tile = tile_rows(cfg->dtype);
   if (plan->cu_seqlens[0] != 0) return HKV_EINVAL;
   lo.cu.assign(plan->cu_seqlens, plan->cu_seqlens + B + 1);
   std::vector<int32_t> n_txt(B), n_vis(B), csz(B);
@@ -129,7 +130,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
         }
         lo.n_rows += phys_rows + cfg->max_new_tokens;
         d.item_begin = (int32_t)lo.items.size();
-        d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + kTile - 1) / kTile);
+        d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + tile - 1) / tile);
         for (int t = 0; t < d.n_tiles_max; ++t) lo.items.push_back(make_int2(u, t));
         if (lo.items.size() > (size_t)0x7fffff00) return HKV_ESHAPE;
         lo.units[u] = d;
@@ -150,6 +151,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
   lo.off_dynamic = take(std::max<size_t>(1, lo.dynamic_units.size()) * 4);
   lo.off_vis = take((size_t)lo.total_tokens);
   lo.off_cnt = take((size_t)2 * L * 4);
+  lo.off_done = take(lo.units.size() * 4);
   lo.off_kept = take((size_t)std::max<int64_t>(1, lo.n_kept) * 4);
   lo.off_sel = take((size_t)std::max<int64_t>(1, lo.n_sel) * 4);
   lo.off_scores = take((size_t)std::max<int64_t>(1, lo.n_scores) * 4);
@@ -233,6 +235,7 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   cv.is_visual = reinterpret_cast<const uint8_t*>(a + lo.off_vis);
   cv.cnt_a = reinterpret_cast<int32_t*>(a + lo.off_cnt);
   cv.cnt_b = cv.cnt_a + cfg->n_layers;
+  cv.done = reinterpret_cast<int32_t*>(a + lo.off_done);
   cv.kept_idx = reinterpret_cast<int32_t*>(a + lo.off_kept);
   cv.sel = reinterpret_cast<int32_t*>(a + lo.off_sel);
   cv.scores = reinterpret_cast<float*>(a + lo.off_scores);
@@ -256,6 +259,7 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   up(lo.off_dynamic, lo.dynamic_units.data(), lo.dynamic_units.size() * 4);
   up(lo.off_vis, plan->is_visual, (size_t)lo.total_tokens);
   if (e == hipSuccess) e = hipMemset(a + lo.off_cnt, 0, (size_t)2 * cfg->n_layers * 4);
+  if (e == hipSuccess) e = hipMemset(a + lo.off_done, 0, lo.units.size() * 4);
   if (e != hipSuccess) { delete c; return HKV_EHIP; }
   *out = c;
   return HKV_OK;
@@ -370,9 +374,8 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   if (ev) e = hipEventRecord(ev[0], st);
   if (e == hipSuccess) e = launch_prepare(c->cv, c->cfg.dtype, lb, le, q, k_new, v_new, 0, 1, lo.max_chunks, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
-  if (e == hipSuccess) e = launch_attn_partial(c->cv, c->cfg.dtype, lb, ib, ni, q, static_cast<float*>(workspace), st);
+  if (e == hipSuccess) e = launch_attn(c->cv, c->cfg.dtype, lb, ib, ni, q, static_cast<float*>(workspace), out, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[2], st);
-  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, ib, static_cast<const float*>(workspace), out, 1, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[3], st);
   if (e != hipSuccess) return HKV_EHIP;
   if (ev) c->prof_calls += 1;
@@ -411,7 +414,8 @@ static int full_view(const hkv_config* cfg, int32_t batch, const int32_t* cu, in
   std::memcpy(fv.cu, cu, (size_t)(batch + 1) * 4);
   fv.batch = batch; fv.n_layers_call = n_layers_call; fv.n_q_heads = cfg->n_q_heads; fv.n_kv_heads = cfg->n_kv_heads;
   fv.G = cfg->n_q_heads / cfg->n_kv_heads;
-  fv.n_tiles_max = (max_len + kTile - 1) / kTile;
+  const int tile = tile_rows(cfg->dtype);
+  fv.n_tiles_max = (max_len + tile - 1) / tile;
   fv.total_tokens = cu[batch];
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   fv.scale_log2e = scale * 1.4426950408889634f;
@@ -425,7 +429,8 @@ int hkv_full_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t*
   FullView fv;
   int rc = full_view(cfg, batch, cu_seqlens, n_layers_call, fv);
   if (rc != HKV_OK) return rc;
-  *workspace_bytes = align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float));
+  *workspace_bytes = align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float)) +
+                     align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * sizeof(int32_t));
   return HKV_OK;
 }
 
@@ -440,6 +445,9 @@ int hkv_full_decode_attn(const hkv_config* cfg, int32_t batch, const int32_t* cu
   size_t need = 0;
   hkv_full_workspace_size(cfg, batch, cu_seqlens, n_layers_call, &need);
   if (workspace_bytes < need) return HKV_ENOSPACE;
+  fv.done = reinterpret_cast<int32_t*>(
+      static_cast<char*>(workspace) +
+      align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float)));
   hipError_t e = launch_full_attn(fv, cfg->dtype, q, k, v, static_cast<float*>(workspace), out,
                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;

@@ -10,7 +10,9 @@ namespace hkv {
 
 constexpr int kD = 128;          // head_dim
 constexpr int kMaxG = 8;         // query heads per KV head
-constexpr int kTile = 128;       // logical rows per split-K work item of decode attention
+constexpr int kTileF32 = 128;    // logical rows per split-K work item of decode attention, fp32 path
+constexpr int kTileBf16 = 256;   // same, bf16 path (four waves x two 32-row half batches)
+inline constexpr int tile_rows(int dtype) { return dtype == HKV_BF16 ? kTileBf16 : kTileF32; }
 constexpr int kPartStride = 132; // floats per (work item, query head): m, l, 2 pad, o[128]
 constexpr int kKeysPerBlock = 512;   // keys one scoring block covers
 constexpr int kMaxScoreRows = 256;   // G * window upper bound
@@ -49,6 +51,7 @@ struct CacheView {
   const uint8_t* is_visual;
   int32_t* cnt_a;             // [n_layers] tail length before the step in flight
   int32_t* cnt_b;             // [n_layers] tail length the step in flight attends
+  int32_t* done;              // [n_units] split-K tiles finished in the step in flight (self-resetting)
   int32_t* kept_idx;
   int32_t* sel;
   float* scores;
@@ -65,10 +68,8 @@ struct CacheView {
 hipError_t launch_prepare(const CacheView& cv, int dtype, int layer_begin, int layer_end, const void* q,
                           const void* k_new, const void* v_new, int use_stored_sigma, int do_scoring,
                           int max_chunks, hipStream_t st);
-hipError_t launch_attn_partial(const CacheView& cv, int dtype, int layer_begin, int item_begin, int n_items,
-                               const void* q, float* partials, hipStream_t st);
-hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int item_base,
-                             const float* partials, void* out, int advance_tail, hipStream_t st);
+hipError_t launch_attn(const CacheView& cv, int dtype, int layer_begin, int item_begin, int n_items,
+                       const void* q, float* partials, void* out, hipStream_t st);
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
 
 struct FullView {
@@ -76,6 +77,7 @@ struct FullView {
   int32_t batch, n_layers_call, n_q_heads, n_kv_heads, G, n_tiles_max;
   int64_t total_tokens;
   float scale_log2e;
+  int32_t* done;              // [units] tile counters inside the workspace (zeroed by the launcher)
 };
 hipError_t launch_full_attn(const FullView& fv, int dtype, const void* q, const void* k, const void* v,
                             float* partials, void* out, hipStream_t st);
