@@ -193,7 +193,7 @@ HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end
  * decode call on this cache (up to max_calls) records HIP events between its kernels on the
  * call's own stream (no synchronisation).  hkv_profile_read waits for the recorded events, returns
  * the summed durations in milliseconds -- ms[0] tail append + chunk scoring + chunk top-k,
- * ms[1] split-K attention including its fused combination, ms[2] reserved (0) -- and the number of
+ * ms[1] split-K attention, ms[2] combination of the split-K tiles -- and the number of
  * calls summed, then starts over.
  * hkv_profile_disable releases the events. */
 HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);

@@ -20,7 +20,7 @@ inline size_t elem_size(int dtype) { return dtype == HKV_BF16 ? 2 : 4; }
 struct Layout {
   // host tables
   std::vector<UnitDesc> units;
-  std::vector<int2> items;
+  std::vector<AttnItem> items;
   std::vector<int32_t> static_units, dynamic_units;
   std::vector<int32_t> static_begin, dynamic_begin, item_begin;   // [n_layers + 1]
   std::vector<int32_t> cu;
@@ -29,7 +29,7 @@ struct Layout {
   // element counts
   int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
   // arena offsets (bytes)
-  size_t off_units = 0, off_items = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_done = 0, off_kept = 0,
+  size_t off_units = 0, off_items = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
          off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
   size_t ws_bytes = 0;
 };
@@ -131,7 +131,22 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
         lo.n_rows += phys_rows + cfg->max_new_tokens;
         d.item_begin = (int32_t)lo.items.size();
         d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + tile - 1) / tile);
-        for (int t = 0; t < d.n_tiles_max; ++t) lo.items.push_back(make_int2(u, t));
+        if ((int64_t)C + cfg->max_new_tokens >= (1 << 24)) return HKV_ESHAPE;   // 24-bit row arithmetic in the kernels
+        for (int t = 0; t < d.n_tiles_max; ++t) {
+          AttnItem it;
+          std::memset(&it, 0, sizeof(it));
+          it.kv_row_off = d.kv_row_off;
+          it.q_off = (((int64_t)l * B + b) * cfg->n_q_heads + (int64_t)h * G) * kD;
+          it.sel_off = ht == HKV_DYNAMIC ? (int32_t)d.idx_off : 0;
+          it.n_prompt_rows = d.n_prompt_rows;
+          it.row0 = t * tile;
+          it.C = C;
+          it.c_log2 = d.c_log2;
+          it.dynamic = ht == HKV_DYNAMIC;
+          it.layer = l;
+          it.unit = u;
+          lo.items.push_back(it);
+        }
         if (lo.items.size() > (size_t)0x7fffff00) return HKV_ESHAPE;
         lo.units[u] = d;
       }
@@ -146,12 +161,11 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   lo.off_units = take(lo.units.size() * sizeof(UnitDesc));
-  lo.off_items = take(lo.items.size() * sizeof(int2));
+  lo.off_items = take(lo.items.size() * sizeof(AttnItem));
   lo.off_static = take(std::max<size_t>(1, lo.static_units.size()) * 4);
   lo.off_dynamic = take(std::max<size_t>(1, lo.dynamic_units.size()) * 4);
   lo.off_vis = take((size_t)lo.total_tokens);
   lo.off_cnt = take((size_t)2 * L * 4);
-  lo.off_done = take(lo.units.size() * 4);
   lo.off_kept = take((size_t)std::max<int64_t>(1, lo.n_kept) * 4);
   lo.off_sel = take((size_t)std::max<int64_t>(1, lo.n_sel) * 4);
   lo.off_scores = take((size_t)std::max<int64_t>(1, lo.n_scores) * 4);
@@ -229,13 +243,12 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   char* a = c->arena;
   CacheView& cv = c->cv;
   cv.units = reinterpret_cast<const UnitDesc*>(a + lo.off_units);
-  cv.items = reinterpret_cast<const int2*>(a + lo.off_items);
+  cv.items = reinterpret_cast<const AttnItem*>(a + lo.off_items);
   cv.static_units = reinterpret_cast<const int32_t*>(a + lo.off_static);
   cv.dynamic_units = reinterpret_cast<const int32_t*>(a + lo.off_dynamic);
   cv.is_visual = reinterpret_cast<const uint8_t*>(a + lo.off_vis);
   cv.cnt_a = reinterpret_cast<int32_t*>(a + lo.off_cnt);
   cv.cnt_b = cv.cnt_a + cfg->n_layers;
-  cv.done = reinterpret_cast<int32_t*>(a + lo.off_done);
   cv.kept_idx = reinterpret_cast<int32_t*>(a + lo.off_kept);
   cv.sel = reinterpret_cast<int32_t*>(a + lo.off_sel);
   cv.scores = reinterpret_cast<float*>(a + lo.off_scores);
@@ -254,12 +267,11 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
     if (e == hipSuccess && bytes) e = hipMemcpy(a + off, src, bytes, hipMemcpyHostToDevice);
   };
   up(lo.off_units, lo.units.data(), lo.units.size() * sizeof(UnitDesc));
-  up(lo.off_items, lo.items.data(), lo.items.size() * sizeof(int2));
+  up(lo.off_items, lo.items.data(), lo.items.size() * sizeof(AttnItem));
   up(lo.off_static, lo.static_units.data(), lo.static_units.size() * 4);
   up(lo.off_dynamic, lo.dynamic_units.data(), lo.dynamic_units.size() * 4);
   up(lo.off_vis, plan->is_visual, (size_t)lo.total_tokens);
   if (e == hipSuccess) e = hipMemset(a + lo.off_cnt, 0, (size_t)2 * cfg->n_layers * 4);
-  if (e == hipSuccess) e = hipMemset(a + lo.off_done, 0, lo.units.size() * 4);
   if (e != hipSuccess) { delete c; return HKV_EHIP; }
   *out = c;
   return HKV_OK;
@@ -369,13 +381,19 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   const Layout& lo = c->lo;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int ib = lo.item_begin[lb], ni = lo.item_begin[le] - ib;
+  // tail length: when every layer of the call has the same one (the normal case) it travels as a
+  // kernel argument; otherwise the kernels read the per-layer device counters
+  int t_before = c->host_tail[lb];
+  for (int l = lb; l < le; ++l) if (c->host_tail[l] != t_before) t_before = -1;
+  const int t_after = t_before < 0 ? -1 : t_before + (k_new ? 1 : 0);
   hipEvent_t* ev = (c->prof_max > 0 && c->prof_calls < c->prof_max) ? &c->events[(size_t)4 * c->prof_calls] : nullptr;
   hipError_t e = hipSuccess;
   if (ev) e = hipEventRecord(ev[0], st);
-  if (e == hipSuccess) e = launch_prepare(c->cv, c->cfg.dtype, lb, le, q, k_new, v_new, 0, 1, lo.max_chunks, st);
+  if (e == hipSuccess) e = launch_prepare(c->cv, c->cfg.dtype, lb, le, q, k_new, v_new, 0, 1, t_before, lo.max_chunks, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
-  if (e == hipSuccess) e = launch_attn(c->cv, c->cfg.dtype, lb, ib, ni, q, static_cast<float*>(workspace), out, st);
+  if (e == hipSuccess) e = launch_attn(c->cv, c->cfg.dtype, lb, ib, ni, q, static_cast<float*>(workspace), t_after, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[2], st);
+  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, ib, static_cast<const float*>(workspace), out, t_after, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[3], st);
   if (e != hipSuccess) return HKV_EHIP;
   if (ev) c->prof_calls += 1;
@@ -386,7 +404,7 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
 int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
   int rc = check_range(c, lb, le);
   if (rc != HKV_OK) return rc;
-  hipError_t e = launch_prepare(c->cv, c->cfg.dtype, lb, le, nullptr, nullptr, nullptr, 1, 0, c->lo.max_chunks,
+  hipError_t e = launch_prepare(c->cv, c->cfg.dtype, lb, le, nullptr, nullptr, nullptr, 1, 0, -1, c->lo.max_chunks,
                                 static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;
 }
@@ -408,6 +426,9 @@ static int full_view(const hkv_config* cfg, int32_t batch, const int32_t* cu, in
   int32_t max_len = 0;
   for (int b = 0; b < batch; ++b) {
     if (cu[b + 1] <= cu[b]) return HKV_ESHAPE;
+    // 24-bit row index times row stride must fit 32 bits inside the kernels
+    if ((int64_t)(cu[b + 1] - cu[b]) >= (1 << 24) ||
+        (int64_t)(cu[b + 1] - cu[b]) * cfg->n_kv_heads * kD * 4 >= ((int64_t)1 << 32)) return HKV_ESHAPE;
     max_len = std::max(max_len, cu[b + 1] - cu[b]);
   }
   std::memset(&fv, 0, sizeof(fv));
@@ -429,8 +450,7 @@ int hkv_full_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t*
   FullView fv;
   int rc = full_view(cfg, batch, cu_seqlens, n_layers_call, fv);
   if (rc != HKV_OK) return rc;
-  *workspace_bytes = align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float)) +
-                     align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * sizeof(int32_t));
+  *workspace_bytes = align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float));
   return HKV_OK;
 }
 
@@ -445,9 +465,6 @@ int hkv_full_decode_attn(const hkv_config* cfg, int32_t batch, const int32_t* cu
   size_t need = 0;
   hkv_full_workspace_size(cfg, batch, cu_seqlens, n_layers_call, &need);
   if (workspace_bytes < need) return HKV_ENOSPACE;
-  fv.done = reinterpret_cast<int32_t*>(
-      static_cast<char*>(workspace) +
-      align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float)));
   hipError_t e = launch_full_attn(fv, cfg->dtype, q, k, v, static_cast<float*>(workspace), out,
                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;

@@ -2,9 +2,13 @@
 //   prepare_kernel   append the step's K/V rows to every head's tail; for dynamic heads score all
 //                    chunk summaries with the group-summed query and pick the top-k chunks
 //                    (paper, Appendix A, "KV Cache Retrieval for Dynamic Heads")
-//   attn_partial     split-K softmax attention over a tile of a head's retained rows: compacted
+//   attn_kernel      split-K softmax attention over a tile of a head's retained rows: compacted
 //                    rows (static heads), gathered chunk rows (dynamic heads) or all rows (full KV)
 //   attn_merge       log-sum-exp combination of the tiles in fixed order, cast to the output dtype
+//
+// All three are short kernels on small inputs, so their structure is driven by memory latency as
+// much as by bandwidth: descriptors come in through scalar loads, every thread issues its global
+// loads in independent batches, and nothing walks a dependent chain longer than it must.
 #include "hkv_device.h"
 #include "hkv_internal.h"
 #include "hkv_select.h"
@@ -15,7 +19,7 @@ namespace hkv {
 struct RowMap {
   const char* kbase;
   const char* vbase;
-  int64_t stride;        // bytes between consecutive physical rows
+  uint32_t stride;       // bytes between consecutive physical rows
   const int32_t* sel;    // dynamic: selected chunk ids (ascending)
   int32_t dynamic;
   int32_t n_sel_rows;    // dynamic: k_sel << c_log2
@@ -35,7 +39,10 @@ __device__ __forceinline__ bool resolve_row(const RowMap& rm, int r, int64_t& ph
   return true;
 }
 
-// One tile (kTileF32 logical rows starting at row0) of one KV head for its G query heads; any dtype.
+// ---------------------------------------------------------------------------------------------
+// generic tile (any dtype; used for fp32): 16 or 32 lanes per row, fp32 FMAs, wave reductions
+// ---------------------------------------------------------------------------------------------
+// One tile (kTileF32 logical rows starting at row0) of one KV head for its G query heads.
 // Writes G records of kPartStride floats: [0]=running max (log2 domain), [1]=sum, [4..131]=unnormalised o.
 template <typename T, int G>
 __device__ __forceinline__ void attn_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
@@ -136,28 +143,42 @@ __device__ __forceinline__ void attn_tile(const RowMap& rm, const T* __restrict_
   }
 }
 
-// ---- bf16 tile: packed dot products, transpose-reduce across the 16 lanes of a row ----------------
+// ---------------------------------------------------------------------------------------------
+// bf16 tile: packed dot products, transpose-reduce across the 16 lanes of a row
+// ---------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 __device__ __forceinline__ float dot2bf(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
-template <int CTRL> __device__ __forceinline__ float dpp_max(float x) { return fmaxf(x, dpp_mov<CTRL>(x)); }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  bf16x2_t v = {(__bf16)lo, (__bf16)hi};        // round to nearest even
+  return __builtin_bit_cast(uint32_t, v);
+}
+template <int CTRL> __device__ __forceinline__ float dpp_max(float x) {
+  const int xi = __builtin_bit_cast(int, x);
+  return fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(xi, xi, CTRL, 0xf, 0xf, false)));
+}
+__device__ __forceinline__ float max16(float x) {
+  x = dpp_max<0xB1>(x); x = dpp_max<0x4E>(x); x = dpp_max<0x141>(x); return dpp_max<0x140>(x);
+}
 
 constexpr int kStreams = 16;          // 4 waves x 4 row groups, each an independent online-softmax stream
 constexpr int kPGroupStride = 40;     // dwords per (wave, group) in the weight exchange buffer (32 + pad)
+constexpr float kRescaleSlack = 8.f;  // a stream's reference maximum may lag the true one by 2^8
 template <int G> constexpr size_t attn_bf16_smem_bytes() {
   return (size_t)kStreams * G * kPartStride * sizeof(float) + (size_t)kStreams * kPGroupStride * 4;
 }
 
-// One tile of kTileBf16 logical rows.  Lane (grp = lane / 16, sub = lane % 16) loads 16 bytes (8 dims) of
-// row 4*i + grp for i = 0..7 of each 32-row half batch; per query head the 8 partial dot products are
-// summed across the 16 lanes by a butterfly that leaves lane `sub` with the full score of row i = sub % 8.
-// Softmax weights go through shared memory as bf16 pairs of two rows so that the weighted sum of V uses
-// packed dot products as well.
-template <int G>
+// One tile of 128 * NHB logical rows.  Lane (grp = lane / 16, sub = lane % 16) loads 16 bytes (8 dims)
+// of row 4*i + grp for i = 0..7 of each 32-row half batch; per query head the 8 partial dot products
+// are summed across the 16 lanes by a butterfly that leaves lane `sub` with the full score of row
+// i = sub % 8.  Softmax weights go through shared memory as bf16 pairs of two rows so that the
+// weighted sum of V uses packed dot products as well.  The softmax reference maximum of a stream is
+// only raised when a score exceeds it by more than kRescaleSlack, which keeps every weight below 2^8
+// and removes the rescaling of the accumulators from almost every half batch.
+template <int G, int NHB, bool DYN>
 __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* __restrict__ q, float scale_log2e,
                                                int row0, float* __restrict__ part, float* smem) {
-  constexpr int HB = 32, NHB = kTileBf16 / 4 / HB;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
   uint32_t* pbuf = reinterpret_cast<uint32_t*>(smem + (size_t)kStreams * G * kPartStride) +
@@ -177,27 +198,46 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
   }
   const bool b4 = (sub & 4) != 0, b2 = (sub & 2) != 0, b1 = (sub & 1) != 0;
+  const int wrow0 = __builtin_amdgcn_readfirstlane(row0 + wv * 32 * NHB);
+  const uint32_t lane_off = (uint32_t)sub * 16u;
+  const uint32_t cmask = (1u << rm.c_log2) - 1u;
 
 #pragma unroll 1
   for (int hb = 0; hb < NHB; ++hb) {
-    const int rbase = row0 + (wv * NHB + hb) * HB;
+    const int rbase = wrow0 + hb * 32;
     if (rbase >= rm.n_rows) break;                       // wave-uniform
-    uint4 kraw[8], vraw[8];
+    // ---- addresses: invalid rows are redirected to a row that exists and masked out below ----
+    uint32_t off[8];
     uint32_t vmask = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = rbase + 4 * i + grp;
-      bool valid = r < rm.n_rows;
-      int64_t phys = 0;
-      if (valid) valid = resolve_row(rm, r, phys);
-      kraw[i] = make_uint4(0, 0, 0, 0); vraw[i] = make_uint4(0, 0, 0, 0);
-      if (valid) {
-        kraw[i] = ld16(rm.kbase + phys * rm.stride + sub * 16);
-        vraw[i] = ld16(rm.vbase + phys * rm.stride + sub * 16);
-        vmask |= 1u << i;
+      uint32_t phys;
+      bool valid;
+      if constexpr (!DYN) {
+        valid = r < rm.n_rows;
+        phys = (uint32_t)min(r, rm.n_rows - 1);
+      } else {
+        if (rbase + 4 * i < rm.n_sel_rows) {              // wave-uniform: chunks are multiples of 4 rows
+          const int ch = rm.sel[(rbase + 4 * i) >> rm.c_log2];
+          phys = ((uint32_t)ch << rm.c_log2) + ((uint32_t)r & cmask);
+          valid = phys < (uint32_t)rm.C;                  // the last chunk of the prompt may be short
+        } else {
+          phys = (uint32_t)rm.C + (uint32_t)(r - rm.n_sel_rows);
+          valid = r < rm.n_rows;
+        }
+        phys = valid ? phys : 0u;
       }
+      off[i] = __umul24(phys, rm.stride) + lane_off;   // < 2^32 (checked on the host)
+      vmask |= valid ? (1u << i) : 0u;
     }
-    // partial scores, then all-reduce over the mirror pair (stage 1 of the butterfly)
+    uint4 kraw[8], vraw[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) kraw[i] = ld16(rm.kbase + off[i]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vraw[i] = ld16(rm.vbase + off[i]);
+
+    // ---- scores: partial dot products, all-reduce over the mirror pair, then reduce-scatter ----
     float v[8][G];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -210,7 +250,6 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
         v[i][g] = s + dpp_mov<0x140>(s);                 // row_mirror: lanes sub and 15 - sub
       }
     }
-    // reduce-scatter: after the three stages lane sub holds row i = sub & 7, summed over all 16 lanes
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -227,34 +266,39 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
         v[i][g] = keep + dpp_mov<0x4E>(send);            // quad_perm [2,3,0,1]: partner sub ^ 2
       }
     }
-    const bool my_valid = (vmask >> (sub & 7)) & 1u;
-    float p[G];
+    const bool my_valid = (vmask >> (sub & 7)) & 1u;     // lane sub now owns row i = sub & 7 of its group
+    float s[G];
+    bool raise = false;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const float keep = b1 ? v[1][g] : v[0][g], send = b1 ? v[0][g] : v[1][g];
-      float s = (keep + dpp_mov<0xB1>(send)) * scale_log2e;   // quad_perm [1,0,3,2]: partner sub ^ 1
-      s = my_valid ? s : kNeg;
-      float gm = dpp_max<0xB1>(s);
-      gm = dpp_max<0x4E>(gm);
-      gm = dpp_max<0x141>(gm);
-      gm = dpp_max<0x140>(gm);                           // maximum over the row group's 8 rows
-      const float mn = fmaxf(m[g], gm);
-      const float corr = fast_exp2(m[g] - mn);
-      p[g] = my_valid ? fast_exp2(s - mn) : 0.f;
-      l[g] = fmaf(l[g], corr, sub < 8 ? p[g] : 0.f);     // lanes sub >= 8 hold duplicates of rows 0..7
-      m[g] = mn;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+      const float x = (keep + dpp_mov<0xB1>(send)) * scale_log2e;   // quad_perm [1,0,3,2]: partner sub ^ 1
+      s[g] = my_valid ? x : kNeg;
+      raise |= s[g] > m[g] + kRescaleSlack;
     }
-    // weights -> shared memory as bf16, paired by rows (2t, 2t+1): dword [t][g] = (p_2t, p_2t+1)
-    if (sub < 8) {
-      uint16_t* ph = reinterpret_cast<uint16_t*>(pbuf) + (size_t)((sub >> 1) * 8) * 2 + (sub & 1);
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {       // wave-uniform and rare after the first half batch
 #pragma unroll
-      for (int g = 0; g < G; ++g) ph[g * 2] = f32_to_bf16_rne(p[g]);
+      for (int g = 0; g < G; ++g) {
+        const float mn = fmaxf(m[g], max16(s[g]));       // maximum over the row group's rows
+        const float corr = fast_exp2(m[g] - mn);
+        l[g] *= corr;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+        m[g] = mn;
+      }
+    }
+    // ---- weights -> shared memory as bf16 pairs of rows (2t, 2t+1): dword [t][g] ----
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float p = my_valid ? fast_exp2(s[g] - m[g]) : 0.f;
+      l[g] += p;                                         // lanes sub >= 8 hold duplicates; dropped at the end
+      const float pn = dpp_mov<0xB1>(p);                 // weight of the next row (lane sub ^ 1)
+      if ((sub & 9) == 0) pbuf[(sub >> 1) * 8 + g] = pack_bf16(p, pn);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- weighted sum of V: two rows per packed dot product ----
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       uint32_t pp[8];
@@ -285,7 +329,7 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
   float* mine = smem + (size_t)(wv * 4 + grp) * G * kPartStride;
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const float lt = sum16(l[g]);
+    const float lt = sum16(sub < 8 ? l[g] : 0.f);
     if (sub == 0) { mine[g * kPartStride + 0] = m[g]; mine[g * kPartStride + 1] = lt; }
     float4* dst = reinterpret_cast<float4*>(mine + g * kPartStride + 4 + sub * 8);
     dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
@@ -296,84 +340,90 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
     const int g = idx >> 7, dd = idx & (kD - 1);
     float mm = kNeg;
 #pragma unroll
-    for (int s = 0; s < kStreams; ++s) mm = fmaxf(mm, smem[(s * G + g) * kPartStride]);
+    for (int st = 0; st < kStreams; ++st) mm = fmaxf(mm, smem[(st * G + g) * kPartStride]);
     float ll = 0.f, oo = 0.f;
 #pragma unroll
-    for (int s = 0; s < kStreams; ++s) {
-      const float c = fast_exp2(smem[(s * G + g) * kPartStride] - mm);
-      ll = fmaf(smem[(s * G + g) * kPartStride + 1], c, ll);
-      oo = fmaf(smem[(s * G + g) * kPartStride + 4 + dd], c, oo);
+    for (int st = 0; st < kStreams; ++st) {
+      const float c = fast_exp2(smem[(st * G + g) * kPartStride] - mm);
+      ll = fmaf(smem[(st * G + g) * kPartStride + 1], c, ll);
+      oo = fmaf(smem[(st * G + g) * kPartStride + 4 + dd], c, oo);
     }
     part[g * kPartStride + 4 + dd] = oo;
     if (dd == 0) { part[g * kPartStride] = mm; part[g * kPartStride + 1] = ll; }
   }
 }
 
+constexpr int kNhbBf16 = kTileBf16 / 128;
 template <typename T, int G> constexpr size_t attn_smem_bytes() {
-  if constexpr (sizeof(T) == 2) return attn_bf16_smem_bytes<G>() + 16;
-  else return (size_t)4 * G * kPartStride * sizeof(float) + 16;
+  if constexpr (sizeof(T) == 2) return attn_bf16_smem_bytes<G>();
+  else return (size_t)4 * G * kPartStride * sizeof(float);
 }
 template <typename T> __device__ __forceinline__ constexpr int tile_of() { return sizeof(T) == 2 ? kTileBf16 : kTileF32; }
 
 template <typename T, int G>
 __device__ __forceinline__ void run_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
                                          float* __restrict__ part, float* smem) {
-  if constexpr (sizeof(T) == 2) attn_tile_bf16<G>(rm, q, scale_log2e, row0, part, smem);
-  else attn_tile<T, G>(rm, q, scale_log2e, row0, part, smem);
+  if constexpr (sizeof(T) == 2) {
+    if (rm.dynamic) attn_tile_bf16<G, kNhbBf16, true>(rm, q, scale_log2e, row0, part, smem);
+    else attn_tile_bf16<G, kNhbBf16, false>(rm, q, scale_log2e, row0, part, smem);
+  } else {
+    attn_tile<T, G>(rm, q, scale_log2e, row0, part, smem);
+  }
 }
 
-// After a block has written its record: count it; the block that completes the unit combines all
-// n_tiles records in tile order (so the result does not depend on which block that is), writes the
-// G output rows and re-arms the counter.  Returns true in the combining block.
+// Combine the n_tiles records of one (unit, query head) in tile order -- eight records per round
+// of independent loads -- and write the output row.  blockDim.x == 128, one thread per element.
 template <typename T>
-__device__ __forceinline__ bool finish_unit(const float* __restrict__ unit_parts, int n_tiles, int G, int32_t* counter,
-                                            T* __restrict__ out_rows, int* flag) {
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int old = n_tiles > 1 ? atomicAdd(counter, 1) : 0;
-    *flag = (old == n_tiles - 1) ? 1 : 0;
-  }
-  __syncthreads();
-  if (!*flag) return false;
-  __threadfence();
-  const int rec = G * kPartStride;
-  for (int idx = threadIdx.x; idx < G * kD; idx += blockDim.x) {
-    const int g = idx >> 7, dd = idx & (kD - 1);
-    const float* p0 = unit_parts + g * kPartStride;
-    float mm = kNeg;
-    for (int t = 0; t < n_tiles; ++t) mm = fmaxf(mm, __builtin_nontemporal_load(p0 + (size_t)t * rec));
-    float ll = 0.f, oo = 0.f;
-    for (int t = 0; t < n_tiles; ++t) {
-      const float* p = p0 + (size_t)t * rec;
-      const float c = fast_exp2(__builtin_nontemporal_load(p) - mm);
-      ll = fmaf(__builtin_nontemporal_load(p + 1), c, ll);
-      oo = fmaf(__builtin_nontemporal_load(p + 4 + dd), c, oo);
+__device__ __forceinline__ void merge_head(const float* __restrict__ p0, int n_tiles, int rec, T* __restrict__ out_row) {
+  const int dd = threadIdx.x;
+  float M = kNeg, L = 0.f, O = 0.f;
+  for (int t0 = 0; t0 < n_tiles; t0 += 8) {
+    float mv[8], lv[8], ov[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool in = t0 + j < n_tiles;
+      const float* p = p0 + (size_t)(in ? t0 + j : t0) * rec;
+      mv[j] = in ? p[0] : kNeg; lv[j] = in ? p[1] : 0.f; ov[j] = in ? p[4 + dd] : 0.f;
     }
-    const float o = ll > 0.f ? oo / ll : 0.f;
-    if constexpr (sizeof(T) == 4) reinterpret_cast<float*>(out_rows)[idx] = o;
-    else reinterpret_cast<uint16_t*>(out_rows)[idx] = f32_to_bf16_rne(o);
+    float bm = mv[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) bm = fmaxf(bm, mv[j]);
+    const float Mn = fmaxf(M, bm);
+    const float c = fast_exp2(M - Mn);
+    L *= c; O *= c;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float cj = fast_exp2(mv[j] - Mn);
+      L = fmaf(lv[j], cj, L);
+      O = fmaf(ov[j], cj, O);
+    }
+    M = Mn;
   }
-  if (threadIdx.x == 0 && n_tiles > 1) *counter = 0;
-  return true;
+  const float o = L > 0.f ? O / L : 0.f;
+  if constexpr (sizeof(T) == 4) reinterpret_cast<float*>(out_row)[dd] = o;
+  else reinterpret_cast<uint16_t*>(out_row)[dd] = f32_to_bf16_rne(o);
 }
 
 // ------------------------------------------------------------------------------------------
 // hybrid cache kernels
 // ------------------------------------------------------------------------------------------
+// grid = units of the call (layer-major), block = 256 threads.  t_arg >= 0: the tail length before
+// this step, known to the host; t_arg < 0: read it from the device counter.
 template <typename T>
 __global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_begin, int unit_begin,
                                                       const T* __restrict__ q, const T* __restrict__ k_new,
                                                       const T* __restrict__ v_new, int use_stored_sigma,
-                                                      int do_step) {
-  extern __shared__ float dsm[];
-  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow;
+                                                      int do_step, int t_arg) {
+  extern __shared__ __attribute__((aligned(16))) float dsm[];
+  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = 256 / LPR;
   const int tid = threadIdx.x;
-  const UnitDesc d = cv.units[unit_begin + blockIdx.x];
-  const int lrel = d.layer - layer_begin;
+  const int u = unit_begin + blockIdx.x;
+  const int layer = u / (cv.batch * cv.n_kv_heads);
+  const UnitDesc d = cv.units[u];
+  const int lrel = layer - layer_begin;
 
   if (do_step) {
-    const int t = cv.cnt_a[d.layer];
+    const int t = t_arg >= 0 ? t_arg : cv.cnt_a[layer];
     const bool append = (k_new != nullptr) && (t < cv.max_new);
     if (append && tid < 2 * LPR) {
       const int which = tid / LPR, sub = tid % LPR;
@@ -383,54 +433,81 @@ __global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_be
       if (which == 0) st16(reinterpret_cast<char*>(cv.k_rows) + dst, ld16(reinterpret_cast<const char*>(k_new) + src));
       else st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v_new) + src));
     }
-    if (d.seq == 0 && d.head == 0 && tid == 0) cv.cnt_b[d.layer] = t + (append ? 1 : 0);
+    if (d.seq == 0 && d.head == 0 && tid == 0) cv.cnt_b[layer] = t + (append ? 1 : 0);
   }
   if (d.kind != HKV_DYNAMIC) return;
 
-  float* qsum = dsm;                                         // [128]
-  uint32_t* hist = reinterpret_cast<uint32_t*>(dsm + kD);    // [256]
+  uint32_t* hist = reinterpret_cast<uint32_t*>(dsm);         // [256]
   uint32_t* bc = hist + 256;                                 // [2]
   int* scan = reinterpret_cast<int*>(bc + 2);                // [6]
-  float* sig = dsm + kD + 256 + 8;                           // [n_chunks]
+  float* sig = dsm + 256 + 8;                                // [n_chunks rounded up to 4]
   const int n_c = d.n_chunks;
+  const int n_c4 = (n_c + 3) & ~3;
 
   if (!use_stored_sigma) {
-    if (tid < kD) {
-      const T* qp = q + (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * cv.G) * kD + tid;
-      float s = 0.f;
-      for (int g = 0; g < cv.G; ++g) {
-        float x;
-        if constexpr (sizeof(T) == 4) x = reinterpret_cast<const float*>(qp)[(size_t)g * kD];
-        else x = bits_to_float((uint32_t)reinterpret_cast<const uint16_t*>(qp)[(size_t)g * kD] << 16);
-        s += x;
-      }
-      qsum[tid] = s;
-    }
-    __syncthreads();
+    // group-summed query for this lane's 16-byte slice, summed in head order
     const int sub = tid % LPR, slot = tid / LPR;
-    constexpr int RP = 256 / LPR;
     float qf[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qf[e] = qsum[sub * EPL + e];
-    const char* mu = reinterpret_cast<const char*>(cv.mu) + (size_t)d.aux_off * kD * sizeof(T);
-    for (int ch0 = 0; ch0 < n_c; ch0 += RP) {       // uniform trip count
-      const int ch = ch0 + slot;
-      float dot = 0.f;
-      if (ch < n_c) {
+    for (int e = 0; e < EPL; ++e) qf[e] = 0.f;
+    const char* qb = reinterpret_cast<const char*>(q) +
+                     (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * cv.G) * kD * sizeof(T) + sub * 16;
+    uint4 qraw[kMaxG];
+#pragma unroll
+    for (int g = 0; g < kMaxG; ++g) qraw[g] = g < cv.G ? ld16(qb + (size_t)g * kD * sizeof(T)) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int g = 0; g < kMaxG; ++g) {
+      float t[EPL];
+      unpack16(qraw[g], t, T{});
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qf[e] += t[e];
+    }
+    const char* mu = reinterpret_cast<const char*>(cv.mu) + (size_t)d.aux_off * kD * sizeof(T) + sub * 16;
+    for (int ch0 = 0; ch0 < n_c; ch0 += RP * 8) {       // uniform trip count; eight independent loads per round
+      uint4 raw[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int ch = ch0 + j * RP + slot;
+        raw[j] = ld16(mu + (size_t)min(ch, n_c - 1) * kD * sizeof(T));
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int ch = ch0 + j * RP + slot;
         float mf[EPL];
-        unpack16(ld16(mu + (size_t)ch * kD * sizeof(T) + sub * 16), mf, T{});
+        unpack16(raw[j], mf, T{});
+        float dot = 0.f;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) dot = fmaf(qf[e], mf[e], dot);
+        dot = sum_lanes<LPR>(dot);
+        if (ch < n_c && sub == 0) { sig[ch] = dot; cv.sigma[d.aux_off + ch] = dot; }
       }
-      dot = sum_lanes<LPR>(dot);
-      if (ch < n_c && sub == 0) { sig[ch] = dot; cv.sigma[d.aux_off + ch] = dot; }
     }
   } else {
     for (int ch = tid; ch < n_c; ch += 256) sig[ch] = cv.sigma[d.aux_off + ch];
   }
+  if (tid < n_c4 - n_c) sig[n_c + tid] = -__builtin_inff();   // padding never outranks a real chunk
   __syncthreads();
 
-  // top-k chunks, ties to the lower chunk id, emitted ascending
+  // top-k chunks, ties to the lower chunk id, emitted ascending by chunk id
+  if (n_c <= 256) {
+    // rank by counting: chunk i is picked iff fewer than k chunks beat it (greater score, or an
+    // equal score at a lower id)
+    const int i = tid;
+    const float si = i < n_c ? sig[i] : 0.f;
+    int rank = 0;
+    for (int j = 0; j < n_c4; j += 4) {
+      const float4 sj = *reinterpret_cast<const float4*>(sig + j);
+      rank += (sj.x > si || (sj.x == si && j + 0 < i)) ? 1 : 0;
+      rank += (sj.y > si || (sj.y == si && j + 1 < i)) ? 1 : 0;
+      rank += (sj.z > si || (sj.z == si && j + 2 < i)) ? 1 : 0;
+      rank += (sj.w > si || (sj.w == si && j + 3 < i)) ? 1 : 0;
+    }
+    const int keep = (i < n_c && rank < d.k_sel) ? 1 : 0;
+    int tot;
+    const int pos = block_exclusive_scan<256>(keep, scan, &tot);
+    if (keep) cv.sel[d.idx_off + pos] = i;
+    return;
+  }
   uint32_t T_key = 0;
   int r_adm = n_c;
   if (d.k_sel < n_c) {
@@ -458,37 +535,44 @@ __global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_be
 
 template <typename T, int G>
 __global__ __launch_bounds__(256) void attn_kernel(CacheView cv, int layer_begin, int item_begin,
-                                                   const T* __restrict__ q, float* __restrict__ partials,
-                                                   T* __restrict__ out) {
+                                                   const T* __restrict__ q, float* __restrict__ partials, int t_arg) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   constexpr int TILE = tile_of<T>();
-  const int2 item = cv.items[item_begin + blockIdx.x];
-  const UnitDesc d = cv.units[item.x];
-  const int t = cv.cnt_b[d.layer];
+  const AttnItem it = cv.items[item_begin + blockIdx.x];
+  const int t = t_arg >= 0 ? min(t_arg, cv.max_new) : cv.cnt_b[it.layer];
   RowMap rm;
-  rm.n_rows = d.n_prompt_rows + t;
-  const int row0 = item.y * TILE;
-  if (row0 >= rm.n_rows) return;          // tile reserved for tail growth, not reached yet
-  rm.kbase = reinterpret_cast<const char*>(cv.k_rows) + (size_t)d.kv_row_off * kD * sizeof(T);
-  rm.vbase = reinterpret_cast<const char*>(cv.v_rows) + (size_t)d.kv_row_off * kD * sizeof(T);
+  rm.n_rows = it.n_prompt_rows + t;
+  if (it.row0 >= rm.n_rows) return;          // tile reserved for tail growth, not reached yet
+  rm.kbase = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
+  rm.vbase = reinterpret_cast<const char*>(cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.stride = kD * sizeof(T);
-  rm.dynamic = d.kind == HKV_DYNAMIC;
-  rm.sel = cv.sel + d.idx_off;
-  rm.n_sel_rows = d.n_prompt_rows;
-  rm.c_log2 = d.c_log2;
-  rm.C = d.C;
-  const int lrel = d.layer - layer_begin;
-  const size_t qoff = (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G) * kD;
+  rm.dynamic = it.dynamic;
+  rm.sel = cv.sel + it.sel_off;
+  rm.n_sel_rows = it.n_prompt_rows;
+  rm.c_log2 = it.c_log2;
+  rm.C = it.C;
+  const size_t qoff = (size_t)it.q_off - (size_t)layer_begin * cv.batch * cv.n_q_heads * kD;
   float* part = partials + (size_t)blockIdx.x * G * kPartStride;
-  run_tile<T, G>(rm, q + qoff, cv.scale_log2e, row0, part, smem);
+  run_tile<T, G>(rm, q + qoff, cv.scale_log2e, it.row0, part, smem);
+}
 
-  const int n_tiles = (rm.n_rows + TILE - 1) / TILE;
-  int* flag = reinterpret_cast<int*>(smem + attn_smem_bytes<T, G>() / sizeof(float) - 4);
-  const float* unit_parts = partials + (size_t)(d.item_begin - item_begin) * G * kPartStride;
-  if (finish_unit<T>(unit_parts, n_tiles, G, cv.done + item.x, out + qoff, flag)) {
-    // the step is complete for this unit; one unit per layer moves the tail counter on
-    if (d.seq == 0 && d.head == 0 && threadIdx.x == 0) cv.cnt_a[d.layer] = t;
-  }
+// grid = (units of the call) x G, block = 128 threads.
+template <typename T>
+__global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, int layer_begin, int unit_begin,
+                                                         int item_base, const float* __restrict__ partials,
+                                                         T* __restrict__ out, int t_arg) {
+  const int G = cv.G;
+  const int u = unit_begin + blockIdx.x / G, g = blockIdx.x % G;
+  const int layer = u / (cv.batch * cv.n_kv_heads);
+  const int t = t_arg >= 0 ? min(t_arg, cv.max_new) : cv.cnt_b[layer];
+  const UnitDesc d = cv.units[u];
+  constexpr int TILE = tile_of<T>();
+  const int n_tiles = (d.n_prompt_rows + t + TILE - 1) / TILE;
+  const int lrel = layer - layer_begin;
+  const float* p0 = partials + ((size_t)(d.item_begin - item_base) * G + g) * kPartStride;
+  T* orow = out + (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G + g) * kD;
+  merge_head<T>(p0, n_tiles, G * kPartStride, orow);
+  if (g == 0 && d.seq == 0 && d.head == 0 && threadIdx.x == 0) cv.cnt_a[layer] = t;
 }
 
 __global__ void rewind_kernel(CacheView cv, int layer_begin, int layer_end) {
@@ -497,17 +581,12 @@ __global__ void rewind_kernel(CacheView cv, int layer_begin, int layer_end) {
 }
 
 // ------------------------------------------------------------------------------------------
-// full-KV comparison kernel: same tile code and the same fused combination, rows read in place
+// full-KV comparison kernels: same tile and combination code, rows read in place
 // ------------------------------------------------------------------------------------------
-__global__ void zero_kernel(int32_t* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
-}
-
 template <typename T, int G>
 __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __restrict__ q,
                                                         const T* __restrict__ k, const T* __restrict__ v,
-                                                        float* __restrict__ partials, T* __restrict__ out) {
+                                                        float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   constexpr int TILE = tile_of<T>();
   const int unit = blockIdx.y;                       // (lrel * batch + b) * Hkv + h
@@ -521,14 +600,27 @@ __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __
   const size_t off = (((size_t)lrel * fv.total_tokens + fv.cu[b]) * fv.n_kv_heads + h) * kD * sizeof(T);
   rm.kbase = reinterpret_cast<const char*>(k) + off;
   rm.vbase = reinterpret_cast<const char*>(v) + off;
-  rm.stride = (int64_t)fv.n_kv_heads * kD * sizeof(T);
+  rm.stride = (uint32_t)fv.n_kv_heads * kD * sizeof(T);
   rm.dynamic = 0; rm.sel = nullptr; rm.n_sel_rows = 0; rm.c_log2 = 0; rm.C = rm.n_rows;
   const size_t qoff = (((size_t)lrel * fv.batch + b) * fv.n_q_heads + (size_t)h * G) * kD;
-  float* unit_parts = partials + (size_t)unit * fv.n_tiles_max * G * kPartStride;
-  run_tile<T, G>(rm, q + qoff, fv.scale_log2e, row0, unit_parts + (size_t)blockIdx.x * G * kPartStride, smem);
-  const int n_tiles = (rm.n_rows + TILE - 1) / TILE;
-  int* flag = reinterpret_cast<int*>(smem + attn_smem_bytes<T, G>() / sizeof(float) - 4);
-  finish_unit<T>(unit_parts, n_tiles, G, fv.done + unit, out + qoff, flag);
+  float* part = partials + ((size_t)unit * fv.n_tiles_max + blockIdx.x) * G * kPartStride;
+  run_tile<T, G>(rm, q + qoff, fv.scale_log2e, row0, part, smem);
+}
+
+template <typename T>
+__global__ __launch_bounds__(128) void full_merge_kernel(FullView fv, const float* __restrict__ partials,
+                                                         T* __restrict__ out) {
+  const int G = fv.G;
+  const int unit = blockIdx.x / G, g = blockIdx.x % G;
+  const int h = unit % fv.n_kv_heads;
+  const int b = (unit / fv.n_kv_heads) % fv.batch;
+  const int lrel = unit / (fv.n_kv_heads * fv.batch);
+  const int n_rows = fv.cu[b + 1] - fv.cu[b];
+  constexpr int TILE = tile_of<T>();
+  const int n_tiles = (n_rows + TILE - 1) / TILE;
+  const float* p0 = partials + (((size_t)unit * fv.n_tiles_max) * G + g) * kPartStride;
+  T* orow = out + (((size_t)lrel * fv.batch + b) * fv.n_q_heads + (size_t)h * G + g) * kD;
+  merge_head<T>(p0, n_tiles, G * kPartStride, orow);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -548,24 +640,24 @@ __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __
   }
 
 hipError_t launch_prepare(const CacheView& cv, int dtype, int layer_begin, int layer_end, const void* q,
-                          const void* k_new, const void* v_new, int use_stored_sigma, int do_step,
+                          const void* k_new, const void* v_new, int use_stored_sigma, int do_step, int t_arg,
                           int max_chunks, hipStream_t st) {
   const int upl = cv.batch * cv.n_kv_heads;
   const int n_units = (layer_end - layer_begin) * upl;
   if (n_units <= 0) return hipSuccess;
-  const size_t smem = (size_t)(kD + 256 + 8 + max_chunks) * sizeof(float);
+  const size_t smem = (size_t)(256 + 8 + max_chunks + 4) * sizeof(float);
   if (dtype == HKV_F32)
     hipLaunchKernelGGL(prepare_kernel<float>, dim3(n_units), dim3(256), smem, st, cv, layer_begin, layer_begin * upl,
-                       (const float*)q, (const float*)k_new, (const float*)v_new, use_stored_sigma, do_step);
+                       (const float*)q, (const float*)k_new, (const float*)v_new, use_stored_sigma, do_step, t_arg);
   else
     hipLaunchKernelGGL(prepare_kernel<bf16_t>, dim3(n_units), dim3(256), smem, st, cv, layer_begin, layer_begin * upl,
-                       (const bf16_t*)q, (const bf16_t*)k_new, (const bf16_t*)v_new, use_stored_sigma, do_step);
+                       (const bf16_t*)q, (const bf16_t*)k_new, (const bf16_t*)v_new, use_stored_sigma, do_step, t_arg);
   return hipGetLastError();
 }
 
 template <typename T, int G>
 static hipError_t launch_attn_t(const CacheView& cv, int layer_begin, int item_begin, int n_items, const void* q,
-                                float* partials, void* out, hipStream_t st) {
+                                float* partials, int t_arg, hipStream_t st) {
   constexpr size_t smem = attn_smem_bytes<T, G>();
   static bool attr_set = false;     // per instantiation; the attribute is sticky for the process
   if (!attr_set) {
@@ -575,19 +667,33 @@ static hipError_t launch_attn_t(const CacheView& cv, int layer_begin, int item_b
     attr_set = true;
   }
   hipLaunchKernelGGL((attn_kernel<T, G>), dim3(n_items), dim3(256), smem, st, cv, layer_begin, item_begin,
-                     (const T*)q, partials, (T*)out);
+                     (const T*)q, partials, t_arg);
   return hipGetLastError();
 }
 
 hipError_t launch_attn(const CacheView& cv, int dtype, int layer_begin, int item_begin, int n_items, const void* q,
-                       float* partials, void* out, hipStream_t st) {
+                       float* partials, int t_arg, hipStream_t st) {
   if (n_items <= 0) return hipSuccess;
   if (dtype == HKV_F32) {
-    HKV_DISPATCH_G(cv.G, return (launch_attn_t<float, GG>(cv, layer_begin, item_begin, n_items, q, partials, out, st)));
+    HKV_DISPATCH_G(cv.G, return (launch_attn_t<float, GG>(cv, layer_begin, item_begin, n_items, q, partials, t_arg, st)));
   } else {
-    HKV_DISPATCH_G(cv.G, return (launch_attn_t<bf16_t, GG>(cv, layer_begin, item_begin, n_items, q, partials, out, st)));
+    HKV_DISPATCH_G(cv.G, return (launch_attn_t<bf16_t, GG>(cv, layer_begin, item_begin, n_items, q, partials, t_arg, st)));
   }
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int item_base,
+                             const float* partials, void* out, int t_arg, hipStream_t st) {
+  const int upl = cv.batch * cv.n_kv_heads;
+  const int n_blocks = (layer_end - layer_begin) * upl * cv.G;
+  if (n_blocks <= 0) return hipSuccess;
+  if (dtype == HKV_F32)
+    hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0, st, cv, layer_begin, layer_begin * upl,
+                       item_base, partials, (float*)out, t_arg);
+  else
+    hipLaunchKernelGGL(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0, st, cv, layer_begin,
+                       layer_begin * upl, item_base, partials, (bf16_t*)out, t_arg);
+  return hipGetLastError();
 }
 
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st) {
@@ -609,9 +715,9 @@ static hipError_t launch_full_t(const FullView& fv, const void* q, const void* k
     attr_set = true;
   }
   const int n_units = fv.n_layers_call * fv.batch * fv.n_kv_heads;
-  hipLaunchKernelGGL(zero_kernel, dim3((n_units + 255) / 256), dim3(256), 0, st, fv.done, n_units);
   hipLaunchKernelGGL((full_attn_kernel<T, G>), dim3(fv.n_tiles_max, n_units), dim3(256), smem, st, fv, (const T*)q,
-                     (const T*)k, (const T*)v, partials, (T*)out);
+                     (const T*)k, (const T*)v, partials);
+  hipLaunchKernelGGL(full_merge_kernel<T>, dim3(n_units * G), dim3(128), 0, st, fv, (const float*)partials, (T*)out);
   return hipGetLastError();
 }
 

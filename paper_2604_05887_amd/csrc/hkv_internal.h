@@ -43,15 +43,28 @@ struct UnitDesc {
   int32_t type_ord;     // ordinal among the static (or dynamic) units, layer-major
 };
 
+// One split-K tile of decode attention: everything the attention kernel needs, in one record.
+struct AttnItem {
+  int64_t kv_row_off;   // first row of the unit in the cache K / V row arrays
+  int64_t q_off;        // element offset of the unit's first query row in a [n_layers][batch][Hq][128] tensor
+  int32_t sel_off;      // dynamic: offset into sel[]
+  int32_t n_prompt_rows;
+  int32_t row0;         // first logical row of the tile
+  int32_t C;
+  int32_t c_log2;
+  int32_t dynamic;
+  int32_t layer;
+  int32_t unit;
+};
+
 struct CacheView {
   const UnitDesc* units;
-  const int2* items;          // (unit, tile)
+  const AttnItem* items;
   const int32_t* static_units;
   const int32_t* dynamic_units;
   const uint8_t* is_visual;
   int32_t* cnt_a;             // [n_layers] tail length before the step in flight
   int32_t* cnt_b;             // [n_layers] tail length the step in flight attends
-  int32_t* done;              // [n_units] split-K tiles finished in the step in flight (self-resetting)
   int32_t* kept_idx;
   int32_t* sel;
   float* scores;
@@ -65,11 +78,15 @@ struct CacheView {
 
 // ---- launchers implemented in the kernel translation units (all asynchronous on `st`) ----
 // decode
+// t_arg: tail length known to the host (prepare: before the step; attention and merge: the length
+// the step attends), or -1 to read the device counters instead.
 hipError_t launch_prepare(const CacheView& cv, int dtype, int layer_begin, int layer_end, const void* q,
-                          const void* k_new, const void* v_new, int use_stored_sigma, int do_scoring,
+                          const void* k_new, const void* v_new, int use_stored_sigma, int do_step, int t_arg,
                           int max_chunks, hipStream_t st);
 hipError_t launch_attn(const CacheView& cv, int dtype, int layer_begin, int item_begin, int n_items,
-                       const void* q, float* partials, void* out, hipStream_t st);
+                       const void* q, float* partials, int t_arg, hipStream_t st);
+hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int item_base,
+                             const float* partials, void* out, int t_arg, hipStream_t st);
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
 
 struct FullView {
@@ -77,7 +94,6 @@ struct FullView {
   int32_t batch, n_layers_call, n_q_heads, n_kv_heads, G, n_tiles_max;
   int64_t total_tokens;
   float scale_log2e;
-  int32_t* done;              // [units] tile counters inside the workspace (zeroed by the launcher)
 };
 hipError_t launch_full_attn(const FullView& fv, int dtype, const void* q, const void* k, const void* v,
                             float* partials, void* out, hipStream_t st);
