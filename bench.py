@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--budget-frac", type=float, default=None)
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-kv", action="store_true", help="skip the full-KV comparison kernel")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain device copies of a known size (for scaling HBM byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -76,6 +79,19 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        # 10 copies of 256 MiB: each dispatch reads 268435456 B and writes 268435456 B
+        n = 256 << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(7)
+        dst = torch.empty(n, dtype=torch.uint8, device=dev)
+        scrub = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        for _ in range(10):
+            scrub.fill_(1)            # push src/dst out of the memory-side cache
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "copies": 10}), flush=True)
+        return 0
 
     K, W = args.steps, args.warmup
     n_inputs = min(max(K, 16), 128)
@@ -188,15 +204,15 @@ def main() -> int:
         if st != 0:
             raise B.HkvError(st, "hkv_full_decode_attn")
 
-    n_full = max(8, min(K, 32))
-    for i in range(4):
+    n_full = 0 if args.no_full_kv else max(8, min(K, 32))
+    for i in range(4 if n_full else 0):
         full_step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(n_full):
         full_step(i)
     torch.cuda.synchronize()
-    full_ms = (time.perf_counter() - t0) * 1e3 / n_full
+    full_ms = (time.perf_counter() - t0) * 1e3 / n_full if n_full else float("nan")
     full_bytes = 2 * R * int(wl.cu_seqlens[-1]) * Hkv * L
     full_gbs = full_bytes / (full_ms * 1e-3) / 1e9
 
