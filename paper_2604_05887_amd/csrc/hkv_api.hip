@@ -60,6 +60,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
   const int B = plan->batch, L = cfg->n_layers, H = cfg->n_kv_heads, w = cfg->window;
   const int G = cfg->n_q_heads / H;
   const int tile = tile_rows(cfg->dtype);
+  const bool blocked = cfg->dtype == HKV_BF16;
   if (plan->cu_seqlens[0] != 0) return HKV_EINVAL;
   lo.cu.assign(plan->cu_seqlens, plan->cu_seqlens + B + 1);
   std::vector<int32_t> n_txt(B), n_vis(B), csz(B);
@@ -114,6 +115,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
           lo.static_units.push_back(u);
           lo.max_rows_static = std::max(lo.max_rows_static, d.n_prompt_rows);
           phys_rows = d.n_prompt_rows;
+          d.tail_row = d.n_prompt_rows;
         } else {
           const int c = csz[b];
           int lg = 0; while ((1 << lg) < c) ++lg;
@@ -126,9 +128,14 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
           d.type_ord = (int32_t)lo.dynamic_units.size();
           lo.dynamic_units.push_back(u);
           lo.max_chunks = std::max(lo.max_chunks, d.n_chunks);
-          phys_rows = C;
+          if (blocked && c < kBlkRows) return HKV_ESHAPE;     // bf16 caches gather whole 8-row blocks
+          phys_rows = blocked ? (C + kBlkRows - 1) / kBlkRows * kBlkRows : C;
+          d.tail_row = (int32_t)phys_rows;
         }
-        lo.n_rows += phys_rows + cfg->max_new_tokens;
+        {
+          const int64_t cap = phys_rows + cfg->max_new_tokens;
+          lo.n_rows += blocked ? (cap + kBlkRows - 1) / kBlkRows * kBlkRows : cap;
+        }
         d.item_begin = (int32_t)lo.items.size();
         d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + tile - 1) / tile);
         if ((int64_t)C + cfg->max_new_tokens >= (1 << 24)) return HKV_ESHAPE;   // 24-bit row arithmetic in the kernels
@@ -144,7 +151,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
           it.c_log2 = d.c_log2;
           it.dynamic = ht == HKV_DYNAMIC;
           it.layer = l;
-          it.unit = u;
+          it.tail_row = d.tail_row;
           lo.items.push_back(it);
         }
         if (lo.items.size() > (size_t)0x7fffff00) return HKV_ESHAPE;
@@ -272,6 +279,9 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   up(lo.off_dynamic, lo.dynamic_units.data(), lo.dynamic_units.size() * 4);
   up(lo.off_vis, plan->is_visual, (size_t)lo.total_tokens);
   if (e == hipSuccess) e = hipMemset(a + lo.off_cnt, 0, (size_t)2 * cfg->n_layers * 4);
+  // rows that are allocated but not (yet) written must hold finite values: masked rows still enter the
+  // weighted sum with weight zero
+  if (e == hipSuccess) e = hipMemset(a + lo.off_k, 0, lo.arena_bytes - lo.off_k);
   if (e != hipSuccess) { delete c; return HKV_EHIP; }
   *out = c;
   return HKV_OK;
@@ -349,7 +359,7 @@ static int compress_impl(hkv_cache* c, int lb, int le, const void* q_window, con
   }
   if (e == hipSuccess) e = launch_select(c->cv, sb, ns, st);
   if (e == hipSuccess) e = launch_compact(c->cv, c->cfg.dtype, lb, sb, ns, lo.max_rows_static, k, v, lo.total_tokens, st);
-  if (e == hipSuccess) e = launch_adopt(c->cv, c->cfg.dtype, lb, db, nd, lo.max_chunks, k, v, lo.total_tokens, st);
+  if (e == hipSuccess) e = launch_adopt(c->cv, c->cfg.dtype, lb, db, nd, lo.max_chunks, lo.max_C, k, v, lo.total_tokens, st);
   if (e == hipSuccess) e = launch_rewind(c->cv, lb, le, st);
   if (e != hipSuccess) return HKV_EHIP;
   for (int l = lb; l < le; ++l) { c->compressed[l] = 1; c->host_tail[l] = 0; }
@@ -545,7 +555,7 @@ static int locate(const hkv_cache* c, int what, const UnitDesc* d, size_t& off, 
     case HKV_X_V_ROWS: {
       const size_t rows = (size_t)(d->kind == HKV_STATIC ? d->n_prompt_rows : d->C) + tail;
       off = (what == HKV_X_K_ROWS ? lo.off_k : lo.off_v) + (size_t)d->kv_row_off * kD * es;
-      bytes = rows * kD * es; return HKV_OK;
+      bytes = rows * kD * es; return HKV_OK;     // logical size; blocked caches are unpacked by the caller
     }
     default: return HKV_EINVAL;
   }
@@ -561,6 +571,26 @@ int hkv_cache_export(const hkv_cache* c, int what, int seq, int layer, int head,
   if (written) *written = need;
   if (!dst || bytes < need) return HKV_ENOSPACE;
   if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return HKV_EHIP;
+  if ((what == HKV_X_K_ROWS || what == HKV_X_V_ROWS) && c->cfg.dtype == HKV_BF16) {
+    // blocked layout -> plain rows: prompt rows, then the tail rows
+    const int tail = c->host_tail[d->layer];
+    const int n_prompt = d->kind == HKV_STATIC ? d->n_prompt_rows : d->C;
+    const size_t phys_rows = (size_t)d->tail_row + tail;
+    const size_t n_blk = (phys_rows + kBlkRows - 1) / kBlkRows;
+    std::vector<uint16_t> raw(n_blk * kBlkRows * kD);
+    if (n_blk && hipMemcpy(raw.data(), c->arena + off, n_blk * kBlkBytes, hipMemcpyDeviceToHost) != hipSuccess)
+      return HKV_EHIP;
+    uint16_t* out = static_cast<uint16_t*>(dst);
+    for (int r = 0; r < n_prompt + tail; ++r) {
+      const size_t pr = r < n_prompt ? (size_t)r : (size_t)d->tail_row + (r - n_prompt);
+      const uint16_t* blk = raw.data() + (pr / kBlkRows) * (kBlkRows * kD);
+      const int e = (int)(pr % kBlkRows);
+      for (int dd = 0; dd < kD; ++dd)
+        out[(size_t)r * kD + dd] = what == HKV_X_K_ROWS ? blk[k_piece_index(e, dd >> 3) * 8 + (dd & 7)]
+                                                        : blk[dd * 8 + e];
+    }
+    return HKV_OK;
+  }
   if (need && hipMemcpy(dst, c->arena + off, need, hipMemcpyDeviceToHost) != hipSuccess) return HKV_EHIP;
   return HKV_OK;
 }

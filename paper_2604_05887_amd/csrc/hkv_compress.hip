@@ -5,9 +5,12 @@
 //                         G*w window rows -> relevance vector s_w over all prompt tokens
 //   select_kernel         Top-M of s_w over the historical visual tokens (radix select, ties to the
 //                         lower position) + window + historical text -> ascending kept positions
-//   compact_kernel        copy the kept K/V rows into the head's ragged cache segment
-//   adopt_kernel          dynamic heads: copy the whole K/V head-major into the cache and reduce
+//   compact_kernel        fp32: copy the kept K/V rows into the head's ragged cache segment
+//   adopt_kernel          fp32, dynamic heads: copy the whole K/V head-major into the cache and reduce
 //                         every chunk's keys to their mean (the chunk-level index)
+//   pack_rows_kernel      bf16: the same two copies, but into the blocked layout the matrix-core
+//                         decode kernel reads (8-row blocks, V transposed inside a block)
+//   chunk_mean_kernel     bf16, dynamic heads: the chunk means
 #include "hkv_device.h"
 #include "hkv_internal.h"
 #include "hkv_select.h"
@@ -301,6 +304,98 @@ __global__ __launch_bounds__(256) void adopt_kernel(CacheView cv, int layer_begi
   }
 }
 
+// bf16 caches: gather 8 source rows into one K block and one V block of the blocked layout.
+// grid = (groups of 4 blocks, units of the list); block = 256 threads, one wave per 8-row block.
+// STATIC: rows come from kept_idx (compaction); else they are the prompt rows themselves (adoption).
+template <bool STATIC>
+__global__ __launch_bounds__(256) void pack_rows_kernel(CacheView cv, int layer_begin, int list_begin,
+                                                        const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+                                                        int64_t total_tokens) {
+  __shared__ __attribute__((aligned(16))) uint16_t vt[4][kBlkRows][kD + 8];
+  const int32_t* list = STATIC ? cv.static_units : cv.dynamic_units;
+  const UnitDesc d = cv.units[list[list_begin + blockIdx.y]];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int n_src = STATIC ? d.n_prompt_rows : d.C;
+  const int blk = blockIdx.x * 4 + wv;
+  const int n_blk = (n_src + kBlkRows - 1) / kBlkRows;
+  if (blockIdx.x * 4 * kBlkRows >= n_src) return;           // whole workgroup beyond the unit
+  const bool active = blk < n_blk;                          // wave-uniform
+  const int lrel = d.layer - layer_begin;
+  const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * (kD * 2);
+  const size_t sstride = (size_t)cv.n_kv_heads * kD * 2;
+  const int32_t* kept = cv.kept_idx + d.idx_off;
+  char* kdst = reinterpret_cast<char*>(cv.k_rows) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
+  char* vdst = reinterpret_cast<char*>(cv.v_rows) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
+  // each lane moves two 16-byte pieces of K and of V: piece p = lane, lane + 64 -> row e = p / 16, dims 8*(p % 16)
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int p = lane + 64 * h, e = p >> 4, d8 = p & 15;
+    const int r = blk * kBlkRows + e;
+    uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+    if (active && r < n_src) {
+      const int pos = STATIC ? min(max(kept[r], 0), d.C - 1) : r;
+      kk = ld16(reinterpret_cast<const char*>(k) + src0 + (size_t)pos * sstride + d8 * 16);
+      vv = ld16(reinterpret_cast<const char*>(v) + src0 + (size_t)pos * sstride + d8 * 16);
+    }
+    if (active) st16(kdst + k_piece_index(e, d8) * 16, kk);
+    *reinterpret_cast<uint4*>(&vt[wv][e][d8 * 8]) = vv;
+  }
+  __syncthreads();
+  if (!active) return;
+  // transpose V: lane writes the pieces of dims 2*lane and 2*lane + 1 (8 rows each)
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int dd = 2 * lane + h;
+    uint4 o;
+    o.x = (uint32_t)vt[wv][0][dd] | ((uint32_t)vt[wv][1][dd] << 16);
+    o.y = (uint32_t)vt[wv][2][dd] | ((uint32_t)vt[wv][3][dd] << 16);
+    o.z = (uint32_t)vt[wv][4][dd] | ((uint32_t)vt[wv][5][dd] << 16);
+    o.w = (uint32_t)vt[wv][6][dd] | ((uint32_t)vt[wv][7][dd] << 16);
+    st16(vdst + dd * 16, o);
+  }
+}
+
+// Chunk means only (bf16 caches; the rows themselves are moved by pack_rows_kernel).
+// grid = (chunk groups of 4, dynamic units of the call); block = 256 threads, one wave per chunk.
+template <typename T>
+__global__ __launch_bounds__(256) void chunk_mean_kernel(CacheView cv, int layer_begin, int dynamic_begin,
+                                                         const T* __restrict__ k, int64_t total_tokens) {
+  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RPW = 64 / LPR, ROWB = kD * sizeof(T);
+  const UnitDesc d = cv.units[cv.dynamic_units[dynamic_begin + blockIdx.y]];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int ch = blockIdx.x * 4 + wv;
+  if (ch >= d.n_chunks) return;               // wave-uniform
+  const int c = 1 << d.c_log2;
+  const int r_begin = ch * c, r_end = min(r_begin + c, d.C);
+  const int lrel = d.layer - layer_begin;
+  const int sub = lane % LPR, grp = lane / LPR;
+  const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
+  const size_t sstride = (size_t)cv.n_kv_heads * ROWB;
+  float acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  for (int r = r_begin + grp; r < r_begin + c; r += RPW) {     // uniform trip count (c is a multiple of RPW)
+    if (r < r_end) {
+      float kf[EPL];
+      unpack16(ld16(reinterpret_cast<const char*>(k) + src0 + (size_t)r * sstride + sub * 16), kf, T{});
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] += kf[e];
+    }
+  }
+#pragma unroll
+  for (int mask = LPR; mask < 64; mask <<= 1) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] += lane_xor(acc[e], mask);
+  }
+  if (grp == 0) {
+    const float n_rows = (float)(r_end - r_begin);
+    float mf[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) mf[e] = acc[e] / n_rows;
+    st16(reinterpret_cast<char*>(cv.mu) + (size_t)(d.aux_off + ch) * ROWB + sub * 16, pack16(mf, T{}));
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
@@ -347,26 +442,31 @@ hipError_t launch_select(const CacheView& cv, int static_begin, int n_static, hi
 hipError_t launch_compact(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,
                           int max_rows, const void* k, const void* v, int64_t total_tokens, hipStream_t st) {
   if (n_static <= 0 || max_rows <= 0) return hipSuccess;
-  const dim3 grid((max_rows + 63) / 64, n_static);
   if (dtype == HKV_F32)
-    hipLaunchKernelGGL(compact_kernel<float>, grid, dim3(256), 0, st, cv, layer_begin, static_begin, (const float*)k,
-                       (const float*)v, total_tokens);
+    hipLaunchKernelGGL(compact_kernel<float>, dim3((max_rows + 63) / 64, n_static), dim3(256), 0, st, cv, layer_begin,
+                       static_begin, (const float*)k, (const float*)v, total_tokens);
   else
-    hipLaunchKernelGGL(compact_kernel<bf16_t>, grid, dim3(256), 0, st, cv, layer_begin, static_begin,
-                       (const bf16_t*)k, (const bf16_t*)v, total_tokens);
+    hipLaunchKernelGGL(pack_rows_kernel<true>, dim3((max_rows + 4 * kBlkRows - 1) / (4 * kBlkRows), n_static),
+                       dim3(256), 0, st, cv, layer_begin, static_begin, (const bf16_t*)k, (const bf16_t*)v,
+                       total_tokens);
   return hipGetLastError();
 }
 
 hipError_t launch_adopt(const CacheView& cv, int dtype, int layer_begin, int dynamic_begin, int n_dynamic,
-                        int max_chunks, const void* k, const void* v, int64_t total_tokens, hipStream_t st) {
+                        int max_chunks, int max_C, const void* k, const void* v, int64_t total_tokens,
+                        hipStream_t st) {
   if (n_dynamic <= 0 || max_chunks <= 0) return hipSuccess;
   const dim3 grid((max_chunks + 3) / 4, n_dynamic);
-  if (dtype == HKV_F32)
+  if (dtype == HKV_F32) {
     hipLaunchKernelGGL(adopt_kernel<float>, grid, dim3(256), 0, st, cv, layer_begin, dynamic_begin, (const float*)k,
                        (const float*)v, total_tokens);
-  else
-    hipLaunchKernelGGL(adopt_kernel<bf16_t>, grid, dim3(256), 0, st, cv, layer_begin, dynamic_begin,
-                       (const bf16_t*)k, (const bf16_t*)v, total_tokens);
+  } else {
+    hipLaunchKernelGGL(chunk_mean_kernel<bf16_t>, grid, dim3(256), 0, st, cv, layer_begin, dynamic_begin,
+                       (const bf16_t*)k, total_tokens);
+    hipLaunchKernelGGL(pack_rows_kernel<false>, dim3((max_C + 4 * kBlkRows - 1) / (4 * kBlkRows), n_dynamic),
+                       dim3(256), 0, st, cv, layer_begin, dynamic_begin, (const bf16_t*)k, (const bf16_t*)v,
+                       total_tokens);
+  }
   return hipGetLastError();
 }
 

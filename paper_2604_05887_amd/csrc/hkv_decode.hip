@@ -24,7 +24,8 @@ struct RowMap {
   int32_t dynamic;
   int32_t n_sel_rows;    // dynamic: k_sel << c_log2
   int32_t c_log2;
-  int32_t C;             // dynamic: prompt rows (tail starts at physical row C)
+  int32_t C;             // dynamic: prompt rows
+  int32_t tail_row;      // physical row of the first appended token (row-major caches: static = retained rows, dynamic = C)
   int32_t n_rows;        // logical rows to attend (prompt part + tail)
 };
 
@@ -35,7 +36,7 @@ __device__ __forceinline__ bool resolve_row(const RowMap& rm, int r, int64_t& ph
     phys = ((int64_t)ch << rm.c_log2) + (r & ((1 << rm.c_log2) - 1));
     return phys >= 0 && phys < rm.C;    // the last chunk of the prompt may be short
   }
-  phys = (int64_t)rm.C + (r - rm.n_sel_rows);
+  phys = (int64_t)rm.tail_row + (r - rm.n_sel_rows);
   return true;
 }
 
@@ -223,7 +224,7 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
           phys = ((uint32_t)ch << rm.c_log2) + ((uint32_t)r & cmask);
           valid = phys < (uint32_t)rm.C;                  // the last chunk of the prompt may be short
         } else {
-          phys = (uint32_t)rm.C + (uint32_t)(r - rm.n_sel_rows);
+          phys = (uint32_t)rm.tail_row + (uint32_t)(r - rm.n_sel_rows);
           valid = r < rm.n_rows;
         }
         phys = valid ? phys : 0u;
@@ -353,19 +354,163 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 tile on the matrix cores, for caches in the blocked layout (hkv_internal.h)
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+
+// Physical 8-row block that holds logical rows Lr .. Lr+7 (Lr a multiple of 8) and how many of them
+// are real (0..8).  A block with no real row is redirected to block 0, which always exists.
+template <bool DYN>
+__device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t& blk, int& nv) {
+  int pb;
+  if constexpr (!DYN) {
+    pb = Lr;
+    nv = rm.n_rows - Lr;
+  } else {
+    if (Lr < rm.n_sel_rows) {
+      const int ch = rm.sel[Lr >> rm.c_log2];
+      pb = (ch << rm.c_log2) + (Lr & ((1 << rm.c_log2) - 1));
+      nv = rm.C - pb;                                   // the last chunk of the prompt may be short
+    } else {
+      pb = rm.tail_row + (Lr - rm.n_sel_rows);
+      nv = rm.n_rows - Lr;
+    }
+  }
+  nv = min(max(nv, 0), kBlkRows);
+  blk = nv > 0 ? (uint32_t)pb >> 3 : 0u;
+}
+
+// One tile of kTileBf16 logical rows; each wave takes 64 of them in two steps of 32 keys.
+// Scores S^T = K Q^T: the A operand is a K block piece (key-major), the B operand the query rows
+// (zero beyond G), so lane (q = lane % 16, j = lane / 16) ends with the scores of query head q for
+// the 8 rows of block j of the step -- which is exactly the B operand the second contraction
+// O^T += V^T P^T needs from that lane, so the weights never move between lanes.  The A operand of the
+// second contraction is a 16-byte piece of the transposed V block.  Nothing is staged through LDS.
+template <int G, bool DYN>
+__device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* __restrict__ q, float scale_log2e,
+                                               int row0, float* __restrict__ part, float* smem) {
+  constexpr int NSTEP = kTileBf16 / 4 / 32;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int qi = lane & 15, jv = lane >> 4, ja = qi >> 2, e1 = lane & 3;
+
+  bf16x8 qb[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    uint4 t = make_uint4(0, 0, 0, 0);
+    if (qi < G) t = ld16(reinterpret_cast<const char*>(q) + (size_t)qi * kD * 2 + (32 * s + 8 * jv) * 2);
+    qb[s] = __builtin_bit_cast(bf16x8, t);
+  }
+  const int wrow0 = __builtin_amdgcn_readfirstlane(row0 + wv * 32 * NSTEP);
+  uint32_t blk_a[NSTEP], blk_v[NSTEP];
+  int nv_v[NSTEP];
+#pragma unroll
+  for (int st = 0; st < NSTEP; ++st) {
+    int unused;
+    resolve_block<DYN>(rm, wrow0 + st * 32 + 8 * ja, blk_a[st], unused);
+    resolve_block<DYN>(rm, wrow0 + st * 32 + 8 * jv, blk_v[st], nv_v[st]);
+  }
+  floatx4 o[8];
+#pragma unroll
+  for (int db = 0; db < 8; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m = kNeg, lsum = 0.f;
+
+#pragma unroll
+  for (int st = 0; st < NSTEP; ++st) {
+    if (wrow0 + st * 32 >= rm.n_rows) break;             // wave-uniform
+    const char* kp = rm.kbase + (size_t)blk_a[st] * kBlkBytes + (jv * 4 + e1) * 16;
+    const char* vp = rm.vbase + (size_t)blk_v[st] * kBlkBytes + qi * 16;
+    uint4 ka[8], va[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
+#pragma unroll
+    for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);     // i = 16-dim block of the output
+    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[2 * s]), qb[s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[2 * s + 1]), qb[s], s1, 0, 0, 0);
+    }
+    const int nv = nv_v[st];
+    float sc[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      sc[e] = e < nv ? s0[e] * scale_log2e : kNeg;        // rows 0..3 of block jv
+      sc[e + 4] = e + 4 < nv ? s1[e] * scale_log2e : kNeg;  // rows 4..7
+    }
+    float mx = sc[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sc[e]);
+    if (__builtin_amdgcn_ballot_w64(mx > m + kRescaleSlack) != 0) {   // wave-uniform, rare after the first step
+      mx = fmaxf(mx, lane_xor(mx, 16));
+      mx = fmaxf(mx, lane_xor(mx, 32));                  // over the four lanes that share a query head
+      const float mn = fmaxf(m, mx);
+      const float corr = fast_exp2(m - mn);
+      lsum *= corr;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) o[db] *= corr;
+      m = mn;
+    }
+    float p[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = e < nv ? fast_exp2(sc[e] - m) : 0.f;
+      lsum += p[e];
+    }
+    uint4 pw;
+    pw.x = pack_bf16(p[0], p[1]); pw.y = pack_bf16(p[2], p[3]);
+    pw.z = pack_bf16(p[4], p[5]); pw.w = pack_bf16(p[6], p[7]);
+    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), pb, o[db], 0, 0, 0);
+  }
+
+  lsum += lane_xor(lsum, 16);
+  lsum += lane_xor(lsum, 32);
+  float* mine = smem + (size_t)wv * G * kPartStride;
+  if (qi < G) {
+    if (jv == 0) { mine[qi * kPartStride] = m; mine[qi * kPartStride + 1] = lsum; }
+#pragma unroll
+    for (int db = 0; db < 8; ++db)      // o[db][r] is output dim 16*db + 4*jv + r of query head qi
+      *reinterpret_cast<float4*>(mine + qi * kPartStride + 4 + 16 * db + 4 * jv) =
+          make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * kD; idx += 256) {
+    const int g = idx >> 7, dd = idx & (kD - 1);
+    float mm = kNeg;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) mm = fmaxf(mm, smem[(w * G + g) * kPartStride]);
+    float ll = 0.f, oo = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float c = fast_exp2(smem[(w * G + g) * kPartStride] - mm);
+      ll = fmaf(smem[(w * G + g) * kPartStride + 1], c, ll);
+      oo = fmaf(smem[(w * G + g) * kPartStride + 4 + dd], c, oo);
+    }
+    part[g * kPartStride + 4 + dd] = oo;
+    if (dd == 0) { part[g * kPartStride] = mm; part[g * kPartStride + 1] = ll; }
+  }
+}
+
 constexpr int kNhbBf16 = kTileBf16 / 128;
-template <typename T, int G> constexpr size_t attn_smem_bytes() {
-  if constexpr (sizeof(T) == 2) return attn_bf16_smem_bytes<G>();
+// BLOCKED: the K/V rows are in the blocked cache layout (bf16 caches) -> matrix-core tile.
+template <typename T, int G, bool BLOCKED> constexpr size_t attn_smem_bytes() {
+  if constexpr (sizeof(T) == 2 && !BLOCKED) return attn_bf16_smem_bytes<G>();
   else return (size_t)4 * G * kPartStride * sizeof(float);
 }
 template <typename T> __device__ __forceinline__ constexpr int tile_of() { return sizeof(T) == 2 ? kTileBf16 : kTileF32; }
 
-template <typename T, int G>
+template <typename T, int G, bool BLOCKED>
 __device__ __forceinline__ void run_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
                                          float* __restrict__ part, float* smem) {
-  if constexpr (sizeof(T) == 2) {
-    if (rm.dynamic) attn_tile_bf16<G, kNhbBf16, true>(rm, q, scale_log2e, row0, part, smem);
-    else attn_tile_bf16<G, kNhbBf16, false>(rm, q, scale_log2e, row0, part, smem);
+  if constexpr (sizeof(T) == 2 && BLOCKED) {
+    if (rm.dynamic) attn_tile_mfma<G, true>(rm, q, scale_log2e, row0, part, smem);
+    else attn_tile_mfma<G, false>(rm, q, scale_log2e, row0, part, smem);
+  } else if constexpr (sizeof(T) == 2) {
+    attn_tile_bf16<G, kNhbBf16, false>(rm, q, scale_log2e, row0, part, smem);   // row-major rows, never gathered
   } else {
     attn_tile<T, G>(rm, q, scale_log2e, row0, part, smem);
   }
@@ -425,11 +570,24 @@ __global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_be
   if (do_step) {
     const int t = t_arg >= 0 ? t_arg : cv.cnt_a[layer];
     const bool append = (k_new != nullptr) && (t < cv.max_new);
-    if (append && tid < 2 * LPR) {
+    const size_t src_row = (((size_t)lrel * cv.batch + d.seq) * cv.n_kv_heads + d.head) * kD * sizeof(T);
+    if constexpr (sizeof(T) == 2) {
+      // blocked cache: 16 key pieces go to their slots of the row's block, V is scattered one element per dim
+      const int64_t prow = d.kv_row_off + d.tail_row + t;
+      const size_t blk_off = (size_t)(prow >> 3) * kBlkBytes;
+      const int e = (int)(prow & 7);
+      if (append && tid < 16)
+        st16(reinterpret_cast<char*>(cv.k_rows) + blk_off + k_piece_index(e, tid) * 16,
+             ld16(reinterpret_cast<const char*>(k_new) + src_row + tid * 16));
+      if (append && tid >= 64 && tid < 64 + kD) {
+        const int dd = tid - 64;
+        *reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(cv.v_rows) + blk_off + dd * 16 + e * 2) =
+            *reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(v_new) + src_row + dd * 2);
+      }
+    } else if (append && tid < 2 * LPR) {
       const int which = tid / LPR, sub = tid % LPR;
-      const int64_t base_rows = d.kind == HKV_STATIC ? d.n_prompt_rows : d.C;
-      const size_t src = (((size_t)lrel * cv.batch + d.seq) * cv.n_kv_heads + d.head) * kD * sizeof(T) + sub * 16;
-      const size_t dst = (size_t)(d.kv_row_off + base_rows + t) * kD * sizeof(T) + sub * 16;
+      const size_t src = src_row + sub * 16;
+      const size_t dst = (size_t)(d.kv_row_off + d.tail_row + t) * kD * sizeof(T) + sub * 16;
       if (which == 0) st16(reinterpret_cast<char*>(cv.k_rows) + dst, ld16(reinterpret_cast<const char*>(k_new) + src));
       else st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v_new) + src));
     }
@@ -551,9 +709,10 @@ __global__ __launch_bounds__(256) void attn_kernel(CacheView cv, int layer_begin
   rm.n_sel_rows = it.n_prompt_rows;
   rm.c_log2 = it.c_log2;
   rm.C = it.C;
+  rm.tail_row = it.tail_row;
   const size_t qoff = (size_t)it.q_off - (size_t)layer_begin * cv.batch * cv.n_q_heads * kD;
   float* part = partials + (size_t)blockIdx.x * G * kPartStride;
-  run_tile<T, G>(rm, q + qoff, cv.scale_log2e, it.row0, part, smem);
+  run_tile<T, G, true>(rm, q + qoff, cv.scale_log2e, it.row0, part, smem);
 }
 
 // grid = (units of the call) x G, block = 128 threads.
@@ -601,10 +760,10 @@ __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __
   rm.kbase = reinterpret_cast<const char*>(k) + off;
   rm.vbase = reinterpret_cast<const char*>(v) + off;
   rm.stride = (uint32_t)fv.n_kv_heads * kD * sizeof(T);
-  rm.dynamic = 0; rm.sel = nullptr; rm.n_sel_rows = 0; rm.c_log2 = 0; rm.C = rm.n_rows;
+  rm.dynamic = 0; rm.sel = nullptr; rm.n_sel_rows = 0; rm.c_log2 = 0; rm.C = rm.n_rows; rm.tail_row = rm.n_rows;
   const size_t qoff = (((size_t)lrel * fv.batch + b) * fv.n_q_heads + (size_t)h * G) * kD;
   float* part = partials + ((size_t)unit * fv.n_tiles_max + blockIdx.x) * G * kPartStride;
-  run_tile<T, G>(rm, q + qoff, fv.scale_log2e, row0, part, smem);
+  run_tile<T, G, false>(rm, q + qoff, fv.scale_log2e, row0, part, smem);
 }
 
 template <typename T>
@@ -658,7 +817,7 @@ hipError_t launch_prepare(const CacheView& cv, int dtype, int layer_begin, int l
 template <typename T, int G>
 static hipError_t launch_attn_t(const CacheView& cv, int layer_begin, int item_begin, int n_items, const void* q,
                                 float* partials, int t_arg, hipStream_t st) {
-  constexpr size_t smem = attn_smem_bytes<T, G>();
+  constexpr size_t smem = attn_smem_bytes<T, G, true>();
   static bool attr_set = false;     // per instantiation; the attribute is sticky for the process
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, G>),
@@ -706,7 +865,7 @@ hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hi
 template <typename T, int G>
 static hipError_t launch_full_t(const FullView& fv, const void* q, const void* k, const void* v, float* partials,
                                 void* out, hipStream_t st) {
-  constexpr size_t smem = attn_smem_bytes<T, G>();
+  constexpr size_t smem = attn_smem_bytes<T, G, false>();
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&full_attn_kernel<T, G>),

@@ -19,6 +19,16 @@ constexpr int kMaxScoreRows = 256;   // G * window upper bound
 constexpr int kFullMaxBatch = 256;
 constexpr float kNeg = -1.0e30f;     // "minus infinity" that stays finite under subtraction
 
+// bf16 caches store K and V in blocks of 8 rows (2048 bytes per block each) laid out so that the
+// matrix-core operands of decode attention are plain 16-byte loads:
+//   K block: 128 pieces of 16 bytes; the piece holding dims 8*d8 .. 8*d8+7 of row e sits at index
+//            (((d8 / 4) * 2 + e / 4) * 4 + d8 % 4) * 4 + e % 4
+//   V block: piece d (0..127) holds the 8 rows' values of dim d (row e at byte 2 * e)
+// fp32 caches keep plain row-major rows.
+constexpr int kBlkRows = 8;
+constexpr int kBlkBytes = kBlkRows * kD * 2;
+__host__ __device__ inline int k_piece_index(int e, int d8) { return ((((d8 >> 2) * 2 + (e >> 2)) * 4 + (d8 & 3)) * 4) + (e & 3); }
+
 enum SelMode : int32_t { kSelVisual = 0, kSelText = 1, kSelSuffix = 2 };
 
 // One (sequence, layer, KV head) unit.  Units are numbered layer-major:
@@ -41,6 +51,8 @@ struct UnitDesc {
   int32_t n_tiles_max;  // work items reserved for the unit (tail at full capacity)
   int32_t seq, layer, head;
   int32_t type_ord;     // ordinal among the static (or dynamic) units, layer-major
+  int32_t tail_row;     // physical row (within the unit) of the first appended decode token
+  int32_t pad_;
 };
 
 // One split-K tile of decode attention: everything the attention kernel needs, in one record.
@@ -54,7 +66,7 @@ struct AttnItem {
   int32_t c_log2;
   int32_t dynamic;
   int32_t layer;
-  int32_t unit;
+  int32_t tail_row;     // physical row of the first appended decode token
 };
 
 struct CacheView {
@@ -106,6 +118,7 @@ hipError_t launch_select(const CacheView& cv, int static_begin, int n_static, hi
 hipError_t launch_compact(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,
                           int max_rows, const void* k, const void* v, int64_t total_tokens, hipStream_t st);
 hipError_t launch_adopt(const CacheView& cv, int dtype, int layer_begin, int dynamic_begin, int n_dynamic,
-                        int max_chunks, const void* k, const void* v, int64_t total_tokens, hipStream_t st);
+                        int max_chunks, int max_C, const void* k, const void* v, int64_t total_tokens,
+                        hipStream_t st);
 
 }  // namespace hkv
