@@ -177,17 +177,23 @@ def main() -> int:
         kms = [a + b for a, b in zip(kms, ms)]
         ncalls += n
         B.hkv_profile_disable(dw.cache.handle)
-    prep_us, attn_us, merge_us = (x / ncalls * 1e3 for x in kms)
+    a_us, b_us, merge_us = (x / ncalls * 1e3 for x in kms)
     R = d * wl.elem_bytes
     tail_prof = tail0 + K / n_copies + (K / n_copies) / 2.0
-    # algorithmic bytes of ONE launch of the attention kernel: K and V rows of every retained row
-    attn_bytes = 0
+    # algorithmic bytes of ONE launch of the dominant kernel (launch A): K and V rows of every row the
+    # static heads retain + the chunk summaries of the dynamic heads; launch B: gathered K and V rows
+    a_bytes = b_bytes = 0
     for l in range(L):
         for b in range(Bn):
             for h in range(Hkv):
-                rows, _, _ = copies[0].cache.unit_info(b, l, h)
-                attn_bytes += 2 * R * (rows + tail_prof)
-    attn_gbs = attn_bytes / (attn_us * 1e-6) / 1e9
+                rows, n_c, _ = copies[0].cache.unit_info(b, l, h)
+                if wl.head_type[b, l, h] == 0:
+                    a_bytes += 2 * R * (rows + tail_prof)
+                else:
+                    a_bytes += n_c * R
+                    b_bytes += 2 * R * (rows + tail_prof)
+    a_gbs = a_bytes / (a_us * 1e-6) / 1e9
+    b_gbs = b_bytes / (b_us * 1e-6) / 1e9
 
     # ---- full-KV comparison kernel ------------------------------------------------------------------
     cfg = copies[0].cfg
@@ -272,11 +278,13 @@ def main() -> int:
         "speedup_vs_full_kv": round(full_ms / ms_per_step, 3),
         "compress_ms": round(compress_ms, 3),
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
-        "kernel_us": {"prepare": round(prep_us, 2), "attention": round(attn_us, 2), "merge": round(merge_us, 2)},
-        "roofline": {"kernel": "attn_partial_kernel", "bound": "hbm", "achieved": round(attn_gbs, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": _read_traffic(f"pmc_attn_partial_{wl.name}.txt"),
-                     "bytes_per_launch": int(attn_bytes), "avg_launch_us": round(attn_us, 2)},
+        "kernel_us": {"decode_a_select_and_static_attention": round(a_us, 2),
+                      "decode_b_dynamic_attention": round(b_us, 2), "merge": round(merge_us, 2)},
+        "decode_b_gbs": round(b_gbs, 1),
+        "roofline": {"kernel": "decode_a_kernel", "bound": "hbm", "achieved": round(a_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(a_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": _read_traffic(f"pmc_decode_a_kernel_{wl.name}.txt"),
+                     "bytes_per_launch": int(a_bytes), "avg_launch_us": round(a_us, 2)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)

@@ -192,9 +192,10 @@ HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end
 /* Optional per-kernel timing of hkv_decode_attn, for benchmarks.  After hkv_profile_enable every
  * decode call on this cache (up to max_calls) records HIP events between its kernels on the
  * call's own stream (no synchronisation).  hkv_profile_read waits for the recorded events, returns
- * the summed durations in milliseconds -- ms[0] tail append + chunk scoring + chunk top-k,
- * ms[1] split-K attention, ms[2] combination of the split-K tiles -- and the number of
- * calls summed, then starts over.
+ * the summed durations in milliseconds -- ms[0] first launch (chunk scoring and chunk top-k of the
+ * dynamic heads together with the split-K attention of the static heads), ms[1] second launch
+ * (split-K attention of the dynamic heads), ms[2] combination of the split-K tiles -- and the number
+ * of calls summed, then starts over.
  * hkv_profile_disable releases the events. */
 HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);
 HKV_API int hkv_profile_read(hkv_cache* cache, double* ms, int* n_calls);

@@ -20,16 +20,17 @@ inline size_t elem_size(int dtype) { return dtype == HKV_BF16 ? 2 : 4; }
 struct Layout {
   // host tables
   std::vector<UnitDesc> units;
-  std::vector<AttnItem> items;
+  std::vector<AttnItem> sitems, ditems;
+  int64_t n_items = 0;
   std::vector<int32_t> static_units, dynamic_units;
-  std::vector<int32_t> static_begin, dynamic_begin, item_begin;   // [n_layers + 1]
+  std::vector<int32_t> static_begin, dynamic_begin, item_begin, sitem_begin, ditem_begin;   // [n_layers + 1]
   std::vector<int32_t> cu;
   int64_t total_tokens = 0;
   int32_t max_C = 0, max_rows_static = 0, max_chunks = 0;
   // element counts
   int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
   // arena offsets (bytes)
-  size_t off_units = 0, off_items = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
+  size_t off_units = 0, off_sitems = 0, off_ditems = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
          off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
   size_t ws_bytes = 0;
 };
@@ -81,10 +82,13 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
 
   lo.units.resize((size_t)L * B * H);
   lo.static_begin.assign(L + 1, 0); lo.dynamic_begin.assign(L + 1, 0); lo.item_begin.assign(L + 1, 0);
+  lo.sitem_begin.assign(L + 1, 0); lo.ditem_begin.assign(L + 1, 0);
   for (int l = 0; l < L; ++l) {
     lo.static_begin[l] = (int32_t)lo.static_units.size();
     lo.dynamic_begin[l] = (int32_t)lo.dynamic_units.size();
-    lo.item_begin[l] = (int32_t)lo.items.size();
+    lo.item_begin[l] = (int32_t)lo.n_items;
+    lo.sitem_begin[l] = (int32_t)lo.sitems.size();
+    lo.ditem_begin[l] = (int32_t)lo.ditems.size();
     for (int b = 0; b < B; ++b) {
       const int32_t C = lo.cu[b + 1] - lo.cu[b];
       for (int h = 0; h < H; ++h) {
@@ -136,39 +140,42 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
           const int64_t cap = phys_rows + cfg->max_new_tokens;
           lo.n_rows += blocked ? (cap + kBlkRows - 1) / kBlkRows * kBlkRows : cap;
         }
-        d.item_begin = (int32_t)lo.items.size();
+        d.item_begin = (int32_t)lo.n_items;
         d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + tile - 1) / tile);
         if ((int64_t)C + cfg->max_new_tokens >= (1 << 24)) return HKV_ESHAPE;   // 24-bit row arithmetic in the kernels
         for (int t = 0; t < d.n_tiles_max; ++t) {
           AttnItem it;
           std::memset(&it, 0, sizeof(it));
           it.kv_row_off = d.kv_row_off;
-          it.q_off = (((int64_t)l * B + b) * cfg->n_q_heads + (int64_t)h * G) * kD;
           it.sel_off = ht == HKV_DYNAMIC ? (int32_t)d.idx_off : 0;
           it.n_prompt_rows = d.n_prompt_rows;
           it.row0 = t * tile;
           it.C = C;
           it.c_log2 = d.c_log2;
           it.dynamic = ht == HKV_DYNAMIC;
-          it.layer = l;
+          it.layer = l; it.seq = b; it.head = h;
           it.tail_row = d.tail_row;
-          lo.items.push_back(it);
+          it.slot = (int32_t)lo.n_items++;
+          (ht == HKV_DYNAMIC ? lo.ditems : lo.sitems).push_back(it);
         }
-        if (lo.items.size() > (size_t)0x7fffff00) return HKV_ESHAPE;
+        if (lo.n_items > (int64_t)0x7fffff00) return HKV_ESHAPE;
         lo.units[u] = d;
       }
     }
   }
   lo.static_begin[L] = (int32_t)lo.static_units.size();
   lo.dynamic_begin[L] = (int32_t)lo.dynamic_units.size();
-  lo.item_begin[L] = (int32_t)lo.items.size();
-  if ((size_t)(kD + 256 + 8 + lo.max_chunks) * sizeof(float) > 64 * 1024) return HKV_ESHAPE;
+  lo.item_begin[L] = (int32_t)lo.n_items;
+  lo.sitem_begin[L] = (int32_t)lo.sitems.size();
+  lo.ditem_begin[L] = (int32_t)lo.ditems.size();
+  if ((size_t)(256 + 8 + lo.max_chunks + 4) * 4 + (size_t)(lo.max_chunks + 4) * 8 > 150 * 1024) return HKV_ESHAPE;
 
   const size_t es = elem_size(cfg->dtype);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   lo.off_units = take(lo.units.size() * sizeof(UnitDesc));
-  lo.off_items = take(lo.items.size() * sizeof(AttnItem));
+  lo.off_sitems = take(std::max<size_t>(1, lo.sitems.size()) * sizeof(AttnItem));
+  lo.off_ditems = take(std::max<size_t>(1, lo.ditems.size()) * sizeof(AttnItem));
   lo.off_static = take(std::max<size_t>(1, lo.static_units.size()) * 4);
   lo.off_dynamic = take(std::max<size_t>(1, lo.dynamic_units.size()) * 4);
   lo.off_vis = take((size_t)lo.total_tokens);
@@ -185,7 +192,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
   const int n_splits = (lo.max_C + kKeysPerBlock - 1) / kKeysPerBlock;
   const size_t ws_compress = align_up(lo.static_units.size() * (size_t)n_splits * kMaxScoreRows * sizeof(float2)) +
                              align_up(lo.static_units.size() * (size_t)kMaxScoreRows * sizeof(float2));
-  const size_t ws_decode = align_up(lo.items.size() * (size_t)G * kPartStride * sizeof(float));
+  const size_t ws_decode = align_up((size_t)lo.n_items * G * kPartStride * sizeof(float));
   lo.ws_bytes = std::max<size_t>(kAlign, std::max(ws_compress, ws_decode));
   return HKV_OK;
 }
@@ -250,7 +257,8 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   char* a = c->arena;
   CacheView& cv = c->cv;
   cv.units = reinterpret_cast<const UnitDesc*>(a + lo.off_units);
-  cv.items = reinterpret_cast<const AttnItem*>(a + lo.off_items);
+  cv.static_items = reinterpret_cast<const AttnItem*>(a + lo.off_sitems);
+  cv.dynamic_items = reinterpret_cast<const AttnItem*>(a + lo.off_ditems);
   cv.static_units = reinterpret_cast<const int32_t*>(a + lo.off_static);
   cv.dynamic_units = reinterpret_cast<const int32_t*>(a + lo.off_dynamic);
   cv.is_visual = reinterpret_cast<const uint8_t*>(a + lo.off_vis);
@@ -274,7 +282,8 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
     if (e == hipSuccess && bytes) e = hipMemcpy(a + off, src, bytes, hipMemcpyHostToDevice);
   };
   up(lo.off_units, lo.units.data(), lo.units.size() * sizeof(UnitDesc));
-  up(lo.off_items, lo.items.data(), lo.items.size() * sizeof(AttnItem));
+  up(lo.off_sitems, lo.sitems.data(), lo.sitems.size() * sizeof(AttnItem));
+  up(lo.off_ditems, lo.ditems.data(), lo.ditems.size() * sizeof(AttnItem));
   up(lo.off_static, lo.static_units.data(), lo.static_units.size() * 4);
   up(lo.off_dynamic, lo.dynamic_units.data(), lo.dynamic_units.size() * 4);
   up(lo.off_vis, plan->is_visual, (size_t)lo.total_tokens);
@@ -390,20 +399,25 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   }
   const Layout& lo = c->lo;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int ib = lo.item_begin[lb], ni = lo.item_begin[le] - ib;
+  const int slot_base = lo.item_begin[lb];
+  const int db = lo.dynamic_begin[lb], nd = lo.dynamic_begin[le] - db;
+  const int sb = lo.sitem_begin[lb], ns = lo.sitem_begin[le] - sb;
+  const int dib = lo.ditem_begin[lb], ndi = lo.ditem_begin[le] - dib;
   // tail length: when every layer of the call has the same one (the normal case) it travels as a
   // kernel argument; otherwise the kernels read the per-layer device counters
   int t_before = c->host_tail[lb];
   for (int l = lb; l < le; ++l) if (c->host_tail[l] != t_before) t_before = -1;
-  const int t_after = t_before < 0 ? -1 : t_before + (k_new ? 1 : 0);
   hipEvent_t* ev = (c->prof_max > 0 && c->prof_calls < c->prof_max) ? &c->events[(size_t)4 * c->prof_calls] : nullptr;
   hipError_t e = hipSuccess;
+  float* parts = static_cast<float*>(workspace);
   if (ev) e = hipEventRecord(ev[0], st);
-  if (e == hipSuccess) e = launch_prepare(c->cv, c->cfg.dtype, lb, le, q, k_new, v_new, 0, 1, t_before, lo.max_chunks, st);
+  if (e == hipSuccess) e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, sb, ns, dib, 0, slot_base, q, k_new, v_new, parts,
+                                         t_before, 0, lo.max_chunks, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
-  if (e == hipSuccess) e = launch_attn(c->cv, c->cfg.dtype, lb, ib, ni, q, static_cast<float*>(workspace), t_after, st);
+  if (e == hipSuccess) e = launch_decode(c->cv, c->cfg.dtype, lb, db, 0, sb, 0, dib, ndi, slot_base, q, k_new, v_new, parts,
+                                         t_before, 0, lo.max_chunks, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[2], st);
-  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, ib, static_cast<const float*>(workspace), out, t_after, st);
+  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, slot_base, parts, out, t_before, k_new ? 1 : 0, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[3], st);
   if (e != hipSuccess) return HKV_EHIP;
   if (ev) c->prof_calls += 1;
@@ -414,8 +428,10 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
 int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
   int rc = check_range(c, lb, le);
   if (rc != HKV_OK) return rc;
-  hipError_t e = launch_prepare(c->cv, c->cfg.dtype, lb, le, nullptr, nullptr, nullptr, 1, 0, -1, c->lo.max_chunks,
-                                static_cast<hipStream_t>(stream));
+  const Layout& lo = c->lo;
+  const int db = lo.dynamic_begin[lb], nd = lo.dynamic_begin[le] - db;
+  hipError_t e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, 0, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, -1, 1,
+                               lo.max_chunks, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;
 }
 

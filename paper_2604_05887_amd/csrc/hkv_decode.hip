@@ -1,10 +1,11 @@
 // Decode-step kernels of libhkv (gfx950):
-//   prepare_kernel   append the step's K/V rows to every head's tail; for dynamic heads score all
-//                    chunk summaries with the group-summed query and pick the top-k chunks
-//                    (paper, Appendix A, "KV Cache Retrieval for Dynamic Heads")
-//   attn_kernel      split-K softmax attention over a tile of a head's retained rows: compacted
-//                    rows (static heads), gathered chunk rows (dynamic heads) or all rows (full KV)
+//   decode_a_kernel  dynamic heads: score all chunk summaries with the group-summed query and pick the
+//                    top-k chunks (paper, Appendix A, "KV Cache Retrieval for Dynamic Heads"); in the
+//                    same launch, split-K softmax attention over the static heads' compacted rows
+//   decode_b_kernel  split-K attention over the dynamic heads' gathered chunk rows
 //   attn_merge       log-sum-exp combination of the tiles in fixed order, cast to the output dtype
+//   full_attn_kernel the same attention over caller-held, uncompressed K/V (comparison kernel)
+// The step's new K/V row is appended by the attention block whose tile contains it.
 //
 // All three are short kernels on small inputs, so their structure is driven by memory latency as
 // much as by bandwidth: descriptors come in through scalar loads, every thread issues its global
@@ -12,6 +13,8 @@
 #include "hkv_device.h"
 #include "hkv_internal.h"
 #include "hkv_select.h"
+
+#include <algorithm>
 
 namespace hkv {
 
@@ -552,55 +555,29 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p0, int n_t
 // ------------------------------------------------------------------------------------------
 // hybrid cache kernels
 // ------------------------------------------------------------------------------------------
-// grid = units of the call (layer-major), block = 256 threads.  t_arg >= 0: the tail length before
-// this step, known to the host; t_arg < 0: read it from the device counter.
+// A decode step is three launches:
+//   A  decode_a_kernel: blocks [0, n_dyn) score and pick chunks for the dynamic units of the call,
+//      the remaining blocks run the attention tiles of the static units -- the two kinds of work do
+//      not depend on each other, so the selection latency hides behind the static heads' streaming;
+//   B  decode_b_kernel: attention tiles of the dynamic units (they need A's picks);
+//   C  attn_merge_kernel: combines every unit's tiles in tile order and moves the tail counter on.
+// The step's new K/V row is written by the one block whose tile contains it, before that block reads.
+// Tail length: t_arg >= 0 is the length before this step, known to the host; t_arg < 0 reads the
+// device counter cnt_a[layer] (written only by launch C).
+
+// Chunk scoring and chunk top-k of one dynamic unit; whole block (256 threads).
 template <typename T>
-__global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_begin, int unit_begin,
-                                                      const T* __restrict__ q, const T* __restrict__ k_new,
-                                                      const T* __restrict__ v_new, int use_stored_sigma,
-                                                      int do_step, int t_arg) {
-  extern __shared__ __attribute__((aligned(16))) float dsm[];
+__device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const UnitDesc& d, int lrel,
+                                                      const T* __restrict__ q, int use_stored_sigma, float* dsm) {
   constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = 256 / LPR;
   const int tid = threadIdx.x;
-  const int u = unit_begin + blockIdx.x;
-  const int layer = u / (cv.batch * cv.n_kv_heads);
-  const UnitDesc d = cv.units[u];
-  const int lrel = layer - layer_begin;
-
-  if (do_step) {
-    const int t = t_arg >= 0 ? t_arg : cv.cnt_a[layer];
-    const bool append = (k_new != nullptr) && (t < cv.max_new);
-    const size_t src_row = (((size_t)lrel * cv.batch + d.seq) * cv.n_kv_heads + d.head) * kD * sizeof(T);
-    if constexpr (sizeof(T) == 2) {
-      // blocked cache: 16 key pieces go to their slots of the row's block, V is scattered one element per dim
-      const int64_t prow = d.kv_row_off + d.tail_row + t;
-      const size_t blk_off = (size_t)(prow >> 3) * kBlkBytes;
-      const int e = (int)(prow & 7);
-      if (append && tid < 16)
-        st16(reinterpret_cast<char*>(cv.k_rows) + blk_off + k_piece_index(e, tid) * 16,
-             ld16(reinterpret_cast<const char*>(k_new) + src_row + tid * 16));
-      if (append && tid >= 64 && tid < 64 + kD) {
-        const int dd = tid - 64;
-        *reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(cv.v_rows) + blk_off + dd * 16 + e * 2) =
-            *reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(v_new) + src_row + dd * 2);
-      }
-    } else if (append && tid < 2 * LPR) {
-      const int which = tid / LPR, sub = tid % LPR;
-      const size_t src = src_row + sub * 16;
-      const size_t dst = (size_t)(d.kv_row_off + d.tail_row + t) * kD * sizeof(T) + sub * 16;
-      if (which == 0) st16(reinterpret_cast<char*>(cv.k_rows) + dst, ld16(reinterpret_cast<const char*>(k_new) + src));
-      else st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v_new) + src));
-    }
-    if (d.seq == 0 && d.head == 0 && tid == 0) cv.cnt_b[layer] = t + (append ? 1 : 0);
-  }
-  if (d.kind != HKV_DYNAMIC) return;
-
   uint32_t* hist = reinterpret_cast<uint32_t*>(dsm);         // [256]
   uint32_t* bc = hist + 256;                                 // [2]
   int* scan = reinterpret_cast<int*>(bc + 2);                // [6]
   float* sig = dsm + 256 + 8;                                // [n_chunks rounded up to 4]
   const int n_c = d.n_chunks;
   const int n_c4 = (n_c + 3) & ~3;
+  unsigned long long* key64 = reinterpret_cast<unsigned long long*>(sig + n_c4);   // [n_c4], 8-byte aligned
 
   if (!use_stored_sigma) {
     // group-summed query for this lane's 16-byte slice, summed in head order
@@ -610,26 +587,28 @@ __global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_be
     for (int e = 0; e < EPL; ++e) qf[e] = 0.f;
     const char* qb = reinterpret_cast<const char*>(q) +
                      (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * cv.G) * kD * sizeof(T) + sub * 16;
+    const char* mu = reinterpret_cast<const char*>(cv.mu) + (size_t)d.aux_off * kD * sizeof(T) + sub * 16;
     uint4 qraw[kMaxG];
 #pragma unroll
     for (int g = 0; g < kMaxG; ++g) qraw[g] = g < cv.G ? ld16(qb + (size_t)g * kD * sizeof(T)) : make_uint4(0, 0, 0, 0);
+    for (int ch0 = 0; ch0 < n_c; ch0 += RP * 16) {      // uniform trip count; sixteen independent loads per round
+      uint4 raw[16];
 #pragma unroll
-    for (int g = 0; g < kMaxG; ++g) {
-      float t[EPL];
-      unpack16(qraw[g], t, T{});
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) qf[e] += t[e];
-    }
-    const char* mu = reinterpret_cast<const char*>(cv.mu) + (size_t)d.aux_off * kD * sizeof(T) + sub * 16;
-    for (int ch0 = 0; ch0 < n_c; ch0 += RP * 8) {       // uniform trip count; eight independent loads per round
-      uint4 raw[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
+      for (int j = 0; j < 16; ++j) {
         const int ch = ch0 + j * RP + slot;
         raw[j] = ld16(mu + (size_t)min(ch, n_c - 1) * kD * sizeof(T));
       }
+      if (ch0 == 0) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
+        for (int g = 0; g < kMaxG; ++g) {
+          float t[EPL];
+          unpack16(qraw[g], t, T{});
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) qf[e] += t[e];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
         const int ch = ch0 + j * RP + slot;
         float mf[EPL];
         unpack16(raw[j], mf, T{});
@@ -643,22 +622,24 @@ __global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_be
   } else {
     for (int ch = tid; ch < n_c; ch += 256) sig[ch] = cv.sigma[d.aux_off + ch];
   }
-  if (tid < n_c4 - n_c) sig[n_c + tid] = -__builtin_inff();   // padding never outranks a real chunk
   __syncthreads();
 
   // top-k chunks, ties to the lower chunk id, emitted ascending by chunk id
   if (n_c <= 256) {
-    // rank by counting: chunk i is picked iff fewer than k chunks beat it (greater score, or an
-    // equal score at a lower id)
+    // rank by counting over 64-bit keys (score order, then lower id first): chunk i is picked iff
+    // fewer than k keys exceed its own
     const int i = tid;
-    const float si = i < n_c ? sig[i] : 0.f;
+    unsigned long long mine = 0;
+    if (i < n_c4) {
+      if (i < n_c) mine = ((unsigned long long)float_order_key(sig[i]) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
+      key64[i] = mine;                                   // padding entries are 0: below every real key
+    }
+    __syncthreads();
     int rank = 0;
-    for (int j = 0; j < n_c4; j += 4) {
-      const float4 sj = *reinterpret_cast<const float4*>(sig + j);
-      rank += (sj.x > si || (sj.x == si && j + 0 < i)) ? 1 : 0;
-      rank += (sj.y > si || (sj.y == si && j + 1 < i)) ? 1 : 0;
-      rank += (sj.z > si || (sj.z == si && j + 2 < i)) ? 1 : 0;
-      rank += (sj.w > si || (sj.w == si && j + 3 < i)) ? 1 : 0;
+    for (int j = 0; j < n_c4; j += 2) {
+      const ulonglong2 kj = *reinterpret_cast<const ulonglong2*>(key64 + j);
+      rank += kj.x > mine ? 1 : 0;
+      rank += kj.y > mine ? 1 : 0;
     }
     const int keep = (i < n_c && rank < d.k_sel) ? 1 : 0;
     int tot;
@@ -691,16 +672,46 @@ __global__ __launch_bounds__(256) void prepare_kernel(CacheView cv, int layer_be
   }
 }
 
+// One split-K tile of the hybrid cache: optional tail append, then attention, record -> workspace.
 template <typename T, int G>
-__global__ __launch_bounds__(256) void attn_kernel(CacheView cv, int layer_begin, int item_begin,
-                                                   const T* __restrict__ q, float* __restrict__ partials, int t_arg) {
-  extern __shared__ __attribute__((aligned(16))) float smem[];
+__device__ __forceinline__ void attention_item(const CacheView& cv, const AttnItem& it, int layer_begin, int slot_base,
+                                               const T* __restrict__ q, const T* __restrict__ k_new,
+                                               const T* __restrict__ v_new, float* __restrict__ partials, int t_arg,
+                                               float* smem) {
   constexpr int TILE = tile_of<T>();
-  const AttnItem it = cv.items[item_begin + blockIdx.x];
-  const int t = t_arg >= 0 ? min(t_arg, cv.max_new) : cv.cnt_b[it.layer];
+  constexpr int LPR = Elem<T>::kLanesPerRow;
+  const int tid = threadIdx.x;
+  const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
+  const bool append = (k_new != nullptr) && (t_before < cv.max_new);
   RowMap rm;
-  rm.n_rows = it.n_prompt_rows + t;
+  rm.n_rows = it.n_prompt_rows + t_before + (append ? 1 : 0);
   if (it.row0 >= rm.n_rows) return;          // tile reserved for tail growth, not reached yet
+  const int lrel = it.layer - layer_begin;
+  const int new_row = it.n_prompt_rows + t_before;          // logical index of the appended row
+  if (append && new_row >= it.row0 && new_row < it.row0 + TILE) {   // block-uniform
+    const size_t src_row = (((size_t)lrel * cv.batch + it.seq) * cv.n_kv_heads + it.head) * kD * sizeof(T);
+    const int64_t prow = it.kv_row_off + it.tail_row + t_before;
+    if constexpr (sizeof(T) == 2) {
+      // blocked cache: 16 key pieces go to their slots of the row's block, V is scattered one element per dim
+      const size_t blk_off = (size_t)(prow >> 3) * kBlkBytes;
+      const int e = (int)(prow & 7);
+      if (tid < 16)
+        st16(reinterpret_cast<char*>(cv.k_rows) + blk_off + k_piece_index(e, tid) * 16,
+             ld16(reinterpret_cast<const char*>(k_new) + src_row + tid * 16));
+      if (tid >= 64 && tid < 64 + kD) {
+        const int dd = tid - 64;
+        *reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(cv.v_rows) + blk_off + dd * 16 + e * 2) =
+            *reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(v_new) + src_row + dd * 2);
+      }
+    } else if (tid < 2 * LPR) {
+      const int which = tid / LPR, sub = tid % LPR;
+      const size_t dst = (size_t)prow * kD * sizeof(T) + sub * 16;
+      if (which == 0) st16(reinterpret_cast<char*>(cv.k_rows) + dst, ld16(reinterpret_cast<const char*>(k_new) + src_row + sub * 16));
+      else st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v_new) + src_row + sub * 16));
+    }
+    __threadfence_block();
+    __syncthreads();                        // the row is in memory before any lane of this block reads it
+  }
   rm.kbase = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.vbase = reinterpret_cast<const char*>(cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.stride = kD * sizeof(T);
@@ -710,28 +721,62 @@ __global__ __launch_bounds__(256) void attn_kernel(CacheView cv, int layer_begin
   rm.c_log2 = it.c_log2;
   rm.C = it.C;
   rm.tail_row = it.tail_row;
-  const size_t qoff = (size_t)it.q_off - (size_t)layer_begin * cv.batch * cv.n_q_heads * kD;
-  float* part = partials + (size_t)blockIdx.x * G * kPartStride;
+  const size_t qoff = (((size_t)lrel * cv.batch + it.seq) * cv.n_q_heads + (size_t)it.head * G) * kD;
+  float* part = partials + (size_t)(it.slot - slot_base) * G * kPartStride;
   run_tile<T, G, true>(rm, q + qoff, cv.scale_log2e, it.row0, part, smem);
+}
+
+template <typename T, int G>
+__global__ __launch_bounds__(256) void decode_a_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn,
+                                                       int sitem_begin, int slot_base, const T* __restrict__ q,
+                                                       const T* __restrict__ k_new, const T* __restrict__ v_new,
+                                                       float* __restrict__ partials, int t_arg, int use_stored_sigma) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  if ((int)blockIdx.x < n_dyn) {
+    const UnitDesc d = cv.units[cv.dynamic_units[dyn_begin + blockIdx.x]];
+    select_chunks_of_unit<T>(cv, d, d.layer - layer_begin, q, use_stored_sigma, smem);
+  } else {
+    const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_dyn)];
+    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, smem);
+  }
+}
+
+template <typename T, int G>
+__global__ __launch_bounds__(256) void decode_b_kernel(CacheView cv, int layer_begin, int ditem_begin, int slot_base,
+                                                       const T* __restrict__ q, const T* __restrict__ k_new,
+                                                       const T* __restrict__ v_new, float* __restrict__ partials,
+                                                       int t_arg) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  const AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
+  attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, smem);
 }
 
 // grid = (units of the call) x G, block = 128 threads.
 template <typename T>
 __global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, int layer_begin, int unit_begin,
-                                                         int item_base, const float* __restrict__ partials,
-                                                         T* __restrict__ out, int t_arg) {
+                                                         int slot_base, const float* __restrict__ partials,
+                                                         T* __restrict__ out, int t_arg, int appending) {
   const int G = cv.G;
   const int u = unit_begin + blockIdx.x / G, g = blockIdx.x % G;
   const int layer = u / (cv.batch * cv.n_kv_heads);
-  const int t = t_arg >= 0 ? min(t_arg, cv.max_new) : cv.cnt_b[layer];
+  const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[layer];
+  const int t = t_before + ((appending && t_before < cv.max_new) ? 1 : 0);
   const UnitDesc d = cv.units[u];
   constexpr int TILE = tile_of<T>();
   const int n_tiles = (d.n_prompt_rows + t + TILE - 1) / TILE;
   const int lrel = layer - layer_begin;
-  const float* p0 = partials + ((size_t)(d.item_begin - item_base) * G + g) * kPartStride;
+  const float* p0 = partials + ((size_t)(d.item_begin - slot_base) * G + g) * kPartStride;
   T* orow = out + (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G + g) * kD;
   merge_head<T>(p0, n_tiles, G * kPartStride, orow);
-  if (g == 0 && d.seq == 0 && d.head == 0 && threadIdx.x == 0) cv.cnt_a[layer] = t;
+  // host-known tail: nobody reads the counter during this step, so it is updated in place; otherwise
+  // other blocks of this launch may still read cnt_a, so the new value goes to cnt_b and a follow-up
+  // kernel publishes it
+  if (g == 0 && d.seq == 0 && d.head == 0 && threadIdx.x == 0) (t_arg >= 0 ? cv.cnt_a : cv.cnt_b)[layer] = t;
+}
+
+__global__ void publish_tail_kernel(CacheView cv, int layer_begin, int layer_end) {
+  const int i = layer_begin + blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < layer_end) cv.cnt_a[i] = cv.cnt_b[i];
 }
 
 __global__ void rewind_kernel(CacheView cv, int layer_begin, int layer_end) {
@@ -798,60 +843,71 @@ __global__ __launch_bounds__(128) void full_merge_kernel(FullView fv, const floa
     default: return hipErrorInvalidValue;       \
   }
 
-hipError_t launch_prepare(const CacheView& cv, int dtype, int layer_begin, int layer_end, const void* q,
-                          const void* k_new, const void* v_new, int use_stored_sigma, int do_step, int t_arg,
-                          int max_chunks, hipStream_t st) {
-  const int upl = cv.batch * cv.n_kv_heads;
-  const int n_units = (layer_end - layer_begin) * upl;
-  if (n_units <= 0) return hipSuccess;
-  const size_t smem = (size_t)(256 + 8 + max_chunks + 4) * sizeof(float);
-  if (dtype == HKV_F32)
-    hipLaunchKernelGGL(prepare_kernel<float>, dim3(n_units), dim3(256), smem, st, cv, layer_begin, layer_begin * upl,
-                       (const float*)q, (const float*)k_new, (const float*)v_new, use_stored_sigma, do_step, t_arg);
-  else
-    hipLaunchKernelGGL(prepare_kernel<bf16_t>, dim3(n_units), dim3(256), smem, st, cv, layer_begin, layer_begin * upl,
-                       (const bf16_t*)q, (const bf16_t*)k_new, (const bf16_t*)v_new, use_stored_sigma, do_step, t_arg);
-  return hipGetLastError();
+static size_t select_smem_bytes(int max_chunks) {
+  const size_t n4 = ((size_t)max_chunks + 3) & ~(size_t)3;
+  return (256 + 8 + n4) * sizeof(float) + n4 * sizeof(unsigned long long);
 }
 
 template <typename T, int G>
-static hipError_t launch_attn_t(const CacheView& cv, int layer_begin, int item_begin, int n_items, const void* q,
-                                float* partials, int t_arg, hipStream_t st) {
-  constexpr size_t smem = attn_smem_bytes<T, G, true>();
-  static bool attr_set = false;     // per instantiation; the attribute is sticky for the process
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, G>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
+                                  int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
+                                  const void* k_new, const void* v_new, float* partials, int t_arg,
+                                  int use_stored_sigma, int max_chunks, hipStream_t st) {
+  const size_t smem_attn = attn_smem_bytes<T, G, true>();
+  const size_t smem_a = std::max(smem_attn, select_smem_bytes(max_chunks));
+  static size_t attr_a = 0, attr_b = 0;      // per instantiation; the attribute is sticky for the process
+  if (smem_a > attr_a) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_a_kernel<T, G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_a);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_a = smem_a;
   }
-  hipLaunchKernelGGL((attn_kernel<T, G>), dim3(n_items), dim3(256), smem, st, cv, layer_begin, item_begin,
-                     (const T*)q, partials, t_arg);
+  if (smem_attn > attr_b) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_b_kernel<T, G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_attn);
+    if (e != hipSuccess) return e;
+    attr_b = smem_attn;
+  }
+  if (n_dyn + n_sitems > 0)
+    hipLaunchKernelGGL((decode_a_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), smem_a, st, cv, layer_begin, dyn_begin,
+                       n_dyn, sitem_begin, slot_base, (const T*)q, (const T*)k_new, (const T*)v_new, partials, t_arg,
+                       use_stored_sigma);
+  if (n_ditems > 0)
+    hipLaunchKernelGGL((decode_b_kernel<T, G>), dim3(n_ditems), dim3(256), smem_attn, st, cv, layer_begin, ditem_begin,
+                       slot_base, (const T*)q, (const T*)k_new, (const T*)v_new, partials, t_arg);
   return hipGetLastError();
 }
 
-hipError_t launch_attn(const CacheView& cv, int dtype, int layer_begin, int item_begin, int n_items, const void* q,
-                       float* partials, int t_arg, hipStream_t st) {
-  if (n_items <= 0) return hipSuccess;
+hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
+                         int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
+                         const void* k_new, const void* v_new, float* partials, int t_arg, int use_stored_sigma,
+                         int max_chunks, hipStream_t st) {
   if (dtype == HKV_F32) {
-    HKV_DISPATCH_G(cv.G, return (launch_attn_t<float, GG>(cv, layer_begin, item_begin, n_items, q, partials, t_arg, st)));
+    HKV_DISPATCH_G(cv.G, return (launch_decode_t<float, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
+                                                            ditem_begin, n_ditems, slot_base, q, k_new, v_new, partials,
+                                                            t_arg, use_stored_sigma, max_chunks, st)));
   } else {
-    HKV_DISPATCH_G(cv.G, return (launch_attn_t<bf16_t, GG>(cv, layer_begin, item_begin, n_items, q, partials, t_arg, st)));
+    HKV_DISPATCH_G(cv.G, return (launch_decode_t<bf16_t, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
+                                                             ditem_begin, n_ditems, slot_base, q, k_new, v_new, partials,
+                                                             t_arg, use_stored_sigma, max_chunks, st)));
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int item_base,
-                             const float* partials, void* out, int t_arg, hipStream_t st) {
+hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int slot_base,
+                             const float* partials, void* out, int t_arg, int appending, hipStream_t st) {
   const int upl = cv.batch * cv.n_kv_heads;
   const int n_blocks = (layer_end - layer_begin) * upl * cv.G;
   if (n_blocks <= 0) return hipSuccess;
   if (dtype == HKV_F32)
     hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0, st, cv, layer_begin, layer_begin * upl,
-                       item_base, partials, (float*)out, t_arg);
+                       slot_base, partials, (float*)out, t_arg, appending);
   else
     hipLaunchKernelGGL(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0, st, cv, layer_begin,
-                       layer_begin * upl, item_base, partials, (bf16_t*)out, t_arg);
+                       layer_begin * upl, slot_base, partials, (bf16_t*)out, t_arg, appending);
+  if (t_arg < 0)
+    hipLaunchKernelGGL(publish_tail_kernel, dim3((layer_end - layer_begin + 63) / 64), dim3(64), 0, st, cv, layer_begin,
+                       layer_end);
   return hipGetLastError();
 }
 

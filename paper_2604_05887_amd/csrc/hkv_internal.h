@@ -55,23 +55,25 @@ struct UnitDesc {
   int32_t pad_;
 };
 
-// One split-K tile of decode attention: everything the attention kernel needs, in one record.
+// One split-K tile of decode attention: everything the attention block needs, in one record.
 struct AttnItem {
   int64_t kv_row_off;   // first row of the unit in the cache K / V row arrays
-  int64_t q_off;        // element offset of the unit's first query row in a [n_layers][batch][Hq][128] tensor
   int32_t sel_off;      // dynamic: offset into sel[]
   int32_t n_prompt_rows;
   int32_t row0;         // first logical row of the tile
   int32_t C;
   int32_t c_log2;
   int32_t dynamic;
-  int32_t layer;
+  int32_t layer, seq, head;
   int32_t tail_row;     // physical row of the first appended decode token
+  int32_t slot;         // global index of the tile's record in the split-K workspace
+  int32_t pad_[3];
 };
 
 struct CacheView {
   const UnitDesc* units;
-  const AttnItem* items;
+  const AttnItem* static_items;   // tiles of static units, layer-major
+  const AttnItem* dynamic_items;  // tiles of dynamic units, layer-major
   const int32_t* static_units;
   const int32_t* dynamic_units;
   const uint8_t* is_visual;
@@ -90,15 +92,15 @@ struct CacheView {
 
 // ---- launchers implemented in the kernel translation units (all asynchronous on `st`) ----
 // decode
-// t_arg: tail length known to the host (prepare: before the step; attention and merge: the length
-// the step attends), or -1 to read the device counters instead.
-hipError_t launch_prepare(const CacheView& cv, int dtype, int layer_begin, int layer_end, const void* q,
-                          const void* k_new, const void* v_new, int use_stored_sigma, int do_step, int t_arg,
-                          int max_chunks, hipStream_t st);
-hipError_t launch_attn(const CacheView& cv, int dtype, int layer_begin, int item_begin, int n_items,
-                       const void* q, float* partials, int t_arg, hipStream_t st);
-hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int item_base,
-                             const float* partials, void* out, int t_arg, hipStream_t st);
+// One decode step over a layer range: launch A (chunk selection of the dynamic units + attention
+// tiles of the static units) and launch B (attention tiles of the dynamic units).  t_arg: tail
+// length before the step if the host knows it, else -1 (device counters).
+hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
+                         int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
+                         const void* k_new, const void* v_new, float* partials, int t_arg, int use_stored_sigma,
+                         int max_chunks, hipStream_t st);
+hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int slot_base,
+                             const float* partials, void* out, int t_arg, int appending, hipStream_t st);
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
 
 struct FullView {
