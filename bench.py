@@ -53,6 +53,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=1, help="workload id (1 = Qwen2.5-VL-7B shape, 8K context)")
     ap.add_argument("--budget-rule", default="text_exempt", choices=["text_exempt", "literal_total"])
     ap.add_argument("--budget-frac", type=float, default=None)
+    ap.add_argument("--head-mix", default=None, choices=["all_static", "all_dynamic"])
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-kv", action="store_true", help="skip the full-KV comparison kernel")
@@ -96,7 +97,7 @@ def main() -> int:
     K, W = args.steps, args.warmup
     n_inputs = min(max(K, 16), 128)
     wl = make_workload(args.config, steps=n_inputs, budget_rule=args.budget_rule, budget_frac=args.budget_frac,
-                       max_new_tokens=None)
+                       max_new_tokens=None, head_mix=args.head_mix)
     L, Bn, Hq, Hkv, d = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
     tdt = runner.torch_dtype(wl.dtype)
 

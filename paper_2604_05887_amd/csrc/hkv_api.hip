@@ -30,7 +30,7 @@ struct Layout {
   // element counts
   int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
   // arena offsets (bytes)
-  size_t off_units = 0, off_sitems = 0, off_ditems = 0, off_static = 0, off_dynamic = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
+  size_t off_units = 0, off_sitems = 0, off_ditems = 0, off_static = 0, off_dynamic = 0, off_dyn_descs = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
          off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
   size_t ws_bytes = 0;
 };
@@ -178,6 +178,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
   lo.off_ditems = take(std::max<size_t>(1, lo.ditems.size()) * sizeof(AttnItem));
   lo.off_static = take(std::max<size_t>(1, lo.static_units.size()) * 4);
   lo.off_dynamic = take(std::max<size_t>(1, lo.dynamic_units.size()) * 4);
+  lo.off_dyn_descs = take(std::max<size_t>(1, lo.dynamic_units.size()) * sizeof(UnitDesc));
   lo.off_vis = take((size_t)lo.total_tokens);
   lo.off_cnt = take((size_t)2 * L * 4);
   lo.off_kept = take((size_t)std::max<int64_t>(1, lo.n_kept) * 4);
@@ -261,6 +262,7 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   cv.dynamic_items = reinterpret_cast<const AttnItem*>(a + lo.off_ditems);
   cv.static_units = reinterpret_cast<const int32_t*>(a + lo.off_static);
   cv.dynamic_units = reinterpret_cast<const int32_t*>(a + lo.off_dynamic);
+  cv.dyn_descs = reinterpret_cast<const UnitDesc*>(a + lo.off_dyn_descs);
   cv.is_visual = reinterpret_cast<const uint8_t*>(a + lo.off_vis);
   cv.cnt_a = reinterpret_cast<int32_t*>(a + lo.off_cnt);
   cv.cnt_b = cv.cnt_a + cfg->n_layers;
@@ -286,6 +288,11 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   up(lo.off_ditems, lo.ditems.data(), lo.ditems.size() * sizeof(AttnItem));
   up(lo.off_static, lo.static_units.data(), lo.static_units.size() * 4);
   up(lo.off_dynamic, lo.dynamic_units.data(), lo.dynamic_units.size() * 4);
+  {
+    std::vector<UnitDesc> dd;
+    for (int32_t u : lo.dynamic_units) dd.push_back(lo.units[u]);
+    up(lo.off_dyn_descs, dd.data(), dd.size() * sizeof(UnitDesc));
+  }
   up(lo.off_vis, plan->is_visual, (size_t)lo.total_tokens);
   if (e == hipSuccess) e = hipMemset(a + lo.off_cnt, 0, (size_t)2 * cfg->n_layers * 4);
   // rows that are allocated but not (yet) written must hold finite values: masked rows still enter the

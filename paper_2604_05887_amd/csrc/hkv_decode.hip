@@ -419,21 +419,28 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
   for (int db = 0; db < 8; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
   float m = kNeg, lsum = 0.f;
 
+  // all of the wave's loads are issued before any arithmetic: a wave has at most 2 x 16 of them and
+  // a decode step is short enough that memory latency, not bandwidth, is what a wave waits for
+  uint4 ka[NSTEP][8], va[NSTEP][8];
+#pragma unroll
+  for (int st = 0; st < NSTEP; ++st) {
+    if (wrow0 + st * 32 < rm.n_rows) {                   // wave-uniform
+      const char* kp = rm.kbase + (size_t)blk_a[st] * kBlkBytes + (jv * 4 + e1) * 16;
+      const char* vp = rm.vbase + (size_t)blk_v[st] * kBlkBytes + qi * 16;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ka[st][i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
+#pragma unroll
+      for (int i = 0; i < 8; ++i) va[st][i] = ld16(vp + i * 256);     // i = 16-dim block of the output
+    }
+  }
 #pragma unroll
   for (int st = 0; st < NSTEP; ++st) {
     if (wrow0 + st * 32 >= rm.n_rows) break;             // wave-uniform
-    const char* kp = rm.kbase + (size_t)blk_a[st] * kBlkBytes + (jv * 4 + e1) * 16;
-    const char* vp = rm.vbase + (size_t)blk_v[st] * kBlkBytes + qi * 16;
-    uint4 ka[8], va[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
-#pragma unroll
-    for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);     // i = 16-dim block of the output
     floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[2 * s]), qb[s], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[2 * s + 1]), qb[s], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[st][2 * s]), qb[s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[st][2 * s + 1]), qb[s], s1, 0, 0, 0);
     }
     const int nv = nv_v[st];
     float sc[8];
@@ -467,7 +474,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
     for (int db = 0; db < 8; ++db)
-      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), pb, o[db], 0, 0, 0);
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[st][db]), pb, o[db], 0, 0, 0);
   }
 
   lsum += lane_xor(lsum, 16);
@@ -636,10 +643,18 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     }
     __syncthreads();
     int rank = 0;
-    for (int j = 0; j < n_c4; j += 2) {
-      const ulonglong2 kj = *reinterpret_cast<const ulonglong2*>(key64 + j);
-      rank += kj.x > mine ? 1 : 0;
-      rank += kj.y > mine ? 1 : 0;
+    for (int j0 = 0; j0 < n_c4; j0 += 16) {              // eight independent 16-byte LDS reads per round
+      ulonglong2 kj[8];
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const int j = min(j0 + 2 * x, n_c4 - 2);         // a repeated pair is weighted 0 below
+        kj[x] = *reinterpret_cast<const ulonglong2*>(key64 + j);
+      }
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const int in = (j0 + 2 * x < n_c4) ? 1 : 0;
+        rank += (kj[x].x > mine ? in : 0) + (kj[x].y > mine ? in : 0);
+      }
     }
     const int keep = (i < n_c && rank < d.k_sel) ? 1 : 0;
     int tot;
@@ -733,7 +748,7 @@ __global__ __launch_bounds__(256) void decode_a_kernel(CacheView cv, int layer_b
                                                        float* __restrict__ partials, int t_arg, int use_stored_sigma) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   if ((int)blockIdx.x < n_dyn) {
-    const UnitDesc d = cv.units[cv.dynamic_units[dyn_begin + blockIdx.x]];
+    const UnitDesc d = cv.dyn_descs[dyn_begin + blockIdx.x];
     select_chunks_of_unit<T>(cv, d, d.layer - layer_begin, q, use_stored_sigma, smem);
   } else {
     const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_dyn)];

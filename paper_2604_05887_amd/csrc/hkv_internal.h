@@ -76,6 +76,7 @@ struct CacheView {
   const AttnItem* dynamic_items;  // tiles of dynamic units, layer-major
   const int32_t* static_units;
   const int32_t* dynamic_units;
+  const UnitDesc* dyn_descs;      // descriptors of the dynamic units in dynamic_units order
   const uint8_t* is_visual;
   int32_t* cnt_a;             // [n_layers] tail length before the step in flight
   int32_t* cnt_b;             // [n_layers] tail length the step in flight attends
