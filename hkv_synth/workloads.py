@@ -209,12 +209,15 @@ def allocate_budgets(rng: np.random.Generator, *, rule: str, hierarchical: bool,
 def make_workload(cfg_id: int, seed: Optional[int] = None, *, budget_rule: str = "text_exempt",
                   n_layers: Optional[int] = None, steps: Optional[int] = None,
                   shrink: int = 1, budget_frac: Optional[float] = None,
-                  head_mix: Optional[str] = None, max_new_tokens: Optional[int] = None) -> Workload:
+                  head_mix: Optional[str] = None, max_new_tokens: Optional[int] = None,
+                  tensors: bool = True) -> Workload:
     """Build configuration `cfg_id` (0..4).
 
     `n_layers`, `steps` and `shrink` (divide every sequence's visual/text counts by
     it) give smaller variants with the same structure for parity tests.
     `head_mix` in {"all_static", "all_dynamic"} overrides the head-type map.
+    `tensors=False` builds only the layout, head types and budgets (Q/K/V fields are None): the
+    benchmark then draws the large configurations' tensors on the device.
     """
     c = dict(CONFIGS[cfg_id])
     seed = cfg_id if seed is None else seed
@@ -282,6 +285,15 @@ def make_workload(cfg_id: int, seed: Optional[int] = None, *, budget_rule: str =
             rng, rule=budget_rule, hierarchical=c["hierarchical"], head_type=head_type[b], n_ctx=C,
             n_text_hist=int((hist == 0).sum()), n_vis_hist=int((hist == 1).sum()), window=w,
             frac=float(fracs[b]), chunk=int(chunk[b]), k_chunks=c["k_chunks"])
+
+    if not tensors:
+        return Workload(
+            name=c["name"] + (f"_shrink{shrink}" if shrink > 1 else "") + (f"_L{L}" if L != c["n_layers"] else ""),
+            dtype=dtype, n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, window=w, batch=B,
+            seqlens=seqlens, cu_seqlens=cu, chunk_size=chunk.astype(np.int32), is_visual=is_visual,
+            head_type=head_type, budget=budget, budget_rule=budget_rule, budget_frac=fracs,
+            max_new_tokens=max_new_tokens if max_new_tokens is not None else max(n_steps, 1), steps=n_steps,
+            q_window=None, k=None, v=None, q_steps=None, k_new=None, v_new=None, planted={}, seed=seed)
 
     # tensors
     def normal(shape):

@@ -94,6 +94,9 @@ typedef struct {
   int32_t score_causal;     /* 0: S_w as printed (no mask); 1: window row i sees keys <= C-w+i */
   int32_t max_new_tokens;   /* capacity of every head's uncompressed decode tail */
   float softmax_scale;      /* 0 -> 1/sqrt(head_dim) */
+  int32_t decode_tile_rows; /* rows per split-K tile of decode attention: 0 = chosen from the amount of
+                               work; bf16 caches also accept 128, 256, 512 or 1024 (tuning knob; the
+                               result does not depend on it beyond fp32 summation order) */
 } hkv_config;
 
 /* Per-prompt plan.  All arrays live in HOST memory and are only read during the call. */

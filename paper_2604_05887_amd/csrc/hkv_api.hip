@@ -32,7 +32,8 @@ struct Layout {
   // arena offsets (bytes)
   size_t off_units = 0, off_sitems = 0, off_ditems = 0, off_static = 0, off_dynamic = 0, off_dyn_descs = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
          off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
-  size_t ws_bytes = 0;
+  size_t ws_bytes = 0, ws_o_bytes = 0;
+  int tile = 0;
 };
 
 int validate_config(const hkv_config* cfg) {
@@ -47,21 +48,25 @@ int validate_config(const hkv_config* cfg) {
   if (G < 1 || G > kMaxG) return HKV_ESHAPE;
   if (cfg->window < 1 || G * cfg->window > kMaxScoreRows) return HKV_ESHAPE;
   if (cfg->max_new_tokens < 0) return HKV_ESHAPE;
+  if (cfg->decode_tile_rows != 0) {
+    const int t = cfg->decode_tile_rows;
+    if (cfg->dtype != HKV_BF16 || (t != 128 && t != 256 && t != 512 && t != 1024)) return HKV_ESHAPE;
+  }
   if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
   return HKV_OK;
 }
 
 inline bool pow2_ge4(int c) { return c >= 4 && (c & (c - 1)) == 0; }
 
-int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
+int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, int tile) {
   int rc = validate_config(cfg);
   if (rc != HKV_OK) return rc;
   if (!plan || !plan->cu_seqlens || !plan->is_visual || !plan->head_type || !plan->budget) return HKV_EINVAL;
   if (plan->batch < 1 || plan->batch > 4096) return HKV_ESHAPE;
   const int B = plan->batch, L = cfg->n_layers, H = cfg->n_kv_heads, w = cfg->window;
   const int G = cfg->n_q_heads / H;
-  const int tile = tile_rows(cfg->dtype);
   const bool blocked = cfg->dtype == HKV_BF16;
+  lo.tile = tile;
   if (plan->cu_seqlens[0] != 0) return HKV_EINVAL;
   lo.cu.assign(plan->cu_seqlens, plan->cu_seqlens + B + 1);
   std::vector<int32_t> n_txt(B), n_vis(B), csz(B);
@@ -193,9 +198,27 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
   const int n_splits = (lo.max_C + kKeysPerBlock - 1) / kKeysPerBlock;
   const size_t ws_compress = align_up(lo.static_units.size() * (size_t)n_splits * kMaxScoreRows * sizeof(float2)) +
                              align_up(lo.static_units.size() * (size_t)kMaxScoreRows * sizeof(float2));
-  const size_t ws_decode = align_up((size_t)lo.n_items * G * kPartStride * sizeof(float));
+  lo.ws_o_bytes = align_up((size_t)lo.n_items * G * kD * sizeof(float));
+  const size_t ws_decode = lo.ws_o_bytes + align_up((size_t)lo.n_items * kMlFloats * sizeof(float));
   lo.ws_bytes = std::max<size_t>(kAlign, std::max(ws_compress, ws_decode));
   return HKV_OK;
+}
+
+// Tile size: fp32 caches use 128 rows; bf16 caches start at 256 rows and double (up to 1024) while the
+// whole cache still yields at least 2048 tiles, so that small steps keep every CU busy and large
+// ones amortise the per-tile cost.
+int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
+  if (cfg && cfg->dtype != HKV_BF16) return plan_layout_tile(cfg, plan, lo, kTileF32);
+  if (cfg && cfg->decode_tile_rows != 0) return plan_layout_tile(cfg, plan, lo, cfg->decode_tile_rows);
+  int tile = kTileBf16;
+  int rc = plan_layout_tile(cfg, plan, lo, tile);
+  while (rc == HKV_OK && tile < kTileBf16Max) {
+    Layout next;
+    if (plan_layout_tile(cfg, plan, next, tile * 2) != HKV_OK || next.n_items < 2048) break;
+    tile *= 2;
+    lo = std::move(next);
+  }
+  return rc;
 }
 
 }  // namespace
@@ -276,6 +299,7 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   cv.n_layers = cfg->n_layers; cv.batch = plan->batch; cv.n_q_heads = cfg->n_q_heads; cv.n_kv_heads = cfg->n_kv_heads;
   cv.G = cfg->n_q_heads / cfg->n_kv_heads; cv.window = cfg->window; cv.max_new = cfg->max_new_tokens;
   cv.causal = cfg->score_causal;
+  cv.tile_rows = lo.tile;
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   cv.scale_log2e = scale * 1.4426950408889634f;
 
@@ -417,14 +441,15 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   hipEvent_t* ev = (c->prof_max > 0 && c->prof_calls < c->prof_max) ? &c->events[(size_t)4 * c->prof_calls] : nullptr;
   hipError_t e = hipSuccess;
   float* parts = static_cast<float*>(workspace);
+  float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + lo.ws_o_bytes);
   if (ev) e = hipEventRecord(ev[0], st);
   if (e == hipSuccess) e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, sb, ns, dib, 0, slot_base, q, k_new, v_new, parts,
-                                         t_before, 0, lo.max_chunks, st);
+                                         parts_ml, t_before, 0, lo.max_chunks, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
   if (e == hipSuccess) e = launch_decode(c->cv, c->cfg.dtype, lb, db, 0, sb, 0, dib, ndi, slot_base, q, k_new, v_new, parts,
-                                         t_before, 0, lo.max_chunks, st);
+                                         parts_ml, t_before, 0, lo.max_chunks, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[2], st);
-  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, slot_base, parts, out, t_before, k_new ? 1 : 0, st);
+  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, slot_base, parts, parts_ml, out, t_before, k_new ? 1 : 0, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[3], st);
   if (e != hipSuccess) return HKV_EHIP;
   if (ev) c->prof_calls += 1;
@@ -437,7 +462,7 @@ int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
   if (rc != HKV_OK) return rc;
   const Layout& lo = c->lo;
   const int db = lo.dynamic_begin[lb], nd = lo.dynamic_begin[le] - db;
-  hipError_t e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, 0, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, -1, 1,
+  hipError_t e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, 0, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, -1, 1,
                                lo.max_chunks, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;
 }
@@ -468,7 +493,7 @@ static int full_view(const hkv_config* cfg, int32_t batch, const int32_t* cu, in
   std::memcpy(fv.cu, cu, (size_t)(batch + 1) * 4);
   fv.batch = batch; fv.n_layers_call = n_layers_call; fv.n_q_heads = cfg->n_q_heads; fv.n_kv_heads = cfg->n_kv_heads;
   fv.G = cfg->n_q_heads / cfg->n_kv_heads;
-  const int tile = tile_rows(cfg->dtype);
+  const int tile = cfg->dtype == HKV_BF16 ? kTileBf16 : kTileF32;
   fv.n_tiles_max = (max_len + tile - 1) / tile;
   fv.total_tokens = cu[batch];
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
@@ -483,7 +508,8 @@ int hkv_full_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t*
   FullView fv;
   int rc = full_view(cfg, batch, cu_seqlens, n_layers_call, fv);
   if (rc != HKV_OK) return rc;
-  *workspace_bytes = align_up((size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max * fv.G * kPartStride * sizeof(float));
+  const size_t n_slots = (size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max;
+  *workspace_bytes = align_up(n_slots * fv.G * kD * sizeof(float)) + align_up(n_slots * kMlFloats * sizeof(float));
   return HKV_OK;
 }
 
@@ -498,7 +524,9 @@ int hkv_full_decode_attn(const hkv_config* cfg, int32_t batch, const int32_t* cu
   size_t need = 0;
   hkv_full_workspace_size(cfg, batch, cu_seqlens, n_layers_call, &need);
   if (workspace_bytes < need) return HKV_ENOSPACE;
-  hipError_t e = launch_full_attn(fv, cfg->dtype, q, k, v, static_cast<float*>(workspace), out,
+  const size_t n_slots = (size_t)n_layers_call * batch * cfg->n_kv_heads * fv.n_tiles_max;
+  float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up(n_slots * fv.G * kD * sizeof(float)));
+  hipError_t e = launch_full_attn(fv, cfg->dtype, q, k, v, static_cast<float*>(workspace), parts_ml, out,
                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;
 }

@@ -43,6 +43,48 @@ __device__ __forceinline__ bool resolve_row(const RowMap& rm, int r, int64_t& ph
   return true;
 }
 
+
+// Where a tile's split-K record goes: o = [G][128] unnormalised outputs (512-byte rows), ml = [8][2]
+// (running max in the log2 domain, sum) -- one fully written 64-byte line per tile.  Records are
+// whole, aligned lines on purpose: partially written lines made the memory side read-modify-write
+// and cost the attention kernel 8 % of its time.
+struct PartOut {
+  float* o;
+  float* ml;
+};
+constexpr int kMlStride = kMlFloats;
+
+// Combine NS online-softmax streams staged in shared memory ([stream][G][kPartStride]: max, sum, pad,
+// pad, o[128]) in stream order and store the tile's record.  All 256 threads; smem must be ready.
+template <int G, int NS>
+__device__ __forceinline__ void combine_streams_and_store(const float* smem, const PartOut& po) {
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < G * kD; idx += 256) {
+    const int g = idx >> 7, dd = idx & (kD - 1);
+    float mm = kNeg;
+#pragma unroll
+    for (int st = 0; st < NS; ++st) mm = fmaxf(mm, smem[(st * G + g) * kPartStride]);
+    float oo = 0.f;
+#pragma unroll
+    for (int st = 0; st < NS; ++st)
+      oo = fmaf(smem[(st * G + g) * kPartStride + 4 + dd], fast_exp2(smem[(st * G + g) * kPartStride] - mm), oo);
+    __builtin_nontemporal_store(oo, po.o + idx);
+  }
+  if (tid < 8) {
+    float mm = 0.f, ll = 0.f;
+    if (tid < G) {
+      mm = kNeg;
+#pragma unroll
+      for (int st = 0; st < NS; ++st) mm = fmaxf(mm, smem[(st * G + tid) * kPartStride]);
+#pragma unroll
+      for (int st = 0; st < NS; ++st)
+        ll = fmaf(smem[(st * G + tid) * kPartStride + 1], fast_exp2(smem[(st * G + tid) * kPartStride] - mm), ll);
+    }
+    __builtin_nontemporal_store(mm, po.ml + 2 * tid);
+    __builtin_nontemporal_store(ll, po.ml + 2 * tid + 1);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // generic tile (any dtype; used for fp32): 16 or 32 lanes per row, fp32 FMAs, wave reductions
 // ---------------------------------------------------------------------------------------------
@@ -50,7 +92,7 @@ __device__ __forceinline__ bool resolve_row(const RowMap& rm, int r, int64_t& ph
 // Writes G records of kPartStride floats: [0]=running max (log2 domain), [1]=sum, [4..131]=unnormalised o.
 template <typename T, int G>
 __device__ __forceinline__ void attn_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
-                                          float* __restrict__ part, float* smem) {
+                                          const PartOut& part, float* smem) {
   constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RPW = 64 / LPR;
   constexpr int WROWS = kTileF32 / 4;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -128,23 +170,7 @@ __device__ __forceinline__ void attn_tile(const RowMap& rm, const T* __restrict_
     }
   }
   __syncthreads();
-  if (tid < kD) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float mm = kNeg;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) mm = fmaxf(mm, smem[(w * G + g) * kPartStride]);
-      float ll = 0.f, oo = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float c = fast_exp2(smem[(w * G + g) * kPartStride] - mm);
-        ll = fmaf(smem[(w * G + g) * kPartStride + 1], c, ll);
-        oo = fmaf(smem[(w * G + g) * kPartStride + 4 + tid], c, oo);
-      }
-      part[g * kPartStride + 4 + tid] = oo;
-      if (tid == 0) { part[g * kPartStride] = mm; part[g * kPartStride + 1] = ll; }
-    }
-  }
+  combine_streams_and_store<G, 4>(smem, part);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -182,7 +208,7 @@ template <int G> constexpr size_t attn_bf16_smem_bytes() {
 // and removes the rescaling of the accumulators from almost every half batch.
 template <int G, int NHB, bool DYN>
 __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* __restrict__ q, float scale_log2e,
-                                               int row0, float* __restrict__ part, float* smem) {
+                                               int row0, const PartOut& part, float* smem) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
   uint32_t* pbuf = reinterpret_cast<uint32_t*>(smem + (size_t)kStreams * G * kPartStride) +
@@ -340,21 +366,7 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
     dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
   }
   __syncthreads();
-  for (int idx = tid; idx < G * kD; idx += 256) {
-    const int g = idx >> 7, dd = idx & (kD - 1);
-    float mm = kNeg;
-#pragma unroll
-    for (int st = 0; st < kStreams; ++st) mm = fmaxf(mm, smem[(st * G + g) * kPartStride]);
-    float ll = 0.f, oo = 0.f;
-#pragma unroll
-    for (int st = 0; st < kStreams; ++st) {
-      const float c = fast_exp2(smem[(st * G + g) * kPartStride] - mm);
-      ll = fmaf(smem[(st * G + g) * kPartStride + 1], c, ll);
-      oo = fmaf(smem[(st * G + g) * kPartStride + 4 + dd], c, oo);
-    }
-    part[g * kPartStride + 4 + dd] = oo;
-    if (dd == 0) { part[g * kPartStride] = mm; part[g * kPartStride + 1] = ll; }
-  }
+  combine_streams_and_store<G, kStreams>(smem, part);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -385,16 +397,16 @@ __device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t
   blk = nv > 0 ? (uint32_t)pb >> 3 : 0u;
 }
 
-// One tile of kTileBf16 logical rows; each wave takes 64 of them in two steps of 32 keys.
+// One tile of `tile_rows` logical rows (a multiple of 128).  The tile is cut into steps of 32 keys;
+// wave w takes steps w, w+4, w+8, ... and keeps one step of loads in flight ahead of its arithmetic.
 // Scores S^T = K Q^T: the A operand is a K block piece (key-major), the B operand the query rows
 // (zero beyond G), so lane (q = lane % 16, j = lane / 16) ends with the scores of query head q for
 // the 8 rows of block j of the step -- which is exactly the B operand the second contraction
 // O^T += V^T P^T needs from that lane, so the weights never move between lanes.  The A operand of the
-// second contraction is a 16-byte piece of the transposed V block.  Nothing is staged through LDS.
+// second contraction is a 16-byte piece of the transposed V block.  No operand is staged through LDS.
 template <int G, bool DYN>
 __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* __restrict__ q, float scale_log2e,
-                                               int row0, float* __restrict__ part, float* smem) {
-  constexpr int NSTEP = kTileBf16 / 4 / 32;
+                                               int row0, int tile_rows, const PartOut& part, float* smem) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int qi = lane & 15, jv = lane >> 4, ja = qi >> 2, e1 = lane & 3;
 
@@ -405,44 +417,52 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     if (qi < G) t = ld16(reinterpret_cast<const char*>(q) + (size_t)qi * kD * 2 + (32 * s + 8 * jv) * 2);
     qb[s] = __builtin_bit_cast(bf16x8, t);
   }
-  const int wrow0 = __builtin_amdgcn_readfirstlane(row0 + wv * 32 * NSTEP);
-  uint32_t blk_a[NSTEP], blk_v[NSTEP];
-  int nv_v[NSTEP];
-#pragma unroll
-  for (int st = 0; st < NSTEP; ++st) {
-    int unused;
-    resolve_block<DYN>(rm, wrow0 + st * 32 + 8 * ja, blk_a[st], unused);
-    resolve_block<DYN>(rm, wrow0 + st * 32 + 8 * jv, blk_v[st], nv_v[st]);
-  }
+  const int rows_here = min(tile_rows, rm.n_rows - row0);
+  const int n_steps = (rows_here + 31) >> 5;
+  const uint32_t k_lane = (uint32_t)(jv * 4 + e1) * 16u, v_lane = (uint32_t)qi * 16u;
+
   floatx4 o[8];
 #pragma unroll
   for (int db = 0; db < 8; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
   float m = kNeg, lsum = 0.f;
 
-  // all of the wave's loads are issued before any arithmetic: a wave has at most 2 x 16 of them and
-  // a decode step is short enough that memory latency, not bandwidth, is what a wave waits for
-  uint4 ka[NSTEP][8], va[NSTEP][8];
+  uint4 ka[8], va[8];
+  int nv = 0;
+  int st = wv;                                           // wave-uniform
+  if (st < n_steps) {
+    uint32_t ba, bv;
+    int unused;
+    resolve_block<DYN>(rm, row0 + st * 32 + 8 * ja, ba, unused);
+    resolve_block<DYN>(rm, row0 + st * 32 + 8 * jv, bv, nv);
+    const char* kp = rm.kbase + (size_t)ba * kBlkBytes + k_lane;
+    const char* vp = rm.vbase + (size_t)bv * kBlkBytes + v_lane;
 #pragma unroll
-  for (int st = 0; st < NSTEP; ++st) {
-    if (wrow0 + st * 32 < rm.n_rows) {                   // wave-uniform
-      const char* kp = rm.kbase + (size_t)blk_a[st] * kBlkBytes + (jv * 4 + e1) * 16;
-      const char* vp = rm.vbase + (size_t)blk_v[st] * kBlkBytes + qi * 16;
+    for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ka[st][i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
-#pragma unroll
-      for (int i = 0; i < 8; ++i) va[st][i] = ld16(vp + i * 256);     // i = 16-dim block of the output
-    }
+    for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);     // i = 16-dim block of the output
   }
-#pragma unroll
-  for (int st = 0; st < NSTEP; ++st) {
-    if (wrow0 + st * 32 >= rm.n_rows) break;             // wave-uniform
+#pragma unroll 1
+  while (st < n_steps) {
     floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[st][2 * s]), qb[s], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[st][2 * s + 1]), qb[s], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[2 * s]), qb[s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[2 * s + 1]), qb[s], s1, 0, 0, 0);
     }
-    const int nv = nv_v[st];
+    // next step's addresses and K loads go out while this step's softmax and second contraction run
+    const int nst = st + 4;
+    const bool more = nst < n_steps;                     // wave-uniform
+    uint32_t bv_next = 0;
+    int nv_next = 0;
+    if (more) {
+      uint32_t ba;
+      int unused;
+      resolve_block<DYN>(rm, row0 + nst * 32 + 8 * ja, ba, unused);
+      resolve_block<DYN>(rm, row0 + nst * 32 + 8 * jv, bv_next, nv_next);
+      const char* kp = rm.kbase + (size_t)ba * kBlkBytes + k_lane;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);
+    }
     float sc[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -474,7 +494,14 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
     for (int db = 0; db < 8; ++db)
-      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[st][db]), pb, o[db], 0, 0, 0);
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), pb, o[db], 0, 0, 0);
+    if (more) {
+      const char* vp = rm.vbase + (size_t)bv_next * kBlkBytes + v_lane;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);
+    }
+    nv = nv_next;
+    st = nst;
   }
 
   lsum += lane_xor(lsum, 16);
@@ -488,21 +515,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
           make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
   }
   __syncthreads();
-  for (int idx = tid; idx < G * kD; idx += 256) {
-    const int g = idx >> 7, dd = idx & (kD - 1);
-    float mm = kNeg;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) mm = fmaxf(mm, smem[(w * G + g) * kPartStride]);
-    float ll = 0.f, oo = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float c = fast_exp2(smem[(w * G + g) * kPartStride] - mm);
-      ll = fmaf(smem[(w * G + g) * kPartStride + 1], c, ll);
-      oo = fmaf(smem[(w * G + g) * kPartStride + 4 + dd], c, oo);
-    }
-    part[g * kPartStride + 4 + dd] = oo;
-    if (dd == 0) { part[g * kPartStride] = mm; part[g * kPartStride + 1] = ll; }
-  }
+  combine_streams_and_store<G, 4>(smem, part);
 }
 
 constexpr int kNhbBf16 = kTileBf16 / 128;
@@ -515,10 +528,10 @@ template <typename T> __device__ __forceinline__ constexpr int tile_of() { retur
 
 template <typename T, int G, bool BLOCKED>
 __device__ __forceinline__ void run_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
-                                         float* __restrict__ part, float* smem) {
+                                         int tile_rows, const PartOut& part, float* smem) {
   if constexpr (sizeof(T) == 2 && BLOCKED) {
-    if (rm.dynamic) attn_tile_mfma<G, true>(rm, q, scale_log2e, row0, part, smem);
-    else attn_tile_mfma<G, false>(rm, q, scale_log2e, row0, part, smem);
+    if (rm.dynamic) attn_tile_mfma<G, true>(rm, q, scale_log2e, row0, tile_rows, part, smem);
+    else attn_tile_mfma<G, false>(rm, q, scale_log2e, row0, tile_rows, part, smem);
   } else if constexpr (sizeof(T) == 2) {
     attn_tile_bf16<G, kNhbBf16, false>(rm, q, scale_log2e, row0, part, smem);   // row-major rows, never gathered
   } else {
@@ -528,8 +541,11 @@ __device__ __forceinline__ void run_tile(const RowMap& rm, const T* __restrict__
 
 // Combine the n_tiles records of one (unit, query head) in tile order -- eight records per round
 // of independent loads -- and write the output row.  blockDim.x == 128, one thread per element.
+// o0 / ml0 point at the first tile's entries for this query head; consecutive tiles are rec_o floats
+// (resp. kMlStride floats) apart.
 template <typename T>
-__device__ __forceinline__ void merge_head(const float* __restrict__ p0, int n_tiles, int rec, T* __restrict__ out_row) {
+__device__ __forceinline__ void merge_head(const float* __restrict__ o0, const float* __restrict__ ml0, int n_tiles,
+                                           int rec_o, T* __restrict__ out_row) {
   const int dd = threadIdx.x;
   float M = kNeg, L = 0.f, O = 0.f;
   for (int t0 = 0; t0 < n_tiles; t0 += 8) {
@@ -537,8 +553,9 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ p0, int n_t
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const bool in = t0 + j < n_tiles;
-      const float* p = p0 + (size_t)(in ? t0 + j : t0) * rec;
-      mv[j] = in ? p[0] : kNeg; lv[j] = in ? p[1] : 0.f; ov[j] = in ? p[4 + dd] : 0.f;
+      const int t = in ? t0 + j : t0;
+      const float2 ml = *reinterpret_cast<const float2*>(ml0 + (size_t)t * kMlStride);
+      mv[j] = in ? ml.x : kNeg; lv[j] = in ? ml.y : 0.f; ov[j] = in ? o0[(size_t)t * rec_o + dd] : 0.f;
     }
     float bm = mv[0];
 #pragma unroll
@@ -691,9 +708,9 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
 template <typename T, int G>
 __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnItem& it, int layer_begin, int slot_base,
                                                const T* __restrict__ q, const T* __restrict__ k_new,
-                                               const T* __restrict__ v_new, float* __restrict__ partials, int t_arg,
+                                               const T* __restrict__ v_new, const PartOut& partials, int t_arg,
                                                float* smem) {
-  constexpr int TILE = tile_of<T>();
+  const int TILE = cv.tile_rows;
   constexpr int LPR = Elem<T>::kLanesPerRow;
   const int tid = threadIdx.x;
   const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
@@ -737,15 +754,16 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   rm.C = it.C;
   rm.tail_row = it.tail_row;
   const size_t qoff = (((size_t)lrel * cv.batch + it.seq) * cv.n_q_heads + (size_t)it.head * G) * kD;
-  float* part = partials + (size_t)(it.slot - slot_base) * G * kPartStride;
-  run_tile<T, G, true>(rm, q + qoff, cv.scale_log2e, it.row0, part, smem);
+  const PartOut part = {partials.o + (size_t)(it.slot - slot_base) * G * kD,
+                        partials.ml + (size_t)(it.slot - slot_base) * kMlStride};
+  run_tile<T, G, true>(rm, q + qoff, cv.scale_log2e, it.row0, TILE, part, smem);
 }
 
 template <typename T, int G>
-__global__ __launch_bounds__(256) void decode_a_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void decode_a_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn,
                                                        int sitem_begin, int slot_base, const T* __restrict__ q,
                                                        const T* __restrict__ k_new, const T* __restrict__ v_new,
-                                                       float* __restrict__ partials, int t_arg, int use_stored_sigma) {
+                                                       PartOut partials, int t_arg, int use_stored_sigma) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   if ((int)blockIdx.x < n_dyn) {
     const UnitDesc d = cv.dyn_descs[dyn_begin + blockIdx.x];
@@ -757,9 +775,9 @@ __global__ __launch_bounds__(256) void decode_a_kernel(CacheView cv, int layer_b
 }
 
 template <typename T, int G>
-__global__ __launch_bounds__(256) void decode_b_kernel(CacheView cv, int layer_begin, int ditem_begin, int slot_base,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void decode_b_kernel(CacheView cv, int layer_begin, int ditem_begin, int slot_base,
                                                        const T* __restrict__ q, const T* __restrict__ k_new,
-                                                       const T* __restrict__ v_new, float* __restrict__ partials,
+                                                       const T* __restrict__ v_new, PartOut partials,
                                                        int t_arg) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   const AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
@@ -769,7 +787,7 @@ __global__ __launch_bounds__(256) void decode_b_kernel(CacheView cv, int layer_b
 // grid = (units of the call) x G, block = 128 threads.
 template <typename T>
 __global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, int layer_begin, int unit_begin,
-                                                         int slot_base, const float* __restrict__ partials,
+                                                         int slot_base, PartOut partials,
                                                          T* __restrict__ out, int t_arg, int appending) {
   const int G = cv.G;
   const int u = unit_begin + blockIdx.x / G, g = blockIdx.x % G;
@@ -777,12 +795,13 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, int layer
   const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[layer];
   const int t = t_before + ((appending && t_before < cv.max_new) ? 1 : 0);
   const UnitDesc d = cv.units[u];
-  constexpr int TILE = tile_of<T>();
+  const int TILE = cv.tile_rows;
   const int n_tiles = (d.n_prompt_rows + t + TILE - 1) / TILE;
   const int lrel = layer - layer_begin;
-  const float* p0 = partials + ((size_t)(d.item_begin - slot_base) * G + g) * kPartStride;
+  const float* o0 = partials.o + ((size_t)(d.item_begin - slot_base) * G + g) * kD;
+  const float* ml0 = partials.ml + (size_t)(d.item_begin - slot_base) * kMlStride + 2 * g;
   T* orow = out + (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G + g) * kD;
-  merge_head<T>(p0, n_tiles, G * kPartStride, orow);
+  merge_head<T>(o0, ml0, n_tiles, G * kD, orow);
   // host-known tail: nobody reads the counter during this step, so it is updated in place; otherwise
   // other blocks of this launch may still read cnt_a, so the new value goes to cnt_b and a follow-up
   // kernel publishes it
@@ -805,7 +824,7 @@ __global__ void rewind_kernel(CacheView cv, int layer_begin, int layer_end) {
 template <typename T, int G>
 __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __restrict__ q,
                                                         const T* __restrict__ k, const T* __restrict__ v,
-                                                        float* __restrict__ partials) {
+                                                        PartOut partials) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   constexpr int TILE = tile_of<T>();
   const int unit = blockIdx.y;                       // (lrel * batch + b) * Hkv + h
@@ -822,13 +841,13 @@ __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __
   rm.stride = (uint32_t)fv.n_kv_heads * kD * sizeof(T);
   rm.dynamic = 0; rm.sel = nullptr; rm.n_sel_rows = 0; rm.c_log2 = 0; rm.C = rm.n_rows; rm.tail_row = rm.n_rows;
   const size_t qoff = (((size_t)lrel * fv.batch + b) * fv.n_q_heads + (size_t)h * G) * kD;
-  float* part = partials + ((size_t)unit * fv.n_tiles_max + blockIdx.x) * G * kPartStride;
-  run_tile<T, G, false>(rm, q + qoff, fv.scale_log2e, row0, part, smem);
+  const size_t slot = (size_t)unit * fv.n_tiles_max + blockIdx.x;
+  const PartOut part = {partials.o + slot * G * kD, partials.ml + slot * kMlStride};
+  run_tile<T, G, false>(rm, q + qoff, fv.scale_log2e, row0, TILE, part, smem);
 }
 
 template <typename T>
-__global__ __launch_bounds__(128) void full_merge_kernel(FullView fv, const float* __restrict__ partials,
-                                                         T* __restrict__ out) {
+__global__ __launch_bounds__(128) void full_merge_kernel(FullView fv, PartOut partials, T* __restrict__ out) {
   const int G = fv.G;
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int h = unit % fv.n_kv_heads;
@@ -837,9 +856,10 @@ __global__ __launch_bounds__(128) void full_merge_kernel(FullView fv, const floa
   const int n_rows = fv.cu[b + 1] - fv.cu[b];
   constexpr int TILE = tile_of<T>();
   const int n_tiles = (n_rows + TILE - 1) / TILE;
-  const float* p0 = partials + (((size_t)unit * fv.n_tiles_max) * G + g) * kPartStride;
+  const float* o0 = partials.o + (((size_t)unit * fv.n_tiles_max) * G + g) * kD;
+  const float* ml0 = partials.ml + (size_t)unit * fv.n_tiles_max * kMlStride + 2 * g;
   T* orow = out + (((size_t)lrel * fv.batch + b) * fv.n_q_heads + (size_t)h * G + g) * kD;
-  merge_head<T>(p0, n_tiles, G * kPartStride, orow);
+  merge_head<T>(o0, ml0, n_tiles, G * kD, orow);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -866,8 +886,9 @@ static size_t select_smem_bytes(int max_chunks) {
 template <typename T, int G>
 static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                                   int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
-                                  const void* k_new, const void* v_new, float* partials, int t_arg,
+                                  const void* k_new, const void* v_new, float* parts_o, float* parts_ml, int t_arg,
                                   int use_stored_sigma, int max_chunks, hipStream_t st) {
+  const PartOut partials = {parts_o, parts_ml};
   const size_t smem_attn = attn_smem_bytes<T, G, true>();
   const size_t smem_a = std::max(smem_attn, select_smem_bytes(max_chunks));
   static size_t attr_a = 0, attr_b = 0;      // per instantiation; the attribute is sticky for the process
@@ -895,22 +916,24 @@ static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_
 
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                          int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
-                         const void* k_new, const void* v_new, float* partials, int t_arg, int use_stored_sigma,
-                         int max_chunks, hipStream_t st) {
+                         const void* k_new, const void* v_new, float* parts_o, float* parts_ml, int t_arg,
+                         int use_stored_sigma, int max_chunks, hipStream_t st) {
   if (dtype == HKV_F32) {
     HKV_DISPATCH_G(cv.G, return (launch_decode_t<float, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
-                                                            ditem_begin, n_ditems, slot_base, q, k_new, v_new, partials,
-                                                            t_arg, use_stored_sigma, max_chunks, st)));
+                                                            ditem_begin, n_ditems, slot_base, q, k_new, v_new, parts_o,
+                                                            parts_ml, t_arg, use_stored_sigma, max_chunks, st)));
   } else {
     HKV_DISPATCH_G(cv.G, return (launch_decode_t<bf16_t, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
-                                                             ditem_begin, n_ditems, slot_base, q, k_new, v_new, partials,
-                                                             t_arg, use_stored_sigma, max_chunks, st)));
+                                                             ditem_begin, n_ditems, slot_base, q, k_new, v_new, parts_o,
+                                                             parts_ml, t_arg, use_stored_sigma, max_chunks, st)));
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int slot_base,
-                             const float* partials, void* out, int t_arg, int appending, hipStream_t st) {
+                             float* parts_o, float* parts_ml, void* out, int t_arg, int appending,
+                             hipStream_t st) {
+  const PartOut partials = {parts_o, parts_ml};
   const int upl = cv.batch * cv.n_kv_heads;
   const int n_blocks = (layer_end - layer_begin) * upl * cv.G;
   if (n_blocks <= 0) return hipSuccess;
@@ -934,8 +957,9 @@ hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hi
 }
 
 template <typename T, int G>
-static hipError_t launch_full_t(const FullView& fv, const void* q, const void* k, const void* v, float* partials,
-                                void* out, hipStream_t st) {
+static hipError_t launch_full_t(const FullView& fv, const void* q, const void* k, const void* v, float* parts_o,
+                                float* parts_ml, void* out, hipStream_t st) {
+  const PartOut partials = {parts_o, parts_ml};
   constexpr size_t smem = attn_smem_bytes<T, G, false>();
   static bool attr_set = false;
   if (!attr_set) {
@@ -947,18 +971,18 @@ static hipError_t launch_full_t(const FullView& fv, const void* q, const void* k
   const int n_units = fv.n_layers_call * fv.batch * fv.n_kv_heads;
   hipLaunchKernelGGL((full_attn_kernel<T, G>), dim3(fv.n_tiles_max, n_units), dim3(256), smem, st, fv, (const T*)q,
                      (const T*)k, (const T*)v, partials);
-  hipLaunchKernelGGL(full_merge_kernel<T>, dim3(n_units * G), dim3(128), 0, st, fv, (const float*)partials, (T*)out);
+  hipLaunchKernelGGL(full_merge_kernel<T>, dim3(n_units * G), dim3(128), 0, st, fv, partials, (T*)out);
   return hipGetLastError();
 }
 
 hipError_t launch_full_attn(const FullView& fv, int dtype, const void* q, const void* k, const void* v,
-                            float* partials, void* out, hipStream_t st) {
+                            float* parts_o, float* parts_ml, void* out, hipStream_t st) {
   const int n_units = fv.n_layers_call * fv.batch * fv.n_kv_heads;
   if (n_units <= 0 || fv.n_tiles_max <= 0) return hipSuccess;
   if (dtype == HKV_F32) {
-    HKV_DISPATCH_G(fv.G, return (launch_full_t<float, GG>(fv, q, k, v, partials, out, st)));
+    HKV_DISPATCH_G(fv.G, return (launch_full_t<float, GG>(fv, q, k, v, parts_o, parts_ml, out, st)));
   } else {
-    HKV_DISPATCH_G(fv.G, return (launch_full_t<bf16_t, GG>(fv, q, k, v, partials, out, st)));
+    HKV_DISPATCH_G(fv.G, return (launch_full_t<bf16_t, GG>(fv, q, k, v, parts_o, parts_ml, out, st)));
   }
   return hipErrorInvalidValue;
 }

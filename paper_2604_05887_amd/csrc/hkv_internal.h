@@ -11,9 +11,10 @@ namespace hkv {
 constexpr int kD = 128;          // head_dim
 constexpr int kMaxG = 8;         // query heads per KV head
 constexpr int kTileF32 = 128;    // logical rows per split-K work item of decode attention, fp32 path
-constexpr int kTileBf16 = 256;   // same, bf16 path (four waves x two 32-row half batches)
-inline constexpr int tile_rows(int dtype) { return dtype == HKV_BF16 ? kTileBf16 : kTileF32; }
-constexpr int kPartStride = 132; // floats per (work item, query head): m, l, 2 pad, o[128]
+constexpr int kTileBf16 = 256;   // same, bf16 rows read in place (full-KV kernel); smallest tile of a bf16 cache
+constexpr int kTileBf16Max = 1024;   // bf16 caches pick 256, 512 or 1024 rows per tile from the amount of work
+constexpr int kPartStride = 132; // floats per (stream, query head) in the shared-memory staging: m, l, 2 pad, o[128]
+constexpr int kMlFloats = 16;    // floats per split-K tile in the workspace's (max, sum) array: 8 query heads x 2
 constexpr int kKeysPerBlock = 512;   // keys one scoring block covers
 constexpr int kMaxScoreRows = 256;   // G * window upper bound
 constexpr int kFullMaxBatch = 256;
@@ -88,6 +89,7 @@ struct CacheView {
   void* k_rows;
   void* v_rows;
   int32_t n_layers, batch, n_q_heads, n_kv_heads, G, window, max_new, causal;
+  int32_t tile_rows;          // logical rows per split-K tile of this cache
   float scale_log2e;          // softmax scale * log2(e)
 };
 
@@ -98,10 +100,11 @@ struct CacheView {
 // length before the step if the host knows it, else -1 (device counters).
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                          int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
-                         const void* k_new, const void* v_new, float* partials, int t_arg, int use_stored_sigma,
-                         int max_chunks, hipStream_t st);
+                         const void* k_new, const void* v_new, float* parts_o, float* parts_ml, int t_arg,
+                         int use_stored_sigma, int max_chunks, hipStream_t st);
 hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int slot_base,
-                             const float* partials, void* out, int t_arg, int appending, hipStream_t st);
+                             float* parts_o, float* parts_ml, void* out, int t_arg, int appending,
+                             hipStream_t st);
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
 
 struct FullView {
@@ -111,7 +114,7 @@ struct FullView {
   float scale_log2e;
 };
 hipError_t launch_full_attn(const FullView& fv, int dtype, const void* q, const void* k, const void* v,
-                            float* partials, void* out, hipStream_t st);
+                            float* parts_o, float* parts_ml, void* out, hipStream_t st);
 
 // compress
 hipError_t launch_score(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,

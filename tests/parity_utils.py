@@ -120,7 +120,7 @@ def compare_compress(wl, dw, ocache, stats: Dict[str, float]) -> Dict[Tuple[int,
 
 
 def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float], layer_ranges=None,
-                           append: bool = True):
+                           append: bool = True, oracle_layers=None):
     """n_steps decode steps on both sides; the oracle takes the device's chunk summaries (they may
     differ from its own by one rounding) and, inside a tie band, the device's chunk picks."""
     L, Bn = wl.n_layers, wl.batch
@@ -162,7 +162,10 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
                 sel_over[key] = sel_gpu
                 stats["banded_chunk_picks"] = stats.get("banded_chunk_picks", 0) + 1
         ref, _ = O.decode_attn(ocache, wl.q_steps[s], wl.k_new[s] if append else None,
-                               wl.v_new[s] if append else None, sel_override=sel_over, mu_override=mu_dev)
+                               wl.v_new[s] if append else None, layers=oracle_layers, sel_override=sel_over,
+                               mu_override=mu_dev)
+        if oracle_layers is not None:       # the oracle only ran a sample of layers
+            got, ref = got[oracle_layers], ref[oracle_layers]
         err = np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
         stats["out_err"] = max(stats.get("out_err", 0.0), float(err.max()))
         assert err.max() <= OUT_TOL[wl.dtype], f"step {s}: output off by {err.max():.3e}"

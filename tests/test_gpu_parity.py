@@ -205,3 +205,55 @@ def test_tail_capacity_and_rewind():
     torch.cuda.synchronize()
     assert torch.equal(out, first)      # same state, same bits: the path is deterministic
     dw.cache.close()
+
+
+def test_cfg1_full_size_sampled_units():
+    """Config 1 at full size (28 layers, 8192 tokens) in the launch configuration bench.py times:
+    one hkv_compress and one hkv_decode_attn call over all layers.  The oracle runs on a seeded
+    sample of layers (all units of those layers, every step)."""
+    wl = make_workload(1, steps=4)
+    rng = np.random.default_rng(11)
+    layers = sorted(rng.choice(wl.n_layers, size=3, replace=False).tolist())
+    print(f"\n[cfg1 full] sampled layers {layers}", flush=True)
+    dw = runner.setup(wl)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    torch.cuda.synchronize()
+    ocfg, oplan = P.oracle_setup(wl)
+    ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers)
+    stats = {}
+    overrides = P.compare_compress(wl, dw, ocache, stats)
+    if overrides:
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers, keep_override=overrides)
+    P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers)
+    _say("cfg1 full", stats)
+    dw.cache.close()
+
+
+@pytest.mark.parametrize("chunk,k_chunks,shrink", [(8, 24, 2), (16, 300, 1)])
+def test_many_small_chunks_radix_path(chunk, k_chunks, shrink):
+    """Small chunks (the paper's example is 8 tokens) give more than 256 chunks per head, which takes
+    the radix-select path of the chunk top-k; k larger than 256 as well."""
+    wl = make_workload(1, n_layers=2, shrink=shrink, steps=3)
+    wl.chunk_size[:] = chunk
+    dyn = wl.head_type == 1
+    wl.budget[dyn] = chunk * k_chunks
+    stats = P.full_pipeline(wl)
+    n_c = -(-int(wl.seqlens[0]) // chunk)
+    assert n_c > 256
+    _say(f"chunk {chunk} k {k_chunks} n_c {n_c}", stats)
+
+
+@pytest.mark.parametrize("n_q,n_kv,window", [(4, 4, 48), (6, 2, 16), (10, 2, 8), (12, 2, 20)])
+def test_other_group_sizes_and_windows(n_q, n_kv, window):
+    """Group sizes 1, 3, 5, 6 and windows that are not 32 (G * w not a multiple of 32 included)."""
+    from hkv_synth import workloads as W
+    base = dict(W.CONFIGS[1])
+    base.update(name=f"g{n_q // n_kv}_w{window}", n_layers=2, n_q_heads=n_q, n_kv_heads=n_kv, window=window,
+                n_visual=[1200], n_text=[300], block=1200, steps=2)
+    W.CONFIGS[99] = base
+    try:
+        wl = make_workload(99, seed=3)
+    finally:
+        del W.CONFIGS[99]
+    stats = P.full_pipeline(wl)
+    _say(f"G{n_q // n_kv} w{window}", stats)
