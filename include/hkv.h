@@ -97,6 +97,13 @@ typedef struct {
   int32_t decode_tile_rows; /* rows per split-K tile of decode attention: 0 = chosen from the amount of
                                work; bf16 caches also accept 128, 256, 512 or 1024 (tuning knob; the
                                result does not depend on it beyond fp32 summation order) */
+  int32_t decode_dynamic;   /* how a decode step runs the dynamic heads: 1 = one workgroup per head does
+                               chunk selection, attention and the output inside the main launch;
+                               2 = chunk selection in the main launch, split-K tiles over many
+                               workgroups in a second launch; 3 = a single launch of split-K tiles, each
+                               repeating its head's chunk selection; 0 = 3 unless the repeated summary reads
+                               would exceed a quarter of a step's bytes, then 2
+                               (tuning knob, same results up to fp32 summation order) */
 } hkv_config;
 
 /* Per-prompt plan.  All arrays live in HOST memory and are only read during the call. */
@@ -176,6 +183,11 @@ HKV_API int hkv_plan_unit_info(const hkv_config* cfg, const hkv_plan* plan, int 
 HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int layer_end, int tail,
                          uint64_t* bytes);
 
+/* How decode steps of this cache run (decided at creation, see hkv_config.decode_tile_rows and
+ * decode_dynamic): *tile_rows = rows per split-K tile, *dynamic_mode = 1, 2 or 3 as described at
+ * hkv_config.decode_dynamic.  Either pointer may be NULL. */
+HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, int32_t* dynamic_mode);
+
 /* Test / debug access to one unit (synchronises `stream`, then copies).  `dst`/`src` are [host].
  * Export returns HKV_ENOSPACE if `bytes` is smaller than the item; *written gets its size. */
 HKV_API int hkv_cache_export(const hkv_cache* cache, int what, int seq, int layer, int head, void* dst,
@@ -195,10 +207,11 @@ HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end
 /* Optional per-kernel timing of hkv_decode_attn, for benchmarks.  After hkv_profile_enable every
  * decode call on this cache (up to max_calls) records HIP events between its kernels on the
  * call's own stream (no synchronisation).  hkv_profile_read waits for the recorded events, returns
- * the summed durations in milliseconds -- ms[0] first launch (chunk scoring and chunk top-k of the
- * dynamic heads together with the split-K attention of the static heads), ms[1] second launch
- * (split-K attention of the dynamic heads), ms[2] combination of the split-K tiles -- and the number
- * of calls summed, then starts over.
+ * the summed durations in milliseconds -- ms[0] main launch (chunk scoring and chunk top-k of the
+ * dynamic heads together with the split-K attention of the static heads; in dynamic modes 1 and 3
+ * also the dynamic heads' attention), ms[1] second launch (split-K attention of the dynamic heads,
+ * dynamic mode 2 only), ms[2] combination of the split-K tiles -- and the number of calls summed,
+ * then starts over.
  * hkv_profile_disable releases the events. */
 HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);
 HKV_API int hkv_profile_read(hkv_cache* cache, double* ms, int* n_calls);

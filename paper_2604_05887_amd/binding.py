@@ -26,7 +26,7 @@ HKV_ABI_VERSION = 1
 EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
-    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
+    "hkv_cache_decode_shape",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
     "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
@@ -43,7 +43,7 @@ class hkv_config(C.Structure):
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("dtype", C.c_int32), ("window", C.c_int32), ("chunk_size", C.c_int32),
                 ("score_causal", C.c_int32), ("max_new_tokens", C.c_int32), ("softmax_scale", C.c_float),
-                ("decode_tile_rows", C.c_int32)]
+                ("decode_tile_rows", C.c_int32), ("decode_dynamic", C.c_int32)]
 
 
 class hkv_plan(C.Structure):
@@ -78,6 +78,7 @@ def load_library() -> C.CDLL:
     lib.hkv_plan_unit_info.argtypes = [C.POINTER(hkv_config), C.POINTER(hkv_plan), i32, i32, i32,
                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_step_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_uint64)]
+    lib.hkv_cache_decode_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_export.argtypes = [vp, i32, i32, i32, i32, vp, sz, C.POINTER(sz), vp]
     lib.hkv_cache_import.argtypes = [vp, i32, i32, i32, i32, vp, sz, vp]
     lib.hkv_compress_from_scores.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -116,9 +117,9 @@ def _stream(stream) -> Optional[int]:
 
 def make_config(*, n_layers: int, n_q_heads: int, n_kv_heads: int, dtype: int, window: int, chunk_size: int = 32,
                 max_new_tokens: int = 0, head_dim: int = 128, score_causal: int = 0,
-                softmax_scale: float = 0.0, decode_tile_rows: int = 0) -> hkv_config:
+                softmax_scale: float = 0.0, decode_tile_rows: int = 0, decode_dynamic: int = 0) -> hkv_config:
     return hkv_config(C.sizeof(hkv_config), HKV_ABI_VERSION, n_layers, n_q_heads, n_kv_heads, head_dim, dtype,
-                      window, chunk_size, score_causal, max_new_tokens, softmax_scale, decode_tile_rows)
+                      window, chunk_size, score_causal, max_new_tokens, softmax_scale, decode_tile_rows, decode_dynamic)
 
 
 class PlanArrays:
@@ -230,6 +231,13 @@ def hkv_cache_step_bytes(handle: int, layer_begin: int, layer_end: int, tail: in
     return int(v.value)
 
 
+def hkv_cache_decode_shape(handle: int) -> Tuple[int, int]:
+    """(rows per split-K tile, dynamic mode) the cache's decode steps run with."""
+    t, m = C.c_int32(0), C.c_int32(0)
+    _check(load_library().hkv_cache_decode_shape(handle, C.byref(t), C.byref(m)), "hkv_cache_decode_shape")
+    return int(t.value), int(m.value)
+
+
 def hkv_profile_enable(handle: int, max_calls: int) -> None:
     _check(load_library().hkv_profile_enable(handle, max_calls), "hkv_profile_enable")
 
@@ -326,6 +334,9 @@ class HybridKVCache:
     def step_bytes(self, tail, layer_begin=0, layer_end=None):
         le = self.cfg.n_layers if layer_end is None else layer_end
         return hkv_cache_step_bytes(self.handle, layer_begin, le, tail)
+
+    def decode_shape(self):
+        return hkv_cache_decode_shape(self.handle)
 
     def rewind(self, stream=None):
         hkv_cache_rewind(self.handle, stream)

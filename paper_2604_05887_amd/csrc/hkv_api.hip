@@ -26,11 +26,13 @@ struct Layout {
   std::vector<int32_t> static_begin, dynamic_begin, item_begin, sitem_begin, ditem_begin;   // [n_layers + 1]
   std::vector<int32_t> cu;
   int64_t total_tokens = 0;
-  int32_t max_C = 0, max_rows_static = 0, max_chunks = 0;
+  int32_t max_C = 0, max_rows_static = 0, max_rows_dynamic = 0, max_chunks = 0;
+  int64_t step_bytes0 = 0, reselect_extra_bytes = 0;   // per step at an empty tail; extra summary reads of mode 3
+  int mode = 2;                    // how decode steps run the dynamic heads (hkv_config.decode_dynamic, resolved)
   // element counts
   int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
   // arena offsets (bytes)
-  size_t off_units = 0, off_sitems = 0, off_ditems = 0, off_static = 0, off_dynamic = 0, off_dyn_descs = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
+  size_t off_units = 0, off_sitems = 0, off_ditems = 0, off_static_descs = 0, off_static = 0, off_dynamic = 0, off_dyn_descs = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
          off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
   size_t ws_bytes = 0, ws_o_bytes = 0;
   int tile = 0;
@@ -52,6 +54,7 @@ int validate_config(const hkv_config* cfg) {
     const int t = cfg->decode_tile_rows;
     if (cfg->dtype != HKV_BF16 || (t != 128 && t != 256 && t != 512 && t != 1024)) return HKV_ESHAPE;
   }
+  if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 3) return HKV_EINVAL;
   if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
   return HKV_OK;
 }
@@ -137,6 +140,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
           d.type_ord = (int32_t)lo.dynamic_units.size();
           lo.dynamic_units.push_back(u);
           lo.max_chunks = std::max(lo.max_chunks, d.n_chunks);
+          lo.max_rows_dynamic = std::max(lo.max_rows_dynamic, d.n_prompt_rows + cfg->max_new_tokens);
           if (blocked && c < kBlkRows) return HKV_ESHAPE;     // bf16 caches gather whole 8-row blocks
           phys_rows = blocked ? (C + kBlkRows - 1) / kBlkRows * kBlkRows : C;
           d.tail_row = (int32_t)phys_rows;
@@ -144,6 +148,11 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
         {
           const int64_t cap = phys_rows + cfg->max_new_tokens;
           lo.n_rows += blocked ? (cap + kBlkRows - 1) / kBlkRows * kBlkRows : cap;
+        }
+        {
+          const int64_t R = (int64_t)kD * (blocked ? 2 : 4);
+          lo.step_bytes0 += 2 * R * d.n_prompt_rows + (ht == HKV_DYNAMIC ? R * d.n_chunks : 0);
+          if (ht == HKV_DYNAMIC) lo.reselect_extra_bytes += R * d.n_chunks * ((d.n_prompt_rows + tile - 1) / tile - 1);
         }
         d.item_begin = (int32_t)lo.n_items;
         d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + tile - 1) / tile);
@@ -161,6 +170,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
           it.layer = l; it.seq = b; it.head = h;
           it.tail_row = d.tail_row;
           it.slot = (int32_t)lo.n_items++;
+          it.unit_ord = ht == HKV_DYNAMIC ? d.type_ord : 0;
           (ht == HKV_DYNAMIC ? lo.ditems : lo.sitems).push_back(it);
         }
         if (lo.n_items > (int64_t)0x7fffff00) return HKV_ESHAPE;
@@ -181,6 +191,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
   lo.off_units = take(lo.units.size() * sizeof(UnitDesc));
   lo.off_sitems = take(std::max<size_t>(1, lo.sitems.size()) * sizeof(AttnItem));
   lo.off_ditems = take(std::max<size_t>(1, lo.ditems.size()) * sizeof(AttnItem));
+  lo.off_static_descs = take(std::max<size_t>(1, lo.static_units.size()) * sizeof(UnitDesc));
   lo.off_static = take(std::max<size_t>(1, lo.static_units.size()) * 4);
   lo.off_dynamic = take(std::max<size_t>(1, lo.dynamic_units.size()) * 4);
   lo.off_dyn_descs = take(std::max<size_t>(1, lo.dynamic_units.size()) * sizeof(UnitDesc));
@@ -207,18 +218,27 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 // Tile size: fp32 caches use 128 rows; bf16 caches start at 256 rows and double (up to 1024) while the
 // whole cache still yields at least 2048 tiles, so that small steps keep every CU busy and large
 // ones amortise the per-tile cost.
+// Dynamic heads: every dynamic tile repeats its head's chunk selection, so that the step is one launch
+// plus the combination, as long as the repeated reads of the chunk summaries stay below a quarter of
+// the step's bytes (they mostly hit the L2); with many small chunks the selection runs once per head
+// and the tiles follow in a second launch.
 int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
-  if (cfg && cfg->dtype != HKV_BF16) return plan_layout_tile(cfg, plan, lo, kTileF32);
-  if (cfg && cfg->decode_tile_rows != 0) return plan_layout_tile(cfg, plan, lo, cfg->decode_tile_rows);
-  int tile = kTileBf16;
-  int rc = plan_layout_tile(cfg, plan, lo, tile);
-  while (rc == HKV_OK && tile < kTileBf16Max) {
-    Layout next;
-    if (plan_layout_tile(cfg, plan, next, tile * 2) != HKV_OK || next.n_items < 2048) break;
-    tile *= 2;
-    lo = std::move(next);
+  int rc;
+  if (cfg && cfg->dtype != HKV_BF16) rc = plan_layout_tile(cfg, plan, lo, kTileF32);
+  else if (cfg && cfg->decode_tile_rows != 0) rc = plan_layout_tile(cfg, plan, lo, cfg->decode_tile_rows);
+  else {
+    int tile = kTileBf16;
+    rc = plan_layout_tile(cfg, plan, lo, tile);
+    while (rc == HKV_OK && tile < kTileBf16Max) {
+      Layout next;
+      if (plan_layout_tile(cfg, plan, next, tile * 2) != HKV_OK || next.n_items < 2048) break;
+      tile *= 2;
+      lo = std::move(next);
+    }
   }
-  return rc;
+  if (rc != HKV_OK) return rc;
+  lo.mode = cfg->decode_dynamic != 0 ? cfg->decode_dynamic : (4 * lo.reselect_extra_bytes <= lo.step_bytes0 ? 3 : 2);
+  return HKV_OK;
 }
 
 }  // namespace
@@ -283,6 +303,7 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   cv.units = reinterpret_cast<const UnitDesc*>(a + lo.off_units);
   cv.static_items = reinterpret_cast<const AttnItem*>(a + lo.off_sitems);
   cv.dynamic_items = reinterpret_cast<const AttnItem*>(a + lo.off_ditems);
+  cv.static_descs = reinterpret_cast<const UnitDesc*>(a + lo.off_static_descs);
   cv.static_units = reinterpret_cast<const int32_t*>(a + lo.off_static);
   cv.dynamic_units = reinterpret_cast<const int32_t*>(a + lo.off_dynamic);
   cv.dyn_descs = reinterpret_cast<const UnitDesc*>(a + lo.off_dyn_descs);
@@ -310,6 +331,11 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   up(lo.off_units, lo.units.data(), lo.units.size() * sizeof(UnitDesc));
   up(lo.off_sitems, lo.sitems.data(), lo.sitems.size() * sizeof(AttnItem));
   up(lo.off_ditems, lo.ditems.data(), lo.ditems.size() * sizeof(AttnItem));
+  {
+    std::vector<UnitDesc> sd;
+    for (int32_t u : lo.static_units) sd.push_back(lo.units[u]);
+    up(lo.off_static_descs, sd.data(), sd.size() * sizeof(UnitDesc));
+  }
   up(lo.off_static, lo.static_units.data(), lo.static_units.size() * 4);
   up(lo.off_dynamic, lo.dynamic_units.data(), lo.dynamic_units.size() * 4);
   {
@@ -434,6 +460,8 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   const int db = lo.dynamic_begin[lb], nd = lo.dynamic_begin[le] - db;
   const int sb = lo.sitem_begin[lb], ns = lo.sitem_begin[le] - sb;
   const int dib = lo.ditem_begin[lb], ndi = lo.ditem_begin[le] - dib;
+  const int sub = lo.static_begin[lb], nsu = lo.static_begin[le] - sub;
+  const int ub = lb * c->batch * c->cfg.n_kv_heads, nu = (le - lb) * c->batch * c->cfg.n_kv_heads;
   // tail length: when every layer of the call has the same one (the normal case) it travels as a
   // kernel argument; otherwise the kernels read the per-layer device counters
   int t_before = c->host_tail[lb];
@@ -442,14 +470,27 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   hipError_t e = hipSuccess;
   float* parts = static_cast<float*>(workspace);
   float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + lo.ws_o_bytes);
+  const int dt = c->cfg.dtype, app = k_new ? 1 : 0;
+  const int mode = lo.mode;
   if (ev) e = hipEventRecord(ev[0], st);
-  if (e == hipSuccess) e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, sb, ns, dib, 0, slot_base, q, k_new, v_new, parts,
-                                         parts_ml, t_before, 0, lo.max_chunks, st);
-  if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
-  if (e == hipSuccess) e = launch_decode(c->cv, c->cfg.dtype, lb, db, 0, sb, 0, dib, ndi, slot_base, q, k_new, v_new, parts,
-                                         parts_ml, t_before, 0, lo.max_chunks, st);
+  if (mode == 3) {
+    if (e == hipSuccess) e = launch_dynamic_tiles(c->cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts,
+                                                  parts_ml, t_before, 1, lo.max_chunks, st);
+    if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
+  } else {
+    if (e == hipSuccess) e = launch_decode(c->cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out,
+                                           t_before, 0, mode == 2 ? 1 : 0, lo.max_chunks, st);
+    if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
+    if (e == hipSuccess && mode == 2)
+      e = launch_dynamic_tiles(c->cv, dt, lb, dib, ndi, sb, 0, slot_base, q, k_new, v_new, parts, parts_ml, t_before, 0,
+                               lo.max_chunks, st);
+  }
   if (ev && e == hipSuccess) e = hipEventRecord(ev[2], st);
-  if (e == hipSuccess) e = launch_attn_merge(c->cv, c->cfg.dtype, lb, le, slot_base, parts, parts_ml, out, t_before, k_new ? 1 : 0, st);
+  if (e == hipSuccess)
+    e = mode == 1 ? launch_attn_merge(c->cv, dt, c->cv.static_descs + sub, nsu, lb, le, slot_base, parts, parts_ml, out,
+                                      t_before, app, st)
+                  : launch_attn_merge(c->cv, dt, c->cv.units + ub, nu, lb, le, slot_base, parts, parts_ml, out, t_before,
+                                      app, st);
   if (ev && e == hipSuccess) e = hipEventRecord(ev[3], st);
   if (e != hipSuccess) return HKV_EHIP;
   if (ev) c->prof_calls += 1;
@@ -462,8 +503,8 @@ int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
   if (rc != HKV_OK) return rc;
   const Layout& lo = c->lo;
   const int db = lo.dynamic_begin[lb], nd = lo.dynamic_begin[le] - db;
-  hipError_t e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, 0, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, -1, 1,
-                               lo.max_chunks, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr,
+                               nullptr, -1, 1, 1, lo.max_chunks, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;
 }
 
@@ -610,6 +651,13 @@ static int locate(const hkv_cache* c, int what, const UnitDesc* d, size_t& off, 
     }
     default: return HKV_EINVAL;
   }
+}
+
+int hkv_cache_decode_shape(const hkv_cache* c, int32_t* tile_rows, int32_t* dynamic_mode) {
+  if (!c) return HKV_EINVAL;
+  if (tile_rows) *tile_rows = c->lo.tile;
+  if (dynamic_mode) *dynamic_mode = c->lo.mode;
+  return HKV_OK;
 }
 
 int hkv_cache_export(const hkv_cache* c, int what, int seq, int layer, int head, void* dst, size_t bytes,

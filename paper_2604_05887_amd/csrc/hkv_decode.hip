@@ -1,9 +1,11 @@
 // Decode-step kernels of libhkv (gfx950):
-//   decode_a_kernel  dynamic heads: score all chunk summaries with the group-summed query and pick the
-//                    top-k chunks (paper, Appendix A, "KV Cache Retrieval for Dynamic Heads"); in the
-//                    same launch, split-K softmax attention over the static heads' compacted rows
-//   decode_b_kernel  split-K attention over the dynamic heads' gathered chunk rows
-//   attn_merge       log-sum-exp combination of the tiles in fixed order, cast to the output dtype
+//   decode_kernel    one launch for the whole step.  A block either owns a dynamic head: it scores all
+//                    chunk summaries with the group-summed query, picks the top-k chunks (paper,
+//                    Appendix A, "KV Cache Retrieval for Dynamic Heads"), attends the gathered rows tile
+//                    by tile and combines its own tiles into the output rows; or it owns one split-K
+//                    tile of a static head's compacted rows and leaves a record in the workspace
+//   attn_merge       log-sum-exp combination of the static heads' tiles in fixed order, cast to the
+//                    output dtype
 //   full_attn_kernel the same attention over caller-held, uncompressed K/V (comparison kernel)
 // The step's new K/V row is appended by the attention block whose tile contains it.
 //
@@ -579,15 +581,27 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ o0, const f
 // ------------------------------------------------------------------------------------------
 // hybrid cache kernels
 // ------------------------------------------------------------------------------------------
-// A decode step is three launches:
-//   A  decode_a_kernel: blocks [0, n_dyn) score and pick chunks for the dynamic units of the call,
-//      the remaining blocks run the attention tiles of the static units -- the two kinds of work do
-//      not depend on each other, so the selection latency hides behind the static heads' streaming;
-//   B  decode_b_kernel: attention tiles of the dynamic units (they need A's picks);
-//   C  attn_merge_kernel: combines every unit's tiles in tile order and moves the tail counter on.
-// The step's new K/V row is written by the one block whose tile contains it, before that block reads.
-// Tail length: t_arg >= 0 is the length before this step, known to the host; t_arg < 0 reads the
-// device counter cnt_a[layer] (written only by launch C).
+// A decode step runs in one of two shapes, fixed when the cache is laid out.
+// Fused (dynamic heads of moderate length):
+//   1  decode_kernel: blocks [0, n_dyn) each own one dynamic unit of the call -- chunk selection, then
+//      attention over all gathered rows, then the unit's output rows; the remaining blocks run the
+//      split-K tiles of the static units.  The two kinds of work do not depend on each other, and the
+//      dynamic blocks -- the longest dependent chains -- are dispatched first, so their latency hides
+//      behind the static heads' streaming.
+//   2  attn_merge_kernel over the static units only.
+// Split (large steps, bound by memory throughput):
+//   1  decode_kernel with the dynamic blocks stopping after the chunk selection,
+//   2  dynamic_tiles_kernel: split-K tiles of the dynamic units (they need the picks),
+//   3  attn_merge_kernel over all units.
+// Repeated selection (small steps, bound by the chain of dependent launches): one launch of
+// dynamic_tiles_kernel over all tiles, every dynamic tile repeating its head's chunk selection (the
+// summaries are a small fraction of the step and mostly come from the L2), then attn_merge_kernel
+// over all units.
+// The step's new K/V row is written by the one block whose tile contains it, before that block reads;
+// the block that owns the first tile of (sequence 0, head 0) moves the layer's tail counter on.
+// Tail length: t_arg >= 0 is the length before this step, known to the host, and the counter is
+// updated in place since nobody reads it; t_arg < 0 reads the device counter cnt_a[layer], the new
+// length goes to cnt_b, and a follow-up kernel publishes it once every reader is done.
 
 // Chunk scoring and chunk top-k of one dynamic unit; whole block (256 threads).
 template <typename T>
@@ -709,14 +723,15 @@ template <typename T, int G>
 __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnItem& it, int layer_begin, int slot_base,
                                                const T* __restrict__ q, const T* __restrict__ k_new,
                                                const T* __restrict__ v_new, const PartOut& partials, int t_arg,
-                                               float* smem) {
-  const int TILE = cv.tile_rows;
+                                               int TILE, float* smem) {
   constexpr int LPR = Elem<T>::kLanesPerRow;
   const int tid = threadIdx.x;
   const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
   const bool append = (k_new != nullptr) && (t_before < cv.max_new);
   RowMap rm;
   rm.n_rows = it.n_prompt_rows + t_before + (append ? 1 : 0);
+  if (it.row0 == 0 && it.seq == 0 && it.head == 0 && tid == 0)     // one block per layer moves the tail counter on
+    (t_arg >= 0 ? cv.cnt_a : cv.cnt_b)[it.layer] = t_before + (append ? 1 : 0);
   if (it.row0 >= rm.n_rows) return;          // tile reserved for tail growth, not reached yet
   const int lrel = it.layer - layer_begin;
   const int new_row = it.n_prompt_rows + t_before;          // logical index of the appended row
@@ -759,53 +774,116 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   run_tile<T, G, true>(rm, q + qoff, cv.scale_log2e, it.row0, TILE, part, smem);
 }
 
-template <typename T, int G>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void decode_a_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn,
-                                                       int sitem_begin, int slot_base, const T* __restrict__ q,
-                                                       const T* __restrict__ k_new, const T* __restrict__ v_new,
-                                                       PartOut partials, int t_arg, int use_stored_sigma) {
-  extern __shared__ __attribute__((aligned(16))) float smem[];
-  if ((int)blockIdx.x < n_dyn) {
-    const UnitDesc d = cv.dyn_descs[dyn_begin + blockIdx.x];
-    select_chunks_of_unit<T>(cv, d, d.layer - layer_begin, q, use_stored_sigma, smem);
-  } else {
-    const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_dyn)];
-    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, smem);
+// Combine the tiles [0, n_tiles) of one unit, whose records this block wrote itself, and write the G
+// output rows.  All 256 threads.
+template <typename T>
+__device__ __forceinline__ void merge_own_tiles(const PartOut& first, int n_tiles, int G, T* __restrict__ out_rows) {
+  for (int idx = threadIdx.x; idx < G * kD; idx += 256) {
+    const int g = idx >> 7;
+    float M = kNeg, L = 0.f, O = 0.f;
+    for (int t = 0; t < n_tiles; ++t) {
+      const float2 ml = *reinterpret_cast<const float2*>(first.ml + (size_t)t * kMlStride + 2 * g);
+      const float ov = first.o[(size_t)t * G * kD + idx];
+      const float Mn = fmaxf(M, ml.x);
+      const float c0 = fast_exp2(M - Mn), c1 = fast_exp2(ml.x - Mn);
+      L = L * c0 + ml.y * c1;
+      O = O * c0 + ov * c1;
+      M = Mn;
+    }
+    const float o = L > 0.f ? O / L : 0.f;
+    if constexpr (sizeof(T) == 4) reinterpret_cast<float*>(out_rows)[idx] = o;
+    else reinterpret_cast<uint16_t*>(out_rows)[idx] = f32_to_bf16_rne(o);
   }
 }
 
+constexpr int kWholeUnit = 1 << 28;   // tile size that covers any unit (row counts stay below 2^24)
+
 template <typename T, int G>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void decode_b_kernel(CacheView cv, int layer_begin, int ditem_begin, int slot_base,
-                                                       const T* __restrict__ q, const T* __restrict__ k_new,
-                                                       const T* __restrict__ v_new, PartOut partials,
-                                                       int t_arg) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin, int slot_base,
+                   const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new,
+                   PartOut partials, T* __restrict__ out, int t_arg, int use_stored_sigma, int select_only) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
-  const AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
-  attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, smem);
+  if ((int)blockIdx.x >= n_dyn) {
+    const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_dyn)];
+    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+    return;
+  }
+  const UnitDesc d = cv.dyn_descs[dyn_begin + blockIdx.x];
+  const int lrel = d.layer - layer_begin;
+  select_chunks_of_unit<T>(cv, d, lrel, q, use_stored_sigma, smem);
+  if (select_only) return;
+  // ---- the rest of the dynamic unit, in this block ----
+  __threadfence_block();
+  __syncthreads();                          // the picks are in memory before the tile code reads them
+  const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[d.layer];
+  const int t_after = t_before + ((k_new != nullptr && t_before < cv.max_new) ? 1 : 0);
+  // the matrix-core tile takes any number of rows, so the whole unit is one tile and one record;
+  // the fp32 tile has a fixed size
+  const int TILE = sizeof(T) == 2 ? kWholeUnit : cv.tile_rows;
+  const int n_tiles = sizeof(T) == 2 ? 1 : (d.n_prompt_rows + t_after + TILE - 1) / TILE;
+  AttnItem it;
+  it.kv_row_off = d.kv_row_off; it.sel_off = (int32_t)d.idx_off; it.n_prompt_rows = d.n_prompt_rows;
+  it.C = d.C; it.c_log2 = d.c_log2; it.dynamic = 1; it.layer = d.layer; it.seq = d.seq; it.head = d.head;
+  it.tail_row = d.tail_row;
+  for (int t = 0; t < n_tiles; ++t) {
+    if (t > 0) __syncthreads();             // the previous tile's staging area is free again
+    it.row0 = t * TILE;
+    it.slot = d.item_begin + t;
+    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, TILE, smem);
+  }
+  __threadfence_block();
+  __syncthreads();                          // this block's own records are visible to all its threads
+  const PartOut first = {partials.o + (size_t)(d.item_begin - slot_base) * G * kD,
+                         partials.ml + (size_t)(d.item_begin - slot_base) * kMlStride};
+  T* orow = out + (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G) * kD;
+  merge_own_tiles<T>(first, n_tiles, G, orow);
 }
 
-// grid = (units of the call) x G, block = 128 threads.
+// Split-K tiles of the dynamic units.  reselect = 0: the picks are already in memory (an earlier launch
+// made them).  reselect = 1: every block first repeats its unit's chunk selection, so that no launch
+// boundary is needed; all blocks of a unit compute and store identical picks.  In that shape the grid
+// also carries the static tiles: blocks [n_ditems, n_ditems + n_sitems).
+template <typename T, int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_ditems, int sitem_begin,
+                          int slot_base, const T* __restrict__ q, const T* __restrict__ k_new,
+                          const T* __restrict__ v_new, PartOut partials, int t_arg, int reselect) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  if ((int)blockIdx.x >= n_ditems) {
+    const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_ditems)];
+    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+    return;
+  }
+  const AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
+  if (reselect) {
+    const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
+    if (it.row0 >= it.n_prompt_rows + t_before + 1) return;     // tile not reached yet, with or without an append
+    const UnitDesc d = cv.dyn_descs[it.unit_ord];
+    select_chunks_of_unit<T>(cv, d, d.layer - layer_begin, q, 0, smem);
+    __threadfence_block();
+    __syncthreads();                        // the picks are in memory before the tile code reads them
+  }
+  attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+}
+
+// grid = n_units x G, block = 128 threads; descs points at the first unit's descriptor.
 template <typename T>
-__global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, int layer_begin, int unit_begin,
-                                                         int slot_base, PartOut partials,
+__global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, const UnitDesc* __restrict__ descs,
+                                                         int layer_begin, int slot_base, PartOut partials,
                                                          T* __restrict__ out, int t_arg, int appending) {
   const int G = cv.G;
-  const int u = unit_begin + blockIdx.x / G, g = blockIdx.x % G;
-  const int layer = u / (cv.batch * cv.n_kv_heads);
-  const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[layer];
+  const int g = blockIdx.x % G;
+  const UnitDesc d = descs[blockIdx.x / G];
+  const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[d.layer];
   const int t = t_before + ((appending && t_before < cv.max_new) ? 1 : 0);
-  const UnitDesc d = cv.units[u];
   const int TILE = cv.tile_rows;
   const int n_tiles = (d.n_prompt_rows + t + TILE - 1) / TILE;
-  const int lrel = layer - layer_begin;
+  const int lrel = d.layer - layer_begin;
   const float* o0 = partials.o + ((size_t)(d.item_begin - slot_base) * G + g) * kD;
   const float* ml0 = partials.ml + (size_t)(d.item_begin - slot_base) * kMlStride + 2 * g;
   T* orow = out + (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G + g) * kD;
   merge_head<T>(o0, ml0, n_tiles, G * kD, orow);
-  // host-known tail: nobody reads the counter during this step, so it is updated in place; otherwise
-  // other blocks of this launch may still read cnt_a, so the new value goes to cnt_b and a follow-up
-  // kernel publishes it
-  if (g == 0 && d.seq == 0 && d.head == 0 && threadIdx.x == 0) (t_arg >= 0 ? cv.cnt_a : cv.cnt_b)[layer] = t;
 }
 
 __global__ void publish_tail_kernel(CacheView cv, int layer_begin, int layer_end) {
@@ -885,65 +963,92 @@ static size_t select_smem_bytes(int max_chunks) {
 
 template <typename T, int G>
 static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
-                                  int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
-                                  const void* k_new, const void* v_new, float* parts_o, float* parts_ml, int t_arg,
-                                  int use_stored_sigma, int max_chunks, hipStream_t st) {
+                                  int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
+                                  float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma,
+                                  int select_only, int max_chunks, hipStream_t st) {
   const PartOut partials = {parts_o, parts_ml};
-  const size_t smem_attn = attn_smem_bytes<T, G, true>();
-  const size_t smem_a = std::max(smem_attn, select_smem_bytes(max_chunks));
-  static size_t attr_a = 0, attr_b = 0;      // per instantiation; the attribute is sticky for the process
-  if (smem_a > attr_a) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_a_kernel<T, G>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_a);
+  const size_t smem = std::max(attn_smem_bytes<T, G, true>(), select_smem_bytes(max_chunks));
+  static size_t attr = 0;      // per instantiation; the attribute is sticky for the process
+  if (smem > attr) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr_a = smem_a;
-  }
-  if (smem_attn > attr_b) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_b_kernel<T, G>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_attn);
-    if (e != hipSuccess) return e;
-    attr_b = smem_attn;
+    attr = smem;
   }
   if (n_dyn + n_sitems > 0)
-    hipLaunchKernelGGL((decode_a_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), smem_a, st, cv, layer_begin, dyn_begin,
-                       n_dyn, sitem_begin, slot_base, (const T*)q, (const T*)k_new, (const T*)v_new, partials, t_arg,
-                       use_stored_sigma);
-  if (n_ditems > 0)
-    hipLaunchKernelGGL((decode_b_kernel<T, G>), dim3(n_ditems), dim3(256), smem_attn, st, cv, layer_begin, ditem_begin,
-                       slot_base, (const T*)q, (const T*)k_new, (const T*)v_new, partials, t_arg);
+    hipLaunchKernelGGL((decode_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), smem, st, cv, layer_begin, dyn_begin,
+                       n_dyn, sitem_begin, slot_base, (const T*)q, (const T*)k_new, (const T*)v_new, partials, (T*)out,
+                       t_arg, use_stored_sigma, select_only);
   return hipGetLastError();
 }
 
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
-                         int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
-                         const void* k_new, const void* v_new, float* parts_o, float* parts_ml, int t_arg,
-                         int use_stored_sigma, int max_chunks, hipStream_t st) {
+                         int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
+                         float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma, int select_only,
+                         int max_chunks, hipStream_t st) {
   if (dtype == HKV_F32) {
     HKV_DISPATCH_G(cv.G, return (launch_decode_t<float, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
-                                                            ditem_begin, n_ditems, slot_base, q, k_new, v_new, parts_o,
-                                                            parts_ml, t_arg, use_stored_sigma, max_chunks, st)));
+                                                            slot_base, q, k_new, v_new, parts_o, parts_ml, out, t_arg,
+                                                            use_stored_sigma, select_only, max_chunks, st)));
   } else {
     HKV_DISPATCH_G(cv.G, return (launch_decode_t<bf16_t, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
-                                                             ditem_begin, n_ditems, slot_base, q, k_new, v_new, parts_o,
-                                                             parts_ml, t_arg, use_stored_sigma, max_chunks, st)));
+                                                             slot_base, q, k_new, v_new, parts_o, parts_ml, out, t_arg,
+                                                             use_stored_sigma, select_only, max_chunks, st)));
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int slot_base,
-                             float* parts_o, float* parts_ml, void* out, int t_arg, int appending,
-                             hipStream_t st) {
+template <typename T, int G>
+static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, int ditem_begin, int n_ditems,
+                                         int sitem_begin, int n_sitems, int slot_base, const void* q,
+                                         const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
+                                         int t_arg, int reselect, int max_chunks, hipStream_t st) {
   const PartOut partials = {parts_o, parts_ml};
-  const int upl = cv.batch * cv.n_kv_heads;
-  const int n_blocks = (layer_end - layer_begin) * upl * cv.G;
-  if (n_blocks <= 0) return hipSuccess;
-  if (dtype == HKV_F32)
-    hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0, st, cv, layer_begin, layer_begin * upl,
-                       slot_base, partials, (float*)out, t_arg, appending);
-  else
-    hipLaunchKernelGGL(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0, st, cv, layer_begin,
-                       layer_begin * upl, slot_base, partials, (bf16_t*)out, t_arg, appending);
-  if (t_arg < 0)
+  const size_t smem = std::max(attn_smem_bytes<T, G, true>(), reselect ? select_smem_bytes(max_chunks) : (size_t)0);
+  static size_t attr = 0;
+  if (smem > attr) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr = smem;
+  }
+  hipLaunchKernelGGL((dynamic_tiles_kernel<T, G>), dim3(n_ditems + n_sitems), dim3(256), smem, st, cv, layer_begin,
+                     ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new, (const T*)v_new,
+                     partials, t_arg, reselect);
+  return hipGetLastError();
+}
+
+hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
+                                int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
+                                const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
+                                int max_chunks, hipStream_t st) {
+  if (n_ditems + n_sitems <= 0) return hipSuccess;
+  if (dtype == HKV_F32) {
+    HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<float, GG>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
+                                                                   n_sitems, slot_base, q, k_new, v_new, parts_o,
+                                                                   parts_ml, t_arg, reselect, max_chunks, st)));
+  } else {
+    HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
+                                                                    n_sitems, slot_base, q, k_new, v_new, parts_o,
+                                                                    parts_ml, t_arg, reselect, max_chunks, st)));
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* descs, int n_units, int layer_begin,
+                             int layer_end, int slot_base, float* parts_o, float* parts_ml, void* out, int t_arg,
+                             int appending, hipStream_t st) {
+  const PartOut partials = {parts_o, parts_ml};
+  const int n_blocks = n_units * cv.G;
+  if (n_blocks > 0) {
+    if (dtype == HKV_F32)
+      hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0, st, cv, descs, layer_begin, slot_base,
+                         partials, (float*)out, t_arg, appending);
+    else
+      hipLaunchKernelGGL(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0, st, cv, descs, layer_begin, slot_base,
+                         partials, (bf16_t*)out, t_arg, appending);
+  }
+  if (t_arg < 0 && layer_end > layer_begin)
     hipLaunchKernelGGL(publish_tail_kernel, dim3((layer_end - layer_begin + 63) / 64), dim3(64), 0, st, cv, layer_begin,
                        layer_end);
   return hipGetLastError();

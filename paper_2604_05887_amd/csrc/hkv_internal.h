@@ -68,7 +68,8 @@ struct AttnItem {
   int32_t layer, seq, head;
   int32_t tail_row;     // physical row of the first appended decode token
   int32_t slot;         // global index of the tile's record in the split-K workspace
-  int32_t pad_[3];
+  int32_t unit_ord;     // dynamic: index of the unit's descriptor in dyn_descs
+  int32_t pad_[2];
 };
 
 struct CacheView {
@@ -78,6 +79,7 @@ struct CacheView {
   const int32_t* static_units;
   const int32_t* dynamic_units;
   const UnitDesc* dyn_descs;      // descriptors of the dynamic units in dynamic_units order
+  const UnitDesc* static_descs;   // descriptors of the static units in static_units order
   const uint8_t* is_visual;
   int32_t* cnt_a;             // [n_layers] tail length before the step in flight
   int32_t* cnt_b;             // [n_layers] tail length the step in flight attends
@@ -95,16 +97,20 @@ struct CacheView {
 
 // ---- launchers implemented in the kernel translation units (all asynchronous on `st`) ----
 // decode
-// One decode step over a layer range: launch A (chunk selection of the dynamic units + attention
-// tiles of the static units) and launch B (attention tiles of the dynamic units).  t_arg: tail
-// length before the step if the host knows it, else -1 (device counters).
+// The launches of a decode step over a layer range.  t_arg: tail length before the step if the host
+// knows it, else -1 (device counters).  select_only: the dynamic blocks stop after the chunk selection.
+// launch_attn_merge also publishes the new tail counters when t_arg < 0, so it runs last.
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
-                         int n_sitems, int ditem_begin, int n_ditems, int slot_base, const void* q,
-                         const void* k_new, const void* v_new, float* parts_o, float* parts_ml, int t_arg,
-                         int use_stored_sigma, int max_chunks, hipStream_t st);
-hipError_t launch_attn_merge(const CacheView& cv, int dtype, int layer_begin, int layer_end, int slot_base,
-                             float* parts_o, float* parts_ml, void* out, int t_arg, int appending,
-                             hipStream_t st);
+                         int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
+                         float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma, int select_only,
+                         int max_chunks, hipStream_t st);
+hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
+                                int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
+                                const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
+                                int max_chunks, hipStream_t st);
+hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* descs, int n_units, int layer_begin,
+                             int layer_end, int slot_base, float* parts_o, float* parts_ml, void* out, int t_arg,
+                             int appending, hipStream_t st);
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
 
 struct FullView {

@@ -172,9 +172,9 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
     return out
 
 
-def full_pipeline(wl, budget=None, head_type=None, causal=False, n_steps=None, layer_ranges=None):
+def full_pipeline(wl, budget=None, head_type=None, causal=False, n_steps=None, layer_ranges=None, **setup_kw):
     stats: Dict[str, float] = {}
-    dw = runner.setup(wl, budget=budget, head_type=head_type, score_causal=int(causal))
+    dw = runner.setup(wl, budget=budget, head_type=head_type, score_causal=int(causal), **setup_kw)
     ocfg, oplan = oracle_setup(wl, budget, head_type, causal)
     ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual)
     if layer_ranges:

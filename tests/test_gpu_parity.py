@@ -257,3 +257,33 @@ def test_other_group_sizes_and_windows(n_q, n_kv, window):
         del W.CONFIGS[99]
     stats = P.full_pipeline(wl)
     _say(f"G{n_q // n_kv} w{window}", stats)
+
+
+@pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
+def test_both_decode_shapes_for_dynamic_heads(dtype_cfg, mode, tile):
+    """Dynamic heads handled by one workgroup each (mode 1), by split-K tiles in a second launch
+    (mode 2) and by tiles that repeat the selection (mode 3) all match the oracle; bf16 (config 1 shape, heads spanning several tiles) and fp32
+    (config 0)."""
+    if dtype_cfg == 1:
+        wl = make_workload(1, n_layers=3, shrink=2, steps=4)
+    else:
+        wl = make_workload(0, n_layers=3, steps=4)
+    stats = P.full_pipeline(wl, decode_dynamic=mode, decode_tile_rows=tile)
+    _say(f"cfg{dtype_cfg} dynamic mode {mode} tile {tile}", stats)
+
+
+def test_decode_shape_is_reported_and_auto_rule():
+    wl = make_workload(1, n_layers=2, shrink=4, steps=1)
+    for mode in (1, 2, 3):
+        dw = runner.setup(wl, decode_dynamic=mode, upload_prompt=False)
+        assert dw.cache.decode_shape()[1] == mode
+        dw.cache.close()
+    dw = runner.setup(wl, upload_prompt=False)
+    tile, mode = dw.cache.decode_shape()
+    assert tile in (256, 512, 1024) and mode == 3      # 32-token chunks: summaries are cheap to re-read
+    dw.cache.close()
+    wl.chunk_size[:] = 8
+    wl.budget[wl.head_type == 1] = 1024
+    dw = runner.setup(wl, upload_prompt=False, decode_tile_rows=128)
+    assert dw.cache.decode_shape() == (128, 2)          # small chunks, many tiles: the selection runs once per head
+    dw.cache.close()
