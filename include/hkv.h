@@ -205,8 +205,9 @@ HKV_API int hkv_compress_from_scores(hkv_cache* cache, int layer_begin, int laye
 HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end, void* stream);
 
 /* Optional per-kernel timing of hkv_decode_attn, for benchmarks.  After hkv_profile_enable every
- * decode call on this cache (up to max_calls) records HIP events between its kernels on the
- * call's own stream (no synchronisation).  hkv_profile_read waits for the recorded events, returns
+ * decode call on this cache (up to max_calls) attaches a pair of HIP events to each of its kernels
+ * (the kernel's own start and stop time stamps; no synchronisation, no extra work on the stream).
+ * hkv_profile_read waits for the stream of the profiled calls, returns
  * the summed durations in milliseconds -- ms[0] main launch (chunk scoring and chunk top-k of the
  * dynamic heads together with the split-K attention of the static heads; in dynamic modes 1 and 3
  * also the dynamic heads' attention), ms[1] second launch (split-K attention of the dynamic heads,

@@ -24,6 +24,7 @@ struct Layout {
   int64_t n_items = 0;
   std::vector<int32_t> static_units, dynamic_units;
   std::vector<int32_t> static_begin, dynamic_begin, item_begin, sitem_begin, ditem_begin;   // [n_layers + 1]
+  std::vector<int64_t> dmu_begin;  // [n_layers + 1] summary bytes read by the dynamic tiles of the layers before
   std::vector<int32_t> cu;
   int64_t total_tokens = 0;
   int32_t max_C = 0, max_rows_static = 0, max_rows_dynamic = 0, max_chunks = 0;
@@ -90,13 +91,14 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 
   lo.units.resize((size_t)L * B * H);
   lo.static_begin.assign(L + 1, 0); lo.dynamic_begin.assign(L + 1, 0); lo.item_begin.assign(L + 1, 0);
-  lo.sitem_begin.assign(L + 1, 0); lo.ditem_begin.assign(L + 1, 0);
+  lo.sitem_begin.assign(L + 1, 0); lo.ditem_begin.assign(L + 1, 0); lo.dmu_begin.assign(L + 1, 0);
   for (int l = 0; l < L; ++l) {
     lo.static_begin[l] = (int32_t)lo.static_units.size();
     lo.dynamic_begin[l] = (int32_t)lo.dynamic_units.size();
     lo.item_begin[l] = (int32_t)lo.n_items;
     lo.sitem_begin[l] = (int32_t)lo.sitems.size();
     lo.ditem_begin[l] = (int32_t)lo.ditems.size();
+    lo.dmu_begin[l + 1] = lo.dmu_begin[l];
     for (int b = 0; b < B; ++b) {
       const int32_t C = lo.cu[b + 1] - lo.cu[b];
       for (int h = 0; h < H; ++h) {
@@ -170,7 +172,10 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
           it.layer = l; it.seq = b; it.head = h;
           it.tail_row = d.tail_row;
           it.slot = (int32_t)lo.n_items++;
-          it.unit_ord = ht == HKV_DYNAMIC ? d.type_ord : 0;
+          if (ht == HKV_DYNAMIC) {
+            it.n_chunks = d.n_chunks; it.k_sel = d.k_sel; it.aux_off = d.aux_off;
+            lo.dmu_begin[l + 1] += (int64_t)d.n_chunks * kD * (blocked ? 2 : 4);
+          }
           (ht == HKV_DYNAMIC ? lo.ditems : lo.sitems).push_back(it);
         }
         if (lo.n_items > (int64_t)0x7fffff00) return HKV_ESHAPE;
@@ -183,7 +188,8 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
   lo.item_begin[L] = (int32_t)lo.n_items;
   lo.sitem_begin[L] = (int32_t)lo.sitems.size();
   lo.ditem_begin[L] = (int32_t)lo.ditems.size();
-  if ((size_t)(256 + 8 + lo.max_chunks + 4) * 4 + (size_t)(lo.max_chunks + 4) * 8 > 150 * 1024) return HKV_ESHAPE;
+  // LDS of the chunk selection: histogram, scores, 64-bit keys and the picks of every chunk
+  if ((size_t)(256 + 8 + lo.max_chunks + 4) * 4 + (size_t)(lo.max_chunks + 4) * 12 > 150 * 1024) return HKV_ESHAPE;
 
   const size_t es = elem_size(cfg->dtype);
   size_t off = 0;
@@ -251,8 +257,11 @@ struct hkv_cache {
   char* arena;
   std::vector<int32_t> host_tail;     // [n_layers] appended tokens (host mirror of the device counter)
   std::vector<uint8_t> compressed;    // [n_layers]
-  std::vector<hipEvent_t> events;     // 4 per profiled decode call
+  std::vector<hipEvent_t> events;     // 6 per profiled decode call: start and stop of up to three kernels
   int prof_calls = 0, prof_max = 0;
+  int n_cus = 256;                    // compute units of the device the cache lives on
+  hipStream_t prof_stream = nullptr;  // stream of the profiled calls
+  std::vector<uint8_t> prof_mask;     // per profiled call: bit j set if kernel j was launched
 };
 
 extern "C" {
@@ -294,6 +303,12 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   if (cache_bytes < c->lo.arena_bytes) { delete c; return HKV_ENOSPACE; }
   c->cfg = *cfg;
   c->batch = plan->batch;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      c->n_cus = cus;
+  }
   c->arena = static_cast<char*>(cache_dev);
   c->host_tail.assign(cfg->n_layers, 0);
   c->compressed.assign(cfg->n_layers, 0);
@@ -364,7 +379,7 @@ int hkv_profile_disable(hkv_cache* c) {
 int hkv_profile_enable(hkv_cache* c, int max_calls) {
   if (!c || max_calls < 1 || max_calls > (1 << 20)) return HKV_EINVAL;
   hkv_profile_disable(c);
-  c->events.resize((size_t)4 * max_calls);
+  c->events.resize((size_t)6 * max_calls);
   for (size_t i = 0; i < c->events.size(); ++i) {
     if (hipEventCreate(&c->events[i]) != hipSuccess) {
       c->events.resize(i);
@@ -373,18 +388,20 @@ int hkv_profile_enable(hkv_cache* c, int max_calls) {
     }
   }
   c->prof_max = max_calls;
+  c->prof_mask.assign(max_calls, 0);
   return HKV_OK;
 }
 
 int hkv_profile_read(hkv_cache* c, double* ms, int* n_calls) {
   if (!c || !ms || !n_calls) return HKV_EINVAL;
   ms[0] = ms[1] = ms[2] = 0.0;
+  if (c->prof_calls > 0 && hipStreamSynchronize(c->prof_stream) != hipSuccess) return HKV_EHIP;
   for (int i = 0; i < c->prof_calls; ++i) {
-    hipEvent_t* e = &c->events[(size_t)4 * i];
-    if (hipEventSynchronize(e[3]) != hipSuccess) return HKV_EHIP;
+    hipEvent_t* e = &c->events[(size_t)6 * i];
     for (int j = 0; j < 3; ++j) {
+      if (!(c->prof_mask[i] >> j & 1)) continue;        // that kernel was not part of the call
       float t = 0.f;
-      if (hipEventElapsedTime(&t, e[j], e[j + 1]) != hipSuccess) return HKV_EHIP;
+      if (hipEventElapsedTime(&t, e[2 * j], e[2 * j + 1]) != hipSuccess) return HKV_EHIP;
       ms[j] += t;
     }
   }
@@ -466,34 +483,40 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   // kernel argument; otherwise the kernels read the per-layer device counters
   int t_before = c->host_tail[lb];
   for (int l = lb; l < le; ++l) if (c->host_tail[l] != t_before) t_before = -1;
-  hipEvent_t* ev = (c->prof_max > 0 && c->prof_calls < c->prof_max) ? &c->events[(size_t)4 * c->prof_calls] : nullptr;
+  hipEvent_t none[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  const bool prof = c->prof_max > 0 && c->prof_calls < c->prof_max;
+  hipEvent_t* ev = prof ? &c->events[(size_t)6 * c->prof_calls] : none;
   hipError_t e = hipSuccess;
   float* parts = static_cast<float*>(workspace);
   float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + lo.ws_o_bytes);
   const int dt = c->cfg.dtype, app = k_new ? 1 : 0;
   const int mode = lo.mode;
-  if (ev) e = hipEventRecord(ev[0], st);
   if (mode == 3) {
-    if (e == hipSuccess) e = launch_dynamic_tiles(c->cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts,
-                                                  parts_ml, t_before, 1, lo.max_chunks, st);
-    if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
+    // a grid that is resident in one round: the static tiles wait for the time the dynamic tiles' summary
+    // reads take at ~5 TB/s, in units of 512 clocks at ~2.4 GHz, at most 16
+    int hold = 0;
+    if (ndi > 0 && ndi + ns <= 3 * c->n_cus)
+      hold = (int)std::min<int64_t>(16, (lo.dmu_begin[le] - lo.dmu_begin[lb]) / 1070000);
+    e = launch_dynamic_tiles(c->cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, t_before, 1,
+                             hold, lo.max_chunks, st, ev[0], ev[1]);
   } else {
-    if (e == hipSuccess) e = launch_decode(c->cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out,
-                                           t_before, 0, mode == 2 ? 1 : 0, lo.max_chunks, st);
-    if (ev && e == hipSuccess) e = hipEventRecord(ev[1], st);
+    e = launch_decode(c->cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
+                      mode == 2 ? 1 : 0, lo.max_chunks, st, ev[0], ev[1]);
     if (e == hipSuccess && mode == 2)
       e = launch_dynamic_tiles(c->cv, dt, lb, dib, ndi, sb, 0, slot_base, q, k_new, v_new, parts, parts_ml, t_before, 0,
-                               lo.max_chunks, st);
+                               0, lo.max_chunks, st, ev[2], ev[3]);
   }
-  if (ev && e == hipSuccess) e = hipEventRecord(ev[2], st);
   if (e == hipSuccess)
     e = mode == 1 ? launch_attn_merge(c->cv, dt, c->cv.static_descs + sub, nsu, lb, le, slot_base, parts, parts_ml, out,
-                                      t_before, app, st)
+                                      t_before, app, st, ev[4], ev[5])
                   : launch_attn_merge(c->cv, dt, c->cv.units + ub, nu, lb, le, slot_base, parts, parts_ml, out, t_before,
-                                      app, st);
-  if (ev && e == hipSuccess) e = hipEventRecord(ev[3], st);
+                                      app, st, ev[4], ev[5]);
   if (e != hipSuccess) return HKV_EHIP;
-  if (ev) c->prof_calls += 1;
+  if (prof) {
+    c->prof_mask[c->prof_calls] = (uint8_t)(1 | ((mode == 2 && ndi > 0) ? 2 : 0) | ((mode == 1 ? nsu : nu) > 0 ? 4 : 0));
+    c->prof_calls += 1;
+    c->prof_stream = st;
+  }
   if (k_new) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
   return HKV_OK;
 }

@@ -13,6 +13,8 @@
 // much as by bandwidth: descriptors come in through scalar loads, every thread issues its global
 // loads in independent batches, and nothing walks a dependent chain longer than it must.
 #include "hkv_device.h"
+#include <hip/hip_ext.h>
+
 #include "hkv_internal.h"
 #include "hkv_select.h"
 
@@ -606,7 +608,8 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ o0, const f
 // Chunk scoring and chunk top-k of one dynamic unit; whole block (256 threads).
 template <typename T>
 __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const UnitDesc& d, int lrel,
-                                                      const T* __restrict__ q, int use_stored_sigma, float* dsm) {
+                                                      const T* __restrict__ q, int use_stored_sigma, float* dsm,
+                                                      int32_t* sel_lds = nullptr, bool to_memory = true) {
   constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = 256 / LPR;
   const int tid = threadIdx.x;
   uint32_t* hist = reinterpret_cast<uint32_t*>(dsm);         // [256]
@@ -654,7 +657,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
 #pragma unroll
         for (int e = 0; e < EPL; ++e) dot = fmaf(qf[e], mf[e], dot);
         dot = sum_lanes<LPR>(dot);
-        if (ch < n_c && sub == 0) { sig[ch] = dot; cv.sigma[d.aux_off + ch] = dot; }
+        if (ch < n_c && sub == 0) { sig[ch] = dot; if (to_memory) cv.sigma[d.aux_off + ch] = dot; }
       }
     }
   } else {
@@ -664,33 +667,48 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
 
   // top-k chunks, ties to the lower chunk id, emitted ascending by chunk id
   if (n_c <= 256) {
-    // rank by counting over 64-bit keys (score order, then lower id first): chunk i is picked iff
-    // fewer than k keys exceed its own
-    const int i = tid;
-    unsigned long long mine = 0;
-    if (i < n_c4) {
-      if (i < n_c) mine = ((unsigned long long)float_order_key(sig[i]) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
-      key64[i] = mine;                                   // padding entries are 0: below every real key
-    }
-    __syncthreads();
-    int rank = 0;
-    for (int j0 = 0; j0 < n_c4; j0 += 16) {              // eight independent 16-byte LDS reads per round
-      ulonglong2 kj[8];
+    // Every wave holds all keys (four per lane) and finds the k-th largest key value by a bitwise search
+    // on wave-wide vote counts -- no barrier, no memory traffic; the four waves do the same arithmetic.
+    // Chunks with a key above it are picked, those equal to it in chunk order up to the k-th place.
+    const int lane = tid & 63, wv = tid >> 6;
+    const int k = d.k_sel;
+    uint32_t key[4];
 #pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const int j = min(j0 + 2 * x, n_c4 - 2);         // a repeated pair is weighted 0 below
-        kj[x] = *reinterpret_cast<const ulonglong2*>(key64 + j);
-      }
+    for (int m = 0; m < 4; ++m) {
+      const int ch = lane + 64 * m;
+      key[m] = ch < n_c ? float_order_key(sig[ch]) : 0u;   // 0 is below every candidate threshold
+    }
+    uint32_t thr = 0;
+#pragma unroll 4
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = thr | (1u << bit);
+      int cnt = 0;
 #pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const int in = (j0 + 2 * x < n_c4) ? 1 : 0;
-        rank += (kj[x].x > mine ? in : 0) + (kj[x].y > mine ? in : 0);
+      for (int m = 0; m < 4; ++m) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[m] >= cand));
+      if (cnt >= k) thr = cand;                             // wave-uniform
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int n_gt = 0, gt_before = 0, eq_before = 0;
+    bool is_gt = false, is_eq = false;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const unsigned long long gtb = __builtin_amdgcn_ballot_w64(key[m] > thr);
+      const unsigned long long eqb = __builtin_amdgcn_ballot_w64(key[m] == thr && lane + 64 * m < n_c);
+      n_gt += __builtin_popcountll(gtb);
+      if (m < wv) { gt_before += __builtin_popcountll(gtb); eq_before += __builtin_popcountll(eqb); }
+      if (m == wv) {                                       // this thread's own chunk is 64 * wv + lane
+        gt_before += __builtin_popcountll(gtb & below);
+        eq_before += __builtin_popcountll(eqb & below);
+        is_gt = (gtb >> lane) & 1ull;
+        is_eq = (eqb >> lane) & 1ull;
       }
     }
-    const int keep = (i < n_c && rank < d.k_sel) ? 1 : 0;
-    int tot;
-    const int pos = block_exclusive_scan<256>(keep, scan, &tot);
-    if (keep) cv.sel[d.idx_off + pos] = i;
+    const int r_adm = k - n_gt;                            // >= 1 places left for keys equal to the threshold
+    if (is_gt || (is_eq && eq_before < r_adm)) {
+      const int pos = gt_before + min(eq_before, r_adm);   // picks with a lower chunk id
+      if (to_memory) cv.sel[d.idx_off + pos] = tid;
+      if (sel_lds) sel_lds[pos] = tid;
+    }
     return;
   }
   uint32_t T_key = 0;
@@ -712,7 +730,10 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     const int eq_rank = base_eq + block_exclusive_scan<256>(eq, scan, &tot_eq);
     const int keep = gt | (eq & (eq_rank < r_adm ? 1 : 0));
     const int pos = base_keep + block_exclusive_scan<256>(keep, scan, &tot_keep);
-    if (keep && pos < d.k_sel) cv.sel[d.idx_off + pos] = ch;
+    if (keep && pos < d.k_sel) {
+      if (to_memory) cv.sel[d.idx_off + pos] = ch;
+      if (sel_lds) sel_lds[pos] = ch;
+    }
     base_eq += tot_eq;
     base_keep += tot_keep;
   }
@@ -723,7 +744,7 @@ template <typename T, int G>
 __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnItem& it, int layer_begin, int slot_base,
                                                const T* __restrict__ q, const T* __restrict__ k_new,
                                                const T* __restrict__ v_new, const PartOut& partials, int t_arg,
-                                               int TILE, float* smem) {
+                                               int TILE, float* smem, const int32_t* sel_override = nullptr) {
   constexpr int LPR = Elem<T>::kLanesPerRow;
   const int tid = threadIdx.x;
   const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
@@ -763,7 +784,7 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   rm.vbase = reinterpret_cast<const char*>(cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.stride = kD * sizeof(T);
   rm.dynamic = it.dynamic;
-  rm.sel = cv.sel + it.sel_off;
+  rm.sel = sel_override ? sel_override : cv.sel + it.sel_off;
   rm.n_sel_rows = it.n_prompt_rows;
   rm.c_log2 = it.c_log2;
   rm.C = it.C;
@@ -843,28 +864,41 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
 // Split-K tiles of the dynamic units.  reselect = 0: the picks are already in memory (an earlier launch
 // made them).  reselect = 1: every block first repeats its unit's chunk selection, so that no launch
 // boundary is needed; all blocks of a unit compute and store identical picks.  In that shape the grid
-// also carries the static tiles: blocks [n_ditems, n_ditems + n_sitems).
+// also carries the static tiles: blocks [n_ditems, n_ditems + n_sitems), which wait static_hold x 512
+// clocks before their first loads.
 template <typename T, int G>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_ditems, int sitem_begin,
                           int slot_base, const T* __restrict__ q, const T* __restrict__ k_new,
-                          const T* __restrict__ v_new, PartOut partials, int t_arg, int reselect) {
+                          const T* __restrict__ v_new, PartOut partials, int t_arg, int reselect, int lds_sel_off,
+                          int static_hold) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   if ((int)blockIdx.x >= n_ditems) {
     const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_ditems)];
+    // When the whole grid is resident at once, every block asks for its first rows at the same moment and
+    // the dynamic heads' summary reads -- the head of the longest dependent chain of the launch -- queue
+    // behind all of them.  The static tiles therefore start a little later: static_hold x 512 clocks,
+    // the time the summaries need on the memory system (0 for grids of several rounds).
+    for (int i = 0; i < static_hold; ++i) __builtin_amdgcn_s_sleep(8);
     attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
     return;
   }
   const AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
+  const int32_t* picks = nullptr;
   if (reselect) {
     const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
     if (it.row0 >= it.n_prompt_rows + t_before + 1) return;     // tile not reached yet, with or without an append
-    const UnitDesc d = cv.dyn_descs[it.unit_ord];
-    select_chunks_of_unit<T>(cv, d, d.layer - layer_begin, q, 0, smem);
-    __threadfence_block();
-    __syncthreads();                        // the picks are in memory before the tile code reads them
+    UnitDesc d;                                                 // the fields the selection reads
+    d.aux_off = it.aux_off; d.idx_off = it.sel_off; d.n_chunks = it.n_chunks; d.k_sel = it.k_sel;
+    d.seq = it.seq; d.head = it.head;
+    int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
+    // the picks stay in LDS for this block's own tile; the first tile also leaves them (and the chunk
+    // scores) in memory for export
+    select_chunks_of_unit<T>(cv, d, it.layer - layer_begin, q, 0, smem, sel_lds, it.row0 == 0);
+    __syncthreads();
+    picks = sel_lds;
   }
-  attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+  attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem, picks);
 }
 
 // grid = n_units x G, block = 128 threads; descs points at the first unit's descriptor.
@@ -965,7 +999,7 @@ template <typename T, int G>
 static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                                   int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
                                   float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma,
-                                  int select_only, int max_chunks, hipStream_t st) {
+                                  int select_only, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const PartOut partials = {parts_o, parts_ml};
   const size_t smem = std::max(attn_smem_bytes<T, G, true>(), select_smem_bytes(max_chunks));
   static size_t attr = 0;      // per instantiation; the attribute is sticky for the process
@@ -976,24 +1010,24 @@ static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_
     attr = smem;
   }
   if (n_dyn + n_sitems > 0)
-    hipLaunchKernelGGL((decode_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), smem, st, cv, layer_begin, dyn_begin,
-                       n_dyn, sitem_begin, slot_base, (const T*)q, (const T*)k_new, (const T*)v_new, partials, (T*)out,
-                       t_arg, use_stored_sigma, select_only);
+    hipExtLaunchKernelGGL((decode_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1, 0u, cv,
+                          layer_begin, dyn_begin, n_dyn, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
+                          (const T*)v_new, partials, (T*)out, t_arg, use_stored_sigma, select_only);
   return hipGetLastError();
 }
 
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                          int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
                          float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma, int select_only,
-                         int max_chunks, hipStream_t st) {
+                         int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (dtype == HKV_F32) {
     HKV_DISPATCH_G(cv.G, return (launch_decode_t<float, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
                                                             slot_base, q, k_new, v_new, parts_o, parts_ml, out, t_arg,
-                                                            use_stored_sigma, select_only, max_chunks, st)));
+                                                            use_stored_sigma, select_only, max_chunks, st, ev0, ev1)));
   } else {
     HKV_DISPATCH_G(cv.G, return (launch_decode_t<bf16_t, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
                                                              slot_base, q, k_new, v_new, parts_o, parts_ml, out, t_arg,
-                                                             use_stored_sigma, select_only, max_chunks, st)));
+                                                             use_stored_sigma, select_only, max_chunks, st, ev0, ev1)));
   }
   return hipErrorInvalidValue;
 }
@@ -1002,9 +1036,12 @@ template <typename T, int G>
 static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, int ditem_begin, int n_ditems,
                                          int sitem_begin, int n_sitems, int slot_base, const void* q,
                                          const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
-                                         int t_arg, int reselect, int max_chunks, hipStream_t st) {
+                                         int t_arg, int reselect, int static_hold, int max_chunks, hipStream_t st,
+                                         hipEvent_t ev0, hipEvent_t ev1) {
   const PartOut partials = {parts_o, parts_ml};
-  const size_t smem = std::max(attn_smem_bytes<T, G, true>(), reselect ? select_smem_bytes(max_chunks) : (size_t)0);
+  // reselect: selection scratch and the tile's staging area share the front; the picks sit behind both
+  const size_t front = std::max(attn_smem_bytes<T, G, true>(), reselect ? select_smem_bytes(max_chunks) : (size_t)0);
+  const size_t smem = front + (reselect ? (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t) : 0);
   static size_t attr = 0;
   if (smem > attr) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G>),
@@ -1012,41 +1049,41 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
     if (e != hipSuccess) return e;
     attr = smem;
   }
-  hipLaunchKernelGGL((dynamic_tiles_kernel<T, G>), dim3(n_ditems + n_sitems), dim3(256), smem, st, cv, layer_begin,
-                     ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new, (const T*)v_new,
-                     partials, t_arg, reselect);
+  hipExtLaunchKernelGGL((dynamic_tiles_kernel<T, G>), dim3(n_ditems + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1,
+                        0u, cv, layer_begin, ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
+                        (const T*)v_new, partials, t_arg, reselect, (int)(front / sizeof(float)), static_hold);
   return hipGetLastError();
 }
 
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
                                 const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
-                                int max_chunks, hipStream_t st) {
+                                int static_hold, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (n_ditems + n_sitems <= 0) return hipSuccess;
   if (dtype == HKV_F32) {
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<float, GG>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
                                                                    n_sitems, slot_base, q, k_new, v_new, parts_o,
-                                                                   parts_ml, t_arg, reselect, max_chunks, st)));
+                                                                   parts_ml, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
   } else {
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
                                                                     n_sitems, slot_base, q, k_new, v_new, parts_o,
-                                                                    parts_ml, t_arg, reselect, max_chunks, st)));
+                                                                    parts_ml, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* descs, int n_units, int layer_begin,
                              int layer_end, int slot_base, float* parts_o, float* parts_ml, void* out, int t_arg,
-                             int appending, hipStream_t st) {
+                             int appending, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const PartOut partials = {parts_o, parts_ml};
   const int n_blocks = n_units * cv.G;
   if (n_blocks > 0) {
     if (dtype == HKV_F32)
-      hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0, st, cv, descs, layer_begin, slot_base,
-                         partials, (float*)out, t_arg, appending);
+      hipExtLaunchKernelGGL(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0u, st, ev0, ev1, 0u, cv, descs,
+                            layer_begin, slot_base, partials, (float*)out, t_arg, appending);
     else
-      hipLaunchKernelGGL(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0, st, cv, descs, layer_begin, slot_base,
-                         partials, (bf16_t*)out, t_arg, appending);
+      hipExtLaunchKernelGGL(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0u, st, ev0, ev1, 0u, cv, descs,
+                            layer_begin, slot_base, partials, (bf16_t*)out, t_arg, appending);
   }
   if (t_arg < 0 && layer_end > layer_begin)
     hipLaunchKernelGGL(publish_tail_kernel, dim3((layer_end - layer_begin + 63) / 64), dim3(64), 0, st, cv, layer_begin,

@@ -117,4 +117,25 @@ template <int NT> __device__ __forceinline__ int block_exclusive_scan(int v, int
   return res;
 }
 
+// Block-wide exclusive count of set flags for blockDim.x == NT (multiple of 64): the number of threads
+// with a lower index whose flag is set; *total gets the block count.  `smem` holds NT/64 ints.  One
+// barrier; the caller separates two uses of the same `smem` by a barrier of its own.
+template <int NT> __device__ __forceinline__ int block_exclusive_count(bool flag, int* smem, int* total) {
+  constexpr int NW = NT / 64;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const unsigned long long b = __builtin_amdgcn_ballot_w64(flag);
+  const int pre = __builtin_popcountll(b & ((1ull << lane) - 1ull));
+  if (lane == 0) smem[wv] = __builtin_popcountll(b);
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    const int t = smem[i];
+    base += i < wv ? t : 0;
+    tot += t;
+  }
+  *total = tot;
+  return base + pre;
+}
+
 }  // namespace hkv

@@ -68,8 +68,11 @@ struct AttnItem {
   int32_t layer, seq, head;
   int32_t tail_row;     // physical row of the first appended decode token
   int32_t slot;         // global index of the tile's record in the split-K workspace
-  int32_t unit_ord;     // dynamic: index of the unit's descriptor in dyn_descs
-  int32_t pad_[2];
+  int32_t n_chunks;     // dynamic: chunks of the prompt
+  int32_t k_sel;        // dynamic: chunks attended per step
+  int32_t pad_;
+  int64_t aux_off;      // dynamic: first chunk's offset into sigma[] / mu[]
+  int64_t pad2_;
 };
 
 struct CacheView {
@@ -100,17 +103,19 @@ struct CacheView {
 // The launches of a decode step over a layer range.  t_arg: tail length before the step if the host
 // knows it, else -1 (device counters).  select_only: the dynamic blocks stop after the chunk selection.
 // launch_attn_merge also publishes the new tail counters when t_arg < 0, so it runs last.
+// ev0 / ev1 (both or neither) receive the kernel's own start and stop time stamps.
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                          int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
                          float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma, int select_only,
-                         int max_chunks, hipStream_t st);
+                         int max_chunks, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
                                 const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
-                                int max_chunks, hipStream_t st);
+                                int static_hold, int max_chunks, hipStream_t st, hipEvent_t ev0 = nullptr,
+                                hipEvent_t ev1 = nullptr);
 hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* descs, int n_units, int layer_begin,
                              int layer_end, int slot_base, float* parts_o, float* parts_ml, void* out, int t_arg,
-                             int appending, hipStream_t st);
+                             int appending, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
 
 struct FullView {
