@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-kv", action="store_true", help="skip the full-KV comparison kernel")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="keep the library's default way of running the dynamic heads instead of timing all three")
+    ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read reference")
     ap.add_argument("--no-layerwise", action="store_true", help="skip the one-call-per-layer timing")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device copies of a known size (for scaling HBM byte counters)")
@@ -169,6 +172,18 @@ def main() -> int:
     for dw in copies:                      # tail pre-roll (setup, untimed)
         for i in range(preroll):
             raw_step(dw, i)
+
+    # ---- how the dynamic heads run: time the three shapes on this workload, keep the fastest (setup) ----
+    tuned_us = None
+    if args.dynamic_mode == 0 and not args.no_tune:
+        def probe_step(dw, i):
+            j = i % n_inputs
+            st = lib.hkv_decode_attn(dw.cache.handle, 0, L, q_all[j].data_ptr(), None, None, out.data_ptr(),
+                                     dw.cache.workspace.data_ptr(), dw.cache.workspace_bytes, sptr)
+            if st != 0:
+                raise B.HkvError(st, "hkv_decode_attn")
+        tuned = runner.tune_decode_dynamic(copies, probe_step, steps=max(12, min(48, K)))
+        tuned_us = {str(m): round(v, 2) for m, v in tuned.items()}
     for i in range(W):                     # warm-up
         raw_step(copies[i % n_copies], i)
     torch.cuda.synchronize()
@@ -225,6 +240,15 @@ def main() -> int:
         b_bytes = 0
     a_gbs = a_bytes / (a_us * 1e-6) / 1e9
     b_gbs = b_bytes / (b_us * 1e-6) / 1e9 if b_bytes else 0.0
+
+    # ---- reference: a kernel that only reads as many bytes as the main launch does (launch ramp included) ----
+    probe_us = None
+    if not args.no_probe:
+        probe_bytes = max(int(a_bytes), 1 << 20)
+        pbuf = torch.empty(min(max(8 * probe_bytes, 5 * MALL_BYTES // 4), 8 << 30), dtype=torch.uint8, device=dev).fill_(3)
+        torch.cuda.synchronize()
+        probe_us = B.hkv_probe_stream_read(pbuf.data_ptr(), pbuf.numel(), min(probe_bytes, pbuf.numel()), 24, sptr)
+        del pbuf
 
     # ---- layer-by-layer driving (one call per layer, as a model interleaves them with its other layers) ----
     lw_us = None
@@ -361,14 +385,16 @@ def main() -> int:
         "speedup_vs_full_kv": round(full_ms / ms_per_step, 3),
         "compress_ms": round(compress_ms, 3),
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
-        "decode_shape": {"tile_rows": tile_rows, "dynamic_mode": dyn_mode},
+        "decode_shape": {"tile_rows": tile_rows, "dynamic_mode": dyn_mode, "tuned_us_per_step": tuned_us},
         "kernel_us": {"main_launch": round(a_us, 2), "second_launch": round(b_us, 2),
                       "attn_merge_kernel": round(merge_us, 2)},
         "dynamic_tiles_gbs": round(b_gbs, 1),
         "roofline": {"kernel": "dynamic_tiles_kernel" if dyn_mode == 3 else "decode_kernel", "bound": "hbm", "achieved": round(a_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(a_gbs / HBM_PEAK_GBS, 4),
                      "traffic": _read_traffic(f"pmc_main_decode_launch_{wl.name}.txt"),
-                     "bytes_per_launch": int(a_bytes), "avg_launch_us": round(a_us, 2)},
+                     "bytes_per_launch": int(a_bytes), "avg_launch_us": round(a_us, 2),
+                     "plain_read_same_bytes_us": None if probe_us is None else round(probe_us, 2),
+                     "frac_of_plain_read": None if probe_us is None else round(probe_us / a_us, 4)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)

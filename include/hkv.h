@@ -188,6 +188,11 @@ HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int la
  * hkv_config.decode_dynamic.  Either pointer may be NULL. */
 HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, int32_t* dynamic_mode);
 
+/* Switches the way decode steps run the dynamic heads (1, 2 or 3 as at hkv_config.decode_dynamic); for
+ * callers that time the three on their own workload and keep the fastest.  Takes effect with the next
+ * hkv_decode_attn; the cache content is not touched.  HKV_EINVAL for any other value. */
+HKV_API int hkv_cache_set_decode_dynamic(hkv_cache* cache, int32_t dynamic_mode);
+
 /* Test / debug access to one unit (synchronises `stream`, then copies).  `dst`/`src` are [host].
  * Export returns HKV_ENOSPACE if `bytes` is smaller than the item; *written gets its size. */
 HKV_API int hkv_cache_export(const hkv_cache* cache, int what, int seq, int layer, int head, void* dst,
@@ -217,6 +222,14 @@ HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end
 HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);
 HKV_API int hkv_profile_read(hkv_cache* cache, double* ms, int* n_calls);
 HKV_API int hkv_profile_disable(hkv_cache* cache);
+
+/* Reference measurement for benchmarks (not part of the method): average duration, in microseconds,
+ * of a kernel that only reads `read_bytes` (rounded down to a multiple of 128 KiB) of `buf` [device,
+ * 16-byte aligned, buf_bytes long], taken from the kernel's own start/stop time stamps over `reps`
+ * launches on `stream` (1..4096; two untimed launches first).  Successive launches walk through
+ * `buf`, so give it several times the memory-side cache.  Synchronises `stream` after every launch. */
+HKV_API int hkv_probe_stream_read(const void* buf, size_t buf_bytes, size_t read_bytes, int reps, void* stream,
+                          double* avg_us);
 
 HKV_API void hkv_cache_destroy(hkv_cache* cache);   /* frees the host descriptor only */
 HKV_API const char* hkv_strerror(int status);

@@ -26,8 +26,8 @@ HKV_ABI_VERSION = 1
 EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
-    "hkv_cache_decode_shape",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
-    "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable",
+    "hkv_cache_decode_shape", "hkv_cache_set_decode_dynamic",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
+    "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
 
@@ -79,6 +79,7 @@ def load_library() -> C.CDLL:
                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_step_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_uint64)]
     lib.hkv_cache_decode_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.hkv_cache_set_decode_dynamic.argtypes = [vp, C.c_int32]
     lib.hkv_cache_export.argtypes = [vp, i32, i32, i32, i32, vp, sz, C.POINTER(sz), vp]
     lib.hkv_cache_import.argtypes = [vp, i32, i32, i32, i32, vp, sz, vp]
     lib.hkv_compress_from_scores.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -86,6 +87,7 @@ def load_library() -> C.CDLL:
     lib.hkv_profile_enable.argtypes = [vp, i32]
     lib.hkv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.hkv_profile_disable.argtypes = [vp]
+    lib.hkv_probe_stream_read.argtypes = [vp, sz, sz, i32, vp, C.POINTER(C.c_double)]
     lib.hkv_cache_destroy.argtypes = [vp]
     lib.hkv_cache_destroy.restype = None
     lib.hkv_strerror.argtypes = [i32]
@@ -238,6 +240,18 @@ def hkv_cache_decode_shape(handle: int) -> Tuple[int, int]:
     return int(t.value), int(m.value)
 
 
+def hkv_cache_set_decode_dynamic(handle: int, mode: int) -> None:
+    _check(load_library().hkv_cache_set_decode_dynamic(handle, mode), "hkv_cache_set_decode_dynamic")
+
+
+def hkv_probe_stream_read(buf_ptr: int, buf_bytes: int, read_bytes: int, reps: int, stream: int = 0) -> float:
+    """Average microseconds of a kernel that only reads read_bytes of the device buffer."""
+    v = C.c_double(0.0)
+    _check(load_library().hkv_probe_stream_read(buf_ptr, buf_bytes, read_bytes, reps, stream, C.byref(v)),
+           "hkv_probe_stream_read")
+    return float(v.value)
+
+
 def hkv_profile_enable(handle: int, max_calls: int) -> None:
     _check(load_library().hkv_profile_enable(handle, max_calls), "hkv_profile_enable")
 
@@ -337,6 +351,9 @@ class HybridKVCache:
 
     def decode_shape(self):
         return hkv_cache_decode_shape(self.handle)
+
+    def set_decode_dynamic(self, mode: int):
+        hkv_cache_set_decode_dynamic(self.handle, mode)
 
     def rewind(self, stream=None):
         hkv_cache_rewind(self.handle, stream)

@@ -683,6 +683,12 @@ int hkv_cache_decode_shape(const hkv_cache* c, int32_t* tile_rows, int32_t* dyna
   return HKV_OK;
 }
 
+int hkv_cache_set_decode_dynamic(hkv_cache* c, int32_t dynamic_mode) {
+  if (!c || dynamic_mode < 1 || dynamic_mode > 3) return HKV_EINVAL;
+  c->lo.mode = dynamic_mode;
+  return HKV_OK;
+}
+
 int hkv_cache_export(const hkv_cache* c, int what, int seq, int layer, int head, void* dst, size_t bytes,
                      size_t* written, void* stream) {
   const UnitDesc* d = find_unit(c, seq, layer, head);

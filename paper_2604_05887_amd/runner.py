@@ -3,7 +3,7 @@ to the C ABI.  Memory plumbing only: no step of the method is computed here."""
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import Optional
+from typing import Callable, Dict, Optional, Sequence
 
 import numpy as np
 import torch
@@ -56,3 +56,29 @@ def setup(wl, device="cuda:0", budget: Optional[np.ndarray] = None, head_type: O
     else:
         qw = k = v = None
     return DeviceWorkload(cfg=cfg, plan=plan, cache=cache, q_window=qw, k=k, v=v, dtype=wl.dtype)
+
+
+def tune_decode_dynamic(caches: Sequence, step_fn: Callable[[object, int], None], modes=(1, 2, 3), steps: int = 24,
+                        warmup: int = 6) -> Dict[int, float]:
+    """Time the three ways a decode step can run the dynamic heads on the caller's own caches and keep
+    the fastest on all of them.  step_fn(cache_holder, i) issues one step WITHOUT appending (k_new = None),
+    so the caches come out unchanged; the caches are visited in rotation, as a benchmark that defeats the
+    memory-side cache does.  Returns {mode: microseconds per step}."""
+    result: Dict[int, float] = {}
+    for m in modes:
+        for c in caches:
+            c.cache.set_decode_dynamic(m)
+        for i in range(warmup):
+            step_fn(caches[i % len(caches)], i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(steps):
+            step_fn(caches[(warmup + i) % len(caches)], i)
+        e1.record()
+        torch.cuda.synchronize()
+        result[m] = e0.elapsed_time(e1) / steps * 1e3
+    best = min(result, key=result.get)
+    for c in caches:
+        c.cache.set_decode_dynamic(best)
+    return result

@@ -287,3 +287,35 @@ def test_decode_shape_is_reported_and_auto_rule():
     dw = runner.setup(wl, upload_prompt=False, decode_tile_rows=128)
     assert dw.cache.decode_shape() == (128, 2)          # small chunks, many tiles: the selection runs once per head
     dw.cache.close()
+
+
+def test_stream_read_probe_reports_a_plausible_rate():
+    buf = torch.full((512 << 20,), 5, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    us = B.hkv_probe_stream_read(buf.data_ptr(), buf.numel(), 64 << 20, 8)
+    gbs = (64 << 20) / (us * 1e-6) / 1e9
+    print(f"\n[probe] 64 MiB in {us:.2f} us = {gbs:.0f} GB/s", flush=True)
+    assert 200.0 < gbs < 8000.0                      # below the HBM peak, above any sane floor
+    with pytest.raises(B.HkvError):
+        B.hkv_probe_stream_read(buf.data_ptr(), buf.numel(), buf.numel() + (1 << 20), 1)
+
+
+def test_switching_the_decode_shape_on_a_live_cache():
+    """hkv_cache_set_decode_dynamic changes how later steps run, not what they compute."""
+    wl = make_workload(1, n_layers=2, shrink=4, steps=3)
+    dw = runner.setup(wl)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    q = runner.to_device(wl.q_steps[0], wl.dtype)
+    outs = []
+    for mode in (1, 2, 3):
+        dw.cache.set_decode_dynamic(mode)
+        assert dw.cache.decode_shape()[1] == mode
+        out = torch.empty((2, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+        dw.cache.decode_attn(q, None, None, out)
+        torch.cuda.synchronize()
+        outs.append(out.float())
+    for o in outs[1:]:
+        assert (o - outs[0]).abs().max().item() <= 2e-2 * outs[0].abs().max().item()
+    with pytest.raises(B.HkvError):
+        dw.cache.set_decode_dynamic(4)
+    dw.cache.close()
