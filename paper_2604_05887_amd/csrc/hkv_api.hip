@@ -491,11 +491,12 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + lo.ws_o_bytes);
   const int dt = c->cfg.dtype, app = k_new ? 1 : 0;
   const int mode = lo.mode;
+  const int resident = 3 * c->n_cus;      // workgroups resident at once (three per compute unit)
   if (mode == 3) {
     // a grid that is resident in one round: the static tiles wait for the time the dynamic tiles' summary
     // reads take at ~5 TB/s, in units of 512 clocks at ~2.4 GHz, at most 16
     int hold = 0;
-    if (ndi > 0 && ndi + ns <= 3 * c->n_cus)
+    if (ndi > 0 && ndi + ns <= resident)
       hold = (int)std::min<int64_t>(16, (lo.dmu_begin[le] - lo.dmu_begin[lb]) / 1070000);
     e = launch_dynamic_tiles(c->cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, t_before, 1,
                              hold, lo.max_chunks, st, ev[0], ev[1]);

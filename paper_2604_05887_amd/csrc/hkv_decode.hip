@@ -15,6 +15,8 @@
 #include "hkv_device.h"
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "hkv_internal.h"
 #include "hkv_select.h"
 
@@ -62,7 +64,7 @@ constexpr int kMlStride = kMlFloats;
 // pad, o[128]) in stream order and store the tile's record.  All 256 threads; smem must be ready.
 template <int G, int NS>
 __device__ __forceinline__ void combine_streams_and_store(const float* smem, const PartOut& po) {
-  const int tid = threadIdx.x;
+  const int tid = thread_index();
   for (int idx = tid; idx < G * kD; idx += 256) {
     const int g = idx >> 7, dd = idx & (kD - 1);
     float mm = kNeg;
@@ -401,6 +403,33 @@ __device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t
   blk = nv > 0 ? (uint32_t)pb >> 3 : 0u;
 }
 
+// Operands of one 32-row step in flight: eight 16-byte K pieces and eight V pieces per lane, and how many
+// of the 8 rows of this lane's V block exist.
+struct StepBufs {
+  uint4 ka[8], va[8];
+  int nv;
+};
+
+// Issues the loads of step `st` of the tile at row0 for this lane (wave-uniform st).  Rows past the end of
+// the unit resolve to its block 0 with no valid rows, so any step number is safe to ask for.
+template <bool DYN>
+__device__ __forceinline__ void issue_step_loads(const RowMap& rm, int row0, int st, StepBufs& sb) {
+  const int lane = thread_index() & 63;
+  const int qi = lane & 15, jv = lane >> 4, ja = qi >> 2, e1 = lane & 3;
+  uint32_t ba, bv;
+  int unused;
+  resolve_block<DYN>(rm, row0 + st * 32 + 8 * ja, ba, unused);
+  resolve_block<DYN>(rm, row0 + st * 32 + 8 * jv, bv, sb.nv);
+  const char* kp = rm.kbase + (size_t)ba * kBlkBytes + (uint32_t)(jv * 4 + e1) * 16u;
+  const char* vp = rm.vbase + (size_t)bv * kBlkBytes + (uint32_t)qi * 16u;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sb.ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sb.va[i] = ld16(vp + i * 256);     // i = 16-dim block of the output
+}
+
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+
 // One tile of `tile_rows` logical rows (a multiple of 128).  The tile is cut into steps of 32 keys;
 // wave w takes steps w, w+4, w+8, ... and keeps one step of loads in flight ahead of its arithmetic.
 // Scores S^T = K Q^T: the A operand is a K block piece (key-major), the B operand the query rows
@@ -408,10 +437,14 @@ __device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t
 // the 8 rows of block j of the step -- which is exactly the B operand the second contraction
 // O^T += V^T P^T needs from that lane, so the weights never move between lanes.  The A operand of the
 // second contraction is a 16-byte piece of the transposed V block.  No operand is staged through LDS.
-template <int G, bool DYN>
+// `sb` holds the operands in flight; with `preloaded` the caller has already issued this wave's first
+// step into it.  `between` runs after the last step's arithmetic and before the combination of the
+// waves, when `sb` is free again (a hook for callers that overlap something with the combination).
+template <int G, bool DYN, class Between = NoHook>
 __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* __restrict__ q, float scale_log2e,
-                                               int row0, int tile_rows, const PartOut& part, float* smem) {
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+                                               int row0, int tile_rows, const PartOut& part, float* smem,
+                                               StepBufs& sb, bool preloaded = false, Between between = Between()) {
+  const int tid = thread_index(), lane = tid & 63, wv = tid >> 6;
   const int qi = lane & 15, jv = lane >> 4, ja = qi >> 2, e1 = lane & 3;
 
   bf16x8 qb[4];
@@ -430,21 +463,11 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
   for (int db = 0; db < 8; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
   float m = kNeg, lsum = 0.f;
 
-  uint4 ka[8], va[8];
-  int nv = 0;
+  uint4 (&ka)[8] = sb.ka;
+  uint4 (&va)[8] = sb.va;
   int st = wv;                                           // wave-uniform
-  if (st < n_steps) {
-    uint32_t ba, bv;
-    int unused;
-    resolve_block<DYN>(rm, row0 + st * 32 + 8 * ja, ba, unused);
-    resolve_block<DYN>(rm, row0 + st * 32 + 8 * jv, bv, nv);
-    const char* kp = rm.kbase + (size_t)ba * kBlkBytes + k_lane;
-    const char* vp = rm.vbase + (size_t)bv * kBlkBytes + v_lane;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
-#pragma unroll
-    for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);     // i = 16-dim block of the output
-  }
+  if (st < n_steps && !preloaded) issue_step_loads<DYN>(rm, row0, st, sb);
+  int nv = sb.nv;
 #pragma unroll 1
   while (st < n_steps) {
     floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -508,6 +531,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     st = nst;
   }
 
+  between();
   lsum += lane_xor(lsum, 16);
   lsum += lane_xor(lsum, 32);
   float* mine = smem + (size_t)wv * G * kPartStride;
@@ -518,7 +542,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
       *reinterpret_cast<float4*>(mine + qi * kPartStride + 4 + 16 * db + 4 * jv) =
           make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
   }
-  __syncthreads();
+  lds_barrier();                       // staging is LDS only; loads for the next tile may be in flight
   combine_streams_and_store<G, 4>(smem, part);
 }
 
@@ -534,8 +558,10 @@ template <typename T, int G, bool BLOCKED>
 __device__ __forceinline__ void run_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
                                          int tile_rows, const PartOut& part, float* smem) {
   if constexpr (sizeof(T) == 2 && BLOCKED) {
-    if (rm.dynamic) attn_tile_mfma<G, true>(rm, q, scale_log2e, row0, tile_rows, part, smem);
-    else attn_tile_mfma<G, false>(rm, q, scale_log2e, row0, tile_rows, part, smem);
+    StepBufs sb;
+    sb.nv = 0;
+    if (rm.dynamic) attn_tile_mfma<G, true>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
+    else attn_tile_mfma<G, false>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
   } else if constexpr (sizeof(T) == 2) {
     attn_tile_bf16<G, kNhbBf16, false>(rm, q, scale_log2e, row0, part, smem);   // row-major rows, never gathered
   } else {
@@ -611,7 +637,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
                                                       const T* __restrict__ q, int use_stored_sigma, float* dsm,
                                                       int32_t* sel_lds = nullptr, bool to_memory = true) {
   constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = 256 / LPR;
-  const int tid = threadIdx.x;
+  const int tid = thread_index();
   uint32_t* hist = reinterpret_cast<uint32_t*>(dsm);         // [256]
   uint32_t* bc = hist + 256;                                 // [2]
   int* scan = reinterpret_cast<int*>(bc + 2);                // [6]
@@ -739,6 +765,37 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
   }
 }
 
+// Writes the step's new K/V row of one unit into its tail (all threads of the block; ends with a barrier,
+// so the row is in memory before any lane of this block reads it).
+template <typename T>
+__device__ __forceinline__ void append_row(const CacheView& cv, const AttnItem& it, int lrel, int t_before,
+                                           const T* __restrict__ k_new, const T* __restrict__ v_new) {
+  constexpr int LPR = Elem<T>::kLanesPerRow;
+  const int tid = thread_index();
+  const size_t src_row = (((size_t)lrel * cv.batch + it.seq) * cv.n_kv_heads + it.head) * kD * sizeof(T);
+  const int64_t prow = it.kv_row_off + it.tail_row + t_before;
+  if constexpr (sizeof(T) == 2) {
+    // blocked cache: 16 key pieces go to their slots of the row's block, V is scattered one element per dim
+    const size_t blk_off = (size_t)(prow >> 3) * kBlkBytes;
+    const int e = (int)(prow & 7);
+    if (tid < 16)
+      st16(reinterpret_cast<char*>(cv.k_rows) + blk_off + k_piece_index(e, tid) * 16,
+           ld16(reinterpret_cast<const char*>(k_new) + src_row + tid * 16));
+    if (tid >= 64 && tid < 64 + kD) {
+      const int dd = tid - 64;
+      *reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(cv.v_rows) + blk_off + dd * 16 + e * 2) =
+          *reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(v_new) + src_row + dd * 2);
+    }
+  } else if (tid < 2 * LPR) {
+    const int which = tid / LPR, sub = tid % LPR;
+    const size_t dst = (size_t)prow * kD * sizeof(T) + sub * 16;
+    if (which == 0) st16(reinterpret_cast<char*>(cv.k_rows) + dst, ld16(reinterpret_cast<const char*>(k_new) + src_row + sub * 16));
+    else st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v_new) + src_row + sub * 16));
+  }
+  __threadfence_block();
+  __syncthreads();                        // the row is in memory before any lane of this block reads it
+}
+
 // One split-K tile of the hybrid cache: optional tail append, then attention, record -> workspace.
 template <typename T, int G>
 __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnItem& it, int layer_begin, int slot_base,
@@ -756,30 +813,8 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   if (it.row0 >= rm.n_rows) return;          // tile reserved for tail growth, not reached yet
   const int lrel = it.layer - layer_begin;
   const int new_row = it.n_prompt_rows + t_before;          // logical index of the appended row
-  if (append && new_row >= it.row0 && new_row < it.row0 + TILE) {   // block-uniform
-    const size_t src_row = (((size_t)lrel * cv.batch + it.seq) * cv.n_kv_heads + it.head) * kD * sizeof(T);
-    const int64_t prow = it.kv_row_off + it.tail_row + t_before;
-    if constexpr (sizeof(T) == 2) {
-      // blocked cache: 16 key pieces go to their slots of the row's block, V is scattered one element per dim
-      const size_t blk_off = (size_t)(prow >> 3) * kBlkBytes;
-      const int e = (int)(prow & 7);
-      if (tid < 16)
-        st16(reinterpret_cast<char*>(cv.k_rows) + blk_off + k_piece_index(e, tid) * 16,
-             ld16(reinterpret_cast<const char*>(k_new) + src_row + tid * 16));
-      if (tid >= 64 && tid < 64 + kD) {
-        const int dd = tid - 64;
-        *reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(cv.v_rows) + blk_off + dd * 16 + e * 2) =
-            *reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(v_new) + src_row + dd * 2);
-      }
-    } else if (tid < 2 * LPR) {
-      const int which = tid / LPR, sub = tid % LPR;
-      const size_t dst = (size_t)prow * kD * sizeof(T) + sub * 16;
-      if (which == 0) st16(reinterpret_cast<char*>(cv.k_rows) + dst, ld16(reinterpret_cast<const char*>(k_new) + src_row + sub * 16));
-      else st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v_new) + src_row + sub * 16));
-    }
-    __threadfence_block();
-    __syncthreads();                        // the row is in memory before any lane of this block reads it
-  }
+  if (append && new_row >= it.row0 && new_row < it.row0 + TILE)    // block-uniform
+    append_row<T>(cv, it, lrel, t_before, k_new, v_new);
   rm.kbase = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.vbase = reinterpret_cast<const char*>(cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.stride = kD * sizeof(T);

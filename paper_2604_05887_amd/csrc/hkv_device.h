@@ -6,6 +6,24 @@
 
 namespace hkv {
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load and
+// store the wave has in flight; a wave that has already asked for its next tile's rows, or has just
+// stored a record nobody in the workgroup reads, must not stall on those at a barrier that only guards
+// shared memory.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// threadIdx.x behind an optimisation barrier.  In a kernel whose workgroups loop over many tiles the
+// compiler otherwise hoists every per-thread address term of every inner loop out of the tile loop and
+// then spills them; an opaque copy per use keeps those terms local to the tile (a handful of ALU ops).
+__device__ __forceinline__ int thread_index() {
+  int t = (int)threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+
+
 struct bf16_t { uint16_t bits; };   // storage type of bfloat16 tensors
 
 template <typename T> struct Elem;

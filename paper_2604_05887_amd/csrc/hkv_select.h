@@ -20,7 +20,7 @@ __device__ __forceinline__ uint32_t float_order_key(float f) {
 template <int NT, class KeyFn>
 __device__ __forceinline__ void radix_select(int n, int m_sel, KeyFn keyfn, uint32_t* hist, uint32_t* bc,
                                              uint32_t& T, int& r_adm) {
-  const int tid = threadIdx.x;
+  const int tid = thread_index();
   uint32_t prefix = 0, mask = 0;
   int remaining = m_sel;
 #pragma unroll 1
