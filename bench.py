@@ -144,7 +144,7 @@ def main() -> int:
     n_copies = args.copies or int(min(8, max(2, -(-5 * MALL_BYTES // (4 * step_bytes_mid)) + 1)))
     per_copy = -(-(K + W) // n_copies)
     preroll = max(0, wl.steps // 2 - per_copy // 2)
-    wl.max_new_tokens = preroll + 2 * per_copy + 2 + K   # room for the profiled pass as well
+    wl.max_new_tokens = preroll + 2 * per_copy + 2 + K + 64   # room for the profiled and per-layer passes as well
     copies = [runner.setup(wl, dev, upload_prompt=False, decode_tile_rows=args.tile_rows, decode_dynamic=args.dynamic_mode) for _ in range(n_copies)]
     stream = torch.cuda.current_stream()
     sptr = int(stream.cuda_stream) or None
@@ -251,7 +251,7 @@ def main() -> int:
         del pbuf
 
     # ---- layer-by-layer driving (one call per layer, as a model interleaves them with its other layers) ----
-    lw_us = None
+    lw_us = lw_graph_us = None
     if L > 1 and not args.no_layerwise:
         def layerwise_step(dw, i):
             j = i % n_inputs
@@ -270,6 +270,35 @@ def main() -> int:
             layerwise_step(copies[i % n_copies], i)
         torch.cuda.synchronize()
         lw_us = (time.perf_counter() - t0) * 1e6 / n_lw
+
+        # the same per-layer calls recorded once into a HIP graph per cache copy (tail lengths on the device,
+        # so a recording stays valid) and replayed: what a serving loop that records its decode step pays
+        graphs = []
+        side = torch.cuda.Stream()
+        for dw in copies:
+            dw.cache.set_device_tail(True)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                sp = int(torch.cuda.current_stream().cuda_stream)
+                for l in range(L):
+                    st = lib.hkv_decode_attn(dw.cache.handle, l, l + 1, q_all[0, l].data_ptr(), kn_all[0, l].data_ptr(),
+                                             vn_all[0, l].data_ptr(), out[l].data_ptr(), dw.cache.workspace.data_ptr(),
+                                             dw.cache.workspace_bytes, sp)
+                    if st != 0:
+                        raise B.HkvError(st, "hkv_decode_attn")
+            graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(2):
+            graphs[i % n_copies].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_lw):
+            graphs[i % n_copies].replay()
+        torch.cuda.synchronize()
+        lw_graph_us = (time.perf_counter() - t0) * 1e6 / n_lw
+        del graphs
+        for dw in copies:
+            dw.cache.set_device_tail(False)
 
     # ---- full-KV comparison --------------------------------------------------------------------------
     # (1) the library's full-KV kernel on the caller's uncompressed K/V (rows read in place);
@@ -382,6 +411,7 @@ def main() -> int:
         "full_kv_detail_us": {"rows_read_in_place": round(full_inplace_ms * 1e3, 2),
                               "cache_retaining_everything": round(full_cache_ms * 1e3, 2)},
         "us_per_step_one_call_per_layer": None if lw_us is None else round(lw_us, 2),
+        "us_per_step_one_call_per_layer_hip_graph": None if lw_graph_us is None else round(lw_graph_us, 2),
         "speedup_vs_full_kv": round(full_ms / ms_per_step, 3),
         "compress_ms": round(compress_ms, 3),
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),

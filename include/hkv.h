@@ -188,6 +188,15 @@ HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int la
  * hkv_config.decode_dynamic.  Either pointer may be NULL. */
 HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, int32_t* dynamic_mode);
 
+/* Tail bookkeeping for callers that record hkv_decode_attn into a HIP graph.  Normally the host mirrors
+ * every head's tail length and passes it to the kernels as an argument, which a recorded call would
+ * replay unchanged.  With enable = 1 decode calls read and advance the per-layer counters in device
+ * memory only, so one recorded call is valid for every replay (three kernels per call instead of two;
+ * a full tail is not reported as HKV_ENOSPACE any more: the step then attends without appending).
+ * enable = 0 returns to host bookkeeping after reading the counters back (synchronises `stream`).
+ * Exports of K/V rows use the host's figure, so switch back before exporting. */
+HKV_API int hkv_cache_set_device_tail(hkv_cache* cache, int enable, void* stream);
+
 /* Switches the way decode steps run the dynamic heads (1, 2 or 3 as at hkv_config.decode_dynamic); for
  * callers that time the three on their own workload and keep the fastest.  Takes effect with the next
  * hkv_decode_attn; the cache content is not touched.  HKV_EINVAL for any other value. */

@@ -26,7 +26,7 @@ HKV_ABI_VERSION = 1
 EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
-    "hkv_cache_decode_shape", "hkv_cache_set_decode_dynamic",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
+    "hkv_cache_decode_shape", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
     "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
     lib.hkv_cache_step_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_uint64)]
     lib.hkv_cache_decode_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_set_decode_dynamic.argtypes = [vp, C.c_int32]
+    lib.hkv_cache_set_device_tail.argtypes = [vp, i32, vp]
     lib.hkv_cache_export.argtypes = [vp, i32, i32, i32, i32, vp, sz, C.POINTER(sz), vp]
     lib.hkv_cache_import.argtypes = [vp, i32, i32, i32, i32, vp, sz, vp]
     lib.hkv_compress_from_scores.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -244,6 +245,10 @@ def hkv_cache_set_decode_dynamic(handle: int, mode: int) -> None:
     _check(load_library().hkv_cache_set_decode_dynamic(handle, mode), "hkv_cache_set_decode_dynamic")
 
 
+def hkv_cache_set_device_tail(handle: int, enable: bool, stream=None) -> None:
+    _check(load_library().hkv_cache_set_device_tail(handle, 1 if enable else 0, stream), "hkv_cache_set_device_tail")
+
+
 def hkv_probe_stream_read(buf_ptr: int, buf_bytes: int, read_bytes: int, reps: int, stream: int = 0) -> float:
     """Average microseconds of a kernel that only reads read_bytes of the device buffer."""
     v = C.c_double(0.0)
@@ -354,6 +359,9 @@ class HybridKVCache:
 
     def set_decode_dynamic(self, mode: int):
         hkv_cache_set_decode_dynamic(self.handle, mode)
+
+    def set_device_tail(self, enable: bool, stream=None):
+        hkv_cache_set_device_tail(self.handle, enable, stream)
 
     def rewind(self, stream=None):
         hkv_cache_rewind(self.handle, stream)

@@ -256,6 +256,7 @@ struct hkv_cache {
   CacheView cv;
   char* arena;
   std::vector<int32_t> host_tail;     // [n_layers] appended tokens (host mirror of the device counter)
+  bool device_tail = false;           // decode calls take the tail length from the device counters only
   std::vector<uint8_t> compressed;    // [n_layers]
   std::vector<hipEvent_t> events;     // 6 per profiled decode call: start and stop of up to three kernels
   int prof_calls = 0, prof_max = 0;
@@ -469,7 +470,7 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   if (workspace_bytes < c->lo.ws_bytes) return HKV_ENOSPACE;
   for (int l = lb; l < le; ++l) {
     if (!c->compressed[l]) return HKV_ESTATE;
-    if (k_new && c->host_tail[l] + 1 > c->cfg.max_new_tokens) return HKV_ENOSPACE;
+    if (k_new && !c->device_tail && c->host_tail[l] + 1 > c->cfg.max_new_tokens) return HKV_ENOSPACE;
   }
   const Layout& lo = c->lo;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -481,7 +482,7 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   const int ub = lb * c->batch * c->cfg.n_kv_heads, nu = (le - lb) * c->batch * c->cfg.n_kv_heads;
   // tail length: when every layer of the call has the same one (the normal case) it travels as a
   // kernel argument; otherwise the kernels read the per-layer device counters
-  int t_before = c->host_tail[lb];
+  int t_before = c->device_tail ? -1 : c->host_tail[lb];
   for (int l = lb; l < le; ++l) if (c->host_tail[l] != t_before) t_before = -1;
   hipEvent_t none[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   const bool prof = c->prof_max > 0 && c->prof_calls < c->prof_max;
@@ -518,7 +519,7 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
     c->prof_calls += 1;
     c->prof_stream = st;
   }
-  if (k_new) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
+  if (k_new && !c->device_tail) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
   return HKV_OK;
 }
 
@@ -530,6 +531,18 @@ int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
   hipError_t e = launch_decode(c->cv, c->cfg.dtype, lb, db, nd, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr,
                                nullptr, -1, 1, 1, lo.max_chunks, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? HKV_OK : HKV_EHIP;
+}
+
+int hkv_cache_set_device_tail(hkv_cache* c, int enable, void* stream) {
+  if (!c || (enable != 0 && enable != 1)) return HKV_EINVAL;
+  if (!enable && c->device_tail) {
+    // back to host bookkeeping: fetch what the device counted meanwhile
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(c->host_tail.data(), c->cv.cnt_a, (size_t)c->cfg.n_layers * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) return HKV_EHIP;
+  }
+  c->device_tail = enable != 0;
+  return HKV_OK;
 }
 
 int hkv_cache_rewind(hkv_cache* c, void* stream) {

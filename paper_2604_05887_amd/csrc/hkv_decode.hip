@@ -22,6 +22,14 @@
 
 #include <algorithm>
 
+// A launch that carries start/stop events when a profiled call asks for them and is a plain launch
+// otherwise (plain launches are what stream capture records).
+#define HKV_LAUNCH(kernel, grid, block, smem, stream, ev0, ev1, ...)                                   \
+  do {                                                                                                 \
+    if ((ev0) != nullptr) hipExtLaunchKernelGGL(kernel, grid, block, smem, stream, ev0, ev1, 0u, __VA_ARGS__); \
+    else hipLaunchKernelGGL(kernel, grid, block, smem, stream, __VA_ARGS__);                           \
+  } while (0)
+
 namespace hkv {
 
 // Where the logical rows of one head live.
@@ -1045,7 +1053,7 @@ static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_
     attr = smem;
   }
   if (n_dyn + n_sitems > 0)
-    hipExtLaunchKernelGGL((decode_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1, 0u, cv,
+    HKV_LAUNCH((decode_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1, cv,
                           layer_begin, dyn_begin, n_dyn, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
                           (const T*)v_new, partials, (T*)out, t_arg, use_stored_sigma, select_only);
   return hipGetLastError();
@@ -1084,8 +1092,8 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
     if (e != hipSuccess) return e;
     attr = smem;
   }
-  hipExtLaunchKernelGGL((dynamic_tiles_kernel<T, G>), dim3(n_ditems + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1,
-                        0u, cv, layer_begin, ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
+  HKV_LAUNCH((dynamic_tiles_kernel<T, G>), dim3(n_ditems + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1,
+                        cv, layer_begin, ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
                         (const T*)v_new, partials, t_arg, reselect, (int)(front / sizeof(float)), static_hold);
   return hipGetLastError();
 }
@@ -1114,10 +1122,10 @@ hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* des
   const int n_blocks = n_units * cv.G;
   if (n_blocks > 0) {
     if (dtype == HKV_F32)
-      hipExtLaunchKernelGGL(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0u, st, ev0, ev1, 0u, cv, descs,
+      HKV_LAUNCH(attn_merge_kernel<float>, dim3(n_blocks), dim3(128), 0u, st, ev0, ev1, cv, descs,
                             layer_begin, slot_base, partials, (float*)out, t_arg, appending);
     else
-      hipExtLaunchKernelGGL(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0u, st, ev0, ev1, 0u, cv, descs,
+      HKV_LAUNCH(attn_merge_kernel<bf16_t>, dim3(n_blocks), dim3(128), 0u, st, ev0, ev1, cv, descs,
                             layer_begin, slot_base, partials, (bf16_t*)out, t_arg, appending);
   }
   if (t_arg < 0 && layer_end > layer_begin)

@@ -319,3 +319,51 @@ def test_switching_the_decode_shape_on_a_live_cache():
     with pytest.raises(B.HkvError):
         dw.cache.set_decode_dynamic(4)
     dw.cache.close()
+
+
+def test_decode_recorded_in_a_hip_graph_replays_correctly():
+    """One recorded step (a call per layer, tail lengths on the device) replayed several times, with eager
+    work and synchronisation between the replays, gives on every replay the bits of an eager cache that
+    takes the same steps; afterwards the host bookkeeping is back in step and the tails hold the rows."""
+    n_rep = 4
+    wl = make_workload(1, n_layers=3, shrink=4, steps=2, max_new_tokens=n_rep + 1)
+    L = wl.n_layers
+    q, kn, vn = (runner.to_device(x[0], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+    eager, rec, warm = runner.setup(wl), runner.setup(wl), runner.setup(wl)
+    for dw in (eager, rec, warm):
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+    out_e = torch.empty((L, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+    out_g = torch.zeros_like(out_e)
+    warm.cache.set_device_tail(True)
+    warm.cache.decode_attn(q, kn, vn, out_g)               # first use of the kernels happens outside the recording
+    torch.cuda.synchronize()
+    rec.cache.set_device_tail(True)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sp = torch.cuda.current_stream().cuda_stream
+        for l in range(L):
+            rec.cache.decode_attn(q[l:l + 1], kn[l:l + 1], vn[l:l + 1], out_g[l:l + 1], layer_begin=l, layer_end=l + 1,
+                                  stream=sp)
+    torch.cuda.synchronize()
+    scratch = torch.randn(1 << 20, device="cuda:0")
+    for r in range(n_rep):
+        graph.replay()
+        torch.cuda.synchronize()
+        scratch = scratch * 1.0001 + 1.0                    # the program's own eager work between replays
+        eager.cache.decode_attn(q, kn, vn, out_e)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), f"replay {r} differs from the eager step"
+    rec.cache.set_device_tail(False)
+    for l in range(L):
+        for h in range(wl.n_kv_heads):
+            a = rec.cache.export(B.HKV_X_K_ROWS, 0, l, h)
+            b = eager.cache.export(B.HKV_X_K_ROWS, 0, l, h)
+            assert a.shape == b.shape and np.array_equal(a, b)
+    # host bookkeeping continues where the device left off: one more eager step on both
+    rec.cache.decode_attn(q, kn, vn, out_g)
+    eager.cache.decode_attn(q, kn, vn, out_e)
+    torch.cuda.synchronize()
+    assert torch.equal(out_g, out_e)
+    for dw in (eager, rec, warm):
+        dw.cache.close()
