@@ -78,6 +78,15 @@ __global__ __launch_bounds__(256) void score_kernel(CacheView cv, int layer_begi
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = kNeg; z_run[rb] = 0.f; }
 
+  float2 fstat[NRB];                            // pass 2: this lane's rows' (maximum, 1/(Z*G*w))
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    fstat[rb] = make_float2(0.f, 0.f);
+    if constexpr (PASS == 2) {
+      if (rb < n_rb) fstat[rb] = final_stats[(size_t)su * kMaxScoreRows + rb * 32 + l32];
+    }
+  }
+
   const char* kbase = reinterpret_cast<const char*>(k) +
                       (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
   const size_t kstride = (size_t)cv.n_kv_heads * ROWB;
@@ -96,6 +105,10 @@ __global__ __launch_bounds__(256) void score_kernel(CacheView cv, int layer_begi
     float col[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) col[r] = 0.f;
+    // a tile is clean when none of its 32 keys is past the end or (with the causal option) inside the
+    // window: then no logit is masked and the scale folds into the exponent's multiply-add
+    const bool clean = (j0 + 32 <= d.C) && (!cv.causal || j0 + 31 <= hist_end);      // wave-uniform
+    const float s2 = cv.scale_log2e;
 
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
@@ -104,29 +117,47 @@ __global__ __launch_bounds__(256) void score_kernel(CacheView cv, int layer_begi
         const char* qrow = qs + (size_t)(rb * 32 + l32) * PITCH + half * 16;
 #pragma unroll
         for (int j = 0; j < NPIECE; ++j) acc = mma_piece(a[j], ld16(qrow + j * 32), acc, T{});
-        // acc[r] = q_row(rb*32 + l32) . k(j0 + 8*(r/4) + 4*half + r%4)
+        // acc[r] = q_row(rb*32 + l32) . k(j0 + 8*(r/4) + 4*half + r%4); the logit is acc[r] * s2, and both
+        // passes form "logit - row maximum" as one fused multiply-add, so they agree bit for bit
         const int qr = rb * 32 + l32;
-        const int qi = qr % w;                   // position of the row inside the window
-        float lg[16];
+        if (clean) {
+          if constexpr (PASS == 1) {
+            float mx = acc[0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kk = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
-          const bool masked = (kk >= d.C) || (cv.causal && kk > hist_end + qi);
-          lg[r] = masked ? kNeg : acc[r] * cv.scale_log2e;
-        }
-        if constexpr (PASS == 1) {
-          float mx = lg[0];
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+            const float mn = fmaxf(m_run[rb], mx * s2);
+            float z = z_run[rb] * fast_exp2(m_run[rb] - mn);
 #pragma unroll
-          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, lg[r]);
-          const float mn = fmaxf(m_run[rb], mx);
-          float z = z_run[rb] * fast_exp2(m_run[rb] - mn);
+            for (int r = 0; r < 16; ++r) z += fast_exp2(fmaf(acc[r], s2, -mn));
+            z_run[rb] = z; m_run[rb] = mn;
+          } else {
+            const float2 st = fstat[rb];         // (row max, 1/(Z*G*w)); zero for pad rows
 #pragma unroll
-          for (int r = 0; r < 16; ++r) z += (lg[r] > 0.5f * kNeg) ? fast_exp2(lg[r] - mn) : 0.f;
-          z_run[rb] = z; m_run[rb] = mn;
+            for (int r = 0; r < 16; ++r) col[r] = fmaf(fast_exp2(fmaf(acc[r], s2, -st.x)), st.y, col[r]);
+          }
         } else {
-          const float2 st = final_stats[(size_t)su * kMaxScoreRows + qr];   // (row max, 1/(Z*G*w)); zero for pad rows
+          const int qi = qr % w;                 // position of the row inside the window
+          bool masked[16];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) col[r] += (lg[r] > 0.5f * kNeg) ? fast_exp2(lg[r] - st.x) * st.y : 0.f;
+          for (int r = 0; r < 16; ++r) {
+            const int kk = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+            masked[r] = (kk >= d.C) || (cv.causal && kk > hist_end + qi);
+          }
+          if constexpr (PASS == 1) {
+            float mx = kNeg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = masked[r] ? mx : fmaxf(mx, acc[r] * s2);
+            const float mn = fmaxf(m_run[rb], mx);
+            float z = z_run[rb] * fast_exp2(m_run[rb] - mn);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z += masked[r] ? 0.f : fast_exp2(fmaf(acc[r], s2, -mn));
+            z_run[rb] = z; m_run[rb] = mn;
+          } else {
+            const float2 st = fstat[rb];
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              col[r] = masked[r] ? col[r] : fmaf(fast_exp2(fmaf(acc[r], s2, -st.x)), st.y, col[r]);
+          }
         }
       }
     }
