@@ -62,15 +62,29 @@ __global__ __launch_bounds__(256) void score_kernel(CacheView cv, int layer_begi
   const int half = lane >> 5, l32 = lane & 31;
 
   // stage the window queries: row r = g * w + i  <-  q_window[lrel][seq][i][head*G + g][:]
-  for (int idx = tid; idx < n_rb * 32 * (ROWB / 16); idx += 256) {
-    const int r = idx / (ROWB / 16), piece = idx % (ROWB / 16);
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (r < rows) {
-      const int g = r / w, i = r % w;
-      const size_t src = ((((size_t)lrel * cv.batch + d.seq) * w + i) * cv.n_q_heads + (size_t)d.head * G + g) * ROWB;
-      val = ld16(reinterpret_cast<const char*>(q_window) + src + piece * 16);
+  // (eight independent loads per round: a load-then-store loop would pay one memory round trip per piece)
+  {
+    constexpr int PPR = ROWB / 16;              // 16-byte pieces per row
+    const int n_pieces = n_rb * 32 * PPR;
+    for (int base = 0; base < n_pieces; base += 256 * 8) {
+      uint4 val[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int idx = base + u * 256 + tid;
+        const int r = idx / PPR, piece = idx % PPR;
+        val[u] = make_uint4(0, 0, 0, 0);
+        if (idx < n_pieces && r < rows) {
+          const int g = r / w, i = r % w;
+          const size_t src = ((((size_t)lrel * cv.batch + d.seq) * w + i) * cv.n_q_heads + (size_t)d.head * G + g) * ROWB;
+          val[u] = ld16(reinterpret_cast<const char*>(q_window) + src + piece * 16);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int idx = base + u * 256 + tid;
+        if (idx < n_pieces) st16(qs + (size_t)(idx / PPR) * PITCH + (idx % PPR) * 16, val[u]);
+      }
     }
-    st16(qs + (size_t)r * PITCH + piece * 16, val);
   }
   __syncthreads();
 
