@@ -23,6 +23,13 @@ order and notation of the paper:
                        (Section 3.3: static and dynamic parts share one buffer
                        and are attended together)
 
+  * text_sparsity_score  Section 3.1, text-centric attention S_text and the
+                       sparsity score S_{l,h} (sum of each text row's top-k
+                       probabilities, averaged over text rows)
+  * classify_heads     Section 3.1, threshold theta on S_{l,h}
+  * type_level_budgets / static_head_budgets
+                       Section 3.2, the two allocation equations
+
 Where the paper is silent the reading taken is written next to the code
 (grouped-query heads, ties, budgets smaller than text + window, ragged last
 chunk, rounding of the chunk metadata); the same list is in the design notes.
@@ -35,6 +42,11 @@ rational softmax values worked by hand), brute-force subset enumeration,
 chunk size 1, permutation invariance and count invariants.  The paper prints no
 worked numeric example for this path, so beyond those pins the actual values of
 s_w and of the attention outputs are "parity unpinned".
+text_sparsity_score is pinned by closed forms (uniform rows give k/C, k = C
+gives 1, a one-hot row gives 1), by a sort-based restatement on random inputs
+and by hand-worked rational softmax rows; the budget equations by their printed
+invariants (type budgets add up to the total, r = 1 and equal scores give the
+uniform split, every ceiling is at most one token above its argument).
 """
 from __future__ import annotations
 
@@ -228,6 +240,95 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float,
 
 
 # ----------------------------------------------------------------------------
+# head classification and budget allocation (upstream of the compression)
+# ----------------------------------------------------------------------------
+def focus_count(C: int, rho: float = 0.05) -> int:
+    """k = ceil(rho * C): how many positions of a row count as its focus (Section 2.1 states
+    k = ceil(0.05 C) for the focus count; the sparsity score of Section 3.1 names no k and is read
+    with the same one)."""
+    return max(1, min(C, int(np.ceil(rho * C - 1e-12))))
+
+
+def text_sparsity_score(q_text: np.ndarray, k: np.ndarray, text_pos: np.ndarray, scale: float, k_top: int,
+                        causal: bool = False) -> float:
+    """Text-centric sparsity score of one KV head (Section 3.1).
+
+    q_text  : [G, T, d]  queries of the T text tokens of the prompt for the G query heads that share
+              this KV head (the paper writes one head; with grouped-query attention the rows of all
+              G heads are averaged together, as for s_w),
+    k       : [C, d]     keys of the whole prompt,
+    text_pos: [T]        prompt positions of those text tokens (used by `causal` only).
+    S_text = softmax(Q_text K^T * scale) row by row over all C keys (as printed: no mask; `causal`
+    lets text token at position p see keys j <= p).  Each row contributes the sum of its k_top
+    largest probabilities; the score is the mean over all G*T rows.
+    """
+    q = np.asarray(q_text, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    G, T, d = q.shape
+    C = kk.shape[0]
+    if T == 0:
+        return 0.0
+    total = 0.0
+    for g in range(G):
+        logits = (q[g] @ kk.T) * scale                                # [T, C]
+        if causal:
+            j = np.arange(C)[None, :]
+            logits = np.where(j > np.asarray(text_pos)[:, None], -np.inf, logits)
+        logits = logits - logits.max(axis=1, keepdims=True)
+        e = np.exp(logits)
+        p = e / e.sum(axis=1, keepdims=True)
+        kt = min(k_top, C)
+        top = np.partition(p, C - kt, axis=1)[:, C - kt:]             # the kt largest of every row
+        total += float(np.sort(top, axis=1).sum())                    # ascending order: small terms first
+    return total / (G * T)
+
+
+def classify_heads(scores: np.ndarray, theta: float) -> np.ndarray:
+    """Head types from sparsity scores (Section 3.1): static where S >= theta, dynamic below."""
+    return np.where(np.asarray(scores, dtype=np.float64) >= theta, STATIC, DYNAMIC).astype(np.uint8)
+
+
+def type_level_budgets(b_total: int, n_stat: int, n_dyn: int, r: float) -> Tuple[int, int]:
+    """Split of the total token budget between the head types (Section 3.2, first equation):
+    B_dyna = ceil(r * B_bar * N_dyna) with B_bar = B_total / (N_stat + N_dyna); B_stat is the rest.
+    r is clipped to the bound the paper states, r <= B_total / (B_bar * N_dyna)."""
+    n = n_stat + n_dyn
+    if n == 0 or n_dyn == 0:
+        return int(b_total), 0
+    b_bar = b_total / n
+    r_eff = min(r, b_total / (b_bar * n_dyn))
+    b_dyn = min(int(b_total), int(np.ceil(r_eff * b_bar * n_dyn - 1e-9)))
+    return int(b_total) - b_dyn, b_dyn
+
+
+def static_head_budgets(b_stat: int, scores: np.ndarray, alpha: float) -> np.ndarray:
+    """Budgets of the static heads (Section 3.2, second equation): scores are L1-normalised over all
+    static heads; b = ceil(alpha * B_stat / N_stat + (1 - alpha) * B_stat * S_norm)."""
+    sc = np.asarray(scores, dtype=np.float64).reshape(-1)
+    n = sc.size
+    if n == 0:
+        return np.zeros(0, np.int64)
+    tot = sc.sum()
+    s_norm = sc / tot if tot > 0 else np.full(n, 1.0 / n)
+    return np.ceil(alpha * b_stat / n + (1.0 - alpha) * b_stat * s_norm - 1e-9).astype(np.int64)
+
+
+def dynamic_head_budget(b_dyn: int, n_dyn: int, pad_pow2: bool = True) -> int:
+    """Uniform budget of a dynamic head (Section 3.2); `pad_pow2` applies the paper's padding to the
+    nearest power of two (nearest in linear distance, ties upwards)."""
+    if n_dyn == 0:
+        return 0
+    b = b_dyn / n_dyn
+    if not pad_pow2:
+        return int(b)
+    if b <= 1:
+        return 1
+    lo = 2 ** int(np.floor(np.log2(b)))
+    hi = 2 * lo
+    return int(lo if (b - lo) < (hi - b) else hi)
+
+
+# ----------------------------------------------------------------------------
 # drivers over all (sequence, layer, KV head) units
 # ----------------------------------------------------------------------------
 @dataclass
@@ -368,6 +469,26 @@ def decode_attn(cache: OracleCache, q: np.ndarray, k_new: Optional[np.ndarray], 
                     V_rows = np.concatenate([V_rows, np.stack(u.V_tail)], axis=0)
                 out[l, b, h * G:(h + 1) * G, :] = attention(qh, K_rows, V_rows, cfg.scale)
     return out, info
+
+
+def head_scores(cfg: OracleConfig, cu_seqlens: np.ndarray, q_prompt: np.ndarray, k: np.ndarray,
+                is_visual: np.ndarray, rho: float = 0.05, layers: Optional[range] = None) -> np.ndarray:
+    """Sparsity score of every (sequence, layer, KV head): q_prompt [L, total_tokens, Hq, d] (queries of
+    the whole prompt; only the text tokens' rows are used), k [L, total_tokens, Hkv, d].
+    Returns [batch, L, Hkv] (zeros for layers not asked for)."""
+    G = cfg.group
+    B = len(cu_seqlens) - 1
+    out = np.zeros((B, cfg.n_layers, cfg.n_kv_heads))
+    for b in range(B):
+        s0, s1 = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        C = s1 - s0
+        text_pos = np.nonzero(np.asarray(is_visual[s0:s1]) == 0)[0]
+        k_top = focus_count(C, rho)
+        for l in (layers if layers is not None else range(cfg.n_layers)):
+            for h in range(cfg.n_kv_heads):
+                qt = np.stack([q_prompt[l, s0:s1][text_pos, h * G + g] for g in range(G)])      # [G, T, d]
+                out[b, l, h] = text_sparsity_score(qt, k[l, s0:s1, h], text_pos, cfg.scale, k_top, cfg.score_causal)
+    return out
 
 
 def full_decode_attn(cfg: OracleConfig, cu_seqlens: np.ndarray, q: np.ndarray, k: np.ndarray, v: np.ndarray,

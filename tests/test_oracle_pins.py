@@ -320,3 +320,118 @@ def test_paper_byte_model():
     assert round(per_token_72b * g["intro_72b_tokens_video"] / 1e9) == g["intro_72b_gb_video"]
     assert round(g["table3_full_gb"] / g["table3_b10_gb"], 1) == g["claimed_memory_ratio"]
     assert round(g["table3_full_ms"] / g["table3_b10_ms"], 2) == g["claimed_decode_speedup"]
+
+
+# ---------------------------------------------------------------- head classification (Section 3.1)
+def test_sparsity_score_closed_forms():
+    rng = np.random.default_rng(5)
+    k = rng.standard_normal((40, 8))
+    pos = np.arange(5)
+    # zero queries: every row is uniform, its k largest entries hold k/C of the mass
+    assert abs(O.text_sparsity_score(np.zeros((2, 5, 8)), k, pos, 0.3, 4) - 4 / 40) < 1e-15
+    # identical keys: uniform again, whatever the queries
+    assert abs(O.text_sparsity_score(rng.standard_normal((3, 5, 8)), np.ones((40, 8)), pos, 0.3, 7) - 7 / 40) < 1e-15
+    # k = C keeps everything
+    assert abs(O.text_sparsity_score(rng.standard_normal((2, 5, 8)), k, pos, 0.3, 40) - 1.0) < 1e-14
+    # one key far above the rest: nearly all mass in the top-1
+    kk = np.zeros((40, 1)); kk[17] = 60.0
+    assert abs(O.text_sparsity_score(np.ones((1, 3, 1)), kk, np.arange(3), 1.0, 1) - 1.0) < 1e-15
+    # the same key only ln(39) above 39 zeros: half of the mass
+    kk[17] = math.log(39.0)
+    assert abs(O.text_sparsity_score(np.ones((1, 3, 1)), kk, np.arange(3), 1.0, 1) - 0.5) < 1e-15
+
+
+def test_sparsity_score_hand_worked_rows():
+    # d = 1, q = 1, keys ln(1..4): row probabilities 1/10, 2/10, 3/10, 4/10; top-2 sum 7/10
+    k = np.log(np.array([[1.0], [2.0], [3.0], [4.0]]))
+    assert abs(O.text_sparsity_score(np.ones((1, 1, 1)), k, np.array([3]), 1.0, 2) - 0.7) < 1e-15
+    # second row with q = 2: weights 1, 4, 9, 16 over 30; top-2 sum 25/30; mean of the two rows
+    q = np.array([[[1.0], [2.0]]])
+    assert abs(O.text_sparsity_score(q, k, np.array([2, 3]), 1.0, 2) - 0.5 * (0.7 + 25 / 30)) < 1e-15
+    # causal: the token at position 1 sees keys 0..1 only: weights 1/3, 2/3 -> top-2 = 1, top-1 = 2/3
+    assert abs(O.text_sparsity_score(np.ones((1, 1, 1)), k, np.array([1]), 1.0, 1, causal=True) - 2 / 3) < 1e-15
+    assert abs(O.text_sparsity_score(np.ones((1, 1, 1)), k, np.array([0]), 1.0, 1, causal=True) - 1.0) < 1e-15
+
+
+def test_sparsity_score_against_sorted_library_softmax():
+    rng = np.random.default_rng(6)
+    G, T, C, d = 3, 11, 97, 16
+    q, k = rng.standard_normal((G, T, d)), rng.standard_normal((C, d))
+    pos = np.sort(rng.choice(C, T, replace=False))
+    for causal in (False, True):
+        want = 0.0
+        for g in range(G):
+            for t in range(T):
+                lg = (k @ q[g, t]) * 0.7
+                if causal:
+                    lg = lg[: pos[t] + 1]
+                p = np.sort(scipy.special.softmax(lg))[::-1]
+                want += p[:9].sum()
+        got = O.text_sparsity_score(q, k, pos, 0.7, 9, causal=causal)
+        assert abs(got - want / (G * T)) < 1e-13
+    # grouped heads: the score is the mean of the single-head scores
+    singles = [O.text_sparsity_score(q[g:g + 1], k, pos, 0.7, 9) for g in range(G)]
+    assert abs(O.text_sparsity_score(q, k, pos, 0.7, 9) - np.mean(singles)) < 1e-14
+    # key order does not matter without the mask; more focus positions never lower the score
+    perm = rng.permutation(C)
+    assert abs(O.text_sparsity_score(q, k[perm], pos, 0.7, 9) - O.text_sparsity_score(q, k, pos, 0.7, 9)) < 1e-13
+    vals = [O.text_sparsity_score(q, k, pos, 0.7, kt) for kt in (1, 5, 20, 97)]
+    assert all(a < b for a, b in zip(vals, vals[1:])) and all(v >= kt / C - 1e-15 for v, kt in zip(vals, (1, 5, 20, 97)))
+
+
+def test_focus_count_and_threshold():
+    assert O.focus_count(8192) == 410 and O.focus_count(2048) == 103 and O.focus_count(10) == 1 and O.focus_count(40, 0.5) == 20
+    types = O.classify_heads(np.array([0.95, 0.9, 0.8999]), 0.9)
+    assert types.tolist() == [O.STATIC, O.STATIC, O.DYNAMIC]
+
+
+def test_head_scores_driver_matches_unit_calls():
+    wl = make_workload(0, n_layers=1, shrink=8, steps=1)
+    cfg = O.OracleConfig(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128, window=wl.window,
+                         dtype=wl.dtype)
+    rng = np.random.default_rng(3)
+    qp = rng.standard_normal((1, wl.total_tokens, wl.n_q_heads, 128))
+    sc = O.head_scores(cfg, wl.cu_seqlens, qp, wl.k, wl.is_visual)
+    G = wl.n_q_heads // wl.n_kv_heads
+    pos = np.nonzero(wl.is_visual == 0)[0]
+    h = 2
+    qt = np.stack([qp[0, pos, h * G + g] for g in range(G)])
+    want = O.text_sparsity_score(qt, wl.k[0, :, h], pos, cfg.scale, O.focus_count(wl.total_tokens))
+    assert sc.shape == (1, 1, wl.n_kv_heads) and abs(sc[0, 0, h] - want) < 1e-15
+
+
+# ---------------------------------------------------------------- budget allocation (Section 3.2)
+def test_type_level_budget_split():
+    for b_total, ns, nd, r in [(1000, 3, 5, 0.75), (22932, 56, 56, 0.75), (999, 1, 7, 1.0), (500, 4, 0, 0.75), (64, 0, 4, 0.5)]:
+        bs, bd = O.type_level_budgets(b_total, ns, nd, r)
+        assert bs + bd == b_total and bs >= 0 and bd >= 0
+        if nd:
+            exact = r * b_total / (ns + nd) * nd
+            assert exact - 1e-9 <= bd < exact + 1
+    # r = 1: the dynamic heads get their uniform share
+    assert O.type_level_budgets(1200, 2, 4, 1.0) == (400, 800)
+    # r above the stated bound is clipped: nothing is left over-committed
+    assert O.type_level_budgets(100, 1, 1, 5.0) == (0, 100)
+
+
+def test_static_head_budgets_invariants():
+    rng = np.random.default_rng(8)
+    sc = rng.uniform(0.9, 1.0, 17)
+    for alpha in (0.0, 0.3, 1.0):
+        b = O.static_head_budgets(5000, sc, alpha)
+        exact = alpha * 5000 / 17 + (1 - alpha) * 5000 * sc / sc.sum()
+        assert np.all(b >= exact - 1e-9) and np.all(b < exact + 1)          # each is a ceiling
+        assert 5000 <= b.sum() < 5000 + 17                                   # total exceeds B_stat by < N_stat
+    assert np.all(O.static_head_budgets(5000, sc, 1.0) == math.ceil(5000 / 17))           # base budget only
+    assert np.all(O.static_head_budgets(340, np.full(17, 0.93), 0.4) == 20)              # equal scores: uniform
+    b = O.static_head_budgets(1000, np.array([1.0, 3.0]), 0.0)                            # proportional only
+    assert b.tolist() == [250, 750]
+
+
+def test_dynamic_budget_padding():
+    # 10 % of 2048 tokens at r = 0.75 is 153.6 per head: nearest power of two is 128 (four chunks of 32)
+    assert O.dynamic_head_budget(round(153.6 * 10), 10) == 128
+    assert O.dynamic_head_budget(96 * 3, 3) == 128          # tie between 64 and 128 goes up
+    assert O.dynamic_head_budget(95 * 3, 3) == 64
+    assert O.dynamic_head_budget(300, 3, pad_pow2=False) == 100
+    assert O.dynamic_head_budget(0, 0) == 0
