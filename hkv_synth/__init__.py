@@ -7,6 +7,7 @@ tests/bench take their inputs from here, and nothing else is shared between
 the two.
 """
 from .workloads import (  # noqa: F401
+    make_prompt_queries,
     CONFIGS,
     Workload,
     bf16_round,

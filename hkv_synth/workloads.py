@@ -349,3 +349,28 @@ def make_workload(cfg_id: int, seed: Optional[int] = None, *, budget_rule: str =
         head_type=head_type, budget=budget, budget_rule=budget_rule, budget_frac=fracs,
         max_new_tokens=max_new_tokens if max_new_tokens is not None else max(n_steps, 1), steps=n_steps,
         q_window=q_window, k=k, v=v, q_steps=q_steps, k_new=k_new, v_new=v_new, planted=planted, seed=seed)
+
+
+def make_prompt_queries(wl: Workload, seed: int = 0, sharp_gain: float = 2.5) -> np.ndarray:
+    """Queries of the whole prompt, [L, total_tokens, Hq, d] (float32 holding dtype-exact values), for the
+    head-classification step that runs before the compression.
+
+    N(0,1) everywhere; on the query heads of KV heads marked static in the workload, the text tokens'
+    queries additionally point at that head's planted keys (along the mean planted key, which is the
+    planted direction up to noise), so that their attention concentrates on about 5 % of the visual
+    tokens and the head comes out sparse; the other heads stay diffuse.  Needs wl.k and wl.planted.
+    """
+    rng = np.random.default_rng([0x48594B51, int(wl.seed if wl.seed is not None else 0), int(seed)])
+    L, Hq, Hkv, d = wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    G = Hq // Hkv
+    total = int(wl.cu_seqlens[-1])
+    q = rng.standard_normal((L, total, Hq, d), dtype=np.float32)
+    for (b, l, h), pos in wl.planted.items():
+        if pos.size == 0:
+            continue
+        s0, s1 = int(wl.cu_seqlens[b]), int(wl.cu_seqlens[b + 1])
+        direction = wl.k[l, s0 + pos, h, :].astype(np.float64).mean(axis=0)
+        direction /= np.linalg.norm(direction)
+        text = s0 + np.nonzero(wl.is_visual[s0:s1] == 0)[0]
+        q[l, text[:, None], np.arange(h * G, (h + 1) * G)[None, :], :] += (sharp_gain * math.sqrt(d) * direction).astype(np.float32)
+    return _cast(q, wl.dtype)

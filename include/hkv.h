@@ -232,6 +232,42 @@ HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);
 HKV_API int hkv_profile_read(hkv_cache* cache, double* ms, int* n_calls);
 HKV_API int hkv_profile_disable(hkv_cache* cache);
 
+/* ---- upstream of hkv_compress: head classification and budget allocation ------------------------
+ *
+ * hkv_head_scores: text-centric sparsity score of every (layer, sequence, KV head) (paper, Section 3.1).
+ * Every text token of the prompt (is_visual == 0) attends over the whole prompt with its G query heads,
+ * softmax(q K^T * scale) over all keys (with cfg->score_causal = 1 only over keys at or before the
+ * token); a row contributes the sum of its k = ceil(focus_fraction * C) largest probabilities (ties at
+ * the k-th place counted as often as they fit); the score is the mean over the G*T rows, 0 for a
+ * sequence without text.  The paper states k = ceil(0.05 C) for its focus measure; pass 0.05 for that
+ * (a double, so that 0.05 * C does not creep over an integer).
+ *   cu_seqlens, is_visual : [host] as in hkv_plan
+ *   q_prompt : [device] [n_layers_call][total_tokens][n_q_heads][head_dim]  queries of the whole prompt
+ *   k        : [device] [n_layers_call][total_tokens][n_kv_heads][head_dim]
+ *   scores   : [device] [n_layers_call][batch][n_kv_heads] float
+ *   workspace: [device, 16-byte aligned] at least *min_bytes of hkv_head_scores_workspace_size (one head's
+ *              logits at a time); with *best_bytes all KV heads of a (layer, sequence) go in one pass.
+ * Uses cfg's shape, dtype, softmax_scale and score_causal.  Work is enqueued on `stream`; the call
+ * synchronises the stream once at entry (it uploads the text positions).  Not meant for graph capture. */
+HKV_API int hkv_head_scores_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens,
+                                   const uint8_t* is_visual, size_t* min_bytes, size_t* best_bytes);
+HKV_API int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens, const uint8_t* is_visual,
+                    int n_layers_call, const void* q_prompt, const void* k, double focus_fraction, float* scores,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* hkv_allocate_budgets: head types and token budgets of one sequence from its sparsity scores (paper,
+ * Section 3.1 threshold and Section 3.2, both equations).  Pure host arithmetic on [host] arrays of
+ * n_heads entries (all layers and KV heads of the sequence, any order):
+ *   head_type[i] = HKV_STATIC if scores[i] >= theta else HKV_DYNAMIC;
+ *   B_dyna = ceil(r * (B_total / N) * N_dyna) with r = share_ratio clipped so that B_dyna <= B_total,
+ *   B_stat = B_total - B_dyna;
+ *   static head: ceil(alpha * B_stat / N_stat + (1 - alpha) * B_stat * score / (sum of static scores));
+ *   dynamic head: B_dyna / N_dyna, rounded to the nearest power of two (ties upwards) if pad_pow2 != 0,
+ *                 else rounded down.
+ * The budgets feed hkv_plan.budget as they are ("total retained prompt tokens" for static heads). */
+HKV_API int hkv_allocate_budgets(int32_t n_heads, const float* scores, float theta, int64_t total_budget,
+                         float share_ratio, float alpha, int32_t pad_pow2, uint8_t* head_type, int32_t* budget);
+
 /* Reference measurement for benchmarks (not part of the method): average duration, in microseconds,
  * of a kernel that only reads `read_bytes` (rounded down to a multiple of 128 KiB) of `buf` [device,
  * 16-byte aligned, buf_bytes long], taken from the kernel's own start/stop time stamps over `reps`

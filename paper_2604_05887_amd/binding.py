@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
     "hkv_cache_decode_shape", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
-    "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read",
+    "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read", "hkv_head_scores_workspace_size", "hkv_head_scores", "hkv_allocate_budgets",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
 
@@ -89,6 +89,12 @@ def load_library() -> C.CDLL:
     lib.hkv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.hkv_profile_disable.argtypes = [vp]
     lib.hkv_probe_stream_read.argtypes = [vp, sz, sz, i32, vp, C.POINTER(C.c_double)]
+    lib.hkv_head_scores_workspace_size.argtypes = [C.POINTER(hkv_config), C.c_int32, C.POINTER(C.c_int32),
+                                                   C.POINTER(C.c_uint8), C.POINTER(sz), C.POINTER(sz)]
+    lib.hkv_head_scores.argtypes = [C.POINTER(hkv_config), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_uint8), i32, vp, vp,
+                                    C.c_double, vp, vp, sz, vp]
+    lib.hkv_allocate_budgets.argtypes = [C.c_int32, C.POINTER(C.c_float), C.c_float, C.c_int64, C.c_float, C.c_float,
+                                         C.c_int32, C.POINTER(C.c_uint8), C.POINTER(C.c_int32)]
     lib.hkv_cache_destroy.argtypes = [vp]
     lib.hkv_cache_destroy.restype = None
     lib.hkv_strerror.argtypes = [i32]
@@ -247,6 +253,39 @@ def hkv_cache_set_decode_dynamic(handle: int, mode: int) -> None:
 
 def hkv_cache_set_device_tail(handle: int, enable: bool, stream=None) -> None:
     _check(load_library().hkv_cache_set_device_tail(handle, 1 if enable else 0, stream), "hkv_cache_set_device_tail")
+
+
+def hkv_head_scores_workspace_size(cfg: hkv_config, cu_seqlens, is_visual) -> Tuple[int, int]:
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    vis = np.ascontiguousarray(is_visual, dtype=np.uint8)
+    lo, hi = C.c_size_t(0), C.c_size_t(0)
+    _check(load_library().hkv_head_scores_workspace_size(C.byref(cfg), len(cu) - 1, cu.ctypes.data_as(C.POINTER(C.c_int32)),
+                                                         vis.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(lo), C.byref(hi)),
+           "hkv_head_scores_workspace_size")
+    return int(lo.value), int(hi.value)
+
+
+def hkv_head_scores(cfg: hkv_config, cu_seqlens, is_visual, n_layers_call: int, q_prompt, k, focus_fraction: float,
+                    scores, workspace, workspace_bytes: int, stream=None) -> None:
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    vis = np.ascontiguousarray(is_visual, dtype=np.uint8)
+    _check(load_library().hkv_head_scores(C.byref(cfg), len(cu) - 1, cu.ctypes.data_as(C.POINTER(C.c_int32)),
+                                          vis.ctypes.data_as(C.POINTER(C.c_uint8)), n_layers_call, _ptr(q_prompt), _ptr(k),
+                                          focus_fraction, _ptr(scores), _ptr(workspace), workspace_bytes, _stream(stream)),
+           "hkv_head_scores")
+
+
+def hkv_allocate_budgets(scores, theta: float, total_budget: int, share_ratio: float, alpha: float,
+                         pad_pow2: bool = True) -> Tuple[np.ndarray, np.ndarray]:
+    """(head_type uint8, budget int32), same shape as `scores` (host arrays)."""
+    sc = np.ascontiguousarray(scores, dtype=np.float32)
+    types = np.zeros(sc.shape, np.uint8)
+    budget = np.zeros(sc.shape, np.int32)
+    _check(load_library().hkv_allocate_budgets(sc.size, sc.ctypes.data_as(C.POINTER(C.c_float)), theta, total_budget,
+                                               share_ratio, alpha, 1 if pad_pow2 else 0,
+                                               types.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                               budget.ctypes.data_as(C.POINTER(C.c_int32))), "hkv_allocate_budgets")
+    return types, budget
 
 
 def hkv_probe_stream_read(buf_ptr: int, buf_bytes: int, read_bytes: int, reps: int, stream: int = 0) -> float:

@@ -8,6 +8,31 @@
 
 #include "hkv_internal.h"
 
+namespace hkv {
+
+int validate_config(const hkv_config* cfg) {
+  if (!cfg) return HKV_EINVAL;
+  if (cfg->struct_size != sizeof(hkv_config) || cfg->abi_version != HKV_ABI_VERSION) return HKV_EINVAL;
+  if (cfg->dtype != HKV_F32 && cfg->dtype != HKV_BF16) return HKV_EINVAL;
+  if (cfg->score_causal != 0 && cfg->score_causal != 1) return HKV_EINVAL;
+  if (cfg->head_dim != kD) return HKV_ESHAPE;
+  if (cfg->n_layers < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1) return HKV_ESHAPE;
+  if (cfg->n_q_heads % cfg->n_kv_heads != 0) return HKV_ESHAPE;
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  if (G < 1 || G > kMaxG) return HKV_ESHAPE;
+  if (cfg->window < 1 || G * cfg->window > kMaxScoreRows) return HKV_ESHAPE;
+  if (cfg->max_new_tokens < 0) return HKV_ESHAPE;
+  if (cfg->decode_tile_rows != 0) {
+    const int t = cfg->decode_tile_rows;
+    if (cfg->dtype != HKV_BF16 || (t != 128 && t != 256 && t != 512 && t != 1024)) return HKV_ESHAPE;
+  }
+  if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 3) return HKV_EINVAL;
+  if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
+  return HKV_OK;
+}
+
+}  // namespace hkv
+
 using namespace hkv;
 
 namespace {
@@ -38,27 +63,6 @@ struct Layout {
   size_t ws_bytes = 0, ws_o_bytes = 0;
   int tile = 0;
 };
-
-int validate_config(const hkv_config* cfg) {
-  if (!cfg) return HKV_EINVAL;
-  if (cfg->struct_size != sizeof(hkv_config) || cfg->abi_version != HKV_ABI_VERSION) return HKV_EINVAL;
-  if (cfg->dtype != HKV_F32 && cfg->dtype != HKV_BF16) return HKV_EINVAL;
-  if (cfg->score_causal != 0 && cfg->score_causal != 1) return HKV_EINVAL;
-  if (cfg->head_dim != kD) return HKV_ESHAPE;
-  if (cfg->n_layers < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1) return HKV_ESHAPE;
-  if (cfg->n_q_heads % cfg->n_kv_heads != 0) return HKV_ESHAPE;
-  const int G = cfg->n_q_heads / cfg->n_kv_heads;
-  if (G < 1 || G > kMaxG) return HKV_ESHAPE;
-  if (cfg->window < 1 || G * cfg->window > kMaxScoreRows) return HKV_ESHAPE;
-  if (cfg->max_new_tokens < 0) return HKV_ESHAPE;
-  if (cfg->decode_tile_rows != 0) {
-    const int t = cfg->decode_tile_rows;
-    if (cfg->dtype != HKV_BF16 || (t != 128 && t != 256 && t != 512 && t != 1024)) return HKV_ESHAPE;
-  }
-  if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 3) return HKV_EINVAL;
-  if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
-  return HKV_OK;
-}
 
 inline bool pow2_ge4(int c) { return c >= 4 && (c & (c - 1)) == 0; }
 

@@ -1,0 +1,350 @@
+// Text-centric head classification (paper, Section 3.1) and the host side of the top-down budget
+// allocation (Section 3.2): the two steps upstream of hkv_compress.
+//
+// Sparsity score of a KV head: every text token of the prompt attends over the whole prompt,
+// S_text = softmax(Q_text K^T / sqrt(d)); a row contributes the sum of its k largest probabilities,
+// k = ceil(focus * C); the score is the mean over the text rows (and over the G query heads that
+// share the KV head).  Heads at or above a threshold are static, the others dynamic.
+//
+// Device plan, one (layer, sequence) pass at a time, all KV heads of the pass together:
+//   logits_kernel   S = Q_text K^T on the matrix cores, logits (log2 domain) written to the workspace
+//   row_topk_kernel one workgroup per text row: row maximum, normaliser, exact k-th largest logit by
+//                   radix selection, sum of the probabilities above it plus the admitted ties
+//   reduce_kernel   mean of the row values of each head, in a fixed order
+// The logits of a pass are materialised (rows x C floats per head): the exact top-k of a row needs the
+// whole row several times, and 288 GB of HBM make that the simple way to have it.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "hkv_internal.h"
+#include "hkv_mma.h"
+#include "hkv_select.h"
+
+namespace hkv {
+
+constexpr int kRowsPerBlock = 256;     // text rows staged per workgroup of logits_kernel
+constexpr int kKeysPerLogitBlock = 512;
+
+// grid = (key splits, row chunks, heads of the pass); block = 256 threads.
+// Row r of a head is (g = r / T, t = r % T): query head head*G + g at the t-th text token.
+template <typename T>
+__global__ __launch_bounds__(256) void logits_kernel(const T* __restrict__ q_layer, const T* __restrict__ k_layer,
+                                                     const int32_t* __restrict__ text_pos, int64_t seq_start, int C,
+                                                     int n_text, int G, int n_q_heads, int n_kv_heads, int head0,
+                                                     float scale_log2e, float* __restrict__ logits,
+                                                     int64_t head_stride, int pitch) {
+  constexpr int ROWB = kD * sizeof(T);
+  constexpr int PITCH = ROWB + 16;
+  constexpr int NPIECE = ROWB / 32;
+  constexpr int PPR = ROWB / 16;
+  extern __shared__ char qs[];                  // [kRowsPerBlock][PITCH]
+  const int tid = thread_index(), lane = tid & 63, wv = tid >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int head = head0 + blockIdx.z;
+  const int rows = G * n_text;
+  const int row0 = blockIdx.y * kRowsPerBlock;
+  const int rows_here = min(kRowsPerBlock, rows - row0);
+  const int n_rb = (rows_here + 31) / 32;
+  const int key0 = blockIdx.x * kKeysPerLogitBlock;
+
+  // stage the query rows of this chunk (zero rows past the end), eight independent loads per round
+  for (int base = 0; base < n_rb * 32 * PPR; base += 256 * 8) {
+    uint4 val[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * 256 + tid;
+      const int rl = idx / PPR, piece = idx % PPR;
+      val[u] = make_uint4(0, 0, 0, 0);
+      if (idx < n_rb * 32 * PPR && rl < rows_here) {
+        const int r = row0 + rl, g = r / n_text, t = r % n_text;
+        const size_t src = ((size_t)(seq_start + text_pos[t]) * n_q_heads + (size_t)head * G + g) * ROWB;
+        val[u] = ld16(reinterpret_cast<const char*>(q_layer) + src + piece * 16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * 256 + tid;
+      if (idx < n_rb * 32 * PPR) st16(qs + (size_t)(idx / PPR) * PITCH + (idx % PPR) * 16, val[u]);
+    }
+  }
+  __syncthreads();
+
+  const char* kbase = reinterpret_cast<const char*>(k_layer) + ((size_t)seq_start * n_kv_heads + head) * ROWB;
+  const size_t kstride = (size_t)n_kv_heads * ROWB;
+  float* out = logits + (size_t)blockIdx.z * head_stride;
+  for (int kt = 0; kt < kKeysPerLogitBlock / 128; ++kt) {
+    const int j0 = key0 + (kt * 4 + wv) * 32;
+    if (j0 >= C) break;                          // wave-uniform
+    const int key = j0 + l32;
+    uint4 a[NPIECE];
+#pragma unroll
+    for (int j = 0; j < NPIECE; ++j) {
+      a[j] = make_uint4(0, 0, 0, 0);
+      if (key < C) a[j] = ld16(kbase + (size_t)key * kstride + j * 32 + half * 16);
+    }
+    for (int rb = 0; rb < n_rb; ++rb) {
+      floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+      const char* qrow = qs + (size_t)(rb * 32 + l32) * PITCH + half * 16;
+#pragma unroll
+      for (int j = 0; j < NPIECE; ++j) acc = mma_piece(a[j], ld16(qrow + j * 32), acc, T{});
+      // acc[r] = q_row(rb*32 + l32) . k(j0 + 8*(r/4) + 4*half + r%4): four runs of four consecutive keys.
+      // The row pitch is a multiple of 32 keys, so a run past C stays inside the row and is never read.
+      const int rl = rb * 32 + l32;
+      if (rl < rows_here) {
+        float* dst = out + (size_t)(row0 + rl) * pitch + j0 + 4 * half;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+          *reinterpret_cast<float4*>(dst + 8 * g4) =
+              make_float4(acc[4 * g4] * scale_log2e, acc[4 * g4 + 1] * scale_log2e, acc[4 * g4 + 2] * scale_log2e,
+                          acc[4 * g4 + 3] * scale_log2e);
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ float key_to_float(uint32_t key) {      // inverse of float_order_key
+  return bits_to_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+}
+
+// Block-wide reductions in thread order (deterministic); `red` holds 4 floats.  Two barriers each.
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = fmaxf(v, lane_xor(v, 1)); v = fmaxf(v, lane_xor(v, 2)); v = fmaxf(v, lane_xor(v, 4));
+  v = fmaxf(v, lane_xor(v, 8)); v = fmaxf(v, lane_xor(v, 16)); v = fmaxf(v, lane_xor(v, 32));
+  if ((thread_index() & 63) == 0) red[thread_index() >> 6] = v;
+  __syncthreads();
+  const float r = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  return r;
+}
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = sum64(v);
+  if ((thread_index() & 63) == 0) red[thread_index() >> 6] = v;
+  __syncthreads();
+  const float r = (red[0] + red[1]) + (red[2] + red[3]);
+  __syncthreads();
+  return r;
+}
+
+// grid = rows of the pass (heads x G x T), block = 256 threads: one text row per workgroup.
+// row value = (sum of the k_top largest probabilities of the row), ties at the k-th place counted as
+// often as they are admitted.
+__global__ __launch_bounds__(256) void row_topk_kernel(const float* __restrict__ logits, int64_t head_stride, int pitch,
+                                                       const int32_t* __restrict__ text_pos, int C, int n_text,
+                                                       int rows_per_head, int k_top, int causal,
+                                                       float* __restrict__ row_value) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t bc[2];
+  __shared__ float red[4];
+  const int tid = thread_index();
+  const int hp = blockIdx.x / rows_per_head, r = blockIdx.x % rows_per_head;
+  const float* row = logits + (size_t)hp * head_stride + (size_t)r * pitch;
+  const int n = causal ? min(C, text_pos[r % n_text] + 1) : C;       // keys this text token sees
+  const int kt = min(k_top, n);
+
+  float m = kNeg;
+  for (int j = tid; j < n; j += 256) m = fmaxf(m, row[j]);
+  m = block_max(m, red);
+  float z = 0.f;
+  for (int j = tid; j < n; j += 256) z += fast_exp2(row[j] - m);
+  z = block_sum(z, red);
+
+  uint32_t t_key = 0;
+  int r_adm = 0;
+  radix_select<256>(n, kt, [&](int j, uint32_t& key) { key = float_order_key(row[j]); return true; }, hist, bc, t_key,
+                    r_adm);
+  float above = 0.f;
+  for (int j = tid; j < n; j += 256) {
+    const float l = row[j];
+    above += float_order_key(l) > t_key ? fast_exp2(l - m) : 0.f;
+  }
+  above = block_sum(above, red);
+  if (tid == 0) row_value[blockIdx.x] = (above + (float)r_adm * fast_exp2(key_to_float(t_key) - m)) / z;
+}
+
+// grid = heads of the pass, block = 256 threads: mean of the head's row values, fixed summation order.
+__global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ row_value, int rows_per_head,
+                                                     float* __restrict__ scores) {
+  __shared__ float red[4];
+  const int tid = thread_index();
+  const float* v = row_value + (size_t)blockIdx.x * rows_per_head;
+  float s = 0.f;
+  for (int j = tid; j < rows_per_head; j += 256) s += v[j];
+  s = block_sum(s, red);
+  if (tid == 0) scores[blockIdx.x] = s / (float)rows_per_head;
+}
+
+}  // namespace hkv
+
+using namespace hkv;
+
+namespace {
+
+constexpr size_t kAlignC = 256;
+inline size_t align_up_c(size_t x) { return (x + kAlignC - 1) / kAlignC * kAlignC; }
+
+struct ClassifyShape {
+  std::vector<int32_t> text_pos;        // all sequences, packed
+  std::vector<int64_t> text_begin;      // [batch + 1]
+  size_t off_pos = 0, off_rows = 0, off_logits = 0;
+  size_t max_rows = 0;                  // G * T of the sequence with the most text
+  size_t head_bytes_max = 0;            // logits of one head of the largest sequence
+};
+
+int classify_shape(const hkv_config* cfg, int32_t batch, const int32_t* cu, const uint8_t* is_visual, ClassifyShape& sh) {
+  int rc = validate_config(cfg);
+  if (rc != HKV_OK) return rc;
+  if (!cu || !is_visual) return HKV_EINVAL;
+  if (batch < 1 || batch > 4096 || cu[0] != 0) return HKV_ESHAPE;
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  sh.text_begin.assign(batch + 1, 0);
+  for (int b = 0; b < batch; ++b) {
+    const int64_t C = (int64_t)cu[b + 1] - cu[b];
+    if (C < 1 || C >= (1 << 24)) return HKV_ESHAPE;
+    for (int64_t j = cu[b]; j < cu[b + 1]; ++j) {
+      if (is_visual[j] > 1) return HKV_EINVAL;
+      if (!is_visual[j]) sh.text_pos.push_back((int32_t)(j - cu[b]));
+    }
+    sh.text_begin[b + 1] = (int64_t)sh.text_pos.size();
+    const size_t T = (size_t)(sh.text_begin[b + 1] - sh.text_begin[b]);
+    const size_t pitch = ((size_t)C + 31) / 32 * 32;
+    sh.max_rows = std::max(sh.max_rows, (size_t)G * T);
+    sh.head_bytes_max = std::max(sh.head_bytes_max, (size_t)G * T * pitch * sizeof(float));
+  }
+  sh.off_pos = 0;
+  sh.off_rows = align_up_c(std::max<size_t>(1, sh.text_pos.size()) * 4);
+  sh.off_logits = sh.off_rows + align_up_c(std::max<size_t>(1, (size_t)cfg->n_kv_heads * sh.max_rows) * 4);
+  return HKV_OK;
+}
+
+}  // namespace
+
+int hkv_head_scores_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens,
+                                   const uint8_t* is_visual, size_t* min_bytes, size_t* best_bytes) {
+  if (!min_bytes && !best_bytes) return HKV_EINVAL;
+  ClassifyShape sh;
+  int rc = classify_shape(cfg, batch, cu_seqlens, is_visual, sh);
+  if (rc != HKV_OK) return rc;
+  if (min_bytes) *min_bytes = sh.off_logits + align_up_c(sh.head_bytes_max);
+  if (best_bytes) *best_bytes = sh.off_logits + align_up_c(sh.head_bytes_max * (size_t)cfg->n_kv_heads);
+  return HKV_OK;
+}
+
+int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens, const uint8_t* is_visual,
+                    int n_layers_call, const void* q_prompt, const void* k, double focus_fraction, float* scores,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  ClassifyShape sh;
+  int rc = classify_shape(cfg, batch, cu_seqlens, is_visual, sh);
+  if (rc != HKV_OK) return rc;
+  if (!q_prompt || !k || !scores || !workspace || n_layers_call < 1) return HKV_EINVAL;
+  if (!(focus_fraction > 0.0) || !(focus_fraction <= 1.0)) return HKV_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(q_prompt) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(workspace)) & 15u)
+    return HKV_EALIGN;
+  if (workspace_bytes < sh.off_logits + align_up_c(sh.head_bytes_max)) return HKV_ENOSPACE;
+  const int Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, G = Hq / Hkv;
+  const size_t es = cfg->dtype == HKV_BF16 ? 2 : 4;
+  const int64_t total = cu_seqlens[batch];
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  int32_t* d_pos = reinterpret_cast<int32_t*>(ws + sh.off_pos);
+  float* d_rows = reinterpret_cast<float*>(ws + sh.off_rows);
+  float* d_logits = reinterpret_cast<float*>(ws + sh.off_logits);
+  // the text positions are the only host data the kernels need; the copy must be over before this
+  // function's vectors go away, hence the one synchronisation
+  if (!sh.text_pos.empty() &&
+      (hipMemcpyAsync(d_pos, sh.text_pos.data(), sh.text_pos.size() * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
+       hipStreamSynchronize(st) != hipSuccess))
+    return HKV_EHIP;
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)kD);
+  const float scale_log2e = scale * 1.4426950408889634f;
+  const size_t logits_room = workspace_bytes - sh.off_logits;
+  const size_t smem = (size_t)kRowsPerBlock * (kD * es + 16);
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[cfg->dtype == HKV_BF16]) {
+    const void* fn = cfg->dtype == HKV_BF16 ? reinterpret_cast<const void*>(&logits_kernel<bf16_t>)
+                                            : reinterpret_cast<const void*>(&logits_kernel<float>);
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) return HKV_EHIP;
+    attr_set[cfg->dtype == HKV_BF16] = true;
+  }
+  for (int l = 0; l < n_layers_call; ++l) {
+    const char* q_layer = static_cast<const char*>(q_prompt) + (size_t)l * total * Hq * kD * es;
+    const char* k_layer = static_cast<const char*>(k) + (size_t)l * total * Hkv * kD * es;
+    for (int b = 0; b < batch; ++b) {
+      const int C = cu_seqlens[b + 1] - cu_seqlens[b];
+      const int T = (int)(sh.text_begin[b + 1] - sh.text_begin[b]);
+      float* out = scores + ((size_t)l * batch + b) * Hkv;
+      if (T == 0) {                              // no text token: the score is defined as 0
+        if (hipMemsetAsync(out, 0, (size_t)Hkv * 4, st) != hipSuccess) return HKV_EHIP;
+        continue;
+      }
+      const int rows = G * T;
+      const int pitch = (C + 31) / 32 * 32;
+      const int64_t head_stride = (int64_t)rows * pitch;
+      const int heads_per_pass = (int)std::min<size_t>((size_t)Hkv, logits_room / ((size_t)head_stride * 4));
+      const int k_top = std::max(1, std::min(C, (int)std::ceil(focus_fraction * C - 1e-9)));
+      const int32_t* pos = d_pos + sh.text_begin[b];
+      for (int h0 = 0; h0 < Hkv; h0 += heads_per_pass) {
+        const int nh = std::min(heads_per_pass, Hkv - h0);
+        const dim3 grid((C + kKeysPerLogitBlock - 1) / kKeysPerLogitBlock, (rows + kRowsPerBlock - 1) / kRowsPerBlock, nh);
+        if (cfg->dtype == HKV_BF16)
+          hipLaunchKernelGGL(logits_kernel<bf16_t>, grid, dim3(256), smem, st, reinterpret_cast<const bf16_t*>(q_layer),
+                             reinterpret_cast<const bf16_t*>(k_layer), pos, (int64_t)cu_seqlens[b], C, T, G, Hq, Hkv, h0,
+                             scale_log2e, d_logits, head_stride, pitch);
+        else
+          hipLaunchKernelGGL(logits_kernel<float>, grid, dim3(256), smem, st, reinterpret_cast<const float*>(q_layer),
+                             reinterpret_cast<const float*>(k_layer), pos, (int64_t)cu_seqlens[b], C, T, G, Hq, Hkv, h0,
+                             scale_log2e, d_logits, head_stride, pitch);
+        hipLaunchKernelGGL(row_topk_kernel, dim3((unsigned)(nh * rows)), dim3(256), 0, st, d_logits, head_stride, pitch, pos,
+                           C, T, rows, k_top, cfg->score_causal, d_rows);
+        hipLaunchKernelGGL(reduce_kernel, dim3(nh), dim3(256), 0, st, d_rows, rows, out + h0);
+        if (hipGetLastError() != hipSuccess) return HKV_EHIP;
+      }
+    }
+  }
+  return HKV_OK;
+}
+
+// ---- budget allocation (host arithmetic, Section 3.2) ---------------------------------------------
+int hkv_allocate_budgets(int32_t n_heads, const float* scores, float theta, int64_t total_budget, float share_ratio,
+                         float alpha, int32_t pad_pow2, uint8_t* head_type, int32_t* budget) {
+  if (n_heads < 1 || !scores || !head_type || !budget || total_budget < 0) return HKV_EINVAL;
+  if (!(share_ratio >= 0.f) || !(alpha >= 0.f) || !(alpha <= 1.f)) return HKV_EINVAL;
+  int n_stat = 0, n_dyn = 0;
+  double stat_sum = 0.0;
+  for (int i = 0; i < n_heads; ++i) {
+    if (!(scores[i] >= 0.f)) return HKV_EINVAL;                    // NaN or negative
+    head_type[i] = scores[i] >= theta ? HKV_STATIC : HKV_DYNAMIC;
+    if (head_type[i] == HKV_STATIC) { ++n_stat; stat_sum += (double)scores[i]; } else ++n_dyn;
+  }
+  // type level: B_dyna = ceil(r * B_bar * N_dyna), r clipped so that it cannot exceed the total
+  int64_t b_dyn = 0;
+  if (n_dyn > 0) {
+    const double b_bar = (double)total_budget / n_heads;
+    const double r = std::min((double)share_ratio, (double)total_budget / std::max(b_bar * n_dyn, 1e-300));
+    b_dyn = std::min<int64_t>(total_budget, (int64_t)std::ceil(r * b_bar * n_dyn - 1e-9));
+  }
+  const int64_t b_stat = total_budget - b_dyn;
+  // dynamic heads: uniform share, optionally to the nearest power of two (ties upwards)
+  int64_t dyn_each = 0;
+  if (n_dyn > 0) {
+    const double b = (double)b_dyn / n_dyn;
+    if (!pad_pow2) dyn_each = (int64_t)b;
+    else if (b <= 1.0) dyn_each = 1;
+    else {
+      const double lo = std::exp2(std::floor(std::log2(b)));
+      dyn_each = (int64_t)((b - lo) < (2.0 * lo - b) ? lo : 2.0 * lo);
+    }
+  }
+  for (int i = 0; i < n_heads; ++i) {
+    int64_t v;
+    if (head_type[i] == HKV_DYNAMIC) v = dyn_each;
+    else {
+      const double s_norm = stat_sum > 0.0 ? (double)scores[i] / stat_sum : 1.0 / n_stat;
+      v = (int64_t)std::ceil((double)alpha * b_stat / n_stat + (1.0 - (double)alpha) * b_stat * s_norm - 1e-9);
+    }
+    if (v > 0x7fffffff) return HKV_ESHAPE;
+    budget[i] = (int32_t)v;
+  }
+  return HKV_OK;
+}

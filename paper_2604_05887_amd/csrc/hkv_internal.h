@@ -100,6 +100,9 @@ struct CacheView {
 
 // ---- launchers implemented in the kernel translation units (all asynchronous on `st`) ----
 // decode
+// Field-by-field check of a configuration (HKV_OK or the status the entry points return for it).
+int validate_config(const hkv_config* cfg);
+
 // The launches of a decode step over a layer range.  t_arg: tail length before the step if the host
 // knows it, else -1 (device counters).  select_only: the dynamic blocks stop after the chunk selection.
 // launch_attn_merge also publishes the new tail counters when t_arg < 0, so it runs last.

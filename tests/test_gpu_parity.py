@@ -367,3 +367,57 @@ def test_decode_recorded_in_a_hip_graph_replays_correctly():
     assert torch.equal(out_g, out_e)
     for dw in (eager, rec, warm):
         dw.cache.close()
+
+
+def _device_head_scores(wl, qp, causal=False, rho=0.05, small_workspace=False):
+    cfg = B.make_config(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                        dtype=runner.hkv_dtype(wl.dtype), window=wl.window, score_causal=int(causal))
+    lo, hi = B.hkv_head_scores_workspace_size(cfg, wl.cu_seqlens, wl.is_visual)
+    nbytes = lo if small_workspace else hi
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    q_dev, k_dev = runner.to_device(qp, wl.dtype), runner.to_device(wl.k, wl.dtype)
+    scores = torch.full((wl.n_layers, wl.batch, wl.n_kv_heads), -1.0, dtype=torch.float32, device="cuda:0")
+    B.hkv_head_scores(cfg, wl.cu_seqlens, wl.is_visual, wl.n_layers, q_dev, k_dev, rho, scores, ws, nbytes)
+    torch.cuda.synchronize()
+    return scores.cpu().numpy().transpose(1, 0, 2)          # [batch, L, Hkv] like the oracle
+
+
+SCORE_ATOL = 5e-5     # fp32 logits (exact bf16/fp32 products, fp32 accumulation of 128 terms), exp2, fp32 sums
+
+
+@pytest.mark.parametrize("cfg_id,shrink,causal", [(1, 4, False), (1, 4, True), (0, 2, False), (4, 8, False), (4, 8, True)])
+def test_head_sparsity_scores_match_the_oracle(cfg_id, shrink, causal):
+    """Text-centric sparsity score of every (sequence, layer, KV head) against the float64 oracle: bf16 and
+    fp32, one sequence and a ragged batch, with and without the causal option; the head types at the
+    paper's threshold agree wherever the score is not within the tolerance of it."""
+    from hkv_synth import make_prompt_queries
+    wl = make_workload(cfg_id, n_layers=2, shrink=shrink, steps=1)
+    qp = make_prompt_queries(wl)
+    got = _device_head_scores(wl, qp, causal=causal)
+    ocfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128,
+                          window=wl.window, dtype=wl.dtype, score_causal=causal)
+    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual)
+    err = np.abs(got - want).max()
+    print(f"\n[head scores cfg{cfg_id}/{shrink} causal={causal}] max abs err {err:.2e}; scores {want.min():.3f}..{want.max():.3f}",
+          flush=True)
+    assert err <= SCORE_ATOL
+    clear = np.abs(want - 0.9) > 2 * SCORE_ATOL
+    assert np.array_equal(O.classify_heads(got, 0.9)[clear], O.classify_heads(want, 0.9)[clear])
+    # the generator's static heads are the sparse ones
+    assert np.all(want[wl.head_type == 0] > 0.9) and np.all(want[wl.head_type == 1] < 0.6)
+
+
+def test_head_scores_do_not_depend_on_the_workspace_size_and_focus_edges():
+    from hkv_synth import make_prompt_queries
+    wl = make_workload(1, n_layers=1, shrink=8, steps=1)
+    qp = make_prompt_queries(wl)
+    a = _device_head_scores(wl, qp)
+    b = _device_head_scores(wl, qp, small_workspace=True)       # one head per pass
+    assert np.array_equal(a, b)
+    ocfg = O.OracleConfig(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128, window=wl.window,
+                          dtype=wl.dtype)
+    full = _device_head_scores(wl, qp, rho=1.0)                 # every position counts: the score is 1
+    assert np.abs(full - 1.0).max() <= SCORE_ATOL
+    tiny = _device_head_scores(wl, qp, rho=1e-6)                # k = 1: mean of the row maxima
+    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual, rho=1e-6)
+    assert np.abs(tiny - want).max() <= SCORE_ATOL

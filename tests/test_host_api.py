@@ -114,3 +114,47 @@ def test_cache_size_covers_the_rows_it_promises(lib):
             rows += (r if wl.head_type[0, l, h] == 0 else int(wl.seqlens[0])) + 8
     assert cache_bytes >= 2 * rows * 128 * 2
     assert cache_bytes < 2 * rows * 128 * 2 * 1.2 + (1 << 20)
+
+
+def test_budget_allocation_matches_the_oracle_equations(lib):
+    """hkv_allocate_budgets (host arithmetic) against the oracle's type-level split, static-head formula
+    and power-of-two padding, on random score sets and on the degenerate head maps."""
+    rng = np.random.default_rng(21)
+    for trial in range(40):
+        n = int(rng.integers(1, 120))
+        scores = rng.uniform(0.7, 1.0, n).astype(np.float32)
+        if trial == 0:
+            scores[:] = 0.95                       # all static
+        if trial == 1:
+            scores[:] = 0.5                        # all dynamic
+        theta = 0.9
+        b_total = int(rng.integers(n, 400 * n))
+        r, alpha = float(rng.uniform(0.3, 1.2)), float(rng.uniform(0.0, 1.0))
+        pad = bool(trial % 2)
+        types, budget = B.hkv_allocate_budgets(scores, theta, b_total, r, alpha, pad)
+        want_types = O.classify_heads(scores, theta)
+        assert np.array_equal(types, want_types)
+        stat = want_types == O.STATIC
+        b_stat, b_dyn = O.type_level_budgets(b_total, int(stat.sum()), int((~stat).sum()), r)
+        want = np.zeros(n, np.int64)
+        want[stat] = O.static_head_budgets(b_stat, scores[stat].astype(np.float64), alpha)
+        want[~stat] = O.dynamic_head_budget(b_dyn, int((~stat).sum()), pad_pow2=pad)
+        assert np.array_equal(budget.astype(np.int64), want), (trial, n, b_total, r, alpha)
+    with pytest.raises(B.HkvError):
+        B.hkv_allocate_budgets(np.array([0.5, np.nan], np.float32), 0.9, 100, 0.75, 0.5)
+    with pytest.raises(B.HkvError):
+        B.hkv_allocate_budgets(np.array([0.5], np.float32), 0.9, 100, 0.75, 1.5)
+
+
+def test_head_scores_workspace_and_argument_checks(lib):
+    wl = make_workload(1, n_layers=1, shrink=8, tensors=False)
+    cfg = B.make_config(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, dtype=B.HKV_BF16, window=wl.window)
+    lo, hi = B.hkv_head_scores_workspace_size(cfg, wl.cu_seqlens, wl.is_visual)
+    G = wl.n_q_heads // wl.n_kv_heads
+    T = int((wl.is_visual == 0).sum())
+    C = int(wl.cu_seqlens[-1])
+    head_bytes = G * T * ((C + 31) // 32 * 32) * 4
+    assert lo >= head_bytes and hi >= wl.n_kv_heads * head_bytes and hi - lo >= (wl.n_kv_heads - 1) * head_bytes
+    bad = np.array(wl.is_visual, copy=True); bad[3] = 7
+    with pytest.raises(B.HkvError):
+        B.hkv_head_scores_workspace_size(cfg, wl.cu_seqlens, bad)
