@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-kv", action="store_true", help="skip the full-KV comparison kernel")
+    ap.add_argument("--classify", action="store_true",
+                    help="also time the head-classification scores (hkv_head_scores) on device-drawn prompt queries")
+    ap.add_argument("--classify-layers", type=int, default=4, help="layers to run the classification on (0 = all)")
     ap.add_argument("--no-tune", action="store_true",
                     help="keep the library's default way of running the dynamic heads instead of timing all three")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read reference")
@@ -160,6 +163,44 @@ def main() -> int:
         torch.cuda.synchronize()
         comp_ms.append(e0.elapsed_time(e1))
     compress_ms = statistics.median(comp_ms[1:]) if len(comp_ms) > 1 else comp_ms[0]
+
+    # ---- upstream step: head classification scores of the whole prompt (device-drawn queries) ----------
+    classify = None
+    if args.classify:
+        cfg0 = copies[0].cfg
+        lo_b, hi_b = B.hkv_head_scores_workspace_size(cfg0, wl.cu_seqlens, wl.is_visual)
+        cws_bytes = min(hi_b, max(lo_b, 48 << 30))
+        cws = torch.empty(cws_bytes, dtype=torch.uint8, device=dev)
+        n_lc = min(L, args.classify_layers) if args.classify_layers > 0 else L
+        gq = torch.Generator(device=dev)
+        gq.manual_seed(77)
+        qp = torch.empty((n_lc, wl.total_tokens, Hq, d), dtype=tdt, device=dev)
+        for i in range(n_lc):
+            qp[i] = torch.randn((wl.total_tokens, Hq, d), generator=gq, device=dev, dtype=torch.float32).to(tdt)
+        sc = torch.empty((n_lc, Bn, Hkv), dtype=torch.float32, device=dev)
+        times = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            B.hkv_head_scores(cfg0, wl.cu_seqlens, wl.is_visual, n_lc, qp, k[:n_lc], 0.05, sc, cws, cws_bytes, sptr)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        G_ = Hq // Hkv
+        flops = 0.0
+        logit_bytes = 0.0
+        for b in range(Bn):
+            C_b = int(wl.seqlens[b])
+            T_b = int((wl.is_visual[wl.cu_seqlens[b]:wl.cu_seqlens[b + 1]] == 0).sum())
+            flops += 2.0 * G_ * T_b * C_b * d * Hkv * n_lc
+            logit_bytes += 4.0 * G_ * T_b * C_b * Hkv * n_lc
+        ms = min(times[1:])
+        classify = {"layers": n_lc, "ms": round(ms, 3), "ms_scaled_to_all_layers": round(ms * L / n_lc, 3),
+                    "contraction_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                    "logit_bytes_written": int(logit_bytes), "workspace_bytes": int(cws_bytes),
+                    "mean_score": round(float(sc.mean().item()), 4)}
+        del cws, qp
 
     def raw_step(dw, i):
         j = i % n_inputs
@@ -414,6 +455,7 @@ def main() -> int:
         "us_per_step_one_call_per_layer_hip_graph": None if lw_graph_us is None else round(lw_graph_us, 2),
         "speedup_vs_full_kv": round(full_ms / ms_per_step, 3),
         "compress_ms": round(compress_ms, 3),
+        "head_classification": classify,
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
         "decode_shape": {"tile_rows": tile_rows, "dynamic_mode": dyn_mode, "tuned_us_per_step": tuned_us},
         "kernel_us": {"main_launch": round(a_us, 2), "second_launch": round(b_us, 2),

@@ -163,6 +163,64 @@ __global__ __launch_bounds__(256) void row_topk_kernel(const float* __restrict__
   if (tid == 0) row_value[blockIdx.x] = (above + (float)r_adm * fast_exp2(key_to_float(t_key) - m)) / z;
 }
 
+// Same result as row_topk_kernel for rows of at most 256 * EPT keys, with the row read once and held in
+// registers (EPT logits per thread).  The k-th largest key is found by a 32-step bitwise search on
+// workgroup-wide vote counts (one barrier per step), as the chunk top-k of the decode path does per wave.
+template <int EPT>
+__global__ __launch_bounds__(256) void row_topk_reg_kernel(const float* __restrict__ logits, int64_t head_stride, int pitch,
+                                                           const int32_t* __restrict__ text_pos, int C, int n_text,
+                                                           int rows_per_head, int k_top, int causal,
+                                                           float* __restrict__ row_value) {
+  __shared__ float red[4];
+  __shared__ int cnt[2][4];
+  const int tid = thread_index(), wv = tid >> 6;
+  const int hp = blockIdx.x / rows_per_head, r = blockIdx.x % rows_per_head;
+  const float* row = logits + (size_t)hp * head_stride + (size_t)r * pitch;
+  const int n = causal ? min(C, text_pos[r % n_text] + 1) : C;
+  const int kt = min(k_top, n);
+
+  float v[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int j = tid + 256 * e;
+    v[e] = j < n ? row[j] : kNeg;
+  }
+  float m = v[0];
+#pragma unroll
+  for (int e = 1; e < EPT; ++e) m = fmaxf(m, v[e]);
+  m = block_max(m, red);
+  float z = 0.f;
+  uint32_t key[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const bool in = tid + 256 * e < n;
+    key[e] = in ? float_order_key(v[e]) : 0u;                      // 0 is below the key of every finite logit
+    v[e] = in ? fast_exp2(v[e] - m) : 0.f;                         // from here on v holds the unnormalised weight
+    z += v[e];
+  }
+  z = block_sum(z, red);
+
+  uint32_t thr = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = thr | (1u << bit);
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+    if ((tid & 63) == 0) cnt[bit & 1][wv] = c;
+    __syncthreads();                       // the other buffer is rewritten only after the next barrier
+    if (cnt[bit & 1][0] + cnt[bit & 1][1] + cnt[bit & 1][2] + cnt[bit & 1][3] >= kt) thr = cand;
+  }
+  float above = 0.f, n_gt = 0.f;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    above += key[e] > thr ? v[e] : 0.f;
+    n_gt += key[e] > thr ? 1.f : 0.f;
+  }
+  above = block_sum(above, red);
+  n_gt = block_sum(n_gt, red);             // exact: at most 2^24 keys
+  if (tid == 0) row_value[blockIdx.x] = (above + ((float)kt - n_gt) * fast_exp2(key_to_float(thr) - m)) / z;
+}
+
 // grid = heads of the pass, block = 256 threads: mean of the head's row values, fixed summation order.
 __global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ row_value, int rows_per_head,
                                                      float* __restrict__ scores) {
@@ -295,8 +353,15 @@ int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seql
           hipLaunchKernelGGL(logits_kernel<float>, grid, dim3(256), smem, st, reinterpret_cast<const float*>(q_layer),
                              reinterpret_cast<const float*>(k_layer), pos, (int64_t)cu_seqlens[b], C, T, G, Hq, Hkv, h0,
                              scale_log2e, d_logits, head_stride, pitch);
-        hipLaunchKernelGGL(row_topk_kernel, dim3((unsigned)(nh * rows)), dim3(256), 0, st, d_logits, head_stride, pitch, pos,
-                           C, T, rows, k_top, cfg->score_causal, d_rows);
+        const dim3 rgrid((unsigned)(nh * rows));
+#define HKV_ROW_TOPK(KERNEL) \
+  hipLaunchKernelGGL(KERNEL, rgrid, dim3(256), 0, st, d_logits, head_stride, pitch, pos, C, T, rows, k_top, \
+                     cfg->score_causal, d_rows)
+        if (C <= 256 * 32) HKV_ROW_TOPK(row_topk_reg_kernel<32>);
+        else if (C <= 256 * 64) HKV_ROW_TOPK(row_topk_reg_kernel<64>);
+        else if (C <= 256 * 128) HKV_ROW_TOPK(row_topk_reg_kernel<128>);
+        else HKV_ROW_TOPK(row_topk_kernel);      // longer rows are re-read from memory on every pass
+#undef HKV_ROW_TOPK
         hipLaunchKernelGGL(reduce_kernel, dim3(nh), dim3(256), 0, st, d_rows, rows, out + h0);
         if (hipGetLastError() != hipSuccess) return HKV_EHIP;
       }

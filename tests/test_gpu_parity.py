@@ -421,3 +421,27 @@ def test_head_scores_do_not_depend_on_the_workspace_size_and_focus_edges():
     tiny = _device_head_scores(wl, qp, rho=1e-6)                # k = 1: mean of the row maxima
     want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual, rho=1e-6)
     assert np.abs(tiny - want).max() <= SCORE_ATOL
+
+
+@pytest.mark.parametrize("n_visual", [9800, 19900, 40000])
+def test_head_scores_on_long_rows(n_visual):
+    """Rows longer than 8192 keys take the wider register-resident forms of the per-row top-k (up to 16384
+    and 32768 keys) and, beyond that, the form that re-reads the row from memory; few text tokens keep
+    the oracle quick."""
+    from hkv_synth import make_prompt_queries
+    from hkv_synth import workloads as W
+    base = dict(W.CONFIGS[1])
+    base.update(name=f"long_{n_visual}", n_layers=1, n_visual=[n_visual], n_text=[96], block=n_visual, steps=1)
+    W.CONFIGS[98] = base
+    try:
+        wl = make_workload(98, seed=5)
+    finally:
+        del W.CONFIGS[98]
+    qp = make_prompt_queries(wl)
+    got = _device_head_scores(wl, qp)
+    ocfg = O.OracleConfig(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128, window=wl.window,
+                          dtype=wl.dtype)
+    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual)
+    err = np.abs(got - want).max()
+    print(f"\n[head scores C={int(wl.seqlens[0])}] max abs err {err:.2e}", flush=True)
+    assert err <= SCORE_ATOL
