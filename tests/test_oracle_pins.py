@@ -435,3 +435,16 @@ def test_dynamic_budget_padding():
     assert O.dynamic_head_budget(95 * 3, 3) == 64
     assert O.dynamic_head_budget(300, 3, pad_pow2=False) == 100
     assert O.dynamic_head_budget(0, 0) == 0
+
+
+def test_sparsity_score_gaussian_logits_closed_form():
+    """Logits that are i.i.d. N(0,1): the top 5 % of the positions carry 1 - Phi(z_0.95 - 1) = 0.2595 of the
+    softmax mass in the limit of many keys (the mass of e^x above the 95th percentile of a standard normal)."""
+    from scipy.stats import norm
+    rng = np.random.default_rng(12)
+    C, d = 40000, 16
+    q = np.zeros((1, 6, d)); q[0, :, 0] = 1.0                      # unit queries: logit = first key coordinate
+    k = rng.standard_normal((C, d))
+    got = O.text_sparsity_score(q, k, np.arange(6), 1.0, O.focus_count(C))
+    want = 1.0 - norm.cdf(norm.ppf(0.95) - 1.0)
+    assert abs(want - 0.2595) < 1e-3 and abs(got - want) < 0.01
