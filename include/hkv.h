@@ -135,6 +135,31 @@ HKV_API int hkv_query_sizes(const hkv_config* cfg, const hkv_plan* plan, size_t*
 HKV_API int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev, size_t cache_bytes,
                      hkv_cache** out);
 
+/* Host-memory tier for the dynamic heads (Section 3.3: a dynamic head keeps its whole prompt K/V
+ * outside GPU memory, only the chunk summaries stay resident, and each decode step brings in the
+ * chunks it selected).  bf16 caches only (HKV_ESHAPE otherwise).
+ *
+ * A tiered cache keeps, in the device arena: the static heads' rows, every head's decode tail, the
+ * chunk summaries, the selections and the descriptor tables; and in `host_tier`: the prompt rows
+ * of the dynamic heads, in the same blocked layout.  hkv_compress writes those rows straight into
+ * the host tier, and the decode kernels read the selected chunks' blocks from it in place (the
+ * reads travel over the host link while other workgroups of the same launch read device memory),
+ * so there is no staging buffer and no copy call.  Results are identical to those of an untiered
+ * cache.
+ *
+ * hkv_query_tier_sizes reports the three sizes for that arrangement.
+ * hkv_cache_create_tiered takes, besides hkv_cache_create's arguments,
+ *   host_tier [host] >= host_bytes, 256-byte aligned: page-locked host memory that the current
+ *             device can address (hipHostMalloc or an allocator built on it).  Pageable memory or a
+ *             device pointer -> HKV_EINVAL, found through hipPointerGetAttributes before any kernel
+ *             runs.  The call zero-fills it.  The caller owns it and keeps it allocated and
+ *             unmodified for the life of the cache.
+ * All other entry points take a tiered cache like any other. */
+HKV_API int hkv_query_tier_sizes(const hkv_config* cfg, const hkv_plan* plan, size_t* cache_bytes,
+                         size_t* host_bytes, size_t* workspace_bytes);
+HKV_API int hkv_cache_create_tiered(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev,
+                            size_t cache_bytes, void* host_tier, size_t host_bytes, hkv_cache** out);
+
 /* Prefill compression of layers [layer_begin, layer_end) (Section 3.3, Appendix A).
  *   q_window [dev] [n][batch][window][n_q_heads][head_dim]  queries of each sequence's last
  *            `window` prompt positions,

@@ -24,7 +24,7 @@ HKV_STATIC, HKV_DYNAMIC = 0, 1
 HKV_ABI_VERSION = 1
 
 EXPORTED_SYMBOLS = (
-    "hkv_query_sizes", "hkv_cache_create", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
+    "hkv_query_sizes", "hkv_cache_create", "hkv_query_tier_sizes", "hkv_cache_create_tiered", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
     "hkv_cache_decode_shape", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
     "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read", "hkv_head_scores_workspace_size", "hkv_head_scores", "hkv_allocate_budgets",
@@ -67,6 +67,9 @@ def load_library() -> C.CDLL:
     vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
     lib.hkv_query_sizes.argtypes = [C.POINTER(hkv_config), C.POINTER(hkv_plan), C.POINTER(sz), C.POINTER(sz)]
     lib.hkv_cache_create.argtypes = [C.POINTER(hkv_config), C.POINTER(hkv_plan), vp, sz, C.POINTER(vp)]
+    lib.hkv_query_tier_sizes.argtypes = [C.POINTER(hkv_config), C.POINTER(hkv_plan), C.POINTER(sz), C.POINTER(sz),
+                                         C.POINTER(sz)]
+    lib.hkv_cache_create_tiered.argtypes = [C.POINTER(hkv_config), C.POINTER(hkv_plan), vp, sz, vp, sz, C.POINTER(vp)]
     lib.hkv_compress.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.hkv_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.hkv_full_workspace_size.argtypes = [C.POINTER(hkv_config), C.c_int32, C.POINTER(C.c_int32), i32, C.POINTER(sz)]
@@ -169,6 +172,22 @@ def hkv_cache_create(cfg: hkv_config, plan: PlanArrays, cache_dev, cache_bytes: 
     h = C.c_void_p(None)
     _check(load_library().hkv_cache_create(C.byref(cfg), C.byref(plan.struct), _ptr(cache_dev), cache_bytes,
                                            C.byref(h)), "hkv_cache_create")
+    return int(h.value)
+
+
+def hkv_query_tier_sizes(cfg: hkv_config, plan: PlanArrays) -> Tuple[int, int, int]:
+    cb, hb, wb = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check(load_library().hkv_query_tier_sizes(C.byref(cfg), C.byref(plan.struct), C.byref(cb), C.byref(hb),
+                                               C.byref(wb)), "hkv_query_tier_sizes")
+    return int(cb.value), int(hb.value), int(wb.value)
+
+
+def hkv_cache_create_tiered(cfg: hkv_config, plan: PlanArrays, cache_dev, cache_bytes: int, host_tier,
+                            host_bytes: int) -> int:
+    h = C.c_void_p(None)
+    _check(load_library().hkv_cache_create_tiered(C.byref(cfg), C.byref(plan.struct), _ptr(cache_dev), cache_bytes,
+                                                  _ptr(host_tier), host_bytes, C.byref(h)),
+           "hkv_cache_create_tiered")
     return int(h.value)
 
 
@@ -357,15 +376,27 @@ def hkv_cache_import(handle: int, what: int, seq: int, layer: int, head: int, va
 class HybridKVCache:
     """Allocates the cache arena and workspace as torch tensors and forwards to the C entry points."""
 
-    def __init__(self, cfg: hkv_config, plan: PlanArrays, device="cuda:0"):
+    def __init__(self, cfg: hkv_config, plan: PlanArrays, device="cuda:0", host_tier: bool = False):
+        """host_tier: keep the dynamic heads' prompt rows in page-locked host memory (bf16 caches)."""
         import torch
         self.cfg, self.plan = cfg, plan
-        self.cache_bytes, self.workspace_bytes = hkv_query_sizes(cfg, plan)
+        self.host_bytes = 0
+        if host_tier:
+            self.cache_bytes, self.host_bytes, self.workspace_bytes = hkv_query_tier_sizes(cfg, plan)
+        else:
+            self.cache_bytes, self.workspace_bytes = hkv_query_sizes(cfg, plan)
         self.arena = torch.empty(self.cache_bytes + 256, dtype=torch.uint8, device=device)
         pad = (-self.arena.data_ptr()) % 256
         self.arena_view = self.arena[pad:pad + self.cache_bytes]
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
-        self.handle = hkv_cache_create(cfg, plan, self.arena_view, self.cache_bytes)
+        if host_tier:
+            self.host_arena = torch.empty(self.host_bytes + 256, dtype=torch.uint8, pin_memory=True)
+            hpad = (-self.host_arena.data_ptr()) % 256
+            self.host_view = self.host_arena[hpad:hpad + self.host_bytes]
+            self.handle = hkv_cache_create_tiered(cfg, plan, self.arena_view, self.cache_bytes, self.host_view,
+                                                  self.host_bytes)
+        else:
+            self.handle = hkv_cache_create(cfg, plan, self.arena_view, self.cache_bytes)
 
     def compress(self, q_window, k, v, layer_begin=0, layer_end=None, stream=None):
         le = self.cfg.n_layers if layer_end is None else layer_end

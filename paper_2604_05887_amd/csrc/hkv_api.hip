@@ -57,6 +57,10 @@ struct Layout {
   int mode = 2;                    // how decode steps run the dynamic heads (hkv_config.decode_dynamic, resolved)
   // element counts
   int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
+  // host tier (bf16 caches only): the dynamic units' prompt rows live in mapped host memory
+  bool tiered = false;
+  int64_t n_rows_host = 0;
+  size_t host_off_k = 0, host_off_v = 0, host_bytes = 0;
   // arena offsets (bytes)
   size_t off_units = 0, off_sitems = 0, off_ditems = 0, off_static_descs = 0, off_static = 0, off_dynamic = 0, off_dyn_descs = 0, off_vis = 0, off_cnt = 0, off_kept = 0,
          off_sel = 0, off_scores = 0, off_sigma = 0, off_mu = 0, off_k = 0, off_v = 0, arena_bytes = 0;
@@ -66,9 +70,11 @@ struct Layout {
 
 inline bool pow2_ge4(int c) { return c >= 4 && (c & (c - 1)) == 0; }
 
-int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, int tile) {
+int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, int tile, bool tiered) {
   int rc = validate_config(cfg);
   if (rc != HKV_OK) return rc;
+  if (tiered && cfg->dtype != HKV_BF16) return HKV_ESHAPE;   // the host tier exists for bf16 caches only
+  lo.tiered = tiered;
   if (!plan || !plan->cu_seqlens || !plan->is_visual || !plan->head_type || !plan->budget) return HKV_EINVAL;
   if (plan->batch < 1 || plan->batch > 4096) return HKV_ESHAPE;
   const int B = plan->batch, L = cfg->n_layers, H = cfg->n_kv_heads, w = cfg->window;
@@ -117,6 +123,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
         d.seq_start = lo.cu[b]; d.C = C; d.kind = ht; d.seq = b; d.layer = l; d.head = h;
         d.kv_row_off = lo.n_rows;
         int64_t phys_rows;
+        bool rows_on_host = false;
         if (ht == HKV_STATIC) {
           // Keep set = window + historical text + Top-M historical visual, M = budget - w - #text
           // (Appendix A); text outranks visual when the budget is short (Section 3.3).
@@ -150,8 +157,16 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
           if (blocked && c < kBlkRows) return HKV_ESHAPE;     // bf16 caches gather whole 8-row blocks
           phys_rows = blocked ? (C + kBlkRows - 1) / kBlkRows * kBlkRows : C;
           d.tail_row = (int32_t)phys_rows;
+          rows_on_host = tiered;
         }
-        {
+        if (rows_on_host) {
+          // prompt rows in the host arrays, the decode tail (whole blocks) in the device arrays
+          d.kv_row_off = lo.n_rows_host;
+          lo.n_rows_host += phys_rows;
+          d.tail_off = lo.n_rows;
+          lo.n_rows += ((int64_t)cfg->max_new_tokens + kBlkRows - 1) / kBlkRows * kBlkRows;
+        } else {
+          d.tail_off = d.kv_row_off + d.tail_row;
           const int64_t cap = phys_rows + cfg->max_new_tokens;
           lo.n_rows += blocked ? (cap + kBlkRows - 1) / kBlkRows * kBlkRows : cap;
         }
@@ -175,6 +190,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
           it.dynamic = ht == HKV_DYNAMIC;
           it.layer = l; it.seq = b; it.head = h;
           it.tail_row = d.tail_row;
+          it.tail_off = d.tail_off;
           it.slot = (int32_t)lo.n_items++;
           if (ht == HKV_DYNAMIC) {
             it.n_chunks = d.n_chunks; it.k_sel = d.k_sel; it.aux_off = d.aux_off;
@@ -215,6 +231,9 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
   lo.off_k = take((size_t)lo.n_rows * kD * es);
   lo.off_v = take((size_t)lo.n_rows * kD * es);
   lo.arena_bytes = off;
+  lo.host_off_k = 0;
+  lo.host_off_v = align_up((size_t)lo.n_rows_host * kD * es);
+  lo.host_bytes = tiered ? std::max<size_t>(kAlign, lo.host_off_v + align_up((size_t)lo.n_rows_host * kD * es)) : 0;
 
   const int n_splits = (lo.max_C + kKeysPerBlock - 1) / kKeysPerBlock;
   const size_t ws_compress = align_up(lo.static_units.size() * (size_t)n_splits * kMaxScoreRows * sizeof(float2)) +
@@ -232,16 +251,16 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 // plus the combination, as long as the repeated reads of the chunk summaries stay below a quarter of
 // the step's bytes (they mostly hit the L2); with many small chunks the selection runs once per head
 // and the tiles follow in a second launch.
-int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo) {
+int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool tiered = false) {
   int rc;
-  if (cfg && cfg->dtype != HKV_BF16) rc = plan_layout_tile(cfg, plan, lo, kTileF32);
-  else if (cfg && cfg->decode_tile_rows != 0) rc = plan_layout_tile(cfg, plan, lo, cfg->decode_tile_rows);
+  if (cfg && cfg->dtype != HKV_BF16) rc = plan_layout_tile(cfg, plan, lo, kTileF32, tiered);
+  else if (cfg && cfg->decode_tile_rows != 0) rc = plan_layout_tile(cfg, plan, lo, cfg->decode_tile_rows, tiered);
   else {
     int tile = kTileBf16;
-    rc = plan_layout_tile(cfg, plan, lo, tile);
+    rc = plan_layout_tile(cfg, plan, lo, tile, tiered);
     while (rc == HKV_OK && tile < kTileBf16Max) {
       Layout next;
-      if (plan_layout_tile(cfg, plan, next, tile * 2) != HKV_OK || next.n_items < 2048) break;
+      if (plan_layout_tile(cfg, plan, next, tile * 2, tiered) != HKV_OK || next.n_items < 2048) break;
       tile *= 2;
       lo = std::move(next);
     }
@@ -259,6 +278,7 @@ struct hkv_cache {
   Layout lo;
   CacheView cv;
   char* arena;
+  char* host_tier = nullptr;          // host address of the host tier (null: every row is in device memory)
   std::vector<int32_t> host_tail;     // [n_layers] appended tokens (host mirror of the device counter)
   bool device_tail = false;           // decode calls take the tail length from the device counters only
   std::vector<uint8_t> compressed;    // [n_layers]
@@ -297,15 +317,42 @@ int hkv_query_sizes(const hkv_config* cfg, const hkv_plan* plan, size_t* cache_b
   return HKV_OK;
 }
 
-int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev, size_t cache_bytes,
-                     hkv_cache** out) {
-  if (!out || !cache_dev) return HKV_EINVAL;
+int hkv_query_tier_sizes(const hkv_config* cfg, const hkv_plan* plan, size_t* cache_bytes, size_t* host_bytes,
+                         size_t* workspace_bytes) {
+  if (!cache_bytes || !host_bytes || !workspace_bytes) return HKV_EINVAL;
+  Layout lo;
+  const int rc = plan_layout(cfg, plan, lo, true);
+  if (rc != HKV_OK) return rc;
+  *cache_bytes = lo.arena_bytes;
+  *host_bytes = lo.host_bytes;
+  *workspace_bytes = lo.ws_bytes;
+  return HKV_OK;
+}
+
+static int create_cache(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev, size_t cache_bytes,
+                        void* host_tier, size_t host_bytes, bool tiered, hkv_cache** out) {
+  if (!out || !cache_dev || (tiered && !host_tier)) return HKV_EINVAL;
   if (reinterpret_cast<uintptr_t>(cache_dev) % kAlign != 0) return HKV_EALIGN;
+  if (tiered && reinterpret_cast<uintptr_t>(host_tier) % kAlign != 0) return HKV_EALIGN;
   hkv_cache* c = new (std::nothrow) hkv_cache();
   if (!c) return HKV_EINVAL;
-  int rc = plan_layout(cfg, plan, c->lo);
+  int rc = plan_layout(cfg, plan, c->lo, tiered);
   if (rc != HKV_OK) { delete c; return rc; }
-  if (cache_bytes < c->lo.arena_bytes) { delete c; return HKV_ENOSPACE; }
+  if (cache_bytes < c->lo.arena_bytes || (tiered && host_bytes < c->lo.host_bytes)) { delete c; return HKV_ENOSPACE; }
+  char* host_dev = nullptr;            // the host tier as the kernels address it
+  if (tiered) {
+    // The tier must be page-locked host memory that the current device can address; anything else
+    // (pageable memory, a device allocation) is turned away here, before a kernel could touch it.
+    hipPointerAttribute_t at;
+    std::memset(&at, 0, sizeof(at));
+    if (hipPointerGetAttributes(&at, host_tier) != hipSuccess) { (void)hipGetLastError(); delete c; return HKV_EINVAL; }
+    if (at.type != hipMemoryTypeHost || !at.devicePointer || !at.hostPointer) { delete c; return HKV_EINVAL; }
+    host_dev = static_cast<char*>(at.devicePointer);
+    if (reinterpret_cast<uintptr_t>(host_dev) % kAlign != 0) { delete c; return HKV_EALIGN; }
+    // unwritten rows of a short last chunk still enter the weighted sums with weight zero: keep them finite
+    std::memset(host_tier, 0, c->lo.host_bytes);
+  }
+  c->host_tier = static_cast<char*>(host_tier);
   c->cfg = *cfg;
   c->batch = plan->batch;
   {
@@ -337,6 +384,8 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   cv.mu = a + lo.off_mu;
   cv.k_rows = a + lo.off_k;
   cv.v_rows = a + lo.off_v;
+  cv.k_dyn = tiered ? host_dev + lo.host_off_k : cv.k_rows;
+  cv.v_dyn = tiered ? host_dev + lo.host_off_v : cv.v_rows;
   cv.n_layers = cfg->n_layers; cv.batch = plan->batch; cv.n_q_heads = cfg->n_q_heads; cv.n_kv_heads = cfg->n_kv_heads;
   cv.G = cfg->n_q_heads / cfg->n_kv_heads; cv.window = cfg->window; cv.max_new = cfg->max_new_tokens;
   cv.causal = cfg->score_causal;
@@ -371,6 +420,16 @@ int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_de
   if (e != hipSuccess) { delete c; return HKV_EHIP; }
   *out = c;
   return HKV_OK;
+}
+
+int hkv_cache_create(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev, size_t cache_bytes,
+                     hkv_cache** out) {
+  return create_cache(cfg, plan, cache_dev, cache_bytes, nullptr, 0, false, out);
+}
+
+int hkv_cache_create_tiered(const hkv_config* cfg, const hkv_plan* plan, void* cache_dev, size_t cache_bytes,
+                            void* host_tier, size_t host_bytes, hkv_cache** out) {
+  return create_cache(cfg, plan, cache_dev, cache_bytes, host_tier, host_bytes, true, out);
 }
 
 int hkv_profile_disable(hkv_cache* c) {
@@ -718,22 +777,36 @@ int hkv_cache_export(const hkv_cache* c, int what, int seq, int layer, int head,
   if (!dst || bytes < need) return HKV_ENOSPACE;
   if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return HKV_EHIP;
   if ((what == HKV_X_K_ROWS || what == HKV_X_V_ROWS) && c->cfg.dtype == HKV_BF16) {
-    // blocked layout -> plain rows: prompt rows, then the tail rows
+    // blocked layout -> plain rows: the prompt rows (device arrays, or the host tier for a dynamic unit of
+    // a tiered cache), then the tail rows (always in the device arrays)
+    const bool is_k = what == HKV_X_K_ROWS;
     const int tail = c->host_tail[d->layer];
     const int n_prompt = d->kind == HKV_STATIC ? d->n_prompt_rows : d->C;
-    const size_t phys_rows = (size_t)d->tail_row + tail;
-    const size_t n_blk = (phys_rows + kBlkRows - 1) / kBlkRows;
-    std::vector<uint16_t> raw(n_blk * kBlkRows * kD);
-    if (n_blk && hipMemcpy(raw.data(), c->arena + off, n_blk * kBlkBytes, hipMemcpyDeviceToHost) != hipSuccess)
-      return HKV_EHIP;
+    const char* prompt_base = static_cast<const char*>(d->kind == HKV_DYNAMIC ? (is_k ? c->cv.k_dyn : c->cv.v_dyn)
+                                                                              : (is_k ? c->cv.k_rows : c->cv.v_rows));
+    const char* tail_base = static_cast<const char*>(is_k ? c->cv.k_rows : c->cv.v_rows);
+    // physical rows [r0, r0 + n) of one array, as whole blocks
+    auto fetch = [&](const char* base, int64_t r0, int64_t n, std::vector<uint16_t>& raw, int64_t& first_blk) {
+      first_blk = r0 / kBlkRows;
+      const int64_t n_blk = n > 0 ? (r0 + n + kBlkRows - 1) / kBlkRows - first_blk : 0;
+      raw.resize((size_t)n_blk * kBlkRows * kD);
+      if (n_blk == 0) return true;
+      return hipMemcpy(raw.data(), base + (size_t)first_blk * kBlkBytes, (size_t)n_blk * kBlkBytes, hipMemcpyDefault) ==
+             hipSuccess;
+    };
+    std::vector<uint16_t> raw_p, raw_t;
+    int64_t fb_p = 0, fb_t = 0;
+    if (!fetch(prompt_base, d->kv_row_off, n_prompt, raw_p, fb_p)) return HKV_EHIP;
+    if (!fetch(tail_base, d->tail_off, tail, raw_t, fb_t)) return HKV_EHIP;
     uint16_t* out = static_cast<uint16_t*>(dst);
     for (int r = 0; r < n_prompt + tail; ++r) {
-      const size_t pr = r < n_prompt ? (size_t)r : (size_t)d->tail_row + (r - n_prompt);
-      const uint16_t* blk = raw.data() + (pr / kBlkRows) * (kBlkRows * kD);
+      const bool in_tail = r >= n_prompt;
+      const int64_t pr = in_tail ? d->tail_off + (r - n_prompt) : d->kv_row_off + r;
+      const uint16_t* blk = (in_tail ? raw_t.data() : raw_p.data()) +
+                            (size_t)(pr / kBlkRows - (in_tail ? fb_t : fb_p)) * (kBlkRows * kD);
       const int e = (int)(pr % kBlkRows);
       for (int dd = 0; dd < kD; ++dd)
-        out[(size_t)r * kD + dd] = what == HKV_X_K_ROWS ? blk[k_piece_index(e, dd >> 3) * 8 + (dd & 7)]
-                                                        : blk[dd * 8 + e];
+        out[(size_t)r * kD + dd] = is_k ? blk[k_piece_index(e, dd >> 3) * 8 + (dd & 7)] : blk[dd * 8 + e];
     }
     return HKV_OK;
   }

@@ -311,8 +311,8 @@ __global__ __launch_bounds__(256) void adopt_kernel(CacheView cv, int layer_begi
       const size_t src = src0 + (size_t)r * sstride + sub * 16;
       const size_t dst = (size_t)(d.kv_row_off + r) * ROWB + sub * 16;
       const uint4 kraw = ld16(reinterpret_cast<const char*>(k) + src);
-      st16(reinterpret_cast<char*>(cv.k_rows) + dst, kraw);
-      st16(reinterpret_cast<char*>(cv.v_rows) + dst, ld16(reinterpret_cast<const char*>(v) + src));
+      st16(reinterpret_cast<char*>(cv.k_dyn) + dst, kraw);
+      st16(reinterpret_cast<char*>(cv.v_dyn) + dst, ld16(reinterpret_cast<const char*>(v) + src));
       float kf[EPL];
       unpack16(kraw, kf, T{});
 #pragma unroll
@@ -353,8 +353,8 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(CacheView cv, int layer_
   const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * (kD * 2);
   const size_t sstride = (size_t)cv.n_kv_heads * kD * 2;
   const int32_t* kept = cv.kept_idx + d.idx_off;
-  char* kdst = reinterpret_cast<char*>(cv.k_rows) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
-  char* vdst = reinterpret_cast<char*>(cv.v_rows) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
+  char* kdst = reinterpret_cast<char*>(STATIC ? cv.k_rows : cv.k_dyn) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
+  char* vdst = reinterpret_cast<char*>(STATIC ? cv.v_rows : cv.v_dyn) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
   // each lane moves two 16-byte pieces of K and of V: piece p = lane, lane + 64 -> row e = p / 16, dims 8*(p % 16)
 #pragma unroll
   for (int h = 0; h < 2; ++h) {

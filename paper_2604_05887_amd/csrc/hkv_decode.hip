@@ -36,6 +36,8 @@ namespace hkv {
 struct RowMap {
   const char* kbase;
   const char* vbase;
+  const char* ktail;     // blocked caches: base of the unit's decode tail (its rows may live in another memory)
+  const char* vtail;
   uint32_t stride;       // bytes between consecutive physical rows
   const int32_t* sel;    // dynamic: selected chunk ids (ascending)
   int32_t dynamic;
@@ -392,8 +394,9 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 // Physical 8-row block that holds logical rows Lr .. Lr+7 (Lr a multiple of 8) and how many of them
 // are real (0..8).  A block with no real row is redirected to block 0, which always exists.
 template <bool DYN>
-__device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t& blk, int& nv) {
+__device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t& blk, int& nv, bool& tail) {
   int pb;
+  tail = false;
   if constexpr (!DYN) {
     pb = Lr;
     nv = rm.n_rows - Lr;
@@ -403,12 +406,14 @@ __device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t
       pb = (ch << rm.c_log2) + (Lr & ((1 << rm.c_log2) - 1));
       nv = rm.C - pb;                                   // the last chunk of the prompt may be short
     } else {
-      pb = rm.tail_row + (Lr - rm.n_sel_rows);
+      pb = Lr - rm.n_sel_rows;                          // row of the tail, counted from the tail's base
       nv = rm.n_rows - Lr;
+      tail = true;
     }
   }
   nv = min(max(nv, 0), kBlkRows);
   blk = nv > 0 ? (uint32_t)pb >> 3 : 0u;
+  if (nv <= 0) tail = false;
 }
 
 // Operands of one 32-row step in flight: eight 16-byte K pieces and eight V pieces per lane, and how many
@@ -426,10 +431,11 @@ __device__ __forceinline__ void issue_step_loads(const RowMap& rm, int row0, int
   const int qi = lane & 15, jv = lane >> 4, ja = qi >> 2, e1 = lane & 3;
   uint32_t ba, bv;
   int unused;
-  resolve_block<DYN>(rm, row0 + st * 32 + 8 * ja, ba, unused);
-  resolve_block<DYN>(rm, row0 + st * 32 + 8 * jv, bv, sb.nv);
-  const char* kp = rm.kbase + (size_t)ba * kBlkBytes + (uint32_t)(jv * 4 + e1) * 16u;
-  const char* vp = rm.vbase + (size_t)bv * kBlkBytes + (uint32_t)qi * 16u;
+  bool ta, tv;
+  resolve_block<DYN>(rm, row0 + st * 32 + 8 * ja, ba, unused, ta);
+  resolve_block<DYN>(rm, row0 + st * 32 + 8 * jv, bv, sb.nv, tv);
+  const char* kp = (ta ? rm.ktail : rm.kbase) + (size_t)ba * kBlkBytes + (uint32_t)(jv * 4 + e1) * 16u;
+  const char* vp = (tv ? rm.vtail : rm.vbase) + (size_t)bv * kBlkBytes + (uint32_t)qi * 16u;
 #pragma unroll
   for (int i = 0; i < 8; ++i) sb.ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
 #pragma unroll
@@ -489,12 +495,14 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     const bool more = nst < n_steps;                     // wave-uniform
     uint32_t bv_next = 0;
     int nv_next = 0;
+    bool tv_next = false;
     if (more) {
       uint32_t ba;
       int unused;
-      resolve_block<DYN>(rm, row0 + nst * 32 + 8 * ja, ba, unused);
-      resolve_block<DYN>(rm, row0 + nst * 32 + 8 * jv, bv_next, nv_next);
-      const char* kp = rm.kbase + (size_t)ba * kBlkBytes + k_lane;
+      bool ta;
+      resolve_block<DYN>(rm, row0 + nst * 32 + 8 * ja, ba, unused, ta);
+      resolve_block<DYN>(rm, row0 + nst * 32 + 8 * jv, bv_next, nv_next, tv_next);
+      const char* kp = (ta ? rm.ktail : rm.kbase) + (size_t)ba * kBlkBytes + k_lane;
 #pragma unroll
       for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);
     }
@@ -531,7 +539,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     for (int db = 0; db < 8; ++db)
       o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), pb, o[db], 0, 0, 0);
     if (more) {
-      const char* vp = rm.vbase + (size_t)bv_next * kBlkBytes + v_lane;
+      const char* vp = (tv_next ? rm.vtail : rm.vbase) + (size_t)bv_next * kBlkBytes + v_lane;
 #pragma unroll
       for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);
     }
@@ -781,7 +789,7 @@ __device__ __forceinline__ void append_row(const CacheView& cv, const AttnItem& 
   constexpr int LPR = Elem<T>::kLanesPerRow;
   const int tid = thread_index();
   const size_t src_row = (((size_t)lrel * cv.batch + it.seq) * cv.n_kv_heads + it.head) * kD * sizeof(T);
-  const int64_t prow = it.kv_row_off + it.tail_row + t_before;
+  const int64_t prow = it.tail_off + t_before;                 // row in the device arrays
   if constexpr (sizeof(T) == 2) {
     // blocked cache: 16 key pieces go to their slots of the row's block, V is scattered one element per dim
     const size_t blk_off = (size_t)(prow >> 3) * kBlkBytes;
@@ -823,8 +831,10 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   const int new_row = it.n_prompt_rows + t_before;          // logical index of the appended row
   if (append && new_row >= it.row0 && new_row < it.row0 + TILE)    // block-uniform
     append_row<T>(cv, it, lrel, t_before, k_new, v_new);
-  rm.kbase = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
-  rm.vbase = reinterpret_cast<const char*>(cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
+  rm.kbase = reinterpret_cast<const char*>(it.dynamic ? cv.k_dyn : cv.k_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
+  rm.vbase = reinterpret_cast<const char*>(it.dynamic ? cv.v_dyn : cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
+  rm.ktail = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.tail_off * kD * sizeof(T);
+  rm.vtail = reinterpret_cast<const char*>(cv.v_rows) + (size_t)it.tail_off * kD * sizeof(T);
   rm.stride = kD * sizeof(T);
   rm.dynamic = it.dynamic;
   rm.sel = sel_override ? sel_override : cv.sel + it.sel_off;
@@ -889,7 +899,7 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
   AttnItem it;
   it.kv_row_off = d.kv_row_off; it.sel_off = (int32_t)d.idx_off; it.n_prompt_rows = d.n_prompt_rows;
   it.C = d.C; it.c_log2 = d.c_log2; it.dynamic = 1; it.layer = d.layer; it.seq = d.seq; it.head = d.head;
-  it.tail_row = d.tail_row;
+  it.tail_row = d.tail_row; it.tail_off = d.tail_off;
   for (int t = 0; t < n_tiles; ++t) {
     if (t > 0) __syncthreads();             // the previous tile's staging area is free again
     it.row0 = t * TILE;
@@ -995,6 +1005,7 @@ __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __
   rm.vbase = reinterpret_cast<const char*>(v) + off;
   rm.stride = (uint32_t)fv.n_kv_heads * kD * sizeof(T);
   rm.dynamic = 0; rm.sel = nullptr; rm.n_sel_rows = 0; rm.c_log2 = 0; rm.C = rm.n_rows; rm.tail_row = rm.n_rows;
+  rm.ktail = rm.kbase; rm.vtail = rm.vbase;
   const size_t qoff = (((size_t)lrel * fv.batch + b) * fv.n_q_heads + (size_t)h * G) * kD;
   const size_t slot = (size_t)unit * fv.n_tiles_max + blockIdx.x;
   const PartOut part = {partials.o + slot * G * kD, partials.ml + slot * kMlStride};

@@ -35,7 +35,7 @@ enum SelMode : int32_t { kSelVisual = 0, kSelText = 1, kSelSuffix = 2 };
 // One (sequence, layer, KV head) unit.  Units are numbered layer-major:
 // u = (layer * batch + seq) * n_kv_heads + head, so a layer range is a contiguous unit range.
 struct UnitDesc {
-  int64_t kv_row_off;   // first row of the unit in the cache K / V row arrays
+  int64_t kv_row_off;   // first prompt row of the unit in the K / V row arrays (dynamic units: the k_dyn / v_dyn arrays)
   int64_t aux_off;      // static: element offset into scores[]; dynamic: chunk offset into mu[] rows and sigma[]
   int64_t idx_off;      // static: offset into kept_idx[]; dynamic: offset into sel[]
   int32_t seq_start;    // first token of the sequence in the packed prompt tensors
@@ -54,6 +54,7 @@ struct UnitDesc {
   int32_t type_ord;     // ordinal among the static (or dynamic) units, layer-major
   int32_t tail_row;     // physical row (within the unit) of the first appended decode token
   int32_t pad_;
+  int64_t tail_off;     // first row of the unit's decode tail in the device K / V row arrays
 };
 
 // One split-K tile of decode attention: everything the attention block needs, in one record.
@@ -72,7 +73,7 @@ struct AttnItem {
   int32_t k_sel;        // dynamic: chunks attended per step
   int32_t pad_;
   int64_t aux_off;      // dynamic: first chunk's offset into sigma[] / mu[]
-  int64_t pad2_;
+  int64_t tail_off;     // first row of the unit's decode tail in the device K / V row arrays
 };
 
 struct CacheView {
@@ -91,8 +92,10 @@ struct CacheView {
   float* scores;
   float* sigma;
   void* mu;
-  void* k_rows;
+  void* k_rows;               // static units' rows and every unit's decode tail (device memory)
   void* v_rows;
+  void* k_dyn;                // dynamic units' prompt rows: k_rows / v_rows, or the host tier's arrays
+  void* v_dyn;
   int32_t n_layers, batch, n_q_heads, n_kv_heads, G, window, max_new, causal;
   int32_t tile_rows;          // logical rows per split-K tile of this cache
   float scale_log2e;          // softmax scale * log2(e)

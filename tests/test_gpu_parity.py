@@ -445,3 +445,74 @@ def test_head_scores_on_long_rows(n_visual):
     err = np.abs(got - want).max()
     print(f"\n[head scores C={int(wl.seqlens[0])}] max abs err {err:.2e}", flush=True)
     assert err <= SCORE_ATOL
+
+
+# ---- host-memory tier for the dynamic heads (Section 3.3: their prompt K/V lives outside GPU memory) ----
+
+@pytest.mark.parametrize("mode,tile", [(1, 0), (2, 0), (3, 0), (3, 128)])
+def test_host_tier_matches_the_oracle(mode, tile):
+    """The dynamic heads' prompt rows live in page-locked host memory; compression writes them there,
+    decode gathers the selected chunks from there.  Same oracle, same tolerances as an untiered cache;
+    the exported rows (prompt part from the host tier, tail part from device memory) are compared too."""
+    wl = make_workload(1, n_layers=3, shrink=2, steps=4)
+    stats = P.full_pipeline(wl, host_tier=True, decode_dynamic=mode, decode_tile_rows=tile)
+    _say(f"host tier mode {mode} tile {tile}", stats)
+
+
+def test_host_tier_ragged_batch_and_layer_ranges():
+    wl = make_workload(4, n_layers=2, shrink=8, steps=3)
+    stats = P.full_pipeline(wl, host_tier=True, layer_ranges=[(0, 1), (1, 2)])
+    _say("host tier cfg4/8", stats)
+
+
+def test_host_tier_outputs_equal_the_untiered_cache_bit_for_bit():
+    """Where the rows live changes no arithmetic: outputs of a tiered and an untiered cache are equal,
+    and the device arena shrinks by the dynamic heads' prompt rows."""
+    wl = make_workload(1, n_layers=2, shrink=4, steps=6)
+    outs, sizes = [], []
+    for tier in (False, True):
+        dw = runner.setup(wl, host_tier=tier)
+        sizes.append((dw.cache.cache_bytes, dw.cache.host_bytes))
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+        out = torch.empty((wl.n_layers, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+        res = []
+        for s in range(wl.steps):
+            q, kn, vn = (runner.to_device(x[s], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+            dw.cache.decode_attn(q, kn, vn, out)
+            torch.cuda.synchronize()
+            res.append(out.clone())
+        outs.append(torch.stack(res))
+        dw.cache.close()
+    assert torch.equal(outs[0], outs[1])
+    (dev0, host0), (dev1, host1) = sizes
+    n_dyn = int((wl.head_type == O.DYNAMIC).sum())
+    C = int(wl.seqlens[0])
+    assert host0 == 0 and host1 >= 2 * n_dyn * C * 128 * 2
+    assert dev0 - dev1 >= 2 * n_dyn * (C - 8) * 128 * 2          # up to block rounding of the tails
+
+
+def test_host_tier_rejects_memory_the_device_cannot_address():
+    wl = make_workload(1, n_layers=1, shrink=8, steps=1)
+    dw = runner.setup(wl, upload_prompt=False)           # supplies cfg and plan
+    cb, hb, wb = B.hkv_query_tier_sizes(dw.cfg, dw.plan)
+    arena = torch.empty(cb + 256, dtype=torch.uint8, device="cuda:0")
+    a = arena[(-arena.data_ptr()) % 256:]
+    pageable = torch.empty(hb + 256, dtype=torch.uint8)              # ordinary host memory
+    pg = pageable[(-pageable.data_ptr()) % 256:]
+    with pytest.raises(B.HkvError) as ei:
+        B.hkv_cache_create_tiered(dw.cfg, dw.plan, a, cb, pg, hb)
+    assert ei.value.status == B.HKV_EINVAL
+    devmem = torch.empty(hb + 256, dtype=torch.uint8, device="cuda:0")   # device memory is no host tier
+    dm = devmem[(-devmem.data_ptr()) % 256:]
+    with pytest.raises(B.HkvError) as ei:
+        B.hkv_cache_create_tiered(dw.cfg, dw.plan, a, cb, dm, hb)
+    assert ei.value.status == B.HKV_EINVAL
+    pinned = torch.empty(hb + 256, dtype=torch.uint8, pin_memory=True)
+    pn = pinned[(-pinned.data_ptr()) % 256:]
+    with pytest.raises(B.HkvError) as ei:
+        B.hkv_cache_create_tiered(dw.cfg, dw.plan, a, cb, pn, hb - 1)    # too small
+    assert ei.value.status == B.HKV_ENOSPACE
+    h = B.hkv_cache_create_tiered(dw.cfg, dw.plan, a, cb, pn, hb)
+    B.hkv_cache_destroy(h)
+    dw.cache.close()
+    torch.cuda.synchronize()          # no error left behind by the refused pointers

@@ -158,3 +158,29 @@ def test_head_scores_workspace_and_argument_checks(lib):
     bad = np.array(wl.is_visual, copy=True); bad[3] = 7
     with pytest.raises(B.HkvError):
         B.hkv_head_scores_workspace_size(cfg, wl.cu_seqlens, bad)
+
+
+def test_host_tier_sizes_move_exactly_the_dynamic_prompt_rows(lib):
+    """Tiered layout: the dynamic heads' prompt rows (whole 8-row blocks, K and V) leave the device
+    arena for the host tier; everything else stays.  fp32 caches have no host tier."""
+    wl = make_workload(1, n_layers=2, shrink=4, steps=1)
+    cfg = _cfg(n_layers=2, dtype=B.HKV_BF16, window=wl.window, max_new_tokens=wl.max_new_tokens)
+    plan = _plan(wl)
+    dev0, ws0 = B.hkv_query_sizes(cfg, plan)
+    dev1, host1, ws1 = B.hkv_query_tier_sizes(cfg, plan)
+    assert ws0 == ws1
+    C = int(wl.seqlens[0])
+    n_dyn = int((wl.head_type == O.DYNAMIC).sum())
+    assert n_dyn > 0
+    rows = (C + 7) // 8 * 8
+    row_bytes = 128 * 2
+    assert host1 == 2 * ((n_dyn * rows * row_bytes + 255) // 256 * 256)
+    cap = lambda r: (r + wl.max_new_tokens + 7) // 8 * 8
+    moved = n_dyn * (cap(rows) - cap(0))
+    assert 0 <= (dev0 - dev1) - 2 * moved * row_bytes < 2 * 256        # only alignment padding may differ
+    with pytest.raises(B.HkvError) as ei:
+        B.hkv_query_tier_sizes(_cfg(n_layers=2, window=wl.window), plan)   # fp32
+    assert ei.value.status == B.HKV_ESHAPE
+    with pytest.raises(B.HkvError) as ei:
+        B.hkv_cache_create_tiered(cfg, plan, None, dev1, None, host1)
+    assert ei.value.status == B.HKV_EINVAL
