@@ -59,6 +59,8 @@ def main() -> int:
                     help="dynamic heads: 1 = one workgroup per head in the main launch, 2 = split-K tiles in a "
                          "second launch, 3 = single launch with repeated selection, 0 = library default")
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
+    ap.add_argument("--host-tier", action="store_true",
+                    help="keep the dynamic heads' prompt rows in page-locked host memory (bf16 workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-kv", action="store_true", help="skip the full-KV comparison kernel")
     ap.add_argument("--classify", action="store_true",
@@ -138,7 +140,8 @@ def main() -> int:
 
     # the real run appends one token per step for `steps` steps; the rotation spreads the timed steps
     # over several copies, so every copy's tail is pre-rolled to the middle of that range
-    probe = runner.setup(wl, dev, upload_prompt=False, decode_tile_rows=args.tile_rows, decode_dynamic=args.dynamic_mode)
+    probe = runner.setup(wl, dev, upload_prompt=False, decode_tile_rows=args.tile_rows, decode_dynamic=args.dynamic_mode,
+                         host_tier=args.host_tier)
     step_bytes_mid = probe.cache.step_bytes(wl.steps // 2)
     probe.cache.close()
     del probe
@@ -148,7 +151,8 @@ def main() -> int:
     per_copy = -(-(K + W) // n_copies)
     preroll = max(0, wl.steps // 2 - per_copy // 2)
     wl.max_new_tokens = preroll + 2 * per_copy + 2 + K + 64   # room for the profiled and per-layer passes as well
-    copies = [runner.setup(wl, dev, upload_prompt=False, decode_tile_rows=args.tile_rows, decode_dynamic=args.dynamic_mode) for _ in range(n_copies)]
+    copies = [runner.setup(wl, dev, upload_prompt=False, decode_tile_rows=args.tile_rows, decode_dynamic=args.dynamic_mode,
+                           host_tier=args.host_tier) for _ in range(n_copies)]
     stream = torch.cuda.current_stream()
     sptr = int(stream.cuda_stream) or None
 
@@ -275,6 +279,12 @@ def main() -> int:
                 else:
                     a_bytes += n_c * R
                     b_bytes += 2 * R * (rows + tail_prof)
+    link_bytes = 0
+    for l in range(L):
+        for b in range(Bn):
+            for h in range(Hkv):
+                if wl.head_type[b, l, h] != 0:
+                    link_bytes += 2 * R * copies[0].cache.unit_info(b, l, h)[0]
     tile_rows, dyn_mode = copies[0].cache.decode_shape()
     if dyn_mode != 2:        # the main launch also reads the dynamic heads' gathered rows
         a_bytes += b_bytes
@@ -456,6 +466,12 @@ def main() -> int:
         "speedup_vs_full_kv": round(full_ms / ms_per_step, 3),
         "compress_ms": round(compress_ms, 3),
         "head_classification": classify,
+        "memory_tier": {"host_tier": bool(args.host_tier), "device_arena_bytes": int(copies[0].cache.cache_bytes),
+                        "host_tier_bytes": int(copies[0].cache.host_bytes),
+                        # bytes a step brings over the host link: the selected chunks' K and V rows
+                        "host_link_bytes_per_step": int(link_bytes) if args.host_tier else 0,
+                        "host_link_gbs": round(link_bytes / (ms_per_step * 1e-3) / 1e9, 1) if args.host_tier else 0.0,
+                        "host_link_peak_gbs": 64.0},      # PCIe 5.0 x16, one direction, before packet overhead
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
         "decode_shape": {"tile_rows": tile_rows, "dynamic_mode": dyn_mode, "tuned_us_per_step": tuned_us},
         "kernel_us": {"main_launch": round(a_us, 2), "second_launch": round(b_us, 2),

@@ -36,8 +36,8 @@ namespace hkv {
 struct RowMap {
   const char* kbase;
   const char* vbase;
-  const char* ktail;     // blocked caches: base of the unit's decode tail (its rows may live in another memory)
-  const char* vtail;
+  int64_t ktail;         // blocked caches: bytes from kbase / vbase to the base of the unit's decode tail
+  int64_t vtail;         //   (the tail may live in another memory than the gathered prompt rows)
   uint32_t stride;       // bytes between consecutive physical rows
   const int32_t* sel;    // dynamic: selected chunk ids (ascending)
   int32_t dynamic;
@@ -434,8 +434,8 @@ __device__ __forceinline__ void issue_step_loads(const RowMap& rm, int row0, int
   bool ta, tv;
   resolve_block<DYN>(rm, row0 + st * 32 + 8 * ja, ba, unused, ta);
   resolve_block<DYN>(rm, row0 + st * 32 + 8 * jv, bv, sb.nv, tv);
-  const char* kp = (ta ? rm.ktail : rm.kbase) + (size_t)ba * kBlkBytes + (uint32_t)(jv * 4 + e1) * 16u;
-  const char* vp = (tv ? rm.vtail : rm.vbase) + (size_t)bv * kBlkBytes + (uint32_t)qi * 16u;
+  const char* kp = rm.kbase + ((int64_t)ba * kBlkBytes + (ta ? rm.ktail : (int64_t)0)) + (uint32_t)(jv * 4 + e1) * 16u;
+  const char* vp = rm.vbase + ((int64_t)bv * kBlkBytes + (tv ? rm.vtail : (int64_t)0)) + (uint32_t)qi * 16u;
 #pragma unroll
   for (int i = 0; i < 8; ++i) sb.ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
 #pragma unroll
@@ -502,7 +502,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
       bool ta;
       resolve_block<DYN>(rm, row0 + nst * 32 + 8 * ja, ba, unused, ta);
       resolve_block<DYN>(rm, row0 + nst * 32 + 8 * jv, bv_next, nv_next, tv_next);
-      const char* kp = (ta ? rm.ktail : rm.kbase) + (size_t)ba * kBlkBytes + k_lane;
+      const char* kp = rm.kbase + ((int64_t)ba * kBlkBytes + (ta ? rm.ktail : (int64_t)0)) + k_lane;
 #pragma unroll
       for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);
     }
@@ -539,7 +539,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     for (int db = 0; db < 8; ++db)
       o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[db]), pb, o[db], 0, 0, 0);
     if (more) {
-      const char* vp = (tv_next ? rm.vtail : rm.vbase) + (size_t)bv_next * kBlkBytes + v_lane;
+      const char* vp = rm.vbase + ((int64_t)bv_next * kBlkBytes + (tv_next ? rm.vtail : (int64_t)0)) + v_lane;
 #pragma unroll
       for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);
     }
@@ -833,8 +833,10 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
     append_row<T>(cv, it, lrel, t_before, k_new, v_new);
   rm.kbase = reinterpret_cast<const char*>(it.dynamic ? cv.k_dyn : cv.k_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.vbase = reinterpret_cast<const char*>(it.dynamic ? cv.v_dyn : cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
-  rm.ktail = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.tail_off * kD * sizeof(T);
-  rm.vtail = reinterpret_cast<const char*>(cv.v_rows) + (size_t)it.tail_off * kD * sizeof(T);
+  rm.ktail = (int64_t)(reinterpret_cast<intptr_t>(cv.k_rows) + it.tail_off * (int64_t)(kD * sizeof(T)) -
+                       reinterpret_cast<intptr_t>(rm.kbase));
+  rm.vtail = (int64_t)(reinterpret_cast<intptr_t>(cv.v_rows) + it.tail_off * (int64_t)(kD * sizeof(T)) -
+                       reinterpret_cast<intptr_t>(rm.vbase));
   rm.stride = kD * sizeof(T);
   rm.dynamic = it.dynamic;
   rm.sel = sel_override ? sel_override : cv.sel + it.sel_off;
@@ -1005,7 +1007,7 @@ __global__ __launch_bounds__(256) void full_attn_kernel(FullView fv, const T* __
   rm.vbase = reinterpret_cast<const char*>(v) + off;
   rm.stride = (uint32_t)fv.n_kv_heads * kD * sizeof(T);
   rm.dynamic = 0; rm.sel = nullptr; rm.n_sel_rows = 0; rm.c_log2 = 0; rm.C = rm.n_rows; rm.tail_row = rm.n_rows;
-  rm.ktail = rm.kbase; rm.vtail = rm.vbase;
+  rm.ktail = 0; rm.vtail = 0;
   const size_t qoff = (((size_t)lrel * fv.batch + b) * fv.n_q_heads + (size_t)h * G) * kD;
   const size_t slot = (size_t)unit * fv.n_tiles_max + blockIdx.x;
   const PartOut part = {partials.o + slot * G * kD, partials.ml + slot * kMlStride};
