@@ -104,6 +104,10 @@ typedef struct {
                                repeating its head's chunk selection; 0 = 3 unless the repeated summary reads
                                would exceed a quarter of a step's bytes, then 2
                                (tuning knob, same results up to fp32 summation order) */
+  int32_t chunk_score_group;/* how the query heads that share a KV head score a chunk (Appendix A gives one
+                               query vector per head and does not treat grouped heads): 0 = the inner
+                               product of the chunk summary with the SUM of the group's query vectors;
+                               1 = the LARGEST of the group's inner products with the chunk summary */
 } hkv_config;
 
 /* Per-prompt plan.  All arrays live in HOST memory and are only read during the call. */

@@ -196,12 +196,21 @@ def chunk_means(k: np.ndarray, c: int, dtype: str) -> np.ndarray:
     return round_to_dtype(mu, dtype)
 
 
-def chunk_scores(q: np.ndarray, mu: np.ndarray) -> np.ndarray:
+def chunk_scores(q: np.ndarray, mu: np.ndarray, group: str = "sum") -> np.ndarray:
     """Inner product of the step's query with every chunk's metadata (Appendix A).
-    One selection is made per cached (KV) head, so the G query heads of the group
-    are summed into one query vector first; no scaling (it cannot change ranks)."""
-    q_sum = np.asarray(q, dtype=np.float64).sum(axis=0)          # [d]
-    return np.asarray(mu, dtype=np.float64) @ q_sum               # [n_c]
+    One selection is made per cached (KV) head; the paper writes one query vector
+    and is silent on grouped-query heads.  group="sum" (the default reading): the G
+    query heads of the group are summed into one query vector first.  group="max":
+    every query head scores every chunk and a chunk takes the largest of its G
+    scores (a chunk that matters to any one head of the group ranks high).
+    No scaling in either (it cannot change ranks); with G = 1 the two coincide."""
+    qq = np.asarray(q, dtype=np.float64)                          # [G, d]
+    m = np.asarray(mu, dtype=np.float64)                          # [n_c, d]
+    if group == "sum":
+        return m @ qq.sum(axis=0)                                 # [n_c]
+    if group == "max":
+        return (m @ qq.T).max(axis=1)                             # [n_c]
+    raise ValueError(group)
 
 
 def n_selected_chunks(budget: int, c: int, n_c: int) -> int:
@@ -341,6 +350,7 @@ class OracleConfig:
     dtype: str = "f32"              # dtype of Q/K/V (their values are exact in it)
     score_causal: bool = False
     softmax_scale: float = 0.0      # 0 -> 1/sqrt(head_dim)
+    chunk_score_group: str = "sum"  # how the G query heads of a group score a chunk: "sum" or "max"
 
     @property
     def scale(self) -> float:
@@ -457,7 +467,7 @@ def decode_attn(cache: OracleCache, q: np.ndarray, k_new: Optional[np.ndarray], 
                     mu = u.mu
                     if mu_override is not None and (b, l, h) in mu_override:
                         mu = np.asarray(mu_override[(b, l, h)], dtype=np.float64)
-                    sigma = chunk_scores(qh, mu)
+                    sigma = chunk_scores(qh, mu, cfg.chunk_score_group)
                     sel = select_chunks(sigma, u.k_sel)
                     if sel_override is not None and (b, l, h) in sel_override:
                         sel = np.asarray(sel_override[(b, l, h)], dtype=np.int64)

@@ -27,6 +27,7 @@ int validate_config(const hkv_config* cfg) {
     if (cfg->dtype != HKV_BF16 || (t != 128 && t != 256 && t != 512 && t != 1024)) return HKV_ESHAPE;
   }
   if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 3) return HKV_EINVAL;
+  if (cfg->chunk_score_group != 0 && cfg->chunk_score_group != 1) return HKV_EINVAL;
   if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
   return HKV_OK;
 }
@@ -390,6 +391,7 @@ static int create_cache(const hkv_config* cfg, const hkv_plan* plan, void* cache
   cv.G = cfg->n_q_heads / cfg->n_kv_heads; cv.window = cfg->window; cv.max_new = cfg->max_new_tokens;
   cv.causal = cfg->score_causal;
   cv.tile_rows = lo.tile;
+  cv.sigma_max = cfg->chunk_score_group;
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   cv.scale_log2e = scale * 1.4426950408889634f;
 

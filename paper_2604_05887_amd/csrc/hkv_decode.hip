@@ -674,6 +674,41 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     uint4 qraw[kMaxG];
 #pragma unroll
     for (int g = 0; g < kMaxG; ++g) qraw[g] = g < cv.G ? ld16(qb + (size_t)g * kD * sizeof(T)) : make_uint4(0, 0, 0, 0);
+    if (cv.sigma_max) {
+      // every query head of the group scores the chunk; the chunk takes the largest of the G scores
+      for (int ch0 = 0; ch0 < n_c; ch0 += RP * 4) {     // uniform trip count; four independent loads per round
+        uint4 raw[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int ch = ch0 + j * RP + slot;
+          raw[j] = ld16(mu + (size_t)min(ch, n_c - 1) * kD * sizeof(T));
+        }
+        float best[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) best[j] = -INFINITY;
+#pragma unroll
+        for (int g = 0; g < kMaxG; ++g) {
+          if (g < cv.G) {                                // uniform
+            float t[EPL];
+            unpack16(qraw[g], t, T{});
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              float mf[EPL];
+              unpack16(raw[j], mf, T{});
+              float dot = 0.f;
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) dot = fmaf(t[e], mf[e], dot);
+              best[j] = fmaxf(best[j], sum_lanes<LPR>(dot));
+            }
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int ch = ch0 + j * RP + slot;
+          if (ch < n_c && sub == 0) { sig[ch] = best[j]; if (to_memory) cv.sigma[d.aux_off + ch] = best[j]; }
+        }
+      }
+    } else {
     for (int ch0 = 0; ch0 < n_c; ch0 += RP * 16) {      // uniform trip count; sixteen independent loads per round
       uint4 raw[16];
 #pragma unroll
@@ -701,6 +736,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
         dot = sum_lanes<LPR>(dot);
         if (ch < n_c && sub == 0) { sig[ch] = dot; if (to_memory) cv.sigma[d.aux_off + ch] = dot; }
       }
+    }
     }
   } else {
     for (int ch = tid; ch < n_c; ch += 256) sig[ch] = cv.sigma[d.aux_off + ch];

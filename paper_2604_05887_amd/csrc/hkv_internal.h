@@ -98,6 +98,7 @@ struct CacheView {
   void* v_dyn;
   int32_t n_layers, batch, n_q_heads, n_kv_heads, G, window, max_new, causal;
   int32_t tile_rows;          // logical rows per split-K tile of this cache
+  int32_t sigma_max;          // chunk score of a group: 0 = summed query, 1 = largest of the heads' inner products
   float scale_log2e;          // softmax scale * log2(e)
 };
 

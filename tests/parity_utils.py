@@ -28,9 +28,10 @@ SCORE_RTOL = 2e-5   # fp32 MFMA accumulation + exp2 + fp32 column sums vs double
 OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}
 
 
-def oracle_setup(wl, budget=None, head_type=None, causal=False):
+def oracle_setup(wl, budget=None, head_type=None, causal=False, chunk_score_group="sum"):
     cfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
-                         head_dim=wl.head_dim, window=wl.window, dtype=wl.dtype, score_causal=causal)
+                         head_dim=wl.head_dim, window=wl.window, dtype=wl.dtype, score_causal=causal,
+                         chunk_score_group=chunk_score_group)
     plan = O.OraclePlan(cu_seqlens=wl.cu_seqlens, head_type=wl.head_type if head_type is None else head_type,
                         budget=wl.budget if budget is None else budget, chunk_size=wl.chunk_size)
     return cfg, plan
@@ -151,8 +152,10 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
             sel_gpu = dw.cache.export(B.HKV_X_CHUNK_SEL, b, l, h).astype(np.int64)
             assert np.array_equal(sel_gpu, O.select_chunks(sig_gpu, u.k_sel)), f"chunk top-k not exact on {key}"
             qh = wl.q_steps[s][l, b, h * G:(h + 1) * G].astype(np.float64)
-            sig_ref = O.chunk_scores(qh, mu_dev[key])
-            scale = np.linalg.norm(qh.sum(0)) * np.linalg.norm(mu_dev[key], axis=1).max()
+            group = ocache.cfg.chunk_score_group
+            sig_ref = O.chunk_scores(qh, mu_dev[key], group)
+            q_norm = np.linalg.norm(qh.sum(0)) if group == "sum" else np.linalg.norm(qh, axis=1).max()
+            scale = q_norm * np.linalg.norm(mu_dev[key], axis=1).max()
             err = np.abs(sig_gpu - sig_ref).max() / scale
             stats["sigma_err"] = max(stats.get("sigma_err", 0.0), float(err))
             assert err <= 1e-5, f"chunk scores off by {err:.3e} (relative to |q||mu|) on {key}"
@@ -175,7 +178,8 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
 def full_pipeline(wl, budget=None, head_type=None, causal=False, n_steps=None, layer_ranges=None, **setup_kw):
     stats: Dict[str, float] = {}
     dw = runner.setup(wl, budget=budget, head_type=head_type, score_causal=int(causal), **setup_kw)
-    ocfg, oplan = oracle_setup(wl, budget, head_type, causal)
+    ocfg, oplan = oracle_setup(wl, budget, head_type, causal,
+                               chunk_score_group="max" if setup_kw.get("chunk_score_group", 0) == 1 else "sum")
     ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual)
     if layer_ranges:
         for (lb, le) in layer_ranges:

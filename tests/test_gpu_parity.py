@@ -516,3 +516,34 @@ def test_host_tier_rejects_memory_the_device_cannot_address():
     B.hkv_cache_destroy(h)
     dw.cache.close()
     torch.cuda.synchronize()          # no error left behind by the refused pointers
+
+
+# ---- other reading of the chunk scoring for grouped query heads ----
+
+@pytest.mark.parametrize("cfg_id,mode", [(1, 3), (1, 1), (1, 2), (0, 3), (4, 0)])
+def test_chunk_scores_as_the_largest_over_the_group(cfg_id, mode):
+    """chunk_score_group = 1: a chunk's score is the largest of the G query heads' inner products with
+    its summary (bf16 and fp32 caches, every launch shape, ragged batch with both chunk sizes)."""
+    if cfg_id == 4:
+        wl = make_workload(4, n_layers=2, shrink=8, steps=3)
+    else:
+        wl = make_workload(cfg_id, n_layers=2, shrink=2 if cfg_id == 1 else 1, steps=4)
+    stats = P.full_pipeline(wl, chunk_score_group=1, decode_dynamic=mode)
+    _say(f"cfg{cfg_id} max-over-group mode {mode}", stats)
+
+
+def test_the_two_group_readings_pick_different_chunks():
+    """The variant is not a no-op: on the same inputs the two readings disagree on some head's picks."""
+    wl = make_workload(1, n_layers=2, shrink=4, steps=1)
+    picks = []
+    for grp in (0, 1):
+        dw = runner.setup(wl, chunk_score_group=grp)
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+        out = torch.empty((wl.n_layers, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+        q, kn, vn = (runner.to_device(x[0], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+        dw.cache.decode_attn(q, kn, vn, out)
+        torch.cuda.synchronize()
+        picks.append([dw.cache.export(B.HKV_X_CHUNK_SEL, 0, l, h) for l in range(wl.n_layers)
+                      for h in range(wl.n_kv_heads) if wl.head_type[0, l, h] == O.DYNAMIC])
+        dw.cache.close()
+    assert any(not np.array_equal(a, b) for a, b in zip(*picks))

@@ -55,6 +55,7 @@ def test_argument_errors_are_reported_on_the_host(lib):
         return ei.value.status
 
     assert status(_cfg(head_dim=64), _plan(wl)) == B.HKV_ESHAPE
+    assert status(_cfg(chunk_score_group=2), _plan(wl)) == B.HKV_EINVAL
     assert status(_cfg(n_q_heads=36), _plan(wl)) == B.HKV_ESHAPE          # group of 9
     assert status(_cfg(n_q_heads=30), _plan(wl)) == B.HKV_ESHAPE          # not divisible
     assert status(_cfg(window=64), _plan(wl)) == B.HKV_ESHAPE             # G * w > 256

@@ -448,3 +448,34 @@ def test_sparsity_score_gaussian_logits_closed_form():
     got = O.text_sparsity_score(q, k, np.arange(6), 1.0, O.focus_count(C))
     want = 1.0 - norm.cdf(norm.ppf(0.95) - 1.0)
     assert abs(want - 0.2595) < 1e-3 and abs(got - want) < 0.01
+
+
+# ---------------------------------------------------------------- chunk scoring, other reading for grouped heads
+def test_chunk_scores_max_over_group_against_hand_values_and_the_sum_reading():
+    """Two query heads pointing in opposite directions cancel in the summed query, so the sum
+    reading scores every chunk 0 and picks the lowest ids; the max reading ranks chunks by
+    |component|.  Values worked by hand."""
+    mu = np.array([[1.0, 0.0], [-3.0, 0.0], [0.5, 2.0], [0.0, -1.0]])
+    q = np.array([[1.0, 0.0], [-1.0, 0.0]])
+    np.testing.assert_array_equal(O.chunk_scores(q, mu, "sum"), [0.0, 0.0, 0.0, 0.0])
+    np.testing.assert_array_equal(O.chunk_scores(q, mu, "max"), [1.0, 3.0, 0.5, 0.0])
+    assert O.select_chunks(O.chunk_scores(q, mu, "sum"), 2).tolist() == [0, 1]
+    assert O.select_chunks(O.chunk_scores(q, mu, "max"), 2).tolist() == [0, 1]
+    assert O.select_chunks(O.chunk_scores(q, mu, "sum"), 1).tolist() == [0]
+    assert O.select_chunks(O.chunk_scores(q, mu, "max"), 1).tolist() == [1]
+    # one query head: the two readings are the same thing
+    rng = np.random.default_rng(5)
+    m = rng.standard_normal((37, 16))
+    q1 = rng.standard_normal((1, 16))
+    np.testing.assert_array_equal(O.chunk_scores(q1, m, "max"), O.chunk_scores(q1, m, "sum"))
+    # G copies of one head: max = that head's score, sum = G times it
+    q3 = np.repeat(q1, 3, axis=0)
+    np.testing.assert_allclose(O.chunk_scores(q3, m, "max"), O.chunk_scores(q1, m, "sum"), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(O.chunk_scores(q3, m, "sum"), 3 * O.chunk_scores(q1, m, "sum"), rtol=1e-12, atol=1e-14)
+    # brute force, and max >= mean of the heads' scores
+    q5 = rng.standard_normal((5, 16))
+    brute = np.array([max(float(np.dot(q5[g], m[c])) for g in range(5)) for c in range(37)])
+    np.testing.assert_allclose(O.chunk_scores(q5, m, "max"), brute, rtol=1e-14)
+    assert np.all(O.chunk_scores(q5, m, "max") >= O.chunk_scores(q5, m, "sum") / 5 - 1e-12)
+    with pytest.raises(ValueError):
+        O.chunk_scores(q5, m, "mean")
