@@ -26,6 +26,8 @@ order and notation of the paper:
   * text_sparsity_score  Section 3.1, text-centric attention S_text and the
                        sparsity score S_{l,h} (sum of each text row's top-k
                        probabilities, averaged over text rows)
+  * cumulative_focus   Section 2.1, Eq. 1: how often each context token is among a
+                       head's k most attended tokens over N decoding steps
   * classify_heads     Section 3.1, threshold theta on S_{l,h}
   * type_level_budgets / static_head_budgets
                        Section 3.2, the two allocation equations
@@ -47,6 +49,8 @@ gives 1, a one-hot row gives 1), by a sort-based restatement on random inputs
 and by hand-worked rational softmax rows; the budget equations by their printed
 invariants (type budgets add up to the total, r = 1 and equal scores give the
 uniform split, every ceiling is at most one token above its argument).
+cumulative_focus is pinned by a hand-worked case, by the argmax histogram for
+k = 1, by a library top-k on the logits, and by its count invariants.
 """
 from __future__ import annotations
 
@@ -499,6 +503,27 @@ def head_scores(cfg: OracleConfig, cu_seqlens: np.ndarray, q_prompt: np.ndarray,
                 qt = np.stack([q_prompt[l, s0:s1][text_pos, h * G + g] for g in range(G)])      # [G, T, d]
                 out[b, l, h] = text_sparsity_score(qt, k[l, s0:s1, h], text_pos, cfg.scale, k_top, cfg.score_causal)
     return out
+
+
+def cumulative_focus(q_steps: np.ndarray, k: np.ndarray, scale: float, k_top: int) -> np.ndarray:
+    """Cumulative focus count of one attention head (Section 2.1, Eq. 1).
+
+    q_steps [N, d]: the head's query at each of N decoding steps; k [C, d]: the keys of the context.
+    At step i the attention score vector over the context is a_i = softmax(q_i K^T * scale); token j
+    scores a point when it is among the k_top largest entries of a_i (equal entries go to the lower
+    position, as everywhere else here; the paper does not say).  F_j is the number of steps at which
+    j scored.  Returns int64 [C]."""
+    q = np.asarray(q_steps, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    C = kk.shape[0]
+    F = np.zeros(C, np.int64)
+    pos = np.arange(C)
+    for i in range(q.shape[0]):
+        logits = (kk @ q[i]) * scale
+        e = np.exp(logits - logits.max())
+        a = e / e.sum()
+        F[top_indices(a, pos, min(k_top, C))] += 1
+    return F
 
 
 def full_decode_attn(cfg: OracleConfig, cu_seqlens: np.ndarray, q: np.ndarray, k: np.ndarray, v: np.ndarray,

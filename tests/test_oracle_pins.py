@@ -479,3 +479,30 @@ def test_chunk_scores_max_over_group_against_hand_values_and_the_sum_reading():
     assert np.all(O.chunk_scores(q5, m, "max") >= O.chunk_scores(q5, m, "sum") / 5 - 1e-12)
     with pytest.raises(ValueError):
         O.chunk_scores(q5, m, "mean")
+
+
+# ---------------------------------------------------------------- cumulative focus count (Section 2.1, Eq. 1)
+def test_cumulative_focus_hand_case_and_invariants():
+    # keys are the unit vectors of R^3 and their negatives; a query picks the keys by its components
+    k = np.array([[1.0, 0, 0], [0, 1.0, 0], [0, 0, 1.0], [-1.0, 0, 0], [0, -1.0, 0]])
+    q = np.array([[3.0, 2.0, 1.0],     # logits 3, 2, 1, -3, -2 -> top-2 = {0, 1}
+                  [-1.0, 5.0, 4.0],    # logits -1, 5, 4, 1, -5 -> top-2 = {1, 2}
+                  [0.0, 0.0, 0.0]])    # all equal -> the two lowest positions {0, 1}
+    np.testing.assert_array_equal(O.cumulative_focus(q, k, 1.0, 2), [2, 3, 1, 0, 0])
+    np.testing.assert_array_equal(O.cumulative_focus(q, k, 1.0, 5), [3] * 5)          # k = C: every token, every step
+    # k = 1 is the histogram of the most attended token
+    rng = np.random.default_rng(21)
+    kk = rng.standard_normal((50, 16))
+    qq = rng.standard_normal((200, 16))
+    F1 = O.cumulative_focus(qq, kk, 0.25, 1)
+    np.testing.assert_array_equal(F1, np.bincount((qq @ kk.T).argmax(axis=1), minlength=50))
+    # softmax is increasing, so a library top-k on the logits names the same tokens (distinct values)
+    F7 = O.cumulative_focus(qq, kk, 0.25, 7)
+    idx = torch.topk(torch.from_numpy(qq @ kk.T), 7, dim=1).indices.numpy()
+    np.testing.assert_array_equal(F7, np.bincount(idx.ravel(), minlength=50))
+    assert F7.sum() == 200 * 7 and F7.max() <= 200
+    # a head that asks the same question at every step focuses on the same tokens every time
+    Fs = O.cumulative_focus(np.repeat(qq[:1], 30, axis=0), kk, 0.25, 4)
+    assert sorted(set(Fs.tolist())) == [0, 30] and (Fs == 30).sum() == 4
+    # the scale does not change the ranking
+    np.testing.assert_array_equal(O.cumulative_focus(qq, kk, 1.0, 7), F7)
