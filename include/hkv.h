@@ -261,6 +261,26 @@ HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);
 HKV_API int hkv_profile_read(hkv_cache* cache, double* ms, int* n_calls);
 HKV_API int hkv_profile_disable(hkv_cache* cache);
 
+/* ---- diagnostic: cumulative focus count of every attention head (paper, Section 2.1, Eq. 1) ---------
+ *
+ * For one layer and one sequence: at each of n_steps decoding steps every query head attends over the
+ * context_len context tokens; F[head][j] counts the steps at which token j was among the head's
+ * k = ceil(focus_fraction * context_len) most attended tokens (the paper uses 0.05 and 500 steps).
+ * Softmax is increasing, so the ranking is taken on the scaled logits; equal values go to the lower
+ * position.  A head whose counts pile up on few tokens is what the paper calls static.
+ *   q_steps  : [device] [n_steps][n_q_heads][head_dim]      the layer's queries of the decoding steps
+ *   k        : [device] [context_len][n_kv_heads][head_dim] the layer's keys of the context
+ *   counts   : [device, 16-byte aligned] [n_q_heads][context_len] int32, overwritten
+ *   workspace: [device, 16-byte aligned] at least *min_bytes of hkv_focus_counts_workspace_size (the logits
+ *              of one KV head's query heads); with *best_bytes all KV heads go in one pass.
+ * Uses cfg's shape, dtype and softmax_scale.  Work is enqueued on `stream`; the call does not
+ * synchronise.  (It clears `counts` with a memset on the stream: not meant for graph capture.) */
+HKV_API int hkv_focus_counts_workspace_size(const hkv_config* cfg, int32_t n_steps, int32_t context_len,
+                                    size_t* min_bytes, size_t* best_bytes);
+HKV_API int hkv_focus_counts(const hkv_config* cfg, int32_t n_steps, int32_t context_len, const void* q_steps,
+                     const void* k, double focus_fraction, int32_t* counts, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
 /* ---- upstream of hkv_compress: head classification and budget allocation ------------------------
  *
  * hkv_head_scores: text-centric sparsity score of every (layer, sequence, KV head) (paper, Section 3.1).

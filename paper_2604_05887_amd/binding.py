@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_query_tier_sizes", "hkv_cache_create_tiered", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
     "hkv_cache_decode_shape", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
-    "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read", "hkv_head_scores_workspace_size", "hkv_head_scores", "hkv_allocate_budgets",
+    "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read", "hkv_head_scores_workspace_size", "hkv_head_scores", "hkv_focus_counts_workspace_size", "hkv_focus_counts", "hkv_allocate_budgets",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
 
@@ -97,6 +97,9 @@ def load_library() -> C.CDLL:
                                                    C.POINTER(C.c_uint8), C.POINTER(sz), C.POINTER(sz)]
     lib.hkv_head_scores.argtypes = [C.POINTER(hkv_config), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_uint8), i32, vp, vp,
                                     C.c_double, vp, vp, sz, vp]
+    lib.hkv_focus_counts_workspace_size.argtypes = [C.POINTER(hkv_config), C.c_int32, C.c_int32, C.POINTER(sz),
+                                                    C.POINTER(sz)]
+    lib.hkv_focus_counts.argtypes = [C.POINTER(hkv_config), C.c_int32, C.c_int32, vp, vp, C.c_double, vp, vp, sz, vp]
     lib.hkv_allocate_budgets.argtypes = [C.c_int32, C.POINTER(C.c_float), C.c_float, C.c_int64, C.c_float, C.c_float,
                                          C.c_int32, C.POINTER(C.c_uint8), C.POINTER(C.c_int32)]
     lib.hkv_cache_destroy.argtypes = [vp]
@@ -295,6 +298,20 @@ def hkv_head_scores(cfg: hkv_config, cu_seqlens, is_visual, n_layers_call: int, 
                                           vis.ctypes.data_as(C.POINTER(C.c_uint8)), n_layers_call, _ptr(q_prompt), _ptr(k),
                                           focus_fraction, _ptr(scores), _ptr(workspace), workspace_bytes, _stream(stream)),
            "hkv_head_scores")
+
+
+def hkv_focus_counts_workspace_size(cfg: hkv_config, n_steps: int, context_len: int) -> Tuple[int, int]:
+    lo, hi = C.c_size_t(0), C.c_size_t(0)
+    _check(load_library().hkv_focus_counts_workspace_size(C.byref(cfg), n_steps, context_len, C.byref(lo), C.byref(hi)),
+           "hkv_focus_counts_workspace_size")
+    return int(lo.value), int(hi.value)
+
+
+def hkv_focus_counts(cfg: hkv_config, n_steps: int, context_len: int, q_steps, k, focus_fraction: float, counts,
+                     workspace, workspace_bytes: int, stream=None) -> None:
+    _check(load_library().hkv_focus_counts(C.byref(cfg), n_steps, context_len, _ptr(q_steps), _ptr(k), focus_fraction,
+                                           _ptr(counts), _ptr(workspace), workspace_bytes, _stream(stream)),
+           "hkv_focus_counts")
 
 
 def hkv_allocate_budgets(scores, theta: float, total_budget: int, share_ratio: float, alpha: float,

@@ -28,7 +28,8 @@ constexpr int kRowsPerBlock = 256;     // text rows staged per workgroup of logi
 constexpr int kKeysPerLogitBlock = 512;
 
 // grid = (key splits, row chunks, heads of the pass); block = 256 threads.
-// Row r of a head is (g = r / T, t = r % T): query head head*G + g at the t-th text token.
+// Row r of a head is (g = r / T, t = r % T): query head head*G + g at the t-th text token
+// (text_pos == nullptr: at token t itself).
 template <typename T>
 __global__ __launch_bounds__(256) void logits_kernel(const T* __restrict__ q_layer, const T* __restrict__ k_layer,
                                                      const int32_t* __restrict__ text_pos, int64_t seq_start, int C,
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(256) void logits_kernel(const T* __restrict__ q_lay
       val[u] = make_uint4(0, 0, 0, 0);
       if (idx < n_rb * 32 * PPR && rl < rows_here) {
         const int r = row0 + rl, g = r / n_text, t = r % n_text;
-        const size_t src = ((size_t)(seq_start + text_pos[t]) * n_q_heads + (size_t)head * G + g) * ROWB;
+        const size_t src = ((size_t)(seq_start + (text_pos ? text_pos[t] : t)) * n_q_heads + (size_t)head * G + g) * ROWB;
         val[u] = ld16(reinterpret_cast<const char*>(q_layer) + src + piece * 16);
       }
     }
@@ -221,6 +222,41 @@ __global__ __launch_bounds__(256) void row_topk_reg_kernel(const float* __restri
   if (tid == 0) row_value[blockIdx.x] = (above + ((float)kt - n_gt) * fast_exp2(key_to_float(thr) - m)) / z;
 }
 
+// Cumulative focus count (Section 2.1, Eq. 1).  grid = rows of the pass (KV heads x G x steps), block = 256
+// threads: one step's logit row of one query head per workgroup.  The k_top largest logits of the row
+// (softmax is increasing, so these are the k_top most attended tokens; equal values go to the lower
+// position) each add one to their token's counter.  counts: [n_q_heads][C] int32, head0 = first KV head of
+// the pass.
+__global__ __launch_bounds__(256) void row_focus_kernel(const float* __restrict__ logits, int64_t head_stride, int pitch,
+                                                        int C, int n_steps, int rows_per_head, int k_top, int G,
+                                                        int head0, int32_t* __restrict__ counts) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t bc[2];
+  __shared__ int scan[6];
+  const int tid = thread_index();
+  const int hp = blockIdx.x / rows_per_head, r = blockIdx.x % rows_per_head;
+  const float* row = logits + (size_t)hp * head_stride + (size_t)r * pitch;
+  int32_t* out = counts + ((size_t)(head0 + hp) * G + r / n_steps) * C;
+  const int kt = min(k_top, C);
+  uint32_t t_key = 0;
+  int r_adm = C;
+  if (kt < C)
+    radix_select<256>(C, kt, [&](int j, uint32_t& key) { key = float_order_key(row[j]); return true; }, hist, bc, t_key,
+                      r_adm);
+  int base_eq = 0;
+  for (int j0 = 0; j0 < C; j0 += 256) {              // uniform trip count
+    const int j = j0 + tid;
+    const bool in = j < C;
+    const uint32_t key = in ? float_order_key(row[j]) : 0u;
+    const bool gt = in && key > t_key;
+    const int eq = (in && key == t_key) ? 1 : 0;
+    int tot_eq;
+    const int eq_rank = base_eq + block_exclusive_scan<256>(eq, scan, &tot_eq);
+    if (gt || (eq && eq_rank < r_adm)) atomicAdd(out + j, 1);
+    base_eq += tot_eq;
+  }
+}
+
 // grid = heads of the pass, block = 256 threads: mean of the head's row values, fixed summation order.
 __global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ row_value, int rows_per_head,
                                                      float* __restrict__ scores) {
@@ -371,6 +407,75 @@ int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seql
 }
 
 // ---- budget allocation (host arithmetic, Section 3.2) ---------------------------------------------
+namespace {
+struct FocusShape { size_t off_logits = 0, head_bytes = 0; int pitch = 0; };
+int focus_shape(const hkv_config* cfg, int32_t n_steps, int32_t context_len, FocusShape& fs) {
+  int rc = validate_config(cfg);
+  if (rc != HKV_OK) return rc;
+  if (n_steps < 1 || n_steps > (1 << 20) || context_len < 1 || context_len >= (1 << 24)) return HKV_ESHAPE;
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  fs.pitch = (context_len + 31) / 32 * 32;
+  fs.head_bytes = (size_t)G * n_steps * fs.pitch * sizeof(float);
+  fs.off_logits = 0;
+  return HKV_OK;
+}
+}  // namespace
+
+int hkv_focus_counts_workspace_size(const hkv_config* cfg, int32_t n_steps, int32_t context_len, size_t* min_bytes,
+                                    size_t* best_bytes) {
+  if (!min_bytes && !best_bytes) return HKV_EINVAL;
+  FocusShape fs;
+  int rc = focus_shape(cfg, n_steps, context_len, fs);
+  if (rc != HKV_OK) return rc;
+  if (min_bytes) *min_bytes = align_up_c(fs.head_bytes);
+  if (best_bytes) *best_bytes = align_up_c(fs.head_bytes * (size_t)cfg->n_kv_heads);
+  return HKV_OK;
+}
+
+int hkv_focus_counts(const hkv_config* cfg, int32_t n_steps, int32_t context_len, const void* q_steps, const void* k,
+                     double focus_fraction, int32_t* counts, void* workspace, size_t workspace_bytes, void* stream) {
+  FocusShape fs;
+  int rc = focus_shape(cfg, n_steps, context_len, fs);
+  if (rc != HKV_OK) return rc;
+  if (!q_steps || !k || !counts || !workspace) return HKV_EINVAL;
+  if (!(focus_fraction > 0.0) || !(focus_fraction <= 1.0)) return HKV_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(q_steps) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(workspace) |
+       reinterpret_cast<uintptr_t>(counts)) & 15u)
+    return HKV_EALIGN;
+  if (workspace_bytes < align_up_c(fs.head_bytes)) return HKV_ENOSPACE;
+  const int Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, G = Hq / Hkv, C = context_len;
+  const size_t es = cfg->dtype == HKV_BF16 ? 2 : 4;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* d_logits = static_cast<float*>(workspace);
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)kD);
+  const float scale_log2e = scale * 1.4426950408889634f;
+  const size_t smem = (size_t)kRowsPerBlock * (kD * es + 16);
+  const void* fn = cfg->dtype == HKV_BF16 ? reinterpret_cast<const void*>(&logits_kernel<bf16_t>)
+                                          : reinterpret_cast<const void*>(&logits_kernel<float>);
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) return HKV_EHIP;
+  if (hipMemsetAsync(counts, 0, (size_t)Hq * C * sizeof(int32_t), st) != hipSuccess) return HKV_EHIP;
+  const int rows = G * n_steps;
+  const int64_t head_stride = (int64_t)rows * fs.pitch;
+  const int heads_per_pass = (int)std::min<size_t>((size_t)Hkv, workspace_bytes / fs.head_bytes);
+  const int k_top = std::max(1, std::min(C, (int)std::ceil(focus_fraction * C - 1e-9)));
+  for (int h0 = 0; h0 < Hkv; h0 += heads_per_pass) {
+    const int nh = std::min(heads_per_pass, Hkv - h0);
+    const dim3 grid((C + kKeysPerLogitBlock - 1) / kKeysPerLogitBlock, (rows + kRowsPerBlock - 1) / kRowsPerBlock, nh);
+    if (cfg->dtype == HKV_BF16)
+      hipLaunchKernelGGL(logits_kernel<bf16_t>, grid, dim3(256), smem, st, static_cast<const bf16_t*>(q_steps),
+                         static_cast<const bf16_t*>(k), (const int32_t*)nullptr, (int64_t)0, C, n_steps, G, Hq, Hkv, h0,
+                         scale_log2e, d_logits, head_stride, fs.pitch);
+    else
+      hipLaunchKernelGGL(logits_kernel<float>, grid, dim3(256), smem, st, static_cast<const float*>(q_steps),
+                         static_cast<const float*>(k), (const int32_t*)nullptr, (int64_t)0, C, n_steps, G, Hq, Hkv, h0,
+                         scale_log2e, d_logits, head_stride, fs.pitch);
+    hipLaunchKernelGGL(row_focus_kernel, dim3((unsigned)(nh * rows)), dim3(256), 0, st, d_logits, head_stride, fs.pitch,
+                       C, n_steps, rows, k_top, G, h0, counts);
+    if (hipGetLastError() != hipSuccess) return HKV_EHIP;
+  }
+  return HKV_OK;
+}
+
 int hkv_allocate_budgets(int32_t n_heads, const float* scores, float theta, int64_t total_budget, float share_ratio,
                          float alpha, int32_t pad_pow2, uint8_t* head_type, int32_t* budget) {
   if (n_heads < 1 || !scores || !head_type || !budget || total_budget < 0) return HKV_EINVAL;

@@ -547,3 +547,113 @@ def test_the_two_group_readings_pick_different_chunks():
                       for h in range(wl.n_kv_heads) if wl.head_type[0, l, h] == O.DYNAMIC])
         dw.cache.close()
     assert any(not np.array_equal(a, b) for a, b in zip(*picks))
+
+
+# ---- cumulative focus count of every head (Section 2.1, Eq. 1) ----
+
+def _focus_bounds(q_steps, k, scale, k_top, band_rel):
+    """Per token: in how many steps it is surely / possibly among the k_top largest logits, when a
+    logit within `band` of the cut may fall on either side (fp32 logits on the device, fp64 here)."""
+    q = q_steps.astype(np.float64)
+    kk = k.astype(np.float64)
+    C = kk.shape[0]
+    lo, hi = np.zeros(C, np.int64), np.zeros(C, np.int64)
+    for i in range(q.shape[0]):
+        lg = (kk @ q[i]) * scale
+        if k_top >= C:
+            lo += 1
+            hi += 1
+            continue
+        srt = np.sort(lg)[::-1]
+        band = band_rel * np.linalg.norm(q[i]) * np.linalg.norm(kk, axis=1).max() * scale
+        lo += lg > srt[k_top] + band          # clearly above the first one left out
+        hi += lg >= srt[k_top - 1] - band     # not clearly below the last one taken
+    return lo, hi
+
+
+@pytest.mark.parametrize("cfg_id,n_steps,frac", [(1, 24, 0.05), (0, 16, 0.05), (1, 5, 0.3), (1, 3, 1.0)])
+def test_cumulative_focus_counts_match_the_oracle(cfg_id, n_steps, frac):
+    wl = make_workload(cfg_id, n_layers=2, shrink=4 if cfg_id == 1 else 2, steps=n_steps)
+    l, b = 1, 0
+    C = int(wl.seqlens[b]) - 3                       # a context length that is no multiple of 32
+    cfg = B.make_config(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, dtype=runner.hkv_dtype(wl.dtype),
+                        window=wl.window)
+    q_host = np.ascontiguousarray(wl.q_steps[:n_steps, l, b])            # [N, Hq, d]
+    k_host = np.ascontiguousarray(wl.k[l, :C])                           # [C, Hkv, d]
+    q_dev, k_dev = runner.to_device(q_host, wl.dtype), runner.to_device(k_host, wl.dtype)
+    lo_b, hi_b = B.hkv_focus_counts_workspace_size(cfg, n_steps, C)
+    assert lo_b * wl.n_kv_heads >= hi_b > lo_b
+    got = []
+    for nbytes in (hi_b, lo_b):                      # all KV heads in one pass / one KV head per pass
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+        counts = torch.full((wl.n_q_heads, C), -7, dtype=torch.int32, device="cuda:0")
+        B.hkv_focus_counts(cfg, n_steps, C, q_dev, k_dev, frac, counts, ws, nbytes)
+        torch.cuda.synchronize()
+        got.append(counts.cpu().numpy().astype(np.int64))
+    assert np.array_equal(got[0], got[1])
+    F = got[0]
+    k_top = O.focus_count(C, frac)
+    assert np.all(F.sum(axis=1) == n_steps * k_top) and F.min() >= 0 and F.max() <= n_steps
+    scale = 1.0 / np.sqrt(128.0)
+    G = wl.group
+    exact = 0
+    for hq in range(wl.n_q_heads):
+        ref = O.cumulative_focus(q_host[:, hq], k_host[:, hq // G], scale, k_top)
+        lo, hi = _focus_bounds(q_host[:, hq], k_host[:, hq // G], scale, k_top, 1e-5)
+        assert np.all(lo <= ref) and np.all(ref <= hi)                   # the bounds bracket the oracle itself
+        assert np.all(lo <= F[hq]) and np.all(F[hq] <= hi), f"head {hq}: counts outside the tie band"
+        exact += int(np.array_equal(F[hq], ref))
+    print(f"\n[focus cfg{cfg_id}] C={C} k={k_top} steps={n_steps}: {exact}/{wl.n_q_heads} heads bit-equal to the oracle",
+          flush=True)
+    assert exact >= wl.n_q_heads - 2                 # a near-tie at the cut is rare
+    if frac == 1.0:
+        assert np.all(F == n_steps)
+
+
+def test_focus_counts_argument_checks():
+    cfg = B.make_config(n_layers=1, n_q_heads=28, n_kv_heads=4, dtype=B.HKV_BF16, window=32)
+    t = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
+    for args, status in (((0, 100), B.HKV_ESHAPE), ((4, 0), B.HKV_ESHAPE)):
+        with pytest.raises(B.HkvError) as ei:
+            B.hkv_focus_counts_workspace_size(cfg, *args)
+        assert ei.value.status == status
+    with pytest.raises(B.HkvError) as ei:
+        B.hkv_focus_counts(cfg, 4, 100, t, t, 0.05, t, t, 16)            # workspace too small
+    assert ei.value.status == B.HKV_ENOSPACE
+    with pytest.raises(B.HkvError) as ei:
+        B.hkv_focus_counts(cfg, 4, 100, t, t, 0.0, t, t, 1 << 20)        # fraction out of range
+    assert ei.value.status == B.HKV_EINVAL
+
+
+def test_focus_counts_full_context_and_planted_ties():
+    """Config 1's full context (8192 tokens); every key appears twice (positions 2j and 2j+1), so each
+    row's cut falls between two exactly equal logits whenever k is odd: the lower position must win."""
+    wl = make_workload(1, n_layers=1, steps=8)
+    C = int(wl.seqlens[0]) - 1                        # 8191 -> k = ceil(0.05 * 8191) = 410; use a fraction giving an odd k
+    frac = 411 / C
+    cfg = B.make_config(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, dtype=B.HKV_BF16, window=wl.window)
+    q_host = np.ascontiguousarray(wl.q_steps[:8, 0, 0])
+    k_host = np.ascontiguousarray(wl.k[0, :C]).copy()
+    k_host[1::2] = k_host[0:C - 1:2]
+    k_top = O.focus_count(C, frac)
+    assert k_top == 411
+    q_dev, k_dev = runner.to_device(q_host, "bf16"), runner.to_device(k_host, "bf16")
+    _, hi_b = B.hkv_focus_counts_workspace_size(cfg, 8, C)
+    ws = torch.empty(hi_b, dtype=torch.uint8, device="cuda:0")
+    counts = torch.empty((wl.n_q_heads, C), dtype=torch.int32, device="cuda:0")
+    B.hkv_focus_counts(cfg, 8, C, q_dev, k_dev, frac, counts, ws, hi_b)
+    torch.cuda.synchronize()
+    F = counts.cpu().numpy().astype(np.int64)
+    assert np.all(F.sum(axis=1) == 8 * k_top)
+    # within a pair the lower position is never behind the upper one, and is ahead at every split cut
+    assert np.all(F[:, 0:C - 1:2] >= F[:, 1::2])
+    # odd k: one split pair per step, except at steps where the unpaired last token is among the picks
+    assert np.all((F[:, 0:C - 1:2] - F[:, 1::2]).sum(axis=1) == 8 - F[:, C - 1])
+    G = wl.group
+    exact = 0
+    for hq in range(0, wl.n_q_heads, 3):
+        ref = O.cumulative_focus(q_host[:, hq], k_host[:, hq // G], 1.0 / np.sqrt(128.0), k_top)
+        lo, hi = _focus_bounds(q_host[:, hq], k_host[:, hq // G], 1.0 / np.sqrt(128.0), k_top, 1e-5)
+        assert np.all(lo <= F[hq]) and np.all(F[hq] <= hi)
+        exact += int(np.array_equal(F[hq], ref))
+    assert exact >= len(range(0, wl.n_q_heads, 3)) - 1
