@@ -657,3 +657,40 @@ def test_focus_counts_full_context_and_planted_ties():
         assert np.all(lo <= F[hq]) and np.all(F[hq] <= hi)
         exact += int(np.array_equal(F[hq], ref))
     assert exact >= len(range(0, wl.n_q_heads, 3)) - 1
+
+
+# ---- degenerate prompts ----
+
+@pytest.mark.parametrize("dtype,chunks", [("bf16", [8, 8, 16, 8]), ("f32", [64, 4, 16, 256])])
+def test_degenerate_prompts_in_one_batch(dtype, chunks):
+    """A batch whose sequences sit on the edges of the method: a prompt that is exactly the observation
+    window (no historical token at all), one with five visual tokens, an ordinary one, and one whose text is
+    the window plus a single token; chunk sizes from 4 tokens up to more than the whole prompt (one short
+    chunk)."""
+    import hkv_synth.workloads as W
+    W.CONFIGS[99] = dict(name="degenerate_prompts", dtype=dtype, n_layers=2, n_q_heads=8, n_kv_heads=2, batch=4,
+                         n_visual=[0, 5, 300, 120], n_text=[32, 40, 150, 33], block=64, sep=4, window=32,
+                         chunk=chunks, budget_frac=[0.5, 0.5, 0.2, 0.2], k_chunks=2, static_frac=0.5,
+                         fixed_types=[0, 1], hierarchical=False, steps=3, q_mode="normal")
+    try:
+        wl = make_workload(99, seed=5)
+    finally:
+        del W.CONFIGS[99]
+    assert wl.seqlens.tolist() == [32, 45, 450, 153]
+    for mode in (1, 3):
+        stats = P.full_pipeline(wl, decode_dynamic=mode)
+        _say(f"degenerate prompts {dtype} mode {mode}", stats)
+
+
+@pytest.mark.parametrize("modality", [0, 1])
+def test_prompt_of_a_single_modality(modality):
+    """All text (the visual candidate set is empty, budgets fall under the text-overflow rule) and all
+    visual (no text to exempt, the window itself is visual)."""
+    wl = make_workload(0, shrink=4, steps=2)
+    wl.is_visual[:] = modality
+    stats = P.full_pipeline(wl)
+    _say(f"single modality {modality}", stats)
+    wl2 = make_workload(1, n_layers=2, shrink=8, steps=2)
+    wl2.is_visual[:] = modality
+    stats = P.full_pipeline(wl2)
+    _say(f"single modality {modality} bf16", stats)
