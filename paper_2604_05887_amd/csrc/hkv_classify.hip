@@ -164,16 +164,61 @@ __global__ __launch_bounds__(256) void row_topk_kernel(const float* __restrict__
   if (tid == 0) row_value[blockIdx.x] = (above + (float)r_adm * fast_exp2(key_to_float(t_key) - m)) / z;
 }
 
+__device__ __forceinline__ uint32_t block_min_u32(uint32_t v, uint32_t* red) {
+#pragma unroll
+  for (int mask = 1; mask < 64; mask <<= 1) v = min(v, (uint32_t)lane_xor_i((int)v, mask));
+  if ((thread_index() & 63) == 0) red[thread_index() >> 6] = v;
+  __syncthreads();
+  const uint32_t r = min(min(red[0], red[1]), min(red[2], red[3]));
+  __syncthreads();
+  return r;
+}
+
+// The kth largest of the keys the workgroup holds (N per thread; an absent entry holds 0, which is below
+// every real key), given that at least kth of them lie in [lo, hi] and none above hi: bitwise search on
+// key - lo over workgroup-wide vote counts, one barrier per bit of hi - lo.  cnt: [2][4] ints.
+template <int N>
+__device__ __forceinline__ uint32_t block_kth_largest(const uint32_t (&key)[N], int kth, uint32_t lo, uint32_t hi,
+                                                      int (*cnt)[4]) {
+  const int tid = thread_index(), wv = tid >> 6;
+  const uint32_t span = hi - lo;
+  const int nbits = 32 - __builtin_clz(span | 1u);          // block-uniform
+  __syncthreads();                                          // cnt may still be read from an earlier search
+  uint32_t thr = 0;
+  int buf = 0;
+  for (int bit = nbits - 1; bit >= 0; --bit) {
+    const uint32_t cand = thr | (1u << bit);
+    if (cand > span) continue;                              // no key lies above hi (block-uniform; keeps lo + cand <= hi)
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < N; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= lo + cand));
+    if ((tid & 63) == 0) cnt[buf][wv] = c;
+    __syncthreads();                       // the other buffer is rewritten only after the next barrier
+    if (cnt[buf][0] + cnt[buf][1] + cnt[buf][2] + cnt[buf][3] >= kth) thr = cand;
+    buf ^= 1;
+  }
+  return lo + thr;
+}
+
 // Same result as row_topk_kernel for rows of at most 256 * EPT keys, with the row read once and held in
-// registers (EPT logits per thread).  The k-th largest key is found by a 32-step bitwise search on
-// workgroup-wide vote counts (one barrier per step), as the chunk top-k of the decode path does per wave.
+// registers (EPT logits per thread).  The k-th largest key is found in two rounds of a bitwise search on
+// workgroup-wide vote counts: first among the two largest keys of every group of 32 (a subset of the row,
+// so its k-th largest is a lower bound L of the row's), then among the keys at or above L, which are few
+// and are gathered in shared memory first.  Rows where that does not narrow the field (k above the
+// subset's size, or more than kMaxCand keys at or above L) search all their keys.
+constexpr int kMaxCand = 2048;
 template <int EPT>
 __global__ __launch_bounds__(256) void row_topk_reg_kernel(const float* __restrict__ logits, int64_t head_stride, int pitch,
                                                            const int32_t* __restrict__ text_pos, int C, int n_text,
                                                            int rows_per_head, int k_top, int causal,
                                                            float* __restrict__ row_value) {
+  constexpr int NG = EPT / 32, SUB = 2 * NG, CE = kMaxCand / 256;
   __shared__ float red[4];
+  __shared__ uint32_t redu[4];
   __shared__ int cnt[2][4];
+  __shared__ int wcnt[4];
+  __shared__ uint32_t cand_key[kMaxCand];
+  __shared__ float cand_w[kMaxCand];
   const int tid = thread_index(), wv = tid >> 6;
   const int hp = blockIdx.x / rows_per_head, r = blockIdx.x % rows_per_head;
   const float* row = logits + (size_t)hp * head_stride + (size_t)r * pitch;
@@ -190,6 +235,7 @@ __global__ __launch_bounds__(256) void row_topk_reg_kernel(const float* __restri
 #pragma unroll
   for (int e = 1; e < EPT; ++e) m = fmaxf(m, v[e]);
   m = block_max(m, red);
+  const uint32_t key_max = float_order_key(m);
   float z = 0.f;
   uint32_t key[EPT];
 #pragma unroll
@@ -201,21 +247,75 @@ __global__ __launch_bounds__(256) void row_topk_reg_kernel(const float* __restri
   }
   z = block_sum(z, red);
 
-  uint32_t thr = 0;
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t cand = thr | (1u << bit);
-    int c = 0;
+  // lower bound: the kt-th largest among the two largest keys of every group of 32 keys
+  uint32_t L = 0;
+  if (kt <= 256 * SUB) {                                           // block-uniform
+    uint32_t sub[SUB];
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= cand));
-    if ((tid & 63) == 0) cnt[bit & 1][wv] = c;
-    __syncthreads();                       // the other buffer is rewritten only after the next barrier
-    if (cnt[bit & 1][0] + cnt[bit & 1][1] + cnt[bit & 1][2] + cnt[bit & 1][3] >= kt) thr = cand;
+    for (int g = 0; g < NG; ++g) {
+      uint32_t a = 0, b = 0;
+#pragma unroll
+      for (int e = 0; e < 32; ++e) {
+        const uint32_t k = key[g * 32 + e];
+        b = max(b, min(a, k));
+        a = max(a, k);
+      }
+      sub[2 * g] = a;
+      sub[2 * g + 1] = b;
+    }
+    uint32_t lo = sub[0];
+#pragma unroll
+    for (int i = 1; i < SUB; ++i) lo = min(lo, sub[i]);
+    lo = block_min_u32(lo, redu);                                  // 0 if some group has fewer than two keys
+    L = block_kth_largest<SUB>(sub, kt, lo, key_max, cnt);         // 0 (no bound) if the subset has fewer than kt keys
   }
-  float above = 0.f, n_gt = 0.f;
+
+  // keys at or above L, gathered in shared memory (any order: only their count and their weights matter)
+  int mine = 0;
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    above += key[e] > thr ? v[e] : 0.f;
-    n_gt += key[e] > thr ? 1.f : 0.f;
+  for (int e = 0; e < EPT; ++e)
+    mine += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] != 0u && key[e] >= L));
+  if ((tid & 63) == 0) wcnt[wv] = mine;
+  __syncthreads();
+  const int n_cand = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+  uint32_t thr;
+  float above = 0.f, n_gt = 0.f;
+  if (n_cand <= kMaxCand) {                                        // block-uniform
+    int run = 0;
+    for (int w = 0; w < wv; ++w) run += wcnt[w];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const bool take = key[e] != 0u && key[e] >= L;
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(take);
+      if (take) {
+        const int pos = run + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+        cand_key[pos] = key[e];
+        cand_w[pos] = v[e];
+      }
+      run += __builtin_popcountll(bal);
+    }
+    __syncthreads();
+    uint32_t ck[CE];
+    float cw[CE];
+#pragma unroll
+    for (int c = 0; c < CE; ++c) {
+      const int idx = tid + 256 * c;
+      ck[c] = idx < n_cand ? cand_key[idx] : 0u;
+      cw[c] = idx < n_cand ? cand_w[idx] : 0.f;
+    }
+    thr = block_kth_largest<CE>(ck, kt, L, key_max, cnt);
+#pragma unroll
+    for (int c = 0; c < CE; ++c) {
+      above += ck[c] > thr ? cw[c] : 0.f;
+      n_gt += ck[c] > thr ? 1.f : 0.f;
+    }
+  } else {
+    thr = block_kth_largest<EPT>(key, kt, 0u, key_max, cnt);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      above += key[e] > thr ? v[e] : 0.f;
+      n_gt += key[e] > thr ? 1.f : 0.f;
+    }
   }
   above = block_sum(above, red);
   n_gt = block_sum(n_gt, red);             // exact: at most 2^24 keys
