@@ -8,8 +8,11 @@
 //
 // Device plan, one (layer, sequence) pass at a time, all KV heads of the pass together:
 //   logits_kernel   S = Q_text K^T on the matrix cores, logits (log2 domain) written to the workspace
-//   row_topk_kernel one workgroup per text row: row maximum, normaliser, exact k-th largest logit by
-//                   radix selection, sum of the probabilities above it plus the admitted ties
+//   row top-k       per text row: row maximum, normaliser, exact k-th largest logit, sum of the
+//                   probabilities above it plus the admitted ties -- one wave per row with the row in
+//                   registers (row_topk_wave_kernel, up to 8192 keys), one workgroup per row
+//                   (row_topk_reg_kernel, up to 32768 keys), or radix selection over the row in memory
+//                   (row_topk_kernel)
 //   reduce_kernel   mean of the row values of each head, in a fixed order
 // The logits of a pass are materialised (rows x C floats per head): the exact top-k of a row needs the
 // whole row several times, and 288 GB of HBM make that the simple way to have it.
@@ -322,6 +325,186 @@ __global__ __launch_bounds__(256) void row_topk_reg_kernel(const float* __restri
   if (tid == 0) row_value[blockIdx.x] = (above + ((float)kt - n_gt) * fast_exp2(key_to_float(thr) - m)) / z;
 }
 
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+#pragma unroll
+  for (int mask = 1; mask < 64; mask <<= 1) v = min(v, (uint32_t)lane_xor_i((int)v, mask));
+  return v;
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+  for (int mask = 1; mask < 64; mask <<= 1) v = fmaxf(v, lane_xor(v, mask));
+  return v;
+}
+// Sum of a per-lane count over the wave, as a wave-uniform value (counts stay far below 2^24, so the float
+// lane reduction is exact).
+__device__ __forceinline__ int wave_total(int c) {
+  return __builtin_amdgcn_readfirstlane((int)sum64((float)c));
+}
+
+// The kth largest of the keys one wave holds (N per lane, the first n_used registers of every lane in use;
+// an absent entry holds 0), given that at least kth of them lie in [lo, hi] and none above hi: bitwise search
+// on key - lo over the wave's counts.  No barrier, no memory traffic.  VOTE: the counts are taken with
+// wave votes on the scalar unit (few registers per lane), else per lane with one lane reduction per step.
+template <int N, bool VOTE>
+__device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&key)[N], int n_used, int kth, uint32_t lo,
+                                                     uint32_t hi) {
+  const uint32_t span = hi - lo;
+  const int nbits = 32 - __builtin_clz(span | 1u);          // wave-uniform
+  uint32_t thr = 0;
+  for (int bit = nbits - 1; bit >= 0; --bit) {
+    const uint32_t cand = thr | (1u << bit);
+    if (cand > span) continue;                              // no key lies above hi; keeps lo + cand <= hi
+    const uint32_t x = lo + cand;
+    int c = 0;
+    if constexpr (VOTE) {
+#pragma unroll
+      for (int e = 0; e < N; ++e)
+        if (e < n_used) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= x));   // uniform branch
+    } else {
+#pragma unroll
+      for (int e = 0; e < N; ++e) c += key[e] >= x ? 1 : 0;
+      c = wave_total(c);
+    }
+    if (c >= kth) thr = cand;
+  }
+  return lo + thr;
+}
+
+// Same result as row_topk_reg_kernel for rows of at most 64 * KPL keys, one text row per WAVE (four rows per
+// workgroup): the row stays in the wave's registers (KPL values per lane), every reduction is a wave
+// reduction, so a row needs no barrier at all.
+// A logit v is held as key = ~bits(m - v), m the row maximum: m - v >= 0, and the bit pattern of a
+// non-negative float grows with its value, so a larger logit has a larger key, the maximum has key
+// 0xFFFFFFFF, and the weight comes back as exp2(-(m - v)) without any further conversion.  (Two logits whose
+// distances to m round to the same float share a key; they also share the computed weight, so the sum of
+// the k largest weights does not depend on which of them is taken.)
+// Same two rounds as the workgroup version: lower bound from the two largest keys of every group of 32
+// registers, then a search among the keys at or above it (gathered in the wave's own slice of shared
+// memory; at most kWaveCand, else the wave searches all its keys).
+constexpr int kWaveCand = 1024;
+__device__ __forceinline__ float weight_of_key(uint32_t key) { return fast_exp2(-bits_to_float(~key)); }
+
+template <int KPL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KPL == 128 ? 2 : KPL == 64 ? 3 : 4)))
+void row_topk_wave_kernel(const float* __restrict__ logits, int64_t head_stride, int pitch,
+                          const int32_t* __restrict__ text_pos, int C, int n_text, int rows_per_head, int n_rows_total,
+                          int k_top, int causal, float* __restrict__ row_value) {
+  constexpr int NG = KPL / 32, SUB = 2 * NG, CW = kWaveCand / 64;
+  __shared__ uint32_t cand_s[4][kWaveCand];
+  const int tid = thread_index(), lane = tid & 63, wv = tid >> 6;
+  const int gr = blockIdx.x * 4 + wv;                               // global row of this wave
+  if (gr >= n_rows_total) return;                                   // wave-uniform; no barrier below
+  const int hp = gr / rows_per_head, r = gr % rows_per_head;
+  const float* row = logits + (size_t)hp * head_stride + (size_t)r * pitch;
+  const int n = causal ? min(C, text_pos[r % n_text] + 1) : C;
+  const int kt = min(k_top, n);
+
+  uint32_t key[KPL];                                                // first the logits' bits, then the keys, in place
+  float z = 0.f;
+  {
+    float m = kNeg;
+    if (n == 64 * KPL) {                                            // wave-uniform: a full row needs no bounds checks
+#pragma unroll
+      for (int e = 0; e < KPL; ++e) { key[e] = float_to_bits(row[lane + 64 * e]); m = fmaxf(m, bits_to_float(key[e])); }
+    } else {
+#pragma unroll
+      for (int e = 0; e < KPL; ++e) {
+        const int j = lane + 64 * e;
+        key[e] = float_to_bits(j < n ? row[j] : kNeg);
+        m = fmaxf(m, bits_to_float(key[e]));
+      }
+    }
+    m = wave_max_f32(m);
+#pragma unroll
+    for (int e = 0; e < KPL; ++e) {
+      const float d = m - bits_to_float(key[e]);                    // absent entries: about 1e30
+      z += fast_exp2(-d);                                           // ... which adds exactly 0
+      key[e] = ~float_to_bits(d);
+    }
+    if (n != 64 * KPL) {
+#pragma unroll
+      for (int e = 0; e < KPL; ++e) key[e] = lane + 64 * e < n ? key[e] : 0u;   // 0 is below every real key
+    }
+  }
+  z = sum64(z);
+  constexpr uint32_t key_max = 0xFFFFFFFFu;                         // the row maximum itself
+
+  uint32_t L = 0;
+  if (kt <= 64 * SUB) {                                             // wave-uniform
+    uint32_t sub[SUB];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      uint32_t a = 0, b = 0;
+#pragma unroll
+      for (int e = 0; e < 32; ++e) {
+        const uint32_t k = key[g * 32 + e];
+        b = max(b, min(a, k));
+        a = max(a, k);
+      }
+      sub[2 * g] = a;
+      sub[2 * g + 1] = b;
+    }
+    uint32_t lo = sub[0];
+#pragma unroll
+    for (int i = 1; i < SUB; ++i) lo = min(lo, sub[i]);
+    lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_min_u32(lo));   // 0 if some group has fewer than two keys
+    L = wave_kth_largest<SUB, true>(sub, SUB, kt, lo, key_max);     // 0 (no bound) if the subset has fewer than kt keys
+  }
+
+  const uint32_t Lc = max(L, 1u);                                   // absent entries (0) are never candidates
+  int my_cand = 0;
+#pragma unroll
+  for (int e = 0; e < KPL; ++e) my_cand += key[e] >= Lc ? 1 : 0;
+  const int n_cand = wave_total(my_cand);
+  uint32_t thr;
+  float above = 0.f;
+  int n_gt = 0;
+  if (n_cand <= kWaveCand) {                                        // wave-uniform
+    // every lane writes its own candidates behind those of the lanes before it (any order will do)
+    uint32_t* mine = cand_s[wv];
+    int pos = wave_inclusive_scan(my_cand) - my_cand;
+    uint32_t Lw = Lc;
+    asm volatile("" : "+v"(Lw));            // a value of its own: the compares are redone here, one at a time,
+                                            // instead of keeping KPL lane masks alive from the counting loop
+#pragma unroll
+    for (int e = 0; e < KPL; ++e)
+      if (key[e] >= Lw) mine[pos++] = key[e];
+    // the wave's shared-memory operations execute in issue order; the fences only keep the compiler from
+    // moving the reads below above the writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint32_t ck[CW];
+    const int n_used = (n_cand + 63) >> 6;
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+      const int idx = lane + 64 * c;
+      ck[c] = idx < n_cand ? mine[idx] : 0u;
+    }
+    thr = wave_kth_largest<CW, true>(ck, n_used, kt, L, key_max);
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+      if (c < n_used) {                                             // wave-uniform
+        const bool gt = ck[c] > thr;
+        above += gt ? weight_of_key(ck[c]) : 0.f;
+        n_gt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(gt));
+      }
+    }
+  } else {
+    thr = wave_kth_largest<KPL, false>(key, KPL, kt, 0u, key_max);
+    int my_gt = 0;
+#pragma unroll
+    for (int e = 0; e < KPL; ++e) {
+      const bool gt = key[e] > thr;
+      above += gt ? weight_of_key(key[e]) : 0.f;
+      my_gt += gt ? 1 : 0;
+    }
+    n_gt = wave_total(my_gt);
+  }
+  above = sum64(above);
+  if (lane == 0) row_value[gr] = (above + (float)(kt - n_gt) * weight_of_key(thr)) / z;
+}
+
 // Cumulative focus count (Section 2.1, Eq. 1).  grid = rows of the pass (KV heads x G x steps), block = 256
 // threads: one step's logit row of one query head per workgroup.  The k_top largest logits of the row
 // (softmax is increasing, so these are the k_top most attended tokens; equal values go to the lower
@@ -378,6 +561,15 @@ namespace {
 constexpr size_t kAlignC = 256;
 inline size_t align_up_c(size_t x) { return (x + kAlignC - 1) / kAlignC * kAlignC; }
 
+// Floats per logit row: a multiple of 32 that covers n_keys, and never a multiple of 1024: rows that start
+// a power-of-two number of bytes apart would all begin in the same memory channel, and the row kernels,
+// which walk their rows in step, would queue up on one channel after another.
+inline size_t logit_pitch(size_t n_keys) {
+  size_t pitch = (n_keys + 31) / 32 * 32;
+  if (pitch % 1024 == 0) pitch += 64;
+  return pitch;
+}
+
 struct ClassifyShape {
   std::vector<int32_t> text_pos;        // all sequences, packed
   std::vector<int64_t> text_begin;      // [batch + 1]
@@ -402,7 +594,7 @@ int classify_shape(const hkv_config* cfg, int32_t batch, const int32_t* cu, cons
     }
     sh.text_begin[b + 1] = (int64_t)sh.text_pos.size();
     const size_t T = (size_t)(sh.text_begin[b + 1] - sh.text_begin[b]);
-    const size_t pitch = ((size_t)C + 31) / 32 * 32;
+    const size_t pitch = logit_pitch((size_t)C);
     sh.max_rows = std::max(sh.max_rows, (size_t)G * T);
     sh.head_bytes_max = std::max(sh.head_bytes_max, (size_t)G * T * pitch * sizeof(float));
   }
@@ -473,7 +665,7 @@ int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seql
         continue;
       }
       const int rows = G * T;
-      const int pitch = (C + 31) / 32 * 32;
+      const int pitch = (int)logit_pitch((size_t)C);
       const int64_t head_stride = (int64_t)rows * pitch;
       const int heads_per_pass = (int)std::min<size_t>((size_t)Hkv, logits_room / ((size_t)head_stride * 4));
       const int k_top = std::max(1, std::min(C, (int)std::ceil(focus_fraction * C - 1e-9)));
@@ -493,11 +685,17 @@ int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seql
 #define HKV_ROW_TOPK(KERNEL) \
   hipLaunchKernelGGL(KERNEL, rgrid, dim3(256), 0, st, d_logits, head_stride, pitch, pos, C, T, rows, k_top, \
                      cfg->score_causal, d_rows)
-        if (C <= 256 * 32) HKV_ROW_TOPK(row_topk_reg_kernel<32>);
+#define HKV_ROW_TOPK_WAVE(KERNEL) \
+  hipLaunchKernelGGL(KERNEL, dim3((unsigned)((nh * rows + 3) / 4)), dim3(256), 0, st, d_logits, head_stride, pitch, pos, C, T, \
+                     rows, nh * rows, k_top, cfg->score_causal, d_rows)
+        if (C <= 64 * 32) HKV_ROW_TOPK_WAVE(row_topk_wave_kernel<32>);        // one row per wave, no barriers
+        else if (C <= 64 * 64) HKV_ROW_TOPK_WAVE(row_topk_wave_kernel<64>);
+        else if (C <= 64 * 128) HKV_ROW_TOPK_WAVE(row_topk_wave_kernel<128>);
         else if (C <= 256 * 64) HKV_ROW_TOPK(row_topk_reg_kernel<64>);
         else if (C <= 256 * 128) HKV_ROW_TOPK(row_topk_reg_kernel<128>);
         else HKV_ROW_TOPK(row_topk_kernel);      // longer rows are re-read from memory on every pass
 #undef HKV_ROW_TOPK
+#undef HKV_ROW_TOPK_WAVE
         hipLaunchKernelGGL(reduce_kernel, dim3(nh), dim3(256), 0, st, d_rows, rows, out + h0);
         if (hipGetLastError() != hipSuccess) return HKV_EHIP;
       }
@@ -514,7 +712,7 @@ int focus_shape(const hkv_config* cfg, int32_t n_steps, int32_t context_len, Foc
   if (rc != HKV_OK) return rc;
   if (n_steps < 1 || n_steps > (1 << 20) || context_len < 1 || context_len >= (1 << 24)) return HKV_ESHAPE;
   const int G = cfg->n_q_heads / cfg->n_kv_heads;
-  fs.pitch = (context_len + 31) / 32 * 32;
+  fs.pitch = (int)logit_pitch((size_t)context_len);
   fs.head_bytes = (size_t)G * n_steps * fs.pitch * sizeof(float);
   fs.off_logits = 0;
   return HKV_OK;
