@@ -55,9 +55,10 @@ def main() -> int:
     ap.add_argument("--budget-frac", type=float, default=None)
     ap.add_argument("--head-mix", default=None, choices=["all_static", "all_dynamic"])
     ap.add_argument("--tile-rows", type=int, default=0, help="decode tile rows (0 = library default)")
-    ap.add_argument("--dynamic-mode", type=int, default=0, choices=[0, 1, 2, 3],
+    ap.add_argument("--dynamic-mode", type=int, default=0, choices=[0, 1, 2, 3, 4],
                     help="dynamic heads: 1 = one workgroup per head in the main launch, 2 = split-K tiles in a "
-                         "second launch, 3 = single launch with repeated selection, 0 = library default")
+                         "second launch, 3 = single launch with repeated selection, 4 = one wide workgroup per "
+                         "head of either kind and no split-K, 0 = library default")
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--host-tier", action="store_true",
                     help="keep the dynamic heads' prompt rows in page-locked host memory (bf16 workloads)")
@@ -477,7 +478,7 @@ def main() -> int:
         "kernel_us": {"main_launch": round(a_us, 2), "second_launch": round(b_us, 2),
                       "attn_merge_kernel": round(merge_us, 2)},
         "dynamic_tiles_gbs": round(b_gbs, 1),
-        "roofline": {"kernel": "dynamic_tiles_kernel" if dyn_mode == 3 else "decode_kernel", "bound": "hbm", "achieved": round(a_gbs, 1),
+        "roofline": {"kernel": {3: "dynamic_tiles_kernel", 4: "unit_kernel"}.get(dyn_mode, "decode_kernel"), "bound": "hbm", "achieved": round(a_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(a_gbs / HBM_PEAK_GBS, 4),
                      "traffic": _read_traffic(f"pmc_main_decode_launch_{wl.name}.txt"),
                      "bytes_per_launch": int(a_bytes), "avg_launch_us": round(a_us, 2),

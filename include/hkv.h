@@ -101,8 +101,13 @@ typedef struct {
                                chunk selection, attention and the output inside the main launch;
                                2 = chunk selection in the main launch, split-K tiles over many
                                workgroups in a second launch; 3 = a single launch of split-K tiles, each
-                               repeating its head's chunk selection; 0 = 3 unless the repeated summary reads
-                               would exceed a quarter of a step's bytes, then 2
+                               repeating its head's chunk selection; 4 (bf16 caches only, else
+                               HKV_ESHAPE) = one wide workgroup per head, static or dynamic, does
+                               everything for its head and writes the output rows: a single launch
+                               without split-K records, for steps whose heads are few (per-layer
+                               calls, small batches); 0 = 4 for bf16 caches whose heads all have at
+                               most 768 rows (tail capacity included), else 3 unless the repeated
+                               summary reads would exceed a quarter of a step's bytes, then 2
                                (tuning knob, same results up to fp32 summation order) */
   int32_t chunk_score_group;/* how the query heads that share a KV head score a chunk (Appendix A gives one
                                query vector per head and does not treat grouped heads): 0 = the inner
@@ -213,7 +218,7 @@ HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int la
                          uint64_t* bytes);
 
 /* How decode steps of this cache run (decided at creation, see hkv_config.decode_tile_rows and
- * decode_dynamic): *tile_rows = rows per split-K tile, *dynamic_mode = 1, 2 or 3 as described at
+ * decode_dynamic): *tile_rows = rows per split-K tile, *dynamic_mode = 1 to 4 as described at
  * hkv_config.decode_dynamic.  Either pointer may be NULL. */
 HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, int32_t* dynamic_mode);
 
@@ -226,9 +231,9 @@ HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, i
  * Exports of K/V rows use the host's figure, so switch back before exporting. */
 HKV_API int hkv_cache_set_device_tail(hkv_cache* cache, int enable, void* stream);
 
-/* Switches the way decode steps run the dynamic heads (1, 2 or 3 as at hkv_config.decode_dynamic); for
- * callers that time the three on their own workload and keep the fastest.  Takes effect with the next
- * hkv_decode_attn; the cache content is not touched.  HKV_EINVAL for any other value. */
+/* Switches the way decode steps run (1 to 4 as at hkv_config.decode_dynamic); for callers that time them
+ * on their own workload and keep the fastest.  Takes effect with the next hkv_decode_attn; the cache
+ * content is not touched.  HKV_EINVAL for any other value, HKV_ESHAPE for 4 on an fp32 cache. */
 HKV_API int hkv_cache_set_decode_dynamic(hkv_cache* cache, int32_t dynamic_mode);
 
 /* Test / debug access to one unit (synchronises `stream`, then copies).  `dst`/`src` are [host].

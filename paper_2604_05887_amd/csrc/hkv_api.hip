@@ -26,7 +26,8 @@ int validate_config(const hkv_config* cfg) {
     const int t = cfg->decode_tile_rows;
     if (cfg->dtype != HKV_BF16 || (t != 128 && t != 256 && t != 512 && t != 1024)) return HKV_ESHAPE;
   }
-  if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 3) return HKV_EINVAL;
+  if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 4) return HKV_EINVAL;
+  if (cfg->decode_dynamic == 4 && cfg->dtype != HKV_BF16) return HKV_ESHAPE;   // the per-unit shape is bf16 only
   if (cfg->chunk_score_group != 0 && cfg->chunk_score_group != 1) return HKV_EINVAL;
   if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
   return HKV_OK;
@@ -210,7 +211,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
   lo.sitem_begin[L] = (int32_t)lo.sitems.size();
   lo.ditem_begin[L] = (int32_t)lo.ditems.size();
   // LDS of the chunk selection: histogram, scores, 64-bit keys and the picks of every chunk
-  if ((size_t)(256 + 8 + lo.max_chunks + 4) * 4 + (size_t)(lo.max_chunks + 4) * 12 > 150 * 1024) return HKV_ESHAPE;
+  if ((size_t)(256 + 16 + lo.max_chunks + 4) * 4 + (size_t)(lo.max_chunks + 4) * 12 > 150 * 1024) return HKV_ESHAPE;
 
   const size_t es = elem_size(cfg->dtype);
   size_t off = 0;
@@ -251,7 +252,10 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 // Dynamic heads: every dynamic tile repeats its head's chunk selection, so that the step is one launch
 // plus the combination, as long as the repeated reads of the chunk summaries stay below a quarter of
 // the step's bytes (they mostly hit the L2); with many small chunks the selection runs once per head
-// and the tiles follow in a second launch.
+// and the tiles follow in a second launch.  Heads of at most kUnitShapeMaxRows rows (tail at full
+// capacity included; bf16 caches) are not split at all: measured on the 7B shape, one wide workgroup per
+// head is ahead of the split-K shapes up to about that length and behind them beyond.
+constexpr int kUnitShapeMaxRows = 768;
 int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool tiered = false) {
   int rc;
   if (cfg && cfg->dtype != HKV_BF16) rc = plan_layout_tile(cfg, plan, lo, kTileF32, tiered);
@@ -267,7 +271,11 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
     }
   }
   if (rc != HKV_OK) return rc;
-  lo.mode = cfg->decode_dynamic != 0 ? cfg->decode_dynamic : (4 * lo.reselect_extra_bytes <= lo.step_bytes0 ? 3 : 2);
+  if (cfg->decode_dynamic != 0) lo.mode = cfg->decode_dynamic;
+  else if (cfg->dtype == HKV_BF16 &&
+           std::max(lo.max_rows_static + cfg->max_new_tokens, lo.max_rows_dynamic) <= kUnitShapeMaxRows)
+    lo.mode = 4;         // short heads: one wide workgroup each beats split-K plus the combination launch
+  else lo.mode = 4 * lo.reselect_extra_bytes <= lo.step_bytes0 ? 3 : 2;
   return HKV_OK;
 }
 
@@ -558,6 +566,20 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   const int dt = c->cfg.dtype, app = k_new ? 1 : 0;
   const int mode = lo.mode;
   const int resident = 3 * c->n_cus;      // workgroups resident at once (three per compute unit)
+  if (mode == 4) {
+    // one wide workgroup per unit writes the unit's output rows itself: no records, no combination
+    e = launch_units(c->cv, dt, lb, db, nd, sub, nsu, q, k_new, v_new, out, t_before, lo.max_chunks, st, ev[0], ev[1]);
+    if (e == hipSuccess) e = launch_attn_merge(c->cv, dt, nullptr, 0, lb, le, slot_base, parts, parts_ml, out, t_before,
+                                               app, st);          // publishes device-side tail counters, if in use
+    if (e != hipSuccess) return HKV_EHIP;
+    if (prof) {
+      c->prof_mask[c->prof_calls] = 1;
+      c->prof_calls += 1;
+      c->prof_stream = st;
+    }
+    if (k_new && !c->device_tail) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
+    return HKV_OK;
+  }
   if (mode == 3) {
     // a grid that is resident in one round: the static tiles wait for the time the dynamic tiles' summary
     // reads take at ~5 TB/s, in units of 512 clocks at ~2.4 GHz, at most 16
@@ -763,7 +785,8 @@ int hkv_cache_decode_shape(const hkv_cache* c, int32_t* tile_rows, int32_t* dyna
 }
 
 int hkv_cache_set_decode_dynamic(hkv_cache* c, int32_t dynamic_mode) {
-  if (!c || dynamic_mode < 1 || dynamic_mode > 3) return HKV_EINVAL;
+  if (!c || dynamic_mode < 1 || dynamic_mode > 4) return HKV_EINVAL;
+  if (dynamic_mode == 4 && c->cfg.dtype != HKV_BF16) return HKV_ESHAPE;
   c->lo.mode = dynamic_mode;
   return HKV_OK;
 }

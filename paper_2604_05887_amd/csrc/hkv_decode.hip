@@ -67,15 +67,34 @@ __device__ __forceinline__ bool resolve_row(const RowMap& rm, int r, int64_t& ph
 struct PartOut {
   float* o;
   float* ml;
+  uint16_t* out_bf16;    // not null: the tile is its unit's only one -- write the G normalised output rows (bf16)
+                         // here instead of a record
 };
 constexpr int kMlStride = kMlFloats;
 
 // Combine NS online-softmax streams staged in shared memory ([stream][G][kPartStride]: max, sum, pad,
-// pad, o[128]) in stream order and store the tile's record.  All 256 threads; smem must be ready.
-template <int G, int NS>
+// pad, o[128]) in stream order and store the tile's record.  All NT threads; smem must be ready.
+template <int G, int NS, int NT = 256>
 __device__ __forceinline__ void combine_streams_and_store(const float* smem, const PartOut& po) {
   const int tid = thread_index();
-  for (int idx = tid; idx < G * kD; idx += 256) {
+  if (po.out_bf16 != nullptr) {                 // block-uniform
+    for (int idx = tid; idx < G * kD; idx += NT) {
+      const int g = idx >> 7, dd = idx & (kD - 1);
+      float mm = kNeg;
+#pragma unroll
+      for (int st = 0; st < NS; ++st) mm = fmaxf(mm, smem[(st * G + g) * kPartStride]);
+      float oo = 0.f, ll = 0.f;
+#pragma unroll
+      for (int st = 0; st < NS; ++st) {
+        const float c = fast_exp2(smem[(st * G + g) * kPartStride] - mm);
+        oo = fmaf(smem[(st * G + g) * kPartStride + 4 + dd], c, oo);
+        ll = fmaf(smem[(st * G + g) * kPartStride + 1], c, ll);
+      }
+      po.out_bf16[idx] = f32_to_bf16_rne(ll > 0.f ? oo / ll : 0.f);
+    }
+    return;
+  }
+  for (int idx = tid; idx < G * kD; idx += NT) {
     const int g = idx >> 7, dd = idx & (kD - 1);
     float mm = kNeg;
 #pragma unroll
@@ -445,7 +464,8 @@ __device__ __forceinline__ void issue_step_loads(const RowMap& rm, int row0, int
 struct NoHook { __device__ __forceinline__ void operator()() const {} };
 
 // One tile of `tile_rows` logical rows (a multiple of 128).  The tile is cut into steps of 32 keys;
-// wave w takes steps w, w+4, w+8, ... and keeps one step of loads in flight ahead of its arithmetic.
+// wave w of the NW waves of the workgroup takes steps w, w+NW, w+2NW, ... and keeps one step of loads in
+// flight ahead of its arithmetic.
 // Scores S^T = K Q^T: the A operand is a K block piece (key-major), the B operand the query rows
 // (zero beyond G), so lane (q = lane % 16, j = lane / 16) ends with the scores of query head q for
 // the 8 rows of block j of the step -- which is exactly the B operand the second contraction
@@ -454,7 +474,7 @@ struct NoHook { __device__ __forceinline__ void operator()() const {} };
 // `sb` holds the operands in flight; with `preloaded` the caller has already issued this wave's first
 // step into it.  `between` runs after the last step's arithmetic and before the combination of the
 // waves, when `sb` is free again (a hook for callers that overlap something with the combination).
-template <int G, bool DYN, class Between = NoHook>
+template <int G, bool DYN, class Between = NoHook, int NW = 4>
 __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* __restrict__ q, float scale_log2e,
                                                int row0, int tile_rows, const PartOut& part, float* smem,
                                                StepBufs& sb, bool preloaded = false, Between between = Between()) {
@@ -491,7 +511,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
       s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[2 * s + 1]), qb[s], s1, 0, 0, 0);
     }
     // next step's addresses and K loads go out while this step's softmax and second contraction run
-    const int nst = st + 4;
+    const int nst = st + NW;
     const bool more = nst < n_steps;                     // wave-uniform
     uint32_t bv_next = 0;
     int nv_next = 0;
@@ -559,7 +579,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
           make_float4(o[db][0], o[db][1], o[db][2], o[db][3]);
   }
   lds_barrier();                       // staging is LDS only; loads for the next tile may be in flight
-  combine_streams_and_store<G, 4>(smem, part);
+  combine_streams_and_store<G, NW, NW * 64>(smem, part);
 }
 
 constexpr int kNhbBf16 = kTileBf16 / 128;
@@ -570,14 +590,14 @@ template <typename T, int G, bool BLOCKED> constexpr size_t attn_smem_bytes() {
 }
 template <typename T> __device__ __forceinline__ constexpr int tile_of() { return sizeof(T) == 2 ? kTileBf16 : kTileF32; }
 
-template <typename T, int G, bool BLOCKED>
+template <typename T, int G, bool BLOCKED, int NW = 4>
 __device__ __forceinline__ void run_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
                                          int tile_rows, const PartOut& part, float* smem) {
   if constexpr (sizeof(T) == 2 && BLOCKED) {
     StepBufs sb;
     sb.nv = 0;
-    if (rm.dynamic) attn_tile_mfma<G, true>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
-    else attn_tile_mfma<G, false>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
+    if (rm.dynamic) attn_tile_mfma<G, true, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
+    else attn_tile_mfma<G, false, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
   } else if constexpr (sizeof(T) == 2) {
     attn_tile_bf16<G, kNhbBf16, false>(rm, q, scale_log2e, row0, part, smem);   // row-major rows, never gathered
   } else {
@@ -647,17 +667,18 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ o0, const f
 // updated in place since nobody reads it; t_arg < 0 reads the device counter cnt_a[layer], the new
 // length goes to cnt_b, and a follow-up kernel publishes it once every reader is done.
 
-// Chunk scoring and chunk top-k of one dynamic unit; whole block (256 threads).
-template <typename T>
+// Chunk scoring and chunk top-k of one dynamic unit; whole block (NT threads).
+constexpr int kSelHeader = 256 + 16;       // words before the chunk scores: histogram, 2 broadcast words, scan area
+template <typename T, int NT = 256>
 __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const UnitDesc& d, int lrel,
                                                       const T* __restrict__ q, int use_stored_sigma, float* dsm,
                                                       int32_t* sel_lds = nullptr, bool to_memory = true) {
-  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = 256 / LPR;
+  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = NT / LPR;
   const int tid = thread_index();
   uint32_t* hist = reinterpret_cast<uint32_t*>(dsm);         // [256]
   uint32_t* bc = hist + 256;                                 // [2]
-  int* scan = reinterpret_cast<int*>(bc + 2);                // [6]
-  float* sig = dsm + 256 + 8;                                // [n_chunks rounded up to 4]
+  int* scan = reinterpret_cast<int*>(bc + 2);                // [NT / 64 + 1 <= 14]
+  float* sig = dsm + kSelHeader;                             // [n_chunks rounded up to 4]
   const int n_c = d.n_chunks;
   const int n_c4 = (n_c + 3) & ~3;
   unsigned long long* key64 = reinterpret_cast<unsigned long long*>(sig + n_c4);   // [n_c4], 8-byte aligned
@@ -739,7 +760,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     }
     }
   } else {
-    for (int ch = tid; ch < n_c; ch += 256) sig[ch] = cv.sigma[d.aux_off + ch];
+    for (int ch = tid; ch < n_c; ch += NT) sig[ch] = cv.sigma[d.aux_off + ch];
   }
   __syncthreads();
 
@@ -749,6 +770,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     // on wave-wide vote counts -- no barrier, no memory traffic; the four waves do the same arithmetic.
     // Chunks with a key above it are picked, those equal to it in chunk order up to the k-th place.
     const int lane = tid & 63, wv = tid >> 6;
+    if (NT > 256 && wv >= 4) return;                       // the first four waves cover all 256 chunks
     const int k = d.k_sel;
     uint32_t key[4];
 #pragma unroll
@@ -792,12 +814,12 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
   uint32_t T_key = 0;
   int r_adm = n_c;
   if (d.k_sel < n_c) {
-    radix_select<256>(n_c, d.k_sel,
-                      [&](int j, uint32_t& key) { key = float_order_key(sig[j]); return true; },
-                      hist, bc, T_key, r_adm);
+    radix_select<NT>(n_c, d.k_sel,
+                     [&](int j, uint32_t& key) { key = float_order_key(sig[j]); return true; },
+                     hist, bc, T_key, r_adm);
   }
   int base_eq = 0, base_keep = 0;
-  for (int ch0 = 0; ch0 < n_c; ch0 += 256) {
+  for (int ch0 = 0; ch0 < n_c; ch0 += NT) {
     const int ch = ch0 + tid;
     uint32_t key = 0;
     const bool in = ch < n_c;
@@ -805,9 +827,9 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     const int eq = (in && key == T_key) ? 1 : 0;
     const int gt = (in && key > T_key) ? 1 : 0;
     int tot_eq, tot_keep;
-    const int eq_rank = base_eq + block_exclusive_scan<256>(eq, scan, &tot_eq);
+    const int eq_rank = base_eq + block_exclusive_scan<NT>(eq, scan, &tot_eq);
     const int keep = gt | (eq & (eq_rank < r_adm ? 1 : 0));
-    const int pos = base_keep + block_exclusive_scan<256>(keep, scan, &tot_keep);
+    const int pos = base_keep + block_exclusive_scan<NT>(keep, scan, &tot_keep);
     if (keep && pos < d.k_sel) {
       if (to_memory) cv.sel[d.idx_off + pos] = ch;
       if (sel_lds) sel_lds[pos] = ch;
@@ -849,11 +871,14 @@ __device__ __forceinline__ void append_row(const CacheView& cv, const AttnItem& 
 }
 
 // One split-K tile of the hybrid cache: optional tail append, then attention, record -> workspace.
-template <typename T, int G>
+// NW: waves of the workgroup (bf16 matrix-core tile only).  out_rows (bf16 caches, a tile that covers its
+// whole unit): the unit's G output rows are written there and no record is made.
+template <typename T, int G, int NW = 4>
 __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnItem& it, int layer_begin, int slot_base,
                                                const T* __restrict__ q, const T* __restrict__ k_new,
                                                const T* __restrict__ v_new, const PartOut& partials, int t_arg,
-                                               int TILE, float* smem, const int32_t* sel_override = nullptr) {
+                                               int TILE, float* smem, const int32_t* sel_override = nullptr,
+                                               uint16_t* out_rows = nullptr) {
   constexpr int LPR = Elem<T>::kLanesPerRow;
   const int tid = threadIdx.x;
   const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
@@ -881,9 +906,9 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   rm.C = it.C;
   rm.tail_row = it.tail_row;
   const size_t qoff = (((size_t)lrel * cv.batch + it.seq) * cv.n_q_heads + (size_t)it.head * G) * kD;
-  const PartOut part = {partials.o + (size_t)(it.slot - slot_base) * G * kD,
-                        partials.ml + (size_t)(it.slot - slot_base) * kMlStride};
-  run_tile<T, G, true>(rm, q + qoff, cv.scale_log2e, it.row0, TILE, part, smem);
+  const PartOut part = {out_rows ? nullptr : partials.o + (size_t)(it.slot - slot_base) * G * kD,
+                        out_rows ? nullptr : partials.ml + (size_t)(it.slot - slot_base) * kMlStride, out_rows};
+  run_tile<T, G, true, NW>(rm, q + qoff, cv.scale_log2e, it.row0, TILE, part, smem);
 }
 
 // Combine the tiles [0, n_tiles) of one unit, whose records this block wrote itself, and write the G
@@ -992,6 +1017,38 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
   attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem, picks);
 }
 
+// One workgroup of kUnitWaves waves per unit (bf16 caches): chunk selection for a dynamic unit, then attention
+// over all rows of the unit as a single tile -- the waves share the 32-row steps and combine in shared
+// memory -- and the unit's output rows.  No records, no second launch: the shape for steps whose units
+// are few enough to give every unit a compute unit of its own.  grid = dynamic units of the call, then
+// static units.
+constexpr int kUnitWaves = 12;
+template <int G>
+__global__ __launch_bounds__(kUnitWaves * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void unit_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int static_begin,
+                 const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
+                 bf16_t* __restrict__ out, int t_arg, int lds_sel_off) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  const bool dyn = (int)blockIdx.x < n_dyn;                  // block-uniform
+  const UnitDesc d = dyn ? cv.dyn_descs[dyn_begin + blockIdx.x] : cv.static_descs[static_begin + ((int)blockIdx.x - n_dyn)];
+  const int lrel = d.layer - layer_begin;
+  const int32_t* picks = nullptr;
+  if (dyn) {
+    int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
+    select_chunks_of_unit<bf16_t, kUnitWaves * 64>(cv, d, lrel, q, 0, smem, sel_lds, true);
+    __syncthreads();                                         // the picks are in shared memory; the scratch is free
+    picks = sel_lds;
+  }
+  AttnItem it;
+  it.kv_row_off = d.kv_row_off; it.sel_off = (int32_t)d.idx_off; it.n_prompt_rows = d.n_prompt_rows;
+  it.C = d.C; it.c_log2 = d.c_log2; it.dynamic = dyn ? 1 : 0; it.layer = d.layer; it.seq = d.seq; it.head = d.head;
+  it.tail_row = d.tail_row; it.tail_off = d.tail_off; it.row0 = 0; it.slot = 0;
+  uint16_t* orow = reinterpret_cast<uint16_t*>(out) +
+                   (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G) * kD;
+  const PartOut none = {nullptr, nullptr, nullptr};
+  attention_item<bf16_t, G, kUnitWaves>(cv, it, layer_begin, 0, q, k_new, v_new, none, t_arg, kWholeUnit, smem, picks, orow);
+}
+
 // grid = n_units x G, block = 128 threads; descs points at the first unit's descriptor.
 template <typename T>
 __global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, const UnitDesc* __restrict__ descs,
@@ -1084,7 +1141,7 @@ __global__ __launch_bounds__(128) void full_merge_kernel(FullView fv, PartOut pa
 
 static size_t select_smem_bytes(int max_chunks) {
   const size_t n4 = ((size_t)max_chunks + 3) & ~(size_t)3;
-  return (256 + 8 + n4) * sizeof(float) + n4 * sizeof(unsigned long long);
+  return (kSelHeader + n4) * sizeof(float) + n4 * sizeof(unsigned long long);
 }
 
 template <typename T, int G>
@@ -1161,6 +1218,36 @@ hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin,
                                                                     n_sitems, slot_base, q, k_new, v_new, parts_o,
                                                                     parts_ml, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
   }
+  return hipErrorInvalidValue;
+}
+
+template <int G>
+static hipError_t launch_units_t(const CacheView& cv, int layer_begin, int dyn_begin, int n_dyn, int static_begin,
+                                 int n_static, const void* q, const void* k_new, const void* v_new, void* out, int t_arg,
+                                 int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  // selection scratch and the waves' staging area share the front; the picks sit behind both
+  const size_t front = std::max((size_t)kUnitWaves * G * kPartStride * sizeof(float), select_smem_bytes(max_chunks));
+  const size_t smem = front + (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t);
+  static size_t attr = 0;
+  if (smem > attr) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unit_kernel<G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr = smem;
+  }
+  HKV_LAUNCH((unit_kernel<G>), dim3(n_dyn + n_static), dim3(kUnitWaves * 64), (uint32_t)smem, st, ev0, ev1, cv, layer_begin,
+             dyn_begin, n_dyn, static_begin, (const bf16_t*)q, (const bf16_t*)k_new, (const bf16_t*)v_new, (bf16_t*)out,
+             t_arg, (int)(front / sizeof(float)));
+  return hipGetLastError();
+}
+
+hipError_t launch_units(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int static_begin,
+                        int n_static, const void* q, const void* k_new, const void* v_new, void* out, int t_arg,
+                        int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (dtype != HKV_BF16) return hipErrorInvalidValue;
+  if (n_dyn + n_static <= 0) return hipSuccess;
+  HKV_DISPATCH_G(cv.G, return (launch_units_t<GG>(cv, layer_begin, dyn_begin, n_dyn, static_begin, n_static, q, k_new,
+                                                  v_new, out, t_arg, max_chunks, st, ev0, ev1)));
   return hipErrorInvalidValue;
 }
 

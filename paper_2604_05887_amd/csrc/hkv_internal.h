@@ -120,6 +120,10 @@ hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin,
                                 const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
                                 int static_hold, int max_chunks, hipStream_t st, hipEvent_t ev0 = nullptr,
                                 hipEvent_t ev1 = nullptr);
+// One wide workgroup per unit, outputs written directly (bf16 caches only; no workspace, no merge).
+hipError_t launch_units(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int static_begin,
+                        int n_static, const void* q, const void* k_new, const void* v_new, void* out, int t_arg,
+                        int max_chunks, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* descs, int n_units, int layer_begin,
                              int layer_end, int slot_base, float* parts_o, float* parts_ml, void* out, int t_arg,
                              int appending, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);

@@ -259,11 +259,12 @@ def test_other_group_sizes_and_windows(n_q, n_kv, window):
     _say(f"G{n_q // n_kv} w{window}", stats)
 
 
-@pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
+@pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
 def test_both_decode_shapes_for_dynamic_heads(dtype_cfg, mode, tile):
     """Dynamic heads handled by one workgroup each (mode 1), by split-K tiles in a second launch
-    (mode 2) and by tiles that repeat the selection (mode 3) all match the oracle; bf16 (config 1 shape, heads spanning several tiles) and fp32
-    (config 0)."""
+    (mode 2), by tiles that repeat the selection (mode 3) and by one wide workgroup per head of either
+    kind (mode 4, bf16 only) all match the oracle; bf16 (config 1 shape, heads spanning several tiles)
+    and fp32 (config 0)."""
     if dtype_cfg == 1:
         wl = make_workload(1, n_layers=3, shrink=2, steps=4)
     else:
@@ -274,13 +275,17 @@ def test_both_decode_shapes_for_dynamic_heads(dtype_cfg, mode, tile):
 
 def test_decode_shape_is_reported_and_auto_rule():
     wl = make_workload(1, n_layers=2, shrink=4, steps=1)
-    for mode in (1, 2, 3):
+    for mode in (1, 2, 3, 4):
         dw = runner.setup(wl, decode_dynamic=mode, upload_prompt=False)
         assert dw.cache.decode_shape()[1] == mode
         dw.cache.close()
     dw = runner.setup(wl, upload_prompt=False)
     tile, mode = dw.cache.decode_shape()
-    assert tile in (256, 512, 1024) and mode == 3      # 32-token chunks: summaries are cheap to re-read
+    assert tile in (256, 512, 1024) and mode == 4      # heads of a few hundred rows: one wide workgroup each
+    dw.cache.close()
+    wl8k = make_workload(1, n_layers=2, steps=1, tensors=False)
+    dw = runner.setup(wl8k, upload_prompt=False)
+    assert dw.cache.decode_shape()[1] == 3             # long heads, 32-token chunks: summaries are cheap to re-read
     dw.cache.close()
     wl.chunk_size[:] = 8
     wl.budget[wl.head_type == 1] = 1024
@@ -307,7 +312,7 @@ def test_switching_the_decode_shape_on_a_live_cache():
     dw.cache.compress(dw.q_window, dw.k, dw.v)
     q = runner.to_device(wl.q_steps[0], wl.dtype)
     outs = []
-    for mode in (1, 2, 3):
+    for mode in (1, 2, 3, 4):
         dw.cache.set_decode_dynamic(mode)
         assert dw.cache.decode_shape()[1] == mode
         out = torch.empty((2, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
@@ -317,7 +322,13 @@ def test_switching_the_decode_shape_on_a_live_cache():
     for o in outs[1:]:
         assert (o - outs[0]).abs().max().item() <= 2e-2 * outs[0].abs().max().item()
     with pytest.raises(B.HkvError):
+        dw.cache.set_decode_dynamic(5)
+    dw.cache.close()
+    wl32 = make_workload(0, shrink=4, steps=1)           # the per-unit shape exists for bf16 caches only
+    dw = runner.setup(wl32, upload_prompt=False)
+    with pytest.raises(B.HkvError) as ei:
         dw.cache.set_decode_dynamic(4)
+    assert ei.value.status == B.HKV_ESHAPE
     dw.cache.close()
 
 
@@ -677,7 +688,7 @@ def test_degenerate_prompts_in_one_batch(dtype, chunks):
     finally:
         del W.CONFIGS[99]
     assert wl.seqlens.tolist() == [32, 45, 450, 153]
-    for mode in (1, 3):
+    for mode in (1, 3) + ((4,) if dtype == "bf16" else ()):
         stats = P.full_pipeline(wl, decode_dynamic=mode)
         _say(f"degenerate prompts {dtype} mode {mode}", stats)
 
@@ -694,3 +705,32 @@ def test_prompt_of_a_single_modality(modality):
     wl2.is_visual[:] = modality
     stats = P.full_pipeline(wl2)
     _say(f"single modality {modality} bf16", stats)
+
+
+# ---- one wide workgroup per head, no split-K (decode_dynamic = 4) ----
+
+@pytest.mark.parametrize("case", ["ragged", "g8", "small_chunks", "host_tier", "max_group", "layer_calls"])
+def test_one_workgroup_per_head_shape(case):
+    """The per-unit launch on the shapes that stress it: ragged batch with both chunk sizes, group of
+    eight, many small chunks (radix selection by 768 threads), host tier, the other group reading of the
+    chunk score, per-layer calls."""
+    kw = dict(decode_dynamic=4)
+    if case == "ragged":
+        wl = make_workload(4, n_layers=2, shrink=8, steps=3)
+    elif case == "g8":
+        wl = make_workload(3, n_layers=2, shrink=16, steps=3)
+    elif case == "small_chunks":
+        wl = make_workload(1, n_layers=2, steps=2)
+        wl.chunk_size[:] = 16
+        wl.budget[wl.head_type == O.DYNAMIC] = 16 * 300
+    elif case == "host_tier":
+        wl = make_workload(1, n_layers=2, shrink=2, steps=3)
+        kw["host_tier"] = True
+    elif case == "max_group":
+        wl = make_workload(1, n_layers=2, shrink=2, steps=3)
+        kw["chunk_score_group"] = 1
+    else:
+        wl = make_workload(1, n_layers=3, shrink=4, steps=3)
+        kw["layer_ranges"] = [(0, 1), (1, 2), (2, 3)]
+    stats = P.full_pipeline(wl, **kw)
+    _say(f"per-unit shape, {case}", stats)
