@@ -68,7 +68,7 @@ def main() -> int:
                     help="also time the head-classification scores (hkv_head_scores) on device-drawn prompt queries")
     ap.add_argument("--classify-layers", type=int, default=4, help="layers to run the classification on (0 = all)")
     ap.add_argument("--no-tune", action="store_true",
-                    help="keep the library's default way of running the dynamic heads instead of timing all three")
+                    help="keep the library's default way of running the dynamic heads instead of timing all of them")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read reference")
     ap.add_argument("--no-layerwise", action="store_true", help="skip the one-call-per-layer timing")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -219,7 +219,7 @@ def main() -> int:
         for i in range(preroll):
             raw_step(dw, i)
 
-    # ---- how the dynamic heads run: time the three shapes on this workload, keep the fastest (setup) ----
+    # ---- how the dynamic heads run: time the shapes on this workload, keep the fastest (setup) ----
     tuned_us = None
     if args.dynamic_mode == 0 and not args.no_tune:
         def probe_step(dw, i):

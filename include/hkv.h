@@ -258,8 +258,9 @@ HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end
  * hkv_profile_read waits for the stream of the profiled calls, returns
  * the summed durations in milliseconds -- ms[0] main launch (chunk scoring and chunk top-k of the
  * dynamic heads together with the split-K attention of the static heads; in dynamic modes 1 and 3
- * also the dynamic heads' attention), ms[1] second launch (split-K attention of the dynamic heads,
- * dynamic mode 2 only), ms[2] combination of the split-K tiles -- and the number of calls summed,
+ * also the dynamic heads' attention; in mode 4 the whole step), ms[1] second launch (split-K
+ * attention of the dynamic heads, dynamic mode 2 only), ms[2] combination of the split-K tiles (none
+ * in mode 4) -- and the number of calls summed,
  * then starts over.
  * hkv_profile_disable releases the events. */
 HKV_API int hkv_profile_enable(hkv_cache* cache, int max_calls);

@@ -1,15 +1,19 @@
 // Decode-step kernels of libhkv (gfx950):
-//   decode_kernel    one launch for the whole step.  A block either owns a dynamic head: it scores all
-//                    chunk summaries with the group-summed query, picks the top-k chunks (paper,
-//                    Appendix A, "KV Cache Retrieval for Dynamic Heads"), attends the gathered rows tile
-//                    by tile and combines its own tiles into the output rows; or it owns one split-K
-//                    tile of a static head's compacted rows and leaves a record in the workspace
-//   attn_merge       log-sum-exp combination of the static heads' tiles in fixed order, cast to the
-//                    output dtype
-//   full_attn_kernel the same attention over caller-held, uncompressed K/V (comparison kernel)
+//   decode_kernel         a block either owns a dynamic head: it scores all chunk summaries with the
+//                         group-summed query, picks the top-k chunks (paper, Appendix A, "KV Cache
+//                         Retrieval for Dynamic Heads"), attends the gathered rows and combines its own
+//                         tiles into the output rows (or stops after the selection); or it owns one
+//                         split-K tile of a static head's compacted rows and leaves a record in the
+//                         workspace
+//   dynamic_tiles_kernel  split-K tiles of the dynamic heads (each repeating its head's selection when
+//                         asked to), with the static heads' tiles in the same grid: the whole step in
+//                         one launch
+//   unit_kernel           one wide workgroup per head, selection to output rows, no records (short heads)
+//   attn_merge_kernel     log-sum-exp combination of the tiles in fixed order, cast to the output dtype
+//   full_attn_kernel      the same attention over caller-held, uncompressed K/V (comparison kernel)
 // The step's new K/V row is appended by the attention block whose tile contains it.
 //
-// All three are short kernels on small inputs, so their structure is driven by memory latency as
+// All of them are short kernels on small inputs, so their structure is driven by memory latency as
 // much as by bandwidth: descriptors come in through scalar loads, every thread issues its global
 // loads in independent batches, and nothing walks a dependent chain longer than it must.
 #include "hkv_device.h"
