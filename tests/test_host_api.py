@@ -185,3 +185,47 @@ def test_host_tier_sizes_move_exactly_the_dynamic_prompt_rows(lib):
     with pytest.raises(B.HkvError) as ei:
         B.hkv_cache_create_tiered(cfg, plan, None, dev1, None, host1)
     assert ei.value.status == B.HKV_EINVAL
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(lib, tmp_path):
+    """include/hkv.h compiles as C11 with gcc, and a C program linked against libhkv.so can size a
+    cache (host-only entry points; no kernel runs)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi_check.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "hkv.h"
+int main(void) {
+  hkv_config cfg;
+  memset(&cfg, 0, sizeof cfg);
+  cfg.struct_size = (uint32_t)sizeof cfg; cfg.abi_version = HKV_ABI_VERSION;
+  cfg.n_layers = 1; cfg.n_q_heads = 8; cfg.n_kv_heads = 2; cfg.head_dim = 128; cfg.dtype = HKV_BF16;
+  cfg.window = 16; cfg.chunk_size = 8; cfg.max_new_tokens = 4;
+  int32_t cu[2] = {0, 64};
+  uint8_t vis[64]; for (int i = 0; i < 64; ++i) vis[i] = (uint8_t)(i >= 8 && i < 40);
+  uint8_t types[2] = {HKV_STATIC, HKV_DYNAMIC};
+  int32_t budget[2] = {32, 16};
+  hkv_plan plan; memset(&plan, 0, sizeof plan);
+  plan.batch = 1; plan.cu_seqlens = cu; plan.is_visual = vis; plan.head_type = types; plan.budget = budget;
+  size_t cache = 0, ws = 0, host = 0;
+  int rc = hkv_query_sizes(&cfg, &plan, &cache, &ws);
+  if (rc != HKV_OK || cache == 0 || ws == 0) { printf("query failed: %s\n", hkv_strerror(rc)); return 1; }
+  rc = hkv_query_tier_sizes(&cfg, &plan, &cache, &host, &ws);
+  if (rc != HKV_OK || host == 0) return 2;
+  cfg.head_dim = 64;
+  if (hkv_query_sizes(&cfg, &plan, &cache, &ws) != HKV_ESHAPE) return 3;
+  printf("abi %u ok\n", hkv_abi_version());
+  return 0;
+}
+''')
+    exe = tmp_path / "abi_check"
+    libdir = os.path.join(ROOT, "paper_2604_05887_amd")
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:libhkv.so", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"],
+                   check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert out.strip() == f"abi {B.HKV_ABI_VERSION} ok"
