@@ -24,7 +24,7 @@ int validate_config(const hkv_config* cfg) {
   if (cfg->max_new_tokens < 0) return HKV_ESHAPE;
   if (cfg->decode_tile_rows != 0) {
     const int t = cfg->decode_tile_rows;
-    if (cfg->dtype != HKV_BF16 || (t != 128 && t != 256 && t != 512 && t != 1024)) return HKV_ESHAPE;
+    if (cfg->dtype != HKV_BF16 || t < 128 || t > 4096 || t % 32 != 0) return HKV_ESHAPE;
   }
   if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 4) return HKV_EINVAL;
   if (cfg->decode_dynamic == 4 && cfg->dtype != HKV_BF16) return HKV_ESHAPE;   // the per-unit shape is bf16 only

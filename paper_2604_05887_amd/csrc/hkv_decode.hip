@@ -467,7 +467,7 @@ __device__ __forceinline__ void issue_step_loads(const RowMap& rm, int row0, int
 
 struct NoHook { __device__ __forceinline__ void operator()() const {} };
 
-// One tile of `tile_rows` logical rows (a multiple of 128).  The tile is cut into steps of 32 keys;
+// One tile of `tile_rows` logical rows (a multiple of 32).  The tile is cut into steps of 32 keys;
 // wave w of the NW waves of the workgroup takes steps w, w+NW, w+2NW, ... and keeps one step of loads in
 // flight ahead of its arithmetic.
 // Scores S^T = K Q^T: the A operand is a K block piece (key-major), the B operand the query rows

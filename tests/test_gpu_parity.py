@@ -259,7 +259,7 @@ def test_other_group_sizes_and_windows(n_q, n_kv, window):
     _say(f"G{n_q // n_kv} w{window}", stats)
 
 
-@pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
+@pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 3, 160), (1, 2, 288), (1, 1, 416), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
 def test_both_decode_shapes_for_dynamic_heads(dtype_cfg, mode, tile):
     """Dynamic heads handled by one workgroup each (mode 1), by split-K tiles in a second launch
     (mode 2), by tiles that repeat the selection (mode 3) and by one wide workgroup per head of either

@@ -56,6 +56,9 @@ def test_argument_errors_are_reported_on_the_host(lib):
 
     assert status(_cfg(head_dim=64), _plan(wl)) == B.HKV_ESHAPE
     assert status(_cfg(chunk_score_group=2), _plan(wl)) == B.HKV_EINVAL
+    assert status(_cfg(dtype=B.HKV_BF16, decode_tile_rows=100), _plan(wl)) == B.HKV_ESHAPE    # not a multiple of 32
+    assert status(_cfg(dtype=B.HKV_BF16, decode_tile_rows=96), _plan(wl)) == B.HKV_ESHAPE     # below 128
+    assert status(_cfg(decode_tile_rows=256), _plan(wl)) == B.HKV_ESHAPE                      # fp32 tiles are fixed
     assert status(_cfg(n_q_heads=36), _plan(wl)) == B.HKV_ESHAPE          # group of 9
     assert status(_cfg(n_q_heads=30), _plan(wl)) == B.HKV_ESHAPE          # not divisible
     assert status(_cfg(window=64), _plan(wl)) == B.HKV_ESHAPE             # G * w > 256
