@@ -734,3 +734,30 @@ def test_one_workgroup_per_head_shape(case):
         kw["layer_ranges"] = [(0, 1), (1, 2), (2, 3)]
     stats = P.full_pipeline(wl, **kw)
     _say(f"per-unit shape, {case}", stats)
+
+
+# ---- the larger shapes at their full context length (a few layers; the oracle checks a sampled layer) ----
+
+@pytest.mark.parametrize("cfg_id,n_layers,steps,tile", [(2, 2, 3, 1024), (3, 2, 2, 1024), (2, 1, 2, 0)])
+def test_full_context_of_the_larger_shapes(cfg_id, n_layers, steps, tile):
+    """Config 2 (four 32768-token multi-image prompts, 64-token chunks, decode queries near chunk
+    centroids) and config 3 (72B attention shape, one 51200-token video prompt, group of eight) at their
+    real per-head sizes: hundreds of chunks per head, and the 1024-row tiles that caches of all their
+    layers pick (a cache of two layers would stay at 256 rows)."""
+    wl = make_workload(cfg_id, n_layers=n_layers, steps=steps)
+    assert int(wl.seqlens.max()) == (32768 if cfg_id == 2 else 51200)
+    layers = [n_layers - 1]
+    dw = runner.setup(wl, decode_tile_rows=tile)
+    tile_used, mode = dw.cache.decode_shape()
+    print(f"\n[cfg{cfg_id} full context] tile {tile_used} mode {mode}", flush=True)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    torch.cuda.synchronize()
+    ocfg, oplan = P.oracle_setup(wl)
+    ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers)
+    stats = {}
+    overrides = P.compare_compress(wl, dw, ocache, stats)
+    if overrides:
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers, keep_override=overrides)
+    P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers)
+    _say(f"cfg{cfg_id} full context", stats)
+    dw.cache.close()
