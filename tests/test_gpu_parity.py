@@ -761,3 +761,12 @@ def test_full_context_of_the_larger_shapes(cfg_id, n_layers, steps, tile):
     P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers)
     _say(f"cfg{cfg_id} full context", stats)
     dw.cache.close()
+
+
+def test_serving_mix_at_full_context_lengths():
+    """Config 4 with its real ragged lengths (16 sequences of 4096 to 40960 tokens, both chunk sizes,
+    per-sequence budgets), one layer, every unit checked."""
+    wl = make_workload(4, n_layers=1, steps=2)
+    assert wl.batch == 16 and int(wl.seqlens.max()) > 30000
+    stats = P.full_pipeline(wl, decode_tile_rows=1024)
+    _say("cfg4 full lengths L1", stats)
