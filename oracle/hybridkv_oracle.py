@@ -49,6 +49,9 @@ gives 1, a one-hot row gives 1), by a sort-based restatement on random inputs
 and by hand-worked rational softmax rows; the budget equations by their printed
 invariants (type budgets add up to the total, r = 1 and equal scores give the
 uniform split, every ceiling is at most one token above its argument).
+The indexed-generation variant of decode_attn is pinned by its reductions (no complete
+chunk: the plain reading; room for every chunk: library softmax attention over everything)
+and a hand-built retrieval case.
 cumulative_focus is pinned by a hand-worked case, by the argmax histogram for
 k = 1, by a library top-k on the logits, and by its count invariants.
 """
@@ -355,6 +358,7 @@ class OracleConfig:
     score_causal: bool = False
     softmax_scale: float = 0.0      # 0 -> 1/sqrt(head_dim)
     chunk_score_group: str = "sum"  # how the G query heads of a group score a chunk: "sum" or "max"
+    index_generated: bool = False   # dynamic heads: generated tokens are chunked and retrieved like the prompt
 
     @property
     def scale(self) -> float:
@@ -387,7 +391,9 @@ class OracleUnit:
     # dynamic
     c: int = 0
     k_sel: int = 0
+    k_cap: int = 0                       # budget // c before it is capped by the number of chunks
     mu: Optional[np.ndarray] = None
+    mu_gen: List[np.ndarray] = field(default_factory=list)   # index_generated: means of the complete chunks of generated tokens
     # rows the head attends: static -> compacted rows; dynamic -> the full prompt
     K: Optional[np.ndarray] = None
     V: Optional[np.ndarray] = None
@@ -436,6 +442,7 @@ def compress(cfg: OracleConfig, plan: OraclePlan, q_window: np.ndarray, k: np.nd
                     mu = chunk_means(kk, c, cfg.dtype)
                     units[(b, l, h)] = OracleUnit(kind=DYNAMIC, C=C, c=c, mu=mu,
                                                   k_sel=n_selected_chunks(budget, c, mu.shape[0]),
+                                                  k_cap=max(1, budget // c),
                                                   K=kk, V=vv)
     return OracleCache(cfg=cfg, plan=plan, units=units)
 
@@ -449,6 +456,12 @@ def decode_attn(cache: OracleCache, q: np.ndarray, k_new: Optional[np.ndarray], 
     New tokens are appended uncompressed to every head's tail and always attended.
     Static heads attend their kept rows + tail; dynamic heads score chunks, pick
     the top ones and attend those chunks' rows + tail.
+    cfg.index_generated (a variant for long generations; the paper generates little and
+    says nothing of it): on dynamic heads the generated tokens are cut into chunks of c in
+    order of generation; a chunk that was complete before the step carries the mean of its
+    keys as metadata (same rounding as the prompt's) and competes with the prompt's chunks
+    for the budget // c places (capped by the number of chunks there are); the incomplete
+    rest and the step's own token are always attended.  Static heads are unchanged.
     Returns (out [L, B, Hq, d] float64, info) where info[(b,l,h)] holds sigma/sel
     for dynamic units.
     """
@@ -461,26 +474,45 @@ def decode_attn(cache: OracleCache, q: np.ndarray, k_new: Optional[np.ndarray], 
         for l in layers:
             for h in range(cfg.n_kv_heads):
                 u = cache.units[(b, l, h)]
+                t_before = len(u.K_tail)
                 if k_new is not None:
                     u.K_tail.append(np.asarray(k_new[l, b, h, :], dtype=np.float64))
                     u.V_tail.append(np.asarray(v_new[l, b, h, :], dtype=np.float64))
                 qh = np.asarray(q[l, b, h * G:(h + 1) * G, :], dtype=np.float64)
+                tail_from = 0                       # first tail row that is attended unconditionally
                 if u.kind == STATIC:
                     K_rows, V_rows = u.K, u.V
                 else:
                     mu = u.mu
+                    n_gen = 0
+                    if cfg.index_generated:
+                        # the generated tokens present before this step, in chunks of c in order of generation;
+                        # complete chunks compete with the prompt's chunks, the incomplete rest is always attended
+                        n_gen = t_before // u.c
+                        if n_gen:
+                            mu = np.concatenate([mu, np.stack(u.mu_gen[:n_gen])], axis=0)
+                        tail_from = n_gen * u.c
                     if mu_override is not None and (b, l, h) in mu_override:
                         mu = np.asarray(mu_override[(b, l, h)], dtype=np.float64)
                     sigma = chunk_scores(qh, mu, cfg.chunk_score_group)
-                    sel = select_chunks(sigma, u.k_sel)
+                    k_step = min(u.k_cap, mu.shape[0]) if cfg.index_generated else u.k_sel
+                    sel = select_chunks(sigma, k_step)
                     if sel_override is not None and (b, l, h) in sel_override:
                         sel = np.asarray(sel_override[(b, l, h)], dtype=np.int64)
-                    rows = chunk_rows(sel, u.c, u.C)
+                    n_c = u.mu.shape[0]
+                    rows = chunk_rows(sel[sel < n_c], u.c, u.C)
                     K_rows, V_rows = u.K[rows], u.V[rows]
+                    for g in sel[sel >= n_c] - n_c:                  # selected chunks of generated tokens
+                        K_rows = np.concatenate([K_rows, np.stack(u.K_tail[g * u.c:(g + 1) * u.c])], axis=0)
+                        V_rows = np.concatenate([V_rows, np.stack(u.V_tail[g * u.c:(g + 1) * u.c])], axis=0)
                     info[(b, l, h)] = dict(sigma=sigma, sel=sel)
-                if u.K_tail:
-                    K_rows = np.concatenate([K_rows, np.stack(u.K_tail)], axis=0)
-                    V_rows = np.concatenate([V_rows, np.stack(u.V_tail)], axis=0)
+                    if cfg.index_generated and k_new is not None and len(u.K_tail) % u.c == 0:
+                        # this step's token completes a chunk: its metadata joins the index for the next step
+                        done = np.stack(u.K_tail[-u.c:])
+                        u.mu_gen.append(round_to_dtype(done.sum(axis=0) / u.c, cfg.dtype))
+                if len(u.K_tail) > tail_from:
+                    K_rows = np.concatenate([K_rows, np.stack(u.K_tail[tail_from:])], axis=0)
+                    V_rows = np.concatenate([V_rows, np.stack(u.V_tail[tail_from:])], axis=0)
                 out[l, b, h * G:(h + 1) * G, :] = attention(qh, K_rows, V_rows, cfg.scale)
     return out, info
 

@@ -506,3 +506,84 @@ def test_cumulative_focus_hand_case_and_invariants():
     assert sorted(set(Fs.tolist())) == [0, 30] and (Fs == 30).sum() == 4
     # the scale does not change the ranking
     np.testing.assert_array_equal(O.cumulative_focus(qq, kk, 1.0, 7), F7)
+
+
+# ---------------------------------------------------------------- generated tokens in the chunk index (variant)
+def _indexed_cfg_plan(wl, budget=None, chunk=None):
+    cfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                         head_dim=wl.head_dim, window=wl.window, dtype=wl.dtype, index_generated=True)
+    plan = O.OraclePlan(cu_seqlens=wl.cu_seqlens, head_type=wl.head_type,
+                        budget=wl.budget if budget is None else budget,
+                        chunk_size=wl.chunk_size if chunk is None else chunk)
+    return cfg, plan
+
+
+def test_indexed_generation_equals_the_plain_reading_until_a_chunk_is_complete():
+    """With fewer generated tokens than one chunk nothing is indexed yet: same picks, same outputs."""
+    wl = make_workload(0, shrink=4, steps=6)                     # chunk 32 > 6 steps
+    plain = O.compress(*_cfg_plan(wl), wl.q_window, wl.k, wl.v, wl.is_visual)
+    indexed = O.compress(*_indexed_cfg_plan(wl), wl.q_window, wl.k, wl.v, wl.is_visual)
+    for s in range(wl.steps):
+        a, ia = O.decode_attn(plain, wl.q_steps[s], wl.k_new[s], wl.v_new[s])
+        b, ib = O.decode_attn(indexed, wl.q_steps[s], wl.k_new[s], wl.v_new[s])
+        np.testing.assert_array_equal(a, b)
+        for key in ia:
+            np.testing.assert_array_equal(ia[key]["sel"], ib[key]["sel"])
+
+
+def test_indexed_generation_with_room_for_every_chunk_is_full_attention():
+    """A budget that takes every chunk, the generated ones included, must reproduce plain softmax
+    attention over the prompt and all generated tokens at every step (library check), while the
+    plain reading with the same budget does so too -- the two differ only when chunks are left out."""
+    wl = make_workload(0, shrink=4, steps=20)
+    chunk = np.full_like(wl.chunk_size, 4)                       # 20 steps complete five chunks
+    full = np.full_like(wl.budget, int(wl.seqlens[0]) + 4096)
+    cache = O.compress(*_indexed_cfg_plan(wl, full, chunk), wl.q_window, wl.k, wl.v, wl.is_visual)
+    G = cache.cfg.group
+    dyn = [h for h in range(4) if cache.units[(0, 0, h)].kind == O.DYNAMIC]
+    assert dyn
+    Ks = {h: [wl.k[0, :, h].astype(np.float64)] for h in dyn}
+    Vs = {h: [wl.v[0, :, h].astype(np.float64)] for h in dyn}
+    for s in range(wl.steps):
+        out, info = O.decode_attn(cache, wl.q_steps[s], wl.k_new[s], wl.v_new[s])
+        for h in dyn:
+            Ks[h].append(wl.k_new[s][0, 0, h][None].astype(np.float64))
+            Vs[h].append(wl.v_new[s][0, 0, h][None].astype(np.float64))
+            ref = _sdpa_f64(wl.q_steps[s][0, 0, h * G:(h + 1) * G], np.concatenate(Ks[h]), np.concatenate(Vs[h]),
+                            cache.cfg.scale)
+            np.testing.assert_allclose(out[0, 0, h * G:(h + 1) * G], ref, rtol=1e-11, atol=1e-13)
+            n_c = cache.units[(0, 0, h)].mu.shape[0]
+            assert info[(0, 0, h)]["sel"].tolist() == list(range(n_c + s // 4))      # s tokens before this step
+
+
+def test_indexed_generation_retrieves_a_generated_chunk_and_drops_the_others():
+    """One dynamic head, chunk 4, one chunk per step.  The generated keys of steps 0-3 point along e0,
+    those of steps 4-7 along e1, the prompt keys are small.  A query along e0 at step 9 must pick the
+    first generated chunk (id n_c), attend its four rows, the incomplete rest (token 8) and the new
+    token -- and nothing of the second generated chunk."""
+    rng = np.random.default_rng(2)
+    C, d, c = 16, 8, 4
+    cfg = O.OracleConfig(n_layers=1, n_q_heads=1, n_kv_heads=1, head_dim=d, window=4, dtype="f32",
+                         index_generated=True)
+    plan = O.OraclePlan(cu_seqlens=np.array([0, C], np.int32), head_type=np.array([[[O.DYNAMIC]]], np.uint8),
+                        budget=np.array([[[c]]], np.int32), chunk_size=np.array([c], np.int32))
+    k = (0.01 * rng.standard_normal((1, C, 1, d))).astype(np.float32)
+    v = rng.standard_normal((1, C, 1, d)).astype(np.float32)
+    qw = rng.standard_normal((1, 1, 4, 1, d)).astype(np.float32)
+    cache = O.compress(cfg, plan, qw, k, v, np.zeros(C, np.uint8))
+    u = cache.units[(0, 0, 0)]
+    assert u.k_sel == 1 and u.mu.shape[0] == 4
+    e = np.eye(d, dtype=np.float32)
+    kn = [3 * e[0] if s < 4 else 3 * e[1] if s < 8 else 0.01 * e[2] for s in range(10)]
+    vn = [np.full(d, float(s), np.float32) for s in range(10)]
+    q = (5 * e[0])[None, None, None, :]
+    for s in range(10):
+        out, info = O.decode_attn(cache, q, kn[s][None, None, None, :], vn[s][None, None, None, :])
+    assert info[(0, 0, 0)]["sel"].tolist() == [4]                 # the first generated chunk
+    assert len(u.mu_gen) == 2
+    np.testing.assert_allclose(u.mu_gen[0], 3 * e[0], rtol=1e-6)
+    rows_k = np.stack(kn[0:4] + kn[8:10]).astype(np.float64)
+    rows_v = np.stack(vn[0:4] + vn[8:10]).astype(np.float64)
+    ref = _sdpa_f64(q[0, 0], rows_k, rows_v, cfg.scale)
+    np.testing.assert_allclose(out[0, 0], ref, rtol=1e-12)
+    assert abs(out[0, 0, 0, 0] - 1.5) < 0.05                      # mostly the values 0..3 of the retrieved chunk
