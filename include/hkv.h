@@ -114,6 +114,18 @@ typedef struct {
                                query vector per head and does not treat grouped heads): 0 = the inner
                                product of the chunk summary with the SUM of the group's query vectors;
                                1 = the LARGEST of the group's inner products with the chunk summary */
+  int32_t index_generated;  /* 0: tokens generated during decoding are kept uncompressed and every head
+                               attends all of them (the paper generates at most a few hundred).
+                               1 (bf16 caches, decode_dynamic 0, 1 or 4; else HKV_ESHAPE): a variant for
+                               long generations.  On dynamic heads the generated tokens are cut into
+                               chunks of the head's chunk size in order of generation; a chunk that was
+                               complete before the step has the mean of its keys as its summary and
+                               competes with the prompt's chunks for the budget / chunk places (now
+                               capped by the chunks there are, generated ones included); the rest of
+                               the tail and the step's own token are always attended.  Static heads
+                               are not affected.  hkv_cache_export then reports the summaries (and
+                               the last step's scores and picks, whose trailing entries may predate
+                               that step) of prompt and generated chunks together, prompt first. */
 } hkv_config;
 
 /* Per-prompt plan.  All arrays live in HOST memory and are only read during the call. */

@@ -44,7 +44,7 @@ class hkv_config(C.Structure):
                 ("dtype", C.c_int32), ("window", C.c_int32), ("chunk_size", C.c_int32),
                 ("score_causal", C.c_int32), ("max_new_tokens", C.c_int32), ("softmax_scale", C.c_float),
                 ("decode_tile_rows", C.c_int32), ("decode_dynamic", C.c_int32),
-                ("chunk_score_group", C.c_int32)]
+                ("chunk_score_group", C.c_int32), ("index_generated", C.c_int32)]
 
 
 class hkv_plan(C.Structure):
@@ -134,10 +134,10 @@ def _stream(stream) -> Optional[int]:
 def make_config(*, n_layers: int, n_q_heads: int, n_kv_heads: int, dtype: int, window: int, chunk_size: int = 32,
                 max_new_tokens: int = 0, head_dim: int = 128, score_causal: int = 0,
                 softmax_scale: float = 0.0, decode_tile_rows: int = 0, decode_dynamic: int = 0,
-                chunk_score_group: int = 0) -> hkv_config:
+                chunk_score_group: int = 0, index_generated: int = 0) -> hkv_config:
     return hkv_config(C.sizeof(hkv_config), HKV_ABI_VERSION, n_layers, n_q_heads, n_kv_heads, head_dim, dtype,
                       window, chunk_size, score_causal, max_new_tokens, softmax_scale, decode_tile_rows, decode_dynamic,
-                      chunk_score_group)
+                      chunk_score_group, index_generated)
 
 
 class PlanArrays:

@@ -29,6 +29,11 @@ int validate_config(const hkv_config* cfg) {
   if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 4) return HKV_EINVAL;
   if (cfg->decode_dynamic == 4 && cfg->dtype != HKV_BF16) return HKV_ESHAPE;   // the per-unit shape is bf16 only
   if (cfg->chunk_score_group != 0 && cfg->chunk_score_group != 1) return HKV_EINVAL;
+  if (cfg->index_generated != 0 && cfg->index_generated != 1) return HKV_EINVAL;
+  if (cfg->index_generated) {               // bf16 caches, and only the shapes in which one workgroup owns a dynamic head
+    if (cfg->dtype != HKV_BF16) return HKV_ESHAPE;
+    if (cfg->decode_dynamic == 2 || cfg->decode_dynamic == 3) return HKV_ESHAPE;
+  }
   if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
   return HKV_OK;
 }
@@ -148,13 +153,15 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
           int lg = 0; while ((1 << lg) < c) ++lg;
           d.c_log2 = lg;
           d.n_chunks = (C + c - 1) / c;
-          d.k_sel = (int32_t)std::min<int64_t>(std::max<int64_t>(1, budget / c), d.n_chunks);
+          // caches that index their generated tokens keep room for the chunks generation can complete
+          const int max_gen = cfg->index_generated ? cfg->max_new_tokens / c : 0;
+          d.k_sel = (int32_t)std::min<int64_t>(std::max<int64_t>(1, budget / c), d.n_chunks + max_gen);
           d.n_prompt_rows = d.k_sel * c;
-          d.aux_off = lo.n_sigma; lo.n_sigma += d.n_chunks;
+          d.aux_off = lo.n_sigma; lo.n_sigma += d.n_chunks + max_gen;
           d.idx_off = lo.n_sel; lo.n_sel += d.k_sel;
           d.type_ord = (int32_t)lo.dynamic_units.size();
           lo.dynamic_units.push_back(u);
-          lo.max_chunks = std::max(lo.max_chunks, d.n_chunks);
+          lo.max_chunks = std::max(lo.max_chunks, d.n_chunks + max_gen);
           lo.max_rows_dynamic = std::max(lo.max_rows_dynamic, d.n_prompt_rows + cfg->max_new_tokens);
           if (blocked && c < kBlkRows) return HKV_ESHAPE;     // bf16 caches gather whole 8-row blocks
           phys_rows = blocked ? (C + kBlkRows - 1) / kBlkRows * kBlkRows : C;
@@ -272,6 +279,8 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
   }
   if (rc != HKV_OK) return rc;
   if (cfg->decode_dynamic != 0) lo.mode = cfg->decode_dynamic;
+  else if (cfg->index_generated)       // one workgroup per dynamic head: wide for short heads, else inside the main launch
+    lo.mode = std::max(lo.max_rows_static + cfg->max_new_tokens, lo.max_rows_dynamic) <= kUnitShapeMaxRows ? 4 : 1;
   else if (cfg->dtype == HKV_BF16 &&
            std::max(lo.max_rows_static + cfg->max_new_tokens, lo.max_rows_dynamic) <= kUnitShapeMaxRows)
     lo.mode = 4;         // short heads: one wide workgroup each beats split-K plus the combination launch
@@ -400,6 +409,7 @@ static int create_cache(const hkv_config* cfg, const hkv_plan* plan, void* cache
   cv.causal = cfg->score_causal;
   cv.tile_rows = lo.tile;
   cv.sigma_max = cfg->chunk_score_group;
+  cv.index_gen = cfg->index_generated;
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   cv.scale_log2e = scale * 1.4426950408889634f;
 
@@ -566,6 +576,10 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   const int dt = c->cfg.dtype, app = k_new ? 1 : 0;
   const int mode = lo.mode;
   const int resident = 3 * c->n_cus;      // workgroups resident at once (three per compute unit)
+  if (c->cfg.chunk_score_group == 1) {    // the other group reading scores the chunks in a launch of its own
+    e = launch_chunk_score_max(c->cv, dt, lb, db, nd, q, t_before, st);
+    if (e != hipSuccess) return HKV_EHIP;
+  }
   if (mode == 4) {
     // one wide workgroup per unit writes the unit's output rows itself: no records, no combination
     e = launch_units(c->cv, dt, lb, db, nd, sub, nsu, q, k_new, v_new, out, t_before, lo.max_chunks, st, ev[0], ev[1]);
@@ -740,7 +754,13 @@ int hkv_cache_step_bytes(const hkv_cache* c, int lb, int le, int tail, uint64_t*
     else {
       // selected chunks' actual rows: k*c, minus what the short last chunk lacks cannot be known on
       // the host (it depends on the selection), so the nominal k*c is used
-      tot += (uint64_t)d.n_chunks * R + 2 * R * (uint64_t)(d.n_prompt_rows + tail);
+      if (c->cfg.index_generated) {      // complete chunks of generated tokens are scored and may be among the picks
+        const int cs = 1 << d.c_log2, n_gen = tail / cs;
+        const int k_now = std::min(d.k_sel, d.n_chunks + n_gen);
+        tot += (uint64_t)(d.n_chunks + n_gen) * R + 2 * R * (uint64_t)(k_now * cs + tail % cs);
+      } else {
+        tot += (uint64_t)d.n_chunks * R + 2 * R * (uint64_t)(d.n_prompt_rows + tail);
+      }
     }
   }
   *bytes = tot;
@@ -751,6 +771,8 @@ static int locate(const hkv_cache* c, int what, const UnitDesc* d, size_t& off, 
   const size_t es = elem_size(c->cfg.dtype);
   const Layout& lo = c->lo;
   const int tail = c->host_tail[d->layer];
+  // chunks the unit has now: the prompt's, and with indexed generation the complete chunks of its tail
+  const int n_chunks_now = d->n_chunks + (c->cfg.index_generated && d->kind == HKV_DYNAMIC ? tail >> d->c_log2 : 0);
   switch (what) {
     case HKV_X_KEPT_IDX:
       if (d->kind != HKV_STATIC) return HKV_EINVAL;
@@ -760,13 +782,13 @@ static int locate(const hkv_cache* c, int what, const UnitDesc* d, size_t& off, 
       off = lo.off_scores + (size_t)d->aux_off * 4; bytes = (size_t)d->C * 4; return HKV_OK;
     case HKV_X_CHUNK_SEL:
       if (d->kind != HKV_DYNAMIC) return HKV_EINVAL;
-      off = lo.off_sel + (size_t)d->idx_off * 4; bytes = (size_t)d->k_sel * 4; return HKV_OK;
+      off = lo.off_sel + (size_t)d->idx_off * 4; bytes = (size_t)std::min(d->k_sel, n_chunks_now) * 4; return HKV_OK;
     case HKV_X_CHUNK_SIGMA:
       if (d->kind != HKV_DYNAMIC) return HKV_EINVAL;
-      off = lo.off_sigma + (size_t)d->aux_off * 4; bytes = (size_t)d->n_chunks * 4; return HKV_OK;
+      off = lo.off_sigma + (size_t)d->aux_off * 4; bytes = (size_t)n_chunks_now * 4; return HKV_OK;
     case HKV_X_CHUNK_MEAN:
       if (d->kind != HKV_DYNAMIC) return HKV_EINVAL;
-      off = lo.off_mu + (size_t)d->aux_off * kD * es; bytes = (size_t)d->n_chunks * kD * es; return HKV_OK;
+      off = lo.off_mu + (size_t)d->aux_off * kD * es; bytes = (size_t)n_chunks_now * kD * es; return HKV_OK;
     case HKV_X_K_ROWS:
     case HKV_X_V_ROWS: {
       const size_t rows = (size_t)(d->kind == HKV_STATIC ? d->n_prompt_rows : d->C) + tail;
@@ -787,6 +809,7 @@ int hkv_cache_decode_shape(const hkv_cache* c, int32_t* tile_rows, int32_t* dyna
 int hkv_cache_set_decode_dynamic(hkv_cache* c, int32_t dynamic_mode) {
   if (!c || dynamic_mode < 1 || dynamic_mode > 4) return HKV_EINVAL;
   if (dynamic_mode == 4 && c->cfg.dtype != HKV_BF16) return HKV_ESHAPE;
+  if (c->cfg.index_generated && (dynamic_mode == 2 || dynamic_mode == 3)) return HKV_ESHAPE;
   c->lo.mode = dynamic_mode;
   return HKV_OK;
 }

@@ -49,6 +49,8 @@ struct RowMap {
   int32_t c_log2;
   int32_t C;             // dynamic: prompt rows
   int32_t tail_row;      // physical row of the first appended token (row-major caches: static = retained rows, dynamic = C)
+  int32_t n_chunks_prompt;   // dynamic, generated tokens indexed: picks at or above this id are chunks of the tail
+  int32_t gen0;              // ... and the tail's first row that no complete chunk covers
   int32_t n_rows;        // logical rows to attend (prompt part + tail)
 };
 
@@ -416,20 +418,27 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 
 // Physical 8-row block that holds logical rows Lr .. Lr+7 (Lr a multiple of 8) and how many of them
 // are real (0..8).  A block with no real row is redirected to block 0, which always exists.
-template <bool DYN>
+template <int DYN>
 __device__ __forceinline__ void resolve_block(const RowMap& rm, int Lr, uint32_t& blk, int& nv, bool& tail) {
   int pb;
   tail = false;
-  if constexpr (!DYN) {
+  if constexpr (DYN == 0) {
     pb = Lr;
     nv = rm.n_rows - Lr;
   } else {
     if (Lr < rm.n_sel_rows) {
       const int ch = rm.sel[Lr >> rm.c_log2];
-      pb = (ch << rm.c_log2) + (Lr & ((1 << rm.c_log2) - 1));
-      nv = rm.C - pb;                                   // the last chunk of the prompt may be short
+      const int off = Lr & ((1 << rm.c_log2) - 1);
+      if (DYN == 2 && ch >= rm.n_chunks_prompt) {       // a complete chunk of generated tokens
+        pb = ((ch - rm.n_chunks_prompt) << rm.c_log2) + off;
+        nv = kBlkRows;
+        tail = true;
+      } else {
+        pb = (ch << rm.c_log2) + off;
+        nv = rm.C - pb;                                 // the last chunk of the prompt may be short
+      }
     } else {
-      pb = Lr - rm.n_sel_rows;                          // row of the tail, counted from the tail's base
+      pb = (DYN == 2 ? rm.gen0 : 0) + (Lr - rm.n_sel_rows);   // row of the tail, counted from the tail's base
       nv = rm.n_rows - Lr;
       tail = true;
     }
@@ -448,7 +457,7 @@ struct StepBufs {
 
 // Issues the loads of step `st` of the tile at row0 for this lane (wave-uniform st).  Rows past the end of
 // the unit resolve to its block 0 with no valid rows, so any step number is safe to ask for.
-template <bool DYN>
+template <int DYN>
 __device__ __forceinline__ void issue_step_loads(const RowMap& rm, int row0, int st, StepBufs& sb) {
   const int lane = thread_index() & 63;
   const int qi = lane & 15, jv = lane >> 4, ja = qi >> 2, e1 = lane & 3;
@@ -478,7 +487,7 @@ struct NoHook { __device__ __forceinline__ void operator()() const {} };
 // `sb` holds the operands in flight; with `preloaded` the caller has already issued this wave's first
 // step into it.  `between` runs after the last step's arithmetic and before the combination of the
 // waves, when `sb` is free again (a hook for callers that overlap something with the combination).
-template <int G, bool DYN, class Between = NoHook, int NW = 4>
+template <int G, int DYN, class Between = NoHook, int NW = 4>
 __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* __restrict__ q, float scale_log2e,
                                                int row0, int tile_rows, const PartOut& part, float* smem,
                                                StepBufs& sb, bool preloaded = false, Between between = Between()) {
@@ -594,14 +603,19 @@ template <typename T, int G, bool BLOCKED> constexpr size_t attn_smem_bytes() {
 }
 template <typename T> __device__ __forceinline__ constexpr int tile_of() { return sizeof(T) == 2 ? kTileBf16 : kTileF32; }
 
-template <typename T, int G, bool BLOCKED, int NW = 4>
+template <typename T, int G, bool BLOCKED, int NW = 4, bool INDEXED = false>
 __device__ __forceinline__ void run_tile(const RowMap& rm, const T* __restrict__ q, float scale_log2e, int row0,
                                          int tile_rows, const PartOut& part, float* smem) {
   if constexpr (sizeof(T) == 2 && BLOCKED) {
     StepBufs sb;
     sb.nv = 0;
-    if (rm.dynamic) attn_tile_mfma<G, true, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
-    else attn_tile_mfma<G, false, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
+    if constexpr (INDEXED) {               // kernels of caches that index their generated tokens
+      if (rm.dynamic) attn_tile_mfma<G, 2, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
+      else attn_tile_mfma<G, 0, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
+      return;
+    }
+    if (rm.dynamic) attn_tile_mfma<G, 1, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
+    else attn_tile_mfma<G, 0, NoHook, NW>(rm, q, scale_log2e, row0, tile_rows, part, smem, sb);
   } else if constexpr (sizeof(T) == 2) {
     attn_tile_bf16<G, kNhbBf16, false>(rm, q, scale_log2e, row0, part, smem);   // row-major rows, never gathered
   } else {
@@ -676,14 +690,17 @@ constexpr int kSelHeader = 256 + 16;       // words before the chunk scores: his
 template <typename T, int NT = 256>
 __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const UnitDesc& d, int lrel,
                                                       const T* __restrict__ q, int use_stored_sigma, float* dsm,
-                                                      int32_t* sel_lds = nullptr, bool to_memory = true) {
+                                                      int32_t* sel_lds = nullptr, bool to_memory = true,
+                                                      int n_c_now = -1, int k_now = -1) {
   constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = NT / LPR;
   const int tid = thread_index();
   uint32_t* hist = reinterpret_cast<uint32_t*>(dsm);         // [256]
   uint32_t* bc = hist + 256;                                 // [2]
   int* scan = reinterpret_cast<int*>(bc + 2);                // [NT / 64 + 1 <= 14]
   float* sig = dsm + kSelHeader;                             // [n_chunks rounded up to 4]
-  const int n_c = d.n_chunks;
+  // caches that index generated tokens pass the chunks there are at this step and how many to pick
+  const int n_c = n_c_now >= 0 ? n_c_now : d.n_chunks;
+  const int k_sel = k_now >= 0 ? k_now : d.k_sel;
   const int n_c4 = (n_c + 3) & ~3;
   unsigned long long* key64 = reinterpret_cast<unsigned long long*>(sig + n_c4);   // [n_c4], 8-byte aligned
 
@@ -699,41 +716,6 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     uint4 qraw[kMaxG];
 #pragma unroll
     for (int g = 0; g < kMaxG; ++g) qraw[g] = g < cv.G ? ld16(qb + (size_t)g * kD * sizeof(T)) : make_uint4(0, 0, 0, 0);
-    if (cv.sigma_max) {
-      // every query head of the group scores the chunk; the chunk takes the largest of the G scores
-      for (int ch0 = 0; ch0 < n_c; ch0 += RP * 4) {     // uniform trip count; four independent loads per round
-        uint4 raw[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int ch = ch0 + j * RP + slot;
-          raw[j] = ld16(mu + (size_t)min(ch, n_c - 1) * kD * sizeof(T));
-        }
-        float best[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) best[j] = -INFINITY;
-#pragma unroll
-        for (int g = 0; g < kMaxG; ++g) {
-          if (g < cv.G) {                                // uniform
-            float t[EPL];
-            unpack16(qraw[g], t, T{});
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              float mf[EPL];
-              unpack16(raw[j], mf, T{});
-              float dot = 0.f;
-#pragma unroll
-              for (int e = 0; e < EPL; ++e) dot = fmaf(t[e], mf[e], dot);
-              best[j] = fmaxf(best[j], sum_lanes<LPR>(dot));
-            }
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int ch = ch0 + j * RP + slot;
-          if (ch < n_c && sub == 0) { sig[ch] = best[j]; if (to_memory) cv.sigma[d.aux_off + ch] = best[j]; }
-        }
-      }
-    } else {
     for (int ch0 = 0; ch0 < n_c; ch0 += RP * 16) {      // uniform trip count; sixteen independent loads per round
       uint4 raw[16];
 #pragma unroll
@@ -762,7 +744,6 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
         if (ch < n_c && sub == 0) { sig[ch] = dot; if (to_memory) cv.sigma[d.aux_off + ch] = dot; }
       }
     }
-    }
   } else {
     for (int ch = tid; ch < n_c; ch += NT) sig[ch] = cv.sigma[d.aux_off + ch];
   }
@@ -775,7 +756,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     // Chunks with a key above it are picked, those equal to it in chunk order up to the k-th place.
     const int lane = tid & 63, wv = tid >> 6;
     if (NT > 256 && wv >= 4) return;                       // the first four waves cover all 256 chunks
-    const int k = d.k_sel;
+    const int k = k_sel;
     uint32_t key[4];
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
@@ -817,8 +798,8 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
   }
   uint32_t T_key = 0;
   int r_adm = n_c;
-  if (d.k_sel < n_c) {
-    radix_select<NT>(n_c, d.k_sel,
+  if (k_sel < n_c) {
+    radix_select<NT>(n_c, k_sel,
                      [&](int j, uint32_t& key) { key = float_order_key(sig[j]); return true; },
                      hist, bc, T_key, r_adm);
   }
@@ -834,7 +815,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     const int eq_rank = base_eq + block_exclusive_scan<NT>(eq, scan, &tot_eq);
     const int keep = gt | (eq & (eq_rank < r_adm ? 1 : 0));
     const int pos = base_keep + block_exclusive_scan<NT>(keep, scan, &tot_keep);
-    if (keep && pos < d.k_sel) {
+    if (keep && pos < k_sel) {
       if (to_memory) cv.sel[d.idx_off + pos] = ch;
       if (sel_lds) sel_lds[pos] = ch;
     }
@@ -874,10 +855,29 @@ __device__ __forceinline__ void append_row(const CacheView& cv, const AttnItem& 
   __syncthreads();                        // the row is in memory before any lane of this block reads it
 }
 
+// Caches that index their generated tokens (bf16): the chunk of generated tokens g of a dynamic unit has
+// just been completed by this block's append; its metadata -- the mean of its keys, rounded once to
+// bf16 like the prompt's -- goes behind the prompt's chunk summaries, where the next step's selection
+// finds it.  Threads 0..127 take one dimension each; the chunk's rows are read back from the blocked tail.
+__device__ __forceinline__ void index_generated_chunk(const CacheView& cv, const AttnItem& it, int g) {
+  const int dd = thread_index();
+  if (dd >= kD) return;
+  const int c = 1 << it.c_log2;
+  const char* tail = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.tail_off * kD * 2;
+  float acc = 0.f;
+  for (int r = 0; r < c; ++r) {
+    const int row = g * c + r;
+    const uint16_t bits = *reinterpret_cast<const uint16_t*>(tail + (size_t)(row >> 3) * kBlkBytes +
+                                                             k_piece_index(row & 7, dd >> 3) * 16 + (dd & 7) * 2);
+    acc += bits_to_float((uint32_t)bits << 16);
+  }
+  reinterpret_cast<uint16_t*>(cv.mu)[(size_t)(it.aux_off + it.n_chunks + g) * kD + dd] = f32_to_bf16_rne(acc / (float)c);
+}
+
 // One split-K tile of the hybrid cache: optional tail append, then attention, record -> workspace.
 // NW: waves of the workgroup (bf16 matrix-core tile only).  out_rows (bf16 caches, a tile that covers its
 // whole unit): the unit's G output rows are written there and no record is made.
-template <typename T, int G, int NW = 4>
+template <typename T, int G, int NW = 4, bool INDEXED = false>
 __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnItem& it, int layer_begin, int slot_base,
                                                const T* __restrict__ q, const T* __restrict__ k_new,
                                                const T* __restrict__ v_new, const PartOut& partials, int t_arg,
@@ -887,15 +887,24 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   const int tid = threadIdx.x;
   const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
   const bool append = (k_new != nullptr) && (t_before < cv.max_new);
+  // INDEXED, dynamic unit: it.n_prompt_rows counts the rows of the chunks picked this step (prompt or
+  // generated); of the tail only the rows behind its last complete chunk are attended unconditionally
+  const int gen0 = (INDEXED && it.dynamic) ? (t_before >> it.c_log2) << it.c_log2 : 0;
+  const int t_rest = t_before - gen0;
   RowMap rm;
-  rm.n_rows = it.n_prompt_rows + t_before + (append ? 1 : 0);
+  rm.n_rows = it.n_prompt_rows + t_rest + (append ? 1 : 0);
   if (it.row0 == 0 && it.seq == 0 && it.head == 0 && tid == 0)     // one block per layer moves the tail counter on
     (t_arg >= 0 ? cv.cnt_a : cv.cnt_b)[it.layer] = t_before + (append ? 1 : 0);
   if (it.row0 >= rm.n_rows) return;          // tile reserved for tail growth, not reached yet
   const int lrel = it.layer - layer_begin;
-  const int new_row = it.n_prompt_rows + t_before;          // logical index of the appended row
-  if (append && new_row >= it.row0 && new_row < it.row0 + TILE)    // block-uniform
+  const int new_row = it.n_prompt_rows + t_rest;            // logical index of the appended row
+  if (append && new_row >= it.row0 && new_row < it.row0 + TILE) {  // block-uniform
     append_row<T>(cv, it, lrel, t_before, k_new, v_new);
+    if constexpr (INDEXED && sizeof(T) == 2) {
+      if (it.dynamic && ((t_before + 1) & ((1 << it.c_log2) - 1)) == 0)    // the new token completes a chunk
+        index_generated_chunk(cv, it, t_before >> it.c_log2);
+    }
+  }
   rm.kbase = reinterpret_cast<const char*>(it.dynamic ? cv.k_dyn : cv.k_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.vbase = reinterpret_cast<const char*>(it.dynamic ? cv.v_dyn : cv.v_rows) + (size_t)it.kv_row_off * kD * sizeof(T);
   rm.ktail = (int64_t)(reinterpret_cast<intptr_t>(cv.k_rows) + it.tail_off * (int64_t)(kD * sizeof(T)) -
@@ -909,10 +918,12 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   rm.c_log2 = it.c_log2;
   rm.C = it.C;
   rm.tail_row = it.tail_row;
+  rm.n_chunks_prompt = it.n_chunks;
+  rm.gen0 = gen0;
   const size_t qoff = (((size_t)lrel * cv.batch + it.seq) * cv.n_q_heads + (size_t)it.head * G) * kD;
   const PartOut part = {out_rows ? nullptr : partials.o + (size_t)(it.slot - slot_base) * G * kD,
                         out_rows ? nullptr : partials.ml + (size_t)(it.slot - slot_base) * kMlStride, out_rows};
-  run_tile<T, G, true, NW>(rm, q + qoff, cv.scale_log2e, it.row0, TILE, part, smem);
+  run_tile<T, G, true, NW, INDEXED>(rm, q + qoff, cv.scale_log2e, it.row0, TILE, part, smem);
 }
 
 // Combine the tiles [0, n_tiles) of one unit, whose records this block wrote itself, and write the G
@@ -939,7 +950,61 @@ __device__ __forceinline__ void merge_own_tiles(const PartOut& first, int n_tile
 
 constexpr int kWholeUnit = 1 << 28;   // tile size that covers any unit (row counts stay below 2^24)
 
-template <typename T, int G>
+// Chunk scores under the other reading for grouped query heads (hkv_config.chunk_score_group = 1): every
+// query head of the group scores every chunk and a chunk takes the largest of its G scores.  A launch of
+// its own, ahead of the step's kernels, which then pick from the stored scores; the default reading stays
+// inside those kernels.  grid = dynamic units of the call, block = 256 threads.
+template <typename T>
+__global__ __launch_bounds__(256) void chunk_score_max_kernel(CacheView cv, int layer_begin, int dyn_begin,
+                                                              const T* __restrict__ q, int t_arg) {
+  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = 256 / LPR;
+  const UnitDesc d = cv.dyn_descs[dyn_begin + blockIdx.x];
+  const int lrel = d.layer - layer_begin;
+  int n_c = d.n_chunks;
+  if (cv.index_gen) n_c += (t_arg >= 0 ? t_arg : cv.cnt_a[d.layer]) >> d.c_log2;    // complete chunks of generated tokens
+  const int tid = thread_index(), sub = tid % LPR, slot = tid / LPR;
+  const char* qb = reinterpret_cast<const char*>(q) +
+                   (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * cv.G) * kD * sizeof(T) + sub * 16;
+  const char* mu = reinterpret_cast<const char*>(cv.mu) + (size_t)d.aux_off * kD * sizeof(T) + sub * 16;
+  uint4 qraw[kMaxG];
+#pragma unroll
+  for (int g = 0; g < kMaxG; ++g) qraw[g] = g < cv.G ? ld16(qb + (size_t)g * kD * sizeof(T)) : make_uint4(0, 0, 0, 0);
+  for (int ch0 = 0; ch0 < n_c; ch0 += RP * 4) {       // uniform trip count; four independent loads per round
+    uint4 raw[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int ch = ch0 + j * RP + slot;
+      raw[j] = ld16(mu + (size_t)min(ch, n_c - 1) * kD * sizeof(T));
+    }
+    float best[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) best[j] = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < kMaxG; ++g) {
+      if (g < cv.G) {                                  // uniform
+        float t[EPL];
+        unpack16(qraw[g], t, T{});
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float mf[EPL];
+          unpack16(raw[j], mf, T{});
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) dot = fmaf(t[e], mf[e], dot);
+          best[j] = fmaxf(best[j], sum_lanes<LPR>(dot));
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int ch = ch0 + j * RP + slot;
+      if (ch < n_c && sub == 0) cv.sigma[d.aux_off + ch] = best[j];
+    }
+  }
+}
+
+// INDEXED: the cache indexes its generated tokens (bf16 caches; see attention_item).
+template <typename T, int G, bool INDEXED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin, int slot_base,
                    const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new,
@@ -947,31 +1012,39 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
   extern __shared__ __attribute__((aligned(16))) float smem[];
   if ((int)blockIdx.x >= n_dyn) {
     const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_dyn)];
-    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+    attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
     return;
   }
   const UnitDesc d = cv.dyn_descs[dyn_begin + blockIdx.x];
   const int lrel = d.layer - layer_begin;
-  select_chunks_of_unit<T>(cv, d, lrel, q, use_stored_sigma, smem);
+  const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[d.layer];
+  // chunks there are at this step and how many of them are picked
+  int n_c_now = d.n_chunks, k_now = d.k_sel;
+  if constexpr (INDEXED) {
+    n_c_now += t_before >> d.c_log2;                    // complete chunks of generated tokens
+    k_now = min(d.k_sel, n_c_now);
+  }
+  select_chunks_of_unit<T>(cv, d, lrel, q, use_stored_sigma | cv.sigma_max, smem, nullptr, true, n_c_now, k_now);
   if (select_only) return;
   // ---- the rest of the dynamic unit, in this block ----
   __threadfence_block();
   __syncthreads();                          // the picks are in memory before the tile code reads them
-  const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[d.layer];
-  const int t_after = t_before + ((k_new != nullptr && t_before < cv.max_new) ? 1 : 0);
+  const int rows_sel = INDEXED ? (k_now << d.c_log2) : d.n_prompt_rows;
+  const int t_rest = INDEXED ? t_before - ((t_before >> d.c_log2) << d.c_log2) : t_before;
+  const int t_after = t_rest + ((k_new != nullptr && t_before < cv.max_new) ? 1 : 0);
   // the matrix-core tile takes any number of rows, so the whole unit is one tile and one record;
   // the fp32 tile has a fixed size
   const int TILE = sizeof(T) == 2 ? kWholeUnit : cv.tile_rows;
-  const int n_tiles = sizeof(T) == 2 ? 1 : (d.n_prompt_rows + t_after + TILE - 1) / TILE;
+  const int n_tiles = sizeof(T) == 2 ? 1 : (rows_sel + t_after + TILE - 1) / TILE;
   AttnItem it;
-  it.kv_row_off = d.kv_row_off; it.sel_off = (int32_t)d.idx_off; it.n_prompt_rows = d.n_prompt_rows;
+  it.kv_row_off = d.kv_row_off; it.sel_off = (int32_t)d.idx_off; it.n_prompt_rows = rows_sel;
   it.C = d.C; it.c_log2 = d.c_log2; it.dynamic = 1; it.layer = d.layer; it.seq = d.seq; it.head = d.head;
-  it.tail_row = d.tail_row; it.tail_off = d.tail_off;
+  it.tail_row = d.tail_row; it.tail_off = d.tail_off; it.n_chunks = d.n_chunks; it.aux_off = d.aux_off;
   for (int t = 0; t < n_tiles; ++t) {
     if (t > 0) __syncthreads();             // the previous tile's staging area is free again
     it.row0 = t * TILE;
     it.slot = d.item_begin + t;
-    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, TILE, smem);
+    attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, TILE, smem);
   }
   __threadfence_block();
   __syncthreads();                          // this block's own records are visible to all its threads
@@ -1014,7 +1087,7 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
     int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
     // the picks stay in LDS for this block's own tile; the first tile also leaves them (and the chunk
     // scores) in memory for export
-    select_chunks_of_unit<T>(cv, d, it.layer - layer_begin, q, 0, smem, sel_lds, it.row0 == 0);
+    select_chunks_of_unit<T>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0);
     __syncthreads();
     picks = sel_lds;
   }
@@ -1027,7 +1100,7 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
 // are few enough to give every unit a compute unit of its own.  grid = dynamic units of the call, then
 // static units.
 constexpr int kUnitWaves = 12;
-template <int G>
+template <int G, bool INDEXED = false>
 __global__ __launch_bounds__(kUnitWaves * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void unit_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int static_begin,
                  const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
@@ -1037,20 +1110,30 @@ void unit_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int st
   const UnitDesc d = dyn ? cv.dyn_descs[dyn_begin + blockIdx.x] : cv.static_descs[static_begin + ((int)blockIdx.x - n_dyn)];
   const int lrel = d.layer - layer_begin;
   const int32_t* picks = nullptr;
+  int rows_sel = d.n_prompt_rows;
   if (dyn) {
+    int n_c_now = d.n_chunks, k_now = d.k_sel;
+    if constexpr (INDEXED) {
+      const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[d.layer];
+      n_c_now += t_before >> d.c_log2;                       // complete chunks of generated tokens
+      k_now = min(d.k_sel, n_c_now);
+      rows_sel = k_now << d.c_log2;
+    }
     int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
-    select_chunks_of_unit<bf16_t, kUnitWaves * 64>(cv, d, lrel, q, 0, smem, sel_lds, true);
+    select_chunks_of_unit<bf16_t, kUnitWaves * 64>(cv, d, lrel, q, cv.sigma_max, smem, sel_lds, true, n_c_now, k_now);
     __syncthreads();                                         // the picks are in shared memory; the scratch is free
     picks = sel_lds;
   }
   AttnItem it;
-  it.kv_row_off = d.kv_row_off; it.sel_off = (int32_t)d.idx_off; it.n_prompt_rows = d.n_prompt_rows;
+  it.kv_row_off = d.kv_row_off; it.sel_off = (int32_t)d.idx_off; it.n_prompt_rows = rows_sel;
   it.C = d.C; it.c_log2 = d.c_log2; it.dynamic = dyn ? 1 : 0; it.layer = d.layer; it.seq = d.seq; it.head = d.head;
-  it.tail_row = d.tail_row; it.tail_off = d.tail_off; it.row0 = 0; it.slot = 0;
+  it.tail_row = d.tail_row; it.tail_off = d.tail_off; it.row0 = 0; it.slot = 0; it.n_chunks = d.n_chunks;
+  it.aux_off = d.aux_off;
   uint16_t* orow = reinterpret_cast<uint16_t*>(out) +
                    (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G) * kD;
   const PartOut none = {nullptr, nullptr, nullptr};
-  attention_item<bf16_t, G, kUnitWaves>(cv, it, layer_begin, 0, q, k_new, v_new, none, t_arg, kWholeUnit, smem, picks, orow);
+  attention_item<bf16_t, G, kUnitWaves, INDEXED>(cv, it, layer_begin, 0, q, k_new, v_new, none, t_arg, kWholeUnit, smem,
+                                                 picks, orow);
 }
 
 // grid = n_units x G, block = 128 threads; descs points at the first unit's descriptor.
@@ -1148,7 +1231,7 @@ static size_t select_smem_bytes(int max_chunks) {
   return (kSelHeader + n4) * sizeof(float) + n4 * sizeof(unsigned long long);
 }
 
-template <typename T, int G>
+template <typename T, int G, bool INDEXED = false>
 static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                                   int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
                                   float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma,
@@ -1157,15 +1240,27 @@ static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_
   const size_t smem = std::max(attn_smem_bytes<T, G, true>(), select_smem_bytes(max_chunks));
   static size_t attr = 0;      // per instantiation; the attribute is sticky for the process
   if (smem > attr) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, G>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, G, INDEXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr = smem;
   }
   if (n_dyn + n_sitems > 0)
-    HKV_LAUNCH((decode_kernel<T, G>), dim3(n_dyn + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1, cv,
+    HKV_LAUNCH((decode_kernel<T, G, INDEXED>), dim3(n_dyn + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1, cv,
                           layer_begin, dyn_begin, n_dyn, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
                           (const T*)v_new, partials, (T*)out, t_arg, use_stored_sigma, select_only);
+  return hipGetLastError();
+}
+
+hipError_t launch_chunk_score_max(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, const void* q,
+                                  int t_arg, hipStream_t st) {
+  if (n_dyn <= 0) return hipSuccess;
+  if (dtype == HKV_F32)
+    hipLaunchKernelGGL(chunk_score_max_kernel<float>, dim3(n_dyn), dim3(256), 0, st, cv, layer_begin, dyn_begin,
+                       (const float*)q, t_arg);
+  else
+    hipLaunchKernelGGL(chunk_score_max_kernel<bf16_t>, dim3(n_dyn), dim3(256), 0, st, cv, layer_begin, dyn_begin,
+                       (const bf16_t*)q, t_arg);
   return hipGetLastError();
 }
 
@@ -1173,6 +1268,13 @@ hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dy
                          int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
                          float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma, int select_only,
                          int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (cv.index_gen) {        // bf16 caches only (checked when the cache is laid out)
+    if (dtype != HKV_BF16) return hipErrorInvalidValue;
+    HKV_DISPATCH_G(cv.G, return (launch_decode_t<bf16_t, GG, true>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin,
+                                                                   n_sitems, slot_base, q, k_new, v_new, parts_o, parts_ml,
+                                                                   out, t_arg, use_stored_sigma, select_only, max_chunks,
+                                                                   st, ev0, ev1)));
+  }
   if (dtype == HKV_F32) {
     HKV_DISPATCH_G(cv.G, return (launch_decode_t<float, GG>(cv, layer_begin, dyn_begin, n_dyn, sitem_begin, n_sitems,
                                                             slot_base, q, k_new, v_new, parts_o, parts_ml, out, t_arg,
@@ -1225,7 +1327,7 @@ hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin,
   return hipErrorInvalidValue;
 }
 
-template <int G>
+template <int G, bool INDEXED = false>
 static hipError_t launch_units_t(const CacheView& cv, int layer_begin, int dyn_begin, int n_dyn, int static_begin,
                                  int n_static, const void* q, const void* k_new, const void* v_new, void* out, int t_arg,
                                  int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
@@ -1234,12 +1336,12 @@ static hipError_t launch_units_t(const CacheView& cv, int layer_begin, int dyn_b
   const size_t smem = front + (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t);
   static size_t attr = 0;
   if (smem > attr) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unit_kernel<G>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unit_kernel<G, INDEXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr = smem;
   }
-  HKV_LAUNCH((unit_kernel<G>), dim3(n_dyn + n_static), dim3(kUnitWaves * 64), (uint32_t)smem, st, ev0, ev1, cv, layer_begin,
+  HKV_LAUNCH((unit_kernel<G, INDEXED>), dim3(n_dyn + n_static), dim3(kUnitWaves * 64), (uint32_t)smem, st, ev0, ev1, cv, layer_begin,
              dyn_begin, n_dyn, static_begin, (const bf16_t*)q, (const bf16_t*)k_new, (const bf16_t*)v_new, (bf16_t*)out,
              t_arg, (int)(front / sizeof(float)));
   return hipGetLastError();
@@ -1250,6 +1352,10 @@ hipError_t launch_units(const CacheView& cv, int dtype, int layer_begin, int dyn
                         int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (dtype != HKV_BF16) return hipErrorInvalidValue;
   if (n_dyn + n_static <= 0) return hipSuccess;
+  if (cv.index_gen) {
+    HKV_DISPATCH_G(cv.G, return (launch_units_t<GG, true>(cv, layer_begin, dyn_begin, n_dyn, static_begin, n_static, q,
+                                                          k_new, v_new, out, t_arg, max_chunks, st, ev0, ev1)));
+  }
   HKV_DISPATCH_G(cv.G, return (launch_units_t<GG>(cv, layer_begin, dyn_begin, n_dyn, static_begin, n_static, q, k_new,
                                                   v_new, out, t_arg, max_chunks, st, ev0, ev1)));
   return hipErrorInvalidValue;

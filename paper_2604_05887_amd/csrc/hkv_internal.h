@@ -99,6 +99,7 @@ struct CacheView {
   int32_t n_layers, batch, n_q_heads, n_kv_heads, G, window, max_new, causal;
   int32_t tile_rows;          // logical rows per split-K tile of this cache
   int32_t sigma_max;          // chunk score of a group: 0 = summed query, 1 = largest of the heads' inner products
+  int32_t index_gen;          // dynamic heads: complete chunks of generated tokens are indexed and retrieved like the prompt's
   float scale_log2e;          // softmax scale * log2(e)
 };
 
@@ -111,6 +112,9 @@ int validate_config(const hkv_config* cfg);
 // knows it, else -1 (device counters).  select_only: the dynamic blocks stop after the chunk selection.
 // launch_attn_merge also publishes the new tail counters when t_arg < 0, so it runs last.
 // ev0 / ev1 (both or neither) receive the kernel's own start and stop time stamps.
+// Scores of the chunks under hkv_config.chunk_score_group = 1, stored for the step's kernels to pick from.
+hipError_t launch_chunk_score_max(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, const void* q,
+                                  int t_arg, hipStream_t st);
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
                          int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
                          float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma, int select_only,

@@ -42,12 +42,13 @@ class DeviceWorkload:
 
 def setup(wl, device="cuda:0", budget: Optional[np.ndarray] = None, head_type: Optional[np.ndarray] = None,
           score_causal: int = 0, upload_prompt: bool = True, decode_tile_rows: int = 0,
-          decode_dynamic: int = 0, host_tier: bool = False, chunk_score_group: int = 0) -> DeviceWorkload:
+          decode_dynamic: int = 0, host_tier: bool = False, chunk_score_group: int = 0,
+          index_generated: int = 0) -> DeviceWorkload:
     cfg = B.make_config(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                         dtype=hkv_dtype(wl.dtype), window=wl.window, chunk_size=int(wl.chunk_size[0]),
                         max_new_tokens=wl.max_new_tokens, score_causal=score_causal,
                         decode_tile_rows=decode_tile_rows, decode_dynamic=decode_dynamic,
-                        chunk_score_group=chunk_score_group)
+                        chunk_score_group=chunk_score_group, index_generated=index_generated)
     plan = B.PlanArrays(wl.cu_seqlens, wl.is_visual, wl.head_type if head_type is None else head_type,
                         wl.budget if budget is None else budget, wl.chunk_size)
     cache = B.HybridKVCache(cfg, plan, device=device, host_tier=host_tier)
@@ -69,8 +70,11 @@ def tune_decode_dynamic(caches: Sequence, step_fn: Callable[[object, int], None]
     for m in modes:
         if m == 4 and caches[0].cfg.dtype != B.HKV_BF16:
             continue
-        for c in caches:
-            c.cache.set_decode_dynamic(m)
+        try:
+            for c in caches:
+                c.cache.set_decode_dynamic(m)
+        except B.HkvError:            # a shape this cache does not support
+            continue
         for i in range(warmup):
             step_fn(caches[i % len(caches)], i)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

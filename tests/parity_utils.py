@@ -28,10 +28,10 @@ SCORE_RTOL = 2e-5   # fp32 MFMA accumulation + exp2 + fp32 column sums vs double
 OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}
 
 
-def oracle_setup(wl, budget=None, head_type=None, causal=False, chunk_score_group="sum"):
+def oracle_setup(wl, budget=None, head_type=None, causal=False, chunk_score_group="sum", index_generated=False):
     cfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                          head_dim=wl.head_dim, window=wl.window, dtype=wl.dtype, score_causal=causal,
-                         chunk_score_group=chunk_score_group)
+                         chunk_score_group=chunk_score_group, index_generated=index_generated)
     plan = O.OraclePlan(cu_seqlens=wl.cu_seqlens, head_type=wl.head_type if head_type is None else head_type,
                         budget=wl.budget if budget is None else budget, chunk_size=wl.chunk_size)
     return cfg, plan
@@ -105,7 +105,10 @@ def compare_compress(wl, dw, ocache, stats: Dict[str, float]) -> Dict[Tuple[int,
             assert np.array_equal(Vc[: kept_gpu.size], wl.v[l, lo + kept_gpu, h])
         else:
             rows, n_c, k_sel = dw.cache.unit_info(b, l, h)
-            assert (n_c, k_sel) == (u.mu.shape[0], u.k_sel) and rows == k_sel * u.c
+            k_want = u.k_sel
+            if ocache.cfg.index_generated:         # room for the chunks generation can complete
+                k_want = min(u.k_cap, u.mu.shape[0] + wl.max_new_tokens // u.c)
+            assert (n_c, k_sel) == (u.mu.shape[0], k_want) and rows == k_sel * u.c
             mu_gpu = dw.cache.export(B.HKV_X_CHUNK_MEAN, b, l, h).astype(np.float64)
             # fp32 summation of n rows errs by at most (n-1) * 2^-24 * sum|k| (then / n); storing in bf16
             # can move the result to the neighbouring bf16 value (one ulp <= 2^-7 relative)
@@ -144,13 +147,22 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
         got = runner.to_host_f32(out).astype(np.float64)
         # chunk picks first: they decide which rows the oracle attends
         sel_over = {}
+        indexed = ocache.cfg.index_generated
         for key, u in ocache.units.items():
             if u.kind != O.DYNAMIC:
                 continue
             b, l, h = key
             sig_gpu = dw.cache.export(B.HKV_X_CHUNK_SIGMA, b, l, h)
             sel_gpu = dw.cache.export(B.HKV_X_CHUNK_SEL, b, l, h).astype(np.int64)
-            assert np.array_equal(sel_gpu, O.select_chunks(sig_gpu, u.k_sel)), f"chunk top-k not exact on {key}"
+            k_step = u.k_sel
+            if indexed:
+                # the step saw the chunks complete before it: those of the prompt and of the s tokens generated so far;
+                # the summaries are exported anew because the step may have added one
+                n_now = u.mu.shape[0] + (s if append else 0) // u.c
+                k_step = min(u.k_cap, n_now)
+                mu_dev[key] = dw.cache.export(B.HKV_X_CHUNK_MEAN, b, l, h).astype(np.float64)[:n_now]
+                sig_gpu, sel_gpu = sig_gpu[:n_now], sel_gpu[:k_step]
+            assert np.array_equal(sel_gpu, O.select_chunks(sig_gpu, k_step)), f"chunk top-k not exact on {key}"
             qh = wl.q_steps[s][l, b, h * G:(h + 1) * G].astype(np.float64)
             group = ocache.cfg.chunk_score_group
             sig_ref = O.chunk_scores(qh, mu_dev[key], group)
@@ -159,11 +171,13 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
             err = np.abs(sig_gpu - sig_ref).max() / scale
             stats["sigma_err"] = max(stats.get("sigma_err", 0.0), float(err))
             assert err <= 1e-5, f"chunk scores off by {err:.3e} (relative to |q||mu|) on {key}"
-            want = O.select_chunks(sig_ref, u.k_sel)
-            same = check_banded(sel_gpu, want, sig_ref, np.arange(sig_ref.size), u.k_sel, lambda thr: 1e-5 * scale)
+            want = O.select_chunks(sig_ref, k_step)
+            same = check_banded(sel_gpu, want, sig_ref, np.arange(sig_ref.size), k_step, lambda thr: 1e-5 * scale)
             if not same:
                 sel_over[key] = sel_gpu
                 stats["banded_chunk_picks"] = stats.get("banded_chunk_picks", 0) + 1
+            if indexed:
+                stats["generated_chunks_picked"] = stats.get("generated_chunks_picked", 0) + int((sel_gpu >= u.mu.shape[0]).sum())
         ref, _ = O.decode_attn(ocache, wl.q_steps[s], wl.k_new[s] if append else None,
                                wl.v_new[s] if append else None, layers=oracle_layers, sel_override=sel_over,
                                mu_override=mu_dev)
@@ -172,6 +186,19 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
         err = np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
         stats["out_err"] = max(stats.get("out_err", 0.0), float(err.max()))
         assert err.max() <= OUT_TOL[wl.dtype], f"step {s}: output off by {err.max():.3e}"
+    if ocache.cfg.index_generated:
+        # the summaries of the generated chunks themselves: fp32 sum of c keys, one rounding to the KV dtype
+        for key, u in ocache.units.items():
+            if u.kind != O.DYNAMIC or (oracle_layers is not None and key[1] not in oracle_layers) or not u.mu_gen:
+                continue
+            n_c = u.mu.shape[0]
+            got_mu = dw.cache.export(B.HKV_X_CHUNK_MEAN, *key).astype(np.float64)
+            assert got_mu.shape[0] == n_c + len(u.mu_gen)
+            tail_k = np.abs(np.stack(u.K_tail))
+            for g, ref_mu in enumerate(u.mu_gen):
+                tol = 2.0 ** -24 * tail_k[g * u.c:(g + 1) * u.c].sum(axis=0) + np.abs(ref_mu) * 2.0 ** -7
+                assert np.all(np.abs(got_mu[n_c + g] - ref_mu) <= tol), f"summary of generated chunk {g} of {key} off"
+            stats["generated_chunks_indexed"] = stats.get("generated_chunks_indexed", 0) + len(u.mu_gen)
     return out
 
 
@@ -179,7 +206,8 @@ def full_pipeline(wl, budget=None, head_type=None, causal=False, n_steps=None, l
     stats: Dict[str, float] = {}
     dw = runner.setup(wl, budget=budget, head_type=head_type, score_causal=int(causal), **setup_kw)
     ocfg, oplan = oracle_setup(wl, budget, head_type, causal,
-                               chunk_score_group="max" if setup_kw.get("chunk_score_group", 0) == 1 else "sum")
+                               chunk_score_group="max" if setup_kw.get("chunk_score_group", 0) == 1 else "sum",
+                               index_generated=bool(setup_kw.get("index_generated", 0)))
     ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual)
     if layer_ranges:
         for (lb, le) in layer_ranges:

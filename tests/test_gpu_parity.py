@@ -770,3 +770,64 @@ def test_serving_mix_at_full_context_lengths():
     assert wl.batch == 16 and int(wl.seqlens.max()) > 30000
     stats = P.full_pipeline(wl, decode_tile_rows=1024)
     _say("cfg4 full lengths L1", stats)
+
+
+# ---- generated tokens in the chunk index (index_generated = 1) ----
+
+@pytest.mark.parametrize("mode,case", [(1, "small_chunks"), (4, "small_chunks"), (1, "every_chunk"), (4, "ragged"),
+                                       (1, "host_tier"), (0, "max_group")])
+def test_generated_tokens_are_indexed_and_retrieved(mode, case):
+    """Dynamic heads retrieve complete chunks of generated tokens like chunks of the prompt; the rest of
+    the tail is always attended.  40 steps with 8-token chunks complete five chunks (and carry a head with
+    256 prompt chunks over the 256-chunk boundary between the two selection routines); the ragged case
+    has 32- and 64-token chunks and runs long enough to complete both kinds."""
+    kw = dict(index_generated=1, decode_dynamic=mode)
+    if case == "ragged":
+        wl = make_workload(4, n_layers=1, shrink=8, steps=66)
+    else:
+        wl = make_workload(1, n_layers=2, shrink=4, steps=40)
+        wl.chunk_size[:] = 8
+        dyn = wl.head_type == O.DYNAMIC
+        wl.budget[dyn] = 8 * (10 ** 6 if case == "every_chunk" else 100)
+        if case == "host_tier":
+            kw["host_tier"] = True
+        if case == "max_group":
+            kw["chunk_score_group"] = 1
+    stats = P.full_pipeline(wl, **kw)
+    _say(f"indexed generation, {case}, mode {mode}", stats)
+    assert stats["generated_chunks_picked"] > 0
+
+
+def test_indexed_generation_argument_checks_and_device_tail():
+    wl = make_workload(1, n_layers=2, shrink=8, steps=20)
+    wl.chunk_size[:] = 8
+    for bad in (2, 3):
+        with pytest.raises(B.HkvError) as ei:
+            runner.setup(wl, upload_prompt=False, index_generated=1, decode_dynamic=bad)
+        assert ei.value.status == B.HKV_ESHAPE
+    wl32 = make_workload(0, shrink=4, steps=1)
+    with pytest.raises(B.HkvError) as ei:
+        runner.setup(wl32, upload_prompt=False, index_generated=1)           # fp32 cache
+    assert ei.value.status == B.HKV_ESHAPE
+    # tail lengths kept on the device (as a recorded step needs them) give the same bits as host bookkeeping
+    outs = []
+    for device_tail in (False, True):
+        dw = runner.setup(wl, index_generated=1)
+        assert dw.cache.decode_shape()[1] in (1, 4)
+        with pytest.raises(B.HkvError):
+            dw.cache.set_decode_dynamic(3)
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+        if device_tail:
+            dw.cache.set_device_tail(True)
+        out = torch.empty((wl.n_layers, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+        res = []
+        for s in range(wl.steps):
+            q, kn, vn = (runner.to_device(x[s], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+            dw.cache.decode_attn(q, kn, vn, out)
+            torch.cuda.synchronize()
+            res.append(out.clone())
+        outs.append(torch.stack(res))
+        if device_tail:
+            dw.cache.set_device_tail(False)
+        dw.cache.close()
+    assert torch.equal(outs[0], outs[1])
