@@ -62,6 +62,12 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--host-tier", action="store_true",
                     help="keep the dynamic heads' prompt rows in page-locked host memory (bf16 workloads)")
+    ap.add_argument("--index-generated", action="store_true",
+                    help="dynamic heads retrieve complete chunks of generated tokens instead of attending the whole "
+                         "tail (bf16 workloads; decode shapes 1 and 4)")
+    ap.add_argument("--tail", type=int, default=-1,
+                    help="generated tokens every head already holds when the timed steps start (default: half the "
+                         "workload's step count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-kv", action="store_true", help="skip the full-KV comparison kernel")
     ap.add_argument("--classify", action="store_true",
@@ -142,7 +148,7 @@ def main() -> int:
     # the real run appends one token per step for `steps` steps; the rotation spreads the timed steps
     # over several copies, so every copy's tail is pre-rolled to the middle of that range
     probe = runner.setup(wl, dev, upload_prompt=False, decode_tile_rows=args.tile_rows, decode_dynamic=args.dynamic_mode,
-                         host_tier=args.host_tier)
+                         host_tier=args.host_tier, index_generated=int(args.index_generated))
     step_bytes_mid = probe.cache.step_bytes(wl.steps // 2)
     probe.cache.close()
     del probe
@@ -150,10 +156,10 @@ def main() -> int:
     # show the attention kernels fetch their full algorithmic bytes from HBM even with three copies)
     n_copies = args.copies or int(min(8, max(2, -(-5 * MALL_BYTES // (4 * step_bytes_mid)) + 1)))
     per_copy = -(-(K + W) // n_copies)
-    preroll = max(0, wl.steps // 2 - per_copy // 2)
+    preroll = max(0, wl.steps // 2 - per_copy // 2) if args.tail < 0 else args.tail
     wl.max_new_tokens = preroll + 2 * per_copy + 2 + K + 64   # room for the profiled and per-layer passes as well
     copies = [runner.setup(wl, dev, upload_prompt=False, decode_tile_rows=args.tile_rows, decode_dynamic=args.dynamic_mode,
-                           host_tier=args.host_tier) for _ in range(n_copies)]
+                           host_tier=args.host_tier, index_generated=int(args.index_generated)) for _ in range(n_copies)]
     stream = torch.cuda.current_stream()
     sptr = int(stream.cuda_stream) or None
 
@@ -287,7 +293,9 @@ def main() -> int:
                 if wl.head_type[b, l, h] != 0:
                     link_bytes += 2 * R * copies[0].cache.unit_info(b, l, h)[0]
     tile_rows, dyn_mode = copies[0].cache.decode_shape()
-    if dyn_mode != 2:        # the main launch also reads the dynamic heads' gathered rows
+    if args.index_generated:     # rows and summaries depend on the tail length: the library's own formula
+        a_bytes, b_bytes = copies[0].cache.step_bytes(int(round(tail_prof))), 0
+    elif dyn_mode != 2:        # the main launch also reads the dynamic heads' gathered rows
         a_bytes += b_bytes
         b_bytes = 0
     a_gbs = a_bytes / (a_us * 1e-6) / 1e9
@@ -473,6 +481,7 @@ def main() -> int:
                         "host_link_bytes_per_step": int(link_bytes) if args.host_tier else 0,
                         "host_link_gbs": round(link_bytes / (ms_per_step * 1e-3) / 1e9, 1) if args.host_tier else 0.0,
                         "host_link_peak_gbs": 64.0},      # PCIe 5.0 x16, one direction, before packet overhead
+        "index_generated": bool(args.index_generated),
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
         "decode_shape": {"tile_rows": tile_rows, "dynamic_mode": dyn_mode, "tuned_us_per_step": tuned_us},
         "kernel_us": {"main_launch": round(a_us, 2), "second_launch": round(b_us, 2),
