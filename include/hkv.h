@@ -116,7 +116,7 @@ typedef struct {
                                1 = the LARGEST of the group's inner products with the chunk summary */
   int32_t index_generated;  /* 0: tokens generated during decoding are kept uncompressed and every head
                                attends all of them (the paper generates at most a few hundred).
-                               1 (bf16 caches, decode_dynamic 0, 1 or 4; else HKV_ESHAPE): a variant for
+                               1 (bf16 caches, decode_dynamic other than 2; else HKV_ESHAPE): a variant for
                                long generations.  On dynamic heads the generated tokens are cut into
                                chunks of the head's chunk size in order of generation; a chunk that was
                                complete before the step has the mean of its keys as its summary and

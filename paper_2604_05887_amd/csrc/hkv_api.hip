@@ -30,9 +30,9 @@ int validate_config(const hkv_config* cfg) {
   if (cfg->decode_dynamic == 4 && cfg->dtype != HKV_BF16) return HKV_ESHAPE;   // the per-unit shape is bf16 only
   if (cfg->chunk_score_group != 0 && cfg->chunk_score_group != 1) return HKV_EINVAL;
   if (cfg->index_generated != 0 && cfg->index_generated != 1) return HKV_EINVAL;
-  if (cfg->index_generated) {               // bf16 caches, and only the shapes in which one workgroup owns a dynamic head
+  if (cfg->index_generated) {               // bf16 caches; not the shape that selects in one launch and gathers in the next
     if (cfg->dtype != HKV_BF16) return HKV_ESHAPE;
-    if (cfg->decode_dynamic == 2 || cfg->decode_dynamic == 3) return HKV_ESHAPE;
+    if (cfg->decode_dynamic == 2) return HKV_ESHAPE;
   }
   if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
   return HKV_OK;
@@ -185,7 +185,11 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
           if (ht == HKV_DYNAMIC) lo.reselect_extra_bytes += R * d.n_chunks * ((d.n_prompt_rows + tile - 1) / tile - 1);
         }
         d.item_begin = (int32_t)lo.n_items;
-        d.n_tiles_max = std::max(1, (d.n_prompt_rows + cfg->max_new_tokens + tile - 1) / tile);
+        // rows a unit can attend: its prompt rows and its whole tail -- or, for a dynamic unit of a cache that
+        // indexes generated tokens, the picked chunks and at most one chunk's worth of tail
+        const int tail_rows_max = (ht == HKV_DYNAMIC && cfg->index_generated)
+                                      ? std::min(cfg->max_new_tokens, 1 << d.c_log2) : cfg->max_new_tokens;
+        d.n_tiles_max = std::max(1, (d.n_prompt_rows + tail_rows_max + tile - 1) / tile);
         if ((int64_t)C + cfg->max_new_tokens >= (1 << 24)) return HKV_ESHAPE;   // 24-bit row arithmetic in the kernels
         for (int t = 0; t < d.n_tiles_max; ++t) {
           AttnItem it;
@@ -279,12 +283,10 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
   }
   if (rc != HKV_OK) return rc;
   if (cfg->decode_dynamic != 0) lo.mode = cfg->decode_dynamic;
-  else if (cfg->index_generated)       // one workgroup per dynamic head: wide for short heads, else inside the main launch
-    lo.mode = std::max(lo.max_rows_static + cfg->max_new_tokens, lo.max_rows_dynamic) <= kUnitShapeMaxRows ? 4 : 1;
   else if (cfg->dtype == HKV_BF16 &&
            std::max(lo.max_rows_static + cfg->max_new_tokens, lo.max_rows_dynamic) <= kUnitShapeMaxRows)
     lo.mode = 4;         // short heads: one wide workgroup each beats split-K plus the combination launch
-  else lo.mode = 4 * lo.reselect_extra_bytes <= lo.step_bytes0 ? 3 : 2;
+  else lo.mode = 4 * lo.reselect_extra_bytes <= lo.step_bytes0 ? 3 : (cfg->index_generated ? 1 : 2);
   return HKV_OK;
 }
 
@@ -809,7 +811,7 @@ int hkv_cache_decode_shape(const hkv_cache* c, int32_t* tile_rows, int32_t* dyna
 int hkv_cache_set_decode_dynamic(hkv_cache* c, int32_t dynamic_mode) {
   if (!c || dynamic_mode < 1 || dynamic_mode > 4) return HKV_EINVAL;
   if (dynamic_mode == 4 && c->cfg.dtype != HKV_BF16) return HKV_ESHAPE;
-  if (c->cfg.index_generated && (dynamic_mode == 2 || dynamic_mode == 3)) return HKV_ESHAPE;
+  if (c->cfg.index_generated && dynamic_mode == 2) return HKV_ESHAPE;
   c->lo.mode = dynamic_mode;
   return HKV_OK;
 }

@@ -1059,7 +1059,7 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
 // boundary is needed; all blocks of a unit compute and store identical picks.  In that shape the grid
 // also carries the static tiles: blocks [n_ditems, n_ditems + n_sitems), which wait static_hold x 512
 // clocks before their first loads.
-template <typename T, int G>
+template <typename T, int G, bool INDEXED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_ditems, int sitem_begin,
                           int slot_base, const T* __restrict__ q, const T* __restrict__ k_new,
@@ -1073,25 +1073,32 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
     // behind all of them.  The static tiles therefore start a little later: static_hold x 512 clocks,
     // the time the summaries need on the memory system (0 for grids of several rounds).
     for (int i = 0; i < static_hold; ++i) __builtin_amdgcn_s_sleep(8);
-    attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+    attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
     return;
   }
-  const AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
+  AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
   const int32_t* picks = nullptr;
   if (reselect) {
     const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
-    if (it.row0 >= it.n_prompt_rows + t_before + 1) return;     // tile not reached yet, with or without an append
+    int n_c_now = it.n_chunks, k_now = it.k_sel, t_rest = t_before;
+    if constexpr (INDEXED) {                                    // chunks there are at this step, picks, rows they give
+      n_c_now += t_before >> it.c_log2;
+      k_now = min(it.k_sel, n_c_now);
+      it.n_prompt_rows = k_now << it.c_log2;
+      t_rest = t_before & ((1 << it.c_log2) - 1);
+    }
+    if (it.row0 >= it.n_prompt_rows + t_rest + 1) return;       // tile not reached yet, with or without an append
     UnitDesc d;                                                 // the fields the selection reads
     d.aux_off = it.aux_off; d.idx_off = it.sel_off; d.n_chunks = it.n_chunks; d.k_sel = it.k_sel;
     d.seq = it.seq; d.head = it.head;
     int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
     // the picks stay in LDS for this block's own tile; the first tile also leaves them (and the chunk
     // scores) in memory for export
-    select_chunks_of_unit<T>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0);
+    select_chunks_of_unit<T>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0, n_c_now, k_now);
     __syncthreads();
     picks = sel_lds;
   }
-  attention_item<T, G>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem, picks);
+  attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem, picks);
 }
 
 // One workgroup of kUnitWaves waves per unit (bf16 caches): chunk selection for a dynamic unit, then attention
@@ -1147,7 +1154,12 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, const Uni
   const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[d.layer];
   const int t = t_before + ((appending && t_before < cv.max_new) ? 1 : 0);
   const int TILE = cv.tile_rows;
-  const int n_tiles = (d.n_prompt_rows + t + TILE - 1) / TILE;
+  int rows = d.n_prompt_rows + t;
+  if (cv.index_gen && d.kind == HKV_DYNAMIC) {     // picked chunks (prompt or generated) + the tail behind its last complete chunk
+    const int k_now = min(d.k_sel, d.n_chunks + (t_before >> d.c_log2));
+    rows = (k_now << d.c_log2) + (t_before & ((1 << d.c_log2) - 1)) + (t - t_before);
+  }
+  const int n_tiles = (rows + TILE - 1) / TILE;
   const int lrel = d.layer - layer_begin;
   const float* o0 = partials.o + ((size_t)(d.item_begin - slot_base) * G + g) * kD;
   const float* ml0 = partials.ml + (size_t)(d.item_begin - slot_base) * kMlStride + 2 * g;
@@ -1287,7 +1299,7 @@ hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dy
   return hipErrorInvalidValue;
 }
 
-template <typename T, int G>
+template <typename T, int G, bool INDEXED = false>
 static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, int ditem_begin, int n_ditems,
                                          int sitem_begin, int n_sitems, int slot_base, const void* q,
                                          const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
@@ -1299,12 +1311,12 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
   const size_t smem = front + (reselect ? (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t) : 0);
   static size_t attr = 0;
   if (smem > attr) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G, INDEXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr = smem;
   }
-  HKV_LAUNCH((dynamic_tiles_kernel<T, G>), dim3(n_ditems + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1,
+  HKV_LAUNCH((dynamic_tiles_kernel<T, G, INDEXED>), dim3(n_ditems + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1,
                         cv, layer_begin, ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
                         (const T*)v_new, partials, t_arg, reselect, (int)(front / sizeof(float)), static_hold);
   return hipGetLastError();
@@ -1315,6 +1327,13 @@ hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin,
                                 const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
                                 int static_hold, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (n_ditems + n_sitems <= 0) return hipSuccess;
+  if (cv.index_gen) {        // bf16 caches, tiles that repeat the selection
+    if (dtype != HKV_BF16 || !reselect) return hipErrorInvalidValue;
+    HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, true>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
+                                                                          n_sitems, slot_base, q, k_new, v_new, parts_o,
+                                                                          parts_ml, t_arg, reselect, static_hold, max_chunks,
+                                                                          st, ev0, ev1)));
+  }
   if (dtype == HKV_F32) {
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<float, GG>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
                                                                    n_sitems, slot_base, q, k_new, v_new, parts_o,

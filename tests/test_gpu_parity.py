@@ -774,8 +774,9 @@ def test_serving_mix_at_full_context_lengths():
 
 # ---- generated tokens in the chunk index (index_generated = 1) ----
 
-@pytest.mark.parametrize("mode,case", [(1, "small_chunks"), (4, "small_chunks"), (1, "every_chunk"), (4, "ragged"),
-                                       (1, "host_tier"), (0, "max_group")])
+@pytest.mark.parametrize("mode,case", [(1, "small_chunks"), (4, "small_chunks"), (3, "small_chunks"), (1, "every_chunk"),
+                                       (3, "every_chunk"), (4, "ragged"), (3, "ragged"), (1, "host_tier"),
+                                       (3, "host_tier"), (0, "max_group")])
 def test_generated_tokens_are_indexed_and_retrieved(mode, case):
     """Dynamic heads retrieve complete chunks of generated tokens like chunks of the prompt; the rest of
     the tail is always attended.  40 steps with 8-token chunks complete five chunks (and carry a head with
@@ -801,10 +802,9 @@ def test_generated_tokens_are_indexed_and_retrieved(mode, case):
 def test_indexed_generation_argument_checks_and_device_tail():
     wl = make_workload(1, n_layers=2, shrink=8, steps=20)
     wl.chunk_size[:] = 8
-    for bad in (2, 3):
-        with pytest.raises(B.HkvError) as ei:
-            runner.setup(wl, upload_prompt=False, index_generated=1, decode_dynamic=bad)
-        assert ei.value.status == B.HKV_ESHAPE
+    with pytest.raises(B.HkvError) as ei:
+        runner.setup(wl, upload_prompt=False, index_generated=1, decode_dynamic=2)
+    assert ei.value.status == B.HKV_ESHAPE
     wl32 = make_workload(0, shrink=4, steps=1)
     with pytest.raises(B.HkvError) as ei:
         runner.setup(wl32, upload_prompt=False, index_generated=1)           # fp32 cache
@@ -813,9 +813,9 @@ def test_indexed_generation_argument_checks_and_device_tail():
     outs = []
     for device_tail in (False, True):
         dw = runner.setup(wl, index_generated=1)
-        assert dw.cache.decode_shape()[1] in (1, 4)
+        assert dw.cache.decode_shape()[1] in (1, 3, 4)
         with pytest.raises(B.HkvError):
-            dw.cache.set_decode_dynamic(3)
+            dw.cache.set_decode_dynamic(2)
         dw.cache.compress(dw.q_window, dw.k, dw.v)
         if device_tail:
             dw.cache.set_device_tail(True)
