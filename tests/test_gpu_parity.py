@@ -811,8 +811,8 @@ def test_indexed_generation_argument_checks_and_device_tail():
     assert ei.value.status == B.HKV_ESHAPE
     # tail lengths kept on the device (as a recorded step needs them) give the same bits as host bookkeeping
     outs = []
-    for device_tail in (False, True):
-        dw = runner.setup(wl, index_generated=1)
+    for device_tail, mode in ((False, 0), (True, 0), (True, 1), (True, 3), (True, 4)):
+        dw = runner.setup(wl, index_generated=1, decode_dynamic=mode)
         assert dw.cache.decode_shape()[1] in (1, 3, 4)
         with pytest.raises(B.HkvError):
             dw.cache.set_decode_dynamic(2)
@@ -830,4 +830,6 @@ def test_indexed_generation_argument_checks_and_device_tail():
         if device_tail:
             dw.cache.set_device_tail(False)
         dw.cache.close()
-    assert torch.equal(outs[0], outs[1])
+    assert torch.equal(outs[0], outs[1])                 # same shape, host or device bookkeeping: same bits
+    for o in outs[2:]:                                   # other shapes: same results up to summation order
+        assert (o.float() - outs[0].float()).abs().max().item() <= 2e-2 * outs[0].float().abs().max().item()
