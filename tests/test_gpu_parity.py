@@ -833,3 +833,20 @@ def test_indexed_generation_argument_checks_and_device_tail():
     assert torch.equal(outs[0], outs[1])                 # same shape, host or device bookkeeping: same bits
     for o in outs[2:]:                                   # other shapes: same results up to summation order
         assert (o.float() - outs[0].float()).abs().max().item() <= 2e-2 * outs[0].float().abs().max().item()
+
+
+def test_head_scores_of_sequences_without_text_or_without_visual_tokens():
+    """Sequence 0 of the batch has no text token (its heads score 0 by definition: there is no text row
+    to average), sequence 1 is all text (every token of the prompt is a row), the others are ordinary."""
+    from hkv_synth import make_prompt_queries
+    wl = make_workload(4, n_layers=1, shrink=8, steps=1)
+    lo0, hi0, hi1 = int(wl.cu_seqlens[0]), int(wl.cu_seqlens[1]), int(wl.cu_seqlens[2])
+    wl.is_visual[lo0:hi0] = 1
+    wl.is_visual[hi0:hi1] = 0
+    qp = make_prompt_queries(wl)
+    got = _device_head_scores(wl, qp)
+    ocfg = O.OracleConfig(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128, window=wl.window,
+                          dtype=wl.dtype)
+    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual)
+    assert np.all(got[0] == 0.0) and np.all(want[0] == 0.0)
+    assert np.abs(got - want).max() <= SCORE_ATOL
