@@ -243,9 +243,10 @@ def test_many_small_chunks_radix_path(chunk, k_chunks, shrink):
     _say(f"chunk {chunk} k {k_chunks} n_c {n_c}", stats)
 
 
-@pytest.mark.parametrize("n_q,n_kv,window", [(4, 4, 48), (6, 2, 16), (10, 2, 8), (12, 2, 20)])
+@pytest.mark.parametrize("n_q,n_kv,window", [(4, 4, 48), (8, 4, 32), (6, 2, 16), (8, 2, 64), (10, 2, 8), (12, 2, 20)])
 def test_other_group_sizes_and_windows(n_q, n_kv, window):
-    """Group sizes 1, 3, 5, 6 and windows that are not 32 (G * w not a multiple of 32 included)."""
+    """Group sizes 1 to 6 and windows that are not 32 (G * w not a multiple of 32 included, and G * w at its
+    limit of 256), in the three single-launch decode shapes."""
     from hkv_synth import workloads as W
     base = dict(W.CONFIGS[1])
     base.update(name=f"g{n_q // n_kv}_w{window}", n_layers=2, n_q_heads=n_q, n_kv_heads=n_kv, window=window,
@@ -255,8 +256,9 @@ def test_other_group_sizes_and_windows(n_q, n_kv, window):
         wl = make_workload(99, seed=3)
     finally:
         del W.CONFIGS[99]
-    stats = P.full_pipeline(wl)
-    _say(f"G{n_q // n_kv} w{window}", stats)
+    for mode in (1, 3, 4):
+        stats = P.full_pipeline(wl, decode_dynamic=mode)
+        _say(f"G{n_q // n_kv} w{window} mode {mode}", stats)
 
 
 @pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 3, 160), (1, 2, 288), (1, 1, 416), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
