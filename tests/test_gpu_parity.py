@@ -243,22 +243,24 @@ def test_many_small_chunks_radix_path(chunk, k_chunks, shrink):
     _say(f"chunk {chunk} k {k_chunks} n_c {n_c}", stats)
 
 
-@pytest.mark.parametrize("n_q,n_kv,window", [(4, 4, 48), (8, 4, 32), (6, 2, 16), (8, 2, 64), (10, 2, 8), (12, 2, 20)])
-def test_other_group_sizes_and_windows(n_q, n_kv, window):
+@pytest.mark.parametrize("n_q,n_kv,window,dtype", [(4, 4, 48, "bf16"), (8, 4, 32, "bf16"), (6, 2, 16, "bf16"),
+                                                   (8, 2, 64, "bf16"), (10, 2, 8, "bf16"), (12, 2, 20, "bf16"),
+                                                   (8, 2, 16, "f32"), (3, 3, 10, "f32"), (16, 2, 24, "f32")])
+def test_other_group_sizes_and_windows(n_q, n_kv, window, dtype):
     """Group sizes 1 to 6 and windows that are not 32 (G * w not a multiple of 32 included, and G * w at its
     limit of 256), in the three single-launch decode shapes."""
     from hkv_synth import workloads as W
     base = dict(W.CONFIGS[1])
-    base.update(name=f"g{n_q // n_kv}_w{window}", n_layers=2, n_q_heads=n_q, n_kv_heads=n_kv, window=window,
-                n_visual=[1200], n_text=[300], block=1200, steps=2)
+    base.update(name=f"g{n_q // n_kv}_w{window}_{dtype}", n_layers=2, n_q_heads=n_q, n_kv_heads=n_kv, window=window,
+                n_visual=[1200], n_text=[300], block=1200, steps=2, dtype=dtype)
     W.CONFIGS[99] = base
     try:
         wl = make_workload(99, seed=3)
     finally:
         del W.CONFIGS[99]
-    for mode in (1, 3, 4):
+    for mode in (1, 3, 4) if dtype == "bf16" else (1, 2, 3):
         stats = P.full_pipeline(wl, decode_dynamic=mode)
-        _say(f"G{n_q // n_kv} w{window} mode {mode}", stats)
+        _say(f"G{n_q // n_kv} w{window} {dtype} mode {mode}", stats)
 
 
 @pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 3, 160), (1, 2, 288), (1, 1, 416), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
