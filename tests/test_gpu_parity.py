@@ -854,3 +854,16 @@ def test_head_scores_of_sequences_without_text_or_without_visual_tokens():
     want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual)
     assert np.all(got[0] == 0.0) and np.all(want[0] == 0.0)
     assert np.abs(got - want).max() <= SCORE_ATOL
+
+
+@pytest.mark.parametrize("cfg_id,mode", [(1, 3), (1, 2), (1, 1), (0, 3)])
+def test_long_generation_grows_tails_across_tile_boundaries(cfg_id, mode):
+    """300 decode steps on a short prompt: every head's tail grows through several 128-row tiles that were
+    only reserved at first, the appended row lands in a different tile as it goes, and the combination
+    takes more tiles every few steps."""
+    wl = make_workload(cfg_id, n_layers=1, shrink=8, steps=300)
+    kw = dict(decode_dynamic=mode)
+    if cfg_id == 1:
+        kw["decode_tile_rows"] = 128
+    stats = P.full_pipeline(wl, **kw)
+    _say(f"300 steps cfg{cfg_id} mode {mode}", stats)
