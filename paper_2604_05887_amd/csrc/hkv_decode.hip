@@ -1076,7 +1076,11 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
     attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
     return;
   }
-  AttnItem it = cv.dynamic_items[ditem_begin + blockIdx.x];
+  // Workgroups go to the eight dies in rotation (workgroup b runs on die b % 8) and each die has its own L2.
+  // The tiles of a unit all read the unit's chunk summaries, so the dynamic tiles are dealt out in eight
+  // contiguous runs, one per die: die x takes tiles [x * xq + min(x, xr), ...) in order.
+  const int xq = n_ditems >> 3, xr = n_ditems & 7, xx = blockIdx.x & 7;
+  AttnItem it = cv.dynamic_items[ditem_begin + xx * xq + min(xx, xr) + ((int)blockIdx.x >> 3)];
   const int32_t* picks = nullptr;
   if (reselect) {
     const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
