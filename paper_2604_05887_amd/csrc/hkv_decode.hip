@@ -164,8 +164,8 @@ __device__ __forceinline__ void attn_tile(const RowMap& rm, const T* __restrict_
       if (valid) valid = resolve_row(rm, r, phys);
       uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
       if (valid) {
-        kraw = ld16(rm.kbase + phys * rm.stride + sub * 16);
-        vraw = ld16(rm.vbase + phys * rm.stride + sub * 16);
+        kraw = ld16_stream(rm.kbase + phys * rm.stride + sub * 16);
+        vraw = ld16_stream(rm.vbase + phys * rm.stride + sub * 16);
       }
       float kf[EPL], vf[EPL];
       unpack16(kraw, kf, T{});
@@ -304,9 +304,9 @@ __device__ __forceinline__ void attn_tile_bf16(const RowMap& rm, const bf16_t* _
     }
     uint4 kraw[8], vraw[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) kraw[i] = ld16(rm.kbase + off[i]);
+    for (int i = 0; i < 8; ++i) kraw[i] = ld16_stream(rm.kbase + off[i]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vraw[i] = ld16(rm.vbase + off[i]);
+    for (int i = 0; i < 8; ++i) vraw[i] = ld16_stream(rm.vbase + off[i]);
 
     // ---- scores: partial dot products, all-reduce over the mirror pair, then reduce-scatter ----
     float v[8][G];
@@ -469,9 +469,9 @@ __device__ __forceinline__ void issue_step_loads(const RowMap& rm, int row0, int
   const char* kp = rm.kbase + ((int64_t)ba * kBlkBytes + (ta ? rm.ktail : (int64_t)0)) + (uint32_t)(jv * 4 + e1) * 16u;
   const char* vp = rm.vbase + ((int64_t)bv * kBlkBytes + (tv ? rm.vtail : (int64_t)0)) + (uint32_t)qi * 16u;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) sb.ka[i] = ld16(kp + i * 256);     // i = 2 * kstep + half tile
+  for (int i = 0; i < 8; ++i) sb.ka[i] = ld16_stream(kp + i * 256);     // i = 2 * kstep + half tile
 #pragma unroll
-  for (int i = 0; i < 8; ++i) sb.va[i] = ld16(vp + i * 256);     // i = 16-dim block of the output
+  for (int i = 0; i < 8; ++i) sb.va[i] = ld16_stream(vp + i * 256);     // i = 16-dim block of the output
 }
 
 struct NoHook { __device__ __forceinline__ void operator()() const {} };
@@ -537,7 +537,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
       resolve_block<DYN>(rm, row0 + nst * 32 + 8 * jv, bv_next, nv_next, tv_next);
       const char* kp = rm.kbase + ((int64_t)ba * kBlkBytes + (ta ? rm.ktail : (int64_t)0)) + k_lane;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ka[i] = ld16(kp + i * 256);
+      for (int i = 0; i < 8; ++i) ka[i] = ld16_stream(kp + i * 256);
     }
     float sc[8];
 #pragma unroll
@@ -574,7 +574,7 @@ __device__ __forceinline__ void attn_tile_mfma(const RowMap& rm, const bf16_t* _
     if (more) {
       const char* vp = rm.vbase + ((int64_t)bv_next * kBlkBytes + (tv_next ? rm.vtail : (int64_t)0)) + v_lane;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) va[i] = ld16(vp + i * 256);
+      for (int i = 0; i < 8; ++i) va[i] = ld16_stream(vp + i * 256);
     }
     nv = nv_next;
     st = nst;

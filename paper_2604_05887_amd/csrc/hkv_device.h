@@ -71,6 +71,13 @@ __device__ __forceinline__ uint4 pack16(const float (&f)[8], bf16_t) {
 }
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+// 16-byte load of data that is read once per launch (cache rows): marked non-temporal, so that the rows
+// streaming through do not push the small reused arrays (chunk summaries, descriptors, queries) out of the L2.
+typedef unsigned int u32x4_stream __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld16_stream(const void* p) {
+  const u32x4_stream v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_stream*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ void st16(void* p, const uint4& v) { *reinterpret_cast<uint4*>(p) = v; }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
