@@ -293,6 +293,8 @@ def main() -> int:
                 if wl.head_type[b, l, h] != 0:
                     link_bytes += 2 * R * copies[0].cache.unit_info(b, l, h)[0]
     tile_rows, dyn_mode = copies[0].cache.decode_shape()
+    call_tile_rows, call_tiles = copies[0].cache.call_tiling()            # of the timed call over all layers
+    layer_tile_rows, layer_tiles = copies[0].cache.call_tiling(0, 1)      # of a call over one layer
     if args.index_generated:     # rows and summaries depend on the tail length: the library's own formula
         a_bytes, b_bytes = copies[0].cache.step_bytes(int(round(tail_prof))), 0
     elif dyn_mode != 2:        # the main launch also reads the dynamic heads' gathered rows
@@ -483,7 +485,8 @@ def main() -> int:
                         "host_link_peak_gbs": 64.0},      # PCIe 5.0 x16, one direction, before packet overhead
         "index_generated": bool(args.index_generated),
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
-        "decode_shape": {"tile_rows": tile_rows, "dynamic_mode": dyn_mode, "tuned_us_per_step": tuned_us},
+        "decode_shape": {"tile_rows": call_tile_rows, "tiles": call_tiles, "tile_rows_one_layer_call": layer_tile_rows,
+                         "dynamic_mode": dyn_mode, "tuned_us_per_step": tuned_us},
         "kernel_us": {"main_launch": round(a_us, 2), "second_launch": round(b_us, 2),
                       "attn_merge_kernel": round(merge_us, 2)},
         "dynamic_tiles_gbs": round(b_gbs, 1),

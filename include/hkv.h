@@ -235,6 +235,16 @@ HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int la
  * hkv_config.decode_dynamic.  Either pointer may be NULL. */
 HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, int32_t* dynamic_mode);
 
+/* The tiling a decode call over layers [layer_begin, layer_end) uses.  bf16 caches under the automatic
+ * tile rule (decode_tile_rows = 0) carry a second tiling of 1024-row tiles besides the one that
+ * hkv_cache_decode_shape reports; a call takes the large tiles when it has more small tiles than the
+ * device has compute units and the large tiles give every tile a compute unit of its own (small
+ * whole-model steps), the small tiles otherwise (per-layer calls, large steps).  Same results up to
+ * fp32 summation order.  *tile_rows = rows per tile of such a call, *n_tiles = its tiles (tail at
+ * full capacity).  Either pointer may be NULL. */
+HKV_API int hkv_cache_call_tiling(const hkv_cache* cache, int layer_begin, int layer_end, int32_t* tile_rows,
+                                  int32_t* n_tiles);
+
 /* Tail bookkeeping for callers that record hkv_decode_attn into a HIP graph.  Normally the host mirrors
  * every head's tail length and passes it to the kernels as an argument, which a recorded call would
  * replay unchanged.  With enable = 1 decode calls read and advance the per-layer counters in device

@@ -26,7 +26,7 @@ HKV_ABI_VERSION = 1
 EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_query_tier_sizes", "hkv_cache_create_tiered", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
-    "hkv_cache_decode_shape", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
+    "hkv_cache_decode_shape", "hkv_cache_call_tiling", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
     "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read", "hkv_head_scores_workspace_size", "hkv_head_scores", "hkv_focus_counts_workspace_size", "hkv_focus_counts", "hkv_allocate_budgets",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
@@ -83,6 +83,7 @@ def load_library() -> C.CDLL:
                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_step_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_uint64)]
     lib.hkv_cache_decode_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.hkv_cache_call_tiling.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_set_decode_dynamic.argtypes = [vp, C.c_int32]
     lib.hkv_cache_set_device_tail.argtypes = [vp, i32, vp]
     lib.hkv_cache_export.argtypes = [vp, i32, i32, i32, i32, vp, sz, C.POINTER(sz), vp]
@@ -272,6 +273,14 @@ def hkv_cache_decode_shape(handle: int) -> Tuple[int, int]:
     return int(t.value), int(m.value)
 
 
+def hkv_cache_call_tiling(handle: int, layer_begin: int, layer_end: int) -> Tuple[int, int]:
+    """(rows per tile, tiles) of a decode call over the given layers."""
+    t, n = C.c_int32(0), C.c_int32(0)
+    _check(load_library().hkv_cache_call_tiling(handle, layer_begin, layer_end, C.byref(t), C.byref(n)),
+           "hkv_cache_call_tiling")
+    return int(t.value), int(n.value)
+
+
 def hkv_cache_set_decode_dynamic(handle: int, mode: int) -> None:
     _check(load_library().hkv_cache_set_decode_dynamic(handle, mode), "hkv_cache_set_decode_dynamic")
 
@@ -446,6 +455,10 @@ class HybridKVCache:
 
     def decode_shape(self):
         return hkv_cache_decode_shape(self.handle)
+
+    def call_tiling(self, layer_begin=0, layer_end=None):
+        le = self.cfg.n_layers if layer_end is None else layer_end
+        return hkv_cache_call_tiling(self.handle, layer_begin, le)
 
     def set_decode_dynamic(self, mode: int):
         hkv_cache_set_decode_dynamic(self.handle, mode)

@@ -8,6 +8,7 @@
 #include <cstdint>
 
 #include "hkv.h"
+#include "hkv_device.h"
 
 namespace {
 
@@ -22,7 +23,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const char* __restrict
     uint4 x[kLoadsInFlight];
 #pragma unroll
     for (int i = 0; i < kLoadsInFlight; ++i)
-      x[i] = *reinterpret_cast<const uint4*>(p + (r * kLoadsInFlight + i) * 4096);
+      x[i] = hkv::ld16_stream(p + (r * kLoadsInFlight + i) * 4096);   // non-temporal, as the cache rows are read
 #pragma unroll
     for (int i = 0; i < kLoadsInFlight; ++i) acc += x[i].x ^ x[i].w;
   }

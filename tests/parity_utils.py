@@ -124,9 +124,10 @@ def compare_compress(wl, dw, ocache, stats: Dict[str, float]) -> Dict[Tuple[int,
 
 
 def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float], layer_ranges=None,
-                           append: bool = True, oracle_layers=None):
+                           append: bool = True, oracle_layers=None, layer_ranges_by_step=None):
     """n_steps decode steps on both sides; the oracle takes the device's chunk summaries (they may
-    differ from its own by one rounding) and, inside a tie band, the device's chunk picks."""
+    differ from its own by one rounding) and, inside a tie band, the device's chunk picks.
+    layer_ranges_by_step[s], if given and not None, replaces layer_ranges for step s."""
     L, Bn = wl.n_layers, wl.batch
     tdt = runner.torch_dtype(wl.dtype)
     out = torch.empty((L, Bn, wl.n_q_heads, wl.head_dim), dtype=tdt, device="cuda:0")
@@ -140,7 +141,10 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
         q = runner.to_device(wl.q_steps[s], wl.dtype)
         kn = runner.to_device(wl.k_new[s], wl.dtype) if append else None
         vn = runner.to_device(wl.v_new[s], wl.dtype) if append else None
-        for (lb, le) in layer_ranges:
+        ranges = layer_ranges
+        if layer_ranges_by_step is not None and layer_ranges_by_step[s] is not None:
+            ranges = layer_ranges_by_step[s]
+        for (lb, le) in ranges:
             dw.cache.decode_attn(q[lb:le], None if kn is None else kn[lb:le], None if vn is None else vn[lb:le],
                                  out[lb:le], layer_begin=lb, layer_end=le)
         torch.cuda.synchronize()

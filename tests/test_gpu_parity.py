@@ -867,3 +867,34 @@ def test_long_generation_grows_tails_across_tile_boundaries(cfg_id, mode):
         kw["decode_tile_rows"] = 128
     stats = P.full_pipeline(wl, **kw)
     _say(f"300 steps cfg{cfg_id} mode {mode}", stats)
+
+
+# ---- two tilings in one cache: small whole-model steps take the large tiles, per-layer calls the small ones ----
+
+def test_whole_model_call_takes_large_tiles_and_per_layer_calls_small_ones():
+    """Config 1 at full size (28 layers, 8192-token prompt): a call over all layers has more 256-row tiles
+    than the device has compute units and fewer 1024-row tiles, so it runs the second tiling; a call per
+    layer runs the first.  Both are checked against the oracle on sampled layers at every step, with
+    the tails growing through both kinds of call in turn."""
+    wl = make_workload(1, steps=4)
+    assert wl.n_layers == 28
+    layers = [0, 13, 27]
+    dw = runner.setup(wl)
+    tile, mode = dw.cache.decode_shape()
+    whole = dw.cache.call_tiling()
+    one = dw.cache.call_tiling(5, 6)
+    print(f"\n[two tilings] cache tile {tile} mode {mode}; whole-model call {whole}, one layer {one}", flush=True)
+    assert tile == 256 and whole[0] == 1024 and one[0] == 256 and whole[1] <= 256
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    torch.cuda.synchronize()
+    ocfg, oplan = P.oracle_setup(wl)
+    ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers)
+    stats = {}
+    overrides = P.compare_compress(wl, dw, ocache, stats)
+    if overrides:
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers, keep_override=overrides)
+    per_layer = [(l, l + 1) for l in range(28)]
+    P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers,
+                             layer_ranges_by_step=[None, per_layer, None, [(0, 14), (14, 28)]])
+    _say("two tilings", stats)
+    dw.cache.close()
