@@ -95,9 +95,11 @@ typedef struct {
   int32_t max_new_tokens;   /* capacity of every head's uncompressed decode tail */
   float softmax_scale;      /* 0 -> 1/sqrt(head_dim) */
   int32_t decode_tile_rows; /* rows per split-K tile of decode attention: 0 = chosen from the amount of
-                               work; bf16 caches also accept any multiple of 32 from 128 to 4096
-                               (tuning knob; the result does not depend on it beyond fp32 summation
-                               order) */
+                               work (a bf16 cache then also carries a tiling of 1024-row tiles and
+                               every call takes the one that suits its tile count, see
+                               hkv_cache_call_tiling); bf16 caches also accept any multiple of 32 from
+                               128 to 4096, which every call then uses (tuning knob; the result does
+                               not depend on it beyond fp32 summation order) */
   int32_t decode_dynamic;   /* how a decode step runs the dynamic heads: 1 = one workgroup per head does
                                chunk selection, attention and the output inside the main launch;
                                2 = chunk selection in the main launch, split-K tiles over many

@@ -263,7 +263,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 }
 
 // Tile size: fp32 caches use 128 rows; bf16 caches start at 256 rows and double (up to 1024) while the
-// whole cache still yields at least 2048 tiles, so that small steps keep every CU busy and large
+// whole cache still yields at least 1024 tiles (four per compute unit), so that small steps keep every CU busy and large
 // ones amortise the per-tile cost.
 // Dynamic heads: every dynamic tile repeats its head's chunk selection, so that the step is one launch
 // plus the combination, as long as the repeated reads of the chunk summaries stay below a quarter of
@@ -281,7 +281,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
     rc = plan_layout_tile(cfg, plan, lo, tile, tiered);
     while (rc == HKV_OK && tile < kTileBf16Max) {
       Layout next;
-      if (plan_layout_tile(cfg, plan, next, tile * 2, tiered) != HKV_OK || next.n_items < 2048) break;
+      if (plan_layout_tile(cfg, plan, next, tile * 2, tiered) != HKV_OK || next.n_items < 1024) break;
       tile *= 2;
       lo = std::move(next);
     }
