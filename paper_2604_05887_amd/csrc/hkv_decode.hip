@@ -763,6 +763,8 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
       const int ch = lane + 64 * m;
       key[m] = ch < n_c ? float_order_key(sig[ch]) : 0u;   // 0 is below every candidate threshold
     }
+    // (a candidate that exactly k keys reach already separates the picks from the rest: the search stops
+    // there, usually a dozen bits in, and the code below picks the keys at or above it)
     uint32_t thr = 0;
 #pragma unroll 4
     for (int bit = 31; bit >= 0; --bit) {
@@ -771,6 +773,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
 #pragma unroll
       for (int m = 0; m < 4; ++m) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[m] >= cand));
       if (cnt >= k) thr = cand;                             // wave-uniform
+      if (cnt == k) break;
     }
     const unsigned long long below = (1ull << lane) - 1ull;
     int n_gt = 0, gt_before = 0, eq_before = 0;
