@@ -197,7 +197,9 @@ __device__ __forceinline__ uint32_t block_kth_largest(const uint32_t (&key)[N], 
     for (int e = 0; e < N; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= lo + cand));
     if ((tid & 63) == 0) cnt[buf][wv] = c;
     __syncthreads();                       // the other buffer is rewritten only after the next barrier
-    if (cnt[buf][0] + cnt[buf][1] + cnt[buf][2] + cnt[buf][3] >= kth) thr = cand;
+    const int total = cnt[buf][0] + cnt[buf][1] + cnt[buf][2] + cnt[buf][3];
+    if (total >= kth) thr = cand;
+    if (total == kth) break;               // block-uniform; the candidate separates the kth largest from the rest
     buf ^= 1;
   }
   return lo + thr;
@@ -322,7 +324,10 @@ __global__ __launch_bounds__(256) void row_topk_reg_kernel(const float* __restri
   }
   above = block_sum(above, red);
   n_gt = block_sum(n_gt, red);             // exact: at most 2^24 keys
-  if (tid == 0) row_value[blockIdx.x] = (above + ((float)kt - n_gt) * fast_exp2(key_to_float(thr) - m)) / z;
+  // keys equal to the threshold fill the places left; a threshold that is no key of the row (the search stops
+  // early at a value that separates the kt largest) leaves none, and its bit pattern need not be a number
+  const float ties = (float)kt - n_gt;
+  if (tid == 0) row_value[blockIdx.x] = (above + (ties > 0.f ? ties * fast_exp2(key_to_float(thr) - m) : 0.f)) / z;
 }
 
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
@@ -366,6 +371,9 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&key)[N], i
       c = wave_total(c);
     }
     if (c >= kth) thr = cand;
+    // exactly kth keys at or above the candidate: it separates them from the rest, which is all the callers
+    // need (a bound from below, or the sum of the weights at or above it), so the remaining bits are skipped
+    if (c == kth) break;
   }
   return lo + thr;
 }
@@ -502,7 +510,9 @@ void row_topk_wave_kernel(const float* __restrict__ logits, int64_t head_stride,
     n_gt = wave_total(my_gt);
   }
   above = sum64(above);
-  if (lane == 0) row_value[gr] = (above + (float)(kt - n_gt) * weight_of_key(thr)) / z;
+  // keys equal to the threshold fill the places left; a threshold that is no key of the row (the search stops
+  // early at a value that separates the kt largest) leaves none, and its bit pattern need not be a number
+  if (lane == 0) row_value[gr] = (above + (kt > n_gt ? (float)(kt - n_gt) * weight_of_key(thr) : 0.f)) / z;
 }
 
 // Cumulative focus count (Section 2.1, Eq. 1).  grid = rows of the pass (KV heads x G x steps), block = 256
