@@ -263,8 +263,8 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 }
 
 // Tile size: fp32 caches use 128 rows; bf16 caches start at 256 rows and double (up to 1024) while the
-// whole cache still yields at least 1024 tiles (four per compute unit), so that small steps keep every CU busy and large
-// ones amortise the per-tile cost.
+// whole cache still yields three tiles per compute unit (one full round of resident workgroups), so that
+// small steps keep every compute unit busy and large ones amortise the per-tile cost.
 // Dynamic heads: every dynamic tile repeats its head's chunk selection, so that the step is one launch
 // plus the combination, as long as the repeated reads of the chunk summaries stay below a quarter of
 // the step's bytes (they mostly hit the L2); with many small chunks the selection runs once per head
@@ -272,6 +272,7 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 // capacity included; bf16 caches) are not split at all: measured on the 7B shape, one wide workgroup per
 // head is ahead of the split-K shapes up to about that length and behind them beyond.
 constexpr int kUnitShapeMaxRows = 768;
+constexpr int kDeviceCus = 256;          // compute units of the device this library is written for (MI355X)
 int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool tiered = false) {
   int rc;
   if (cfg && cfg->dtype != HKV_BF16) rc = plan_layout_tile(cfg, plan, lo, kTileF32, tiered);
@@ -281,7 +282,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
     rc = plan_layout_tile(cfg, plan, lo, tile, tiered);
     while (rc == HKV_OK && tile < kTileBf16Max) {
       Layout next;
-      if (plan_layout_tile(cfg, plan, next, tile * 2, tiered) != HKV_OK || next.n_items < 1024) break;
+      if (plan_layout_tile(cfg, plan, next, tile * 2, tiered) != HKV_OK || next.n_items < 3 * kDeviceCus) break;
       tile *= 2;
       lo = std::move(next);
     }
