@@ -871,7 +871,8 @@ def test_long_generation_grows_tails_across_tile_boundaries(cfg_id, mode):
 
 # ---- two tilings in one cache: small whole-model steps take the large tiles, per-layer calls the small ones ----
 
-def test_whole_model_call_takes_large_tiles_and_per_layer_calls_small_ones():
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_whole_model_call_takes_large_tiles_and_per_layer_calls_small_ones(mode):
     """Config 1 at full size (28 layers, 8192-token prompt): a call over all layers has more 256-row tiles
     than the device has compute units and fewer 1024-row tiles, so it runs the second tiling; a call per
     layer runs the first.  Both are checked against the oracle on sampled layers at every step, with
@@ -879,7 +880,7 @@ def test_whole_model_call_takes_large_tiles_and_per_layer_calls_small_ones():
     wl = make_workload(1, steps=4)
     assert wl.n_layers == 28
     layers = [0, 13, 27]
-    dw = runner.setup(wl)
+    dw = runner.setup(wl, decode_dynamic=mode)       # 0: the default shape (3 here); 1 and 2 take the same tilings
     tile, mode = dw.cache.decode_shape()
     whole = dw.cache.call_tiling()
     one = dw.cache.call_tiling(5, 6)
