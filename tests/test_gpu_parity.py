@@ -899,3 +899,30 @@ def test_whole_model_call_takes_large_tiles_and_per_layer_calls_small_ones(mode)
                              layer_ranges_by_step=[None, per_layer, None, [(0, 14), (14, 28)]])
     _say("two tilings", stats)
     dw.cache.close()
+
+
+@pytest.mark.parametrize("variant", ["indexed", "host_tier"])
+def test_large_tiles_with_indexed_generation_and_with_the_host_tier(variant):
+    """The 1024-row tiling of a whole-model call together with the variants that change what a dynamic tile
+    reads: generated tokens in the chunk index (36 steps complete a 32-token chunk in every dynamic head) and
+    prompt rows in host memory.  Config 1 at full size, oracle on sampled layers, every step."""
+    steps = 36 if variant == "indexed" else 3
+    wl = make_workload(1, steps=steps)
+    layers = [5, 20]
+    kw = dict(index_generated=1) if variant == "indexed" else dict(host_tier=True)
+    dw = runner.setup(wl, decode_dynamic=3, **kw)
+    whole = dw.cache.call_tiling()
+    assert whole[0] == 1024 and whole[1] <= 256
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    torch.cuda.synchronize()
+    ocfg, oplan = P.oracle_setup(wl, index_generated=variant == "indexed")
+    ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers)
+    stats = {}
+    overrides = P.compare_compress(wl, dw, ocache, stats)
+    if overrides:
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers, keep_override=overrides)
+    P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers)
+    _say(f"large tiles, {variant}", stats)
+    if variant == "indexed":
+        assert stats.get("generated_chunks_indexed", 0) > 0
+    dw.cache.close()
