@@ -926,3 +926,31 @@ def test_large_tiles_with_indexed_generation_and_with_the_host_tier(variant):
     if variant == "indexed":
         assert stats.get("generated_chunks_indexed", 0) > 0
     dw.cache.close()
+
+
+def test_large_tiles_with_tail_lengths_kept_on_the_device():
+    """Whole-model calls of config 1 at full size (the 1024-row tiling), tail lengths read from the device
+    counters as a recorded step needs them: the same bits as with host bookkeeping, step after step, and
+    the host mirror is back in step afterwards."""
+    wl = make_workload(1, steps=5)
+    outs = []
+    for device_tail in (False, True):
+        dw = runner.setup(wl)
+        assert dw.cache.call_tiling()[0] == 1024
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+        if device_tail:
+            dw.cache.set_device_tail(True)
+        out = torch.empty((wl.n_layers, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+        res = []
+        for s in range(wl.steps):
+            q, kn, vn = (runner.to_device(x[s], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+            dw.cache.decode_attn(q, kn, vn, out)
+            torch.cuda.synchronize()
+            res.append(out.clone())
+        outs.append(torch.stack(res))
+        if device_tail:
+            dw.cache.set_device_tail(False)
+            Kr = dw.cache.export(B.HKV_X_K_ROWS, 0, 27, 3)
+            assert np.array_equal(Kr[-wl.steps:], wl.k_new[:, 27, 0, 3])
+        dw.cache.close()
+    assert torch.equal(outs[0], outs[1])
