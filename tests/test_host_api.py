@@ -75,6 +75,7 @@ def test_argument_errors_are_reported_on_the_host(lib):
     # decode entry point rejects a null cache before touching the device
     assert lib.hkv_decode_attn(None, 0, 1, None, None, None, None, None, 0, None) == B.HKV_EINVAL
     assert lib.hkv_compress(None, 0, 1, None, None, None, None, 0, None) == B.HKV_EINVAL
+    assert lib.hkv_cache_call_tiling(None, 0, 1, None, None) == B.HKV_EINVAL
 
 
 @pytest.mark.parametrize("rule", ["text_exempt", "literal_total"])
