@@ -534,8 +534,8 @@ __global__ __launch_bounds__(256) void row_focus_kernel(const float* __restrict_
   uint32_t t_key = 0;
   int r_adm = C;
   if (kt < C)
-    radix_select<256>(C, kt, [&](int j, uint32_t& key) { key = float_order_key(row[j]); return true; }, hist, bc, t_key,
-                      r_adm);
+    radix_select<256, true>(C, kt, [&](int j, uint32_t& key) { key = float_order_key(row[j]); return true; }, hist, bc,
+                            t_key, r_adm);
   int base_eq = 0;
   for (int j0 = 0; j0 < C; j0 += 256) {              // uniform trip count
     const int j = j0 + tid;

@@ -241,7 +241,7 @@ __global__ __launch_bounds__(1024) void select_kernel(CacheView cv, int static_b
   int r_adm = 0;
   if (d.m_sel >= d.n_cand) { T_key = 0; r_adm = d.n_cand; }       // everything (keys are >= 0)
   else if (d.m_sel > 0) {
-    radix_select<1024>(C, d.m_sel,
+    radix_select<1024, true>(C, d.m_sel,
                        [&](int j, uint32_t& key) { if (!is_cand(j)) return false; key = float_to_bits(sc[j]); return true; },
                        hist, bc, T_key, r_adm);
   }

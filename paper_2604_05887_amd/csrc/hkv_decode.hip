@@ -802,7 +802,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
   uint32_t T_key = 0;
   int r_adm = n_c;
   if (k_sel < n_c) {
-    radix_select<NT>(n_c, k_sel,
+    radix_select<NT, true>(n_c, k_sel,
                      [&](int j, uint32_t& key) { key = float_order_key(sig[j]); return true; },
                      hist, bc, T_key, r_adm);
   }

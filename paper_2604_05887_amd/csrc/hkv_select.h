@@ -17,7 +17,10 @@ __device__ __forceinline__ uint32_t float_order_key(float f) {
 // candidates equal to T belong to the top m_sel (>= 1).  Requires 0 < m_sel <= #candidates.
 // keyfn(j, key) returns whether j is a candidate and, if so, its key.
 // `hist` is 256 words of shared memory, `bc` 2 words.  All NT threads of the block must call.
-template <int NT, class KeyFn>
+// EARLY: the search may stop at a prefix all of whose candidates are wanted; T is then the smallest key
+// with that prefix -- no candidate's key, in general -- and still splits the candidates as above (key > T:
+// in; key == T: in for the first r_adm of them; else out).  For callers that use T only in that way.
+template <int NT, bool EARLY = false, class KeyFn>
 __device__ __forceinline__ void radix_select(int n, int m_sel, KeyFn keyfn, uint32_t* hist, uint32_t* bc,
                                              uint32_t& T, int& r_adm) {
   const int tid = thread_index();
@@ -47,15 +50,20 @@ __device__ __forceinline__ void radix_select(int n, int m_sel, KeyFn keyfn, uint
           else { cum += h2;
             if (cum + h1 >= remaining) d = 1;
             else { cum += h1; d = 0; } } }
+        const int in_bin = d == 3 ? h3 : d == 2 ? h2 : d == 1 ? h1 : h0;
         bc[0] = (uint32_t)(4 * tid + d);
-        bc[1] = (uint32_t)(remaining - cum);
+        // top bit: every candidate of the bin is wanted, so the bin's smallest possible key already separates
+        // the top m_sel from the rest and the remaining digits need not be resolved
+        bc[1] = (uint32_t)(remaining - cum) | (remaining - cum == in_bin ? 0x80000000u : 0u);
       }
     }
     __syncthreads();
     prefix |= bc[0] << shift;
     mask |= 0xFFu << shift;
-    remaining = (int)bc[1];
+    const uint32_t word = bc[1];
+    remaining = (int)(word & 0x7fffffffu);
     __syncthreads();
+    if (EARLY && (word >> 31)) break;          // block-uniform
   }
   T = prefix;
   r_adm = remaining;
