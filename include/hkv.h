@@ -50,6 +50,10 @@ extern "C" {
 
 #define HKV_ABI_VERSION 1u
 
+/* Size of the split-K record array that lives inside the library, one copy per GPU, held from the
+ * library's load to the end of the process (see hkv_decode_attn_noalloc). */
+#define HKV_NOALLOC_SCRATCH_BYTES (16u << 20)
+
 #ifndef HKV_API
 #define HKV_API __attribute__((visibility("default")))
 #endif
@@ -201,6 +205,23 @@ HKV_API int hkv_compress(hkv_cache* cache, int layer_begin, int layer_end, const
  * Returns HKV_ENOSPACE (nothing enqueued) when a tail would exceed max_new_tokens. */
 HKV_API int hkv_decode_attn(hkv_cache* cache, int layer_begin, int layer_end, const void* q, const void* k_new,
                     const void* v_new, void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* hkv_decode_attn for callers that can neither allocate device memory nor hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks,
+ * kernels and results as hkv_decode_attn, except that the split-K records go to an array of
+ * HKV_NOALLOC_SCRATCH_BYTES inside the library (located on the cache's device when the cache was
+ * created) instead of a caller workspace.  The call allocates and frees nothing and makes no runtime
+ * call besides its kernel launches and a device-id query.
+ *   - Returns HKV_ENOSPACE (nothing enqueued) when the records of the call's tiles -- per tile
+ *     (n_q_heads / n_kv_heads) * 512 + 64 bytes, tiles as hkv_cache_call_tiling reports them -- exceed
+ *     the array: use a smaller layer range or hkv_decode_attn.
+ *   - Returns HKV_ESTATE when the current device is not the one the cache was created on.
+ *   - All calls on one GPU share that GPU's array: calls that can overlap there (different streams
+ *     without an ordering between them, several host threads) race on it and must be serialised by
+ *     the caller.  The array keeps the previous call's records; every record a call reads it has
+ *     written first, so nothing needs clearing. */
+HKV_API int hkv_decode_attn_noalloc(hkv_cache* cache, int layer_begin, int layer_end, const void* q,
+                                    const void* k_new, const void* v_new, void* out, void* stream);
 
 /* Uncompressed decode attention over caller-held K/V, the comparison kernel for the decode path:
  * every head attends all tokens of its sequence.

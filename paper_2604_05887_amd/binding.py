@@ -22,9 +22,10 @@ HKV_STATIC, HKV_DYNAMIC = 0, 1
 (HKV_X_KEPT_IDX, HKV_X_SCORES, HKV_X_CHUNK_SEL, HKV_X_CHUNK_SIGMA, HKV_X_CHUNK_MEAN, HKV_X_K_ROWS,
  HKV_X_V_ROWS) = range(7)
 HKV_ABI_VERSION = 1
+HKV_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 EXPORTED_SYMBOLS = (
-    "hkv_query_sizes", "hkv_cache_create", "hkv_query_tier_sizes", "hkv_cache_create_tiered", "hkv_compress", "hkv_decode_attn", "hkv_full_workspace_size",
+    "hkv_query_sizes", "hkv_cache_create", "hkv_query_tier_sizes", "hkv_cache_create_tiered", "hkv_compress", "hkv_decode_attn", "hkv_decode_attn_noalloc", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
     "hkv_cache_decode_shape", "hkv_cache_call_tiling", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
     "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read", "hkv_head_scores_workspace_size", "hkv_head_scores", "hkv_focus_counts_workspace_size", "hkv_focus_counts", "hkv_allocate_budgets",
@@ -73,6 +74,7 @@ def load_library() -> C.CDLL:
     lib.hkv_cache_create_tiered.argtypes = [C.POINTER(hkv_config), C.POINTER(hkv_plan), vp, sz, vp, sz, C.POINTER(vp)]
     lib.hkv_compress.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.hkv_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.hkv_decode_attn_noalloc.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
     lib.hkv_full_workspace_size.argtypes = [C.POINTER(hkv_config), C.c_int32, C.POINTER(C.c_int32), i32, C.POINTER(sz)]
     lib.hkv_full_decode_attn.argtypes = [C.POINTER(hkv_config), C.c_int32, C.POINTER(C.c_int32), i32, vp, vp, vp, vp,
                                          vp, sz, vp]
@@ -218,6 +220,11 @@ def hkv_decode_attn(handle: int, layer_begin: int, layer_end: int, q, k_new, v_n
     _check(load_library().hkv_decode_attn(handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new),
                                           _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream)),
            "hkv_decode_attn")
+
+
+def hkv_decode_attn_noalloc(handle: int, layer_begin: int, layer_end: int, q, k_new, v_new, out, stream=None) -> None:
+    _check(load_library().hkv_decode_attn_noalloc(handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                  _ptr(out), _stream(stream)), "hkv_decode_attn_noalloc")
 
 
 def hkv_reselect_chunks(handle: int, layer_begin: int, layer_end: int, stream=None) -> None:
@@ -439,6 +446,10 @@ class HybridKVCache:
         le = self.cfg.n_layers if layer_end is None else layer_end
         hkv_decode_attn(self.handle, layer_begin, le, q, k_new, v_new, out, self.workspace, self.workspace_bytes,
                         stream)
+
+    def decode_attn_noalloc(self, q, k_new, v_new, out, layer_begin=0, layer_end=None, stream=None):
+        le = self.cfg.n_layers if layer_end is None else layer_end
+        hkv_decode_attn_noalloc(self.handle, layer_begin, le, q, k_new, v_new, out, stream)
 
     def export(self, what, seq, layer, head, stream=None):
         return hkv_cache_export(self.handle, what, seq, layer, head, self.cfg.dtype, stream)

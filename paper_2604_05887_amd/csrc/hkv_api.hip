@@ -5,6 +5,7 @@
 #include <cstring>
 #include <new>
 #include <memory>
+#include <mutex>
 #include <vector>
 
 #include "hkv_internal.h"
@@ -43,10 +44,40 @@ int validate_config(const hkv_config* cfg) {
 
 using namespace hkv;
 
+// Split-K records of hkv_decode_attn_noalloc: one array per GPU inside the library's code object, so that
+// the call needs neither an allocation nor a caller workspace.  In host code the array's name is only a
+// handle for the runtime, not a device address: scratch_of_current_device() asks the runtime for the
+// array's address on the current device (every GPU holds its own copy) and keeps it, and everything
+// that touches the array's memory -- kernel arguments included -- uses that address.
+static __device__ __align__(256) unsigned char scratch[HKV_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device (looked up once per device); *device gets the device id.
+hipError_t scratch_of_current_device(void** ptr, int* device) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p || reinterpret_cast<uintptr_t>(p) % kAlign != 0) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  *device = dev;
+  return hipSuccess;
+}
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t elem_size(int dtype) { return dtype == HKV_BF16 ? 2 : 4; }
 
@@ -328,6 +359,8 @@ struct hkv_cache {
   std::vector<hipEvent_t> events;     // 6 per profiled decode call: start and stop of up to three kernels
   int prof_calls = 0, prof_max = 0;
   int n_cus = 256;                    // compute units of the device the cache lives on
+  int device = -1;                    // device that was current when the cache was created
+  void* scratch_dev = nullptr;        // that device's copy of the library's split-K record array
   CacheView cv_coarse;                // cv with the tables of the coarse tiling (if lo.coarse)
   hipStream_t prof_stream = nullptr;  // stream of the profiled calls
   std::vector<uint8_t> prof_mask;     // per profiled call: bit j set if kernel j was launched
@@ -405,6 +438,9 @@ static int create_cache(const hkv_config* cfg, const hkv_plan* plan, void* cache
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       c->n_cus = cus;
   }
+  // set-up is where the library's own record array is located on this device (hkv_decode_attn_noalloc
+  // itself then makes no runtime call besides its launches)
+  if (scratch_of_current_device(&c->scratch_dev, &c->device) != hipSuccess) { (void)hipGetLastError(); delete c; return HKV_EHIP; }
   c->arena = static_cast<char*>(cache_dev);
   c->host_tail.assign(cfg->n_layers, 0);
   c->compressed.assign(cfg->n_layers, 0);
@@ -609,18 +645,25 @@ int hkv_cache_call_tiling(const hkv_cache* c, int lb, int le, int32_t* tile_rows
   return HKV_OK;
 }
 
-int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new, void* out,
-                    void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks shared by the decode entry points (everything but the workspace).
+static int check_decode_args(const hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new,
+                             const void* out) {
   int rc = check_range(c, lb, le);
   if (rc != HKV_OK) return rc;
-  if (!q || !out || !workspace) return HKV_EINVAL;
+  if (!q || !out) return HKV_EINVAL;
   if ((k_new == nullptr) != (v_new == nullptr)) return HKV_EINVAL;
-  if (!aligned16(q) || !aligned16(out) || !aligned16(workspace) || !aligned16(k_new) || !aligned16(v_new)) return HKV_EALIGN;
-  if (workspace_bytes < c->lo.ws_bytes) return HKV_ENOSPACE;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new)) return HKV_EALIGN;
   for (int l = lb; l < le; ++l) {
     if (!c->compressed[l]) return HKV_ESTATE;
     if (k_new && !c->device_tail && c->host_tail[l] + 1 > c->cfg.max_new_tokens) return HKV_ENOSPACE;
   }
+  return HKV_OK;
+}
+
+// The launches of one decode step over layers [lb, le), arguments already checked.  parts / parts_ml: the
+// split-K records of the call's tiles ([tiles][G][128] floats) and their (max, sum) lines ([tiles][16] floats).
+static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new, void* out,
+                           float* parts, float* parts_ml, void* stream) {
   const bool use_coarse = call_uses_coarse_tiling(c, lb, le);
   const Layout& lo = use_coarse ? *c->lo.coarse : c->lo;
   const CacheView& cv = use_coarse ? c->cv_coarse : c->cv;
@@ -639,8 +682,6 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   const bool prof = c->prof_max > 0 && c->prof_calls < c->prof_max;
   hipEvent_t* ev = prof ? &c->events[(size_t)6 * c->prof_calls] : none;
   hipError_t e = hipSuccess;
-  float* parts = static_cast<float*>(workspace);
-  float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + lo.ws_o_bytes);
   const int dt = c->cfg.dtype, app = k_new ? 1 : 0;
   const int mode = c->lo.mode;
   const int resident = 3 * c->n_cus;      // workgroups resident at once (three per compute unit)
@@ -690,6 +731,39 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   }
   if (k_new && !c->device_tail) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
   return HKV_OK;
+}
+
+int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new, void* out,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_decode_args(c, lb, le, q, k_new, v_new, out);
+  if (rc != HKV_OK) return rc;
+  if (!workspace) return HKV_EINVAL;
+  if (!aligned16(workspace)) return HKV_EALIGN;
+  if (workspace_bytes < c->lo.ws_bytes) return HKV_ENOSPACE;
+  const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
+  return decode_launches(c, lb, le, q, k_new, v_new, out, static_cast<float*>(workspace),
+                         reinterpret_cast<float*>(static_cast<char*>(workspace) + lo.ws_o_bytes), stream);
+}
+
+int hkv_decode_attn_noalloc(hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new,
+                            void* out, void* stream) {
+  int rc = check_range(c, lb, le);
+  if (rc != HKV_OK) return rc;
+  // the records of this call's tiles must fit the library's array (tail at full capacity, as the tables count them)
+  const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
+  const size_t n_tiles = (size_t)(lo.item_begin[le] - lo.item_begin[lb]);
+  const size_t G = (size_t)(c->cfg.n_q_heads / c->cfg.n_kv_heads);
+  const size_t o_bytes = align_up(n_tiles * G * kD * sizeof(float));
+  const size_t need = o_bytes + align_up(n_tiles * kMlFloats * sizeof(float));
+  if (need > (size_t)HKV_NOALLOC_SCRATCH_BYTES) return HKV_ENOSPACE;
+  rc = check_decode_args(c, lb, le, q, k_new, v_new, out);
+  if (rc != HKV_OK) return rc;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return HKV_EHIP;
+  if (dev != c->device || !c->scratch_dev) return HKV_ESTATE;      // the array's address belongs to the cache's device
+  char* base = static_cast<char*>(c->scratch_dev);
+  return decode_launches(c, lb, le, q, k_new, v_new, out, reinterpret_cast<float*>(base),
+                         reinterpret_cast<float*>(base + o_bytes), stream);
 }
 
 int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
