@@ -293,7 +293,7 @@ def hkv_cache_set_decode_dynamic(handle: int, mode: int) -> None:
 
 
 def hkv_cache_set_device_tail(handle: int, enable: bool, stream=None) -> None:
-    _check(load_library().hkv_cache_set_device_tail(handle, 1 if enable else 0, stream), "hkv_cache_set_device_tail")
+    _check(load_library().hkv_cache_set_device_tail(handle, 1 if enable else 0, _stream(stream)), "hkv_cache_set_device_tail")
 
 
 def hkv_head_scores_workspace_size(cfg: hkv_config, cu_seqlens, is_visual) -> Tuple[int, int]:
