@@ -49,6 +49,9 @@ gives 1, a one-hot row gives 1), by a sort-based restatement on random inputs
 and by hand-worked rational softmax rows; the budget equations by their printed
 invariants (type budgets add up to the total, r = 1 and equal scores give the
 uniform split, every ceiling is at most one token above its argument).
+selection_margin is pinned by a hand case and by its relation to a library sort; the
+keep_override / sel_override hooks of the drivers by library softmax attention over
+hand-chosen rows.
 The indexed-generation variant of decode_attn is pinned by its reductions (no complete
 chunk: the plain reading; room for every chunk: library softmax attention over everything)
 and a hand-built retrieval case.
@@ -449,8 +452,7 @@ def compress(cfg: OracleConfig, plan: OraclePlan, q_window: np.ndarray, k: np.nd
 
 def decode_attn(cache: OracleCache, q: np.ndarray, k_new: Optional[np.ndarray], v_new: Optional[np.ndarray],
                 layers: Optional[range] = None,
-                sel_override: Optional[Dict[Tuple[int, int, int], np.ndarray]] = None,
-                mu_override: Optional[Dict[Tuple[int, int, int], np.ndarray]] = None):
+                sel_override: Optional[Dict[Tuple[int, int, int], np.ndarray]] = None):
     """One decode step.  q [L, B, Hq, d]; k_new, v_new [L, B, Hkv, d] or None.
 
     New tokens are appended uncompressed to every head's tail and always attended.
@@ -462,6 +464,8 @@ def decode_attn(cache: OracleCache, q: np.ndarray, k_new: Optional[np.ndarray], 
     keys as metadata (same rounding as the prompt's) and competes with the prompt's chunks
     for the budget // c places (capped by the number of chunks there are); the incomplete
     rest and the step's own token are always attended.  Static heads are unchanged.
+    `sel_override` replaces the computed chunk picks of the listed dynamic units (used
+    when a test needs oracle and device to attend the same rows inside a tie band).
     Returns (out [L, B, Hq, d] float64, info) where info[(b,l,h)] holds sigma/sel
     for dynamic units.
     """
@@ -492,8 +496,6 @@ def decode_attn(cache: OracleCache, q: np.ndarray, k_new: Optional[np.ndarray], 
                         if n_gen:
                             mu = np.concatenate([mu, np.stack(u.mu_gen[:n_gen])], axis=0)
                         tail_from = n_gen * u.c
-                    if mu_override is not None and (b, l, h) in mu_override:
-                        mu = np.asarray(mu_override[(b, l, h)], dtype=np.float64)
                     sigma = chunk_scores(qh, mu, cfg.chunk_score_group)
                     k_step = min(u.k_cap, mu.shape[0]) if cfg.index_generated else u.k_sel
                     sel = select_chunks(sigma, k_step)

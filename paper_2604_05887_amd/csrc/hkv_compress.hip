@@ -8,9 +8,10 @@
 //   compact_kernel        fp32: copy the kept K/V rows into the head's ragged cache segment
 //   adopt_kernel          fp32, dynamic heads: copy the whole K/V head-major into the cache and reduce
 //                         every chunk's keys to their mean (the chunk-level index)
-//   pack_rows_kernel      bf16: the same two copies, but into the blocked layout the matrix-core
+//   pack_rows_kernel      bf16, static heads: the compaction, into the blocked layout the matrix-core
 //                         decode kernel reads (8-row blocks, V transposed inside a block)
-//   chunk_mean_kernel     bf16, dynamic heads: the chunk means
+//   adopt_blocks_kernel   bf16, dynamic heads: the whole prompt into that layout and the chunk means,
+//                         from one read of K
 #include "hkv_device.h"
 #include "hkv_internal.h"
 #include "hkv_mma.h"
@@ -303,9 +304,12 @@ __global__ __launch_bounds__(256) void adopt_kernel(CacheView cv, int layer_begi
   const int sub = lane % LPR, grp = lane / LPR;
   const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
   const size_t sstride = (size_t)cv.n_kv_heads * ROWB;
-  float acc[EPL];
+  // The mean is formed exactly: the keys are summed in double precision (a sum of c fp32 values of similar
+  // size has no rounding error to speak of there), divided in double precision and rounded once to the
+  // cache's type, which is the definition the summaries are checked against.
+  double acc[EPL];
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.0;
   for (int r = r_begin + grp; r < r_begin + c; r += RPW) {     // uniform trip count (c is a multiple of RPW)
     if (r < r_end) {
       const size_t src = src0 + (size_t)r * sstride + sub * 16;
@@ -316,35 +320,33 @@ __global__ __launch_bounds__(256) void adopt_kernel(CacheView cv, int layer_begi
       float kf[EPL];
       unpack16(kraw, kf, T{});
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[e] += kf[e];
+      for (int e = 0; e < EPL; ++e) acc[e] += (double)kf[e];
     }
   }
 #pragma unroll
   for (int mask = LPR; mask < 64; mask <<= 1) {
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] += lane_xor(acc[e], mask);
+    for (int e = 0; e < EPL; ++e) acc[e] += lane_xor_f64(acc[e], mask);
   }
   if (grp == 0) {
-    const float inv_n = (float)(r_end - r_begin);
+    const double n_rows = (double)(r_end - r_begin);
     float mf[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) mf[e] = acc[e] / inv_n;
+    for (int e = 0; e < EPL; ++e) mf[e] = (float)(acc[e] / n_rows);      // one rounding, to nearest even
     st16(reinterpret_cast<char*>(cv.mu) + (size_t)(d.aux_off + ch) * ROWB + sub * 16, pack16(mf, T{}));
   }
 }
 
-// bf16 caches: gather 8 source rows into one K block and one V block of the blocked layout.
-// grid = (groups of 4 blocks, units of the list); block = 256 threads, one wave per 8-row block.
-// STATIC: rows come from kept_idx (compaction); else they are the prompt rows themselves (adoption).
-template <bool STATIC>
+// bf16 caches, static heads: gather the kept rows, 8 at a time, into one K block and one V block of the
+// blocked layout.  grid = (groups of 4 blocks, static units of the call); block = 256 threads, one wave
+// per 8-row block.
 __global__ __launch_bounds__(256) void pack_rows_kernel(CacheView cv, int layer_begin, int list_begin,
                                                         const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                         int64_t total_tokens) {
   __shared__ __attribute__((aligned(16))) uint16_t vt[4][kBlkRows][kD + 8];
-  const int32_t* list = STATIC ? cv.static_units : cv.dynamic_units;
-  const UnitDesc d = cv.units[list[list_begin + blockIdx.y]];
+  const UnitDesc d = cv.units[cv.static_units[list_begin + blockIdx.y]];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int n_src = STATIC ? d.n_prompt_rows : d.C;
+  const int n_src = d.n_prompt_rows;
   const int blk = blockIdx.x * 4 + wv;
   const int n_blk = (n_src + kBlkRows - 1) / kBlkRows;
   if (blockIdx.x * 4 * kBlkRows >= n_src) return;           // whole workgroup beyond the unit
@@ -353,8 +355,8 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(CacheView cv, int layer_
   const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * (kD * 2);
   const size_t sstride = (size_t)cv.n_kv_heads * kD * 2;
   const int32_t* kept = cv.kept_idx + d.idx_off;
-  char* kdst = reinterpret_cast<char*>(STATIC ? cv.k_rows : cv.k_dyn) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
-  char* vdst = reinterpret_cast<char*>(STATIC ? cv.v_rows : cv.v_dyn) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
+  char* kdst = reinterpret_cast<char*>(cv.k_rows) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
+  char* vdst = reinterpret_cast<char*>(cv.v_rows) + ((size_t)d.kv_row_off / kBlkRows + blk) * kBlkBytes;
   // each lane moves two 16-byte pieces of K and of V: piece p = lane, lane + 64 -> row e = p / 16, dims 8*(p % 16)
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
@@ -362,7 +364,7 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(CacheView cv, int layer_
     const int r = blk * kBlkRows + e;
     uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
     if (active && r < n_src) {
-      const int pos = STATIC ? min(max(kept[r], 0), d.C - 1) : r;
+      const int pos = min(max(kept[r], 0), d.C - 1);
       kk = ld16(reinterpret_cast<const char*>(k) + src0 + (size_t)pos * sstride + d8 * 16);
       vv = ld16(reinterpret_cast<const char*>(v) + src0 + (size_t)pos * sstride + d8 * 16);
     }
@@ -384,44 +386,99 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(CacheView cv, int layer_
   }
 }
 
-// Chunk means only (bf16 caches; the rows themselves are moved by pack_rows_kernel).
-// grid = (chunk groups of 4, dynamic units of the call); block = 256 threads, one wave per chunk.
-template <typename T>
-__global__ __launch_bounds__(256) void chunk_mean_kernel(CacheView cv, int layer_begin, int dynamic_begin,
-                                                         const T* __restrict__ k, int64_t total_tokens) {
-  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RPW = 64 / LPR, ROWB = kD * sizeof(T);
+// bf16 caches, dynamic heads: adopt the head's whole prompt into the blocked layout AND reduce every chunk's
+// keys to their mean (the chunk-level index of the paper's Appendix A) from the same read of K.
+// grid = (groups of 32 prompt rows, dynamic units of the call); block = 256 threads.  A workgroup takes
+// W = max(chunk size, 32) consecutive rows -- whole chunks -- so units with larger chunks use fewer of the
+// grid's workgroups; wave w packs the 8-row blocks w, w + 4, ... of those rows, as pack_rows_kernel does.
+// The mean is formed exactly: bf16 keys summed in double precision (no rounding at all while the chunk's
+// values span fewer than 35 binary orders of magnitude), divided in double precision, rounded once to
+// bf16.  Partial sums are combined in a fixed order (lanes, then waves in wave order).
+__global__ __launch_bounds__(256) void adopt_blocks_kernel(CacheView cv, int layer_begin, int dynamic_begin,
+                                                           const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+                                                           int64_t total_tokens) {
+  __shared__ __attribute__((aligned(16))) uint16_t vt[4][kBlkRows][kD + 8];
+  __shared__ double wsum[4][kD];
   const UnitDesc d = cv.units[cv.dynamic_units[dynamic_begin + blockIdx.y]];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int ch = blockIdx.x * 4 + wv;
-  if (ch >= d.n_chunks) return;               // wave-uniform
   const int c = 1 << d.c_log2;
-  const int r_begin = ch * c, r_end = min(r_begin + c, d.C);
+  const int W = max(c, 4 * kBlkRows);                       // rows of this workgroup
+  const int row0 = blockIdx.x * W;
+  if (row0 >= d.C) return;                                  // whole workgroup beyond the unit
+  const int n_blk = (d.C + kBlkRows - 1) / kBlkRows;
   const int lrel = d.layer - layer_begin;
-  const int sub = lane % LPR, grp = lane / LPR;
-  const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
-  const size_t sstride = (size_t)cv.n_kv_heads * ROWB;
-  float acc[EPL];
+  const size_t src0 = (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * (kD * 2);
+  const size_t sstride = (size_t)cv.n_kv_heads * kD * 2;
+  char* kdst0 = reinterpret_cast<char*>(cv.k_dyn) + ((size_t)d.kv_row_off / kBlkRows) * kBlkBytes;
+  char* vdst0 = reinterpret_cast<char*>(cv.v_dyn) + ((size_t)d.kv_row_off / kBlkRows) * kBlkBytes;
+  const int e0 = lane >> 4, d8 = lane & 15;                 // this lane's pieces: rows e0 and e0 + 4, dims 8*d8..8*d8+7
+  double acc[8];
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-  for (int r = r_begin + grp; r < r_begin + c; r += RPW) {     // uniform trip count (c is a multiple of RPW)
-    if (r < r_end) {
-      float kf[EPL];
-      unpack16(ld16(reinterpret_cast<const char*>(k) + src0 + (size_t)r * sstride + sub * 16), kf, T{});
+  for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+  const int blocks_per_wave = W / (4 * kBlkRows);           // uniform over the workgroup
+  for (int it = 0; it < blocks_per_wave; ++it) {
+    const int blk = row0 / kBlkRows + it * 4 + wv;
+    const bool active = blk < n_blk;                        // wave-uniform
+    uint4 kk[2], vv[2];
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[e] += kf[e];
+    for (int h = 0; h < 2; ++h) {
+      const int r = blk * kBlkRows + e0 + 4 * h;
+      kk[h] = make_uint4(0, 0, 0, 0); vv[h] = make_uint4(0, 0, 0, 0);
+      if (active && r < d.C) {
+        kk[h] = ld16(reinterpret_cast<const char*>(k) + src0 + (size_t)r * sstride + d8 * 16);
+        vv[h] = ld16(reinterpret_cast<const char*>(v) + src0 + (size_t)r * sstride + d8 * 16);
+      }
     }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (active) st16(kdst0 + (size_t)blk * kBlkBytes + k_piece_index(e0 + 4 * h, d8) * 16, kk[h]);
+      *reinterpret_cast<uint4*>(&vt[wv][e0 + 4 * h][d8 * 8]) = vv[h];
+      float kf[8];
+      unpack16(kk[h], kf, bf16_t{});
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += (double)kf[e];  // rows past the end contribute zeros
+    }
+    // the wave's own staging area: written and read by this wave only
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (active) {
+      // transpose V: lane writes the pieces of dims 2*lane and 2*lane + 1 (8 rows each)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int dd = 2 * lane + h;
+        uint4 o;
+        o.x = (uint32_t)vt[wv][0][dd] | ((uint32_t)vt[wv][1][dd] << 16);
+        o.y = (uint32_t)vt[wv][2][dd] | ((uint32_t)vt[wv][3][dd] << 16);
+        o.z = (uint32_t)vt[wv][4][dd] | ((uint32_t)vt[wv][5][dd] << 16);
+        o.w = (uint32_t)vt[wv][6][dd] | ((uint32_t)vt[wv][7][dd] << 16);
+        st16(vdst0 + (size_t)blk * kBlkBytes + dd * 16, o);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();                        // the next block overwrites the staging area
   }
+  // rows of the wave's blocks -> one sum per dim: fold the four row groups of the wave
 #pragma unroll
-  for (int mask = LPR; mask < 64; mask <<= 1) {
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] += lane_xor(acc[e], mask);
+  for (int e = 0; e < 8; ++e) {
+    acc[e] += lane_xor_f64(acc[e], 16);
+    acc[e] += lane_xor_f64(acc[e], 32);
   }
-  if (grp == 0) {
-    const float n_rows = (float)(r_end - r_begin);
-    float mf[EPL];
+  if (lane < 16) {
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) mf[e] = acc[e] / n_rows;
-    st16(reinterpret_cast<char*>(cv.mu) + (size_t)(d.aux_off + ch) * ROWB + sub * 16, pack16(mf, T{}));
+    for (int e = 0; e < 8; ++e) wsum[wv][d8 * 8 + e] = acc[e];
+  }
+  __syncthreads();
+  // chunks of this workgroup: W / c of them (1, 2 or 4), each summed over its 4 * c / W waves in wave order
+  const int n_ch = W / c, wpc = 4 / n_ch;
+  for (int idx = threadIdx.x; idx < n_ch * kD; idx += 256) {
+    const int j = idx / kD, dd = idx % kD;
+    const int ch = row0 / c + j;
+    if (ch >= d.n_chunks) continue;
+    double sum = 0.0;
+    for (int x = 0; x < wpc; ++x) sum += wsum[j * wpc + x][dd];
+    const int n_rows = min(c, d.C - ch * c);
+    reinterpret_cast<uint16_t*>(cv.mu)[(size_t)(d.aux_off + ch) * kD + dd] = f64_to_bf16_rne(sum / (double)n_rows);
   }
 }
 
@@ -475,7 +532,7 @@ hipError_t launch_compact(const CacheView& cv, int dtype, int layer_begin, int s
     hipLaunchKernelGGL(compact_kernel<float>, dim3((max_rows + 63) / 64, n_static), dim3(256), 0, st, cv, layer_begin,
                        static_begin, (const float*)k, (const float*)v, total_tokens);
   else
-    hipLaunchKernelGGL(pack_rows_kernel<true>, dim3((max_rows + 4 * kBlkRows - 1) / (4 * kBlkRows), n_static),
+    hipLaunchKernelGGL(pack_rows_kernel, dim3((max_rows + 4 * kBlkRows - 1) / (4 * kBlkRows), n_static),
                        dim3(256), 0, st, cv, layer_begin, static_begin, (const bf16_t*)k, (const bf16_t*)v,
                        total_tokens);
   return hipGetLastError();
@@ -490,9 +547,7 @@ hipError_t launch_adopt(const CacheView& cv, int dtype, int layer_begin, int dyn
     hipLaunchKernelGGL(adopt_kernel<float>, grid, dim3(256), 0, st, cv, layer_begin, dynamic_begin, (const float*)k,
                        (const float*)v, total_tokens);
   } else {
-    hipLaunchKernelGGL(chunk_mean_kernel<bf16_t>, grid, dim3(256), 0, st, cv, layer_begin, dynamic_begin,
-                       (const bf16_t*)k, total_tokens);
-    hipLaunchKernelGGL(pack_rows_kernel<false>, dim3((max_C + 4 * kBlkRows - 1) / (4 * kBlkRows), n_dynamic),
+    hipLaunchKernelGGL(adopt_blocks_kernel, dim3((max_C + 4 * kBlkRows - 1) / (4 * kBlkRows), n_dynamic),
                        dim3(256), 0, st, cv, layer_begin, dynamic_begin, (const bf16_t*)k, (const bf16_t*)v,
                        total_tokens);
   }

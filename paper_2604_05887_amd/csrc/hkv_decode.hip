@@ -859,7 +859,7 @@ __device__ __forceinline__ void append_row(const CacheView& cv, const AttnItem& 
 }
 
 // Caches that index their generated tokens (bf16): the chunk of generated tokens g of a dynamic unit has
-// just been completed by this block's append; its metadata -- the mean of its keys, rounded once to
+// just been completed by this block's append; its metadata -- the exact mean of its keys, rounded once to
 // bf16 like the prompt's -- goes behind the prompt's chunk summaries, where the next step's selection
 // finds it.  Threads 0..127 take one dimension each; the chunk's rows are read back from the blocked tail.
 __device__ __forceinline__ void index_generated_chunk(const CacheView& cv, const AttnItem& it, int g) {
@@ -867,14 +867,14 @@ __device__ __forceinline__ void index_generated_chunk(const CacheView& cv, const
   if (dd >= kD) return;
   const int c = 1 << it.c_log2;
   const char* tail = reinterpret_cast<const char*>(cv.k_rows) + (size_t)it.tail_off * kD * 2;
-  float acc = 0.f;
+  double acc = 0.0;                    // exact, as for the prompt's chunks: double sum, double divide, one rounding
   for (int r = 0; r < c; ++r) {
     const int row = g * c + r;
     const uint16_t bits = *reinterpret_cast<const uint16_t*>(tail + (size_t)(row >> 3) * kBlkBytes +
                                                              k_piece_index(row & 7, dd >> 3) * 16 + (dd & 7) * 2);
-    acc += bits_to_float((uint32_t)bits << 16);
+    acc += (double)bits_to_float((uint32_t)bits << 16);
   }
-  reinterpret_cast<uint16_t*>(cv.mu)[(size_t)(it.aux_off + it.n_chunks + g) * kD + dd] = f32_to_bf16_rne(acc / (float)c);
+  reinterpret_cast<uint16_t*>(cv.mu)[(size_t)(it.aux_off + it.n_chunks + g) * kD + dd] = f64_to_bf16_rne(acc / (double)c);
 }
 
 // One split-K tile of the hybrid cache: optional tail append, then attention, record -> workspace.

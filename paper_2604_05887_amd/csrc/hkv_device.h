@@ -47,6 +47,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// double -> bfloat16 bits in ONE rounding to nearest even (going through float first could round twice):
+// the double's significand is cut to bfloat16's 8 bits in place, after which the conversion to float and
+// the cut to its upper half are exact.  For finite values of normal bfloat16 magnitude, and zero.
+__device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
+  uint64_t u = __builtin_bit_cast(uint64_t, x);
+  u = (u + ((1ull << 44) - 1ull) + ((u >> 45) & 1ull)) & ~((1ull << 45) - 1ull);
+  return (uint16_t)(float_to_bits((float)__builtin_bit_cast(double, u)) >> 16);
+}
+
 // Unpack one 16-byte piece into floats.
 __device__ __forceinline__ void unpack16(const uint4& v, float (&f)[4], float) {
   f[0] = bits_to_float(v.x); f[1] = bits_to_float(v.y); f[2] = bits_to_float(v.z); f[3] = bits_to_float(v.w);
@@ -89,6 +98,13 @@ template <int CTRL> __device__ __forceinline__ float dpp_mov(float x) {
 __device__ __forceinline__ float lane_xor(float x, int mask) {
   const int lane = (int)__lane_id();
   return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, __builtin_bit_cast(int, x)));
+}
+__device__ __forceinline__ double lane_xor_f64(double x, int mask) {
+  const int lane = (int)__lane_id();
+  const uint64_t u = __builtin_bit_cast(uint64_t, x);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, (int)(uint32_t)u);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, (int)(uint32_t)(u >> 32));
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
 __device__ __forceinline__ int lane_xor_i(int x, int mask) {
   const int lane = (int)__lane_id();

@@ -23,8 +23,8 @@ from oracle import hybridkv_oracle as O
 from paper_2604_05887_amd import binding as B
 from paper_2604_05887_amd import runner
 
-TAU = 2e-5          # relative half-width of the tie band around a selection threshold
-SCORE_RTOL = 2e-5   # fp32 MFMA accumulation + exp2 + fp32 column sums vs double
+TAU = 1e-5          # relative half-width of the tie band around a selection threshold
+SCORE_RTOL = 1e-5   # fp32 MFMA accumulation + exp2 + fp32 column sums vs double
 OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}
 
 
@@ -35,6 +35,24 @@ def oracle_setup(wl, budget=None, head_type=None, causal=False, chunk_score_grou
     plan = O.OraclePlan(cu_seqlens=wl.cu_seqlens, head_type=wl.head_type if head_type is None else head_type,
                         budget=wl.budget if budget is None else budget, chunk_size=wl.chunk_size)
     return cfg, plan
+
+
+def assert_summaries_equal(mu_gpu: np.ndarray, mu_ref: np.ndarray, dtype: str, what) -> int:
+    """Chunk summaries are formed exactly on the device (double-precision sum and divide, one rounding to
+    the cache's type), so they must equal the oracle's.  bf16: bit for bit, always (sums of bf16 values are
+    exact in double precision on both sides).  fp32: the two double-precision sums run in different orders
+    and can differ in their last bit, which moves the rounded fp32 value only when the mean sits within
+    ~1e-16 of a rounding boundary; at most two such elements per unit are tolerated, each by one fp32 ulp.
+    Returns the number of unequal elements."""
+    assert mu_gpu.shape == mu_ref.shape, (what, mu_gpu.shape, mu_ref.shape)
+    bad = mu_gpu != mu_ref
+    n_bad = int(bad.sum())
+    if dtype == "bf16":
+        assert n_bad == 0, f"chunk summaries of {what} differ from the oracle's in {n_bad} elements"
+    elif n_bad:
+        ulp = np.spacing(np.abs(mu_ref[bad]).astype(np.float32)).astype(np.float64)
+        assert n_bad <= 2 and np.all(np.abs(mu_gpu[bad] - mu_ref[bad]) <= ulp), f"chunk summaries of {what} off"
+    return n_bad
 
 
 def candidates_of(is_visual: np.ndarray, w: int, budget: int):
@@ -110,13 +128,7 @@ def compare_compress(wl, dw, ocache, stats: Dict[str, float]) -> Dict[Tuple[int,
                 k_want = min(u.k_cap, u.mu.shape[0] + wl.max_new_tokens // u.c)
             assert (n_c, k_sel) == (u.mu.shape[0], k_want) and rows == k_sel * u.c
             mu_gpu = dw.cache.export(B.HKV_X_CHUNK_MEAN, b, l, h).astype(np.float64)
-            # fp32 summation of n rows errs by at most (n-1) * 2^-24 * sum|k| (then / n); storing in bf16
-            # can move the result to the neighbouring bf16 value (one ulp <= 2^-7 relative)
-            kk = np.abs(wl.k[l, lo:hi, h].astype(np.float64))
-            abs_sum = np.add.reduceat(kk, np.arange(0, hi - lo, u.c), axis=0)
-            tol = 2.0 ** -24 * abs_sum + (np.abs(u.mu) * 2.0 ** -7 if wl.dtype == "bf16" else 0.0)
-            assert np.all(np.abs(mu_gpu - u.mu) <= tol), "chunk summary outside its rounding bound"
-            stats["mu_mismatch_frac"] = max(stats.get("mu_mismatch_frac", 0.0), float((mu_gpu != u.mu).mean()))
+            stats["mu_unequal"] = stats.get("mu_unequal", 0) + assert_summaries_equal(mu_gpu, u.mu, wl.dtype, (b, l, h))
             Kd = dw.cache.export(B.HKV_X_K_ROWS, b, l, h)
             Vd = dw.cache.export(B.HKV_X_V_ROWS, b, l, h)
             assert np.array_equal(Kd[: hi - lo], wl.k[l, lo:hi, h]) and np.array_equal(Vd[: hi - lo], wl.v[l, lo:hi, h])
@@ -125,18 +137,16 @@ def compare_compress(wl, dw, ocache, stats: Dict[str, float]) -> Dict[Tuple[int,
 
 def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float], layer_ranges=None,
                            append: bool = True, oracle_layers=None, layer_ranges_by_step=None):
-    """n_steps decode steps on both sides; the oracle takes the device's chunk summaries (they may
-    differ from its own by one rounding) and, inside a tie band, the device's chunk picks.
+    """n_steps decode steps on both sides.  Chunk scores and chunk picks are compared with the oracle's own
+    (computed from its own chunk summaries); only where a cut falls inside a tie band does the oracle
+    adopt the device's picks for the attention that follows.
     layer_ranges_by_step[s], if given and not None, replaces layer_ranges for step s."""
     L, Bn = wl.n_layers, wl.batch
     tdt = runner.torch_dtype(wl.dtype)
     out = torch.empty((L, Bn, wl.n_q_heads, wl.head_dim), dtype=tdt, device="cuda:0")
-    mu_dev = {}
-    for key, u in ocache.units.items():
-        if u.kind == O.DYNAMIC:
-            mu_dev[key] = dw.cache.export(B.HKV_X_CHUNK_MEAN, *key).astype(np.float64)
     layer_ranges = layer_ranges or [(0, L)]
     G = wl.group
+    indexed = ocache.cfg.index_generated
     for s in range(n_steps):
         q = runner.to_device(wl.q_steps[s], wl.dtype)
         kn = runner.to_device(wl.k_new[s], wl.dtype) if append else None
@@ -151,57 +161,58 @@ def run_decode_and_compare(wl, dw, ocache, n_steps: int, stats: Dict[str, float]
         got = runner.to_host_f32(out).astype(np.float64)
         # chunk picks first: they decide which rows the oracle attends
         sel_over = {}
-        indexed = ocache.cfg.index_generated
         for key, u in ocache.units.items():
-            if u.kind != O.DYNAMIC:
+            if u.kind != O.DYNAMIC or (oracle_layers is not None and key[1] not in oracle_layers):
                 continue
             b, l, h = key
             sig_gpu = dw.cache.export(B.HKV_X_CHUNK_SIGMA, b, l, h)
             sel_gpu = dw.cache.export(B.HKV_X_CHUNK_SEL, b, l, h).astype(np.int64)
             k_step = u.k_sel
+            mu_ref = u.mu
             if indexed:
-                # the step saw the chunks complete before it: those of the prompt and of the s tokens generated so far;
-                # the summaries are exported anew because the step may have added one
-                n_now = u.mu.shape[0] + (s if append else 0) // u.c
+                # the step saw the chunks complete before it: those of the prompt and of the tokens generated so
+                # far (the oracle formed their summaries when its own earlier steps completed them)
+                n_gen = (s if append else 0) // u.c
+                n_now = u.mu.shape[0] + n_gen
                 k_step = min(u.k_cap, n_now)
-                mu_dev[key] = dw.cache.export(B.HKV_X_CHUNK_MEAN, b, l, h).astype(np.float64)[:n_now]
+                if n_gen:
+                    mu_ref = np.concatenate([u.mu, np.stack(u.mu_gen[:n_gen])], axis=0)
                 sig_gpu, sel_gpu = sig_gpu[:n_now], sel_gpu[:k_step]
+            # stage-exact: the oracle's rule on the device's own fp32 scores
             assert np.array_equal(sel_gpu, O.select_chunks(sig_gpu, k_step)), f"chunk top-k not exact on {key}"
+            # end to end: scores and picks against the oracle's own summaries, scores and picks
             qh = wl.q_steps[s][l, b, h * G:(h + 1) * G].astype(np.float64)
             group = ocache.cfg.chunk_score_group
-            sig_ref = O.chunk_scores(qh, mu_dev[key], group)
+            sig_ref = O.chunk_scores(qh, mu_ref, group)
             q_norm = np.linalg.norm(qh.sum(0)) if group == "sum" else np.linalg.norm(qh, axis=1).max()
-            scale = q_norm * np.linalg.norm(mu_dev[key], axis=1).max()
+            scale = q_norm * np.linalg.norm(mu_ref, axis=1).max()
             err = np.abs(sig_gpu - sig_ref).max() / scale
             stats["sigma_err"] = max(stats.get("sigma_err", 0.0), float(err))
             assert err <= 1e-5, f"chunk scores off by {err:.3e} (relative to |q||mu|) on {key}"
             want = O.select_chunks(sig_ref, k_step)
             same = check_banded(sel_gpu, want, sig_ref, np.arange(sig_ref.size), k_step, lambda thr: 1e-5 * scale)
+            stats["chunk_picks_compared"] = stats.get("chunk_picks_compared", 0) + 1
             if not same:
                 sel_over[key] = sel_gpu
                 stats["banded_chunk_picks"] = stats.get("banded_chunk_picks", 0) + 1
             if indexed:
                 stats["generated_chunks_picked"] = stats.get("generated_chunks_picked", 0) + int((sel_gpu >= u.mu.shape[0]).sum())
         ref, _ = O.decode_attn(ocache, wl.q_steps[s], wl.k_new[s] if append else None,
-                               wl.v_new[s] if append else None, layers=oracle_layers, sel_override=sel_over,
-                               mu_override=mu_dev)
+                               wl.v_new[s] if append else None, layers=oracle_layers, sel_override=sel_over)
         if oracle_layers is not None:       # the oracle only ran a sample of layers
             got, ref = got[oracle_layers], ref[oracle_layers]
         err = np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
         stats["out_err"] = max(stats.get("out_err", 0.0), float(err.max()))
         assert err.max() <= OUT_TOL[wl.dtype], f"step {s}: output off by {err.max():.3e}"
-    if ocache.cfg.index_generated:
-        # the summaries of the generated chunks themselves: fp32 sum of c keys, one rounding to the KV dtype
+    if indexed:
+        # the summaries of the generated chunks themselves: exact means, equal to the oracle's
         for key, u in ocache.units.items():
             if u.kind != O.DYNAMIC or (oracle_layers is not None and key[1] not in oracle_layers) or not u.mu_gen:
                 continue
             n_c = u.mu.shape[0]
             got_mu = dw.cache.export(B.HKV_X_CHUNK_MEAN, *key).astype(np.float64)
             assert got_mu.shape[0] == n_c + len(u.mu_gen)
-            tail_k = np.abs(np.stack(u.K_tail))
-            for g, ref_mu in enumerate(u.mu_gen):
-                tol = 2.0 ** -24 * tail_k[g * u.c:(g + 1) * u.c].sum(axis=0) + np.abs(ref_mu) * 2.0 ** -7
-                assert np.all(np.abs(got_mu[n_c + g] - ref_mu) <= tol), f"summary of generated chunk {g} of {key} off"
+            assert_summaries_equal(got_mu[n_c:], np.stack(u.mu_gen), wl.dtype, ("generated", key))
             stats["generated_chunks_indexed"] = stats.get("generated_chunks_indexed", 0) + len(u.mu_gen)
     return out
 

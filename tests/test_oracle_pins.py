@@ -284,7 +284,7 @@ def test_compress_counts_scores_and_planted_tokens():
             assert u.mu.shape == (C // 32, 128) and u.k_sel == 4
 
 
-def test_decode_dynamic_rows_and_override():
+def test_decode_dynamic_rows_against_library_attention():
     wl = make_workload(0, shrink=4, steps=2)
     cfg, plan = _cfg_plan(wl)
     cache = O.compress(cfg, plan, wl.q_window, wl.k, wl.v, wl.is_visual)
@@ -299,6 +299,86 @@ def test_decode_dynamic_rows_and_override():
         V = np.concatenate([wl.v[l, rows, h], wl.v_new[0][l, b, h][None]]).astype(np.float64)
         ref = _sdpa_f64(wl.q_steps[0][l, b, h * G:(h + 1) * G], K, V, cfg.scale)
         np.testing.assert_allclose(out[l, b, h * G:(h + 1) * G], ref, rtol=1e-11, atol=1e-13)
+
+
+def test_selection_margin_hand_case_and_library_sort():
+    # candidates 1, 3, 4, 6 carry 0.5, 0.9, 0.5, 0.7; position 0 holds the largest value but is no candidate
+    scores = np.array([9.0, 0.5, 8.0, 0.9, 0.5, 7.0, 0.7])
+    cand = np.array([1, 3, 4, 6])
+    assert O.selection_margin(scores, cand, 1) == (0.9, 0.7)
+    assert O.selection_margin(scores, cand, 2) == (0.7, 0.5)
+    assert O.selection_margin(scores, cand, 3) == (0.5, 0.5)          # an exact tie at the cut
+    assert O.selection_margin(scores, cand, 0) == (float("inf"), float("-inf"))   # nothing is cut off
+    assert O.selection_margin(scores, cand, 4) == (float("inf"), float("-inf"))
+    # against a library sort, and against the selection itself: every pick is at least `hi`, every
+    # candidate left out at most `lo`
+    rng = np.random.default_rng(11)
+    for _ in range(50):
+        n = int(rng.integers(2, 40))
+        sc = rng.integers(0, 6, size=n).astype(np.float64)            # many ties
+        cand = np.sort(rng.choice(n, size=int(rng.integers(1, n + 1)), replace=False))
+        m = int(rng.integers(1, cand.size + 1))
+        hi, lo = O.selection_margin(sc, cand, m)
+        if m == cand.size:
+            assert (hi, lo) == (float("inf"), float("-inf"))
+            continue
+        desc = sorted(sc[cand].tolist(), reverse=True)
+        assert (hi, lo) == (desc[m - 1], desc[m])
+        picked = O.top_indices(sc, cand, m)
+        rest = np.setdiff1d(cand, picked)
+        assert sc[picked].min() == hi and sc[rest].max() == lo
+
+
+def test_keep_override_and_sel_override_attend_exactly_the_given_rows():
+    """The two hooks the GPU tests use inside a tie band: the oracle must then attend the rows it is
+    given, nothing else -- checked with library softmax attention over those rows."""
+    wl = make_workload(0, shrink=4, steps=2)
+    cfg, plan = _cfg_plan(wl)
+    G = cfg.group
+    C = int(wl.seqlens[0])
+    plain = O.compress(cfg, plan, wl.q_window, wl.k, wl.v, wl.is_visual)
+    s_key = next(key for key, u in plain.units.items() if u.kind == O.STATIC)
+    d_key = next(key for key, u in plain.units.items() if u.kind == O.DYNAMIC)
+    # a keep set of the right size that the scores would never produce: every third position from the start
+    n_keep = plain.units[s_key].kept.size
+    forced_keep = np.arange(n_keep) * 3 % C
+    forced_keep = np.sort(np.unique(forced_keep))
+    assert not np.array_equal(forced_keep, plain.units[s_key].kept)
+    cache = O.compress(cfg, plan, wl.q_window, wl.k, wl.v, wl.is_visual, keep_override={s_key: forced_keep})
+    u = cache.units[s_key]
+    np.testing.assert_array_equal(u.kept, forced_keep)
+    np.testing.assert_array_equal(u.K, wl.k[0, forced_keep, s_key[2]].astype(np.float64))
+    np.testing.assert_array_equal(u.V, wl.v[0, forced_keep, s_key[2]].astype(np.float64))
+    np.testing.assert_array_equal(u.s_w, plain.units[s_key].s_w)       # scores are not touched by the hook
+    for key, other in cache.units.items():                              # nor is any unit that was not listed
+        if key != s_key and other.kind == O.STATIC:
+            np.testing.assert_array_equal(other.kept, plain.units[key].kept)
+    # forced chunk picks: the two last chunks, which random queries do not single out
+    ud = cache.units[d_key]
+    n_c = ud.mu.shape[0]
+    forced_sel = np.arange(n_c - ud.k_sel, n_c)
+    _, info0 = O.decode_attn(O.compress(cfg, plan, wl.q_window, wl.k, wl.v, wl.is_visual),
+                             wl.q_steps[0], wl.k_new[0], wl.v_new[0])
+    assert not np.array_equal(info0[d_key]["sel"], forced_sel)
+    out, info = O.decode_attn(cache, wl.q_steps[0], wl.k_new[0], wl.v_new[0], sel_override={d_key: forced_sel})
+    np.testing.assert_array_equal(info[d_key]["sel"], forced_sel)
+    np.testing.assert_array_equal(info[d_key]["sigma"], info0[d_key]["sigma"])     # scores untouched
+    b, l, h = d_key
+    rows = np.concatenate([np.arange(ci * ud.c, min((ci + 1) * ud.c, C)) for ci in forced_sel])
+    K = np.concatenate([wl.k[l, rows, h], wl.k_new[0][l, b, h][None]]).astype(np.float64)
+    V = np.concatenate([wl.v[l, rows, h], wl.v_new[0][l, b, h][None]]).astype(np.float64)
+    np.testing.assert_allclose(out[l, b, h * G:(h + 1) * G], _sdpa_f64(wl.q_steps[0][l, b, h * G:(h + 1) * G], K, V, cfg.scale),
+                               rtol=1e-11, atol=1e-13)
+    # the static unit with the forced keep set attends those rows + the new token
+    b, l, h = s_key
+    K = np.concatenate([wl.k[l, forced_keep, h], wl.k_new[0][l, b, h][None]]).astype(np.float64)
+    V = np.concatenate([wl.v[l, forced_keep, h], wl.v_new[0][l, b, h][None]]).astype(np.float64)
+    np.testing.assert_allclose(out[l, b, h * G:(h + 1) * G], _sdpa_f64(wl.q_steps[0][l, b, h * G:(h + 1) * G], K, V, cfg.scale),
+                               rtol=1e-11, atol=1e-13)
+    # units that were not listed decide for themselves
+    for key, dd in info.items():
+        if key != d_key:
+            np.testing.assert_array_equal(dd["sel"], info0[key]["sel"])
 
 
 # ---------------------------------------------------------------- paper arithmetic
