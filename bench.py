@@ -426,10 +426,11 @@ def main() -> int:
     ap.add_argument("--budget-frac", type=float, default=None)
     ap.add_argument("--head-mix", default=None, choices=["all_static", "all_dynamic"])
     ap.add_argument("--tile-rows", type=int, default=0, help="decode tile rows (0 = library default)")
-    ap.add_argument("--dynamic-mode", type=int, default=0, choices=[0, 1, 2, 3, 4],
+    ap.add_argument("--dynamic-mode", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
                     help="dynamic heads: 1 = one workgroup per head in the main launch, 2 = split-K tiles in a "
                          "second launch, 3 = single launch with repeated selection, 4 = one wide workgroup per "
-                         "head of either kind and no split-K, 0 = library default")
+                         "head of either kind and no split-K, 5 = streamed: every workgroup walks an equal share of the "
+                         "step's rows, 0 = library default")
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--host-tier", action="store_true",
                     help="keep the dynamic heads' prompt rows in page-locked host memory (bf16 workloads)")
@@ -609,7 +610,7 @@ def main() -> int:
     # ---- CPU oracle on the host cores (reported baseline only) -----------------------------------------
     cpu = None if args.no_cpu_baseline else cpu_oracle_baseline(args.config, L, args.cpu_seconds)
 
-    kernel_name = {3: "dynamic_tiles_kernel", 4: "unit_kernel"}.get(dyn_mode, "decode_kernel")
+    kernel_name = {3: "dynamic_tiles_kernel", 4: "unit_kernel", 5: "stream_kernel"}.get(dyn_mode, "decode_kernel")
     result = {
         "metric": METRIC,
         "value": round(ms_per_step * 1e3, 2),

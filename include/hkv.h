@@ -104,16 +104,21 @@ typedef struct {
                                hkv_cache_call_tiling); bf16 caches also accept any multiple of 32 from
                                128 to 4096, which every call then uses (tuning knob; the result does
                                not depend on it beyond fp32 summation order) */
-  int32_t decode_dynamic;   /* how a decode step runs the dynamic heads: 1 = one workgroup per head does
-                               chunk selection, attention and the output inside the main launch;
-                               2 = chunk selection in the main launch, split-K tiles over many
-                               workgroups in a second launch; 3 = a single launch of split-K tiles, each
-                               repeating its head's chunk selection; 4 (bf16 caches only, else
-                               HKV_ESHAPE) = one wide workgroup per head, static or dynamic, does
-                               everything for its head and writes the output rows: a single launch
-                               without split-K records, for steps whose heads are few (per-layer
-                               calls, small batches); 0 = 4 for bf16 caches whose heads all have at
-                               most 768 rows (tail capacity included), else 3 unless the repeated
+  int32_t decode_dynamic;   /* how a decode step is launched: 1 = one workgroup per dynamic head does chunk
+                               selection, attention and the output inside the main launch, static heads run as
+                               split-K tiles beside them; 2 = chunk selection in the main launch, split-K tiles
+                               of the dynamic heads in a second launch; 3 = a single launch of split-K tiles,
+                               each dynamic tile repeating its head's chunk selection; 4 (bf16 caches only, else
+                               HKV_ESHAPE) = one wide workgroup per head, static or dynamic, does everything
+                               for its head and writes the output rows: a single launch without split-K
+                               records, for steps whose heads are few (per-layer calls, small batches);
+                               5 (bf16 caches with index_generated = 0, else HKV_ESHAPE) = streamed: the rows of
+                               all heads of the call form one line of work that is cut into equal shares,
+                               one per resident workgroup, each workgroup walking through the heads its share
+                               covers (calls over all layers or over one layer; other layer ranges run as 3);
+                               0 = chosen when the cache is laid out: 4 for bf16 caches whose heads all have at
+                               most 768 rows (tail capacity included); 5 when a call over all layers gives every
+                               resident workgroup a share of at least 2048 rows; else 3 unless the repeated
                                summary reads would exceed a quarter of a step's bytes, then 2
                                (tuning knob, same results up to fp32 summation order) */
   int32_t chunk_score_group;/* how the query heads that share a KV head score a chunk (Appendix A gives one
@@ -213,8 +218,9 @@ HKV_API int hkv_decode_attn(hkv_cache* cache, int layer_begin, int layer_end, co
  * created) instead of a caller workspace.  The call allocates and frees nothing and makes no runtime
  * call besides its kernel launches and a device-id query.
  *   - Returns HKV_ENOSPACE (nothing enqueued) when the records of the call's tiles -- per tile
- *     (n_q_heads / n_kv_heads) * 512 + 64 bytes, tiles as hkv_cache_call_tiling reports them -- exceed
- *     the array: use a smaller layer range or hkv_decode_attn.
+ *     (n_q_heads / n_kv_heads) * 512 + 64 bytes, tiles as hkv_cache_call_tiling reports them (a streamed
+ *     call: one record per workgroup plus one per head of the call) -- exceed the array: use a smaller
+ *     layer range or hkv_decode_attn.
  *   - Returns HKV_ESTATE when the current device is not the one the cache was created on.
  *   - All calls on one GPU share that GPU's array: calls that can overlap there (different streams
  *     without an ordering between them, several host threads) race on it and must be serialised by
@@ -254,7 +260,7 @@ HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int la
                          uint64_t* bytes);
 
 /* How decode steps of this cache run (decided at creation, see hkv_config.decode_tile_rows and
- * decode_dynamic): *tile_rows = rows per split-K tile, *dynamic_mode = 1 to 4 as described at
+ * decode_dynamic): *tile_rows = rows per split-K tile, *dynamic_mode = 1 to 5 as described at
  * hkv_config.decode_dynamic.  Either pointer may be NULL. */
 HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, int32_t* dynamic_mode);
 
@@ -264,7 +270,8 @@ HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, i
  * device has compute units and the large tiles give every tile a compute unit of its own (small
  * whole-model steps), the small tiles otherwise (per-layer calls, large steps).  Same results up to
  * fp32 summation order.  *tile_rows = rows per tile of such a call, *n_tiles = its tiles (tail at
- * full capacity).  Either pointer may be NULL. */
+ * full capacity).  A streamed call (dynamic mode 5) reports the rows of a workgroup's share and the number of
+ * workgroups instead.  Either pointer may be NULL. */
 HKV_API int hkv_cache_call_tiling(const hkv_cache* cache, int layer_begin, int layer_end, int32_t* tile_rows,
                                   int32_t* n_tiles);
 
@@ -277,9 +284,10 @@ HKV_API int hkv_cache_call_tiling(const hkv_cache* cache, int layer_begin, int l
  * Exports of K/V rows use the host's figure, so switch back before exporting. */
 HKV_API int hkv_cache_set_device_tail(hkv_cache* cache, int enable, void* stream);
 
-/* Switches the way decode steps run (1 to 4 as at hkv_config.decode_dynamic); for callers that time them
+/* Switches the way decode steps run (1 to 5 as at hkv_config.decode_dynamic); for callers that time them
  * on their own workload and keep the fastest.  Takes effect with the next hkv_decode_attn; the cache
- * content is not touched.  HKV_EINVAL for any other value, HKV_ESHAPE for 4 on an fp32 cache. */
+ * content is not touched.  HKV_EINVAL for any other value, HKV_ESHAPE for a value the cache does not
+ * support (4 and 5 on an fp32 cache; 2 and 5 on a cache that indexes generated tokens). */
 HKV_API int hkv_cache_set_decode_dynamic(hkv_cache* cache, int32_t dynamic_mode);
 
 /* Test / debug access to one unit (synchronises `stream`, then copies).  `dst`/`src` are [host].
@@ -303,7 +311,7 @@ HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end
  * (the kernel's own start and stop time stamps; no synchronisation, no extra work on the stream).
  * hkv_profile_read waits for the stream of the profiled calls, returns
  * the summed durations in milliseconds -- ms[0] main launch (chunk scoring and chunk top-k of the
- * dynamic heads together with the split-K attention of the static heads; in dynamic modes 1 and 3
+ * dynamic heads together with the split-K attention of the static heads; in dynamic modes 1, 3 and 5
  * also the dynamic heads' attention; in mode 4 the whole step), ms[1] second launch (split-K
  * attention of the dynamic heads, dynamic mode 2 only), ms[2] combination of the split-K tiles (none
  * in mode 4) -- and the number of calls summed,

@@ -28,13 +28,13 @@ int validate_config(const hkv_config* cfg) {
     const int t = cfg->decode_tile_rows;
     if (cfg->dtype != HKV_BF16 || t < 128 || t > 4096 || t % 32 != 0) return HKV_ESHAPE;
   }
-  if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 4) return HKV_EINVAL;
-  if (cfg->decode_dynamic == 4 && cfg->dtype != HKV_BF16) return HKV_ESHAPE;   // the per-unit shape is bf16 only
+  if (cfg->decode_dynamic < 0 || cfg->decode_dynamic > 5) return HKV_EINVAL;
+  if (cfg->decode_dynamic >= 4 && cfg->dtype != HKV_BF16) return HKV_ESHAPE;   // the per-unit and streamed shapes are bf16 only
   if (cfg->chunk_score_group != 0 && cfg->chunk_score_group != 1) return HKV_EINVAL;
   if (cfg->index_generated != 0 && cfg->index_generated != 1) return HKV_EINVAL;
   if (cfg->index_generated) {               // bf16 caches; not the shape that selects in one launch and gathers in the next
     if (cfg->dtype != HKV_BF16) return HKV_ESHAPE;
-    if (cfg->decode_dynamic == 2) return HKV_ESHAPE;
+    if (cfg->decode_dynamic == 2 || cfg->decode_dynamic == 5) return HKV_ESHAPE;
   }
   if (!(cfg->softmax_scale >= 0.f) || !std::isfinite(cfg->softmax_scale)) return HKV_EINVAL;
   return HKV_OK;
@@ -81,7 +81,23 @@ hipError_t scratch_of_current_device(void** ptr, int* device) {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t elem_size(int dtype) { return dtype == HKV_BF16 ? 2 : 4; }
 
+// Streamed decode shape: the equal shares of one call shape (all layers, or one layer) at one reference
+// tail length.  Offsets are relative to the start of the cache's stream-table section.
+struct StreamTable {
+  int32_t t_ref = 0, n_wg = 0, n_multi = 0, share_rows = 0;
+  size_t off_bounds = 0, off_multi = 0;
+};
+struct StreamShape {
+  int32_t unit_begin = 0, n_units = 0;
+  std::vector<StreamTable> tables;        // ascending t_ref
+};
+
 struct Layout {
+  // streamed shape (bf16 caches that do not index generated tokens): [0] = all layers, [1 + l] = layer l alone
+  std::vector<StreamShape> stream_shapes;
+  std::vector<char> stream_blob;          // every table's boundaries and multi-workgroup unit lists, as uploaded
+  size_t off_stream = 0, rows_end = 0;     // arena offset of the tables; end of the K / V row arrays
+  int64_t stream_slots_max = 0;           // most record slots a streamed call can use
   // host tables
   std::vector<UnitDesc> units;
   std::vector<AttnItem> sitems, ditems;
@@ -293,6 +309,83 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
   return HKV_OK;
 }
 
+// Streamed decode shape: cut the rows of a call's units (unit order, every unit's rows in steps of 32, tail at
+// the reference length t_ref) into n_wg shares of equal size; see stream_kernel.  n_wg = as many as the
+// device keeps resident (three workgroups on each compute unit), fewer when a share would drop below
+// kStreamMinSteps steps.
+constexpr int kStreamMinSteps = 8;
+constexpr int kStreamMaxWg = 3 * 256;
+constexpr int kStreamAutoRows = 2048;     // the automatic rule streams when every workgroup's share is at least this long
+// A dynamic unit costs more than its rows: whoever touches it reads its chunk summaries (one 32-row step
+// of K and V is 16 KB) and waits for the selection's dependent chain (about the time of kSelLatencySteps
+// steps of a streaming workgroup).  That cost sits at the front of the unit on the line of work; a
+// boundary that falls inside it becomes the unit's row 0.
+constexpr int kSelLatencySteps = 3;
+void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref, StreamTable& tb, std::vector<char>& blob) {
+  std::vector<int64_t> start(n_units + 1, 0), lead(n_units, 0);     // first step of every unit; its selection cost
+  std::vector<int32_t> ref_rows(n_units, 0);
+  for (int i = 0; i < n_units; ++i) {
+    const UnitDesc& d = lo.units[unit_begin + i];
+    ref_rows[i] = d.n_prompt_rows + t_ref;
+    if (d.kind == HKV_DYNAMIC) lead[i] = ((int64_t)d.n_chunks * kD * 2 + 16383) / 16384 + kSelLatencySteps;
+    start[i + 1] = start[i] + lead[i] + ((int64_t)ref_rows[i] + 31) / 32;
+  }
+  const int64_t S = start[n_units];
+  const int n_wg = (int)std::max<int64_t>(1, std::min<int64_t>(kStreamMaxWg, S / kStreamMinSteps));
+  std::vector<StreamBound> bounds(n_wg + 1);
+  int u = 0;
+  for (int j = 0; j <= n_wg; ++j) {
+    const int64_t pos = j == n_wg ? S : S * j / n_wg;
+    while (u < n_units && start[u + 1] <= pos) ++u;           // unit that holds step `pos` (n_units at the very end)
+    bounds[j].unit = u;
+    bounds[j].row = u < n_units ? (int32_t)(std::max<int64_t>(0, pos - start[u] - lead[u]) * 32) : 0;
+  }
+  // who touches which unit: walk every workgroup's share as the kernel does
+  std::vector<int32_t> first(n_units, -1), last(n_units, -1);
+  for (int j = 0; j < n_wg; ++j) {
+    int uu = bounds[j].unit, ra = bounds[j].row;
+    while (uu < bounds[j + 1].unit || (uu == bounds[j + 1].unit && ra < bounds[j + 1].row)) {
+      if (first[uu] < 0) first[uu] = j;
+      last[uu] = j;
+      ++uu; ra = 0;
+    }
+  }
+  std::vector<StreamMulti> multi;
+  for (int i = 0; i < n_units; ++i)
+    if (last[i] > first[i]) multi.push_back(StreamMulti{i, first[i] + i, last[i] - first[i] + 1, 0});
+  tb.t_ref = t_ref; tb.n_wg = n_wg; tb.n_multi = (int32_t)multi.size();
+  tb.share_rows = (int32_t)std::min<int64_t>(S * 32 / n_wg, 0x7fffffff);
+  auto put = [&](const void* src, size_t bytes) {
+    const size_t off = (blob.size() + 255) / 256 * 256;
+    blob.resize(off + std::max<size_t>(bytes, 16));
+    std::memcpy(blob.data() + off, src, bytes);
+    return off;
+  };
+  tb.off_bounds = put(bounds.data(), bounds.size() * sizeof(StreamBound));
+  tb.off_multi = put(multi.data(), multi.size() * sizeof(StreamMulti));
+}
+
+void build_stream_shapes(const hkv_config* cfg, int batch, Layout& lo) {
+  lo.stream_shapes.clear(); lo.stream_blob.clear(); lo.stream_slots_max = 0;
+  if (cfg->dtype != HKV_BF16 || cfg->index_generated) return;
+  // reference tail lengths: every 32 tokens up to 256, every 128 up to 1024, then doubling
+  std::vector<int> rungs;
+  for (int t = 0; t <= cfg->max_new_tokens; t += t < 256 ? 32 : (t < 1024 ? 128 : t)) rungs.push_back(t);
+  const int L = cfg->n_layers, upl = batch * cfg->n_kv_heads;
+  const int n_shapes = L > 1 ? 1 + L : 1;
+  lo.stream_shapes.resize(n_shapes);
+  for (int s = 0; s < n_shapes; ++s) {
+    StreamShape& sh = lo.stream_shapes[s];
+    sh.unit_begin = s == 0 ? 0 : (s - 1) * upl;
+    sh.n_units = s == 0 ? L * upl : upl;
+    sh.tables.resize(rungs.size());
+    for (size_t r = 0; r < rungs.size(); ++r) {
+      build_stream_table(lo, sh.unit_begin, sh.n_units, rungs[r], sh.tables[r], lo.stream_blob);
+      lo.stream_slots_max = std::max<int64_t>(lo.stream_slots_max, (int64_t)sh.tables[r].n_wg + sh.n_units);
+    }
+  }
+}
+
 // Tile size: fp32 caches use 128 rows; bf16 caches start at 256 rows and double (up to 1024) while the
 // whole cache still yields three tiles per compute unit (one full round of resident workgroups), so that
 // small steps keep every compute unit busy and large ones amortise the per-tile cost.
@@ -336,10 +429,23 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
       lo.coarse = std::move(co);
     }
   }
+  lo.rows_end = lo.coarse ? lo.coff_units : lo.arena_bytes;
+  build_stream_shapes(cfg, plan->batch, lo);
+  if (!lo.stream_blob.empty()) {
+    lo.off_stream = align_up(lo.arena_bytes);
+    lo.arena_bytes = lo.off_stream + align_up(lo.stream_blob.size());
+    const size_t G = (size_t)(cfg->n_q_heads / cfg->n_kv_heads);
+    const size_t ws_stream = align_up((size_t)lo.stream_slots_max * G * kD * sizeof(float)) +
+                             align_up((size_t)lo.stream_slots_max * kMlFloats * sizeof(float));
+    lo.ws_bytes = std::max(lo.ws_bytes, ws_stream);
+  }
   if (cfg->decode_dynamic != 0) lo.mode = cfg->decode_dynamic;
   else if (cfg->dtype == HKV_BF16 &&
            std::max(lo.max_rows_static + cfg->max_new_tokens, lo.max_rows_dynamic) <= kUnitShapeMaxRows)
     lo.mode = 4;         // short heads: one wide workgroup each beats split-K plus the combination launch
+  else if (!lo.stream_shapes.empty() && lo.stream_shapes[0].tables[0].n_wg == kStreamMaxWg &&
+           lo.stream_shapes[0].tables[0].share_rows >= kStreamAutoRows)
+    lo.mode = 5;         // large steps: equal shares of the rows beat tiles (measured from about 1 GB per step on)
   else lo.mode = 4 * lo.reselect_extra_bytes <= lo.step_bytes0 ? 3 : (cfg->index_generated ? 1 : 2);
   return HKV_OK;
 }
@@ -517,7 +623,8 @@ static int create_cache(const hkv_config* cfg, const hkv_plan* plan, void* cache
   if (e == hipSuccess) e = hipMemset(a + lo.off_cnt, 0, (size_t)2 * cfg->n_layers * 4);
   // rows that are allocated but not (yet) written must hold finite values: masked rows still enter the
   // weighted sum with weight zero
-  if (e == hipSuccess) e = hipMemset(a + lo.off_k, 0, (lo.coarse ? lo.coff_units : lo.arena_bytes) - lo.off_k);
+  if (e == hipSuccess) e = hipMemset(a + lo.off_k, 0, lo.rows_end - lo.off_k);
+  up(lo.off_stream, lo.stream_blob.data(), lo.stream_blob.size());
   if (e != hipSuccess) { delete c; return HKV_EHIP; }
   *out = c;
   return HKV_OK;
@@ -630,15 +737,47 @@ int hkv_compress_from_scores(hkv_cache* cache, int layer_begin, int layer_end, c
 // of 256 rows 24.8 us; a call per layer is 23 % slower with the large tiles).
 static bool call_uses_coarse_tiling(const hkv_cache* c, int lb, int le) {
   if (!c->lo.coarse || c->lo.mode == 4) return false;
+  if (c->lo.mode == 5) return false;            // a streamed cache's other layer ranges take the first tiling
   const Layout& co = *c->lo.coarse;
   const int fine_tiles = c->lo.item_begin[le] - c->lo.item_begin[lb];
   const int coarse_tiles = co.item_begin[le] - co.item_begin[lb];
   return fine_tiles > c->n_cus && coarse_tiles <= c->n_cus;
 }
 
+// The table a streamed call over [lb, le) walks, or null when the call does not run streamed: the cache is
+// not in that shape, or the range is neither all layers nor a single one (such calls take the tiles).
+// The table is the one made for the largest reference tail length not above the tail the host knows of.
+static const StreamTable* stream_table_of_call(const hkv_cache* c, int lb, int le, const StreamShape** shape) {
+  if (c->lo.mode != 5 || c->lo.stream_shapes.empty()) return nullptr;
+  const int L = c->cfg.n_layers;
+  int s = -1;
+  if (lb == 0 && le == L) s = 0;
+  else if (le == lb + 1) s = 1 + lb;
+  if (s < 0 || s >= (int)c->lo.stream_shapes.size()) return nullptr;
+  const StreamShape& sh = c->lo.stream_shapes[s];
+  const int t = c->host_tail[lb];
+  const StreamTable* tb = &sh.tables[0];
+  for (const StreamTable& x : sh.tables) if (x.t_ref <= t) tb = &x;
+  if (shape) *shape = &sh;
+  return tb;
+}
+
+// Record slots a decode call over [lb, le) may write (tail at full capacity for the tile shapes).
+static size_t call_record_slots(const hkv_cache* c, int lb, int le) {
+  const StreamShape* sh = nullptr;
+  if (const StreamTable* tb = stream_table_of_call(c, lb, le, &sh)) return (size_t)tb->n_wg + (size_t)sh->n_units;
+  const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
+  return (size_t)(lo.item_begin[le] - lo.item_begin[lb]);
+}
+
 int hkv_cache_call_tiling(const hkv_cache* c, int lb, int le, int32_t* tile_rows, int32_t* n_tiles) {
   const int rc = check_range(c, lb, le);
   if (rc != HKV_OK) return rc;
+  if (const StreamTable* tb = stream_table_of_call(c, lb, le, nullptr)) {
+    if (tile_rows) *tile_rows = tb->share_rows;
+    if (n_tiles) *n_tiles = tb->n_wg;
+    return HKV_OK;
+  }
   const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
   if (tile_rows) *tile_rows = lo.tile;
   if (n_tiles) *n_tiles = lo.item_begin[le] - lo.item_begin[lb];
@@ -660,10 +799,15 @@ static int check_decode_args(const hkv_cache* c, int lb, int le, const void* q, 
   return HKV_OK;
 }
 
-// The launches of one decode step over layers [lb, le), arguments already checked.  parts / parts_ml: the
-// split-K records of the call's tiles ([tiles][G][128] floats) and their (max, sum) lines ([tiles][16] floats).
+// The launches of one decode step over layers [lb, le), arguments already checked.  `records`: room for the
+// call's split-K records, [slots][G][128] floats followed (256-byte aligned) by their (max, sum) lines,
+// [slots][16] floats, slots = call_record_slots().
 static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new, void* out,
-                           float* parts, float* parts_ml, void* stream) {
+                           void* records, void* stream) {
+  const size_t n_slots = call_record_slots(c, lb, le);
+  float* parts = static_cast<float*>(records);
+  float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(records) +
+                                             align_up(n_slots * (size_t)(c->cfg.n_q_heads / c->cfg.n_kv_heads) * kD * sizeof(float)));
   const bool use_coarse = call_uses_coarse_tiling(c, lb, le);
   const Layout& lo = use_coarse ? *c->lo.coarse : c->lo;
   const CacheView& cv = use_coarse ? c->cv_coarse : c->cv;
@@ -683,11 +827,31 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
   hipEvent_t* ev = prof ? &c->events[(size_t)6 * c->prof_calls] : none;
   hipError_t e = hipSuccess;
   const int dt = c->cfg.dtype, app = k_new ? 1 : 0;
-  const int mode = c->lo.mode;
+  const StreamShape* sshape = nullptr;
+  const StreamTable* stable = stream_table_of_call(c, lb, le, &sshape);
+  const int mode = c->lo.mode == 5 && !stable ? 3 : c->lo.mode;      // streamed caches run other layer ranges as tiles
   const int resident = 3 * c->n_cus;      // workgroups resident at once (three per compute unit)
   if (c->cfg.chunk_score_group == 1) {    // the other group reading scores the chunks in a launch of its own
     e = launch_chunk_score_max(cv, dt, lb, db, nd, q, t_before, st);
     if (e != hipSuccess) return HKV_EHIP;
+  }
+  if (mode == 5) {
+    // equal shares of the call's rows, one per workgroup; units that several workgroups touched are combined after
+    const char* tables = c->arena + c->lo.off_stream;
+    e = launch_stream(c->cv, dt, reinterpret_cast<const StreamBound*>(tables + stable->off_bounds), stable->n_wg,
+                      sshape->unit_begin, lb, q, k_new, v_new, parts, parts_ml, out, t_before,
+                      c->lo.max_chunks, st, ev[0], ev[1]);
+    if (e == hipSuccess)
+      e = launch_stream_merge(c->cv, dt, reinterpret_cast<const StreamMulti*>(tables + stable->off_multi), stable->n_multi,
+                              sshape->unit_begin, lb, le, parts, parts_ml, out, t_before, st, ev[4], ev[5]);
+    if (e != hipSuccess) return HKV_EHIP;
+    if (prof) {
+      c->prof_mask[c->prof_calls] = (uint8_t)(1 | (stable->n_multi > 0 ? 4 : 0));
+      c->prof_calls += 1;
+      c->prof_stream = st;
+    }
+    if (k_new && !c->device_tail) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
+    return HKV_OK;
   }
   if (mode == 4) {
     // one wide workgroup per unit writes the unit's output rows itself: no records, no combination
@@ -740,30 +904,24 @@ int hkv_decode_attn(hkv_cache* c, int lb, int le, const void* q, const void* k_n
   if (!workspace) return HKV_EINVAL;
   if (!aligned16(workspace)) return HKV_EALIGN;
   if (workspace_bytes < c->lo.ws_bytes) return HKV_ENOSPACE;
-  const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
-  return decode_launches(c, lb, le, q, k_new, v_new, out, static_cast<float*>(workspace),
-                         reinterpret_cast<float*>(static_cast<char*>(workspace) + lo.ws_o_bytes), stream);
+  return decode_launches(c, lb, le, q, k_new, v_new, out, workspace, stream);
 }
 
 int hkv_decode_attn_noalloc(hkv_cache* c, int lb, int le, const void* q, const void* k_new, const void* v_new,
                             void* out, void* stream) {
   int rc = check_range(c, lb, le);
   if (rc != HKV_OK) return rc;
-  // the records of this call's tiles must fit the library's array (tail at full capacity, as the tables count them)
-  const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
-  const size_t n_tiles = (size_t)(lo.item_begin[le] - lo.item_begin[lb]);
+  // the records of this call must fit the library's array (tile shapes: tail at full capacity, as the tables count them)
+  const size_t n_slots = call_record_slots(c, lb, le);
   const size_t G = (size_t)(c->cfg.n_q_heads / c->cfg.n_kv_heads);
-  const size_t o_bytes = align_up(n_tiles * G * kD * sizeof(float));
-  const size_t need = o_bytes + align_up(n_tiles * kMlFloats * sizeof(float));
+  const size_t need = align_up(n_slots * G * kD * sizeof(float)) + align_up(n_slots * kMlFloats * sizeof(float));
   if (need > (size_t)HKV_NOALLOC_SCRATCH_BYTES) return HKV_ENOSPACE;
   rc = check_decode_args(c, lb, le, q, k_new, v_new, out);
   if (rc != HKV_OK) return rc;
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return HKV_EHIP;
   if (dev != c->device || !c->scratch_dev) return HKV_ESTATE;      // the array's address belongs to the cache's device
-  char* base = static_cast<char*>(c->scratch_dev);
-  return decode_launches(c, lb, le, q, k_new, v_new, out, reinterpret_cast<float*>(base),
-                         reinterpret_cast<float*>(base + o_bytes), stream);
+  return decode_launches(c, lb, le, q, k_new, v_new, out, c->scratch_dev, stream);
 }
 
 int hkv_reselect_chunks(hkv_cache* c, int lb, int le, void* stream) {
@@ -949,9 +1107,9 @@ int hkv_cache_decode_shape(const hkv_cache* c, int32_t* tile_rows, int32_t* dyna
 }
 
 int hkv_cache_set_decode_dynamic(hkv_cache* c, int32_t dynamic_mode) {
-  if (!c || dynamic_mode < 1 || dynamic_mode > 4) return HKV_EINVAL;
-  if (dynamic_mode == 4 && c->cfg.dtype != HKV_BF16) return HKV_ESHAPE;
-  if (c->cfg.index_generated && dynamic_mode == 2) return HKV_ESHAPE;
+  if (!c || dynamic_mode < 1 || dynamic_mode > 5) return HKV_EINVAL;
+  if (dynamic_mode >= 4 && c->cfg.dtype != HKV_BF16) return HKV_ESHAPE;
+  if (c->cfg.index_generated && (dynamic_mode == 2 || dynamic_mode == 5)) return HKV_ESHAPE;
   c->lo.mode = dynamic_mode;
   return HKV_OK;
 }

@@ -17,6 +17,7 @@
 // The logits of a pass are materialised (rows x C floats per head): the exact top-k of a row needs the
 // whole row several times, and 288 GB of HBM make that the simple way to have it.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -656,12 +657,12 @@ int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seql
   const float scale_log2e = scale * 1.4426950408889634f;
   const size_t logits_room = workspace_bytes - sh.off_logits;
   const size_t smem = (size_t)kRowsPerBlock * (kD * es + 16);
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[cfg->dtype == HKV_BF16]) {
+  static std::atomic<bool> attr_set[2] = {{false}, {false}};
+  if (!attr_set[cfg->dtype == HKV_BF16].load(std::memory_order_acquire)) {
     const void* fn = cfg->dtype == HKV_BF16 ? reinterpret_cast<const void*>(&logits_kernel<bf16_t>)
                                             : reinterpret_cast<const void*>(&logits_kernel<float>);
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) return HKV_EHIP;
-    attr_set[cfg->dtype == HKV_BF16] = true;
+    attr_set[cfg->dtype == HKV_BF16].store(true, std::memory_order_release);
   }
   for (int l = 0; l < n_layers_call; ++l) {
     const char* q_layer = static_cast<const char*>(q_prompt) + (size_t)l * total * Hq * kD * es;

@@ -25,6 +25,7 @@
 #include "hkv_select.h"
 
 #include <algorithm>
+#include <atomic>
 
 // A launch that carries start/stop events when a profiled call asks for them and is a plain launch
 // otherwise (plain launches are what stream capture records).
@@ -830,12 +831,12 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
 // Writes the step's new K/V row of one unit into its tail (all threads of the block; ends with a barrier,
 // so the row is in memory before any lane of this block reads it).
 template <typename T>
-__device__ __forceinline__ void append_row(const CacheView& cv, const AttnItem& it, int lrel, int t_before,
+__device__ __forceinline__ void append_row(const CacheView& cv, int seq, int head, int64_t tail_off, int lrel, int t_before,
                                            const T* __restrict__ k_new, const T* __restrict__ v_new) {
   constexpr int LPR = Elem<T>::kLanesPerRow;
   const int tid = thread_index();
-  const size_t src_row = (((size_t)lrel * cv.batch + it.seq) * cv.n_kv_heads + it.head) * kD * sizeof(T);
-  const int64_t prow = it.tail_off + t_before;                 // row in the device arrays
+  const size_t src_row = (((size_t)lrel * cv.batch + seq) * cv.n_kv_heads + head) * kD * sizeof(T);
+  const int64_t prow = tail_off + t_before;                    // row in the device arrays
   if constexpr (sizeof(T) == 2) {
     // blocked cache: 16 key pieces go to their slots of the row's block, V is scattered one element per dim
     const size_t blk_off = (size_t)(prow >> 3) * kBlkBytes;
@@ -902,7 +903,7 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   const int lrel = it.layer - layer_begin;
   const int new_row = it.n_prompt_rows + t_rest;            // logical index of the appended row
   if (append && new_row >= it.row0 && new_row < it.row0 + TILE) {  // block-uniform
-    append_row<T>(cv, it, lrel, t_before, k_new, v_new);
+    append_row<T>(cv, it.seq, it.head, it.tail_off, lrel, t_before, k_new, v_new);
     if constexpr (INDEXED && sizeof(T) == 2) {
       if (it.dynamic && ((t_before + 1) & ((1 << it.c_log2) - 1)) == 0)    // the new token completes a chunk
         index_generated_chunk(cv, it, t_before >> it.c_log2);
@@ -1150,6 +1151,113 @@ void unit_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int st
                                                  picks, orow);
 }
 
+// ------------------------------------------------------------------------------------------
+// streamed shape: every workgroup takes an equal share of the step's rows
+// ------------------------------------------------------------------------------------------
+// The rows a step attends (every unit of the call, in unit order, each unit's rows in steps of 32) form one
+// line of work; the host cuts it into as many equal shares as the launch has workgroups (a table made when
+// the cache was laid out, one per call shape and reference tail length) and workgroup i walks its share:
+// it may end one unit, cross several whole units and begin another.  Per unit it touches it leaves one
+// record at slot i + (unit's position in the call) -- those sums grow along the line of work, so slots
+// are unique -- or, when the unit lies wholly inside its share, the unit's output rows themselves.  All
+// workgroups read the same number of bytes and end together; what a fresh workgroup per tile pays at
+// every tile (dispatch, descriptor, first loads' latency, record) is paid once per unit crossed.
+// A boundary (unit, row) has 0 <= row < rows of the unit at the table's reference tail length, row a
+// multiple of 32; the end of a unit is written as the start of the next.  A segment that reaches its
+// unit's end in the table takes every row the unit has now (the tail may be longer than the table
+// assumed); one that begins beyond the rows the unit has now is empty and leaves a neutral record.
+// Dynamic units: a workgroup selects the chunks of every dynamic unit it touches (like the tiles that repeat
+// the selection); the workgroup holding row 0 leaves scores and picks in memory for export.
+// Where the logical rows of a unit live, for a step in which the unit has n_rows of them.
+__device__ __forceinline__ RowMap row_map_of_unit(const CacheView& cv, const UnitDesc& d, int n_rows, const int32_t* picks) {
+  const bool dyn = d.kind == HKV_DYNAMIC;
+  RowMap rm;
+  rm.n_rows = n_rows;
+  rm.kbase = reinterpret_cast<const char*>(dyn ? cv.k_dyn : cv.k_rows) + (size_t)d.kv_row_off * kD * 2;
+  rm.vbase = reinterpret_cast<const char*>(dyn ? cv.v_dyn : cv.v_rows) + (size_t)d.kv_row_off * kD * 2;
+  rm.ktail = (int64_t)(reinterpret_cast<intptr_t>(cv.k_rows) + d.tail_off * (int64_t)(kD * 2) - reinterpret_cast<intptr_t>(rm.kbase));
+  rm.vtail = (int64_t)(reinterpret_cast<intptr_t>(cv.v_rows) + d.tail_off * (int64_t)(kD * 2) - reinterpret_cast<intptr_t>(rm.vbase));
+  rm.stride = kD * 2;
+  rm.dynamic = dyn ? 1 : 0;
+  rm.sel = picks;
+  rm.n_sel_rows = d.n_prompt_rows;
+  rm.c_log2 = d.c_log2;
+  rm.C = d.C;
+  rm.tail_row = d.tail_row;
+  rm.n_chunks_prompt = d.n_chunks;
+  rm.gen0 = 0;
+  return rm;
+}
+
+template <int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void stream_kernel(CacheView cv, const StreamBound* __restrict__ bounds, int unit_base, int layer_begin,
+                   const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
+                   PartOut partials, bf16_t* __restrict__ out, int t_arg, int lds_sel_off) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  const StreamBound b0 = bounds[blockIdx.x], b1 = bounds[blockIdx.x + 1];
+  int u = __builtin_amdgcn_readfirstlane(b0.unit), ra = __builtin_amdgcn_readfirstlane(b0.row);
+  const int u_last = __builtin_amdgcn_readfirstlane(b1.unit), r_last = __builtin_amdgcn_readfirstlane(b1.row);
+  StepBufs sb;                   // the operands in flight
+  sb.nv = 0;
+  bool here = u < u_last || (u == u_last && ra < r_last);        // workgroup-uniform
+  while (here) {
+    const UnitDesc d = cv.units[unit_base + u];
+    const bool more = u + 1 < u_last || (u + 1 == u_last && 0 < r_last);     // another unit of the share follows
+    const int lrel = d.layer - layer_begin;
+    const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[d.layer];
+    const bool append = (k_new != nullptr) && (t_before < cv.max_new);
+    const int n_rows = d.n_prompt_rows + t_before + (append ? 1 : 0);      // logical rows the unit has in this step
+    const bool to_end = u < u_last;                                       // else the share ends inside this unit
+    const int rb = to_end ? n_rows : min(r_last, n_rows);
+    if (ra == 0 && d.seq == 0 && d.head == 0 && thread_index() == 0)       // one workgroup per layer moves the tail counter on
+      (t_arg >= 0 ? cv.cnt_a : cv.cnt_b)[d.layer] = t_before + (append ? 1 : 0);
+    const int new_row = n_rows - 1;                                        // logical index of the appended row, if any
+    const bool appends_here = append && ra <= new_row && new_row < rb;
+    const size_t qoff = (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G) * kD;
+    const bool whole = ra == 0 && to_end;                                  // the unit lies inside this share: write its output rows
+    const size_t slot = (size_t)blockIdx.x + (size_t)u;
+    const PartOut part = {whole ? nullptr : partials.o + slot * G * kD, whole ? nullptr : partials.ml + slot * kMlStride,
+                          whole ? reinterpret_cast<uint16_t*>(out) + qoff : nullptr};
+    if (d.kind == HKV_DYNAMIC) {
+      const int32_t* picks = nullptr;
+      if (ra < rb) {
+        int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
+        select_chunks_of_unit<bf16_t>(cv, d, lrel, q, cv.sigma_max, smem, sel_lds, ra == 0);
+        __syncthreads();                                                   // the picks are in shared memory; the scratch is free
+        picks = sel_lds;
+      }
+      if (appends_here) append_row<bf16_t>(cv, d.seq, d.head, d.tail_off, lrel, t_before, k_new, v_new);
+      attn_tile_mfma<G, 1>(row_map_of_unit(cv, d, n_rows, picks), q + qoff, cv.scale_log2e, ra, rb - ra, part, smem, sb,
+                           false);
+    } else {
+      if (appends_here) append_row<bf16_t>(cv, d.seq, d.head, d.tail_off, lrel, t_before, k_new, v_new);
+      attn_tile_mfma<G, 0>(row_map_of_unit(cv, d, n_rows, nullptr), q + qoff, cv.scale_log2e, ra, rb - ra, part, smem, sb,
+                           false);
+    }
+    lds_barrier();                                                         // the staging area is free for the next unit
+    u += 1;
+    ra = 0;
+    here = more;
+  }
+}
+
+// Combination of the records of the units that more than one workgroup of stream_kernel touched.
+// grid = listed units x G, block = 128 threads.
+template <typename T>
+__global__ __launch_bounds__(128) void stream_merge_kernel(CacheView cv, const StreamMulti* __restrict__ multi, int unit_base,
+                                                           int layer_begin, PartOut partials, T* __restrict__ out) {
+  const int G = cv.G;
+  const int g = blockIdx.x % G;
+  const StreamMulti m = multi[blockIdx.x / G];
+  const UnitDesc d = cv.units[unit_base + m.unit];
+  const int lrel = d.layer - layer_begin;
+  const float* o0 = partials.o + ((size_t)m.slot0 * G + g) * kD;
+  const float* ml0 = partials.ml + (size_t)m.slot0 * kMlStride + 2 * g;
+  T* orow = out + (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * G + g) * kD;
+  merge_head<T>(o0, ml0, m.n_rec, G * kD, orow);
+}
+
 // grid = n_units x G, block = 128 threads; descs points at the first unit's descriptor.
 template <typename T>
 __global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, const UnitDesc* __restrict__ descs,
@@ -1257,12 +1365,12 @@ static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_
                                   int select_only, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const PartOut partials = {parts_o, parts_ml};
   const size_t smem = std::max(attn_smem_bytes<T, G, true>(), select_smem_bytes(max_chunks));
-  static size_t attr = 0;      // per instantiation; the attribute is sticky for the process
-  if (smem > attr) {
+  static std::atomic<size_t> attr{0};      // per instantiation; the attribute is sticky for the process
+  if (smem > attr.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, G, INDEXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr = smem;
+    attr.store(smem, std::memory_order_release);
   }
   if (n_dyn + n_sitems > 0)
     HKV_LAUNCH((decode_kernel<T, G, INDEXED>), dim3(n_dyn + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1, cv,
@@ -1316,12 +1424,12 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
   // reselect: selection scratch and the tile's staging area share the front; the picks sit behind both
   const size_t front = std::max(attn_smem_bytes<T, G, true>(), reselect ? select_smem_bytes(max_chunks) : (size_t)0);
   const size_t smem = front + (reselect ? (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t) : 0);
-  static size_t attr = 0;
-  if (smem > attr) {
+  static std::atomic<size_t> attr{0};
+  if (smem > attr.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G, INDEXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr = smem;
+    attr.store(smem, std::memory_order_release);
   }
   HKV_LAUNCH((dynamic_tiles_kernel<T, G, INDEXED>), dim3(n_ditems + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1,
                         cv, layer_begin, ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
@@ -1360,12 +1468,12 @@ static hipError_t launch_units_t(const CacheView& cv, int layer_begin, int dyn_b
   // selection scratch and the waves' staging area share the front; the picks sit behind both
   const size_t front = std::max((size_t)kUnitWaves * G * kPartStride * sizeof(float), select_smem_bytes(max_chunks));
   const size_t smem = front + (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t);
-  static size_t attr = 0;
-  if (smem > attr) {
+  static std::atomic<size_t> attr{0};
+  if (smem > attr.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unit_kernel<G, INDEXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr = smem;
+    attr.store(smem, std::memory_order_release);
   }
   HKV_LAUNCH((unit_kernel<G, INDEXED>), dim3(n_dyn + n_static), dim3(kUnitWaves * 64), (uint32_t)smem, st, ev0, ev1, cv, layer_begin,
              dyn_begin, n_dyn, static_begin, (const bf16_t*)q, (const bf16_t*)k_new, (const bf16_t*)v_new, (bf16_t*)out,
@@ -1406,6 +1514,52 @@ hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* des
   return hipGetLastError();
 }
 
+template <int G>
+static hipError_t launch_stream_t(const CacheView& cv, const StreamBound* bounds, int n_wg, int unit_base, int layer_begin,
+                                  const void* q, const void* k_new, const void* v_new, float* parts_o,
+                                  float* parts_ml, void* out, int t_arg, int max_chunks, hipStream_t st, hipEvent_t ev0,
+                                  hipEvent_t ev1) {
+  const PartOut partials = {parts_o, parts_ml, nullptr};
+  // selection scratch and the waves' staging area share the front; the picks sit behind both
+  const size_t front = std::max(attn_smem_bytes<bf16_t, G, true>(), select_smem_bytes(max_chunks));
+  const size_t smem = front + (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t);
+  static std::atomic<size_t> attr{0};          // per instantiation; the attribute is sticky for the process
+  if (smem > attr.load(std::memory_order_acquire)) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_kernel<G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr.store(smem, std::memory_order_release);
+  }
+  HKV_LAUNCH((stream_kernel<G>), dim3(n_wg), dim3(256), (uint32_t)smem, st, ev0, ev1, cv, bounds, unit_base, layer_begin,
+             (const bf16_t*)q, (const bf16_t*)k_new, (const bf16_t*)v_new, partials, (bf16_t*)out, t_arg,
+             (int)(front / sizeof(float)));
+  return hipGetLastError();
+}
+
+hipError_t launch_stream(const CacheView& cv, int dtype, const StreamBound* bounds, int n_wg, int unit_base, int layer_begin,
+                         const void* q, const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
+                         void* out, int t_arg, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (dtype != HKV_BF16 || cv.index_gen) return hipErrorInvalidValue;
+  if (n_wg <= 0) return hipSuccess;
+  HKV_DISPATCH_G(cv.G, return (launch_stream_t<GG>(cv, bounds, n_wg, unit_base, layer_begin, q, k_new, v_new, parts_o,
+                                                   parts_ml, out, t_arg, max_chunks, st, ev0, ev1)));
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_stream_merge(const CacheView& cv, int dtype, const StreamMulti* multi, int n_multi, int unit_base,
+                               int layer_begin, int layer_end, float* parts_o, float* parts_ml, void* out, int t_arg,
+                               hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (dtype != HKV_BF16) return hipErrorInvalidValue;
+  const PartOut partials = {parts_o, parts_ml, nullptr};
+  if (n_multi > 0)
+    HKV_LAUNCH(stream_merge_kernel<bf16_t>, dim3(n_multi * cv.G), dim3(128), 0u, st, ev0, ev1, cv, multi, unit_base,
+               layer_begin, partials, (bf16_t*)out);
+  if (t_arg < 0 && layer_end > layer_begin)
+    hipLaunchKernelGGL(publish_tail_kernel, dim3((layer_end - layer_begin + 63) / 64), dim3(64), 0, st, cv, layer_begin,
+                       layer_end);
+  return hipGetLastError();
+}
+
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st) {
   if (layer_end <= layer_begin) return hipSuccess;
   hipLaunchKernelGGL(rewind_kernel, dim3((layer_end - layer_begin + 63) / 64), dim3(64), 0, st, cv, layer_begin,
@@ -1418,12 +1572,12 @@ static hipError_t launch_full_t(const FullView& fv, const void* q, const void* k
                                 float* parts_ml, void* out, hipStream_t st) {
   const PartOut partials = {parts_o, parts_ml};
   constexpr size_t smem = attn_smem_bytes<T, G, false>();
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&full_attn_kernel<T, G>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   const int n_units = fv.n_layers_call * fv.batch * fv.n_kv_heads;
   hipLaunchKernelGGL((full_attn_kernel<T, G>), dim3(fv.n_tiles_max, n_units), dim3(256), smem, st, fv, (const T*)q,

@@ -76,6 +76,12 @@ struct AttnItem {
   int64_t tail_off;     // first row of the unit's decode tail in the device K / V row arrays
 };
 
+// Streamed decode shape: boundary of a workgroup's share of the step's rows (unit counted from the first
+// unit of the call, row a multiple of 32 inside that unit), and a unit whose rows more than one workgroup
+// reads (its records sit in consecutive slots).
+struct StreamBound { int32_t unit; int32_t row; };
+struct StreamMulti { int32_t unit; int32_t slot0; int32_t n_rec; int32_t pad_; };
+
 struct CacheView {
   const UnitDesc* units;
   const AttnItem* static_items;   // tiles of static units, layer-major
@@ -131,6 +137,16 @@ hipError_t launch_units(const CacheView& cv, int dtype, int layer_begin, int dyn
 hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* descs, int n_units, int layer_begin,
                              int layer_end, int slot_base, float* parts_o, float* parts_ml, void* out, int t_arg,
                              int appending, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+// Streamed shape (bf16 caches that do not index generated tokens): n_wg workgroups walk equal shares of the
+// call's rows, then the units several workgroups touched are combined (also publishes device-side tail
+// counters when t_arg < 0).
+hipError_t launch_stream(const CacheView& cv, int dtype, const StreamBound* bounds, int n_wg, int unit_base, int layer_begin,
+                         const void* q, const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
+                         void* out, int t_arg, int max_chunks, hipStream_t st, hipEvent_t ev0 = nullptr,
+                         hipEvent_t ev1 = nullptr);
+hipError_t launch_stream_merge(const CacheView& cv, int dtype, const StreamMulti* multi, int n_multi, int unit_base,
+                               int layer_begin, int layer_end, float* parts_o, float* parts_ml, void* out, int t_arg,
+                               hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 hipError_t launch_rewind(const CacheView& cv, int layer_begin, int layer_end, hipStream_t st);
 
 struct FullView {

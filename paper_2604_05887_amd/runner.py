@@ -60,7 +60,7 @@ def setup(wl, device="cuda:0", budget: Optional[np.ndarray] = None, head_type: O
     return DeviceWorkload(cfg=cfg, plan=plan, cache=cache, q_window=qw, k=k, v=v, dtype=wl.dtype)
 
 
-def tune_decode_dynamic(caches: Sequence, step_fn: Callable[[object, int], None], modes=(1, 2, 3, 4), steps: int = 24,
+def tune_decode_dynamic(caches: Sequence, step_fn: Callable[[object, int], None], modes=(1, 2, 3, 4, 5), steps: int = 24,
                         warmup: int = 6) -> Dict[int, float]:
     """Time the ways a decode step can run on the caller's own caches and keep the fastest on all of
     them (mode 4 exists for bf16 caches only and is skipped elsewhere).  step_fn(cache_holder, i) issues one step WITHOUT appending (k_new = None),
@@ -68,7 +68,7 @@ def tune_decode_dynamic(caches: Sequence, step_fn: Callable[[object, int], None]
     memory-side cache does.  Returns {mode: microseconds per step}."""
     result: Dict[int, float] = {}
     for m in modes:
-        if m == 4 and caches[0].cfg.dtype != B.HKV_BF16:
+        if m >= 4 and caches[0].cfg.dtype != B.HKV_BF16:
             continue
         try:
             for c in caches:

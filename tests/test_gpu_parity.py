@@ -316,7 +316,7 @@ def test_switching_the_decode_shape_on_a_live_cache():
     dw.cache.compress(dw.q_window, dw.k, dw.v)
     q = runner.to_device(wl.q_steps[0], wl.dtype)
     outs = []
-    for mode in (1, 2, 3, 4):
+    for mode in (1, 2, 3, 4, 5):
         dw.cache.set_decode_dynamic(mode)
         assert dw.cache.decode_shape()[1] == mode
         out = torch.empty((2, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
@@ -326,13 +326,14 @@ def test_switching_the_decode_shape_on_a_live_cache():
     for o in outs[1:]:
         assert (o - outs[0]).abs().max().item() <= 2e-2 * outs[0].abs().max().item()
     with pytest.raises(B.HkvError):
-        dw.cache.set_decode_dynamic(5)
+        dw.cache.set_decode_dynamic(6)
     dw.cache.close()
-    wl32 = make_workload(0, shrink=4, steps=1)           # the per-unit shape exists for bf16 caches only
+    wl32 = make_workload(0, shrink=4, steps=1)           # the per-unit and streamed shapes exist for bf16 caches only
     dw = runner.setup(wl32, upload_prompt=False)
-    with pytest.raises(B.HkvError) as ei:
-        dw.cache.set_decode_dynamic(4)
-    assert ei.value.status == B.HKV_ESHAPE
+    for mode in (4, 5):
+        with pytest.raises(B.HkvError) as ei:
+            dw.cache.set_decode_dynamic(mode)
+        assert ei.value.status == B.HKV_ESHAPE
     dw.cache.close()
 
 
@@ -954,3 +955,116 @@ def test_large_tiles_with_tail_lengths_kept_on_the_device():
             assert np.array_equal(Kr[-wl.steps:], wl.k_new[:, 27, 0, 3])
         dw.cache.close()
     assert torch.equal(outs[0], outs[1])
+
+
+# ---- streamed shape: every workgroup walks an equal share of the step's rows (decode_dynamic = 5) ----
+
+@pytest.mark.parametrize("case", ["cfg1", "ragged", "g8", "small_chunks", "host_tier", "max_group", "layer_calls",
+                                  "other_ranges", "tiny"])
+def test_streamed_shape(case):
+    """The streamed launch on the shapes that stress it: heads spanning several workgroups and workgroups
+    spanning several heads (config 1 shape), ragged batch with both chunk sizes, group of eight, many small
+    chunks (radix selection), host tier, the other group reading of the chunk score, per-layer calls (a
+    table per layer), layer ranges that have no table (they run as tiles) mixed with ones that have, and
+    a prompt so small that the call is a single workgroup."""
+    kw = dict(decode_dynamic=5)
+    if case == "cfg1":
+        wl = make_workload(1, n_layers=3, shrink=2, steps=4)
+    elif case == "ragged":
+        wl = make_workload(4, n_layers=2, shrink=8, steps=3)
+    elif case == "g8":
+        wl = make_workload(3, n_layers=2, shrink=16, steps=3)
+    elif case == "small_chunks":
+        wl = make_workload(1, n_layers=2, steps=2)
+        wl.chunk_size[:] = 16
+        wl.budget[wl.head_type == O.DYNAMIC] = 16 * 300
+    elif case == "host_tier":
+        wl = make_workload(1, n_layers=2, shrink=2, steps=3)
+        kw["host_tier"] = True
+    elif case == "max_group":
+        wl = make_workload(1, n_layers=2, shrink=2, steps=3)
+        kw["chunk_score_group"] = 1
+    elif case == "layer_calls":
+        wl = make_workload(1, n_layers=3, shrink=4, steps=3)
+        kw["layer_ranges"] = [(0, 1), (1, 2), (2, 3)]
+    elif case == "other_ranges":
+        wl = make_workload(1, n_layers=3, shrink=4, steps=3)
+        kw["layer_ranges"] = [(0, 2), (2, 3)]
+    else:
+        wl = make_workload(1, n_layers=1, shrink=32, steps=3)
+    stats = P.full_pipeline(wl, **kw)
+    _say(f"streamed shape, {case}", stats)
+
+
+def test_streamed_shape_long_generation_crosses_the_reference_tail_lengths():
+    """300 decode steps on a short prompt: the tail outgrows one table's reference length after another
+    (every 32 tokens up to 256, then 384), the appended row moves from share to share, and between two
+    reference lengths the last share of every head takes the rows the table did not count."""
+    wl = make_workload(1, n_layers=1, shrink=8, steps=300)
+    stats = P.full_pipeline(wl, decode_dynamic=5)
+    _say("streamed shape, 300 steps", stats)
+
+
+def test_streamed_shape_at_full_size_whole_model_and_per_layer_calls():
+    """Config 1 at full size (28 layers, 8192-token prompt, 768 workgroups over 112 heads): whole-model
+    calls and per-layer calls in turn, tails growing through both, oracle on sampled layers at every step;
+    then the same steps with the tail lengths kept on the device give the same bits."""
+    wl = make_workload(1, steps=4)
+    layers = [0, 13, 27]
+    dw = runner.setup(wl, decode_dynamic=5)
+    whole, one = dw.cache.call_tiling(), dw.cache.call_tiling(5, 6)
+    print(f"\n[streamed] whole-model call {whole}, one layer {one}", flush=True)
+    assert 1 <= one[1] < whole[1] <= 768
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    torch.cuda.synchronize()
+    ocfg, oplan = P.oracle_setup(wl)
+    ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers)
+    stats = {}
+    overrides = P.compare_compress(wl, dw, ocache, stats)
+    if overrides:
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers, keep_override=overrides)
+    per_layer = [(l, l + 1) for l in range(28)]
+    P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers,
+                             layer_ranges_by_step=[None, per_layer, None, [(0, 14), (14, 28)]])
+    _say("streamed, full size", stats)
+    dw.cache.close()
+    outs = []
+    for device_tail in (False, True):
+        dw = runner.setup(wl, decode_dynamic=5)
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+        if device_tail:
+            dw.cache.set_device_tail(True)
+        out = torch.empty((wl.n_layers, 1, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+        res = []
+        for s in range(wl.steps):
+            q, kn, vn = (runner.to_device(x[s], wl.dtype) for x in (wl.q_steps, wl.k_new, wl.v_new))
+            dw.cache.decode_attn(q, kn, vn, out)
+            torch.cuda.synchronize()
+            res.append(out.clone())
+        outs.append(torch.stack(res))
+        if device_tail:
+            dw.cache.set_device_tail(False)
+            Kr = dw.cache.export(B.HKV_X_K_ROWS, 0, 27, 3)
+            assert np.array_equal(Kr[-wl.steps:], wl.k_new[:, 27, 0, 3])
+        dw.cache.close()
+    assert torch.equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("cfg_id,n_layers,steps", [(2, 2, 3), (3, 2, 2), (4, 1, 2)])
+def test_streamed_shape_on_the_larger_shapes_at_full_context(cfg_id, n_layers, steps):
+    """Configs 2, 3 and 4 at their real per-head sizes through the streamed launch (oracle on one layer)."""
+    wl = make_workload(cfg_id, n_layers=n_layers, steps=steps)
+    layers = [n_layers - 1]
+    dw = runner.setup(wl, decode_dynamic=5)
+    print(f"\n[cfg{cfg_id} streamed] call {dw.cache.call_tiling()}", flush=True)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    torch.cuda.synchronize()
+    ocfg, oplan = P.oracle_setup(wl)
+    ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers)
+    stats = {}
+    overrides = P.compare_compress(wl, dw, ocache, stats)
+    if overrides:
+        ocache = O.compress(ocfg, oplan, wl.q_window, wl.k, wl.v, wl.is_visual, layers=layers, keep_override=overrides)
+    P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers)
+    _say(f"cfg{cfg_id} streamed, full context", stats)
+    dw.cache.close()

@@ -42,13 +42,14 @@ def _step_both(wl, a, b, s, layer_begin=0, layer_end=None, append=True):
     return out_a, out_b
 
 
-@pytest.mark.parametrize("mode", [3, 1, 2])
+@pytest.mark.parametrize("mode", [3, 1, 2, 5])
 def test_noalloc_entry_point_matches_the_workspace_entry_point(mode):
     big = make_workload(1, n_layers=3, shrink=4, steps=4)          # several tiles per head, bf16
-    small = make_workload(0, shrink=4, steps=3)                    # one fp32 layer: far fewer, smaller records
+    # the second, smaller input: one fp32 layer (far fewer, smaller records); fp32 caches have no streamed shape
+    small = make_workload(0, shrink=4, steps=3)
     print(f"\n[noalloc] mode={mode} big={big.name} small={small.name}", flush=True)
     big_a, big_b = _pair(big, decode_dynamic=mode)
-    small_a, small_b = _pair(small, decode_dynamic=mode)
+    small_a, small_b = _pair(small, decode_dynamic=3 if mode == 5 else mode)
     ocfg, oplan = P.oracle_setup(big)
     ocache = O.compress(ocfg, oplan, big.q_window, big.k, big.v, big.is_visual)
     kept_same = all(np.array_equal(big_b.cache.export(B.HKV_X_KEPT_IDX, *key), u.kept)
