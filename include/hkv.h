@@ -373,7 +373,12 @@ HKV_API int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t*
  *   static head: ceil(alpha * B_stat / N_stat + (1 - alpha) * B_stat * score / (sum of static scores));
  *   dynamic head: B_dyna / N_dyna, rounded to the nearest power of two (ties upwards) if pad_pow2 != 0,
  *                 else rounded down.
- * The budgets feed hkv_plan.budget as they are ("total retained prompt tokens" for static heads). */
+ * Every ceiling is taken of its argument minus 1e-9, so that a product that is a whole number up to
+ * floating-point error does not creep up to the next integer.
+ * The budgets feed hkv_plan.budget as they are ("total retained prompt tokens" for static heads).
+ * Errors (nothing is written to head_type or budget): HKV_EINVAL for a NaN or negative score or a
+ * parameter out of range; HKV_EBUDGET when the total is so small that some head would get less than one
+ * token (hkv_plan needs at least one); HKV_ESHAPE when a budget exceeds 2^31 - 1. */
 HKV_API int hkv_allocate_budgets(int32_t n_heads, const float* scores, float theta, int64_t total_budget,
                          float share_ratio, float alpha, int32_t pad_pow2, uint8_t* head_type, int32_t* budget);
 

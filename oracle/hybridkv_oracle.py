@@ -310,7 +310,9 @@ def classify_heads(scores: np.ndarray, theta: float) -> np.ndarray:
 def type_level_budgets(b_total: int, n_stat: int, n_dyn: int, r: float) -> Tuple[int, int]:
     """Split of the total token budget between the head types (Section 3.2, first equation):
     B_dyna = ceil(r * B_bar * N_dyna) with B_bar = B_total / (N_stat + N_dyna); B_stat is the rest.
-    r is clipped to the bound the paper states, r <= B_total / (B_bar * N_dyna)."""
+    r is clipped to the bound the paper states, r <= B_total / (B_bar * N_dyna).
+    (Here and in static_head_budgets the ceiling is taken of the value minus 1e-9: a product that is a
+    whole number up to floating-point error, such as 0.75 of a budget divisible by four, stays there.)"""
     n = n_stat + n_dyn
     if n == 0 or n_dyn == 0:
         return int(b_total), 0

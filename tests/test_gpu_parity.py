@@ -1068,3 +1068,62 @@ def test_streamed_shape_on_the_larger_shapes_at_full_context(cfg_id, n_layers, s
     P.run_decode_and_compare(wl, dw, ocache, wl.steps, stats, oracle_layers=layers)
     _say(f"cfg{cfg_id} streamed, full context", stats)
     dw.cache.close()
+
+
+# ---- classification -> allocation -> plan -> compression -> decode, end to end (Sections 3.1 - 3.3) ----
+
+@pytest.mark.parametrize("cfg_id,n_layers,shrink", [(1, 3, 4), (4, 2, 8)])
+def test_scores_to_budgets_to_compressed_decode_end_to_end(cfg_id, n_layers, shrink):
+    """The whole chain the paper describes, on the device and in the oracle: sparsity scores of the prompt
+    (hkv_head_scores) -> head types at theta = 0.9 and top-down budgets (hkv_allocate_budgets, r = 0.75,
+    alpha = 0.5, power-of-two dynamic budgets) -> hkv_plan -> hkv_compress -> hkv_decode_attn, against
+    head_scores -> classify_heads -> type_level_budgets / static_head_budgets / dynamic_head_budget ->
+    compress -> decode_attn.  Head types must agree wherever the score is not within tolerance of theta;
+    the allocation is exact on the device's own scores and within one token (a ceiling's flip) of the
+    oracle's own chain; compression and decode then run on the allocated plan on both sides."""
+    from hkv_synth import make_prompt_queries
+    theta, r, alpha, frac = 0.9, 0.75, 0.5, 0.2
+    wl = make_workload(cfg_id, n_layers=n_layers, shrink=shrink, steps=3)
+    qp = make_prompt_queries(wl)
+    got = _device_head_scores(wl, qp)                                   # [batch, L, Hkv] float32 values
+    ocfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128,
+                          window=wl.window, dtype=wl.dtype)
+    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual)
+    assert np.abs(got - want).max() <= SCORE_ATOL
+    n_heads = wl.n_layers * wl.n_kv_heads
+    types_dev = np.zeros((wl.batch, wl.n_layers, wl.n_kv_heads), np.uint8)
+    budget_dev = np.zeros((wl.batch, wl.n_layers, wl.n_kv_heads), np.int32)
+    flips = 0
+    for b in range(wl.batch):
+        C = int(wl.seqlens[b])
+        b_total = int(np.ceil(frac * C)) * n_heads                       # the paper's B_total for this prompt
+        t_dev, bud_dev = B.hkv_allocate_budgets(got[b].reshape(-1), theta, b_total, r, alpha, True)
+
+        def oracle_chain(scores):
+            types = O.classify_heads(scores, theta)
+            stat = types == O.STATIC
+            b_stat, b_dyn = O.type_level_budgets(b_total, int(stat.sum()), int((~stat).sum()), r)
+            bud = np.zeros(n_heads, np.int64)
+            bud[stat] = O.static_head_budgets(b_stat, scores[stat], alpha)
+            bud[~stat] = O.dynamic_head_budget(b_dyn, int((~stat).sum()), pad_pow2=True)
+            return types, bud
+
+        # stage-exact: the oracle's equations on the device's own scores
+        t_stage, bud_stage = oracle_chain(got[b].reshape(-1).astype(np.float32).astype(np.float64))
+        assert np.array_equal(t_dev, t_stage) and np.array_equal(bud_dev.astype(np.int64), bud_stage)
+        # end to end: the oracle's own scores
+        t_own, bud_own = oracle_chain(want[b].reshape(-1))
+        clear = np.abs(want[b].reshape(-1) - theta) > 2 * SCORE_ATOL
+        assert np.array_equal(t_dev[clear], t_own[clear])
+        if np.array_equal(t_dev, t_own):
+            diff = np.abs(bud_dev.astype(np.int64) - bud_own)
+            assert diff.max() <= 1, "budgets differ by more than a ceiling's flip"
+            flips += int((diff != 0).sum())
+        types_dev[b] = t_dev.reshape(wl.n_layers, wl.n_kv_heads)
+        budget_dev[b] = bud_dev.reshape(wl.n_layers, wl.n_kv_heads)
+    # the generator's sparse heads come out static, its diffuse ones dynamic
+    assert np.array_equal(types_dev, wl.head_type)
+    assert (types_dev == O.STATIC).any() and (types_dev == O.DYNAMIC).any()
+    stats = P.full_pipeline(wl, budget=budget_dev, head_type=types_dev)
+    stats["budget_ceiling_flips"] = flips
+    _say(f"scores -> budgets -> compress -> decode, cfg{cfg_id}/{shrink}", stats)

@@ -136,19 +136,40 @@ def test_budget_allocation_matches_the_oracle_equations(lib):
         b_total = int(rng.integers(n, 400 * n))
         r, alpha = float(rng.uniform(0.3, 1.2)), float(rng.uniform(0.0, 1.0))
         pad = bool(trial % 2)
-        types, budget = B.hkv_allocate_budgets(scores, theta, b_total, r, alpha, pad)
         want_types = O.classify_heads(scores, theta)
-        assert np.array_equal(types, want_types)
         stat = want_types == O.STATIC
         b_stat, b_dyn = O.type_level_budgets(b_total, int(stat.sum()), int((~stat).sum()), r)
         want = np.zeros(n, np.int64)
         want[stat] = O.static_head_budgets(b_stat, scores[stat].astype(np.float64), alpha)
         want[~stat] = O.dynamic_head_budget(b_dyn, int((~stat).sum()), pad_pow2=pad)
+        if want.min() < 1:                         # a total too small for every head to get a token
+            with pytest.raises(B.HkvError) as ei:
+                B.hkv_allocate_budgets(scores, theta, b_total, r, alpha, pad)
+            assert ei.value.status == B.HKV_EBUDGET
+            continue
+        types, budget = B.hkv_allocate_budgets(scores, theta, b_total, r, alpha, pad)
+        assert np.array_equal(types, want_types)
         assert np.array_equal(budget.astype(np.int64), want), (trial, n, b_total, r, alpha)
     with pytest.raises(B.HkvError):
         B.hkv_allocate_budgets(np.array([0.5, np.nan], np.float32), 0.9, 100, 0.75, 0.5)
     with pytest.raises(B.HkvError):
         B.hkv_allocate_budgets(np.array([0.5], np.float32), 0.9, 100, 0.75, 1.5)
+
+
+def test_budget_allocation_writes_nothing_on_error(lib):
+    """An error return leaves the caller's arrays untouched: a bad score late in the list, and a total
+    too small to give every head a token (three dynamic heads, two tokens, no padding)."""
+    import ctypes as C
+    for scores, total, pad, want in (([0.95, 0.95, 0.5, float("nan")], 100, 1, B.HKV_EINVAL),
+                                     ([0.5, 0.5, 0.5], 2, 0, B.HKV_EBUDGET),
+                                     ([0.95, 0.5, 0.5], 0, 1, B.HKV_EBUDGET)):
+        sc = np.array(scores, np.float32)
+        types = np.full(sc.size, 77, np.uint8)
+        budget = np.full(sc.size, -5, np.int32)
+        st = lib.hkv_allocate_budgets(sc.size, sc.ctypes.data_as(C.POINTER(C.c_float)), 0.9, total, 0.75, 0.5, pad,
+                                      types.ctypes.data_as(C.POINTER(C.c_uint8)), budget.ctypes.data_as(C.POINTER(C.c_int32)))
+        assert st == want
+        assert (types == 77).all() and (budget == -5).all()
 
 
 def test_head_scores_workspace_and_argument_checks(lib):
