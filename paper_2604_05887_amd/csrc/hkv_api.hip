@@ -358,7 +358,7 @@ void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref
   auto put = [&](const void* src, size_t bytes) {
     const size_t off = (blob.size() + 255) / 256 * 256;
     blob.resize(off + std::max<size_t>(bytes, 16));
-    std::memcpy(blob.data() + off, src, bytes);
+    if (bytes) std::memcpy(blob.data() + off, src, bytes);      // an empty list has no data pointer to copy from
     return off;
   };
   tb.off_bounds = put(bounds.data(), bounds.size() * sizeof(StreamBound));
@@ -1173,6 +1173,61 @@ int hkv_cache_import(hkv_cache* c, int what, int seq, int layer, int head, const
   if (bytes != need) return HKV_ENOSPACE;
   if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return HKV_EHIP;
   if (need && hipMemcpy(c->arena + off, src, need, hipMemcpyHostToDevice) != hipSuccess) return HKV_EHIP;
+  return HKV_OK;
+}
+
+// Head types and token budgets of one sequence from its sparsity scores (paper, Section 3.1 threshold and
+// Section 3.2, both allocation equations): host arithmetic only.
+int hkv_allocate_budgets(int32_t n_heads, const float* scores, float theta, int64_t total_budget, float share_ratio,
+                         float alpha, int32_t pad_pow2, uint8_t* head_type, int32_t* budget) {
+  if (n_heads < 1 || !scores || !head_type || !budget || total_budget < 0) return HKV_EINVAL;
+  if (!(share_ratio >= 0.f) || !(alpha >= 0.f) || !(alpha <= 1.f)) return HKV_EINVAL;
+  // every input is checked and every result computed before anything is written: an error leaves the
+  // caller's arrays as they were
+  int n_stat = 0, n_dyn = 0;
+  double stat_sum = 0.0;
+  for (int i = 0; i < n_heads; ++i) {
+    if (!(scores[i] >= 0.f)) return HKV_EINVAL;                    // NaN or negative
+    if (scores[i] >= theta) { ++n_stat; stat_sum += (double)scores[i]; } else ++n_dyn;
+  }
+  // A ceiling is taken of its argument minus 1e-9: a product that is a whole number up to floating-point
+  // error (r = 0.75 of a budget divisible by four) must not creep up to the next integer.
+  constexpr double kCeilSlack = 1e-9;
+  // type level: B_dyna = ceil(r * B_bar * N_dyna), r clipped so that it cannot exceed the total
+  int64_t b_dyn = 0;
+  if (n_dyn > 0) {
+    const double b_bar = (double)total_budget / n_heads;
+    const double r = std::min((double)share_ratio, (double)total_budget / std::max(b_bar * n_dyn, 1e-300));
+    b_dyn = std::min<int64_t>(total_budget, (int64_t)std::ceil(r * b_bar * n_dyn - kCeilSlack));
+  }
+  const int64_t b_stat = total_budget - b_dyn;
+  // dynamic heads: uniform share, optionally to the nearest power of two (ties upwards)
+  int64_t dyn_each = 0;
+  if (n_dyn > 0) {
+    const double b = (double)b_dyn / n_dyn;
+    if (!pad_pow2) dyn_each = (int64_t)b;
+    else if (b <= 1.0) dyn_each = 1;
+    else {
+      const double lo = std::exp2(std::floor(std::log2(b)));
+      dyn_each = (int64_t)((b - lo) < (2.0 * lo - b) ? lo : 2.0 * lo);
+    }
+  }
+  std::vector<int32_t> result((size_t)n_heads);
+  for (int i = 0; i < n_heads; ++i) {
+    int64_t v;
+    if (!(scores[i] >= theta)) v = dyn_each;
+    else {
+      const double s_norm = stat_sum > 0.0 ? (double)scores[i] / stat_sum : 1.0 / n_stat;
+      v = (int64_t)std::ceil((double)alpha * b_stat / n_stat + (1.0 - (double)alpha) * b_stat * s_norm - kCeilSlack);
+    }
+    if (v > 0x7fffffff) return HKV_ESHAPE;
+    if (v < 1) return HKV_EBUDGET;                 // the total is too small to give this head a token: hkv_plan needs >= 1
+    result[(size_t)i] = (int32_t)v;
+  }
+  for (int i = 0; i < n_heads; ++i) {
+    head_type[i] = scores[i] >= theta ? HKV_STATIC : HKV_DYNAMIC;
+    budget[i] = result[(size_t)i];
+  }
   return HKV_OK;
 }
 
