@@ -710,7 +710,21 @@ static int compress_impl(hkv_cache* c, int lb, int le, const void* q_window, con
     float2* part = static_cast<float2*>(workspace);
     float2* fin = reinterpret_cast<float2*>(static_cast<char*>(workspace) +
                                             align_up((size_t)ns * n_splits * kMaxScoreRows * sizeof(float2)));
-    e = launch_score(c->cv, c->cfg.dtype, lb, sb, ns, lo.max_C, q_window, k, lo.total_tokens, part, fin, st);
+    // Keys per scoring block: the one from kKeysPerBlock to twice that (whole 32-key tiles) whose grid takes the
+    // fewest tile-times -- rounds of resident workgroups (three per compute unit) times tiles per block.  A grid
+    // that overflows its last round by a few blocks costs a whole round.
+    int keys_per_block = kKeysPerBlock;
+    {
+      const int64_t resident = 3 * (int64_t)c->n_cus;
+      int64_t best = -1;
+      for (int tiles = kKeysPerBlock / 32; tiles <= 2 * kKeysPerBlock / 32; ++tiles) {
+        int64_t blocks = 0;
+        for (int i = 0; i < ns; ++i) blocks += (lo.units[lo.static_units[sb + i]].C + 32 * tiles - 1) / (32 * tiles);
+        const int64_t cost = (blocks + resident - 1) / resident * tiles;
+        if (best < 0 || cost < best) { best = cost; keys_per_block = 32 * tiles; }
+      }
+    }
+    e = launch_score(c->cv, c->cfg.dtype, lb, sb, ns, lo.max_C, q_window, k, lo.total_tokens, part, fin, keys_per_block, st);
   }
   if (e == hipSuccess) e = launch_select(c->cv, sb, ns, st);
   if (e == hipSuccess) e = launch_compact(c->cv, c->cfg.dtype, lb, sb, ns, lo.max_rows_static, k, v, lo.total_tokens, st);

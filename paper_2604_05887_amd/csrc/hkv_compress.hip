@@ -192,14 +192,218 @@ __global__ __launch_bounds__(256) void score_kernel(CacheView cv, int layer_begi
   }
 }
 
+// bf16 form of score_kernel with the window rows in registers and the keys staged through shared memory.
+// The form above re-reads a query piece from LDS for every matrix instruction (1 KB per wave per
+// instruction: the LDS port's whole bandwidth at full matrix rate), its 70 KB of staged rows leave two
+// workgroups per compute unit, and every lane fetches its own key row from memory (32 cache lines per load
+// instruction).  Here wave w keeps the two 32-row blocks 2w and 2w + 1 of the (at most 256) window rows in
+// registers for the whole key range of the block; the workgroup brings every 32-key tile in once, each
+// load instruction covering four whole 256-byte rows, a tile ahead of its use, and parks it in a
+// double-buffered shared array from which the four waves read their operands (8 KB per wave and tile for 16
+// matrix instructions).  One barrier per tile.
+//   pass 1  keys along the tile's register axis, window rows along lanes: a lane owns its rows' running
+//           maximum and sum outright; nothing crosses lanes until the block's end.
+//   pass 2  the operands swap places -- window rows along the register axis, keys along lanes -- so the sum
+//           over the rows of a column is a sum inside the lane (plus one exchange between the half-waves);
+//           the weight of an element is exp2(logit - c_row) with c_row = row maximum + log2(Z * G * w), one
+//           constant per row.  Per key tile a wave leaves the column sums of its rows in a shared array; the
+//           four waves' sums are added in wave order when the block is done.
+// grid = (key splits, static units of the call); block = 256 threads; a block covers keys_per_block keys (a
+// multiple of 32, at most 32 * kScoreMaxTiles), chosen by the host so that the grid fills whole rounds of
+// resident workgroups (three per compute unit).
+constexpr int kScoreMaxTiles = 32;
+template <int PASS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void score_rows_kernel(CacheView cv, int layer_begin, int static_begin, const bf16_t* __restrict__ q_window,
+                       const bf16_t* __restrict__ k, int64_t total_tokens, float2* __restrict__ part_stats,
+                       const float2* __restrict__ final_stats, int n_splits_max, int keys_per_block) {
+  constexpr int ROWB = kD * 2, NPIECE = ROWB / 32, NT = kScoreMaxTiles, PITCH = ROWB + 16;
+  __shared__ __attribute__((aligned(16))) char ktile[2][32 * PITCH];   // the key tile in use and the next one
+  __shared__ float colpart[PASS == 2 ? NT : 1][4][32];                  // pass 2: per key tile and wave, the column sums of the wave's rows
+  __shared__ __attribute__((aligned(16))) float crow_lds[kMaxScoreRows];
+  __shared__ __attribute__((aligned(16))) int qpos_lds[PASS == 2 ? kMaxScoreRows : 4];
+  const int su = blockIdx.y;
+  const UnitDesc d = cv.units[cv.static_units[static_begin + su]];
+  const int key0 = blockIdx.x * keys_per_block;
+  if (key0 >= d.C) return;
+  const int G = cv.G, w = cv.window, rows = G * w;
+  const int lrel = d.layer - layer_begin;
+  const int tid = thread_index(), lane = tid & 63, wv = tid >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int n_my = min(2, max(0, (rows + 31) / 32 - 2 * wv));         // row blocks this wave really has (wave-uniform)
+
+  // this lane's two window rows (row r = g * w + i), 16 bytes of every 32-byte piece pair
+  uint4 qreg[2][NPIECE];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const int r = (2 * wv + x) * 32 + l32;
+#pragma unroll
+    for (int j = 0; j < NPIECE; ++j) qreg[x][j] = make_uint4(0, 0, 0, 0);
+    if (r < rows) {
+      const int g = r / w, i = r % w;
+      const char* src = reinterpret_cast<const char*>(q_window) +
+                        ((((size_t)lrel * cv.batch + d.seq) * w + i) * cv.n_q_heads + (size_t)d.head * G + g) * ROWB + half * 16;
+#pragma unroll
+      for (int j = 0; j < NPIECE; ++j) qreg[x][j] = ld16(src + j * 32);
+    }
+  }
+  // pass 1: running statistics of this lane's rows.  pass 2: c_row of every window row in shared memory (a
+  // lane meets 16 rows of a row block per tile and reads their constants as four broadcast 16-byte loads);
+  // rows that do not exist get a constant that zeroes their weight
+  float m_run[2] = {kNeg, kNeg}, z_run[2] = {0.f, 0.f};
+  if constexpr (PASS == 2) {
+    float c = 1.0e30f;
+    if (tid < rows) {
+      const float2 st = final_stats[(size_t)su * kMaxScoreRows + tid];           // (row maximum, 1 / (Z * G * w))
+      c = st.x - __builtin_amdgcn_logf(st.y);                                      // log2
+    }
+    crow_lds[tid] = c;                          // blockDim.x == kMaxScoreRows; visible after the first barrier below
+    qpos_lds[tid] = tid % w;                    // position of the row inside the window (causal masking)
+  }
+
+  const char* kbase = reinterpret_cast<const char*>(k) +
+                      (((size_t)lrel * total_tokens + d.seq_start) * cv.n_kv_heads + d.head) * ROWB;
+  const size_t kstride = (size_t)cv.n_kv_heads * ROWB;
+  const int hist_end = d.C - w;
+  const float s2 = cv.scale_log2e;
+  const int n_tiles = min(keys_per_block / 32, (d.C - key0 + 31) / 32);
+
+  // staging: thread t carries the 16-byte pieces t and t + 256 of a tile (piece p = row p / 16, bytes 16 * (p % 16))
+  uint4 stage[2];
+  auto fetch = [&](int kt) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int p = tid + 256 * h, row = p >> 4, key = key0 + kt * 32 + row;
+      stage[h] = make_uint4(0, 0, 0, 0);
+      if (kt < n_tiles && key < d.C) stage[h] = ld16(kbase + (size_t)key * kstride + (p & 15) * 16);
+    }
+  };
+  auto park = [&](int buf) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int p = tid + 256 * h;
+      st16(ktile[buf] + (p >> 4) * PITCH + (p & 15) * 16, stage[h]);
+    }
+  };
+  fetch(0);
+  park(0);
+  fetch(1);
+  lds_barrier();
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int j0 = key0 + kt * 32;
+    // a tile is clean when none of its 32 keys is past the end or (with the causal option) inside the
+    // window: then no logit is masked
+    const bool clean = (j0 + 32 <= d.C) && (!cv.causal || j0 + 31 <= hist_end);      // wave-uniform
+    if (n_my > 0) {
+      uint4 a[NPIECE];
+      const char* krow = ktile[kt & 1] + l32 * PITCH + half * 16;
+#pragma unroll
+      for (int j = 0; j < NPIECE; ++j) a[j] = ld16(krow + j * 32);
+      float colsum = 0.f;
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        if (x >= n_my) continue;
+        floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if constexpr (PASS == 1) {
+          // acc[r] = q_row((2*wv+x)*32 + l32) . k(j0 + 8*(r/4) + 4*half + r%4)
+#pragma unroll
+          for (int j = 0; j < NPIECE; ++j) acc = mma_piece(a[j], qreg[x][j], acc, bf16_t{});
+          if (clean) {
+            float mx = acc[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+            const float mn = fmaxf(m_run[x], mx * s2);
+            float z = z_run[x] * fast_exp2(m_run[x] - mn);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z += fast_exp2(fmaf(acc[r], s2, -mn));
+            z_run[x] = z; m_run[x] = mn;
+          } else {
+            const int qi = ((2 * wv + x) * 32 + l32) % w;       // position of the row inside the window
+            bool masked[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int kk = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+              masked[r] = (kk >= d.C) || (cv.causal && kk > hist_end + qi);
+            }
+            float mx = kNeg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = masked[r] ? mx : fmaxf(mx, acc[r] * s2);
+            const float mn = fmaxf(m_run[x], mx);
+            float z = z_run[x] * fast_exp2(m_run[x] - mn);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z += masked[r] ? 0.f : fast_exp2(fmaf(acc[r], s2, -mn));
+            z_run[x] = z; m_run[x] = mn;
+          }
+        } else {
+          // operands swapped: acc[r] = q_row((2*wv+x)*32 + 8*(r/4) + 4*half + r%4) . k(j0 + l32)
+#pragma unroll
+          for (int j = 0; j < NPIECE; ++j) acc = mma_piece(qreg[x][j], a[j], acc, bf16_t{});
+          float crow[16];
+#pragma unroll
+          for (int qd = 0; qd < 4; ++qd) {
+            const float4 c4 = *reinterpret_cast<const float4*>(crow_lds + (2 * wv + x) * 32 + 8 * qd + 4 * half);
+            crow[4 * qd] = c4.x; crow[4 * qd + 1] = c4.y; crow[4 * qd + 2] = c4.z; crow[4 * qd + 3] = c4.w;
+          }
+          if (clean) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) colsum += fast_exp2(fmaf(acc[r], s2, -crow[r]));
+          } else {
+            // key j0 + l32 is masked for a row when it lies past the end, or (causal option) behind the row's
+            // own position: position in the window < key - (C - w)
+            const int kk = j0 + l32;
+            const int lim = kk >= d.C ? 0x7fffffff : (cv.causal ? kk - hist_end : -1);
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+              const int4 p4 = *reinterpret_cast<const int4*>(qpos_lds + (2 * wv + x) * 32 + 8 * qd + 4 * half);
+              colsum += p4.x < lim ? 0.f : fast_exp2(fmaf(acc[4 * qd], s2, -crow[4 * qd]));
+              colsum += p4.y < lim ? 0.f : fast_exp2(fmaf(acc[4 * qd + 1], s2, -crow[4 * qd + 1]));
+              colsum += p4.z < lim ? 0.f : fast_exp2(fmaf(acc[4 * qd + 2], s2, -crow[4 * qd + 2]));
+              colsum += p4.w < lim ? 0.f : fast_exp2(fmaf(acc[4 * qd + 3], s2, -crow[4 * qd + 3]));
+            }
+          }
+        }
+      }
+      if constexpr (PASS == 2) {
+        colsum += lane_xor(colsum, 32);            // the other half-wave holds the other 16 rows of each block
+        if (half == 0) colpart[kt][wv][l32] = colsum;
+      }
+    }
+    park((kt + 1) & 1);                            // the buffer the workgroup left at the previous barrier
+    fetch(kt + 2);
+    lds_barrier();
+  }
+
+  if constexpr (PASS == 1) {
+    // fold the two half-waves (same window row, different keys); the rows belong to this wave alone
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const float mo = lane_xor(m_run[x], 32), zo = lane_xor(z_run[x], 32);
+      const float mn = fmaxf(m_run[x], mo);
+      const float z = z_run[x] * fast_exp2(m_run[x] - mn) + zo * fast_exp2(mo - mn);
+      const int r = (2 * wv + x) * 32 + l32;
+      if (half == 0) part_stats[((size_t)su * n_splits_max + blockIdx.x) * kMaxScoreRows + r] = make_float2(mn, z);
+    }
+  } else {
+    const int n_wv = (rows + 63) / 64;           // waves that have rows
+    float* sc = cv.scores + d.aux_off;
+    for (int idx = tid; idx < n_tiles * 32; idx += 256) {
+      const int kt = idx >> 5, c = idx & 31;
+      float tot = 0.f;
+      for (int x = 0; x < n_wv; ++x) tot += colpart[kt][x][c];
+      const int kk = key0 + idx;
+      if (kk < d.C) sc[kk] = tot;
+    }
+  }
+}
+
 // grid = static units of the call, block = kMaxScoreRows threads (one per window row).
 __global__ __launch_bounds__(kMaxScoreRows) void stats_finalize_kernel(CacheView cv, int static_begin,
                                                                        const float2* __restrict__ part_stats,
                                                                        float2* __restrict__ final_stats,
-                                                                       int n_splits_max) {
+                                                                       int n_splits_max, int keys_per_block) {
   const int su = blockIdx.x, r = threadIdx.x;
   const UnitDesc d = cv.units[cv.static_units[static_begin + su]];
-  const int n_splits = (d.C + kKeysPerBlock - 1) / kKeysPerBlock;
+  const int n_splits = (d.C + keys_per_block - 1) / keys_per_block;
   const int rows = cv.G * cv.window;
   float2 res = make_float2(0.f, 0.f);
   if (r < rows) {
@@ -488,8 +692,21 @@ __global__ __launch_bounds__(256) void adopt_blocks_kernel(CacheView cv, int lay
 template <typename T>
 static hipError_t launch_score_t(const CacheView& cv, int layer_begin, int static_begin, int n_static, int max_C,
                                  const void* q_window, const void* k, int64_t total_tokens, float2* part_stats,
-                                 float2* final_stats, hipStream_t st) {
+                                 float2* final_stats, int keys_per_block, hipStream_t st) {
+  if constexpr (sizeof(T) == 2) {
+    if (keys_per_block < 32 || keys_per_block % 32 != 0 || keys_per_block > 32 * kScoreMaxTiles) return hipErrorInvalidValue;
+    const int n_splits = (max_C + keys_per_block - 1) / keys_per_block;
+    const dim3 grid(n_splits, n_static);
+    hipLaunchKernelGGL(score_rows_kernel<1>, grid, dim3(256), 0, st, cv, layer_begin, static_begin, (const bf16_t*)q_window,
+                       (const bf16_t*)k, total_tokens, part_stats, (const float2*)final_stats, n_splits, keys_per_block);
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3(n_static), dim3(kMaxScoreRows), 0, st, cv, static_begin,
+                       (const float2*)part_stats, final_stats, n_splits, keys_per_block);
+    hipLaunchKernelGGL(score_rows_kernel<2>, grid, dim3(256), 0, st, cv, layer_begin, static_begin, (const bf16_t*)q_window,
+                       (const bf16_t*)k, total_tokens, part_stats, (const float2*)final_stats, n_splits, keys_per_block);
+    return hipGetLastError();
+  }
   const int n_splits = (max_C + kKeysPerBlock - 1) / kKeysPerBlock;
+  const dim3 grid(n_splits, n_static);
   const int rows_pad = ((cv.G * cv.window + 31) / 32) * 32;
   const size_t smem = (size_t)rows_pad * (kD * sizeof(T) + 16);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, 1>),
@@ -498,11 +715,10 @@ static hipError_t launch_score_t(const CacheView& cv, int layer_begin, int stati
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, 2>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
-  const dim3 grid(n_splits, n_static);
   hipLaunchKernelGGL((score_kernel<T, 1>), grid, dim3(256), smem, st, cv, layer_begin, static_begin,
                      (const T*)q_window, (const T*)k, total_tokens, part_stats, (const float2*)final_stats, n_splits);
   hipLaunchKernelGGL(stats_finalize_kernel, dim3(n_static), dim3(kMaxScoreRows), 0, st, cv, static_begin,
-                     (const float2*)part_stats, final_stats, n_splits);
+                     (const float2*)part_stats, final_stats, n_splits, kKeysPerBlock);
   hipLaunchKernelGGL((score_kernel<T, 2>), grid, dim3(256), smem, st, cv, layer_begin, static_begin,
                      (const T*)q_window, (const T*)k, total_tokens, part_stats, (const float2*)final_stats, n_splits);
   return hipGetLastError();
@@ -510,13 +726,13 @@ static hipError_t launch_score_t(const CacheView& cv, int layer_begin, int stati
 
 hipError_t launch_score(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static, int max_C,
                         const void* q_window, const void* k, int64_t total_tokens, float2* part_stats,
-                        float2* final_stats, hipStream_t st) {
+                        float2* final_stats, int keys_per_block, hipStream_t st) {
   if (n_static <= 0) return hipSuccess;
   if (dtype == HKV_F32)
     return launch_score_t<float>(cv, layer_begin, static_begin, n_static, max_C, q_window, k, total_tokens,
-                                 part_stats, final_stats, st);
+                                 part_stats, final_stats, keys_per_block, st);
   return launch_score_t<bf16_t>(cv, layer_begin, static_begin, n_static, max_C, q_window, k, total_tokens,
-                                part_stats, final_stats, st);
+                                part_stats, final_stats, keys_per_block, st);
 }
 
 hipError_t launch_select(const CacheView& cv, int static_begin, int n_static, hipStream_t st) {

@@ -159,9 +159,12 @@ hipError_t launch_full_attn(const FullView& fv, int dtype, const void* q, const 
                             float* parts_o, float* parts_ml, void* out, hipStream_t st);
 
 // compress
+// keys_per_block: keys one scoring block covers on the bf16 path (a multiple of 32 from kKeysPerBlock to
+// 2 * kKeysPerBlock, so that the row-statistics workspace sized for kKeysPerBlock always suffices); the fp32
+// path uses kKeysPerBlock.
 hipError_t launch_score(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,
                         int max_C, const void* q_window, const void* k, int64_t total_tokens,
-                        float2* part_stats, float2* final_stats, hipStream_t st);
+                        float2* part_stats, float2* final_stats, int keys_per_block, hipStream_t st);
 hipError_t launch_select(const CacheView& cv, int static_begin, int n_static, hipStream_t st);
 hipError_t launch_compact(const CacheView& cv, int dtype, int layer_begin, int static_begin, int n_static,
                           int max_rows, const void* k, const void* v, int64_t total_tokens, hipStream_t st);

@@ -23,7 +23,7 @@ hipError_t launch_stream_merge(const CacheView&, int, const StreamMulti*, int, i
 hipError_t launch_rewind(const CacheView&, int, int, hipStream_t) { return never(); }
 hipError_t launch_full_attn(const FullView&, int, const void*, const void*, const void*, float*, float*, void*, hipStream_t) { return never(); }
 hipError_t launch_score(const CacheView&, int, int, int, int, int, const void*, const void*, int64_t, float2*, float2*,
-                        hipStream_t) { return never(); }
+                        int, hipStream_t) { return never(); }
 hipError_t launch_select(const CacheView&, int, int, hipStream_t) { return never(); }
 hipError_t launch_compact(const CacheView&, int, int, int, int, int, const void*, const void*, int64_t, hipStream_t) { return never(); }
 hipError_t launch_adopt(const CacheView&, int, int, int, int, int, int, const void*, const void*, int64_t, hipStream_t) { return never(); }
