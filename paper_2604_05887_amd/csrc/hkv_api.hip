@@ -465,6 +465,7 @@ struct hkv_cache {
   std::vector<hipEvent_t> events;     // 6 per profiled decode call: start and stop of up to three kernels
   int prof_calls = 0, prof_max = 0;
   int n_cus = 256;                    // compute units of the device the cache lives on
+  int clock_khz = 2400000;            // that device's shader clock
   int device = -1;                    // device that was current when the cache was created
   void* scratch_dev = nullptr;        // that device's copy of the library's split-K record array
   CacheView cv_coarse;                // cv with the tables of the coarse tiling (if lo.coarse)
@@ -539,10 +540,11 @@ static int create_cache(const hkv_config* cfg, const hkv_plan* plan, void* cache
   c->cfg = *cfg;
   c->batch = plan->batch;
   {
-    int dev = 0, cus = 0;
+    int dev = 0, cus = 0, khz = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       c->n_cus = cus;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) == hipSuccess && khz > 0) c->clock_khz = khz;
   }
   // set-up is where the library's own record array is located on this device (hkv_decode_attn_noalloc
   // itself then makes no runtime call besides its launches)
@@ -883,10 +885,14 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
   }
   if (mode == 3) {
     // a grid that is resident in one round: the static tiles wait for the time the dynamic tiles' summary
-    // reads take at ~5 TB/s, in units of 512 clocks at ~2.4 GHz, at most 16
+    // reads take at kSummaryRate (what a launch's first reads were measured to draw while every workgroup
+    // asks at once), in units of 512 clocks of the device's shader clock, at most 16
+    constexpr double kSummaryRate = 5.0e12;   // bytes per second
     int hold = 0;
-    if (ndi > 0 && ndi + ns <= resident)
-      hold = (int)std::min<int64_t>(16, (lo.dmu_begin[le] - lo.dmu_begin[lb]) / 1070000);
+    if (ndi > 0 && ndi + ns <= resident) {
+      const double seconds = (double)(lo.dmu_begin[le] - lo.dmu_begin[lb]) / kSummaryRate;
+      hold = (int)std::min<int64_t>(16, (int64_t)(seconds * c->clock_khz * 1e3 / 512.0));
+    }
     e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, t_before, 1,
                              hold, lo.max_chunks, st, ev[0], ev[1]);
   } else {

@@ -6,16 +6,23 @@
 // k = ceil(focus * C); the score is the mean over the text rows (and over the G query heads that
 // share the KV head).  Heads at or above a threshold are static, the others dynamic.
 //
-// Device plan, one (layer, sequence) pass at a time, all KV heads of the pass together:
-//   logits_kernel   S = Q_text K^T on the matrix cores, logits (log2 domain) written to the workspace
-//   row top-k       per text row: row maximum, normaliser, exact k-th largest logit, sum of the
-//                   probabilities above it plus the admitted ties -- one wave per row with the row in
-//                   registers (row_topk_wave_kernel, up to 8192 keys), one workgroup per row
-//                   (row_topk_reg_kernel, up to 32768 keys), or radix selection over the row in memory
-//                   (row_topk_kernel)
-//   reduce_kernel   mean of the row values of each head, in a fixed order
-// The logits of a pass are materialised (rows x C floats per head): the exact top-k of a row needs the
-// whole row several times, and 288 GB of HBM make that the simple way to have it.
+// Device plan, one (layer, sequence) pass at a time, all KV heads of the pass together.
+// bf16 inputs with a focus fraction of at most 1/18 (the paper's 0.05 is) and rows of at most 65536 keys:
+//   scan_rows_kernel  S = Q_text K^T on the matrix cores, formed once and never written out: per text row the
+//                     running maximum and normaliser, per group of 16 keys of a row its four largest logits
+//   row_final_kernel  per text row: a lower bound for the k-th largest logit from the groups' largest, the
+//                     candidates at or above it (a group that may hold more than four is recomputed), the
+//                     exact k-th largest of the candidates, the sum of the probabilities above it plus the
+//                     admitted ties
+//   reduce_kernel     mean of the row values of each head, in a fixed order
+// Other inputs (fp32, larger focus fractions, longer rows): the logits of a pass are materialised
+//   logits_kernel     S = Q_text K^T on the matrix cores, logits (log2 domain) written to the workspace
+//   row top-k         per text row: row maximum, normaliser, exact k-th largest logit, sum of the
+//                     probabilities above it plus the admitted ties -- one wave per row with the row in
+//                     registers (row_topk_wave_kernel, up to 8192 keys), one workgroup per row
+//                     (row_topk_reg_kernel, up to 32768 keys), or radix selection over the row in memory
+//                     (row_topk_kernel)
+//   reduce_kernel     as above
 #include <algorithm>
 #include <atomic>
 #include <cmath>
@@ -351,7 +358,8 @@ __device__ __forceinline__ int wave_total(int c) {
 // an absent entry holds 0), given that at least kth of them lie in [lo, hi] and none above hi: bitwise search
 // on key - lo over the wave's counts.  No barrier, no memory traffic.  VOTE: the counts are taken with
 // wave votes on the scalar unit (few registers per lane), else per lane with one lane reduction per step.
-template <int N, bool VOTE>
+// STOP_EARLY = false: the search runs through all bits and returns the kth largest key itself.
+template <int N, bool VOTE, bool STOP_EARLY = true>
 __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&key)[N], int n_used, int kth, uint32_t lo,
                                                      uint32_t hi) {
   const uint32_t span = hi - lo;
@@ -374,7 +382,7 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t (&key)[N], i
     if (c >= kth) thr = cand;
     // exactly kth keys at or above the candidate: it separates them from the rest, which is all the callers
     // need (a bound from below, or the sum of the weights at or above it), so the remaining bits are skipped
-    if (c == kth) break;
+    if (STOP_EARLY && c == kth) break;
   }
   return lo + thr;
 }
@@ -516,6 +524,496 @@ void row_topk_wave_kernel(const float* __restrict__ logits, int64_t head_stride,
   if (lane == 0) row_value[gr] = (above + (kt > n_gt ? (float)(kt - n_gt) * weight_of_key(thr) : 0.f)) / z;
 }
 
+// ---- rows scanned on the fly (bf16, focus fraction up to 1/18) -----------------------------------------
+// The two kernels below give the same row values as logits_kernel + row_topk_*_kernel without writing the
+// logits out: the contraction runs once, and of every group of 16 logits of a row (the 16 that one lane
+// holds for a 32-key tile) only the four largest are kept -- a quarter of the logits' bytes.
+//   scan_rows_kernel   per text row: running maximum and normaliser; per (row, group): the four largest
+//                      logits, in descending order.
+//   row_final_kernel   one wave per row.  (1) A lower bound for the row's kt-th largest logit: the kt-th
+//                      largest of the groups' two largest (of the groups' maxima on long rows).  These are
+//                      different logits of the row, so the row's kt-th largest is at or above it, and every
+//                      logit below the bound is out of the top kt.  With kt = 5 % of the keys about 5.4 % of
+//                      the logits lie at or above the bound (9.6 % with the maxima alone).  (2) The
+//                      candidates: the kept logits at or above the bound; a group whose FOURTH largest is
+//                      still at or above the bound may hold more of them than were kept (about one group in
+//                      a thousand), and the wave recomputes that group's 16 logits from the query row and
+//                      the keys.  (3) The exact kt-th largest of the candidates (ties included) and the sum
+//                      of the probabilities above it plus the admitted ties.
+// Text rows run along the lanes of the 32x32 tiles (a lane owns one row of each of its wave's two row
+// blocks); the rows stay in registers and the key tiles pass through shared memory once per workgroup,
+// as in the window scoring of the compression pass.
+// grid = (key splits, chunks of 256 rows, heads of the pass); block = 256 threads.
+// Global row index R = blockIdx.z * rows + r.  part_stats [R][n_splits]; top4 [R][2][n_tiles] (group
+// (half, tile) of row R holds the logits of keys 32 * tile + 8 * (i / 4) + 4 * half + i % 4, i = 0..15).
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void scan_rows_kernel(const bf16_t* __restrict__ q_layer, const bf16_t* __restrict__ k_layer,
+                      const int32_t* __restrict__ text_pos, int64_t seq_start, int C, int n_text, int G,
+                      int n_q_heads, int n_kv_heads, int head0, float s2, int causal, int tiles_per_block,
+                      int n_splits, float2* __restrict__ part_stats, float4* __restrict__ top4) {
+  constexpr int ROWB = kD * 2, NPIECE = ROWB / 32, PITCH = ROWB + 16;
+  constexpr int PLANE = 64 * 16 + 16;                  // one tile's records of a wave's row block, padded
+  __shared__ __attribute__((aligned(16))) char ktile[2][32 * PITCH];
+  __shared__ __attribute__((aligned(16))) char rec[4][2][4 * PLANE];   // [wave][row block][tile % 4][lane] float4
+  const int tid = thread_index(), lane = tid & 63, wv = tid >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int head = head0 + blockIdx.z;
+  const int rows = G * n_text;
+  const int row0 = blockIdx.y * kRowsPerBlock;
+  const int n_tiles_all = (C + 31) / 32;
+  const int tile0 = blockIdx.x * tiles_per_block;
+  const int n_tiles = min(tiles_per_block, n_tiles_all - tile0);
+  const int key0 = tile0 * 32;
+  const int n_my = min(2, max(0, (min(kRowsPerBlock, rows - row0) + 31) / 32 - 2 * wv));   // wave-uniform
+
+  uint4 qreg[2][NPIECE];
+  int pos_row[2];                       // prompt position of the row's text token (causal option)
+  bool valid[2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const int r = row0 + (2 * wv + x) * 32 + l32;
+    valid[x] = r < rows;
+    pos_row[x] = 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < NPIECE; ++j) qreg[x][j] = make_uint4(0, 0, 0, 0);
+    if (valid[x]) {
+      const int g = r / n_text, t = r % n_text;
+      const int p = text_pos ? text_pos[t] : t;
+      if (causal) pos_row[x] = p;
+      const char* src = reinterpret_cast<const char*>(q_layer) +
+                        ((size_t)(seq_start + p) * n_q_heads + (size_t)head * G + g) * ROWB + half * 16;
+#pragma unroll
+      for (int j = 0; j < NPIECE; ++j) qreg[x][j] = ld16(src + j * 32);
+    }
+  }
+  float m_run[2] = {kNeg, kNeg}, z_run[2] = {0.f, 0.f};
+
+  const char* kbase = reinterpret_cast<const char*>(k_layer) + ((size_t)seq_start * n_kv_heads + head) * ROWB;
+  const size_t kstride = (size_t)n_kv_heads * ROWB;
+  uint4 stage[2];
+  auto fetch = [&](int kt) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int p = tid + 256 * h, row = p >> 4, key = key0 + kt * 32 + row;
+      stage[h] = make_uint4(0, 0, 0, 0);
+      if (kt < n_tiles && key < C) stage[h] = ld16(kbase + (size_t)key * kstride + (p & 15) * 16);
+    }
+  };
+  auto park = [&](int buf) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int p = tid + 256 * h;
+      st16(ktile[buf] + (p >> 4) * PITCH + (p & 15) * 16, stage[h]);
+    }
+  };
+  fetch(0);
+  park(0);
+  fetch(1);
+  lds_barrier();
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int j0 = key0 + kt * 32;
+    const bool clean = !causal && j0 + 32 <= C;                 // wave-uniform: no logit of the tile is masked
+    if (n_my > 0) {
+      uint4 a[NPIECE];
+      const char* krow = ktile[kt & 1] + l32 * PITCH + half * 16;
+#pragma unroll
+      for (int j = 0; j < NPIECE; ++j) a[j] = ld16(krow + j * 32);
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        if (x >= n_my) continue;
+        // acc[r] = q_row . k(j0 + 8*(r/4) + 4*half + r%4); the logit is acc[r] * s2, rounded once
+        floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < NPIECE; ++j) acc = mma_piece(a[j], qreg[x][j], acc, bf16_t{});
+        float v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = acc[r] * s2;
+        if (!clean) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kk = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (kk >= C || kk > pos_row[x]) v[r] = kNeg;
+          }
+        }
+        // the four largest, sorted: inserting v into t0 >= t1 >= t2 >= t3 leaves max(t0, v) first and the
+        // median of each neighbouring pair with v behind it
+        float t0 = kNeg, t1 = kNeg, t2 = kNeg, t3 = kNeg;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float n3 = __builtin_amdgcn_fmed3f(t2, t3, v[r]);
+          const float n2 = __builtin_amdgcn_fmed3f(t1, t2, v[r]);
+          const float n1 = __builtin_amdgcn_fmed3f(t0, t1, v[r]);
+          t0 = fmaxf(t0, v[r]); t1 = n1; t2 = n2; t3 = n3;
+        }
+        const float mn = fmaxf(m_run[x], t0);
+        float z = z_run[x] * fast_exp2(m_run[x] - mn);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) z += fast_exp2(v[r] - mn);         // masked: exp2(-1e30 - mn) = 0
+        z_run[x] = z; m_run[x] = mn;
+        *reinterpret_cast<float4*>(rec[wv][x] + (kt & 3) * PLANE + lane * 16) = make_float4(t0, t1, t2, t3);
+      }
+      // every fourth tile (and after the last) the wave writes the records out: four lanes carry the four
+      // tiles' records of one (row, half) list, 64 consecutive bytes in memory, 16 lists per instruction
+      if ((kt & 3) == 3 || kt == n_tiles - 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int kt4 = kt & ~3, piece = lane & 3;
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          if (x >= n_my) continue;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int li = (lane >> 2) + 16 * i;                    // list = lane li of this wave: row li % 32, half li / 32
+            const int rr = row0 + (2 * wv + x) * 32 + (li & 31);
+            if (rr < rows && kt4 + piece <= kt) {
+              const float4 val = *reinterpret_cast<const float4*>(rec[wv][x] + piece * PLANE + li * 16);
+              top4[(((size_t)blockIdx.z * rows + rr) * 2 + (li >> 5)) * n_tiles_all + tile0 + kt4 + piece] = val;
+            }
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+    park((kt + 1) & 1);
+    fetch(kt + 2);
+    lds_barrier();
+  }
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const float mo = lane_xor(m_run[x], 32), zo = lane_xor(z_run[x], 32);
+    const float mn = fmaxf(m_run[x], mo);
+    const float z = z_run[x] * fast_exp2(m_run[x] - mn) + zo * fast_exp2(mo - mn);
+    const size_t R = (size_t)blockIdx.z * rows + row0 + (2 * wv + x) * 32 + l32;
+    if (half == 0 && valid[x]) part_stats[R * n_splits + blockIdx.x] = make_float2(mn, z);
+  }
+}
+
+// One text row per wave (four per workgroup); NGL = groups per lane (64 * NGL >= groups of the row).
+// Candidates are held as keys ~bits(m - v) (see row_topk_wave_kernel); up to 64 * 2 * NGL of them are
+// gathered in the wave's slice of shared memory and searched in registers, more (long runs of equal logits)
+// go to the row's list in `spill` ([row][spill_pitch] keys) and are searched there, one pass per bit.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16_pair;
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {       // c + a.lo * b.lo + a.hi * b.hi
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16_pair, a), __builtin_bit_cast(bf16_pair, b), c, false);
+}
+
+__device__ __forceinline__ void wave_lds_sync() {     // orders the wave's own shared-memory writes before its later reads
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The kth largest of the keys one wave holds (N per lane, the first n_used registers of every lane in use; an
+// absent entry holds 0 and every real key lies in [lo, hi], lo >= 1; at least kth real keys), exactly: radix
+// selection on key - lo, eight bits per round, through a 256-bin histogram in `hist` (the wave's own 256
+// words of shared memory).  A round costs a handful of instructions per register where the bitwise search
+// above costs three per register and BIT.
+// max_rounds < 4: the search stops early and returns the smallest key that shares the decided bits with the
+// kth largest -- a lower bound for it.
+template <int N>
+__device__ __forceinline__ uint32_t wave_radix_kth(const uint32_t (&key)[N], int n_used, int kth, uint32_t lo, uint32_t hi,
+                                                   uint32_t* hist, int max_rounds = 4) {
+  const int lane = thread_index() & 63;
+  const uint32_t span = hi - lo;
+  int shift = 32 - __builtin_clz(span | 1u);                 // bits of key - lo not yet decided (wave-uniform)
+  uint32_t d[N];                                             // key - lo; an absent entry gets 2^32 - 1: above the span
+                                                             // (lo >= 1), so it never shares a prefix with a real key
+#pragma unroll
+  for (int e = 0; e < N; ++e) d[e] = key[e] >= lo ? key[e] - lo : 0xFFFFFFFFu;
+  uint32_t prefix = 0;                                       // the decided bits
+  int need = kth;                                            // rank among the keys that share the prefix
+  for (int round = 0; shift > 0 && round < max_rounds; ++round) {
+    const int w = min(8, shift);
+    const int hi_shift = shift;                              // keys in play: (key - lo) >> hi_shift == prefix
+    shift -= w;
+    *reinterpret_cast<uint4*>(hist + 4 * lane) = make_uint4(0, 0, 0, 0);
+    wave_lds_sync();
+    if (hi_shift >= 32) {                                    // first round of a full-width span: every real key is in play
+#pragma unroll
+      for (int e = 0; e < N; ++e)
+        if (e < n_used && key[e] >= lo) atomicAdd(hist + (d[e] >> shift), 1u);
+    } else {
+#pragma unroll
+      for (int e = 0; e < N; ++e)
+        if (e < n_used && (d[e] >> hi_shift) == prefix) atomicAdd(hist + ((d[e] >> shift) & ((1u << w) - 1u)), 1u);
+    }
+    wave_lds_sync();
+    const uint4 c = *reinterpret_cast<const uint4*>(hist + 4 * lane);          // bins 4 * lane .. 4 * lane + 3
+    const int s = (int)(c.x + c.y + c.z + c.w);
+    const int incl = wave_inclusive_scan_dpp(s);
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    const int a3 = total - incl;                             // keys in bins above this lane's
+    // the largest bin b with (keys in bins >= b) >= need
+    const int c3 = a3 + (int)c.w, c2 = c3 + (int)c.z, c1 = c2 + (int)c.y, c0 = c1 + (int)c.x;
+    int cand = -1, above = 0;
+    if (c0 >= need) { cand = 4 * lane; above = c1; }
+    if (c1 >= need) { cand = 4 * lane + 1; above = c2; }
+    if (c2 >= need) { cand = 4 * lane + 2; above = c3; }
+    if (c3 >= need) { cand = 4 * lane + 3; above = a3; }
+    const uint64_t has = __builtin_amdgcn_ballot_w64(cand >= 0);
+    const int src = 63 - __builtin_clzll(has | 1ull);        // highest lane with a candidate holds the largest bin
+    const int bin = __builtin_amdgcn_readlane(cand, src);
+    need -= __builtin_amdgcn_readlane(above, src);
+    prefix = (prefix << w) | (uint32_t)bin;
+  }
+  return lo + (prefix << shift);
+}
+
+constexpr int kExcList = 256;
+template <int NGL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NGL == 8 ? 5 : NGL == 16 ? 3 : 1)))
+void row_final_kernel(const float2* __restrict__ part_stats, int n_splits, const float4* __restrict__ top4, int n_tiles_all,
+                      const bf16_t* __restrict__ q_layer, const bf16_t* __restrict__ k_layer,
+                      const int32_t* __restrict__ text_pos, int64_t seq_start, int C, int n_text, int G, int n_q_heads,
+                      int n_kv_heads, int head0, float s2, int rows_per_head, int n_rows_total, int k_top, int causal,
+                      uint32_t* __restrict__ spill, int spill_pitch, float* __restrict__ row_value) {
+  constexpr int CW = 2 * NGL, ROWB = kD * 2;
+  constexpr bool TWO = NGL <= 16;                                   // bound from the two largest of every group
+  constexpr int NK = TWO ? 2 * NGL : NGL;
+  extern __shared__ uint32_t flat_s[];                              // [4][64 * CW + 64]
+  __shared__ uint16_t exc_s[4 * kExcList];
+  __shared__ __attribute__((aligned(16))) uint32_t hist_s[4 * 256];
+  const int tid = thread_index(), lane = tid & 63, wv = tid >> 6;
+  const int gr = blockIdx.x * 4 + wv;
+  if (gr >= n_rows_total) return;                                   // wave-uniform; no barrier below
+  uint32_t* hist = hist_s + wv * 256;
+  const int hp = gr / rows_per_head, r = gr % rows_per_head;
+  const int g = r / n_text, tt = r % n_text;
+  const int pos = text_pos ? text_pos[tt] : tt;
+  const int n = causal ? min(C, pos + 1) : C;
+  const int kt = min(k_top, n);
+  const int n_groups = 2 * n_tiles_all;
+
+  float m = kNeg;
+  for (int s = lane; s < n_splits; s += 64) m = fmaxf(m, part_stats[(size_t)gr * n_splits + s].x);
+  m = wave_max_f_dpp(m);
+  float z = 0.f;
+  for (int s = lane; s < n_splits; s += 64) {
+    const float2 p = part_stats[(size_t)gr * n_splits + s];
+    z += p.y * fast_exp2(p.x - m);
+  }
+  z = wave_sum_f_dpp(z);
+
+  // the row's kept logits: lane holds groups lane, lane + 64, ...
+  const float4* trow = top4 + (size_t)gr * n_groups;
+  float4 T[NGL];
+#pragma unroll
+  for (int e = 0; e < NGL; ++e) {
+    const int gi = lane + 64 * e;
+    T[e] = gi < n_groups ? trow[gi] : make_float4(kNeg, kNeg, kNeg, kNeg);
+  }
+  // (1) the bound
+  float t_lo = kNeg;
+  {
+    uint32_t key[NK];
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int e = 0; e < NGL; ++e) {
+      const bool in = lane + 64 * e < n_groups;
+      if constexpr (TWO) {
+        key[2 * e] = in ? float_order_key(T[e].x) : 0u;
+        key[2 * e + 1] = in ? float_order_key(T[e].y) : 0u;
+        if (in) { lo = min(lo, key[2 * e + 1]); hi = max(hi, key[2 * e]); }
+      } else {
+        key[e] = in ? float_order_key(T[e].x) : 0u;
+        if (in) { lo = min(lo, key[e]); hi = max(hi, key[e]); }
+      }
+    }
+    lo = wave_min_u32_dpp(lo);
+    hi = ~wave_min_u32_dpp(~hi);
+    const int n_keys = TWO ? 2 * n_groups : n_groups;
+    if (kt <= n_keys) {                                             // wave-uniform
+      const int n_used = (TWO ? 2 : 1) * ((n_groups + 63) >> 6);
+      // three rounds decide the top 24 bits of the span: the bound is low by a 2^-16th of its size at most
+      t_lo = key_to_float(wave_radix_kth<NK>(key, n_used, kt, max(lo, 1u), hi, hist, 3));
+    }
+  }
+  // (2) candidates.  A group whose fourth largest is a real logit at or above the bound is recomputed.
+  const float tl = fmaxf(t_lo, -9.0e29f);                           // at or above the bound AND a real logit (> kNeg)
+  int my_c = 0, my_x = 0;
+#pragma unroll
+  for (int e = 0; e < NGL; ++e) {
+    const bool exc = T[e].w >= tl;
+    my_x += exc ? 1 : 0;
+    my_c += exc ? 0 : (T[e].x >= tl ? 1 : 0) + (T[e].y >= tl ? 1 : 0) + (T[e].z >= tl ? 1 : 0);
+  }
+  const int n_kept = wave_sum_i_dpp(my_c), n_exc = wave_sum_i_dpp(my_x);
+  const bool in_lds = n_kept + 16 * n_exc <= 64 * CW;               // wave-uniform
+  uint32_t* lds_list = flat_s + wv * (64 * CW + 64);                // 64 * CW candidates + one waste word per lane
+  uint32_t* mem_list = spill + (size_t)gr * spill_pitch;
+  auto key_of = [&](float v) { return ~float_to_bits(fmaxf(m - v, 0.f)); };
+  auto put = [&](int at, uint32_t key) {                            // recomputed logits (few) and the spill path
+    if (in_lds) lds_list[at] = key;
+    else mem_list[at] = key;
+  };
+  {
+    int at = wave_inclusive_scan_dpp(my_c) - my_c;
+    if (in_lds) {
+      // branch-free: a logit that is no candidate goes to the lane's waste word
+      const int waste = 64 * CW + lane;
+#pragma unroll
+      for (int e = 0; e < NGL; ++e) {
+        const bool exc = T[e].w >= tl;
+        const bool c0 = !exc && T[e].x >= tl, c1 = !exc && T[e].y >= tl, c2 = !exc && T[e].z >= tl;
+        lds_list[c0 ? at : waste] = key_of(T[e].x); at += c0 ? 1 : 0;
+        lds_list[c1 ? at : waste] = key_of(T[e].y); at += c1 ? 1 : 0;
+        lds_list[c2 ? at : waste] = key_of(T[e].z); at += c2 ? 1 : 0;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < NGL; ++e) {
+        if (T[e].w >= tl) continue;
+        if (T[e].x >= tl) mem_list[at++] = key_of(T[e].x);
+        if (T[e].y >= tl) mem_list[at++] = key_of(T[e].y);
+        if (T[e].z >= tl) mem_list[at++] = key_of(T[e].z);
+      }
+    }
+  }
+  int n_cand = n_kept;
+  if (n_exc > 0) {                                                  // wave-uniform
+    // The groups to recompute, listed in shared memory (at most kExcList; a row with more -- long runs of
+    // equal logits -- takes the rest one at a time).  Lane (i = lane / 4, quarter = lane % 4) forms a
+    // quarter of the dot product with the group's key i; two groups' keys are in flight at once.  A
+    // recomputed logit may differ from the matrix cores' in the last bits, so the bound is taken a little
+    // lower for them (more candidates never change the result).
+    uint16_t* xl = exc_s + wv * kExcList;
+    {
+      int at = wave_inclusive_scan_dpp(my_x) - my_x;
+#pragma unroll
+      for (int e = 0; e < NGL; ++e) {
+        const bool exc = T[e].w >= tl;
+        if (exc) {
+          if (at < kExcList) xl[at] = (uint16_t)(lane + 64 * e);
+          ++at;
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const float t_acc = t_lo - 1.0e-4f * fmaxf(1.f, fabsf(t_lo));
+    const int ki = lane >> 2, qu = lane & 3;
+    const char* qsrc = reinterpret_cast<const char*>(q_layer) +
+                       ((size_t)(seq_start + pos) * n_q_heads + (size_t)(head0 + hp) * G + g) * ROWB + qu * 64;
+    uint4 qp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) qp[j] = ld16(qsrc + 16 * j);
+    const char* kbase = reinterpret_cast<const char*>(k_layer) + ((size_t)seq_start * n_kv_heads + head0 + hp) * ROWB + qu * 64;
+    const size_t kstride = (size_t)n_kv_heads * ROWB;
+    auto key_index = [&](int gi) {
+      const int hf = gi / n_tiles_all, tile = gi % n_tiles_all;
+      return 32 * tile + 8 * (ki >> 2) + 4 * hf + (ki & 3);
+    };
+    auto finish = [&](const uint4 (&kv)[4], bool visible) {
+      float acc = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        acc = dot2_bf16(kv[j].x, qp[j].x, acc);
+        acc = dot2_bf16(kv[j].y, qp[j].y, acc);
+        acc = dot2_bf16(kv[j].z, qp[j].z, acc);
+        acc = dot2_bf16(kv[j].w, qp[j].w, acc);
+      }
+      acc += lane_xor(acc, 1);
+      acc += lane_xor(acc, 2);
+      const float v = acc * s2;
+      const bool take = visible && qu == 0 && v >= t_acc;
+      const uint64_t tm = __builtin_amdgcn_ballot_w64(take);
+      if (take) put(n_cand + __builtin_popcountll(tm & ((1ull << lane) - 1ull)), key_of(v));
+      n_cand += __builtin_popcountll(tm);
+    };
+    const int n_list = min(n_exc, kExcList);
+    for (int i0 = 0; i0 < n_list; i0 += 2) {                        // wave-uniform
+      uint4 kv[2][4];
+      bool vis[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int kk = i0 + u < n_list ? key_index(xl[i0 + u]) : 0x7fffffff;
+        vis[u] = kk < n;                                            // n <= C; with the causal option keys up to pos
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kv[u][j] = vis[u] ? ld16(kbase + (size_t)kk * kstride + 16 * j) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        if (i0 + u < n_list) finish(kv[u], vis[u]);                 // wave-uniform
+    }
+    if (n_exc > kExcList) {
+      // the list took the first kExcList groups in (lane, register) order; walk the same order over the
+      // row's records in memory and skip those
+      int seen = 0;
+      for (int src = 0; src < 64; ++src) {
+        for (int e = 0; e < NGL; ++e) {
+          const int gi = src + 64 * e;
+          if (gi >= n_groups) break;
+          if (!(trow[gi].w >= tl)) continue;                        // wave-uniform (every lane reads the same record)
+          if (seen++ < kExcList) continue;
+          const int kk = key_index(gi);
+          const bool visible = kk < n;
+          uint4 kv[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) kv[j] = visible ? ld16(kbase + (size_t)kk * kstride + 16 * j) : make_uint4(0, 0, 0, 0);
+          finish(kv, visible);
+        }
+      }
+    }
+  }
+  // the wave's own writes, read back by other lanes of the wave
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+  // (3) exact kt-th largest of the candidates
+  constexpr uint32_t key_max = 0xFFFFFFFFu;                         // the row maximum itself
+  uint32_t thr = 0u;
+  float above = 0.f;
+  int n_gt = 0;
+  if (in_lds) {
+    uint32_t ck[CW];
+    uint32_t lo = key_max;
+    const int n_used = (n_cand + 63) >> 6;
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+      const int idx = lane + 64 * c;
+      ck[c] = idx < n_cand ? lds_list[idx] : 0u;
+      if (idx < n_cand) lo = min(lo, ck[c]);
+    }
+    if (n_cand > kt) {
+      lo = wave_min_u32_dpp(lo);
+      thr = wave_radix_kth<CW>(ck, n_used, kt, max(lo, 1u), key_max, hist);
+    }                                                               // else every candidate counts: thr = 0 is below all
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+      if (c < n_used) {                                             // wave-uniform
+        const bool gt = ck[c] > thr;
+        above += gt ? weight_of_key(ck[c]) : 0.f;
+        n_gt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(gt));
+      }
+    }
+  } else {
+    auto count_at_least = [&](uint32_t x, bool strictly, float* sum) {
+      int c = 0;
+      float s = 0.f;
+      for (int j = lane; j < n_cand; j += 64) {
+        const uint32_t key = mem_list[j];
+        const bool in = strictly ? key > x : key >= x;
+        c += in ? 1 : 0;
+        s += in ? weight_of_key(key) : 0.f;
+      }
+      if (sum) *sum = s;
+      return wave_sum_i_dpp(c);
+    };
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t x = thr | (1u << bit);
+      if (count_at_least(x, false, nullptr) >= kt) thr = x;
+    }
+    n_gt = count_at_least(thr, true, &above);
+  }
+  above = wave_sum_f_dpp(above);
+  const int ties = min(kt, n_cand) - n_gt;      // candidates equal to the threshold fill the places left
+  if (lane == 0) row_value[gr] = (above + (ties > 0 ? (float)ties * weight_of_key(thr) : 0.f)) / z;
+}
+
 // Cumulative focus count (Section 2.1, Eq. 1).  grid = rows of the pass (KV heads x G x steps), block = 256
 // threads: one step's logit row of one query head per workgroup.  The k_top largest logits of the row
 // (softmax is increasing, so these are the k_top most attended tokens; equal values go to the lower
@@ -581,6 +1079,29 @@ inline size_t logit_pitch(size_t n_keys) {
   return pitch;
 }
 
+// Rows scanned on the fly (scan_rows_kernel and its companions): usable for bf16 inputs when the k-th largest
+// of the groups' maxima is a useful bound, i.e. the row has clearly more groups of 16 keys than k.
+constexpr int kScanTilesPerBlock = 32;
+struct ScanShape {
+  bool usable = false;
+  int n_tiles = 0, n_splits = 0, n_groups = 0, spill_pitch = 0;
+  size_t row_bytes = 0;                 // workspace bytes per text row, all arrays together
+};
+constexpr size_t kScanSlack = 4 * 256;  // alignment of the three arrays
+ScanShape scan_shape(const hkv_config* cfg, int64_t C, int64_t k_top) {
+  ScanShape sc;
+  sc.n_tiles = (int)((C + 31) / 32);
+  sc.n_splits = (sc.n_tiles + kScanTilesPerBlock - 1) / kScanTilesPerBlock;
+  sc.n_groups = 2 * sc.n_tiles;
+  sc.spill_pitch = 32 * sc.n_tiles;
+  sc.usable = cfg->dtype == HKV_BF16 && k_top * 18 <= C && sc.n_groups <= 64 * 64;
+  sc.row_bytes = (size_t)sc.n_splits * 8 + (size_t)sc.n_groups * 16 + (size_t)sc.spill_pitch * 4;
+  return sc;
+}
+inline int k_top_of(double focus_fraction, int64_t C) {
+  return (int)std::max<int64_t>(1, std::min<int64_t>(C, (int64_t)std::ceil(focus_fraction * (double)C - 1e-9)));
+}
+
 struct ClassifyShape {
   std::vector<int32_t> text_pos;        // all sequences, packed
   std::vector<int64_t> text_begin;      // [batch + 1]
@@ -608,6 +1129,9 @@ int classify_shape(const hkv_config* cfg, int32_t batch, const int32_t* cu, cons
     const size_t pitch = logit_pitch((size_t)C);
     sh.max_rows = std::max(sh.max_rows, (size_t)G * T);
     sh.head_bytes_max = std::max(sh.head_bytes_max, (size_t)G * T * pitch * sizeof(float));
+    // the scanning form's arrays for one head (whatever the focus fraction of the later call: the bound
+    // holds for every k)
+    sh.head_bytes_max = std::max(sh.head_bytes_max, (size_t)G * T * scan_shape(cfg, C, 1).row_bytes + kScanSlack);
   }
   sh.off_pos = 0;
   sh.off_rows = align_up_c(std::max<size_t>(1, sh.text_pos.size()) * 4);
@@ -679,8 +1203,51 @@ int hkv_head_scores(const hkv_config* cfg, int32_t batch, const int32_t* cu_seql
       const int pitch = (int)logit_pitch((size_t)C);
       const int64_t head_stride = (int64_t)rows * pitch;
       const int heads_per_pass = (int)std::min<size_t>((size_t)Hkv, logits_room / ((size_t)head_stride * 4));
-      const int k_top = std::max(1, std::min(C, (int)std::ceil(focus_fraction * C - 1e-9)));
+      const int k_top = k_top_of(focus_fraction, C);
       const int32_t* pos = d_pos + sh.text_begin[b];
+      const ScanShape sc = scan_shape(cfg, C, k_top);
+      if (sc.usable) {
+        const size_t per_head = (size_t)rows * sc.row_bytes;
+        const int hpp = (int)std::min<size_t>((size_t)Hkv, (logits_room - kScanSlack) / per_head);
+        if (hpp < 1) return HKV_ENOSPACE;
+        for (int h0 = 0; h0 < Hkv; h0 += hpp) {
+          const int nh = std::min(hpp, Hkv - h0);
+          const size_t nr = (size_t)nh * rows;
+          char* base = reinterpret_cast<char*>(d_logits);
+          size_t off = 0;
+          auto take = [&](size_t bytes) { char* p = base + off; off = align_up_c(off + bytes); return p; };
+          float2* d_part = reinterpret_cast<float2*>(take(nr * sc.n_splits * 8));
+          float4* d_top4 = reinterpret_cast<float4*>(take(nr * sc.n_groups * 16));
+          uint32_t* d_spill = reinterpret_cast<uint32_t*>(take(nr * sc.spill_pitch * 4));
+          const dim3 grid(sc.n_splits, (rows + kRowsPerBlock - 1) / kRowsPerBlock, nh);
+          const dim3 wgrid((unsigned)((nr + 3) / 4));
+          const bf16_t* qb = reinterpret_cast<const bf16_t*>(q_layer);
+          const bf16_t* kb = reinterpret_cast<const bf16_t*>(k_layer);
+          hipLaunchKernelGGL(scan_rows_kernel, grid, dim3(256), 0, st, qb, kb, pos, (int64_t)cu_seqlens[b], C, T, G, Hq,
+                             Hkv, h0, scale_log2e, cfg->score_causal, kScanTilesPerBlock, sc.n_splits, d_part, d_top4);
+#define HKV_ROW_FINAL(NGL) \
+  do { \
+    constexpr size_t lds = (size_t)4 * (64 * 2 * NGL + 64) * 4; \
+    static std::atomic<bool> big_lds{false}; \
+    if (lds > 48 * 1024 && !big_lds.load(std::memory_order_acquire)) { \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&row_final_kernel<NGL>), \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return HKV_EHIP; \
+      big_lds.store(true, std::memory_order_release); \
+    } \
+    hipLaunchKernelGGL(row_final_kernel<NGL>, wgrid, dim3(256), lds, st, d_part, sc.n_splits, d_top4, sc.n_tiles, qb, kb, pos, \
+                       (int64_t)cu_seqlens[b], C, T, G, Hq, Hkv, h0, scale_log2e, rows, (int)nr, k_top, cfg->score_causal, \
+                       d_spill, sc.spill_pitch, d_rows); \
+  } while (0)
+          if (sc.n_groups <= 64 * 8) HKV_ROW_FINAL(8);
+          else if (sc.n_groups <= 64 * 16) HKV_ROW_FINAL(16);
+          else if (sc.n_groups <= 64 * 32) HKV_ROW_FINAL(32);
+          else HKV_ROW_FINAL(64);
+#undef HKV_ROW_FINAL
+          hipLaunchKernelGGL(reduce_kernel, dim3(nh), dim3(256), 0, st, d_rows, rows, out + h0);
+          if (hipGetLastError() != hipSuccess) return HKV_EHIP;
+        }
+        continue;
+      }
       for (int h0 = 0; h0 < Hkv; h0 += heads_per_pass) {
         const int nh = std::min(heads_per_pass, Hkv - h0);
         const dim3 grid((C + kKeysPerLogitBlock - 1) / kKeysPerLogitBlock, (rows + kRowsPerBlock - 1) / kRowsPerBlock, nh);

@@ -138,6 +138,54 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
   return v;
 }
 
+// The same prefix sum without shared-memory traffic: shifts inside each row of 16 lanes, then the last lane
+// of a row added to the rows behind it (row broadcasts).  A lane without a source adds 0.
+__device__ __forceinline__ int wave_inclusive_scan_dpp(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+// Wave-wide reductions on the same pattern: after the six steps lane 63 holds the result, which is handed
+// back as a wave-uniform value.  `IDENT` is what a lane without a source contributes.
+#define HKV_DPP_REDUCE(TYPE, OP, IDENT, BITS_IN, BITS_OUT)                                                          \
+  do {                                                                                                               \
+    v = OP(v, BITS_OUT(__builtin_amdgcn_update_dpp(BITS_IN(IDENT), BITS_IN(v), 0x111, 0xf, 0xf, false)));          \
+    v = OP(v, BITS_OUT(__builtin_amdgcn_update_dpp(BITS_IN(IDENT), BITS_IN(v), 0x112, 0xf, 0xf, false)));          \
+    v = OP(v, BITS_OUT(__builtin_amdgcn_update_dpp(BITS_IN(IDENT), BITS_IN(v), 0x114, 0xf, 0xf, false)));          \
+    v = OP(v, BITS_OUT(__builtin_amdgcn_update_dpp(BITS_IN(IDENT), BITS_IN(v), 0x118, 0xf, 0xf, false)));          \
+    v = OP(v, BITS_OUT(__builtin_amdgcn_update_dpp(BITS_IN(IDENT), BITS_IN(v), 0x142, 0xa, 0xf, false)));          \
+    v = OP(v, BITS_OUT(__builtin_amdgcn_update_dpp(BITS_IN(IDENT), BITS_IN(v), 0x143, 0xc, 0xf, false)));          \
+  } while (0)
+__device__ __forceinline__ int hkv_as_int(float f) { return __builtin_bit_cast(int, f); }
+__device__ __forceinline__ float hkv_as_float(int i) { return __builtin_bit_cast(float, i); }
+__device__ __forceinline__ int hkv_keep_int(int i) { return i; }
+__device__ __forceinline__ int hkv_add_i(int a, int b) { return a + b; }
+__device__ __forceinline__ float hkv_add_f(float a, float b) { return a + b; }
+__device__ __forceinline__ int hkv_min_u(int a, int b) { return (int)min((uint32_t)a, (uint32_t)b); }
+__device__ __forceinline__ int wave_sum_i_dpp(int v) {
+  HKV_DPP_REDUCE(int, hkv_add_i, 0, hkv_keep_int, hkv_keep_int);
+  return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ uint32_t wave_min_u32_dpp(uint32_t x) {
+  int v = (int)x;
+  HKV_DPP_REDUCE(int, hkv_min_u, -1, hkv_keep_int, hkv_keep_int);
+  return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ float wave_sum_f_dpp(float v) {           // lanes added in a fixed order
+  HKV_DPP_REDUCE(float, hkv_add_f, 0.f, hkv_as_int, hkv_as_float);
+  return hkv_as_float(__builtin_amdgcn_readlane(hkv_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max_f_dpp(float v) {
+  HKV_DPP_REDUCE(float, fmaxf, -3.0e38f, hkv_as_int, hkv_as_float);
+  return hkv_as_float(__builtin_amdgcn_readlane(hkv_as_int(v), 63));
+}
+#undef HKV_DPP_REDUCE
+
 // Block-wide exclusive prefix sum for blockDim.x == NT (multiple of 64).  `smem` holds NT/64 + 1 ints.
 // Returns the exclusive prefix of `v`; *total gets the block sum.  Contains two barriers.
 template <int NT> __device__ __forceinline__ int block_exclusive_scan(int v, int* smem, int* total) {

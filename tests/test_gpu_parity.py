@@ -439,11 +439,38 @@ def test_head_scores_do_not_depend_on_the_workspace_size_and_focus_edges():
     assert np.abs(tiny - want).max() <= SCORE_ATOL
 
 
-@pytest.mark.parametrize("n_visual", [9800, 19900, 40000])
-def test_head_scores_on_long_rows(n_visual):
-    """Rows longer than 8192 keys take the wider register-resident forms of the per-row top-k (up to 16384
-    and 32768 keys) and, beyond that, the form that re-reads the row from memory; few text tokens keep
-    the oracle quick."""
+def test_head_scores_with_runs_of_equal_logits():
+    """Equal keys give equal logits: a head whose keys are all the same row (every logit of a row ties, the
+    bound from the group maxima admits the whole row and the listed logits no longer fit the registers), a
+    head whose first half repeats one key, and two untouched heads; focus fractions on both sides of the
+    switch between the scanning and the materialising form."""
+    from hkv_synth import make_prompt_queries
+    wl = make_workload(1, n_layers=1, shrink=4, steps=1)
+    qp = make_prompt_queries(wl)
+    k = np.array(wl.k, copy=True)
+    C = int(wl.seqlens[0])
+    k[0, :, 0, :] = k[0, 7, 0, :]
+    k[0, :C // 2, 1, :] = k[0, 11, 1, :]
+    wl.k = k
+    ocfg = O.OracleConfig(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128, window=wl.window,
+                          dtype=wl.dtype)
+    for rho in (0.02, 0.05, 0.2):
+        got = _device_head_scores(wl, qp, rho=rho)
+        want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual, rho=rho)
+        err = np.abs(got - want).max()
+        print(f"\n[head scores, equal keys, rho={rho}] max abs err {err:.2e}; scores {want.ravel()[:4]}", flush=True)
+        assert err <= SCORE_ATOL
+        k_top = O.focus_count(C, rho)
+        assert abs(want[0, 0, 0] - k_top / C) < 1e-12           # all keys equal: every probability is 1/C
+
+
+@pytest.mark.parametrize("n_visual,rho", [(9800, 0.05), (19900, 0.05), (40000, 0.05), (9800, 0.1), (19900, 0.1), (40000, 0.1),
+                                          (70000, 0.05)])
+def test_head_scores_on_long_rows(n_visual, rho):
+    """Long rows.  At a focus fraction of 0.05 the rows are scanned on the fly (up to 65536 keys; more group
+    maxima per lane and more listed logits per row as the rows grow); at 0.1, and beyond 65536 keys, the
+    logits are materialised and the per-row top-k takes its wider register-resident forms (up to 16384 and
+    32768 keys) or the form that re-reads the row from memory.  Few text tokens keep the oracle quick."""
     from hkv_synth import make_prompt_queries
     from hkv_synth import workloads as W
     base = dict(W.CONFIGS[1])
@@ -454,12 +481,12 @@ def test_head_scores_on_long_rows(n_visual):
     finally:
         del W.CONFIGS[98]
     qp = make_prompt_queries(wl)
-    got = _device_head_scores(wl, qp)
+    got = _device_head_scores(wl, qp, rho=rho)
     ocfg = O.OracleConfig(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128, window=wl.window,
                           dtype=wl.dtype)
-    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual)
+    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual, rho=rho)
     err = np.abs(got - want).max()
-    print(f"\n[head scores C={int(wl.seqlens[0])}] max abs err {err:.2e}", flush=True)
+    print(f"\n[head scores C={int(wl.seqlens[0])} rho={rho}] max abs err {err:.2e}", flush=True)
     assert err <= SCORE_ATOL
 
 
