@@ -355,7 +355,11 @@ HKV_API int hkv_focus_counts(const hkv_config* cfg, int32_t n_steps, int32_t con
  *   k        : [device] [n_layers_call][total_tokens][n_kv_heads][head_dim]
  *   scores   : [device] [n_layers_call][batch][n_kv_heads] float
  *   workspace: [device, 16-byte aligned] at least *min_bytes of hkv_head_scores_workspace_size (one head's
- *              logits at a time); with *best_bytes all KV heads of a (layer, sequence) go in one pass.
+ *              intermediate arrays at a time); with *best_bytes all KV heads of a (layer, sequence) go in
+ *              one pass.  Contents are scratch.  bf16 inputs with focus_fraction <= 1/18 and sequences of
+ *              at most 65536 tokens never write the logits out (the workspace then holds, per text row, the
+ *              four largest logits of every 16 keys and a spill list that only rows with long runs of equal
+ *              logits touch); other inputs materialise one pass's logits in it.  The sizes cover both.
  * Uses cfg's shape, dtype, softmax_scale and score_causal.  Work is enqueued on `stream`; the call
  * synchronises the stream once at entry (it uploads the text positions).  Not meant for graph capture. */
 HKV_API int hkv_head_scores_workspace_size(const hkv_config* cfg, int32_t batch, const int32_t* cu_seqlens,
