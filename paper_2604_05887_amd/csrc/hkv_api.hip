@@ -893,13 +893,13 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
       const double seconds = (double)(lo.dmu_begin[le] - lo.dmu_begin[lb]) / kSummaryRate;
       hold = (int)std::min<int64_t>(16, (int64_t)(seconds * c->clock_khz * 1e3 / 512.0));
     }
-    e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, t_before, 1,
+    e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 1,
                              hold, lo.max_chunks, st, ev[0], ev[1]);
   } else {
     e = launch_decode(cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
                       mode == 2 ? 1 : 0, lo.max_chunks, st, ev[0], ev[1]);
     if (e == hipSuccess && mode == 2)
-      e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, 0, slot_base, q, k_new, v_new, parts, parts_ml, t_before, 0,
+      e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, 0, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
                                0, lo.max_chunks, st, ev[2], ev[3]);
   }
   if (e == hipSuccess)

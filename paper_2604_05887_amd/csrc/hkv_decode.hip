@@ -76,6 +76,9 @@ struct PartOut {
   float* ml;
   uint16_t* out_bf16;    // not null: the tile is its unit's only one -- write the G normalised output rows (bf16)
                          // here instead of a record
+  void* out_all;         // not null (bf16 caches): the call's output tensor; a split-K tile that turns out to be
+                         // its unit's only tile at this step writes the unit's rows there, and the combination
+                         // kernel leaves such units alone
 };
 constexpr int kMlStride = kMlFloats;
 
@@ -925,8 +928,13 @@ __device__ __forceinline__ void attention_item(const CacheView& cv, const AttnIt
   rm.n_chunks_prompt = it.n_chunks;
   rm.gen0 = gen0;
   const size_t qoff = (((size_t)lrel * cv.batch + it.seq) * cv.n_q_heads + (size_t)it.head * G) * kD;
+  if constexpr (sizeof(T) == 2) {
+    // the unit's rows all fall into this tile: no record, no combination (same arithmetic, one pass)
+    if (!out_rows && partials.out_all && it.row0 == 0 && rm.n_rows <= TILE)
+      out_rows = reinterpret_cast<uint16_t*>(partials.out_all) + qoff;
+  }
   const PartOut part = {out_rows ? nullptr : partials.o + (size_t)(it.slot - slot_base) * G * kD,
-                        out_rows ? nullptr : partials.ml + (size_t)(it.slot - slot_base) * kMlStride, out_rows};
+                        out_rows ? nullptr : partials.ml + (size_t)(it.slot - slot_base) * kMlStride, out_rows, nullptr};
   run_tile<T, G, true, NW, INDEXED>(rm, q + qoff, cv.scale_log2e, it.row0, TILE, part, smem);
 }
 
@@ -1050,6 +1058,7 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
     it.slot = d.item_begin + t;
     attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, TILE, smem);
   }
+  if (sizeof(T) == 2 && partials.out_all) return;   // the unit's single tile has written the output rows itself
   __threadfence_block();
   __syncthreads();                          // this block's own records are visible to all its threads
   const PartOut first = {partials.o + (size_t)(d.item_begin - slot_base) * G * kD,
@@ -1275,6 +1284,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(CacheView cv, const Uni
     rows = (k_now << d.c_log2) + (t_before & ((1 << d.c_log2) - 1)) + (t - t_before);
   }
   const int n_tiles = (rows + TILE - 1) / TILE;
+  if (sizeof(T) == 2 && partials.out_all && n_tiles == 1) return;    // its only tile has written the rows
   const int lrel = d.layer - layer_begin;
   const float* o0 = partials.o + ((size_t)(d.item_begin - slot_base) * G + g) * kD;
   const float* ml0 = partials.ml + (size_t)(d.item_begin - slot_base) * kMlStride + 2 * g;
@@ -1363,7 +1373,7 @@ static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_
                                   int n_sitems, int slot_base, const void* q, const void* k_new, const void* v_new,
                                   float* parts_o, float* parts_ml, void* out, int t_arg, int use_stored_sigma,
                                   int select_only, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  const PartOut partials = {parts_o, parts_ml};
+  const PartOut partials = {parts_o, parts_ml, nullptr, sizeof(T) == 2 ? out : nullptr};
   const size_t smem = std::max(attn_smem_bytes<T, G, true>(), select_smem_bytes(max_chunks));
   static std::atomic<size_t> attr{0};      // per instantiation; the attribute is sticky for the process
   if (smem > attr.load(std::memory_order_acquire)) {
@@ -1418,9 +1428,9 @@ template <typename T, int G, bool INDEXED = false>
 static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, int ditem_begin, int n_ditems,
                                          int sitem_begin, int n_sitems, int slot_base, const void* q,
                                          const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
-                                         int t_arg, int reselect, int static_hold, int max_chunks, hipStream_t st,
+                                         void* out, int t_arg, int reselect, int static_hold, int max_chunks, hipStream_t st,
                                          hipEvent_t ev0, hipEvent_t ev1) {
-  const PartOut partials = {parts_o, parts_ml};
+  const PartOut partials = {parts_o, parts_ml, nullptr, sizeof(T) == 2 ? out : nullptr};
   // reselect: selection scratch and the tile's staging area share the front; the picks sit behind both
   const size_t front = std::max(attn_smem_bytes<T, G, true>(), reselect ? select_smem_bytes(max_chunks) : (size_t)0);
   const size_t smem = front + (reselect ? (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t) : 0);
@@ -1439,24 +1449,24 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
 
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
-                                const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
+                                const void* v_new, float* parts_o, float* parts_ml, void* out, int t_arg, int reselect,
                                 int static_hold, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (n_ditems + n_sitems <= 0) return hipSuccess;
   if (cv.index_gen) {        // bf16 caches, tiles that repeat the selection
     if (dtype != HKV_BF16 || !reselect) return hipErrorInvalidValue;
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, true>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
                                                                           n_sitems, slot_base, q, k_new, v_new, parts_o,
-                                                                          parts_ml, t_arg, reselect, static_hold, max_chunks,
+                                                                          parts_ml, out, t_arg, reselect, static_hold, max_chunks,
                                                                           st, ev0, ev1)));
   }
   if (dtype == HKV_F32) {
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<float, GG>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
                                                                    n_sitems, slot_base, q, k_new, v_new, parts_o,
-                                                                   parts_ml, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
+                                                                   parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
   } else {
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
                                                                     n_sitems, slot_base, q, k_new, v_new, parts_o,
-                                                                    parts_ml, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
+                                                                    parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
   }
   return hipErrorInvalidValue;
 }
@@ -1498,7 +1508,7 @@ hipError_t launch_units(const CacheView& cv, int dtype, int layer_begin, int dyn
 hipError_t launch_attn_merge(const CacheView& cv, int dtype, const UnitDesc* descs, int n_units, int layer_begin,
                              int layer_end, int slot_base, float* parts_o, float* parts_ml, void* out, int t_arg,
                              int appending, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  const PartOut partials = {parts_o, parts_ml};
+  const PartOut partials = {parts_o, parts_ml, nullptr, dtype == HKV_BF16 ? out : nullptr};
   const int n_blocks = n_units * cv.G;
   if (n_blocks > 0) {
     if (dtype == HKV_F32)

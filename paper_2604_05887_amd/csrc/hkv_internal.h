@@ -127,7 +127,7 @@ hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dy
                          int max_chunks, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
-                                const void* v_new, float* parts_o, float* parts_ml, int t_arg, int reselect,
+                                const void* v_new, float* parts_o, float* parts_ml, void* out, int t_arg, int reselect,
                                 int static_hold, int max_chunks, hipStream_t st, hipEvent_t ev0 = nullptr,
                                 hipEvent_t ev1 = nullptr);
 // One wide workgroup per unit, outputs written directly (bf16 caches only; no workspace, no merge).
