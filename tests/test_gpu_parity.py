@@ -263,6 +263,42 @@ def test_other_group_sizes_and_windows(n_q, n_kv, window, dtype):
         _say(f"G{n_q // n_kv} w{window} {dtype} mode {mode}", stats)
 
 
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_seeded_random_shapes_in_every_decode_shape(seed):
+    """Ten shapes drawn from a seeded generator: group sizes 1 to 8, windows from 4 up to the limit of
+    G * w = 256, chunk sizes 8 to 128, one to three ragged sequences, prompts of 300 to 2600 tokens, budgets of
+    4 % to 45 %, static fractions from none to all, one to three layers, bf16 and fp32; each runs the whole
+    chain compress -> decode steps against the oracle in every decode shape its dtype has (automatic
+    included), once more with a call per layer."""
+    from hkv_synth import workloads as W
+    rng = np.random.default_rng(1000 + seed)
+    n_kv = int(rng.choice([1, 2, 3, 4]))
+    G = int(rng.integers(1, 9))
+    window = int(rng.choice([w for w in (4, 8, 12, 16, 24, 32, 48, 64, 128) if G * w <= 256]))
+    batch = int(rng.integers(1, 4))
+    dtype = "f32" if seed % 5 == 4 else "bf16"
+    n_visual = [int(rng.integers(200, 2200)) for _ in range(batch)]
+    n_text = [int(rng.integers(window + 80, 420)) for _ in range(batch)]
+    chunk = [int(rng.choice([8, 16, 32, 64, 128])) for _ in range(batch)]
+    base = dict(W.CONFIGS[1])
+    base.update(name=f"rand{seed}_{dtype}", dtype=dtype, n_layers=int(rng.integers(1, 4)), n_q_heads=G * n_kv, n_kv_heads=n_kv,
+                batch=batch, n_visual=n_visual, n_text=n_text, block=int(rng.choice([64, 256, 700])), sep=int(rng.choice([0, 4, 16])),
+                window=window, chunk=chunk, budget_frac=[float(rng.uniform(0.04, 0.45)) for _ in range(batch)],
+                static_frac=float(rng.choice([0.0, 0.25, 0.5, 0.75, 1.0])), steps=3,
+                q_mode=str(rng.choice(["normal", "centroid"])))
+    W.CONFIGS[97] = base
+    try:
+        wl = make_workload(97, seed=seed)
+    finally:
+        del W.CONFIGS[97]
+    modes = (0, 1, 2, 3, 4, 5) if dtype == "bf16" else (0, 1, 2, 3)
+    for mode in modes:
+        stats = P.full_pipeline(wl, decode_dynamic=mode)
+        _say(f"random shape {seed}: G{G} kv{n_kv} w{window} B{batch} {dtype} chunks {chunk} mode {mode}", stats)
+    stats = P.full_pipeline(wl, layer_ranges=[(l, l + 1) for l in range(wl.n_layers)])
+    _say(f"random shape {seed}: a call per layer", stats)
+
+
 @pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 3, 160), (1, 2, 288), (1, 1, 416), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
 def test_both_decode_shapes_for_dynamic_heads(dtype_cfg, mode, tile):
     """Dynamic heads handled by one workgroup each (mode 1), by split-K tiles in a second launch
