@@ -587,16 +587,18 @@ void scan_rows_kernel(const bf16_t* __restrict__ q_layer, const bf16_t* __restri
     }
   }
   float m_run[2] = {kNeg, kNeg}, z_run[2] = {0.f, 0.f};
+  float4* top4_wg = top4 + ((size_t)blockIdx.z * rows + row0) * 2 * n_tiles_all;   // records of this workgroup's first row
 
   const char* kbase = reinterpret_cast<const char*>(k_layer) + ((size_t)seq_start * n_kv_heads + head) * ROWB;
-  const size_t kstride = (size_t)n_kv_heads * ROWB;
+  const uint32_t kstride = (uint32_t)n_kv_heads * ROWB;
   uint4 stage[2];
   auto fetch = [&](int kt) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int p = tid + 256 * h, row = p >> 4, key = key0 + kt * 32 + row;
       stage[h] = make_uint4(0, 0, 0, 0);
-      if (kt < n_tiles && key < C) stage[h] = ld16(kbase + (size_t)key * kstride + (p & 15) * 16);
+      // (a row of keys is at most 16 KB long and a sequence at most 65536 tokens: the offset fits 32 bits)
+      if (kt < n_tiles && key < C) stage[h] = ld16(kbase + ((uint32_t)key * kstride + (uint32_t)(p & 15) * 16u));
     }
   };
   auto park = [&](int buf) {
@@ -625,30 +627,31 @@ void scan_rows_kernel(const bf16_t* __restrict__ q_layer, const bf16_t* __restri
         floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < NPIECE; ++j) acc = mma_piece(a[j], qreg[x][j], acc, bf16_t{});
-        float v[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) v[r] = acc[r] * s2;
+        // the selection works on the raw sums (the scale is positive); a masked logit becomes a value whose
+        // scaled form still lies below every real logit and below kNeg's test in row_final_kernel
+        constexpr float kRawNeg = -3.0e38f;
         if (!clean) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int kk = j0 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (kk >= C || kk > pos_row[x]) v[r] = kNeg;
+            if (kk >= C || kk > pos_row[x]) acc[r] = kRawNeg;
           }
         }
         // the four largest, sorted: inserting v into t0 >= t1 >= t2 >= t3 leaves max(t0, v) first and the
         // median of each neighbouring pair with v behind it
-        float t0 = kNeg, t1 = kNeg, t2 = kNeg, t3 = kNeg;
+        float t0 = kRawNeg, t1 = kRawNeg, t2 = kRawNeg, t3 = kRawNeg;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float n3 = __builtin_amdgcn_fmed3f(t2, t3, v[r]);
-          const float n2 = __builtin_amdgcn_fmed3f(t1, t2, v[r]);
-          const float n1 = __builtin_amdgcn_fmed3f(t0, t1, v[r]);
-          t0 = fmaxf(t0, v[r]); t1 = n1; t2 = n2; t3 = n3;
+          const float n3 = __builtin_amdgcn_fmed3f(t2, t3, acc[r]);
+          const float n2 = __builtin_amdgcn_fmed3f(t1, t2, acc[r]);
+          const float n1 = __builtin_amdgcn_fmed3f(t0, t1, acc[r]);
+          t0 = fmaxf(t0, acc[r]); t1 = n1; t2 = n2; t3 = n3;
         }
+        t0 *= s2; t1 *= s2; t2 *= s2; t3 *= s2;                         // the logits themselves: sum * s2, rounded once
         const float mn = fmaxf(m_run[x], t0);
         float z = z_run[x] * fast_exp2(m_run[x] - mn);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) z += fast_exp2(v[r] - mn);         // masked: exp2(-1e30 - mn) = 0
+        for (int r = 0; r < 16; ++r) z += fast_exp2(fmaf(acc[r], s2, -mn));   // masked: exp2 of a huge negative = 0
         z_run[x] = z; m_run[x] = mn;
         *reinterpret_cast<float4*>(rec[wv][x] + (kt & 3) * PLANE + lane * 16) = make_float4(t0, t1, t2, t3);
       }
@@ -668,7 +671,9 @@ void scan_rows_kernel(const bf16_t* __restrict__ q_layer, const bf16_t* __restri
             const int rr = row0 + (2 * wv + x) * 32 + (li & 31);
             if (rr < rows && kt4 + piece <= kt) {
               const float4 val = *reinterpret_cast<const float4*>(rec[wv][x] + piece * PLANE + li * 16);
-              top4[(((size_t)blockIdx.z * rows + rr) * 2 + (li >> 5)) * n_tiles_all + tile0 + kt4 + piece] = val;
+              // offset inside the workgroup's 256 rows: below 2^20 records
+              const uint32_t off = (uint32_t)((((2 * wv + x) * 32 + (li & 31)) * 2 + (li >> 5)) * n_tiles_all + tile0 + kt4 + piece);
+              top4_wg[off] = val;
             }
           }
         }
