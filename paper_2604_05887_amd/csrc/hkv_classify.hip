@@ -704,68 +704,6 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {   
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16_pair, a), __builtin_bit_cast(bf16_pair, b), c, false);
 }
 
-__device__ __forceinline__ void wave_lds_sync() {     // orders the wave's own shared-memory writes before its later reads
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// The kth largest of the keys one wave holds (N per lane, the first n_used registers of every lane in use; an
-// absent entry holds 0 and every real key lies in [lo, hi], lo >= 1; at least kth real keys), exactly: radix
-// selection on key - lo, eight bits per round, through a 256-bin histogram in `hist` (the wave's own 256
-// words of shared memory).  A round costs a handful of instructions per register where the bitwise search
-// above costs three per register and BIT.
-// max_rounds < 4: the search stops early and returns the smallest key that shares the decided bits with the
-// kth largest -- a lower bound for it.
-template <int N>
-__device__ __forceinline__ uint32_t wave_radix_kth(const uint32_t (&key)[N], int n_used, int kth, uint32_t lo, uint32_t hi,
-                                                   uint32_t* hist, int max_rounds = 4) {
-  const int lane = thread_index() & 63;
-  const uint32_t span = hi - lo;
-  int shift = 32 - __builtin_clz(span | 1u);                 // bits of key - lo not yet decided (wave-uniform)
-  uint32_t d[N];                                             // key - lo; an absent entry gets 2^32 - 1: above the span
-                                                             // (lo >= 1), so it never shares a prefix with a real key
-#pragma unroll
-  for (int e = 0; e < N; ++e) d[e] = key[e] >= lo ? key[e] - lo : 0xFFFFFFFFu;
-  uint32_t prefix = 0;                                       // the decided bits
-  int need = kth;                                            // rank among the keys that share the prefix
-  for (int round = 0; shift > 0 && round < max_rounds; ++round) {
-    const int w = min(8, shift);
-    const int hi_shift = shift;                              // keys in play: (key - lo) >> hi_shift == prefix
-    shift -= w;
-    *reinterpret_cast<uint4*>(hist + 4 * lane) = make_uint4(0, 0, 0, 0);
-    wave_lds_sync();
-    if (hi_shift >= 32) {                                    // first round of a full-width span: every real key is in play
-#pragma unroll
-      for (int e = 0; e < N; ++e)
-        if (e < n_used && key[e] >= lo) atomicAdd(hist + (d[e] >> shift), 1u);
-    } else {
-#pragma unroll
-      for (int e = 0; e < N; ++e)
-        if (e < n_used && (d[e] >> hi_shift) == prefix) atomicAdd(hist + ((d[e] >> shift) & ((1u << w) - 1u)), 1u);
-    }
-    wave_lds_sync();
-    const uint4 c = *reinterpret_cast<const uint4*>(hist + 4 * lane);          // bins 4 * lane .. 4 * lane + 3
-    const int s = (int)(c.x + c.y + c.z + c.w);
-    const int incl = wave_inclusive_scan_dpp(s);
-    const int total = __builtin_amdgcn_readlane(incl, 63);
-    const int a3 = total - incl;                             // keys in bins above this lane's
-    // the largest bin b with (keys in bins >= b) >= need
-    const int c3 = a3 + (int)c.w, c2 = c3 + (int)c.z, c1 = c2 + (int)c.y, c0 = c1 + (int)c.x;
-    int cand = -1, above = 0;
-    if (c0 >= need) { cand = 4 * lane; above = c1; }
-    if (c1 >= need) { cand = 4 * lane + 1; above = c2; }
-    if (c2 >= need) { cand = 4 * lane + 2; above = c3; }
-    if (c3 >= need) { cand = 4 * lane + 3; above = a3; }
-    const uint64_t has = __builtin_amdgcn_ballot_w64(cand >= 0);
-    const int src = 63 - __builtin_clzll(has | 1ull);        // highest lane with a candidate holds the largest bin
-    const int bin = __builtin_amdgcn_readlane(cand, src);
-    need -= __builtin_amdgcn_readlane(above, src);
-    prefix = (prefix << w) | (uint32_t)bin;
-  }
-  return lo + (prefix << shift);
-}
-
 constexpr int kExcList = 256;
 template <int NGL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NGL == 8 ? 5 : NGL == 16 ? 3 : 1)))

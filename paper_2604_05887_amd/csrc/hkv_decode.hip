@@ -689,6 +689,63 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ o0, const f
 // updated in place since nobody reads it; t_arg < 0 reads the device counter cnt_a[layer], the new
 // length goes to cnt_b, and a follow-up kernel publishes it once every reader is done.
 
+// Top-k of up to 64 * R chunk scores held in shared memory (sig), without block-wide passes: every wave
+// keeps all keys in registers (R per lane; chunk 64 * m + lane in register m).  Wave 0 finds the k-th
+// largest key by radix selection on its own histogram; after the one barrier that hands it over, every wave
+// counts with wave votes, and wave m % 4 emits the picks of register m -- chunks with a key above the
+// threshold, those equal to it in chunk order up to the k-th place -- ascending by chunk id.  All NT threads
+// call (the barrier); waves beyond the fourth only take part in it.
+template <int R, int NT>
+__device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n_c, int k, uint32_t* hist, uint32_t* bc,
+                                                         bool to_memory, int32_t* sel_mem, int32_t* sel_lds) {
+  const int tid = thread_index(), lane = tid & 63, wv = tid >> 6;
+  const int n_used = (n_c + 63) >> 6;
+  uint32_t key[R];
+#pragma unroll
+  for (int m = 0; m < R; ++m) {
+    const int ch = lane + 64 * m;
+    key[m] = (m < n_used && ch < n_c) ? float_order_key(sig[ch]) : 0u;      // 0: no chunk (below every real key)
+  }
+  if (wv == 0) {
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int m = 0; m < R; ++m) {
+      if (key[m] != 0u) { lo = min(lo, key[m]); hi = max(hi, key[m]); }
+    }
+    lo = wave_min_u32_dpp(lo);
+    hi = ~wave_min_u32_dpp(~hi);
+    const uint32_t t = wave_radix_kth<R>(key, n_used, k, max(lo, 1u), hi, hist);
+    if (lane == 0) bc[0] = t;
+  }
+  __syncthreads();
+  const uint32_t thr = bc[0];
+  if (wv >= 4) return;
+  int n_gt = 0;
+#pragma unroll
+  for (int m = 0; m < R; ++m)
+    if (m < n_used) n_gt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[m] > thr));   // wave-uniform branch
+  const int r_adm = k - n_gt;                            // >= 1 places left for keys equal to the threshold
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int gt_run = 0, eq_run = 0;
+#pragma unroll
+  for (int m = 0; m < R; ++m) {
+    if (m >= n_used) break;                              // wave-uniform
+    const unsigned long long gtb = __builtin_amdgcn_ballot_w64(key[m] > thr);
+    const unsigned long long eqb = __builtin_amdgcn_ballot_w64(key[m] == thr);   // absent entries are 0 < thr
+    if ((m & 3) == wv) {
+      const bool is_gt = (gtb >> lane) & 1ull, is_eq = (eqb >> lane) & 1ull;
+      const int eq_before = eq_run + __builtin_popcountll(eqb & below);
+      if (is_gt || (is_eq && eq_before < r_adm)) {
+        const int pos = gt_run + __builtin_popcountll(gtb & below) + min(eq_before, r_adm);
+        if (to_memory) sel_mem[pos] = lane + 64 * m;
+        if (sel_lds) sel_lds[pos] = lane + 64 * m;
+      }
+    }
+    gt_run += __builtin_popcountll(gtb);
+    eq_run += __builtin_popcountll(eqb);
+  }
+}
+
 // Chunk scoring and chunk top-k of one dynamic unit; whole block (NT threads).
 constexpr int kSelHeader = 256 + 16;       // words before the chunk scores: histogram, 2 broadcast words, scan area
 template <typename T, int NT = 256>
@@ -801,6 +858,15 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
       if (to_memory) cv.sel[d.idx_off + pos] = tid;
       if (sel_lds) sel_lds[pos] = tid;
     }
+    return;
+  }
+  // up to 2048 chunks: the keys fit a wave's registers and the selection needs one barrier instead of the
+  // block-wide radix passes and scans below (about sixty barriers at 1600 chunks)
+  if (n_c <= 64 * 32) {
+    int32_t* sel_mem = cv.sel + d.idx_off;
+    if (n_c <= 64 * 8) topk_chunks_in_registers<8, NT>(sig, n_c, k_sel, hist, bc, to_memory, sel_mem, sel_lds);
+    else if (n_c <= 64 * 16) topk_chunks_in_registers<16, NT>(sig, n_c, k_sel, hist, bc, to_memory, sel_mem, sel_lds);
+    else topk_chunks_in_registers<32, NT>(sig, n_c, k_sel, hist, bc, to_memory, sel_mem, sel_lds);
     return;
   }
   uint32_t T_key = 0;

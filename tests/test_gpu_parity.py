@@ -229,18 +229,43 @@ def test_cfg1_full_size_sampled_units():
     dw.cache.close()
 
 
-@pytest.mark.parametrize("chunk,k_chunks,shrink", [(8, 24, 2), (16, 300, 1)])
+@pytest.mark.parametrize("chunk,k_chunks,shrink", [(8, 24, 2), (16, 300, 1), (8, 40, 1), (8, 700, 1)])
 def test_many_small_chunks_radix_path(chunk, k_chunks, shrink):
-    """Small chunks (the paper's example is 8 tokens) give more than 256 chunks per head, which takes
-    the radix-select path of the chunk top-k; k larger than 256 as well."""
+    """Small chunks (the paper's example is 8 tokens) give more than 256 chunks per head: up to 2048 the
+    chunk top-k keeps the keys in each wave's registers (8 or 16 per lane here: 512 and 1024 chunks; 32 per
+    lane in the next test) and selects by radix over a per-wave histogram; k larger than 256 and k of most
+    chunks as well.
+    Every decode shape that repeats or owns the selection runs it."""
     wl = make_workload(1, n_layers=2, shrink=shrink, steps=3)
     wl.chunk_size[:] = chunk
     dyn = wl.head_type == 1
     wl.budget[dyn] = chunk * k_chunks
-    stats = P.full_pipeline(wl)
     n_c = -(-int(wl.seqlens[0]) // chunk)
     assert n_c > 256
-    _say(f"chunk {chunk} k {k_chunks} n_c {n_c}", stats)
+    for mode in (0, 1, 2, 4, 5):
+        stats = P.full_pipeline(wl, decode_dynamic=mode)
+        _say(f"chunk {chunk} k {k_chunks} n_c {n_c} mode {mode}", stats)
+
+
+@pytest.mark.parametrize("n_visual,expect", [(15360, "registers"), (19456, "block")])
+def test_chunk_counts_around_the_register_limit(n_visual, expect):
+    """8-token chunks on a 16k-token prompt give 2048 chunks per head, the most the register-resident chunk
+    top-k takes (32 keys per lane); on a 20k-token prompt 2560, which runs as block-wide radix passes over the
+    scores in shared memory."""
+    from hkv_synth import workloads as W
+    base = dict(W.CONFIGS[1])
+    base.update(name=f"chunks_{n_visual}", n_layers=1, n_visual=[n_visual], n_text=[1024], block=n_visual, steps=2, chunk=[8],
+                k_chunks=300)
+    W.CONFIGS[96] = base
+    try:
+        wl = make_workload(96, seed=2)
+    finally:
+        del W.CONFIGS[96]
+    n_c = -(-int(wl.seqlens[0]) // 8)
+    assert (n_c == 2048) if expect == "registers" else (n_c > 2048)
+    for mode in (3, 5):
+        stats = P.full_pipeline(wl, decode_dynamic=mode)
+        _say(f"n_c {n_c} mode {mode}", stats)
 
 
 @pytest.mark.parametrize("n_q,n_kv,window,dtype", [(4, 4, 48, "bf16"), (8, 4, 32, "bf16"), (6, 2, 16, "bf16"),
