@@ -500,6 +500,31 @@ def test_head_scores_do_not_depend_on_the_workspace_size_and_focus_edges():
     assert np.abs(tiny - want).max() <= SCORE_ATOL
 
 
+def test_head_scores_on_short_prompts():
+    """Prompts of 120 to 230 tokens (a handful of 32-key tiles, fewer groups of 16 keys than lanes, k = 6 to
+    12), three in a batch, bf16 and fp32."""
+    from hkv_synth import make_prompt_queries
+    from hkv_synth import workloads as W
+    for dtype in ("bf16", "f32"):
+        base = dict(W.CONFIGS[1])
+        base.update(name=f"short_{dtype}", dtype=dtype, n_layers=2, batch=3, n_visual=[8, 40, 100], n_text=[112, 120, 130],
+                    block=64, chunk=[8, 8, 8], budget_frac=[0.3, 0.3, 0.3], steps=1)
+        W.CONFIGS[95] = base
+        try:
+            wl = make_workload(95, seed=4)
+        finally:
+            del W.CONFIGS[95]
+        qp = make_prompt_queries(wl)
+        ocfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128,
+                              window=wl.window, dtype=wl.dtype)
+        for rho in (0.05, 0.01):
+            got = _device_head_scores(wl, qp, rho=rho)
+            want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual, rho=rho)
+            err = np.abs(got - want).max()
+            print(f"\n[head scores, short prompts {list(map(int, wl.seqlens))} {dtype} rho={rho}] max abs err {err:.2e}", flush=True)
+            assert err <= SCORE_ATOL
+
+
 def test_head_scores_with_runs_of_equal_logits():
     """Equal keys give equal logits: a head whose keys are all the same row (every logit of a row ties, the
     bound from the group maxima admits the whole row and the listed logits no longer fit the registers), a
