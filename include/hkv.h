@@ -99,9 +99,9 @@ typedef struct {
   int32_t max_new_tokens;   /* capacity of every head's uncompressed decode tail */
   float softmax_scale;      /* 0 -> 1/sqrt(head_dim) */
   int32_t decode_tile_rows; /* rows per split-K tile of decode attention: 0 = chosen from the amount of
-                               work (a bf16 cache then also carries a tiling of 1024-row tiles and
-                               every call takes the one that suits its tile count, see
-                               hkv_cache_call_tiling); bf16 caches also accept any multiple of 32 from
+                               work (a bf16 cache then also carries a second tiling -- 1024-row tiles, or
+                               256-row tiles when the first has grown to 1024 -- and every call takes the
+                               one that suits its tile count, see hkv_cache_call_tiling); bf16 caches also accept any multiple of 32 from
                                128 to 4096, which every call then uses (tuning knob; the result does
                                not depend on it beyond fp32 summation order) */
   int32_t decode_dynamic;   /* how a decode step is launched: 1 = one workgroup per dynamic head does chunk
@@ -265,10 +265,12 @@ HKV_API int hkv_cache_step_bytes(const hkv_cache* cache, int layer_begin, int la
 HKV_API int hkv_cache_decode_shape(const hkv_cache* cache, int32_t* tile_rows, int32_t* dynamic_mode);
 
 /* The tiling a decode call over layers [layer_begin, layer_end) uses.  bf16 caches under the automatic
- * tile rule (decode_tile_rows = 0) carry a second tiling of 1024-row tiles besides the one that
- * hkv_cache_decode_shape reports; a call takes the large tiles when it has more small tiles than the
- * device has compute units and the large tiles give every tile a compute unit of its own (small
- * whole-model steps), the small tiles otherwise (per-layer calls, large steps).  Same results up to
+ * tile rule (decode_tile_rows = 0) carry a second tiling besides the one that hkv_cache_decode_shape
+ * reports.  Where the first has fewer than 1024 rows per tile the second has 1024: a call takes the large
+ * tiles when it has more small tiles than the device has compute units and the large tiles give every tile a
+ * compute unit of its own (small whole-model steps), the small tiles otherwise (per-layer calls, larger
+ * steps).  Where the first has grown to 1024 rows (large caches) the second has 256: a call takes them when
+ * its large tiles would not give every compute unit one (calls over few layers).  Same results up to
  * fp32 summation order.  *tile_rows = rows per tile of such a call, *n_tiles = its tiles (tail at
  * full capacity).  A streamed call (dynamic mode 5) reports the rows of a workgroup's share and the number of
  * workgroups instead.  Either pointer may be NULL. */

@@ -110,6 +110,7 @@ struct Layout {
   int32_t max_C = 0, max_rows_static = 0, max_rows_dynamic = 0, max_chunks = 0;
   int64_t step_bytes0 = 0, reselect_extra_bytes = 0;   // per step at an empty tail; extra summary reads of mode 3
   int mode = 2;                    // how decode steps run the dynamic heads (hkv_config.decode_dynamic, resolved)
+  bool mode_by_rule = true;        // the automatic rule chose it (a caller's explicit choice is followed to the letter)
   // element counts
   int64_t n_kept = 0, n_sel = 0, n_scores = 0, n_sigma = 0, n_rows = 0;
   // host tier (bf16 caches only): the dynamic units' prompt rows live in mapped host memory
@@ -123,8 +124,8 @@ struct Layout {
   int tile = 0;
   // A second tiling of the same cache with larger tiles (bf16 caches under the automatic tile rule): only its
   // unit and tile tables differ; they sit behind the first tiling's arena.  A call picks one of the two.
-  std::shared_ptr<Layout> coarse;
-  size_t coff_units = 0, coff_sitems = 0, coff_ditems = 0, coff_static_descs = 0, coff_dyn_descs = 0;
+  std::shared_ptr<Layout> second;
+  size_t s2off_units = 0, s2off_sitems = 0, s2off_ditems = 0, s2off_static_descs = 0, s2off_dyn_descs = 0;
 };
 
 inline bool pow2_ge4(int c) { return c >= 4 && (c & (c - 1)) == 0; }
@@ -412,24 +413,28 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
     }
   }
   if (rc != HKV_OK) return rc;
-  // Small steps -- a whole-model call of a short-context cache -- run faster when every tile has a compute
-  // unit to itself, large per-layer calls when the tiles are small: the cache carries a second tiling of
-  // kTileBf16Max rows and every call takes the one that suits its tile count (hkv_decode_attn).
-  if (cfg->dtype == HKV_BF16 && cfg->decode_tile_rows == 0 && lo.tile < kTileBf16Max) {
+  // A bf16 cache under the automatic rule carries a second tiling, and every call takes the one that suits its
+  // tile count (call_uses_second_tiling).  First tiling below kTileBf16Max rows: the second has kTileBf16Max --
+  // small steps, a whole-model call of a short-context cache, run faster when every tile has a compute unit to
+  // itself.  First tiling grown to kTileBf16Max (a large cache): the second has kTileBf16 rows, for calls over
+  // few layers, which would leave most compute units without a tile otherwise.
+  if (cfg->dtype == HKV_BF16 && cfg->decode_tile_rows == 0) {
+    const int tile2 = lo.tile < kTileBf16Max ? kTileBf16Max : kTileBf16;
     auto co = std::make_shared<Layout>();
-    if (plan_layout_tile(cfg, plan, *co, kTileBf16Max, tiered) == HKV_OK && co->n_items < lo.n_items) {
+    if (plan_layout_tile(cfg, plan, *co, tile2, tiered) == HKV_OK && co->n_items != lo.n_items) {
       size_t off = lo.arena_bytes;
       auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-      lo.coff_units = take(co->units.size() * sizeof(UnitDesc));
-      lo.coff_sitems = take(std::max<size_t>(1, co->sitems.size()) * sizeof(AttnItem));
-      lo.coff_ditems = take(std::max<size_t>(1, co->ditems.size()) * sizeof(AttnItem));
-      lo.coff_static_descs = take(std::max<size_t>(1, co->static_units.size()) * sizeof(UnitDesc));
-      lo.coff_dyn_descs = take(std::max<size_t>(1, co->dynamic_units.size()) * sizeof(UnitDesc));
+      lo.s2off_units = take(co->units.size() * sizeof(UnitDesc));
+      lo.s2off_sitems = take(std::max<size_t>(1, co->sitems.size()) * sizeof(AttnItem));
+      lo.s2off_ditems = take(std::max<size_t>(1, co->ditems.size()) * sizeof(AttnItem));
+      lo.s2off_static_descs = take(std::max<size_t>(1, co->static_units.size()) * sizeof(UnitDesc));
+      lo.s2off_dyn_descs = take(std::max<size_t>(1, co->dynamic_units.size()) * sizeof(UnitDesc));
       lo.arena_bytes = off;
-      lo.coarse = std::move(co);
+      lo.ws_bytes = std::max(lo.ws_bytes, co->ws_bytes);       // the finer tiling has more records
+      lo.second = std::move(co);
     }
   }
-  lo.rows_end = lo.coarse ? lo.coff_units : lo.arena_bytes;
+  lo.rows_end = lo.second ? lo.s2off_units : lo.arena_bytes;
   build_stream_shapes(cfg, plan->batch, lo);
   if (!lo.stream_blob.empty()) {
     lo.off_stream = align_up(lo.arena_bytes);
@@ -439,6 +444,7 @@ int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool ti
                              align_up((size_t)lo.stream_slots_max * kMlFloats * sizeof(float));
     lo.ws_bytes = std::max(lo.ws_bytes, ws_stream);
   }
+  lo.mode_by_rule = cfg->decode_dynamic == 0;
   if (cfg->decode_dynamic != 0) lo.mode = cfg->decode_dynamic;
   else if (cfg->dtype == HKV_BF16 &&
            std::max(lo.max_rows_static + cfg->max_new_tokens, lo.max_rows_dynamic) <= kUnitShapeMaxRows)
@@ -468,7 +474,7 @@ struct hkv_cache {
   int clock_khz = 2400000;            // that device's shader clock
   int device = -1;                    // device that was current when the cache was created
   void* scratch_dev = nullptr;        // that device's copy of the library's split-K record array
-  CacheView cv_coarse;                // cv with the tables of the coarse tiling (if lo.coarse)
+  CacheView cv_second;                // cv with the tables of the coarse tiling (if lo.second)
   hipStream_t prof_stream = nullptr;  // stream of the profiled calls
   std::vector<uint8_t> prof_mask;     // per profiled call: bit j set if kernel j was launched
 };
@@ -602,24 +608,24 @@ static int create_cache(const hkv_config* cfg, const hkv_plan* plan, void* cache
     for (int32_t u : lo.dynamic_units) dd.push_back(lo.units[u]);
     up(lo.off_dyn_descs, dd.data(), dd.size() * sizeof(UnitDesc));
   }
-  c->cv_coarse = cv;
-  if (lo.coarse) {
-    const Layout& co = *lo.coarse;
-    CacheView& cc = c->cv_coarse;
-    cc.units = reinterpret_cast<const UnitDesc*>(a + lo.coff_units);
-    cc.static_items = reinterpret_cast<const AttnItem*>(a + lo.coff_sitems);
-    cc.dynamic_items = reinterpret_cast<const AttnItem*>(a + lo.coff_ditems);
-    cc.static_descs = reinterpret_cast<const UnitDesc*>(a + lo.coff_static_descs);
-    cc.dyn_descs = reinterpret_cast<const UnitDesc*>(a + lo.coff_dyn_descs);
+  c->cv_second = cv;
+  if (lo.second) {
+    const Layout& co = *lo.second;
+    CacheView& cc = c->cv_second;
+    cc.units = reinterpret_cast<const UnitDesc*>(a + lo.s2off_units);
+    cc.static_items = reinterpret_cast<const AttnItem*>(a + lo.s2off_sitems);
+    cc.dynamic_items = reinterpret_cast<const AttnItem*>(a + lo.s2off_ditems);
+    cc.static_descs = reinterpret_cast<const UnitDesc*>(a + lo.s2off_static_descs);
+    cc.dyn_descs = reinterpret_cast<const UnitDesc*>(a + lo.s2off_dyn_descs);
     cc.tile_rows = co.tile;
-    up(lo.coff_units, co.units.data(), co.units.size() * sizeof(UnitDesc));
-    up(lo.coff_sitems, co.sitems.data(), co.sitems.size() * sizeof(AttnItem));
-    up(lo.coff_ditems, co.ditems.data(), co.ditems.size() * sizeof(AttnItem));
+    up(lo.s2off_units, co.units.data(), co.units.size() * sizeof(UnitDesc));
+    up(lo.s2off_sitems, co.sitems.data(), co.sitems.size() * sizeof(AttnItem));
+    up(lo.s2off_ditems, co.ditems.data(), co.ditems.size() * sizeof(AttnItem));
     std::vector<UnitDesc> sd, dd;
     for (int32_t u : co.static_units) sd.push_back(co.units[u]);
     for (int32_t u : co.dynamic_units) dd.push_back(co.units[u]);
-    up(lo.coff_static_descs, sd.data(), sd.size() * sizeof(UnitDesc));
-    up(lo.coff_dyn_descs, dd.data(), dd.size() * sizeof(UnitDesc));
+    up(lo.s2off_static_descs, sd.data(), sd.size() * sizeof(UnitDesc));
+    up(lo.s2off_dyn_descs, dd.data(), dd.size() * sizeof(UnitDesc));
   }
   up(lo.off_vis, plan->is_visual, (size_t)lo.total_tokens);
   if (e == hipSuccess) e = hipMemset(a + lo.off_cnt, 0, (size_t)2 * cfg->n_layers * 4);
@@ -747,17 +753,19 @@ int hkv_compress_from_scores(hkv_cache* cache, int layer_begin, int layer_end, c
   return compress_impl(cache, layer_begin, layer_end, nullptr, k, v, nullptr, 0, stream, false);
 }
 
-// Which tiling a decode call over [lb, le) takes: the fine one, unless the call has more fine tiles than the
-// device has compute units and the coarse tiling gives every tile a compute unit of its own (measured on the
-// 7B shape at 8K context, all layers in one call: 228 tiles of 1024 rows take 21.8 us per step, 678 tiles
-// of 256 rows 24.8 us; a call per layer is 23 % slower with the large tiles).
-static bool call_uses_coarse_tiling(const hkv_cache* c, int lb, int le) {
-  if (!c->lo.coarse || c->lo.mode == 4) return false;
-  if (c->lo.mode == 5) return false;            // a streamed cache's other layer ranges take the first tiling
-  const Layout& co = *c->lo.coarse;
-  const int fine_tiles = c->lo.item_begin[le] - c->lo.item_begin[lb];
-  const int coarse_tiles = co.item_begin[le] - co.item_begin[lb];
-  return fine_tiles > c->n_cus && coarse_tiles <= c->n_cus;
+// Which tiling a decode call over [lb, le) takes.  With a coarser second tiling: the first, unless the call has
+// more of its tiles than the device has compute units and the second gives every tile a compute unit of its
+// own (measured on the 7B shape at 8K context, all layers in one call: 228 tiles of 1024 rows take 21.8 us
+// per step, 678 tiles of 256 rows 24.8 us; a call per layer is 23 % slower with the large tiles).
+static bool call_uses_second_tiling(const hkv_cache* c, int lb, int le) {
+  if (!c->lo.second || c->lo.mode == 4) return false;
+  const Layout& s2 = *c->lo.second;
+  const int first_tiles = c->lo.item_begin[le] - c->lo.item_begin[lb];
+  const int second_tiles = s2.item_begin[le] - s2.item_begin[lb];
+  if (s2.tile > c->lo.tile) return first_tiles > c->n_cus && second_tiles <= c->n_cus;
+  // finer second tiling (large caches): for calls whose large tiles would not even give every compute unit one
+  // (a call per layer of the 72B video shape: 28 tiles of 1024 rows 32.3 us, 96 of 256 rows 26.3 us)
+  return first_tiles <= c->n_cus;
 }
 
 // The table a streamed call over [lb, le) walks, or null when the call does not run streamed: the cache is
@@ -774,6 +782,10 @@ static const StreamTable* stream_table_of_call(const hkv_cache* c, int lb, int l
   const int t = c->host_tail[lb];
   const StreamTable* tb = &sh.tables[0];
   for (const StreamTable& x : sh.tables) if (x.t_ref <= t) tb = &x;
+  // under the automatic rule a call per layer streams only when its shares are long enough as well; shorter
+  // ones pay the unit crossings (descriptor, repeated selection) too often and run as tiles (measured on the
+  // serving mix: 56 vs 59 us per call)
+  if (c->lo.mode_by_rule && s > 0 && tb->share_rows < kStreamAutoRows) return nullptr;
   if (shape) *shape = &sh;
   return tb;
 }
@@ -782,7 +794,7 @@ static const StreamTable* stream_table_of_call(const hkv_cache* c, int lb, int l
 static size_t call_record_slots(const hkv_cache* c, int lb, int le) {
   const StreamShape* sh = nullptr;
   if (const StreamTable* tb = stream_table_of_call(c, lb, le, &sh)) return (size_t)tb->n_wg + (size_t)sh->n_units;
-  const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
+  const Layout& lo = call_uses_second_tiling(c, lb, le) ? *c->lo.second : c->lo;
   return (size_t)(lo.item_begin[le] - lo.item_begin[lb]);
 }
 
@@ -794,7 +806,7 @@ int hkv_cache_call_tiling(const hkv_cache* c, int lb, int le, int32_t* tile_rows
     if (n_tiles) *n_tiles = tb->n_wg;
     return HKV_OK;
   }
-  const Layout& lo = call_uses_coarse_tiling(c, lb, le) ? *c->lo.coarse : c->lo;
+  const Layout& lo = call_uses_second_tiling(c, lb, le) ? *c->lo.second : c->lo;
   if (tile_rows) *tile_rows = lo.tile;
   if (n_tiles) *n_tiles = lo.item_begin[le] - lo.item_begin[lb];
   return HKV_OK;
@@ -824,9 +836,9 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
   float* parts = static_cast<float*>(records);
   float* parts_ml = reinterpret_cast<float*>(static_cast<char*>(records) +
                                              align_up(n_slots * (size_t)(c->cfg.n_q_heads / c->cfg.n_kv_heads) * kD * sizeof(float)));
-  const bool use_coarse = call_uses_coarse_tiling(c, lb, le);
-  const Layout& lo = use_coarse ? *c->lo.coarse : c->lo;
-  const CacheView& cv = use_coarse ? c->cv_coarse : c->cv;
+  const bool use_second = call_uses_second_tiling(c, lb, le);
+  const Layout& lo = use_second ? *c->lo.second : c->lo;
+  const CacheView& cv = use_second ? c->cv_second : c->cv;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int slot_base = lo.item_begin[lb];
   const int db = lo.dynamic_begin[lb], nd = lo.dynamic_begin[le] - db;
@@ -1131,6 +1143,7 @@ int hkv_cache_set_decode_dynamic(hkv_cache* c, int32_t dynamic_mode) {
   if (dynamic_mode >= 4 && c->cfg.dtype != HKV_BF16) return HKV_ESHAPE;
   if (c->cfg.index_generated && (dynamic_mode == 2 || dynamic_mode == 5)) return HKV_ESHAPE;
   c->lo.mode = dynamic_mode;
+  c->lo.mode_by_rule = false;
   return HKV_OK;
 }
 

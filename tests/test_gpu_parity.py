@@ -357,6 +357,19 @@ def test_decode_shape_is_reported_and_auto_rule():
     dw = runner.setup(wl, upload_prompt=False, decode_tile_rows=128)
     assert dw.cache.decode_shape() == (128, 2)          # small chunks, many tiles: the selection runs once per head
     dw.cache.close()
+    # a serving mix of 16 long prompts: the whole-model call streams (768 equal shares), a call per layer has
+    # shares too short for that under the automatic rule and runs as tiles; a caller's explicit choice of the
+    # streamed shape is followed for both
+    big = make_workload(4, steps=1, tensors=False)
+    dw = runner.setup(big, upload_prompt=False)
+    assert dw.cache.decode_shape()[1] == 5
+    whole, one = dw.cache.call_tiling(), dw.cache.call_tiling(5, 6)
+    assert whole[1] == 768 and whole[0] >= 2048
+    assert one[0] in (256, 512, 1024) and one[1] > 0
+    dw.cache.set_decode_dynamic(5)
+    forced = dw.cache.call_tiling(5, 6)
+    assert forced[1] == 768 and forced[0] < 2048
+    dw.cache.close()
 
 
 def test_stream_read_probe_reports_a_plausible_rate():
