@@ -1138,8 +1138,12 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
 // boundary is needed; all blocks of a unit compute and store identical picks.  In that shape the grid
 // also carries the static tiles: blocks [n_ditems, n_ditems + n_sitems), which wait static_hold x 512
 // clocks before their first loads.
-template <typename T, int G, bool INDEXED = false>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+// NW: waves per workgroup (bf16 caches).  Calls with no more tiles than compute units run with kWideWaves:
+// every workgroup has a compute unit to itself, and twelve waves bring the chunk summaries in and walk the
+// tile's 32-row steps three times as fast as four -- what such a call waits for is this one chain.
+constexpr int kWideWaves = 12;
+template <typename T, int G, bool INDEXED = false, int NW = 4>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_ditems, int sitem_begin,
                           int slot_base, const T* __restrict__ q, const T* __restrict__ k_new,
                           const T* __restrict__ v_new, PartOut partials, int t_arg, int reselect, int lds_sel_off,
@@ -1152,7 +1156,7 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
     // behind all of them.  The static tiles therefore start a little later: static_hold x 512 clocks,
     // the time the summaries need on the memory system (0 for grids of several rounds).
     for (int i = 0; i < static_hold; ++i) __builtin_amdgcn_s_sleep(8);
-    attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+    attention_item<T, G, NW, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
     return;
   }
   // Workgroups go to the eight dies in rotation (workgroup b runs on die b % 8) and each die has its own L2.
@@ -1177,11 +1181,11 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
     int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
     // the picks stay in LDS for this block's own tile; the first tile also leaves them (and the chunk
     // scores) in memory for export
-    select_chunks_of_unit<T>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0, n_c_now, k_now);
+    select_chunks_of_unit<T, NW * 64>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0, n_c_now, k_now);
     __syncthreads();
     picks = sel_lds;
   }
-  attention_item<T, G, 4, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem, picks);
+  attention_item<T, G, NW, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem, picks);
 }
 
 // One workgroup of kUnitWaves waves per unit (bf16 caches): chunk selection for a dynamic unit, then attention
@@ -1490,7 +1494,7 @@ hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dy
   return hipErrorInvalidValue;
 }
 
-template <typename T, int G, bool INDEXED = false>
+template <typename T, int G, bool INDEXED = false, int NW = 4>
 static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, int ditem_begin, int n_ditems,
                                          int sitem_begin, int n_sitems, int slot_base, const void* q,
                                          const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
@@ -1498,16 +1502,17 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
                                          hipEvent_t ev0, hipEvent_t ev1) {
   const PartOut partials = {parts_o, parts_ml, nullptr, sizeof(T) == 2 ? out : nullptr};
   // reselect: selection scratch and the tile's staging area share the front; the picks sit behind both
-  const size_t front = std::max(attn_smem_bytes<T, G, true>(), reselect ? select_smem_bytes(max_chunks) : (size_t)0);
+  const size_t staging = NW == 4 ? attn_smem_bytes<T, G, true>() : (size_t)NW * G * kPartStride * sizeof(float);
+  const size_t front = std::max(staging, reselect ? select_smem_bytes(max_chunks) : (size_t)0);
   const size_t smem = front + (reselect ? (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t) : 0);
   static std::atomic<size_t> attr{0};
   if (smem > attr.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G, INDEXED>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G, INDEXED, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr.store(smem, std::memory_order_release);
   }
-  HKV_LAUNCH((dynamic_tiles_kernel<T, G, INDEXED>), dim3(n_ditems + n_sitems), dim3(256), (uint32_t)smem, st, ev0, ev1,
+  HKV_LAUNCH((dynamic_tiles_kernel<T, G, INDEXED, NW>), dim3(n_ditems + n_sitems), dim3(NW * 64), (uint32_t)smem, st, ev0, ev1,
                         cv, layer_begin, ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
                         (const T*)v_new, partials, t_arg, reselect, (int)(front / sizeof(float)), static_hold);
   return hipGetLastError();
@@ -1516,8 +1521,19 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
                                 const void* v_new, float* parts_o, float* parts_ml, void* out, int t_arg, int reselect,
-                                int static_hold, int max_chunks, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+                                int static_hold, int max_chunks, int wide, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (n_ditems + n_sitems <= 0) return hipSuccess;
+  if (wide && dtype == HKV_BF16 && reselect) {      // few tiles: workgroups of kWideWaves waves
+    if (cv.index_gen) {
+      HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, true, kWideWaves>(
+                               cv, layer_begin, ditem_begin, n_ditems, sitem_begin, n_sitems, slot_base, q, k_new, v_new,
+                               parts_o, parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
+    }
+    HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, false, kWideWaves>(
+                             cv, layer_begin, ditem_begin, n_ditems, sitem_begin, n_sitems, slot_base, q, k_new, v_new,
+                             parts_o, parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
+    return hipErrorInvalidValue;
+  }
   if (cv.index_gen) {        // bf16 caches, tiles that repeat the selection
     if (dtype != HKV_BF16 || !reselect) return hipErrorInvalidValue;
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, true>(cv, layer_begin, ditem_begin, n_ditems, sitem_begin,
