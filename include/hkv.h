@@ -118,7 +118,9 @@ typedef struct {
                                covers (calls over all layers or over one layer; other layer ranges run as 3);
                                0 = chosen when the cache is laid out: 4 for bf16 caches whose heads all have at
                                most 768 rows (tail capacity included); 5 when a call over all layers gives every
-                               resident workgroup a share of at least 2048 rows; else 3 unless the repeated
+                               resident workgroup a share of at least 2048 rows (a call over one layer of such a
+                               cache then streams only if its shares reach that length too, else it runs as 3;
+                               an explicit 5 streams both); else 3 unless the repeated
                                summary reads would exceed a quarter of a step's bytes, then 2
                                (tuning knob, same results up to fp32 summation order) */
   int32_t chunk_score_group;/* how the query heads that share a KV head score a chunk (Appendix A gives one
