@@ -227,6 +227,48 @@ class Bench:
         del pbuf
         return us
 
+    # ---- per-workgroup time stamps of the tile launch (diagnosis; launch shape 3 only) ---------------------
+    def workgroup_stamps(self, n_steps=12):
+        """Runs n_steps more steps with the instrumented tile kernel and summarises the last one: when the
+        workgroups of the main launch start, read their descriptor, finish the chunk selection and finish
+        their rows, for static and dynamic tiles (microseconds from the first workgroup's start)."""
+        import numpy as np
+        torch, B = self.torch, self.B
+        dw = self.copies[0]
+        if dw.cache.decode_shape()[1] != 3:
+            return None
+        n_tiles = dw.cache.call_tiling()[1]
+        stamps = torch.zeros((n_tiles, B.HKV_STAMP_WORDS), dtype=torch.int64, device=self.dev)
+        dw.cache.set_stamps(stamps, n_tiles)
+        for i in range(n_steps):
+            self.raw_step(dw, i)
+        torch.cuda.synchronize()
+        dw.cache.set_stamps(None)
+        rec = stamps.cpu().numpy()
+        rec = rec[rec[:, 3] > 0]
+        t0 = rec[:, 0].min()
+        us = lambda x: (x - t0) / 100.0
+
+        def pct(x):
+            return {"min": round(float(x.min()), 2), "p50": round(float(np.median(x)), 2),
+                    "p90": round(float(np.percentile(x, 90)), 2), "max": round(float(x.max()), 2)}
+        out = {"what": "instrumented copy of the tile kernel, last of %d steps on one cache copy; microseconds, 10 ns ticks; "
+                       "'at' = from the first workgroup's start" % n_steps,
+               "workgroups": int(len(rec)), "launch_span_us": round(float(us(rec[:, 3]).max()), 2)}
+        for name, m in (("static_tiles", rec[:, 5] == 0), ("dynamic_tiles", rec[:, 5] == 1)):
+            r = rec[m]
+            if len(r) == 0:
+                continue
+            e = {"n": int(len(r)), "start_at": pct(us(r[:, 0])), "descriptor": pct((r[:, 1] - r[:, 0]) / 100.0)}
+            if name == "dynamic_tiles":
+                e["selection"] = pct((r[:, 2] - r[:, 1]) / 100.0)
+                e["rows_and_record"] = pct((r[:, 3] - r[:, 2]) / 100.0)
+            else:
+                e["rows_and_record"] = pct((r[:, 3] - r[:, 1]) / 100.0)
+            e["done_at"] = pct(us(r[:, 3]))
+            out[name] = e
+        return out
+
     # ---- one hkv_decode_attn call per layer, as a model interleaves them with its other layers --------
     def layerwise(self):
         torch, wl, K, n = self.torch, self.wl, self.K, self.n_copies
@@ -450,6 +492,9 @@ def main() -> int:
     ap.add_argument("--tune", action="store_true",
                     help="time every way of running the dynamic heads on this workload and keep the fastest, instead "
                          "of the library's own choice")
+    ap.add_argument("--stamps", action="store_true",
+                    help="also run the instrumented tile kernel and report per-workgroup time stamps "
+                         "(workloads whose main launch is the single launch of split-K tiles)")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read reference")
     ap.add_argument("--no-layerwise", action="store_true", help="skip the one-call-per-layer timing")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -554,6 +599,7 @@ def main() -> int:
     call_tile_rows, call_tiles = hb.copies[0].cache.call_tiling()            # of the timed call over all layers
     layer_tile_rows, layer_tiles = hb.copies[0].cache.call_tiling(0, 1)      # of a call over one layer
     probe_us = None if args.no_probe else hb.probe_read(a_bytes)
+    wg_stamps = hb.workgroup_stamps() if args.stamps else None
     lw_us = lw_graph_us = None
     if L > 1 and not args.no_layerwise:
         lw_us, lw_graph_us = hb.layerwise()
@@ -650,6 +696,7 @@ def main() -> int:
         "compress_ms": round(compress_ms, 3),
         "head_classification": classify,
         "memory_tier": memory_tier,
+        "workgroup_stamps": wg_stamps,
         "index_generated": bool(args.index_generated),
         "job_ms_compress_plus_steps": round(compress_ms + ms_per_step * K, 3),
         "decode_shape": {"tile_rows": call_tile_rows, "tiles": call_tiles, "dynamic_mode": dyn_mode,

@@ -27,7 +27,7 @@ HKV_NOALLOC_SCRATCH_BYTES = 16 << 20
 EXPORTED_SYMBOLS = (
     "hkv_query_sizes", "hkv_cache_create", "hkv_query_tier_sizes", "hkv_cache_create_tiered", "hkv_compress", "hkv_decode_attn", "hkv_decode_attn_noalloc", "hkv_full_workspace_size",
     "hkv_full_decode_attn", "hkv_cache_rewind", "hkv_cache_unit_info", "hkv_plan_unit_info", "hkv_cache_step_bytes",
-    "hkv_cache_decode_shape", "hkv_cache_call_tiling", "hkv_cache_set_decode_dynamic", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
+    "hkv_cache_decode_shape", "hkv_cache_call_tiling", "hkv_cache_set_decode_dynamic", "hkv_cache_set_stamps", "hkv_cache_set_device_tail",    "hkv_cache_export", "hkv_cache_import", "hkv_compress_from_scores", "hkv_reselect_chunks",
     "hkv_profile_enable", "hkv_profile_read", "hkv_profile_disable", "hkv_probe_stream_read", "hkv_head_scores_workspace_size", "hkv_head_scores", "hkv_focus_counts_workspace_size", "hkv_focus_counts", "hkv_allocate_budgets",
     "hkv_cache_destroy", "hkv_strerror", "hkv_abi_version",
 )
@@ -87,6 +87,7 @@ def load_library() -> C.CDLL:
     lib.hkv_cache_decode_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_call_tiling.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.hkv_cache_set_decode_dynamic.argtypes = [vp, C.c_int32]
+    lib.hkv_cache_set_stamps.argtypes = [vp, vp, C.c_int32]
     lib.hkv_cache_set_device_tail.argtypes = [vp, i32, vp]
     lib.hkv_cache_export.argtypes = [vp, i32, i32, i32, i32, vp, sz, C.POINTER(sz), vp]
     lib.hkv_cache_import.argtypes = [vp, i32, i32, i32, i32, vp, sz, vp]
@@ -292,6 +293,14 @@ def hkv_cache_set_decode_dynamic(handle: int, mode: int) -> None:
     _check(load_library().hkv_cache_set_decode_dynamic(handle, mode), "hkv_cache_set_decode_dynamic")
 
 
+HKV_STAMP_WORDS = 8
+
+
+def hkv_cache_set_stamps(handle: int, stamps, n_records: int) -> None:
+    """stamps: device tensor of n_records * HKV_STAMP_WORDS int64 (or None to clear the setting)."""
+    _check(load_library().hkv_cache_set_stamps(handle, _ptr(stamps), int(n_records)), "hkv_cache_set_stamps")
+
+
 def hkv_cache_set_device_tail(handle: int, enable: bool, stream=None) -> None:
     _check(load_library().hkv_cache_set_device_tail(handle, 1 if enable else 0, _stream(stream)), "hkv_cache_set_device_tail")
 
@@ -473,6 +482,9 @@ class HybridKVCache:
 
     def set_decode_dynamic(self, mode: int):
         hkv_cache_set_decode_dynamic(self.handle, mode)
+
+    def set_stamps(self, stamps, n_records: int = 0):
+        hkv_cache_set_stamps(self.handle, stamps, n_records)
 
     def set_device_tail(self, enable: bool, stream=None):
         hkv_cache_set_device_tail(self.handle, enable, stream)

@@ -470,6 +470,8 @@ struct hkv_cache {
   std::vector<uint8_t> compressed;    // [n_layers]
   std::vector<hipEvent_t> events;     // 6 per profiled decode call: start and stop of up to three kernels
   int prof_calls = 0, prof_max = 0;
+  void* stamps = nullptr;             // device buffer for per-workgroup time stamps of the tile launch (diagnosis)
+  int n_stamps = 0;
   int n_cus = 256;                    // compute units of the device the cache lives on
   int clock_khz = 2400000;            // that device's shader clock
   int device = -1;                    // device that was current when the cache was created
@@ -911,13 +913,13 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
     // head: 26.4 -> 24.6 us; with 256 chunks per head the wider workgroups only cost: 14.4 -> 15.5 us)
     const int wide = (ndi + ns <= c->n_cus && lo.max_chunks > 512) ? 1 : 0;
     e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 1,
-                             hold, lo.max_chunks, wide, st, ev[0], ev[1]);
+                             hold, lo.max_chunks, wide, c->stamps, c->n_stamps, st, ev[0], ev[1]);
   } else {
     e = launch_decode(cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
                       mode == 2 ? 1 : 0, lo.max_chunks, st, ev[0], ev[1]);
     if (e == hipSuccess && mode == 2)
       e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, 0, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
-                               0, lo.max_chunks, 0, st, ev[2], ev[3]);
+                               0, lo.max_chunks, 0, nullptr, 0, st, ev[2], ev[3]);
   }
   if (e == hipSuccess)
     e = mode == 1 ? launch_attn_merge(cv, dt, cv.static_descs + sub, nsu, lb, le, slot_base, parts, parts_ml, out,
@@ -1140,6 +1142,15 @@ int hkv_cache_decode_shape(const hkv_cache* c, int32_t* tile_rows, int32_t* dyna
   if (!c) return HKV_EINVAL;
   if (tile_rows) *tile_rows = c->lo.tile;
   if (dynamic_mode) *dynamic_mode = c->lo.mode;
+  return HKV_OK;
+}
+
+int hkv_cache_set_stamps(hkv_cache* c, uint64_t* stamps_dev, int32_t n_records) {
+  if (!c || n_records < 0 || (stamps_dev && n_records == 0)) return HKV_EINVAL;
+  if (stamps_dev && c->cfg.dtype != HKV_BF16) return HKV_ESHAPE;
+  if (reinterpret_cast<uintptr_t>(stamps_dev) & 7u) return HKV_EALIGN;
+  c->stamps = stamps_dev;
+  c->n_stamps = stamps_dev ? n_records : 0;
   return HKV_OK;
 }
 

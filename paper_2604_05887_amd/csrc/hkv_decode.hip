@@ -1142,21 +1142,39 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
 // every workgroup has a compute unit to itself, and twelve waves bring the chunk summaries in and walk the
 // tile's 32-row steps three times as fast as four -- what such a call waits for is this one chain.
 constexpr int kWideWaves = 12;
-template <typename T, int G, bool INDEXED = false, int NW = 4>
+// STAMPS: thread 0 of workgroup b < n_stamps leaves a record of HKV_STAMP_WORDS 64-bit words in stamps (values
+// of the constant 100 MHz counter): [0] start, [1] tile descriptor read, [2] chunk selection done (0 for a
+// static tile), [3] the tile's rows read and its record or output rows written (0: tile not reached at this
+// tail length), [4] first logical row of the tile, [5] 1 for a dynamic tile.  A diagnostic instantiation.
+template <typename T, int G, bool INDEXED = false, int NW = 4, bool STAMPS = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_ditems, int sitem_begin,
                           int slot_base, const T* __restrict__ q, const T* __restrict__ k_new,
                           const T* __restrict__ v_new, PartOut partials, int t_arg, int reselect, int lds_sel_off,
-                          int static_hold) {
+                          int static_hold, unsigned long long* __restrict__ stamps, int n_stamps) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
+  unsigned long long* rec = nullptr;
+  if constexpr (STAMPS) {
+    if (threadIdx.x == 0 && (int)blockIdx.x < n_stamps) {
+      rec = stamps + (size_t)blockIdx.x * HKV_STAMP_WORDS;
+      rec[0] = wall_clock64();
+      for (int i = 1; i < HKV_STAMP_WORDS; ++i) rec[i] = 0;
+    }
+  }
   if ((int)blockIdx.x >= n_ditems) {
     const AttnItem it = cv.static_items[sitem_begin + ((int)blockIdx.x - n_ditems)];
+    if constexpr (STAMPS) {
+      if (rec) { asm volatile("" ::"v"(it.row0), "v"(it.slot) : "memory"); rec[1] = wall_clock64(); rec[4] = (unsigned long long)it.row0; }
+    }
     // When the whole grid is resident at once, every block asks for its first rows at the same moment and
     // the dynamic heads' summary reads -- the head of the longest dependent chain of the launch -- queue
     // behind all of them.  The static tiles therefore start a little later: static_hold x 512 clocks,
     // the time the summaries need on the memory system (0 for grids of several rounds).
     for (int i = 0; i < static_hold; ++i) __builtin_amdgcn_s_sleep(8);
     attention_item<T, G, NW, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem);
+    if constexpr (STAMPS) {
+      if (rec) rec[3] = wall_clock64();
+    }
     return;
   }
   // Workgroups go to the eight dies in rotation (workgroup b runs on die b % 8) and each die has its own L2.
@@ -1164,6 +1182,9 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
   // contiguous runs, one per die: die x takes tiles [x * xq + min(x, xr), ...) in order.
   const int xq = n_ditems >> 3, xr = n_ditems & 7, xx = blockIdx.x & 7;
   AttnItem it = cv.dynamic_items[ditem_begin + xx * xq + min(xx, xr) + ((int)blockIdx.x >> 3)];
+  if constexpr (STAMPS) {
+    if (rec) { asm volatile("" ::"v"(it.row0), "v"(it.slot) : "memory"); rec[1] = wall_clock64(); rec[4] = (unsigned long long)it.row0; rec[5] = 1; }
+  }
   const int32_t* picks = nullptr;
   if (reselect) {
     const int t_before = t_arg >= 0 ? t_arg : cv.cnt_a[it.layer];
@@ -1184,8 +1205,14 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
     select_chunks_of_unit<T, NW * 64>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0, n_c_now, k_now);
     __syncthreads();
     picks = sel_lds;
+    if constexpr (STAMPS) {
+      if (rec) rec[2] = wall_clock64();
+    }
   }
   attention_item<T, G, NW, INDEXED>(cv, it, layer_begin, slot_base, q, k_new, v_new, partials, t_arg, cv.tile_rows, smem, picks);
+  if constexpr (STAMPS) {
+    if (rec) rec[3] = wall_clock64();
+  }
 }
 
 // One workgroup of kUnitWaves waves per unit (bf16 caches): chunk selection for a dynamic unit, then attention
@@ -1494,12 +1521,13 @@ hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dy
   return hipErrorInvalidValue;
 }
 
-template <typename T, int G, bool INDEXED = false, int NW = 4>
+template <typename T, int G, bool INDEXED = false, int NW = 4, bool STAMPS = false>
 static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, int ditem_begin, int n_ditems,
                                          int sitem_begin, int n_sitems, int slot_base, const void* q,
                                          const void* k_new, const void* v_new, float* parts_o, float* parts_ml,
                                          void* out, int t_arg, int reselect, int static_hold, int max_chunks, hipStream_t st,
-                                         hipEvent_t ev0, hipEvent_t ev1) {
+                                         hipEvent_t ev0, hipEvent_t ev1, unsigned long long* stamps = nullptr,
+                                         int n_stamps = 0) {
   const PartOut partials = {parts_o, parts_ml, nullptr, sizeof(T) == 2 ? out : nullptr};
   // reselect: selection scratch and the tile's staging area share the front; the picks sit behind both
   const size_t staging = NW == 4 ? attn_smem_bytes<T, G, true>() : (size_t)NW * G * kPartStride * sizeof(float);
@@ -1507,22 +1535,30 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
   const size_t smem = front + (reselect ? (((size_t)max_chunks + 3) & ~(size_t)3) * sizeof(int32_t) : 0);
   static std::atomic<size_t> attr{0};
   if (smem > attr.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G, INDEXED, NW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dynamic_tiles_kernel<T, G, INDEXED, NW, STAMPS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr.store(smem, std::memory_order_release);
   }
-  HKV_LAUNCH((dynamic_tiles_kernel<T, G, INDEXED, NW>), dim3(n_ditems + n_sitems), dim3(NW * 64), (uint32_t)smem, st, ev0, ev1,
+  HKV_LAUNCH((dynamic_tiles_kernel<T, G, INDEXED, NW, STAMPS>), dim3(n_ditems + n_sitems), dim3(NW * 64), (uint32_t)smem, st, ev0, ev1,
                         cv, layer_begin, ditem_begin, n_ditems, sitem_begin, slot_base, (const T*)q, (const T*)k_new,
-                        (const T*)v_new, partials, t_arg, reselect, (int)(front / sizeof(float)), static_hold);
+                        (const T*)v_new, partials, t_arg, reselect, (int)(front / sizeof(float)), static_hold, stamps, n_stamps);
   return hipGetLastError();
 }
 
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
                                 const void* v_new, float* parts_o, float* parts_ml, void* out, int t_arg, int reselect,
-                                int static_hold, int max_chunks, int wide, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+                                int static_hold, int max_chunks, int wide, void* stamps, int n_stamps, hipStream_t st,
+                                hipEvent_t ev0, hipEvent_t ev1) {
   if (n_ditems + n_sitems <= 0) return hipSuccess;
+  if (stamps && dtype == HKV_BF16 && !cv.index_gen && !wide) {      // diagnostic instantiation with time stamps
+    HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, false, 4, true>(
+                             cv, layer_begin, ditem_begin, n_ditems, sitem_begin, n_sitems, slot_base, q, k_new, v_new,
+                             parts_o, parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1,
+                             static_cast<unsigned long long*>(stamps), n_stamps)));
+    return hipErrorInvalidValue;
+  }
   if (wide && dtype == HKV_BF16 && reselect) {      // few tiles: workgroups of kWideWaves waves
     if (cv.index_gen) {
       HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, true, kWideWaves>(

@@ -128,8 +128,8 @@ hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dy
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
                                 const void* v_new, float* parts_o, float* parts_ml, void* out, int t_arg, int reselect,
-                                int static_hold, int max_chunks, int wide, hipStream_t st, hipEvent_t ev0 = nullptr,
-                                hipEvent_t ev1 = nullptr);
+                                int static_hold, int max_chunks, int wide, void* stamps, int n_stamps, hipStream_t st,
+                                hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // One wide workgroup per unit, outputs written directly (bf16 caches only; no workspace, no merge).
 hipError_t launch_units(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int static_begin,
                         int n_static, const void* q, const void* k_new, const void* v_new, void* out, int t_arg,

@@ -11,7 +11,9 @@ hipError_t launch_chunk_score_max(const CacheView&, int, int, int, int, const vo
 hipError_t launch_decode(const CacheView&, int, int, int, int, int, int, int, const void*, const void*, const void*, float*,
                          float*, void*, int, int, int, int, hipStream_t, hipEvent_t, hipEvent_t) { return never(); }
 hipError_t launch_dynamic_tiles(const CacheView&, int, int, int, int, int, int, int, const void*, const void*, const void*,
-                                float*, float*, void*, int, int, int, int, int, hipStream_t, hipEvent_t, hipEvent_t) { return never(); }
+                                float*, float*, void*, int, int, int, int, int, void*, int, hipStream_t, hipEvent_t, hipEvent_t) {
+  return never();
+}
 hipError_t launch_units(const CacheView&, int, int, int, int, int, int, const void*, const void*, const void*, void*, int, int,
                         hipStream_t, hipEvent_t, hipEvent_t) { return never(); }
 hipError_t launch_attn_merge(const CacheView&, int, const UnitDesc*, int, int, int, int, float*, float*, void*, int, int,

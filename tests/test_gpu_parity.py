@@ -372,6 +372,46 @@ def test_decode_shape_is_reported_and_auto_rule():
     dw.cache.close()
 
 
+def test_workgroup_time_stamps_of_the_tile_launch():
+    """The instrumented instantiation of the tile kernel: every workgroup leaves ordered stamps (start <=
+    descriptor <= selection <= done), dynamic tiles have a selection stamp and static ones none, tiles kept
+    for tail growth stay empty, and the outputs are bit-equal to the plain kernel's."""
+    wl = make_workload(1, n_layers=3, shrink=2, steps=2)
+    dw = runner.setup(wl, decode_dynamic=3)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    tdt = runner.torch_dtype(wl.dtype)
+    q = runner.to_device(wl.q_steps[0], wl.dtype)
+    kn, vn = runner.to_device(wl.k_new[0], wl.dtype), runner.to_device(wl.v_new[0], wl.dtype)
+    out_a = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=tdt, device="cuda:0")
+    out_b = torch.empty_like(out_a)
+    dw.cache.decode_attn(q, kn, vn, out_a)
+    torch.cuda.synchronize()
+    dw.cache.rewind()
+    n_tiles = dw.cache.call_tiling()[1]
+    stamps = torch.full((n_tiles + 3, B.HKV_STAMP_WORDS), -1, dtype=torch.int64, device="cuda:0")
+    dw.cache.set_stamps(stamps, n_tiles)
+    dw.cache.decode_attn(q, kn, vn, out_b)
+    torch.cuda.synchronize()
+    dw.cache.set_stamps(None)
+    assert torch.equal(out_a, out_b)
+    st = stamps.cpu().numpy()
+    assert np.all(st[n_tiles:] == -1)                       # nothing beyond the records asked for
+    rec = st[:n_tiles]
+    assert np.all(rec[:, 0] > 0) and np.all(rec[:, 1] >= rec[:, 0]) and np.all(rec[:, 6:] == 0)
+    reached = rec[:, 3] > 0
+    assert reached.sum() >= n_tiles // 2
+    dyn = rec[:, 5] == 1
+    assert dyn.any() and (~dyn).any()
+    assert np.all(rec[dyn & reached, 2] >= rec[dyn & reached, 1]) and np.all(rec[dyn & reached, 3] >= rec[dyn & reached, 2])
+    assert np.all(rec[~dyn, 2] == 0) and np.all(rec[~dyn & reached, 3] >= rec[~dyn & reached, 1])
+    assert np.all(rec[:, 4] % dw.cache.call_tiling()[0] == 0)       # first rows are multiples of the tile size
+    span_us = (rec[reached, 3].max() - rec[:, 0].min()) / 100.0
+    assert 1.0 < span_us < 1000.0
+    with pytest.raises(B.HkvError):
+        dw.cache.set_stamps(stamps, 0)
+    dw.cache.close()
+
+
 def test_stream_read_probe_reports_a_plausible_rate():
     buf = torch.full((512 << 20,), 5, dtype=torch.uint8, device="cuda:0")
     torch.cuda.synchronize()
