@@ -31,7 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MALL_BYTES = 256 << 20
-METRIC = "hybrid decode-attn us/step + HBM GB/s on retained KV vs full-KV, 1xMI355X"
+METRIC = "hybrid decode-attn \u00b5s/step + HBM GB/s on retained KV vs full-KV, 1\u00d7MI355X"
 
 
 def _read_traffic(name: str, steps: int, warmup: int):
