@@ -1,4 +1,6 @@
 """GPU parity: libhkv (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -288,7 +290,26 @@ def test_other_group_sizes_and_windows(n_q, n_kv, window, dtype):
         _say(f"G{n_q // n_kv} w{window} {dtype} mode {mode}", stats)
 
 
-@pytest.mark.parametrize("seed", list(range(10)))
+def _random_shape_seeds():
+    """Seeds 0..9 always; HKV_RANDOM_SHAPE_SEEDS="a-b" adds the seeds a..b-1 for a longer run."""
+    extra = os.environ.get("HKV_RANDOM_SHAPE_SEEDS", "")
+    seeds = list(range(10))
+    if extra:
+        lo, hi = (int(x) for x in extra.split("-"))
+        seeds += [s for s in range(lo, hi) if s not in seeds]
+    return seeds
+
+
+def _sep_that_fits(n_visual, n_text, block, sep, window):
+    """The drawn separator length, or 0 where the text between the blocks would not leave the window and 16
+    more tokens of some prompt outside them."""
+    for nv, nt in zip(n_visual, n_text):
+        if sep * (max(1, -(-nv // block)) - 1) > nt - window - 16:
+            return 0
+    return sep
+
+
+@pytest.mark.parametrize("seed", _random_shape_seeds())
 def test_seeded_random_shapes_in_every_decode_shape(seed):
     """Ten shapes drawn from a seeded generator: group sizes 1 to 8, windows from 4 up to the limit of
     G * w = 256, chunk sizes 8 to 128, one to three ragged sequences, prompts of 300 to 2600 tokens, budgets of
@@ -306,8 +327,9 @@ def test_seeded_random_shapes_in_every_decode_shape(seed):
     n_text = [int(rng.integers(window + 80, 420)) for _ in range(batch)]
     chunk = [int(rng.choice([8, 16, 32, 64, 128])) for _ in range(batch)]
     base = dict(W.CONFIGS[1])
-    base.update(name=f"rand{seed}_{dtype}", dtype=dtype, n_layers=int(rng.integers(1, 4)), n_q_heads=G * n_kv, n_kv_heads=n_kv,
-                batch=batch, n_visual=n_visual, n_text=n_text, block=int(rng.choice([64, 256, 700])), sep=int(rng.choice([0, 4, 16])),
+    n_layers, block, sep = int(rng.integers(1, 4)), int(rng.choice([64, 256, 700])), int(rng.choice([0, 4, 16]))
+    base.update(name=f"rand{seed}_{dtype}", dtype=dtype, n_layers=n_layers, n_q_heads=G * n_kv, n_kv_heads=n_kv,
+                batch=batch, n_visual=n_visual, n_text=n_text, block=block, sep=_sep_that_fits(n_visual, n_text, block, sep, window),
                 window=window, chunk=chunk, budget_frac=[float(rng.uniform(0.04, 0.45)) for _ in range(batch)],
                 static_frac=float(rng.choice([0.0, 0.25, 0.5, 0.75, 1.0])), steps=3,
                 q_mode=str(rng.choice(["normal", "centroid"])))
@@ -322,6 +344,43 @@ def test_seeded_random_shapes_in_every_decode_shape(seed):
         _say(f"random shape {seed}: G{G} kv{n_kv} w{window} B{batch} {dtype} chunks {chunk} mode {mode}", stats)
     stats = P.full_pipeline(wl, layer_ranges=[(l, l + 1) for l in range(wl.n_layers)])
     _say(f"random shape {seed}: a call per layer", stats)
+
+
+@pytest.mark.parametrize("seed", _random_shape_seeds())
+def test_seeded_random_shapes_across_the_variants(seed):
+    """Shapes drawn as above (bf16 only), each run with a seeded choice of the switches that change what the
+    kernels read or how they are launched: host tier for the dynamic heads, generated tokens in the chunk index,
+    the other group reading of the chunk score, causal window scoring, a tile size between 128 and 1024 rows,
+    one of the launch shapes the switches allow, and enough steps to complete chunks of generated tokens."""
+    from hkv_synth import workloads as W
+    rng = np.random.default_rng(5000 + seed)
+    n_kv = int(rng.choice([1, 2, 4]))
+    G = int(rng.integers(1, 9))
+    window = int(rng.choice([w for w in (4, 8, 16, 32, 64) if G * w <= 256]))
+    batch = int(rng.integers(1, 4))
+    n_visual = [int(rng.integers(200, 2600)) for _ in range(batch)]
+    n_text = [int(rng.integers(window + 80, 420)) for _ in range(batch)]
+    chunk = [int(rng.choice([8, 16, 32, 64])) for _ in range(batch)]
+    indexed = bool(rng.integers(0, 2))
+    base = dict(W.CONFIGS[1])
+    n_layers, block, sep = int(rng.integers(1, 4)), int(rng.choice([64, 256, 700])), int(rng.choice([0, 4, 16]))
+    base.update(name=f"randv{seed}", dtype="bf16", n_layers=n_layers, n_q_heads=G * n_kv, n_kv_heads=n_kv,
+                batch=batch, n_visual=n_visual, n_text=n_text, block=block, sep=_sep_that_fits(n_visual, n_text, block, sep, window),
+                window=window, chunk=chunk, budget_frac=[float(rng.uniform(0.04, 0.45)) for _ in range(batch)],
+                static_frac=float(rng.choice([0.0, 0.25, 0.5, 0.75])), steps=int(rng.integers(9, 20)) if indexed else 3,
+                q_mode=str(rng.choice(["normal", "centroid"])))
+    W.CONFIGS[96] = base
+    try:
+        wl = make_workload(96, seed=seed)
+    finally:
+        del W.CONFIGS[96]
+    kw = dict(host_tier=bool(rng.integers(0, 2)), index_generated=int(indexed), chunk_score_group=int(rng.integers(0, 2)),
+              causal=bool(rng.integers(0, 2)), decode_tile_rows=int(rng.choice([0, 128, 160, 288, 512, 1024])))
+    modes = [0, 1, 3, 4] if indexed else [0, 1, 2, 3, 4, 5]
+    kw["decode_dynamic"] = int(rng.choice(modes))
+    per_layer = bool(rng.integers(0, 2))
+    stats = P.full_pipeline(wl, layer_ranges=[(l, l + 1) for l in range(wl.n_layers)] if per_layer else None, **kw)
+    _say(f"random variant {seed}: G{G} kv{n_kv} w{window} B{batch} chunks {chunk} per_layer={per_layer} {kw}", stats)
 
 
 @pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 3, 160), (1, 2, 288), (1, 1, 416), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
@@ -601,6 +660,41 @@ def test_head_scores_with_runs_of_equal_logits():
         assert err <= SCORE_ATOL
         k_top = O.focus_count(C, rho)
         assert abs(want[0, 0, 0] - k_top / C) < 1e-12           # all keys equal: every probability is 1/C
+
+
+@pytest.mark.parametrize("seed", _random_shape_seeds())
+def test_head_scores_on_seeded_random_shapes(seed):
+    """Group sizes 1 to 8, one to three ragged prompts of 300 to 4500 tokens with 40 to 400 text tokens, focus
+    fractions from 0.005 to 0.4 (both sides of the switch between the scanning and the materialising form),
+    with and without the causal option, bf16 and fp32, full and smallest workspace."""
+    from hkv_synth import make_prompt_queries
+    from hkv_synth import workloads as W
+    rng = np.random.default_rng(9000 + seed)
+    n_kv, G, batch = int(rng.choice([1, 2, 4])), int(rng.integers(1, 9)), int(rng.integers(1, 4))
+    dtype = "f32" if seed % 4 == 3 else "bf16"
+    n_visual = [int(rng.integers(260, 4100)) for _ in range(batch)]
+    n_text = [int(rng.integers(40, 400)) for _ in range(batch)]
+    block = int(rng.choice([256, 700, 5000]))
+    base = dict(W.CONFIGS[1])
+    base.update(name=f"randh{seed}_{dtype}", dtype=dtype, n_layers=int(rng.integers(1, 3)), n_q_heads=G * n_kv, n_kv_heads=n_kv,
+                batch=batch, n_visual=n_visual, n_text=n_text, block=block, sep=0, window=int(rng.choice([8, 16, 32])),
+                chunk=[8] * batch, budget_frac=[0.3] * batch, steps=1)
+    W.CONFIGS[94] = base
+    try:
+        wl = make_workload(94, seed=seed)
+    finally:
+        del W.CONFIGS[94]
+    qp = make_prompt_queries(wl)
+    rho, causal = float(rng.choice([0.005, 0.02, 0.05, 0.055, 0.08, 0.2, 0.4])), bool(rng.integers(0, 2))
+    small = bool(rng.integers(0, 2))
+    ocfg = O.OracleConfig(n_layers=wl.n_layers, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=128,
+                          window=wl.window, dtype=wl.dtype, score_causal=causal)
+    got = _device_head_scores(wl, qp, causal=causal, rho=rho, small_workspace=small)
+    want = O.head_scores(ocfg, wl.cu_seqlens, qp, wl.k, wl.is_visual, rho=rho)
+    err = np.abs(got - want).max()
+    print(f"\n[head scores, random shape {seed}: G{G} kv{n_kv} {dtype} C={list(map(int, wl.seqlens))} T={n_text} rho={rho} "
+          f"causal={causal} small_ws={small}] max abs err {err:.2e}", flush=True)
+    assert err <= SCORE_ATOL
 
 
 @pytest.mark.parametrize("n_visual,rho", [(9800, 0.05), (19900, 0.05), (40000, 0.05), (9800, 0.1), (19900, 0.1), (40000, 0.1),
