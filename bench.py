@@ -19,6 +19,7 @@ effect).  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import os
 import statistics
@@ -38,19 +39,20 @@ def _read_traffic(name: str, steps: int, warmup: int):
     """Measured HBM traffic per launch of the dominant kernel (bytes) from the committed counter summary
     of this workload -- only if that summary was taken with the same step and warm-up counts (the tail
     length, and with it the bytes of a launch, depends on them); else None."""
-    path = os.path.join(ROOT, "profiles", name)
-    vals = {}
-    try:
-        with open(path) as f:
-            for line in f:
-                for key in ("traffic_bytes_per_launch", "bench_steps", "bench_warmup"):
-                    if line.startswith(key):
-                        vals[key] = float(line.split("=")[1].split()[0])
-    except OSError:
-        return None
-    if vals.get("bench_steps") != steps or vals.get("bench_warmup") != warmup:
-        return None
-    return vals.get("traffic_bytes_per_launch")
+    stem = os.path.join(ROOT, "profiles", name[:-len(".txt")])
+    for path in sorted(glob.glob(stem + "*.txt")):          # one summary per (steps, warm-up) pair measured
+        vals = {}
+        try:
+            with open(path) as f:
+                for line in f:
+                    for key in ("traffic_bytes_per_launch", "bench_steps", "bench_warmup"):
+                        if line.startswith(key):
+                            vals[key] = float(line.split("=")[1].split()[0])
+        except OSError:
+            continue
+        if vals.get("bench_steps") == steps and vals.get("bench_warmup") == warmup:
+            return vals.get("traffic_bytes_per_launch")
+    return None
 
 
 def _log(msg: str) -> None:
