@@ -11,14 +11,15 @@ order and notation of the paper:
 
   * window_scores      Appendix A, the two equations for S_w and s_w
                        (observation-window softmax attention, averaged rows)
-  * static_keep_set    Appendix A, "three distinct sets of tokens": window,
-                       historical text, Top-M historical visual tokens
-  * chunk_means        Appendix A, "metadata computed as the average of its
-                       key vectors"
-  * chunk_scores       Appendix A, "inner product between the query vector and
-                       chunk metadata"
-  * select_chunks      Appendix A, "number of loaded chunks is determined by
-                       the per-head budget and chunk size"
+  * static_keep_set    Appendix A, static heads: the retained set is the union
+                       of the window, the historical text and the Top-M
+                       historical visual tokens
+  * chunk_means        Appendix A, dynamic heads: a chunk's summary is the mean
+                       of its key vectors
+  * chunk_scores       Appendix A, dynamic heads: a chunk is scored by the dot
+                       product of the query with its summary
+  * select_chunks      Appendix A, dynamic heads: how many chunks are loaded
+                       follows from the head's budget and the chunk size
   * attention          ordinary softmax attention over the retained rows
                        (Section 3.3: static and dynamic parts share one buffer
                        and are attended together)
