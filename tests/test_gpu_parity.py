@@ -300,6 +300,11 @@ def _random_shape_seeds():
     return seeds
 
 
+def _random_shape_scale():
+    """HKV_RANDOM_SHAPE_SCALE=n multiplies the drawn visual-token counts (longer prompts: more tiles, longer shares)."""
+    return max(1, int(os.environ.get("HKV_RANDOM_SHAPE_SCALE", "1")))
+
+
 def _sep_that_fits(n_visual, n_text, block, sep, window):
     """The drawn separator length, or 0 where the text between the blocks would not leave the window and 16
     more tokens of some prompt outside them."""
@@ -323,7 +328,7 @@ def test_seeded_random_shapes_in_every_decode_shape(seed):
     window = int(rng.choice([w for w in (4, 8, 12, 16, 24, 32, 48, 64, 128) if G * w <= 256]))
     batch = int(rng.integers(1, 4))
     dtype = "f32" if seed % 5 == 4 else "bf16"
-    n_visual = [int(rng.integers(200, 2200)) for _ in range(batch)]
+    n_visual = [int(rng.integers(200, 2200)) * _random_shape_scale() for _ in range(batch)]
     n_text = [int(rng.integers(window + 80, 420)) for _ in range(batch)]
     chunk = [int(rng.choice([8, 16, 32, 64, 128])) for _ in range(batch)]
     base = dict(W.CONFIGS[1])
@@ -358,7 +363,7 @@ def test_seeded_random_shapes_across_the_variants(seed):
     G = int(rng.integers(1, 9))
     window = int(rng.choice([w for w in (4, 8, 16, 32, 64) if G * w <= 256]))
     batch = int(rng.integers(1, 4))
-    n_visual = [int(rng.integers(200, 2600)) for _ in range(batch)]
+    n_visual = [int(rng.integers(200, 2600)) * _random_shape_scale() for _ in range(batch)]
     n_text = [int(rng.integers(window + 80, 420)) for _ in range(batch)]
     chunk = [int(rng.choice([8, 16, 32, 64])) for _ in range(batch)]
     indexed = bool(rng.integers(0, 2))
