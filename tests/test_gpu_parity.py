@@ -19,6 +19,21 @@ def _say(name, stats):
     print(f"\n[{name}] " + " ".join(f"{k}={v:.3g}" for k, v in sorted(stats.items())), flush=True)
 
 
+def _random_shape_seeds():
+    """Seeds 0..9 always; HKV_RANDOM_SHAPE_SEEDS="a-b" adds the seeds a..b-1 for a longer run."""
+    extra = os.environ.get("HKV_RANDOM_SHAPE_SEEDS", "")
+    seeds = list(range(10))
+    if extra:
+        lo, hi = (int(x) for x in extra.split("-"))
+        seeds += [s for s in range(lo, hi) if s not in seeds]
+    return seeds
+
+
+def _random_shape_scale():
+    """HKV_RANDOM_SHAPE_SCALE=n multiplies the drawn visual-token counts (longer prompts: more tiles, longer shares)."""
+    return max(1, int(os.environ.get("HKV_RANDOM_SHAPE_SCALE", "1")))
+
+
 def test_cfg0_fp32_end_to_end():
     """Config 0 at full size: compress + 16 decode steps, every unit, every step."""
     wl = make_workload(0)
@@ -150,6 +165,37 @@ def test_full_kv_kernel_ragged_batch_bf16():
     g = runner.to_host_f32(out).astype(np.float64)
     err = np.abs(g - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
     assert err.max() <= 2e-2, err.max()
+
+
+@pytest.mark.parametrize("seed", _random_shape_seeds())
+def test_full_kv_kernel_on_seeded_random_shapes(seed):
+    """The comparison kernel against textbook attention: group sizes 1 to 8, one to four ragged sequences of 1 to
+    ~6000 rows (single rows, lengths around the tile size and its multiples included), one to three layers, bf16
+    and fp32."""
+    rng = np.random.default_rng(7000 + seed)
+    n_kv, G, batch, L = int(rng.choice([1, 2, 4])), int(rng.integers(1, 9)), int(rng.integers(1, 5)), int(rng.integers(1, 4))
+    dtype = "f32" if seed % 3 == 2 else "bf16"
+    special = [1, 2, 7, 8, 9, 31, 32, 33, 127, 128, 129, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 2048, 4096]
+    lens = [int(rng.choice(special)) if rng.integers(0, 2) else int(rng.integers(1, 6000)) for _ in range(batch)]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n_q = n_kv * G
+    from hkv_synth.workloads import bf16_round
+    to_dtype = bf16_round if dtype == "bf16" else (lambda x: x.astype(np.float32))
+    q, k, v = (to_dtype(rng.standard_normal(shape)) for shape in
+               ((L, batch, n_q, 128), (L, int(cu[-1]), n_kv, 128), (L, int(cu[-1]), n_kv, 128)))
+    cfg = B.make_config(n_layers=L, n_q_heads=n_q, n_kv_heads=n_kv, dtype=runner.hkv_dtype(dtype), window=1, chunk_size=32)
+    qd, kd, vd = (runner.to_device(x, dtype) for x in (q, k, v))
+    ws_bytes = B.hkv_full_workspace_size(cfg, cu, L)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty_like(qd)
+    B.hkv_full_decode_attn(cfg, cu, L, qd, kd, vd, out, ws, ws_bytes)
+    torch.cuda.synchronize()
+    ocfg = O.OracleConfig(n_layers=L, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=128, window=1, dtype=dtype)
+    ref = O.full_decode_attn(ocfg, cu, q.astype(np.float64), k.astype(np.float64), v.astype(np.float64))
+    g = runner.to_host_f32(out).astype(np.float64)
+    err = (np.abs(g - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max()
+    print(f"\n[full KV, random shape {seed}: G{G} kv{n_kv} L{L} {dtype} rows {lens}] max rel err {err:.2e}", flush=True)
+    assert err <= (2e-2 if dtype == "bf16" else 1e-5)
 
 
 def test_selection_stage_with_planted_ties():
@@ -288,21 +334,6 @@ def test_other_group_sizes_and_windows(n_q, n_kv, window, dtype):
     for mode in (1, 3, 4) if dtype == "bf16" else (1, 2, 3):
         stats = P.full_pipeline(wl, decode_dynamic=mode)
         _say(f"G{n_q // n_kv} w{window} {dtype} mode {mode}", stats)
-
-
-def _random_shape_seeds():
-    """Seeds 0..9 always; HKV_RANDOM_SHAPE_SEEDS="a-b" adds the seeds a..b-1 for a longer run."""
-    extra = os.environ.get("HKV_RANDOM_SHAPE_SEEDS", "")
-    seeds = list(range(10))
-    if extra:
-        lo, hi = (int(x) for x in extra.split("-"))
-        seeds += [s for s in range(lo, hi) if s not in seeds]
-    return seeds
-
-
-def _random_shape_scale():
-    """HKV_RANDOM_SHAPE_SCALE=n multiplies the drawn visual-token counts (longer prompts: more tiles, longer shares)."""
-    return max(1, int(os.environ.get("HKV_RANDOM_SHAPE_SCALE", "1")))
 
 
 def _sep_that_fits(n_visual, n_text, block, sep, window):
