@@ -922,6 +922,46 @@ def test_cumulative_focus_counts_match_the_oracle(cfg_id, n_steps, frac):
         assert np.all(F == n_steps)
 
 
+@pytest.mark.parametrize("seed", _random_shape_seeds())
+def test_focus_counts_on_seeded_random_shapes(seed):
+    """Group sizes 1 to 8, 1 to 40 decoding steps, contexts of 40 to 9000 tokens, focus fractions from one token to
+    everything, bf16 and fp32, full and smallest workspace: the counts lie inside the tie band around the oracle's
+    and add up to steps x k."""
+    from hkv_synth.workloads import bf16_round
+    rng = np.random.default_rng(11000 + seed)
+    n_kv, G, n_steps = int(rng.choice([1, 2, 4])), int(rng.integers(1, 9)), int(rng.integers(1, 41))
+    C = int(rng.choice([40, 63, 64, 65, 255, 256, 257, 1000, 2048])) if rng.integers(0, 2) else int(rng.integers(40, 9000))
+    frac = float(rng.choice([1e-6, 0.01, 0.05, 0.05, 0.3, 1.0]))
+    dtype = "f32" if seed % 3 == 1 else "bf16"
+    n_q = G * n_kv
+    to_dtype = bf16_round if dtype == "bf16" else (lambda x: x.astype(np.float32))
+    q_host, k_host = to_dtype(rng.standard_normal((n_steps, n_q, 128))), to_dtype(rng.standard_normal((C, n_kv, 128)))
+    cfg = B.make_config(n_layers=1, n_q_heads=n_q, n_kv_heads=n_kv, dtype=runner.hkv_dtype(dtype), window=1)
+    q_dev, k_dev = runner.to_device(q_host, dtype), runner.to_device(k_host, dtype)
+    lo_b, hi_b = B.hkv_focus_counts_workspace_size(cfg, n_steps, C)
+    nbytes = lo_b if rng.integers(0, 2) else hi_b
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    counts = torch.full((n_q, C), -7, dtype=torch.int32, device="cuda:0")
+    B.hkv_focus_counts(cfg, n_steps, C, q_dev, k_dev, frac, counts, ws, nbytes)
+    torch.cuda.synchronize()
+    F = counts.cpu().numpy().astype(np.int64)
+    k_top = O.focus_count(C, frac)
+    assert np.all(F.sum(axis=1) == n_steps * k_top) and F.min() >= 0 and F.max() <= n_steps
+    scale = 1.0 / np.sqrt(128.0)
+    exact = 0
+    for hq in range(n_q):
+        qd, kd = q_host[:, hq].astype(np.float64), k_host[:, hq // G].astype(np.float64)
+        ref = O.cumulative_focus(qd, kd, scale, k_top)
+        lo, hi = _focus_bounds(qd, kd, scale, k_top, 1e-5)
+        assert np.all(lo <= F[hq]) and np.all(F[hq] <= hi), f"head {hq}: counts outside the tie band"
+        exact += int(np.array_equal(F[hq], ref))
+    print(f"\n[focus, random shape {seed}: G{G} kv{n_kv} {dtype} C={C} k={k_top} steps={n_steps}] {exact}/{n_q} heads bit-equal",
+          flush=True)
+    # a head differs from the oracle only where two logits at the cut lie closer than fp32 resolves: about
+    # 2e-7 * C of the (head, step) pairs for Gaussian logits
+    assert exact >= n_q - 2 - int(4 * 2e-7 * C * n_q * n_steps)
+
+
 def test_focus_counts_argument_checks():
     cfg = B.make_config(n_layers=1, n_q_heads=28, n_kv_heads=4, dtype=B.HKV_BF16, window=32)
     t = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
