@@ -230,24 +230,36 @@ class Bench:
         return us
 
     # ---- per-workgroup time stamps of the tile launch (diagnosis; launch shape 3 only) ---------------------
-    def workgroup_stamps(self, n_steps=12):
+    def workgroup_stamps(self, n_steps=12, layer=None):
         """Runs n_steps more steps with the instrumented tile kernel and summarises the last one: when the
         workgroups of the main launch start, read their descriptor, finish the chunk selection and finish
-        their rows, for static and dynamic tiles (microseconds from the first workgroup's start)."""
+        their rows, for static and dynamic tiles (microseconds from the first workgroup's start).  With
+        `layer`, the steps are calls over that layer alone (the launch a model's layer sees)."""
         import numpy as np
         torch, B = self.torch, self.B
         dw = self.copies[0]
-        if dw.cache.decode_shape()[1] != 3:
+        if layer is None and dw.cache.decode_shape()[1] != 3:
             return None
-        n_tiles = dw.cache.call_tiling()[1]
+        lb, le = (0, self.wl.n_layers) if layer is None else (layer, layer + 1)
+        n_tiles = dw.cache.call_tiling(lb, le)[1]
         stamps = torch.zeros((n_tiles, B.HKV_STAMP_WORDS), dtype=torch.int64, device=self.dev)
         dw.cache.set_stamps(stamps, n_tiles)
         for i in range(n_steps):
-            self.raw_step(dw, i)
+            if layer is None:
+                self.raw_step(dw, i)
+            else:
+                j = i % self.n_inputs
+                st = self.lib.hkv_decode_attn(dw.cache.handle, lb, le, self.q_all[j, lb].data_ptr(), None, None,
+                                              self.out[lb].data_ptr(), dw.cache.workspace.data_ptr(),
+                                              dw.cache.workspace_bytes, self.sptr)       # nothing appended: the tails stay
+                if st != 0:
+                    raise B.HkvError(st, "hkv_decode_attn")
         torch.cuda.synchronize()
         dw.cache.set_stamps(None)
         rec = stamps.cpu().numpy()
         rec = rec[rec[:, 3] > 0]
+        if len(rec) == 0:               # the call did not run as tiles
+            return None
         t0 = rec[:, 0].min()
         us = lambda x: (x - t0) / 100.0
 
@@ -497,6 +509,8 @@ def main() -> int:
     ap.add_argument("--stamps", action="store_true",
                     help="also run the instrumented tile kernel and report per-workgroup time stamps "
                          "(workloads whose main launch is the single launch of split-K tiles)")
+    ap.add_argument("--stamps-layer", type=int, default=-1,
+                    help="with --stamps: stamp a call over this layer alone instead of the whole-model call")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read reference")
     ap.add_argument("--no-layerwise", action="store_true", help="skip the one-call-per-layer timing")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -601,7 +615,7 @@ def main() -> int:
     call_tile_rows, call_tiles = hb.copies[0].cache.call_tiling()            # of the timed call over all layers
     layer_tile_rows, layer_tiles = hb.copies[0].cache.call_tiling(0, 1)      # of a call over one layer
     probe_us = None if args.no_probe else hb.probe_read(a_bytes)
-    wg_stamps = hb.workgroup_stamps() if args.stamps else None
+    wg_stamps = hb.workgroup_stamps(layer=args.stamps_layer if args.stamps_layer >= 0 else None) if args.stamps else None
     lw_us = lw_graph_us = None
     if L > 1 and not args.no_layerwise:
         lw_us, lw_graph_us = hb.layerwise()

@@ -121,7 +121,10 @@ typedef struct {
                                resident workgroup a share of at least 2048 rows (a call over one layer of such a
                                cache then streams only if its shares reach that length too, else it runs as 3;
                                an explicit 5 streams both); else 3 unless the repeated
-                               summary reads would exceed a quarter of a step's bytes, then 2
+                               summary reads would exceed a quarter of a step's bytes, then 2.
+                               Under 0, a call that runs as 3 with all its tiles resident at once on a cache
+                               with more than 512 chunks per head computes the chunk scores in a small launch
+                               of its own ahead of the tiles, which then only pick (same scores, same picks)
                                (tuning knob, same results up to fp32 summation order) */
   int32_t chunk_score_group;/* how the query heads that share a KV head score a chunk (Appendix A gives one
                                query vector per head and does not treat grouped heads): 0 = the inner
@@ -333,7 +336,8 @@ HKV_API int hkv_cache_set_stamps(hkv_cache* cache, uint64_t* stamps_dev, int32_t
  * the summed durations in milliseconds -- ms[0] main launch (chunk scoring and chunk top-k of the
  * dynamic heads together with the split-K attention of the static heads; in dynamic modes 1, 3 and 5
  * also the dynamic heads' attention; in mode 4 the whole step), ms[1] second launch (split-K
- * attention of the dynamic heads, dynamic mode 2 only), ms[2] combination of the split-K tiles (none
+ * attention of the dynamic heads in dynamic mode 2; the chunk scores' own launch where the automatic rule
+ * puts one ahead of the tiles), ms[2] combination of the split-K tiles (none
  * in mode 4) -- and the number of calls summed,
  * then starts over.
  * hkv_profile_disable releases the events. */

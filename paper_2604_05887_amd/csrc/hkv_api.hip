@@ -314,15 +314,19 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 // the reference length t_ref) into n_wg shares of equal size; see stream_kernel.  n_wg = as many as the
 // device keeps resident (three workgroups on each compute unit), fewer when a share would drop below
 // kStreamMinSteps steps.
+constexpr int kDeviceCus = 256;          // compute units of the device this library is written for (MI355X)
 constexpr int kStreamMinSteps = 8;
+constexpr int kStreamLayerMinSteps = 8;   // the same for the shares of a call over one layer
 constexpr int kStreamMaxWg = 3 * 256;
+constexpr int kPreScoreChunks = 512;      // chunks per head from which a one-round call scores them in a launch of its own
 constexpr int kStreamAutoRows = 2048;     // the automatic rule streams when every workgroup's share is at least this long
 // A dynamic unit costs more than its rows: whoever touches it reads its chunk summaries (one 32-row step
 // of K and V is 16 KB) and waits for the selection's dependent chain (about the time of kSelLatencySteps
 // steps of a streaming workgroup).  That cost sits at the front of the unit on the line of work; a
 // boundary that falls inside it becomes the unit's row 0.
 constexpr int kSelLatencySteps = 3;
-void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref, StreamTable& tb, std::vector<char>& blob) {
+void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref, int min_steps, StreamTable& tb,
+                        std::vector<char>& blob) {
   std::vector<int64_t> start(n_units + 1, 0), lead(n_units, 0);     // first step of every unit; its selection cost
   std::vector<int32_t> ref_rows(n_units, 0);
   for (int i = 0; i < n_units; ++i) {
@@ -332,7 +336,9 @@ void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref
     start[i + 1] = start[i] + lead[i] + ((int64_t)ref_rows[i] + 31) / 32;
   }
   const int64_t S = start[n_units];
-  const int n_wg = (int)std::max<int64_t>(1, std::min<int64_t>(kStreamMaxWg, S / kStreamMinSteps));
+  int64_t n_fit = S / min_steps;
+  if (min_steps != kStreamMinSteps && n_fit > kDeviceCus) n_fit = n_fit / kDeviceCus * kDeviceCus;   // whole rounds of the compute units
+  const int n_wg = (int)std::max<int64_t>(1, std::min<int64_t>(kStreamMaxWg, n_fit));
   std::vector<StreamBound> bounds(n_wg + 1);
   int u = 0;
   for (int j = 0; j <= n_wg; ++j) {
@@ -381,7 +387,8 @@ void build_stream_shapes(const hkv_config* cfg, int batch, Layout& lo) {
     sh.n_units = s == 0 ? L * upl : upl;
     sh.tables.resize(rungs.size());
     for (size_t r = 0; r < rungs.size(); ++r) {
-      build_stream_table(lo, sh.unit_begin, sh.n_units, rungs[r], sh.tables[r], lo.stream_blob);
+      build_stream_table(lo, sh.unit_begin, sh.n_units, rungs[r], s == 0 ? kStreamMinSteps : kStreamLayerMinSteps,
+                         sh.tables[r], lo.stream_blob);
       lo.stream_slots_max = std::max<int64_t>(lo.stream_slots_max, (int64_t)sh.tables[r].n_wg + sh.n_units);
     }
   }
@@ -397,7 +404,6 @@ void build_stream_shapes(const hkv_config* cfg, int batch, Layout& lo) {
 // capacity included; bf16 caches) are not split at all: measured on the 7B shape, one wide workgroup per
 // head is ahead of the split-K shapes up to about that length and behind them beyond.
 constexpr int kUnitShapeMaxRows = 768;
-constexpr int kDeviceCus = 256;          // compute units of the device this library is written for (MI355X)
 int plan_layout(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, bool tiered = false) {
   int rc;
   if (cfg && cfg->dtype != HKV_BF16) rc = plan_layout_tile(cfg, plan, lo, kTileF32, tiered);
@@ -897,6 +903,7 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
     if (k_new && !c->device_tail) for (int l = lb; l < le; ++l) c->host_tail[l] += 1;
     return HKV_OK;
   }
+  bool pre_scored = false;
   if (mode == 3) {
     // a grid that is resident in one round: the static tiles wait for the time the dynamic tiles' summary
     // reads take at kSummaryRate (what a launch's first reads were measured to draw while every workgroup
@@ -907,19 +914,29 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
       const double seconds = (double)(lo.dmu_begin[le] - lo.dmu_begin[lb]) / kSummaryRate;
       hold = (int)std::min<int64_t>(16, (int64_t)(seconds * c->clock_khz * 1e3 / 512.0));
     }
-    // a call with no more tiles than compute units, on a cache whose heads have many chunks, runs them in wide
-    // workgroups: what such a call waits for is a dynamic tile's selection, and twelve waves read the chunk
-    // summaries in one round where four take three (a call per layer of the 72B video shape, 800 chunks per
-    // head: 26.4 -> 24.6 us; with 256 chunks per head the wider workgroups only cost: 14.4 -> 15.5 us)
-    const int wide = (ndi + ns <= c->n_cus && lo.max_chunks > 512) ? 1 : 0;
-    e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 1,
-                             hold, lo.max_chunks, wide, c->stamps, c->n_stamps, st, ev[0], ev[1]);
+    // A grid of one round on a cache whose heads have many chunks would end with a dynamic tile whose four waves
+    // bring in all summaries of its head before its rows (12-35 us of a 49 us launch for a call per layer of the
+    // serving mix, up to 1218 chunks per head).  Under the automatic rule the scores then come from a launch of
+    // their own, spread over the compute units, and the tiles only pick: a call per layer of the serving mix
+    // 55.8 -> 45.6 us, of the 72B video shape 24.6 -> 23.9; at 512 chunks per head (32k shape) it costs
+    // 21.5 -> 21.9, at 256 (8k shape) 14.4 -> 17.1, hence the threshold.
+    const bool pre_score = c->lo.mode_by_rule && ndi > 0 && ndi + ns <= resident && lo.max_chunks > kPreScoreChunks &&
+                           !c->cfg.chunk_score_group && !c->cfg.index_generated;
+    CacheView cvs = cv;
+    if (pre_score) {
+      e = launch_chunk_score_sum(cv, dt, lb, db, nd, lo.max_chunks, q, st, ev[2], ev[3]);
+      if (e != hipSuccess) return HKV_EHIP;
+      cvs.sigma_max = 1;              // the tiles read the stored scores
+      pre_scored = true;
+    }
+    e = launch_dynamic_tiles(cvs, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 1,
+                             pre_score ? 0 : hold, lo.max_chunks, c->stamps, c->n_stamps, st, ev[0], ev[1]);
   } else {
     e = launch_decode(cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
                       mode == 2 ? 1 : 0, lo.max_chunks, st, ev[0], ev[1]);
     if (e == hipSuccess && mode == 2)
       e = launch_dynamic_tiles(cv, dt, lb, dib, ndi, sb, 0, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
-                               0, lo.max_chunks, 0, nullptr, 0, st, ev[2], ev[3]);
+                               0, lo.max_chunks, nullptr, 0, st, ev[2], ev[3]);
   }
   if (e == hipSuccess)
     e = mode == 1 ? launch_attn_merge(cv, dt, cv.static_descs + sub, nsu, lb, le, slot_base, parts, parts_ml, out,
@@ -928,7 +945,7 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
                                       app, st, ev[4], ev[5]);
   if (e != hipSuccess) return HKV_EHIP;
   if (prof) {
-    c->prof_mask[c->prof_calls] = (uint8_t)(1 | ((mode == 2 && ndi > 0) ? 2 : 0) | ((mode == 1 ? nsu : nu) > 0 ? 4 : 0));
+    c->prof_mask[c->prof_calls] = (uint8_t)(1 | (((mode == 2 && ndi > 0) || pre_scored) ? 2 : 0) | ((mode == 1 ? nsu : nu) > 0 ? 4 : 0));
     c->prof_calls += 1;
     c->prof_stream = st;
   }

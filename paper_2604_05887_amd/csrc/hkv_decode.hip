@@ -746,6 +746,58 @@ __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n
   }
 }
 
+// Scores of the chunks [ch_begin, ch_end) of one dynamic unit that has n_c chunks: the inner product of the
+// group-summed query (summed in head order) with every chunk summary; whole block (NT threads).  sig (shared
+// memory, indexed by chunk; may be null) and, with to_memory, the unit's score array take the results.  One
+// routine for the step's kernels and for the launch that scores ahead of them, so that both give the same bits.
+template <typename T, int NT>
+__device__ __forceinline__ void score_chunk_range(const CacheView& cv, const UnitDesc& d, int lrel, const T* __restrict__ q,
+                                                  int ch_begin, int ch_end, int n_c, float* sig, bool to_memory) {
+  constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = NT / LPR;
+  const int tid = thread_index();
+  const int sub = tid % LPR, slot = tid / LPR;
+  float qf[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) qf[e] = 0.f;
+  const char* qb = reinterpret_cast<const char*>(q) +
+                   (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * cv.G) * kD * sizeof(T) + sub * 16;
+  const char* mu = reinterpret_cast<const char*>(cv.mu) + (size_t)d.aux_off * kD * sizeof(T) + sub * 16;
+  uint4 qraw[kMaxG];
+#pragma unroll
+  for (int g = 0; g < kMaxG; ++g) qraw[g] = g < cv.G ? ld16(qb + (size_t)g * kD * sizeof(T)) : make_uint4(0, 0, 0, 0);
+  for (int ch0 = ch_begin; ch0 < ch_end; ch0 += RP * 16) {      // uniform trip count; sixteen independent loads per round
+    uint4 raw[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int ch = ch0 + j * RP + slot;
+      raw[j] = ld16(mu + (size_t)min(ch, n_c - 1) * kD * sizeof(T));
+    }
+    if (ch0 == ch_begin) {
+#pragma unroll
+      for (int g = 0; g < kMaxG; ++g) {
+        float t[EPL];
+        unpack16(qraw[g], t, T{});
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qf[e] += t[e];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int ch = ch0 + j * RP + slot;
+      float mf[EPL];
+      unpack16(raw[j], mf, T{});
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) dot = fmaf(qf[e], mf[e], dot);
+      dot = sum_lanes<LPR>(dot);
+      if (ch < ch_end && sub == 0) {
+        if (sig) sig[ch] = dot;
+        if (to_memory) cv.sigma[d.aux_off + ch] = dot;
+      }
+    }
+  }
+}
+
 // Chunk scoring and chunk top-k of one dynamic unit; whole block (NT threads).
 constexpr int kSelHeader = 256 + 16;       // words before the chunk scores: histogram, 2 broadcast words, scan area
 template <typename T, int NT = 256>
@@ -766,45 +818,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
   unsigned long long* key64 = reinterpret_cast<unsigned long long*>(sig + n_c4);   // [n_c4], 8-byte aligned
 
   if (!use_stored_sigma) {
-    // group-summed query for this lane's 16-byte slice, summed in head order
-    const int sub = tid % LPR, slot = tid / LPR;
-    float qf[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) qf[e] = 0.f;
-    const char* qb = reinterpret_cast<const char*>(q) +
-                     (((size_t)lrel * cv.batch + d.seq) * cv.n_q_heads + (size_t)d.head * cv.G) * kD * sizeof(T) + sub * 16;
-    const char* mu = reinterpret_cast<const char*>(cv.mu) + (size_t)d.aux_off * kD * sizeof(T) + sub * 16;
-    uint4 qraw[kMaxG];
-#pragma unroll
-    for (int g = 0; g < kMaxG; ++g) qraw[g] = g < cv.G ? ld16(qb + (size_t)g * kD * sizeof(T)) : make_uint4(0, 0, 0, 0);
-    for (int ch0 = 0; ch0 < n_c; ch0 += RP * 16) {      // uniform trip count; sixteen independent loads per round
-      uint4 raw[16];
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int ch = ch0 + j * RP + slot;
-        raw[j] = ld16(mu + (size_t)min(ch, n_c - 1) * kD * sizeof(T));
-      }
-      if (ch0 == 0) {
-#pragma unroll
-        for (int g = 0; g < kMaxG; ++g) {
-          float t[EPL];
-          unpack16(qraw[g], t, T{});
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) qf[e] += t[e];
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int ch = ch0 + j * RP + slot;
-        float mf[EPL];
-        unpack16(raw[j], mf, T{});
-        float dot = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) dot = fmaf(qf[e], mf[e], dot);
-        dot = sum_lanes<LPR>(dot);
-        if (ch < n_c && sub == 0) { sig[ch] = dot; if (to_memory) cv.sigma[d.aux_off + ch] = dot; }
-      }
-    }
+    score_chunk_range<T, NT>(cv, d, lrel, q, 0, n_c, n_c, sig, to_memory);
   } else {
     for (int ch = tid; ch < n_c; ch += NT) sig[ch] = cv.sigma[d.aux_off + ch];
   }
@@ -1081,6 +1095,21 @@ __global__ __launch_bounds__(256) void chunk_score_max_kernel(CacheView cv, int 
   }
 }
 
+// Chunk scores under the default reading in a launch of their own, ahead of the step's kernels, which then
+// pick from the stored scores: for calls in which a dynamic tile's chunk selection is the longest chain of
+// the launch -- one workgroup bringing in all summaries of its head -- the summaries go through many compute
+// units instead.  grid = (dynamic units of the call, blocks of 256 chunks), block = 256 threads; same
+// arithmetic as inside the step's kernels (score_chunk_range), so the scores and the picks are the same bits.
+template <typename T>
+__global__ __launch_bounds__(256) void chunk_score_sum_kernel(CacheView cv, int layer_begin, int dyn_begin,
+                                                              const T* __restrict__ q) {
+  const UnitDesc d = cv.dyn_descs[dyn_begin + blockIdx.x];
+  const int ch_begin = (int)blockIdx.y * 256;
+  if (ch_begin >= d.n_chunks) return;
+  score_chunk_range<T, 256>(cv, d, d.layer - layer_begin, q, ch_begin, min(d.n_chunks, ch_begin + 256), d.n_chunks,
+                            nullptr, true);
+}
+
 // INDEXED: the cache indexes its generated tokens (bf16 caches; see attention_item).
 template <typename T, int G, bool INDEXED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
@@ -1138,10 +1167,7 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
 // boundary is needed; all blocks of a unit compute and store identical picks.  In that shape the grid
 // also carries the static tiles: blocks [n_ditems, n_ditems + n_sitems), which wait static_hold x 512
 // clocks before their first loads.
-// NW: waves per workgroup (bf16 caches).  Calls with no more tiles than compute units run with kWideWaves:
-// every workgroup has a compute unit to itself, and twelve waves bring the chunk summaries in and walk the
-// tile's 32-row steps three times as fast as four -- what such a call waits for is this one chain.
-constexpr int kWideWaves = 12;
+// NW: waves per workgroup.
 // STAMPS: thread 0 of workgroup b < n_stamps leaves a record of HKV_STAMP_WORDS 64-bit words in stamps (values
 // of the constant 100 MHz counter): [0] start, [1] tile descriptor read, [2] chunk selection done (0 for a
 // static tile), [3] the tile's rows read and its record or output rows written (0: tile not reached at this
@@ -1486,6 +1512,19 @@ static hipError_t launch_decode_t(const CacheView& cv, int layer_begin, int dyn_
   return hipGetLastError();
 }
 
+hipError_t launch_chunk_score_sum(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int max_chunks,
+                                  const void* q, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (n_dyn <= 0) return hipSuccess;
+  const dim3 grid(n_dyn, (max_chunks + 255) / 256);
+  if (dtype == HKV_F32)
+    HKV_LAUNCH(chunk_score_sum_kernel<float>, grid, dim3(256), 0u, st, ev0, ev1, cv, layer_begin, dyn_begin,
+               static_cast<const float*>(q));
+  else
+    HKV_LAUNCH(chunk_score_sum_kernel<bf16_t>, grid, dim3(256), 0u, st, ev0, ev1, cv, layer_begin, dyn_begin,
+               static_cast<const bf16_t*>(q));
+  return hipGetLastError();
+}
+
 hipError_t launch_chunk_score_max(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, const void* q,
                                   int t_arg, hipStream_t st) {
   if (n_dyn <= 0) return hipSuccess;
@@ -1549,25 +1588,14 @@ static hipError_t launch_dynamic_tiles_t(const CacheView& cv, int layer_begin, i
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
                                 const void* v_new, float* parts_o, float* parts_ml, void* out, int t_arg, int reselect,
-                                int static_hold, int max_chunks, int wide, void* stamps, int n_stamps, hipStream_t st,
+                                int static_hold, int max_chunks, void* stamps, int n_stamps, hipStream_t st,
                                 hipEvent_t ev0, hipEvent_t ev1) {
   if (n_ditems + n_sitems <= 0) return hipSuccess;
-  if (stamps && dtype == HKV_BF16 && !cv.index_gen && !wide) {      // diagnostic instantiation with time stamps
+  if (stamps && dtype == HKV_BF16 && !cv.index_gen) {      // diagnostic instantiation with time stamps
     HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, false, 4, true>(
                              cv, layer_begin, ditem_begin, n_ditems, sitem_begin, n_sitems, slot_base, q, k_new, v_new,
                              parts_o, parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1,
                              static_cast<unsigned long long*>(stamps), n_stamps)));
-    return hipErrorInvalidValue;
-  }
-  if (wide && dtype == HKV_BF16 && reselect) {      // few tiles: workgroups of kWideWaves waves
-    if (cv.index_gen) {
-      HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, true, kWideWaves>(
-                               cv, layer_begin, ditem_begin, n_ditems, sitem_begin, n_sitems, slot_base, q, k_new, v_new,
-                               parts_o, parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
-    }
-    HKV_DISPATCH_G(cv.G, return (launch_dynamic_tiles_t<bf16_t, GG, false, kWideWaves>(
-                             cv, layer_begin, ditem_begin, n_ditems, sitem_begin, n_sitems, slot_base, q, k_new, v_new,
-                             parts_o, parts_ml, out, t_arg, reselect, static_hold, max_chunks, st, ev0, ev1)));
     return hipErrorInvalidValue;
   }
   if (cv.index_gen) {        // bf16 caches, tiles that repeat the selection

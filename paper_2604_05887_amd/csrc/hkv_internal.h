@@ -119,6 +119,8 @@ int validate_config(const hkv_config* cfg);
 // launch_attn_merge also publishes the new tail counters when t_arg < 0, so it runs last.
 // ev0 / ev1 (both or neither) receive the kernel's own start and stop time stamps.
 // Scores of the chunks under hkv_config.chunk_score_group = 1, stored for the step's kernels to pick from.
+hipError_t launch_chunk_score_sum(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int max_chunks,
+                                  const void* q, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_chunk_score_max(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, const void* q,
                                   int t_arg, hipStream_t st);
 hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int sitem_begin,
@@ -128,7 +130,7 @@ hipError_t launch_decode(const CacheView& cv, int dtype, int layer_begin, int dy
 hipError_t launch_dynamic_tiles(const CacheView& cv, int dtype, int layer_begin, int ditem_begin, int n_ditems,
                                 int sitem_begin, int n_sitems, int slot_base, const void* q, const void* k_new,
                                 const void* v_new, float* parts_o, float* parts_ml, void* out, int t_arg, int reselect,
-                                int static_hold, int max_chunks, int wide, void* stamps, int n_stamps, hipStream_t st,
+                                int static_hold, int max_chunks, void* stamps, int n_stamps, hipStream_t st,
                                 hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // One wide workgroup per unit, outputs written directly (bf16 caches only; no workspace, no merge).
 hipError_t launch_units(const CacheView& cv, int dtype, int layer_begin, int dyn_begin, int n_dyn, int static_begin,

@@ -7,11 +7,14 @@
 
 namespace hkv {
 static hipError_t never() { std::abort(); }
+hipError_t launch_chunk_score_sum(const CacheView&, int, int, int, int, int, const void*, hipStream_t, hipEvent_t, hipEvent_t) {
+  return never();
+}
 hipError_t launch_chunk_score_max(const CacheView&, int, int, int, int, const void*, int, hipStream_t) { return never(); }
 hipError_t launch_decode(const CacheView&, int, int, int, int, int, int, int, const void*, const void*, const void*, float*,
                          float*, void*, int, int, int, int, hipStream_t, hipEvent_t, hipEvent_t) { return never(); }
 hipError_t launch_dynamic_tiles(const CacheView&, int, int, int, int, int, int, int, const void*, const void*, const void*,
-                                float*, float*, void*, int, int, int, int, int, void*, int, hipStream_t, hipEvent_t, hipEvent_t) {
+                                float*, float*, void*, int, int, int, int, void*, int, hipStream_t, hipEvent_t, hipEvent_t) {
   return never();
 }
 hipError_t launch_units(const CacheView&, int, int, int, int, int, int, const void*, const void*, const void*, void*, int, int,

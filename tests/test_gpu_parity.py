@@ -419,6 +419,42 @@ def test_seeded_random_shapes_across_the_variants(seed):
     _say(f"random variant {seed}: G{G} kv{n_kv} w{window} B{batch} chunks {chunk} per_layer={per_layer} {kw}", stats)
 
 
+def test_chunk_scores_from_their_own_launch_under_the_automatic_rule():
+    """Heads with more than 512 chunks (1024 chunks of 8 tokens) in calls whose tiles are all resident at once:
+    under the automatic rule the chunk scores come from a launch of their own and the tiles only pick.  The
+    whole chain matches the oracle (whole-model calls and a call per layer); the profiled second launch shows
+    that the path was taken, and scores, picks and outputs equal those of the explicit single-launch shape
+    bit for bit."""
+    wl = make_workload(1, n_layers=2, steps=3)
+    wl.chunk_size[:] = 8
+    wl.budget[wl.head_type == O.DYNAMIC] = 8 * 96
+    for ranges in (None, [(0, 1), (1, 2)]):
+        stats = P.full_pipeline(wl, decode_tile_rows=1024, layer_ranges=ranges)
+        _say(f"scores from their own launch, ranges {ranges}", stats)
+    outs, sigmas, picks, second_ms = {}, {}, {}, {}
+    for mode in (0, 3):
+        dw = runner.setup(wl, decode_tile_rows=1024, decode_dynamic=mode)
+        assert dw.cache.decode_shape()[1] == 3
+        dw.cache.compress(dw.q_window, dw.k, dw.v)
+        q = runner.to_device(wl.q_steps[0], wl.dtype)
+        out = torch.zeros_like(q)
+        B.hkv_profile_enable(dw.cache.handle, 4)
+        dw.cache.decode_attn(q, None, None, out)
+        (ms, n_calls) = B.hkv_profile_read(dw.cache.handle)
+        B.hkv_profile_disable(dw.cache.handle)
+        assert n_calls == 1
+        second_ms[mode] = ms[1]
+        outs[mode] = out.view(torch.int16).cpu().numpy()
+        dyn = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads) if wl.head_type[0, l, h] == O.DYNAMIC]
+        sigmas[mode] = [dw.cache.export(B.HKV_X_CHUNK_SIGMA, 0, l, h) for l, h in dyn]
+        picks[mode] = [dw.cache.export(B.HKV_X_CHUNK_SEL, 0, l, h) for l, h in dyn]
+        dw.cache.close()
+    assert second_ms[0] > 0.0 and second_ms[3] == 0.0
+    assert np.array_equal(outs[0], outs[3])
+    for a, b in zip(sigmas[0] + picks[0], sigmas[3] + picks[3]):
+        assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("dtype_cfg,mode,tile", [(1, 1, 0), (1, 2, 128), (1, 2, 0), (1, 3, 128), (1, 3, 0), (1, 3, 160), (1, 2, 288), (1, 1, 416), (1, 4, 0), (0, 1, 0), (0, 2, 0), (0, 3, 0)])
 def test_both_decode_shapes_for_dynamic_heads(dtype_cfg, mode, tile):
     """Dynamic heads handled by one workgroup each (mode 1), by split-K tiles in a second launch
