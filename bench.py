@@ -276,6 +276,7 @@ class Bench:
             e = {"n": int(len(r)), "start_at": pct(us(r[:, 0])), "descriptor": pct((r[:, 1] - r[:, 0]) / 100.0)}
             if name == "dynamic_tiles":
                 e["selection"] = pct((r[:, 2] - r[:, 1]) / 100.0)
+                e["selection_scores_ready"] = pct((r[:, 6] - r[:, 1]) / 100.0)
                 e["rows_and_record"] = pct((r[:, 3] - r[:, 2]) / 100.0)
             else:
                 e["rows_and_record"] = pct((r[:, 3] - r[:, 1]) / 100.0)

@@ -315,12 +315,13 @@ HKV_API int hkv_reselect_chunks(hkv_cache* cache, int layer_begin, int layer_end
 
 /* Optional per-workgroup time stamps of the main decode launch, for diagnosis (bf16 caches).  With
  * stamps_dev != NULL every later hkv_decode_attn call that runs as the single launch of split-K tiles (launch
- * shape 3, four-wave workgroups, index_generated = 0) runs an instrumented instantiation of that kernel:
+ * shape 3, index_generated = 0) runs an instrumented instantiation of that kernel:
  * thread 0 of workgroup b < n_records writes HKV_STAMP_WORDS uint64 words at stamps_dev[HKV_STAMP_WORDS * b]
  * (values of the device's constant 100 MHz counter, 10 ns a tick):
  *   [0] workgroup start, [1] tile descriptor read, [2] chunk selection done (0 for a static tile),
  *   [3] the tile's rows read and its record or output rows written (0: tile not reached at this tail length),
- *   [4] first logical row of the tile, [5] 1 for a dynamic tile, [6..7] 0.
+ *   [4] first logical row of the tile, [5] 1 for a dynamic tile, [6] chunk scores in shared memory (dynamic
+ *   tiles: between [1] and [2]), [7] 0.
  * Every call overwrites the records; results are unchanged.  Other launch shapes ignore the setting.
  *   stamps_dev : [device, 8-byte aligned] n_records * HKV_STAMP_WORDS uint64, owned by the caller, who keeps it
  *                alive until the setting is cleared with stamps_dev = NULL (then n_records = 0).

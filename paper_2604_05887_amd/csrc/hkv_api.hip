@@ -316,8 +316,8 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 // kStreamMinSteps steps.
 constexpr int kDeviceCus = 256;          // compute units of the device this library is written for (MI355X)
 constexpr int kStreamMinSteps = 8;
-constexpr int kStreamLayerMinSteps = 8;   // the same for the shares of a call over one layer
 constexpr int kStreamMaxWg = 3 * 256;
+constexpr int kPreScoreHold = 0;
 constexpr int kPreScoreChunks = 512;      // chunks per head from which a one-round call scores them in a launch of its own
 constexpr int kStreamAutoRows = 2048;     // the automatic rule streams when every workgroup's share is at least this long
 // A dynamic unit costs more than its rows: whoever touches it reads its chunk summaries (one 32-row step
@@ -325,8 +325,7 @@ constexpr int kStreamAutoRows = 2048;     // the automatic rule streams when eve
 // steps of a streaming workgroup).  That cost sits at the front of the unit on the line of work; a
 // boundary that falls inside it becomes the unit's row 0.
 constexpr int kSelLatencySteps = 3;
-void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref, int min_steps, StreamTable& tb,
-                        std::vector<char>& blob) {
+void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref, StreamTable& tb, std::vector<char>& blob) {
   std::vector<int64_t> start(n_units + 1, 0), lead(n_units, 0);     // first step of every unit; its selection cost
   std::vector<int32_t> ref_rows(n_units, 0);
   for (int i = 0; i < n_units; ++i) {
@@ -336,9 +335,7 @@ void build_stream_table(const Layout& lo, int unit_begin, int n_units, int t_ref
     start[i + 1] = start[i] + lead[i] + ((int64_t)ref_rows[i] + 31) / 32;
   }
   const int64_t S = start[n_units];
-  int64_t n_fit = S / min_steps;
-  if (min_steps != kStreamMinSteps && n_fit > kDeviceCus) n_fit = n_fit / kDeviceCus * kDeviceCus;   // whole rounds of the compute units
-  const int n_wg = (int)std::max<int64_t>(1, std::min<int64_t>(kStreamMaxWg, n_fit));
+  const int n_wg = (int)std::max<int64_t>(1, std::min<int64_t>(kStreamMaxWg, S / kStreamMinSteps));
   std::vector<StreamBound> bounds(n_wg + 1);
   int u = 0;
   for (int j = 0; j <= n_wg; ++j) {
@@ -387,8 +384,7 @@ void build_stream_shapes(const hkv_config* cfg, int batch, Layout& lo) {
     sh.n_units = s == 0 ? L * upl : upl;
     sh.tables.resize(rungs.size());
     for (size_t r = 0; r < rungs.size(); ++r) {
-      build_stream_table(lo, sh.unit_begin, sh.n_units, rungs[r], s == 0 ? kStreamMinSteps : kStreamLayerMinSteps,
-                         sh.tables[r], lo.stream_blob);
+      build_stream_table(lo, sh.unit_begin, sh.n_units, rungs[r], sh.tables[r], lo.stream_blob);
       lo.stream_slots_max = std::max<int64_t>(lo.stream_slots_max, (int64_t)sh.tables[r].n_wg + sh.n_units);
     }
   }
@@ -930,7 +926,7 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
       pre_scored = true;
     }
     e = launch_dynamic_tiles(cvs, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 1,
-                             pre_score ? 0 : hold, lo.max_chunks, c->stamps, c->n_stamps, st, ev[0], ev[1]);
+                             pre_score ? kPreScoreHold : hold, lo.max_chunks, c->stamps, c->n_stamps, st, ev[0], ev[1]);
   } else {
     e = launch_decode(cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
                       mode == 2 ? 1 : 0, lo.max_chunks, st, ev[0], ev[1]);

@@ -690,11 +690,19 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ o0, const f
 // length goes to cnt_b, and a follow-up kernel publishes it once every reader is done.
 
 // Top-k of up to 64 * R chunk scores held in shared memory (sig), without block-wide passes: every wave
-// keeps all keys in registers (R per lane; chunk 64 * m + lane in register m).  Wave 0 finds the k-th
-// largest key by radix selection on its own histogram; after the one barrier that hands it over, every wave
-// counts with wave votes, and wave m % 4 emits the picks of register m -- chunks with a key above the
-// threshold, those equal to it in chunk order up to the k-th place -- ascending by chunk id.  All NT threads
-// call (the barrier); waves beyond the fourth only take part in it.
+// keeps all keys in registers (R per lane; chunk 64 * m + lane in register m) and wave 0 searches.
+// k <= kBoundPicks: the k-th largest of the 64 lanes' largest keys, to its upper 20 bits, is a lower bound for the
+// k-th largest key (k of the lanes' maxima reach it) that usually leaves little more than k keys at or above it
+// (for k = 32 it is the median of the lanes' maxima: about 45 of 1000 keys reach it; for k near 64 it approaches
+// the smallest of the maxima and most keys do, hence the limit).
+// If at most 64 do, they go to one lane each, in chunk order; a bitwise search on wave votes over that one
+// register finds the k-th largest exactly, and the picks -- keys above it, those equal to it in chunk order up
+// to the k-th place -- leave from there, ascending by chunk id.  (Scores of one head share their sign and
+// size: over the whole key range a radix round's histogram adds all hit the same few words.)
+// Otherwise: wave 0 finds the k-th largest key by radix selection on its own histogram; after the one barrier
+// that hands it over, every wave counts with wave votes, and wave m % 4 emits the picks of register m.
+// All NT threads call (the barrier); waves beyond the fourth only take part in it.
+constexpr int kBoundPicks = 32;
 template <int R, int NT>
 __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n_c, int k, uint32_t* hist, uint32_t* bc,
                                                          bool to_memory, int32_t* sel_mem, int32_t* sel_lds) {
@@ -712,12 +720,60 @@ __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n
     for (int m = 0; m < R; ++m) {
       if (key[m] != 0u) { lo = min(lo, key[m]); hi = max(hi, key[m]); }
     }
-    lo = wave_min_u32_dpp(lo);
-    hi = ~wave_min_u32_dpp(~hi);
-    const uint32_t t = wave_radix_kth<R>(key, n_used, k, max(lo, 1u), hi, hist);
-    if (lane == 0) bc[0] = t;
+    bool picked = false;                                     // wave-uniform
+    if (k <= kBoundPicks) {
+      const uint32_t lane_max = hi;
+      uint32_t bound = 0;
+#pragma unroll 4
+      for (int bit = 31; bit >= 12; --bit) {
+        const uint32_t cand = bound | (1u << bit);
+        if (__builtin_popcountll(__builtin_amdgcn_ballot_w64(lane_max >= cand)) >= k) bound = cand;   // wave-uniform
+      }
+      uint2* cand_lds = reinterpret_cast<uint2*>(hist);      // [64] (key, chunk id); the histogram is not in use here
+      int n_cand = 0;
+#pragma unroll
+      for (int m = 0; m < R; ++m) {
+        if (m >= n_used) break;                              // wave-uniform
+        const bool in = key[m] != 0u && key[m] >= bound;
+        const unsigned long long inb = __builtin_amdgcn_ballot_w64(in);
+        const int pos = n_cand + lanes_below(inb);
+        if (in && pos < 64) cand_lds[pos] = make_uint2(key[m], (uint32_t)(lane + 64 * m));
+        n_cand += __builtin_popcountll(inb);
+      }
+      if (n_cand <= 64) {                                    // else: too many keys at the bound (k lanes' maxima are low, or ties)
+        wave_lds_sync();
+        const uint2 c = lane < n_cand ? cand_lds[lane] : make_uint2(0u, 0u);
+        uint32_t thr = 0;
+#pragma unroll 4
+        for (int bit = 31; bit >= 0; --bit) {
+          const uint32_t cand = thr | (1u << bit);
+          const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c.x >= cand));
+          if (cnt >= k) thr = cand;                          // wave-uniform
+          if (cnt == k) break;                               // exactly k keys reach it: they are the picks
+        }
+        const unsigned long long gtb = __builtin_amdgcn_ballot_w64(c.x > thr);
+        const unsigned long long eqb = __builtin_amdgcn_ballot_w64(c.x == thr && lane < n_cand);
+        const int r_adm = k - __builtin_popcountll(gtb);     // places left for keys equal to the threshold
+        const int eq_before = lanes_below(eqb);
+        const bool is_gt = (gtb >> lane) & 1ull, is_eq = (eqb >> lane) & 1ull;
+        if (is_gt || (is_eq && eq_before < r_adm)) {
+          const int pos = lanes_below(gtb) + min(eq_before, r_adm);
+          if (to_memory) sel_mem[pos] = (int32_t)c.y;
+          if (sel_lds) sel_lds[pos] = (int32_t)c.y;
+        }
+        picked = true;
+      }
+    }
+    if (!picked) {
+      lo = wave_min_u32_dpp(lo);
+      hi = ~wave_min_u32_dpp(~hi);
+      const uint32_t t = wave_radix_kth<R>(key, n_used, k, max(lo, 1u), hi, hist);
+      if (lane == 0) bc[0] = t;
+    }
+    if (lane == 0) bc[1] = picked ? 1u : 0u;
   }
   __syncthreads();
+  if (bc[1]) return;                                         // wave 0 has left the picks
   const uint32_t thr = bc[0];
   if (wv >= 4) return;
   int n_gt = 0;
@@ -804,7 +860,8 @@ template <typename T, int NT = 256>
 __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const UnitDesc& d, int lrel,
                                                       const T* __restrict__ q, int use_stored_sigma, float* dsm,
                                                       int32_t* sel_lds = nullptr, bool to_memory = true,
-                                                      int n_c_now = -1, int k_now = -1) {
+                                                      int n_c_now = -1, int k_now = -1,
+                                                      unsigned long long* t_scores = nullptr) {
   constexpr int EPL = Elem<T>::kPer16, LPR = Elem<T>::kLanesPerRow, RP = NT / LPR;
   const int tid = thread_index();
   uint32_t* hist = reinterpret_cast<uint32_t*>(dsm);         // [256]
@@ -823,6 +880,7 @@ __device__ __forceinline__ void select_chunks_of_unit(const CacheView& cv, const
     for (int ch = tid; ch < n_c; ch += NT) sig[ch] = cv.sigma[d.aux_off + ch];
   }
   __syncthreads();
+  if (t_scores && tid == 0) *t_scores = wall_clock64();       // diagnostic: the scores are in shared memory
 
   // top-k chunks, ties to the lower chunk id, emitted ascending by chunk id
   if (n_c <= 256) {
@@ -1171,7 +1229,8 @@ void decode_kernel(CacheView cv, int layer_begin, int dyn_begin, int n_dyn, int 
 // STAMPS: thread 0 of workgroup b < n_stamps leaves a record of HKV_STAMP_WORDS 64-bit words in stamps (values
 // of the constant 100 MHz counter): [0] start, [1] tile descriptor read, [2] chunk selection done (0 for a
 // static tile), [3] the tile's rows read and its record or output rows written (0: tile not reached at this
-// tail length), [4] first logical row of the tile, [5] 1 for a dynamic tile.  A diagnostic instantiation.
+// tail length), [4] first logical row of the tile, [5] 1 for a dynamic tile, [6] chunk scores in shared memory
+// (dynamic tiles).  A diagnostic instantiation.
 template <typename T, int G, bool INDEXED = false, int NW = 4, bool STAMPS = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_ditems, int sitem_begin,
@@ -1228,7 +1287,8 @@ void dynamic_tiles_kernel(CacheView cv, int layer_begin, int ditem_begin, int n_
     int32_t* sel_lds = reinterpret_cast<int32_t*>(smem + lds_sel_off);
     // the picks stay in LDS for this block's own tile; the first tile also leaves them (and the chunk
     // scores) in memory for export
-    select_chunks_of_unit<T, NW * 64>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0, n_c_now, k_now);
+    select_chunks_of_unit<T, NW * 64>(cv, d, it.layer - layer_begin, q, cv.sigma_max, smem, sel_lds, it.row0 == 0, n_c_now, k_now,
+                                      STAMPS && rec ? rec + 6 : nullptr);
     __syncthreads();
     picks = sel_lds;
     if constexpr (STAMPS) {

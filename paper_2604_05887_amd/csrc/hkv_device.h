@@ -127,6 +127,11 @@ template <int LANES> __device__ __forceinline__ float sum_lanes(float x) {
   else return sum64(x);
 }
 
+// Number of set bits of a wave vote below this lane.
+__device__ __forceinline__ int lanes_below(unsigned long long votes) {
+  return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)votes, 0u));
+}
+
 // Wave-wide inclusive prefix sum of ints (wave64).
 __device__ __forceinline__ int wave_inclusive_scan(int v) {
   const int lane = (int)__lane_id();

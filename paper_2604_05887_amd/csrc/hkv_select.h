@@ -22,7 +22,8 @@ __device__ __forceinline__ void wave_lds_sync() {     // orders the wave's own s
 }
 
 // The kth largest of the keys one wave holds (N per lane, the first n_used registers of every lane in use; an
-// absent entry holds 0 and every real key lies in [lo, hi], lo >= 1; at least kth real keys), exactly: radix
+// absent entry holds 0; keys below lo are left out, none lies above hi, lo >= 1, and at least kth keys lie in
+// [lo, hi]), exactly: radix
 // selection on key - lo, eight bits per round, through a 256-bin histogram in `hist` (the wave's own 256
 // words of shared memory).  A round costs a handful of instructions per register where the bitwise search
 // above costs three per register and BIT.

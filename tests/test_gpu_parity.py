@@ -236,6 +236,49 @@ def test_selection_stage_with_planted_ties():
     dw.cache.close()
 
 
+@pytest.mark.parametrize("chunk,n_layers", [(8, 4), (32, 4)])
+def test_chunk_selection_with_planted_ties_among_many_chunks(chunk, n_layers):
+    """Heads with 1024 (or 256) chunks: the picks from imported scores equal the oracle's for k below, at and above
+    the limit of the search that starts from the lanes' maxima (32), for scores that are all different, quantised
+    to a few levels (most keys tie at the bound: the radix search takes over), all equal, equal at the cut only,
+    negative throughout, and with the largest values crowded into a few lanes."""
+    wl = make_workload(1, n_layers=n_layers, steps=1)
+    wl.chunk_size[:] = chunk
+    dyn = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads) if wl.head_type[0, l, h] == O.DYNAMIC]
+    ks = [5, 32, 33, 64, 200, 17, 31, 1]
+    for i, (l, h) in enumerate(dyn):
+        wl.budget[0, l, h] = chunk * ks[i % len(ks)]
+    dw = runner.setup(wl)
+    dw.cache.compress(dw.q_window, dw.k, dw.v)
+    rng = np.random.default_rng(11)
+    n_c = dw.cache.unit_info(0, dyn[0][0], dyn[0][1])[1]
+    assert n_c == int(wl.seqlens[0]) // chunk
+
+    def patterns():
+        yield "distinct", rng.standard_normal(n_c).astype(np.float32) * 30
+        yield "three levels", (rng.integers(-1, 2, size=n_c) / 4.0).astype(np.float32)
+        yield "many levels", (rng.integers(-4000, 4000, size=n_c) / 16.0).astype(np.float32)
+        yield "all equal", np.full(n_c, 2.5, np.float32)
+        x = rng.standard_normal(n_c).astype(np.float32)
+        x[np.argsort(x)[-40:-10]] = np.sort(x)[-40]              # thirty values tie across the 17th to 40th place
+        yield "ties at the cut", x
+        yield "negative", -np.abs(rng.standard_normal(n_c).astype(np.float32)) - 1.0
+        x = rng.standard_normal(n_c).astype(np.float32)
+        x[64 * np.arange(n_c // 64) + 3] += 50.0                 # the largest values all sit in one lane's registers
+        x[64 * np.arange(n_c // 64) + 40] += 49.0
+        yield "crowded lanes", x
+
+    for name, sig in patterns():
+        for (l, h) in dyn:
+            dw.cache.import_(B.HKV_X_CHUNK_SIGMA, 0, l, h, sig)
+        B.hkv_reselect_chunks(dw.cache.handle, 0, wl.n_layers)
+        for (l, h) in dyn:
+            k_sel = dw.cache.unit_info(0, l, h)[2]
+            got = dw.cache.export(B.HKV_X_CHUNK_SEL, 0, l, h)
+            assert np.array_equal(got, O.select_chunks(sig, k_sel)), (name, l, h, k_sel)
+    dw.cache.close()
+
+
 def test_tail_capacity_and_rewind():
     wl = make_workload(0, shrink=4, steps=3, max_new_tokens=2)
     dw = runner.setup(wl)
@@ -528,13 +571,15 @@ def test_workgroup_time_stamps_of_the_tile_launch():
     st = stamps.cpu().numpy()
     assert np.all(st[n_tiles:] == -1)                       # nothing beyond the records asked for
     rec = st[:n_tiles]
-    assert np.all(rec[:, 0] > 0) and np.all(rec[:, 1] >= rec[:, 0]) and np.all(rec[:, 6:] == 0)
+    assert np.all(rec[:, 0] > 0) and np.all(rec[:, 1] >= rec[:, 0]) and np.all(rec[:, 7] == 0)
     reached = rec[:, 3] > 0
     assert reached.sum() >= n_tiles // 2
     dyn = rec[:, 5] == 1
     assert dyn.any() and (~dyn).any()
     assert np.all(rec[dyn & reached, 2] >= rec[dyn & reached, 1]) and np.all(rec[dyn & reached, 3] >= rec[dyn & reached, 2])
     assert np.all(rec[~dyn, 2] == 0) and np.all(rec[~dyn & reached, 3] >= rec[~dyn & reached, 1])
+    assert np.all(rec[~dyn, 6] == 0)                        # scores-ready stamp: dynamic tiles only, inside the selection
+    assert np.all(rec[dyn & reached, 6] >= rec[dyn & reached, 1]) and np.all(rec[dyn & reached, 6] <= rec[dyn & reached, 2])
     assert np.all(rec[:, 4] % dw.cache.call_tiling()[0] == 0)       # first rows are multiples of the tile size
     span_us = (rec[reached, 3].max() - rec[:, 0].min()) / 100.0
     assert 1.0 < span_us < 1000.0
