@@ -715,25 +715,27 @@ __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n
     key[m] = (m < n_used && ch < n_c) ? float_order_key(sig[ch]) : 0u;      // 0: no chunk (below every real key)
   }
   if (wv == 0) {
-    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+    uint32_t lane_max = 0u;                                  // absent entries are 0
 #pragma unroll
-    for (int m = 0; m < R; ++m) {
-      if (key[m] != 0u) { lo = min(lo, key[m]); hi = max(hi, key[m]); }
-    }
+    for (int m = 0; m < R; ++m) lane_max = max(lane_max, key[m]);
+    const uint32_t hi = ~wave_min_u32_dpp(~lane_max);        // the largest key
     bool picked = false;                                     // wave-uniform
     if (k <= kBoundPicks) {
-      const uint32_t lane_max = hi;
+      // the searches skip the bits that cannot differ: no key exceeds hi, so a threshold that keeps hi's sign and
+      // exponent bits and is reached often enough is the start for the remaining bits
       uint32_t bound = 0;
+      int bit0 = 31;
+      const uint32_t top = hi & 0xFF800000u;
+      if (__builtin_popcountll(__builtin_amdgcn_ballot_w64(lane_max >= top)) >= k) { bound = top; bit0 = 22; }
 #pragma unroll 4
-      for (int bit = 31; bit >= 12; --bit) {
+      for (int bit = bit0; bit >= 12; --bit) {
         const uint32_t cand = bound | (1u << bit);
         if (__builtin_popcountll(__builtin_amdgcn_ballot_w64(lane_max >= cand)) >= k) bound = cand;   // wave-uniform
       }
       uint2* cand_lds = reinterpret_cast<uint2*>(hist);      // [64] (key, chunk id); the histogram is not in use here
       int n_cand = 0;
 #pragma unroll
-      for (int m = 0; m < R; ++m) {
-        if (m >= n_used) break;                              // wave-uniform
+      for (int m = 0; m < R; ++m) {                          // (registers beyond n_used hold 0: never at the bound)
         const bool in = key[m] != 0u && key[m] >= bound;
         const unsigned long long inb = __builtin_amdgcn_ballot_w64(in);
         const int pos = n_cand + lanes_below(inb);
@@ -743,9 +745,11 @@ __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n
       if (n_cand <= 64) {                                    // else: too many keys at the bound (k lanes' maxima are low, or ties)
         wave_lds_sync();
         const uint2 c = lane < n_cand ? cand_lds[lane] : make_uint2(0u, 0u);
-        uint32_t thr = 0;
+        // every candidate lies in [bound, hi]: the bits above the first one in which the two differ are decided
+        const int free_bits = 32 - __builtin_clz((hi ^ bound) | 1u);
+        uint32_t thr = free_bits >= 32 ? 0u : (hi >> free_bits) << free_bits;
 #pragma unroll 4
-        for (int bit = 31; bit >= 0; --bit) {
+        for (int bit = free_bits - 1; bit >= 0; --bit) {
           const uint32_t cand = thr | (1u << bit);
           const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c.x >= cand));
           if (cnt >= k) thr = cand;                          // wave-uniform
@@ -765,8 +769,11 @@ __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n
       }
     }
     if (!picked) {
+      uint32_t lo = 0xFFFFFFFFu;
+#pragma unroll
+      for (int m = 0; m < R; ++m)
+        if (key[m] != 0u) lo = min(lo, key[m]);
       lo = wave_min_u32_dpp(lo);
-      hi = ~wave_min_u32_dpp(~hi);
       const uint32_t t = wave_radix_kth<R>(key, n_used, k, max(lo, 1u), hi, hist);
       if (lane == 0) bc[0] = t;
     }
