@@ -691,18 +691,104 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ o0, const f
 
 // Top-k of up to 64 * R chunk scores held in shared memory (sig), without block-wide passes: every wave
 // keeps all keys in registers (R per lane; chunk 64 * m + lane in register m) and wave 0 searches.
-// k <= kBoundPicks: the k-th largest of the 64 lanes' largest keys, to its upper 20 bits, is a lower bound for the
+// k <= 32: the k-th largest of the 64 lanes' largest keys, to its upper 20 bits, is a lower bound for the
 // k-th largest key (k of the lanes' maxima reach it) that usually leaves little more than k keys at or above it
-// (for k = 32 it is the median of the lanes' maxima: about 45 of 1000 keys reach it; for k near 64 it approaches
-// the smallest of the maxima and most keys do, hence the limit).
-// If at most 64 do, they go to one lane each, in chunk order; a bitwise search on wave votes over that one
-// register finds the k-th largest exactly, and the picks -- keys above it, those equal to it in chunk order up
-// to the k-th place -- leave from there, ascending by chunk id.  (Scores of one head share their sign and
+// (for k = 32 it is the median of the lanes' maxima: about 45 of 1000 keys reach it).  32 < k <= kBoundPicks: the
+// same with every lane's two largest keys, 128 values.
+// If at most 64 keys reach the bound (128 in the second case), they go to one lane each (two a lane), in chunk
+// order; a bitwise search on wave votes over that register (those two) finds the k-th largest exactly, and the
+// picks -- keys above it, those equal to it in chunk order up to the k-th place -- leave from there, ascending
+// by chunk id.  (Scores of one head share their sign and
 // size: over the whole key range a radix round's histogram adds all hit the same few words.)
 // Otherwise: wave 0 finds the k-th largest key by radix selection on its own histogram; after the one barrier
 // that hands it over, every wave counts with wave votes, and wave m % 4 emits the picks of register m.
 // All NT threads call (the barrier); waves beyond the fourth only take part in it.
-constexpr int kBoundPicks = 32;
+constexpr int kBoundPicks = 64;
+// The search from the lanes' largest keys (TWO: largest and second largest, for 32 < k <= 64) described above, by one
+// wave; false if more keys reach the bound than there are candidate places (64, TWO: 128), nothing written then.
+// lane_max = this lane's largest key, hi = the largest key of all; cand_lds: 128 (key, chunk id) pairs.
+template <int R, bool TWO>
+__device__ __forceinline__ bool topk_from_lane_maxima(const uint32_t (&key)[R], int k, uint32_t lane_max, uint32_t hi,
+                                                      uint2* cand_lds, bool to_memory, int32_t* sel_mem, int32_t* sel_lds) {
+  const int lane = thread_index() & 63;
+  constexpr int kPlaces = TWO ? 128 : 64;
+  uint32_t second = 0u;                                      // this lane's second largest key (an equal one counts)
+  if constexpr (TWO) {
+    uint32_t first = 0u;
+#pragma unroll
+    for (int m = 0; m < R; ++m) { second = max(second, min(first, key[m])); first = max(first, key[m]); }
+  }
+  auto reach = [&](uint32_t t) {                             // how many of the lanes' keys in play reach t (wave-uniform)
+    int n = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane_max >= t));
+    if constexpr (TWO) n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(second >= t));
+    return n;
+  };
+  // the searches skip the bits that cannot differ: no key exceeds hi, so a threshold that keeps hi's sign and
+  // exponent bits and is reached often enough is the start for the remaining bits
+  uint32_t bound = 0;
+  int bit0 = 31;
+  const uint32_t top = hi & 0xFF800000u;
+  if (reach(top) >= k) { bound = top; bit0 = 22; }
+#pragma unroll 4
+  for (int bit = bit0; bit >= 12; --bit) {
+    const uint32_t cand = bound | (1u << bit);
+    if (reach(cand) >= k) bound = cand;
+  }
+  int n_cand = 0;
+#pragma unroll
+  for (int m = 0; m < R; ++m) {                              // (registers without a chunk hold 0: never at the bound)
+    const bool in = key[m] != 0u && key[m] >= bound;
+    const unsigned long long inb = __builtin_amdgcn_ballot_w64(in);
+    const int pos = n_cand + lanes_below(inb);
+    if (in && pos < kPlaces) cand_lds[pos] = make_uint2(key[m], (uint32_t)(lane + 64 * m));
+    n_cand += __builtin_popcountll(inb);
+  }
+  if (n_cand > kPlaces) return false;                        // the lanes' maxima are low, or many keys tie at the bound
+  wave_lds_sync();
+  const uint2 c0 = lane < n_cand ? cand_lds[lane] : make_uint2(0u, 0u);
+  uint2 c1 = make_uint2(0u, 0u);
+  if constexpr (TWO) {
+    if (lane + 64 < n_cand) c1 = cand_lds[lane + 64];
+  }
+  // every candidate lies in [bound, hi]: the bits above the first one in which the two differ are decided
+  const int free_bits = 32 - __builtin_clz((hi ^ bound) | 1u);
+  uint32_t thr = free_bits >= 32 ? 0u : (hi >> free_bits) << free_bits;
+#pragma unroll 4
+  for (int bit = free_bits - 1; bit >= 0; --bit) {
+    const uint32_t cand = thr | (1u << bit);
+    int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c0.x >= cand));
+    if constexpr (TWO) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(c1.x >= cand));
+    if (cnt >= k) thr = cand;                                // wave-uniform
+    if (cnt == k) break;                                     // exactly k keys reach it: they are the picks
+  }
+  // candidate places are in chunk order: place `lane`, then (TWO) place 64 + lane
+  const unsigned long long gt0 = __builtin_amdgcn_ballot_w64(c0.x > thr);
+  const unsigned long long eq0 = __builtin_amdgcn_ballot_w64(c0.x == thr && lane < n_cand);
+  unsigned long long gt1 = 0ull, eq1 = 0ull;
+  if constexpr (TWO) {
+    gt1 = __builtin_amdgcn_ballot_w64(c1.x > thr);
+    eq1 = __builtin_amdgcn_ballot_w64(c1.x == thr && lane + 64 < n_cand);
+  }
+  const int r_adm = k - __builtin_popcountll(gt0) - __builtin_popcountll(gt1);   // places left for keys equal to the threshold
+  {
+    const int eq_before = lanes_below(eq0);
+    if (((gt0 >> lane) & 1ull) || (((eq0 >> lane) & 1ull) && eq_before < r_adm)) {
+      const int pos = lanes_below(gt0) + min(eq_before, r_adm);
+      if (to_memory) sel_mem[pos] = (int32_t)c0.y;
+      if (sel_lds) sel_lds[pos] = (int32_t)c0.y;
+    }
+  }
+  if constexpr (TWO) {
+    const int eq_before = __builtin_popcountll(eq0) + lanes_below(eq1);
+    if (((gt1 >> lane) & 1ull) || (((eq1 >> lane) & 1ull) && eq_before < r_adm)) {
+      const int pos = __builtin_popcountll(gt0) + lanes_below(gt1) + min(eq_before, r_adm);
+      if (to_memory) sel_mem[pos] = (int32_t)c1.y;
+      if (sel_lds) sel_lds[pos] = (int32_t)c1.y;
+    }
+  }
+  return true;
+}
+
 template <int R, int NT>
 __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n_c, int k, uint32_t* hist, uint32_t* bc,
                                                          bool to_memory, int32_t* sel_mem, int32_t* sel_lds) {
@@ -719,55 +805,10 @@ __device__ __forceinline__ void topk_chunks_in_registers(const float* sig, int n
 #pragma unroll
     for (int m = 0; m < R; ++m) lane_max = max(lane_max, key[m]);
     const uint32_t hi = ~wave_min_u32_dpp(~lane_max);        // the largest key
+    uint2* cand_lds = reinterpret_cast<uint2*>(hist);        // the histogram's 256 words, not in use on this path
     bool picked = false;                                     // wave-uniform
-    if (k <= kBoundPicks) {
-      // the searches skip the bits that cannot differ: no key exceeds hi, so a threshold that keeps hi's sign and
-      // exponent bits and is reached often enough is the start for the remaining bits
-      uint32_t bound = 0;
-      int bit0 = 31;
-      const uint32_t top = hi & 0xFF800000u;
-      if (__builtin_popcountll(__builtin_amdgcn_ballot_w64(lane_max >= top)) >= k) { bound = top; bit0 = 22; }
-#pragma unroll 4
-      for (int bit = bit0; bit >= 12; --bit) {
-        const uint32_t cand = bound | (1u << bit);
-        if (__builtin_popcountll(__builtin_amdgcn_ballot_w64(lane_max >= cand)) >= k) bound = cand;   // wave-uniform
-      }
-      uint2* cand_lds = reinterpret_cast<uint2*>(hist);      // [64] (key, chunk id); the histogram is not in use here
-      int n_cand = 0;
-#pragma unroll
-      for (int m = 0; m < R; ++m) {                          // (registers beyond n_used hold 0: never at the bound)
-        const bool in = key[m] != 0u && key[m] >= bound;
-        const unsigned long long inb = __builtin_amdgcn_ballot_w64(in);
-        const int pos = n_cand + lanes_below(inb);
-        if (in && pos < 64) cand_lds[pos] = make_uint2(key[m], (uint32_t)(lane + 64 * m));
-        n_cand += __builtin_popcountll(inb);
-      }
-      if (n_cand <= 64) {                                    // else: too many keys at the bound (k lanes' maxima are low, or ties)
-        wave_lds_sync();
-        const uint2 c = lane < n_cand ? cand_lds[lane] : make_uint2(0u, 0u);
-        // every candidate lies in [bound, hi]: the bits above the first one in which the two differ are decided
-        const int free_bits = 32 - __builtin_clz((hi ^ bound) | 1u);
-        uint32_t thr = free_bits >= 32 ? 0u : (hi >> free_bits) << free_bits;
-#pragma unroll 4
-        for (int bit = free_bits - 1; bit >= 0; --bit) {
-          const uint32_t cand = thr | (1u << bit);
-          const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c.x >= cand));
-          if (cnt >= k) thr = cand;                          // wave-uniform
-          if (cnt == k) break;                               // exactly k keys reach it: they are the picks
-        }
-        const unsigned long long gtb = __builtin_amdgcn_ballot_w64(c.x > thr);
-        const unsigned long long eqb = __builtin_amdgcn_ballot_w64(c.x == thr && lane < n_cand);
-        const int r_adm = k - __builtin_popcountll(gtb);     // places left for keys equal to the threshold
-        const int eq_before = lanes_below(eqb);
-        const bool is_gt = (gtb >> lane) & 1ull, is_eq = (eqb >> lane) & 1ull;
-        if (is_gt || (is_eq && eq_before < r_adm)) {
-          const int pos = lanes_below(gtb) + min(eq_before, r_adm);
-          if (to_memory) sel_mem[pos] = (int32_t)c.y;
-          if (sel_lds) sel_lds[pos] = (int32_t)c.y;
-        }
-        picked = true;
-      }
-    }
+    if (k <= 32) picked = topk_from_lane_maxima<R, false>(key, k, lane_max, hi, cand_lds, to_memory, sel_mem, sel_lds);
+    else if (k <= kBoundPicks) picked = topk_from_lane_maxima<R, true>(key, k, lane_max, hi, cand_lds, to_memory, sel_mem, sel_lds);
     if (!picked) {
       uint32_t lo = 0xFFFFFFFFu;
 #pragma unroll
