@@ -317,7 +317,6 @@ int plan_layout_tile(const hkv_config* cfg, const hkv_plan* plan, Layout& lo, in
 constexpr int kDeviceCus = 256;          // compute units of the device this library is written for (MI355X)
 constexpr int kStreamMinSteps = 8;
 constexpr int kStreamMaxWg = 3 * 256;
-constexpr int kPreScoreHold = 0;
 constexpr int kPreScoreChunks = 512;      // chunks per head from which a one-round call scores them in a launch of its own
 constexpr int kStreamAutoRows = 2048;     // the automatic rule streams when every workgroup's share is at least this long
 // A dynamic unit costs more than its rows: whoever touches it reads its chunk summaries (one 32-row step
@@ -926,7 +925,7 @@ static int decode_launches(hkv_cache* c, int lb, int le, const void* q, const vo
       pre_scored = true;
     }
     e = launch_dynamic_tiles(cvs, dt, lb, dib, ndi, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 1,
-                             pre_score ? kPreScoreHold : hold, lo.max_chunks, c->stamps, c->n_stamps, st, ev[0], ev[1]);
+                             pre_score ? 0 : hold, lo.max_chunks, c->stamps, c->n_stamps, st, ev[0], ev[1]);
   } else {
     e = launch_decode(cv, dt, lb, db, nd, sb, ns, slot_base, q, k_new, v_new, parts, parts_ml, out, t_before, 0,
                       mode == 2 ? 1 : 0, lo.max_chunks, st, ev[0], ev[1]);
