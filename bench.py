@@ -285,7 +285,7 @@ class Bench:
         return out
 
     # ---- one hkv_decode_attn call per layer, as a model interleaves them with its other layers --------
-    def layerwise(self):
+    def layerwise(self, with_graph=True):
         torch, wl, K, n = self.torch, self.wl, self.K, self.n_copies
         L = wl.n_layers
 
@@ -307,6 +307,8 @@ class Bench:
             layerwise_step(self.copies[i % n], i)
         torch.cuda.synchronize()
         lw_us = (time.perf_counter() - t0) * 1e6 / n_lw
+        if not with_graph:
+            return lw_us, None
         # the same per-layer calls recorded once into a HIP graph per cache copy (tail lengths on the device,
         # so a recording stays valid) and replayed: what a serving loop that records its decode step pays
         graphs = []
@@ -440,7 +442,7 @@ def cpu_oracle_baseline(cfg_id: int, L_full: int, seconds: float):
 
 
 def measure_compact(args, cfg_id, K, W, *, budget_rule="text_exempt", budget_frac=None, head_mix=None, inputs=None,
-                    full_us=None, with_full=True):
+                    full_us=None, with_full=True, with_layerwise=False):
     """A short form of the headline measurement for the `extra` rows: compress, K timed steps, the main
     launch's own duration, optionally the full-KV comparison."""
     b = Bench(args, cfg_id, K, W, budget_rule=budget_rule, budget_frac=budget_frac, head_mix=head_mix, inputs=inputs)
@@ -467,6 +469,11 @@ def measure_compact(args, cfg_id, K, W, *, budget_rule="text_exempt", budget_fra
            "compress_ms": round(compress_ms, 3),
            "full_kv_us_per_step": None if full_us is None else round(full_us, 2),
            "speedup_vs_full_kv": None if full_us is None else round(full_us / (b.ms_per_step * 1e3), 3)}
+    if with_layerwise:          # one call per layer, after everything else (it appends to the tails)
+        try:
+            row["per_layer_us_per_call"] = round(b.layerwise(with_graph=False)[0] / wl.n_layers, 2)
+        except b.B.HkvError:    # no room left in the tails
+            row["per_layer_us_per_call"] = None
     inputs = b.inputs
     b.close()
     return row, inputs
@@ -660,7 +667,7 @@ def main() -> int:
         for cid in (1, 2, 3, 4):
             if cid == args.config:
                 continue
-            row, inp = measure_compact(args, cid, Ke, We, with_full=full is not None)
+            row, inp = measure_compact(args, cid, Ke, We, with_full=full is not None, with_layerwise=not args.no_layerwise)
             others.append(row)
             torch.cuda.empty_cache()
             _log(f"{row['workload']}: {row['us_per_step']} us/step ({time.perf_counter() - t_start:.1f} s)")
