@@ -9,6 +9,9 @@
 //                         asked to), with the static heads' tiles in the same grid: the whole step in
 //                         one launch
 //   unit_kernel           one wide workgroup per head, selection to output rows, no records (short heads)
+//   stream_kernel         every workgroup walks an equal share of the rows of all heads of the call
+//   chunk_score_sum_kernel / chunk_score_max_kernel
+//                         the chunk scores in a launch of their own, ahead of kernels that then only pick
 //   attn_merge_kernel     log-sum-exp combination of the tiles in fixed order, cast to the output dtype
 //   full_attn_kernel      the same attention over caller-held, uncompressed K/V (comparison kernel)
 // The step's new K/V row is appended by the attention block whose tile contains it.
